@@ -1,0 +1,164 @@
+/*
+ * z2z.h -- C ABI of the zip2zip dynamic-vocabulary hot path for AMD MI355X (gfx950).
+ *
+ * The four operations follow the paper's statement of the method (arxiv 2506.01084):
+ *   lzw_encode       section 2.1 "LZW Algorithm"; section 2.3 step 2 (compress base tokens to hypertokens)
+ *   lzw_decode       section 2.1 property (2) "self-contained"; section 2.3 steps 11-12 (decompress);
+ *                    in append mode it is the per-step codebook update of steps 9-10
+ *   hyper_embed      section 2.2 (hyper-encoder over the constituent base embeddings, padded to M);
+ *                    "Averaging" row of the hyper-encoder ablation table; "Hyper-Embedding Cache"
+ *   extended_logits  section 2.3 steps 7-9 (hyper rows appended to the LM head, joint softmax, pick)
+ *
+ * Conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller; it must stay valid until the
+ *     work enqueued on `stream` has finished.  Pointers without the prefix are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return without synchronising, except z2z_create / z2z_destroy.
+ *   - One context serves B independent sequences (section 2.4: each document is compressed on its
+ *     own).  The context owns each sequence's codebook; all four calls read the same codebook,
+ *     so the embedding side and the unembedding side always see the same hypertoken set
+ *     (section 2.3, "Consistent Vocabulary Updates").
+ *   - IDs: 0..V-1 are base tokens; V+i is codebook entry i of that sequence, in creation order.
+ *   - Return value: 0 on success, a negative Z2Z_E* code when an argument is rejected on the host
+ *     (nothing is enqueued then).  Data errors are reported per sequence in d_status (bit flags);
+ *     a sequence with an error stops at the offending element, the others are unaffected.
+ *   - Calls on one context must be issued from one host thread at a time, and work of one context
+ *     must be ordered (same stream, or synchronised by the caller).
+ */
+#ifndef Z2Z_H
+#define Z2Z_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct z2z_ctx z2z_ctx;
+
+enum { Z2Z_F32 = 0, Z2Z_BF16 = 1 };                 /* storage type of E, W_base, W_hyper, H        */
+enum { Z2Z_POOL_MEAN = 0, Z2Z_POOL_WEIGHTED = 1 };  /* hyper_embed pooling kind                      */
+enum { Z2Z_APPEND = 0, Z2Z_RESET = 1 };             /* lzw_* flags: continue, or empty codebook first */
+
+enum {                                              /* host-side argument errors                      */
+  Z2Z_OK = 0, Z2Z_EINVAL = -1, Z2Z_ENOMEM = -2, Z2Z_EHIP = -3, Z2Z_EUNSUPPORTED = -4
+};
+enum {                                              /* per-sequence data status bits                  */
+  Z2Z_ST_OK = 0,
+  Z2Z_ST_BAD_TOKEN = 1,   /* base-token ID outside [0, V)                                            */
+  Z2Z_ST_BAD_CODE = 2,    /* code that names no existing entry (a "non-existing hypertoken")          */
+  Z2Z_ST_OVERFLOW = 4     /* output row too short for the result                                      */
+};
+
+#define Z2Z_MAX_M 8
+#define Z2Z_MAX_CAP 65535
+
+typedef struct {
+  int32_t B;      /* sequences served by the context, >= 1                                            */
+  int32_t V;      /* base vocabulary size, >= 1, V + cap < 2^31                                       */
+  int32_t M;      /* maximum merge size (base tokens per hypertoken), 1..Z2Z_MAX_M                    */
+  int32_t cap;    /* codebook capacity per sequence, 0..Z2Z_MAX_CAP; a full codebook is frozen        */
+  int32_t d;      /* embedding width, multiple of 8 (bf16) or 4 (f32)                                 */
+  int32_t dtype;  /* Z2Z_F32 or Z2Z_BF16                                                              */
+  int32_t pool;   /* Z2Z_POOL_MEAN or Z2Z_POOL_WEIGHTED                                               */
+  float w[Z2Z_MAX_M]; /* WEIGHTED: raw position weights; an entry of length L uses softmax(w[0..L))   */
+} z2z_config;
+
+/* Create / destroy a context on the current HIP device.  Allocates the codebook storage
+ * (about cap * (4*M + 16) bytes per sequence) and empties it.  Synchronous. */
+int z2z_create(z2z_ctx** out, const z2z_config* cfg);
+int z2z_destroy(z2z_ctx* ctx);
+
+/* Empty all codebooks and forget the previous phrase of every sequence. */
+int z2z_reset(z2z_ctx* ctx, void* stream);
+
+/* lzw_encode.  Greedy longest-match parse of each sequence against its growing codebook:
+ * a match is extended while phrase+next token is an entry and the phrase is shorter than M; when
+ * it ends its ID is emitted and phrase+next token becomes entry number C (if it spans <= M tokens
+ * and C < cap).  The last phrase of the call is emitted too (adding nothing).  With Z2Z_APPEND the
+ * codebook continues from earlier calls, and the entry "last emitted phrase + first token of this
+ * call" is added first if it is legal and not present yet (what a decoder of the joined code
+ * stream would add).
+ *   d_tokens  [B, stride] int32, row b holds d_lens[b] valid IDs (d_lens NULL: every row has `stride`)
+ *   d_codes   [B, out_stride] int32 out; d_n_codes [B] int32 out (number of codes written)
+ *   d_status  [B] int32 out (Z2Z_ST_* bits); BAD_TOKEN ends the sequence just before that token
+ */
+int z2z_lzw_encode(z2z_ctx* ctx, const int32_t* d_tokens, const int32_t* d_lens, int32_t stride,
+                   int32_t flags, int32_t* d_codes, int32_t* d_n_codes, int32_t out_stride,
+                   int32_t* d_status, void* stream);
+
+/* lzw_decode.  Inverse of lzw_encode; rebuilds the same codebook from the codes alone.  For each
+ * code: resolve its phrase (base token, existing entry, or the one not-yet-defined entry textbook
+ * LZW allows: previous phrase + its own first token); then add "previous phrase + first token of
+ * this phrase" as entry C if the previous phrase is shorter than M, C < cap, and that phrase is
+ * not an entry already.  With Z2Z_APPEND and one code per sequence this is the decode-step update
+ * (at most one new entry per sequence per step).
+ *   d_codes   [B, stride] int32, d_n_codes [B] (NULL: every row has `stride`)
+ *   d_tokens  [B, out_stride] int32 out (may be NULL with out_stride 0: only update the codebook;
+ *             nothing is written and OVERFLOW is not raised); d_n_tokens [B] out (tokens produced)
+ *   d_status  [B] out; BAD_CODE / OVERFLOW end the sequence before the offending code
+ */
+int z2z_lzw_decode(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_codes, int32_t stride,
+                   int32_t flags, int32_t* d_tokens, int32_t* d_n_tokens, int32_t out_stride,
+                   int32_t* d_status, void* stream);
+
+/* Borrowed read-only device views of the codebooks, valid until z2z_destroy:
+ *   entries   [B, cap, M] int32, the flattened base tokens of each entry, padded with -1
+ *   entry_len [B, cap]    int32 (0 for unused slots)
+ *   size      [B]         int32 C_b, the number of entries
+ * Any of the three out-pointers may be NULL. */
+int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entry_len,
+                 const int32_t** d_size);
+
+/* hyper_embed.  W_hyper[b, e, :] = sum_j a_j * E[t_j, :] over the L tokens of entry e of sequence b,
+ * a_j = 1/L (MEAN) or softmax(w[0..L))_j (WEIGHTED); padding slots contribute nothing and are not
+ * in the divisor.  fp32 accumulation in token order, one round-to-nearest-even to the storage type.
+ *   d_E       [V, d]       dtype of the context
+ *   d_W_hyper [B, cap, d]  same dtype, out.  This buffer is the hyper-embedding cache.
+ *   d_first   [B] int32 or NULL.  NULL: embed entries [0, C_b) and zero rows [C_b, cap).
+ *             Otherwise embed only entries [d_first[b], C_b) and leave all other rows untouched.
+ *   max_new   upper bound the caller expects for C_b - d_first[b] (sizes the launch; any value
+ *             >= 1 is correct, a tight one is faster); ignored when d_first is NULL.
+ */
+int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_t* d_first,
+                    int32_t max_new, void* stream);
+
+/* extended_logits.  For row r of sequence b = r / rows_per_seq:
+ *   logit[r, v] = sum_k H[r,k] * W[v,k],  W = W_base for v < V, W_hyper[b, v-V] for V <= v < V + C_b;
+ * slots at and beyond C_b are not columns (never predicted).  Products of the stored values,
+ * fp32 accumulation.  Per row the joint softmax is reduced on the fly to
+ *   d_argmax[r] (lowest index among equal maxima), d_max[r], d_lse[r] = ln sum_v exp(logit[r,v]).
+ *   d_H [rows, d]; rows must be B * rows_per_seq; d_W_base [V, d]; d_W_hyper [B, cap, d]
+ *   d_logits  NULL, or [rows, V + cap] float32 out: the full logits, -inf in unused slots
+ *             (for small shapes only: the reduction above never needs it).
+ * The context keeps a scratch buffer for partial reductions; it is (re)allocated when a call
+ * needs more than any earlier one (hipMalloc, which synchronises the device that once).
+ */
+int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                        const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
+                        float* d_lse, float* d_logits, void* stream);
+
+/* Tuning knobs (kernel variants and tile schedule) and instrumentation; unknown keys return
+ * Z2Z_EINVAL. */
+enum {
+  Z2Z_OPT_LOGITS_KERNEL = 1,   /* 0 = automatic, >0 = force a variant (see the implementation notes) */
+  Z2Z_OPT_LOGITS_STRIP = 2,    /* vocabulary tiles swept per workgroup, 0 = automatic               */
+  Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant                               */
+  Z2Z_OPT_DECODE_KERNEL = 4,   /* 0 = automatic, >0 = force a variant                               */
+  Z2Z_OPT_TIMING = 5           /* 1 = bracket the dominant kernel of every z2z_extended_logits call
+                                  with HIP events on the call's stream (at most 1024 calls are kept
+                                  between two z2z_read_timing calls); 0 = off (default)             */
+};
+int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value);
+
+/* Sum of the event-measured durations (milliseconds) of the dominant extended_logits kernel over
+ * the calls made since the last read, and their number.  Synchronises on the recorded events and
+ * clears the record.  `total_ms` / `launches` are host pointers. */
+int z2z_read_timing(z2z_ctx* ctx, float* total_ms, int32_t* launches);
+
+const char* z2z_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Z2Z_H */

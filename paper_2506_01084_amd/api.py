@@ -1,0 +1,193 @@
+"""Thin ctypes binding of libz2z.so: argument marshalling only, every step runs in the HIP kernels.
+
+PyTorch is used for device memory and streams (tensor.data_ptr(), the current stream's handle).
+There is no CPU fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_void_p
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libz2z.so")
+
+F32, BF16 = 0, 1
+POOL_MEAN, POOL_WEIGHTED = 0, 1
+APPEND, RESET = 0, 1
+ST_OK, ST_BAD_TOKEN, ST_BAD_CODE, ST_OVERFLOW = 0, 1, 2, 4
+OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMING = 1, 2, 3, 4, 5
+MAX_M = 8
+
+EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",
+           "z2z_hyper_embed", "z2z_extended_logits", "z2z_set_option", "z2z_read_timing", "z2z_strerror"]
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("B", c_int32), ("V", c_int32), ("M", c_int32), ("cap", c_int32), ("d", c_int32),
+                ("dtype", c_int32), ("pool", c_int32), ("w", c_float * MAX_M)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libz2z.so (built in-tree by paper_2506_01084_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_01084_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P32 = POINTER(c_int32)
+    lib.z2z_create.argtypes = [POINTER(c_void_p), POINTER(Config)]
+    lib.z2z_destroy.argtypes = [c_void_p]
+    lib.z2z_reset.argtypes = [c_void_p, c_void_p]
+    lib.z2z_lzw_encode.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32,
+                                   c_void_p, c_void_p]
+    lib.z2z_lzw_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32,
+                                   c_void_p, c_void_p]
+    lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
+    lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
+    lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.z2z_set_option.argtypes = [c_void_p, c_int32, c_int32]
+    lib.z2z_read_timing.argtypes = [c_void_p, POINTER(c_float), P32]
+    lib.z2z_strerror.argtypes = [ctypes.c_int]
+    lib.z2z_strerror.restype = c_char_p
+    for name in EXPORTS:
+        if name != "z2z_strerror":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+class Z2ZError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise Z2ZError(f"{what}: {load_library().z2z_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Context:
+    """One z2z_ctx: B independent sequences sharing V, M, cap, d, dtype and pooling kind."""
+
+    def __init__(self, B: int, V: int, M: int, cap: int, d: int, dtype: str = "bf16", pool: str = "mean",
+                 w=None):
+        self._lib = load_library()
+        cfg = Config()
+        cfg.B, cfg.V, cfg.M, cfg.cap, cfg.d = B, V, M, cap, d
+        cfg.dtype = {"f32": F32, "bf16": BF16}[dtype]
+        cfg.pool = {"mean": POOL_MEAN, "weighted": POOL_WEIGHTED}[pool]
+        for j in range(MAX_M):
+            cfg.w[j] = float(w[j]) if w is not None and j < len(w) else 0.0
+        self.B, self.V, self.M, self.cap, self.d, self.dtype = B, V, M, cap, d, dtype
+        self.torch_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
+        self._h = c_void_p()
+        _check(self._lib.z2z_create(byref(self._h), byref(cfg)), "z2z_create")
+
+    def close(self) -> None:
+        if self._h:
+            self._lib.z2z_destroy(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self) -> None:
+        _check(self._lib.z2z_reset(self._h, _stream()), "z2z_reset")
+
+    def set_option(self, key: int, value: int) -> None:
+        _check(self._lib.z2z_set_option(self._h, key, value), "z2z_set_option")
+
+    def read_timing(self):
+        ms, n = c_float(), c_int32()
+        _check(self._lib.z2z_read_timing(self._h, byref(ms), byref(n)), "z2z_read_timing")
+        return ms.value, n.value
+
+    # -- the four operations ------------------------------------------------------------------------
+    def lzw_encode(self, tokens: torch.Tensor, lens: Optional[torch.Tensor], codes: torch.Tensor,
+                   n_codes: torch.Tensor, status: torch.Tensor, flags: int = RESET) -> None:
+        assert tokens.shape[0] == self.B and codes.shape[0] == self.B
+        _check(self._lib.z2z_lzw_encode(self._h, _ptr(tokens, torch.int32), _ptr(lens, torch.int32),
+                                        tokens.shape[1], flags, _ptr(codes, torch.int32),
+                                        _ptr(n_codes, torch.int32), codes.shape[1], _ptr(status, torch.int32),
+                                        _stream()), "z2z_lzw_encode")
+
+    def lzw_decode(self, codes: torch.Tensor, n_codes: Optional[torch.Tensor], tokens: Optional[torch.Tensor],
+                   n_tokens: torch.Tensor, status: torch.Tensor, flags: int = RESET) -> None:
+        assert codes.shape[0] == self.B
+        out_stride = tokens.shape[1] if tokens is not None else 0
+        _check(self._lib.z2z_lzw_decode(self._h, _ptr(codes, torch.int32), _ptr(n_codes, torch.int32),
+                                        codes.shape[1], flags, _ptr(tokens, torch.int32),
+                                        _ptr(n_tokens, torch.int32), out_stride, _ptr(status, torch.int32),
+                                        _stream()), "z2z_lzw_decode")
+
+    def codebook_ptrs(self):
+        e, l, s = c_void_p(), c_void_p(), c_void_p()
+        _check(self._lib.z2z_codebook(self._h, byref(e), byref(l), byref(s)), "z2z_codebook")
+        return e.value, l.value, s.value
+
+    def codebook(self):
+        """Zero-copy int32 device tensors over the borrowed views: entries [B,cap,M], entry_len [B,cap], size [B]."""
+        e, l, s = self.codebook_ptrs()
+        if self.cap == 0:
+            z = torch.empty((self.B, 0, self.M), dtype=torch.int32, device="cuda")
+            return z, z[:, :, 0], _device_view(s, (self.B,))
+        return (_device_view(e, (self.B, self.cap, self.M)), _device_view(l, (self.B, self.cap)),
+                _device_view(s, (self.B,)))
+
+    def hyper_embed(self, E: torch.Tensor, W_hyper: torch.Tensor, first: Optional[torch.Tensor] = None,
+                    max_new: int = 0) -> None:
+        assert tuple(E.shape) == (self.V, self.d) and tuple(W_hyper.shape) == (self.B, self.cap, self.d)
+        _check(self._lib.z2z_hyper_embed(self._h, _ptr(E, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
+                                         _ptr(first, torch.int32), max_new, _stream()), "z2z_hyper_embed")
+
+    def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
+                        argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,
+                        logits: Optional[torch.Tensor] = None) -> None:
+        rows = H.shape[0]
+        assert H.shape[1] == self.d and tuple(W_base.shape) == (self.V, self.d)
+        assert argmax.numel() == rows and mx.numel() == rows and lse.numel() == rows
+        if logits is not None:
+            assert tuple(logits.shape) == (rows, self.V + self.cap)
+        _check(self._lib.z2z_extended_logits(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq,
+                                             _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
+                                             _ptr(argmax, torch.int32), _ptr(mx, torch.float32),
+                                             _ptr(lse, torch.float32), _ptr(logits, torch.float32), _stream()),
+               "z2z_extended_logits")
+
+
+class _DevView:
+    """Describes borrowed int32 device memory through the CUDA array interface (no copy, no ownership)."""
+
+    def __init__(self, ptr: int, shape):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": "<i4", "data": (int(ptr), False),
+                                         "version": 2}
+
+
+def _device_view(ptr: int, shape) -> torch.Tensor:
+    return torch.as_tensor(_DevView(ptr, shape), device="cuda")

@@ -1,0 +1,223 @@
+// C ABI of libz2z: argument checks, context life cycle, option and timing plumbing.
+// Every entry point validates on the host, then hands over to a launcher; nothing here computes.
+#include "z2z_internal.h"
+
+#include <math.h>
+#include <new>
+#include <string.h>
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int next_pow2(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+void free_ctx(z2z_ctx* c) {
+  if (!c) return;
+  (void)hipFree(c->st.size);
+  (void)hipFree(c->st.prev_code);
+  (void)hipFree(c->st.prev_len);
+  (void)hipFree(c->st.ent_tokens);
+  (void)hipFree(c->st.ent_len);
+  (void)hipFree(c->st.keys);
+  (void)hipFree(c->st.slots);
+  (void)hipFree(c->part_m);
+  (void)hipFree(c->part_s);
+  (void)hipFree(c->part_i);
+  if (c->ev_created) {
+    for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
+      (void)hipEventDestroy(c->ev_start[i]);
+      (void)hipEventDestroy(c->ev_stop[i]);
+    }
+  }
+  delete c;
+}
+
+}  // namespace
+
+extern "C" {
+
+Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
+  if (!out || !cfg) return Z2Z_EINVAL;
+  *out = nullptr;
+  if (cfg->B < 1 || cfg->V < 1 || cfg->M < 1 || cfg->M > Z2Z_MAX_M) return Z2Z_EINVAL;
+  if (cfg->cap < 0 || cfg->cap > Z2Z_MAX_CAP) return Z2Z_EINVAL;
+  if ((long long)cfg->V + cfg->cap >= 2147483647LL) return Z2Z_EINVAL;
+  if (cfg->dtype != Z2Z_F32 && cfg->dtype != Z2Z_BF16) return Z2Z_EUNSUPPORTED;
+  if (cfg->pool != Z2Z_POOL_MEAN && cfg->pool != Z2Z_POOL_WEIGHTED) return Z2Z_EUNSUPPORTED;
+  const int epc = cfg->dtype == Z2Z_BF16 ? 8 : 4;
+  if (cfg->d < epc || cfg->d % epc != 0) return Z2Z_EINVAL;
+  for (int j = 0; j < cfg->M; ++j)
+    if (!isfinite(cfg->w[j])) return Z2Z_EINVAL;
+
+  z2z_ctx* c = new (std::nothrow) z2z_ctx();
+  if (!c) return Z2Z_ENOMEM;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  if (hipGetDevice(&c->device) != hipSuccess) {
+    delete c;
+    return Z2Z_EHIP;
+  }
+  int lds = 0, cus = 0;
+  if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device) != hipSuccess) lds = 65536;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) cus = 256;
+  c->lds_limit = lds > 160 * 1024 ? 160 * 1024 : lds;
+  c->num_cu = cus;
+
+  // pooling coefficients: coef[L][j] = 1/L or softmax(w[0..L))_j, computed in double
+  for (int L = 1; L <= Z2Z_MAX_M; ++L) {
+    double mx = -INFINITY, sum = 0.0;
+    for (int j = 0; j < L; ++j) mx = cfg->w[j] > mx ? cfg->w[j] : mx;
+    for (int j = 0; j < L; ++j) sum += exp((double)cfg->w[j] - mx);
+    for (int j = 0; j < L; ++j)
+      c->coef[L][j] = cfg->pool == Z2Z_POOL_MEAN ? (float)(1.0 / L) : (float)(exp((double)cfg->w[j] - mx) / sum);
+  }
+
+  LzwState& st = c->st;
+  st.V = cfg->V;
+  st.M = cfg->M;
+  st.cap = cfg->cap;
+  st.nslots = next_pow2(2 * cfg->cap < 64 ? 64 : 2 * cfg->cap);
+  const size_t B = (size_t)cfg->B;
+  const size_t capn = cfg->cap > 0 ? (size_t)cfg->cap : 1;
+  bool ok = true;
+  ok = ok && hipMalloc(&st.size, B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.prev_code, B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.prev_len, B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.ent_tokens, B * capn * cfg->M * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.ent_len, B * capn * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.keys, B * capn * sizeof(unsigned long long)) == hipSuccess;
+  ok = ok && hipMalloc(&st.slots, B * (size_t)st.nslots * sizeof(uint16_t)) == hipSuccess;
+  if (!ok) {
+    free_ctx(c);
+    return Z2Z_ENOMEM;
+  }
+  if (z2z_lzw_prepare(c) != Z2Z_OK || z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
+      hipStreamSynchronize(nullptr) != hipSuccess) {
+    free_ctx(c);
+    return Z2Z_EHIP;
+  }
+  *out = c;
+  return Z2Z_OK;
+}
+
+Z2Z_API int z2z_destroy(z2z_ctx* ctx) {
+  if (!ctx) return Z2Z_EINVAL;
+  (void)hipDeviceSynchronize();
+  free_ctx(ctx);
+  return Z2Z_OK;
+}
+
+Z2Z_API int z2z_reset(z2z_ctx* ctx, void* stream) {
+  if (!ctx) return Z2Z_EINVAL;
+  return z2z_launch_lzw_reset(ctx, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_lzw_encode(z2z_ctx* ctx, const int32_t* d_tokens, const int32_t* d_lens, int32_t stride,
+                           int32_t flags, int32_t* d_codes, int32_t* d_n_codes, int32_t out_stride,
+                           int32_t* d_status, void* stream) {
+  if (!ctx || !d_n_codes || !d_status) return Z2Z_EINVAL;
+  if (stride < 0 || out_stride < 0) return Z2Z_EINVAL;
+  if ((stride > 0 && !d_tokens) || (out_stride > 0 && !d_codes)) return Z2Z_EINVAL;
+  if (flags != Z2Z_APPEND && flags != Z2Z_RESET) return Z2Z_EINVAL;
+  return z2z_launch_lzw_encode(ctx, d_tokens, d_lens, stride, flags, d_codes, d_n_codes, out_stride, d_status,
+                               static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_lzw_decode(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_codes, int32_t stride,
+                           int32_t flags, int32_t* d_tokens, int32_t* d_n_tokens, int32_t out_stride,
+                           int32_t* d_status, void* stream) {
+  if (!ctx || !d_n_tokens || !d_status) return Z2Z_EINVAL;
+  if (stride < 0 || out_stride < 0) return Z2Z_EINVAL;
+  if (stride > 0 && !d_codes) return Z2Z_EINVAL;
+  if (out_stride > 0 && !d_tokens) return Z2Z_EINVAL;
+  if (out_stride == 0 && d_tokens) return Z2Z_EINVAL;
+  if (flags != Z2Z_APPEND && flags != Z2Z_RESET) return Z2Z_EINVAL;
+  return z2z_launch_lzw_decode(ctx, d_codes, d_n_codes, stride, flags, d_tokens, d_n_tokens, out_stride, d_status,
+                               static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entry_len,
+                         const int32_t** d_size) {
+  if (!ctx) return Z2Z_EINVAL;
+  if (d_entries) *d_entries = ctx->st.ent_tokens;
+  if (d_entry_len) *d_entry_len = ctx->st.ent_len;
+  if (d_size) *d_size = ctx->st.size;
+  return Z2Z_OK;
+}
+
+Z2Z_API int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_t* d_first,
+                            int32_t max_new, void* stream) {
+  if (!ctx || !d_E) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_hyper_embed(ctx, d_E, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                                const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
+                                float* d_lse, float* d_logits, void* stream) {
+  if (!ctx || !d_H || !d_W_base) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
+  if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
+  if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_extended_logits(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_argmax, d_max, d_lse,
+                                    d_logits, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {
+  if (!ctx) return Z2Z_EINVAL;
+  switch (key) {
+    case Z2Z_OPT_LOGITS_KERNEL: ctx->opt_logits_kernel = value; return Z2Z_OK;
+    case Z2Z_OPT_LOGITS_STRIP:
+      if (value < 0) return Z2Z_EINVAL;
+      ctx->opt_logits_strip = value;
+      return Z2Z_OK;
+    case Z2Z_OPT_LZW_KERNEL: ctx->opt_lzw_kernel = value; return Z2Z_OK;
+    case Z2Z_OPT_DECODE_KERNEL: ctx->opt_decode_kernel = value; return Z2Z_OK;
+    case Z2Z_OPT_TIMING:
+      if (value && !ctx->ev_created) {
+        for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
+          if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess || hipEventCreate(&ctx->ev_stop[i]) != hipSuccess)
+            return Z2Z_EHIP;
+        }
+        ctx->ev_created = 1;
+      }
+      ctx->opt_timing = value ? 1 : 0;
+      return Z2Z_OK;
+    default: return Z2Z_EINVAL;
+  }
+}
+
+Z2Z_API int z2z_read_timing(z2z_ctx* ctx, float* total_ms, int32_t* launches) {
+  if (!ctx || !total_ms || !launches) return Z2Z_EINVAL;
+  float sum = 0.f;
+  for (int i = 0; i < ctx->n_timed; ++i) {
+    if (hipEventSynchronize(ctx->ev_stop[i]) != hipSuccess) return Z2Z_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess) return Z2Z_EHIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = ctx->n_timed;
+  ctx->n_timed = 0;
+  return Z2Z_OK;
+}
+
+Z2Z_API const char* z2z_strerror(int code) {
+  switch (code) {
+    case Z2Z_OK: return "ok";
+    case Z2Z_EINVAL: return "invalid argument";
+    case Z2Z_ENOMEM: return "out of device or host memory";
+    case Z2Z_EHIP: return "HIP runtime error";
+    case Z2Z_EUNSUPPORTED: return "unsupported dtype or pooling kind";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

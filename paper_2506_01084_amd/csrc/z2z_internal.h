@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libz2z (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "z2z.h"
+
+#define Z2Z_API __attribute__((visibility("default")))
+#define Z2Z_EMPTY_SLOT 0xFFFFu
+#define Z2Z_MAX_TIMED 1024
+
+// Per-sequence codebook storage, all in device global memory and owned by the context.
+//   size[b]                    number of entries C_b
+//   prev_code[b], prev_len[b]  last phrase emitted / consumed (-1, 0 = none)
+//   ent_tokens[b][e][0..M)     flattened base tokens of entry e, -1 padded
+//   ent_len[b][e]              its length (0 = unused)
+//   keys[b][e]                 (parent code << 32) | last token   -- the trie edge that made entry e
+//   slots[b][h]                open-addressing hash table over the trie edges: entry index or EMPTY
+struct LzwState {
+  int32_t* size;
+  int32_t* prev_code;
+  int32_t* prev_len;
+  int32_t* ent_tokens;
+  int32_t* ent_len;
+  unsigned long long* keys;
+  uint16_t* slots;
+  int32_t V, M, cap, nslots;
+};
+
+struct z2z_ctx {
+  z2z_config cfg;
+  int device;
+  int lds_limit;           // bytes of LDS one workgroup may use on this device
+  int num_cu;
+  LzwState st;
+  float coef[Z2Z_MAX_M + 1][Z2Z_MAX_M];   // coef[L][j]: pooling coefficient of token j of a length-L entry
+  // extended_logits scratch: partial (max, sum-exp, argmax) per (part, row)
+  float* part_m;
+  float* part_s;
+  int32_t* part_i;
+  size_t part_capacity;    // elements in each of the three arrays
+  // options
+  int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing;
+  // timing record
+  hipEvent_t ev_start[Z2Z_MAX_TIMED];
+  hipEvent_t ev_stop[Z2Z_MAX_TIMED];
+  int n_timed;
+  int ev_created;
+};
+
+// launchers (each validates nothing: the C-ABI layer has done so)
+int z2z_lzw_prepare(z2z_ctx* c);   // raises the dynamic-LDS ceiling of the parse kernels
+int z2z_launch_lzw_reset(z2z_ctx* c, hipStream_t s);
+int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens, int32_t stride, int32_t flags,
+                          int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s);
+int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t flags,
+                          int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s);
+int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32_t* first, int32_t max_new,
+                           hipStream_t s);
+int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                               const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
+                               hipStream_t s);
+
+#define Z2Z_HIP_TRY(expr)                      \
+  do {                                         \
+    hipError_t _e = (expr);                    \
+    if (_e != hipSuccess) return Z2Z_EHIP;     \
+  } while (0)

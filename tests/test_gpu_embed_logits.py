@@ -1,0 +1,322 @@
+"""GPU parity: hyper_embed and extended_logits through the C ABI against the float64 oracle.
+
+Tolerances (the stated bars; the arithmetic behind them is in the design notes):
+  hyper_embed   |gpu - ref| <= tol * sum_j a_j |E[t_j]| per element, tol = 1e-5 (f32) / 2e-2 (bf16)
+  logits        max_v |gpu - ref| / max_v |ref| <= 2e-2 per row; max and lse within 2e-2 * max(1, |ref|)
+  argmax        identical wherever the oracle's top-2 gap exceeds 1e-2
+"""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_01084_amd import workloads as wl
+
+from helpers import (check_logits_rows, gpu_encode, hyper_embed_bound, oracle_encode_batch, storage_to_host,
+                     torch_storage)
+
+pytestmark = pytest.mark.gpu
+
+
+def _make_ctx(cfg):
+    from paper_2506_01084_amd import api
+
+    w = wl.make_pool_weights(cfg)
+    return api.Context(B=cfg["B"], V=cfg["V"], M=cfg["M"], cap=cfg["cap"], d=cfg["d"], dtype=cfg["dtype"],
+                       pool=cfg["pool"], w=w.tolist()), w
+
+
+def _encode(ctx, cfg, tokens, lens=None):
+    lens = wl.make_lens(cfg) if lens is None else lens
+    gpu_encode(ctx, tokens, lens)
+    return oracle_encode_batch(tokens, lens, cfg["V"], cfg["M"], cfg["cap"])
+
+
+def _embed_gpu(ctx, cfg, E_host):
+    import torch
+
+    d_E = torch_storage(E_host, cfg["dtype"])
+    poison = 1.0 if cfg["dtype"] == "f32" else 1.0
+    d_W = torch.full((cfg["B"], cfg["cap"], cfg["d"]), poison, dtype=ctx.torch_dtype, device="cuda")
+    ctx.hyper_embed(d_E, d_W)
+    torch.cuda.synchronize()
+    return d_E, d_W
+
+
+def _check_embed(cfg, ref, E_host, d_W, w, seqs=None):
+    tol = 1e-5 if cfg["dtype"] == "f32" else 2e-2
+    W_host = storage_to_host(d_W, cfg["dtype"])
+    worst = 0.0
+    refW = {}
+    for b in (range(cfg["B"]) if seqs is None else seqs):
+        entries = ref[b][1]
+        Wr = oracle.hyper_embed(E_host, cfg["dtype"], entries, cfg["cap"], cfg["pool"], w)
+        refW[b] = Wr
+        got = oracle.to_f64(W_host[b], cfg["dtype"])
+        want = oracle.to_f64(Wr, cfg["dtype"])
+        C = len(entries)
+        assert (got[C:] == 0).all(), f"seq {b}: rows beyond the codebook must be zero"
+        bound = hyper_embed_bound(E_host, cfg["dtype"], entries, cfg["pool"], w, cfg["cap"])
+        err = np.abs(got - want)
+        assert (err <= tol * bound + 1e-30).all(), f"seq {b}: hyper_embed error {np.max(err / (bound + 1e-30))}"
+        worst = max(worst, float(np.max(err[:C] / (bound[:C] + 1e-30))) if C else 0.0)
+    return refW, worst
+
+
+# ---------------------------------------------------------------------------------------------------
+# config 1 at full size: everything, element by element, including the full logits matrix
+# ---------------------------------------------------------------------------------------------------
+def test_c1_full_path_elementwise():
+    import torch
+
+    cfg = wl.CONFIGS["c1"]
+    print("[case] c1 full path", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    rows_per_seq = cfg["N"]
+    rows = cfg["B"] * rows_per_seq
+    H = wl.make_hidden(cfg, rows)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    refW, worst = _check_embed(cfg, ref, E, d_W, w)
+    print(f"  hyper_embed worst relative-to-scale error {worst:.3e}", flush=True)
+
+    d_H = torch_storage(H, cfg["dtype"])
+    am = torch.empty(rows, dtype=torch.int32, device="cuda")
+    mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    full = torch.full((rows, cfg["V"] + cfg["cap"]), 123.0, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_W, am, mx, lse, full)
+    torch.cuda.synchronize()
+    am_h, mx_h, lse_h, full_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy(), full.cpu().numpy()
+    for b in range(cfg["B"]):
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        r = oracle.extended_logits(H[sl], E, refW[b], len(ref[b][1]), cfg["dtype"])
+        errs = check_logits_rows(r, am_h[sl], mx_h[sl], lse_h[sl], full_h[sl], V=cfg["V"])
+        print(f"  seq {b}: C={len(ref[b][1])} errors {errs}", flush=True)
+    # without the full-logits output the reduced results are identical
+    am2 = torch.empty_like(am); mx2 = torch.empty_like(mx); lse2 = torch.empty_like(lse)
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_W, am2, mx2, lse2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(am, am2) and torch.equal(mx, mx2) and torch.equal(lse, lse2)
+    ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# small shapes that span several tiles with ragged tails in every dimension
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,B,N,V,d,M,cap,pool", [
+    ("bf16", 3, 200, 1000, 264, 3, 300, "mean"),       # nothing a multiple of the tile sizes
+    ("bf16", 2, 130, 257, 72, 5, 140, "weighted"),
+    ("f32", 2, 150, 300, 100, 4, 130, "weighted"),
+    ("bf16", 4, 1, 700, 128, 3, 64, "mean"),           # one row per sequence (decode shape)
+    ("bf16", 1, 384, 512, 512, 2, 0, "mean"),          # no hyper vocabulary at all
+])
+def test_small_ragged_shapes(dtype, B, N, V, d, M, cap, pool):
+    import torch
+
+    cfg = dict(name="small", B=B, N=max(N, 400), V=V, d=d, dtype=dtype, M=M, cap=cap, zipf_s=1.1, copy_frac=0.4,
+               span=(2, 6), mode="motif", pool=pool, seed=77 + V)
+    print(f"[case] small ragged {dtype} B={B} rows/seq={N} V={V} d={d} M={M} cap={cap} {pool}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    rows = B * N
+    H = wl.make_hidden(cfg, rows)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens)
+    d_E = torch_storage(E, dtype)
+    if cap:
+        _, d_W = _embed_gpu(ctx, cfg, E)
+        refW, _ = _check_embed(cfg, ref, E, d_W, w)
+    else:
+        d_W = torch.empty((B, 0, d), dtype=ctx.torch_dtype, device="cuda")
+        refW = {b: np.zeros((0, d), dtype=np.float32 if dtype == "f32" else np.uint16) for b in range(B)}
+    d_H = torch_storage(H, dtype)
+    am = torch.empty(rows, dtype=torch.int32, device="cuda")
+    mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    full = torch.full((rows, V + cap), 123.0, dtype=torch.float32, device="cuda")
+    from paper_2506_01084_amd import api
+    for strip in (0, 1, 3):
+        ctx.set_option(api.OPT_LOGITS_STRIP, strip)
+        ctx.extended_logits(d_H, N, d_E, d_W, am, mx, lse, full)
+        torch.cuda.synchronize()
+        am_h, mx_h, lse_h, full_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy(), full.cpu().numpy()
+        for b in range(B):
+            sl = slice(b * N, (b + 1) * N)
+            r = oracle.extended_logits(H[sl], E, refW[b], len(ref[b][1]), dtype)
+            check_logits_rows(r, am_h[sl], mx_h[sl], lse_h[sl], full_h[sl], V=V)
+    ctx.close()
+
+
+def test_exact_ties_pick_lowest_index_and_masked_slots_never_win():
+    """H = 0 makes every logit 0: argmax must be column 0 and lse = ln(V + C_b); then poison unused slots."""
+    import math
+    import torch
+
+    cfg = dict(name="ties", B=2, N=120, V=333, d=64, dtype="bf16", M=3, cap=200, zipf_s=1.1, copy_frac=0.5,
+               span=(2, 5), mode="motif", pool="mean", seed=5)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    rows = cfg["B"] * 5
+    d_H = torch.zeros((rows, cfg["d"]), dtype=torch.bfloat16, device="cuda")
+    am = torch.empty(rows, dtype=torch.int32, device="cuda")
+    mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, 5, d_E, d_W, am, mx, lse, None)
+    torch.cuda.synchronize()
+    assert (am.cpu().numpy() == 0).all() and (mx.cpu().numpy() == 0).all()
+    for b in range(cfg["B"]):
+        C = len(ref[b][1])
+        assert 0 < C < cfg["cap"]
+        assert np.allclose(lse.cpu().numpy()[b * 5:(b + 1) * 5], math.log(cfg["V"] + C), atol=1e-4)
+    # unused hyper slots hold huge rows: they must not change anything
+    H = wl.make_hidden(cfg, rows)
+    d_H = torch_storage(H, "bf16")
+    ctx.extended_logits(d_H, 5, d_E, d_W, am, mx, lse, None)
+    torch.cuda.synchronize()
+    keep = (am.clone(), mx.clone(), lse.clone())
+    d_Wp = d_W.clone()
+    for b in range(cfg["B"]):
+        d_Wp[b, len(ref[b][1]):] = 1000.0
+    ctx.extended_logits(d_H, 5, d_E, d_Wp, am, mx, lse, None)
+    torch.cuda.synchronize()
+    assert torch.equal(am, keep[0]) and torch.equal(mx, keep[1]) and torch.equal(lse, keep[2])
+    ctx.close()
+
+
+def test_incremental_hyper_embed_only_touches_new_rows():
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=4, N=1500, d=256, cap=2048)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    ctx, w = _make_ctx(cfg)
+    half = 700
+    gpu_encode(ctx, np.ascontiguousarray(tokens[:, :half]), None)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    first = ctx.codebook()[2].clone()
+    gpu_encode(ctx, np.ascontiguousarray(tokens[:, half:]), None, flags=api.APPEND)
+    sentinel = d_W.clone()
+    ctx.hyper_embed(d_E, d_W, first, max_new=8)          # a deliberately small launch hint
+    torch.cuda.synchronize()
+    # reference: embed everything from scratch
+    d_W2 = torch.empty_like(d_W)
+    ctx.hyper_embed(d_E, d_W2)
+    torch.cuda.synchronize()
+    size = ctx.codebook()[2].cpu().numpy()
+    f = first.cpu().numpy()
+    assert (size > f).all()
+    for b in range(cfg["B"]):
+        assert torch.equal(d_W[b, f[b]:size[b]], d_W2[b, f[b]:size[b]])
+        assert torch.equal(d_W[b, :f[b]], sentinel[b, :f[b]])
+        assert torch.equal(d_W[b, size[b]:], sentinel[b, size[b]:])
+    ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration the benchmark times: sampled rows vs the oracle
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,per_seq", [("c2", 6), ("c4", 8), ("c5", 3)])
+def test_full_size_prefill_sampled_rows(name, per_seq):
+    import torch
+
+    cfg = wl.CONFIGS[name]
+    t0 = time.time()
+    print(f"[case] full size prefill {name}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    rows_per_seq = cfg["N"]
+    rows = cfg["B"] * rows_per_seq
+    H = wl.make_hidden(cfg, rows)
+    print(f"  inputs ready {time.time() - t0:.1f}s", flush=True)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    seqs = sorted(set([0, cfg["B"] - 1]))
+    refW, worst = _check_embed(cfg, ref, E, d_W, w, seqs=seqs)
+    print(f"  hyper_embed checked on sequences {seqs}: worst {worst:.3e}  {time.time() - t0:.1f}s", flush=True)
+    d_H = torch_storage(H, cfg["dtype"])
+    am = torch.empty(rows, dtype=torch.int32, device="cuda")
+    mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_W, am, mx, lse, None)
+    torch.cuda.synchronize()
+    print(f"  extended_logits done {time.time() - t0:.1f}s", flush=True)
+    am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+    # properties that hold at any size, on every row
+    assert np.isfinite(mx_h).all() and np.isfinite(lse_h).all()
+    assert (lse_h >= mx_h - 1e-4).all()
+    size = ctx.codebook()[2].cpu().numpy()
+    for b in range(cfg["B"]):
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        assert (am_h[sl] >= 0).all() and (am_h[sl] < cfg["V"] + size[b]).all()
+        assert (lse_h[sl] <= mx_h[sl] + np.log(cfg["V"] + size[b]) + 1e-3).all()
+    # sampled rows, all columns, against the oracle (only sequences whose W_hyper reference was built)
+    sub = wl.scaled(cfg, B=cfg["B"])
+    rows_s = wl.sample_rows(sub, rows_per_seq, per_seq)
+    for b in seqs:
+        pick = rows_s[(rows_s // rows_per_seq) == b]
+        r = oracle.extended_logits(H[pick], E, refW[b], len(ref[b][1]), cfg["dtype"], return_logits=True)
+        errs = check_logits_rows(r, am_h[pick], mx_h[pick], lse_h[pick], None)
+        print(f"  seq {b}: {len(pick)} sampled rows, errors {errs}  {time.time() - t0:.1f}s", flush=True)
+    ctx.close()
+
+
+def test_full_size_decode_step_c3():
+    """Config 3: 64 sequences with an 8192-token history, one code per sequence, one hidden row each."""
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.CONFIGS["c3"]
+    t0 = time.time()
+    print("[case] full size decode step c3", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    B = cfg["B"]
+    H = wl.make_hidden(cfg, B)
+    ctx, w = _make_ctx(cfg)
+    streams = [oracle.LZWStream(cfg["V"], cfg["M"], cfg["cap"]) for _ in range(B)]
+    for b in range(B):
+        streams[b].encode_chunk(tokens[b].tolist())
+    gpu_encode(ctx, tokens, None)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    print(f"  history encoded and embedded {time.time() - t0:.1f}s", flush=True)
+    # one decode step: new code -> codebook update -> embed the new entry -> logits
+    sizes = np.array([len(s.entries) for s in streams])
+    first = ctx.codebook()[2].clone()
+    new = wl.make_step_codes(cfg, sizes, 0)
+    d_new = torch.from_numpy(new.reshape(B, 1)).cuda()
+    n_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    st = torch.empty(B, dtype=torch.int32, device="cuda")
+    ctx.lzw_decode(d_new, None, None, n_tok, st, api.APPEND)
+    ctx.hyper_embed(d_E, d_W, first, max_new=1)
+    d_H = torch_storage(H, cfg["dtype"])
+    am = torch.empty(B, dtype=torch.int32, device="cuda")
+    mx = torch.empty(B, dtype=torch.float32, device="cuda")
+    lse = torch.empty(B, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, 1, d_E, d_W, am, mx, lse, None)
+    torch.cuda.synchronize()
+    print(f"  step done {time.time() - t0:.1f}s", flush=True)
+    assert (st.cpu().numpy() == 0).all()
+    for b in range(B):
+        streams[b].decode_chunk([int(new[b])])
+    size = ctx.codebook()[2].cpu().numpy()
+    assert size.tolist() == [len(s.entries) for s in streams]
+    am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+    W_host = storage_to_host(d_W, cfg["dtype"])
+    for b in [0, 1, 31, 63]:
+        Wr = oracle.hyper_embed(E, cfg["dtype"], streams[b].entries, cfg["cap"], cfg["pool"], w)
+        got, want = oracle.to_f64(W_host[b], "bf16"), oracle.to_f64(Wr, "bf16")
+        bound = hyper_embed_bound(E, "bf16", streams[b].entries, cfg["pool"], w, cfg["cap"])
+        assert (np.abs(got - want) <= 2e-2 * bound + 1e-30).all()
+        r = oracle.extended_logits(H[b:b + 1], E, Wr, len(streams[b].entries), "bf16")
+        errs = check_logits_rows(r, am_h[b:b + 1], mx_h[b:b + 1], lse_h[b:b + 1], None)
+        print(f"  seq {b}: C={len(streams[b].entries)} errors {errs}  {time.time() - t0:.1f}s", flush=True)
+    ctx.close()

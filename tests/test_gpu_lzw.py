@@ -1,0 +1,224 @@
+"""GPU parity: lzw_encode / lzw_decode through the C ABI against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_01084_amd import workloads as wl
+
+from helpers import (assert_codebook_equal, gpu_decode, gpu_encode, oracle_encode_batch)
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(cfg, **kw):
+    from paper_2506_01084_amd import api
+
+    args = dict(B=cfg.get("B"), V=cfg["V"], M=cfg["M"], cap=cfg["cap"], d=cfg.get("d", 64),
+                dtype=cfg.get("dtype", "bf16"))
+    args.update(kw)
+    return api.Context(**args)
+
+
+def _check_encode_decode(cfg, tokens, lens, lzw_kernel=0):
+    from paper_2506_01084_amd import api
+
+    B, N = tokens.shape
+    V, M, cap = cfg["V"], cfg["M"], cfg["cap"]
+    ctx = _ctx(cfg, B=B)
+    ctx.set_option(api.OPT_LZW_KERNEL, lzw_kernel)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    codes, n_codes, status = gpu_encode(ctx, tokens, lens)
+    for b, (rc, rentries, rst) in enumerate(ref):
+        assert int(status[b]) == rst, f"seq {b} status"
+        assert int(n_codes[b]) == len(rc), f"seq {b}: {int(n_codes[b])} codes, oracle {len(rc)}"
+        assert (codes[b, : len(rc)] == np.asarray(rc, dtype=np.int32)).all(), f"seq {b} codes differ"
+    assert_codebook_equal(ctx, [r[1] for r in ref], M, cap)
+
+    # decode the GPU's own codes in a fresh context: tokens and codebook must come back
+    ctx2 = _ctx(cfg, B=B)
+    ctx2.set_option(api.OPT_LZW_KERNEL, lzw_kernel)
+    toks, n_tok, st = gpu_decode(ctx2, codes, n_codes, out_stride=max(N, 1))
+    for b in range(B):
+        L = int(lens[b])
+        rt, _, rst = oracle.lzw_decode(ref[b][0], V, M, cap)
+        assert int(st[b]) == rst == 0
+        assert int(n_tok[b]) == len(rt) == L
+        assert (toks[b, :L] == tokens[b, :L]).all(), f"seq {b} round trip"
+    assert_codebook_equal(ctx2, [r[1] for r in ref], M, cap)
+    ctx.close()
+    ctx2.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_full_size_configs_bit_exact(name):
+    cfg = wl.CONFIGS[name]
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    print(f"[case] lzw full size {name} B={cfg['B']} N={cfg['N']} M={cfg['M']} cap={cfg['cap']}", flush=True)
+    _check_encode_decode(cfg, tokens, lens)
+
+
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_global_table_variant_bit_exact(name):
+    """The variant that keeps the hash table in global memory (used for huge capacities and short appends)."""
+    cfg = wl.scaled(wl.CONFIGS[name], B=3, N=3000)
+    tokens = wl.make_tokens(cfg)
+    print(f"[case] lzw global-table variant {name}", flush=True)
+    _check_encode_decode(cfg, tokens, wl.make_lens(cfg), lzw_kernel=2)
+
+
+def test_ragged_and_degenerate_lengths():
+    cfg = wl.scaled(wl.CONFIGS["c1"], B=8, N=777)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg, ragged=True)
+    assert 0 in lens and 1 in lens and cfg["N"] in lens
+    print("[case] lzw ragged lens", lens.tolist(), flush=True)
+    _check_encode_decode(cfg, tokens, lens)
+
+
+@pytest.mark.parametrize("V,M,cap", [(2, 3, 50), (3, 8, 200), (5, 1, 64), (4, 4, 0), (2, 5, 3), (1, 8, 16)])
+def test_tiny_alphabets_and_limits(V, M, cap):
+    """Small alphabets make repeats, the just-created-entry case and a full codebook frequent."""
+    rng = np.random.default_rng(100 * V + 10 * M + cap)
+    B, N = 6, 500
+    tokens = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    tokens[0] = 0                                   # constant sequence
+    lens = np.array([N, N, 63, 64, 65, 129], dtype=np.int32)
+    print(f"[case] lzw tiny alphabet V={V} M={M} cap={cap}", flush=True)
+    _check_encode_decode(dict(V=V, M=M, cap=cap), tokens, lens)
+
+
+def test_bad_token_and_short_output():
+    from paper_2506_01084_amd import api
+
+    V, M, cap = 50, 3, 64
+    rng = np.random.default_rng(5)
+    B, N = 4, 300
+    tokens = rng.integers(0, 6, size=(B, N)).astype(np.int32)
+    tokens[1, 100] = V          # out of range
+    tokens[2, 0] = -3           # out of range at the very start
+    lens = np.full(B, N, dtype=np.int32)
+    ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    codes, n_codes, status = gpu_encode(ctx, tokens, lens)
+    for b in range(B):
+        rc, rentries, rst = oracle.lzw_encode(tokens[b].tolist(), V, M, cap)
+        assert int(status[b]) == rst
+        assert int(n_codes[b]) == len(rc) and (codes[b, : len(rc)] == np.asarray(rc, dtype=np.int32)).all()
+    assert status.tolist() == [0, api.ST_BAD_TOKEN, api.ST_BAD_TOKEN, 0]
+    # output row too short: the first out_stride codes are still the oracle's, status says overflow
+    rc0, _, _ = oracle.lzw_encode(tokens[0].tolist(), V, M, cap)
+    short = len(rc0) - 5
+    codes, n_codes, status = gpu_encode(ctx, tokens, lens, out_stride=short)
+    assert int(status[0]) & api.ST_OVERFLOW and int(n_codes[0]) == short
+    assert (codes[0, :short] == np.asarray(rc0[:short], dtype=np.int32)).all()
+    ctx.close()
+
+
+def test_decoder_error_paths():
+    from paper_2506_01084_amd import api
+
+    V, M, cap = 3, 3, 32
+    B = 5
+    streams = [
+        [0, 3, 4, 1],           # valid; 3 and 4 each name the entry made in that very step (previous phrase + its first token)
+        [0, 1, 9],              # 9 names nothing
+        [4, 0],                 # a hyper code with no previous phrase
+        [0, -2, 1],             # negative
+        [2, 2, 2, 2],           # valid
+    ]
+    n = np.array([len(s) for s in streams], dtype=np.int32)
+    codes = np.zeros((B, 8), dtype=np.int32)
+    for b, s in enumerate(streams):
+        codes[b, : len(s)] = s
+    ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    toks, n_tok, st = gpu_decode(ctx, codes, n, out_stride=16)
+    refs = [oracle.lzw_decode(s, V, M, cap) for s in streams]
+    for b, (rt, rentries, rst) in enumerate(refs):
+        assert int(st[b]) == rst, (b, int(st[b]), rst)
+        assert int(n_tok[b]) == len(rt) and toks[b, : len(rt)].tolist() == rt
+    assert [r[2] for r in refs] == [0, api.ST_BAD_CODE, api.ST_BAD_CODE, api.ST_BAD_CODE, 0]
+    assert_codebook_equal(ctx, [r[1] for r in refs], M, cap)
+    # short output buffer
+    toks, n_tok, st = gpu_decode(ctx, codes, n, out_stride=3)
+    for b, s in enumerate(streams):
+        rt, _, rst = oracle.lzw_decode(s, V, M, cap, max_tokens=3)
+        assert int(st[b]) == rst and int(n_tok[b]) == len(rt) and toks[b, : len(rt)].tolist() == rt
+    ctx.close()
+
+
+def test_chunked_append_encode_matches_stream_oracle():
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c4"], B=3, N=2000, cap=512)
+    V, M, cap = cfg["V"], cfg["M"], cfg["cap"]
+    tokens = wl.make_tokens(cfg)
+    B, N = tokens.shape
+    ctx = _ctx(cfg)
+    streams = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    rng = np.random.default_rng(9)
+    pos, first = 0, True
+    all_codes = [[] for _ in range(B)]
+    while pos < N:
+        step = int(rng.choice([1, 2, 7, 64, 65, 300]))
+        chunk = tokens[:, pos:pos + step]
+        codes, n_codes, status = gpu_encode(ctx, np.ascontiguousarray(chunk), None,
+                                            flags=api.RESET if first else api.APPEND)
+        for b in range(B):
+            rc, rst = streams[b].encode_chunk(chunk[b].tolist())
+            assert int(status[b]) == rst == 0
+            assert codes[b, : int(n_codes[b])].tolist() == rc, (b, pos, step)
+            all_codes[b] += rc
+        assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+        pos += step
+        first = False
+    for b in range(B):      # the joined stream decodes to the input with the same codebook
+        rt, rentries, rst = oracle.lzw_decode(all_codes[b], V, M, cap)
+        assert rst == 0 and rt == tokens[b].tolist() and rentries == streams[b].entries
+    ctx.close()
+
+
+def test_decode_steps_grow_codebook_by_at_most_one():
+    """The per-step update of generation: one new code per sequence, codebook-only decode (no token output)."""
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=6, N=4096)
+    V, M, cap = cfg["V"], cfg["M"], cfg["cap"]
+    tokens = wl.make_tokens(cfg)
+    B = cfg["B"]
+    ctx = _ctx(cfg)
+    streams = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    codes, n_codes, status = gpu_encode(ctx, tokens, None)
+    for b in range(B):
+        rc, _ = streams[b].encode_chunk(tokens[b].tolist())
+        assert codes[b, : len(rc)].tolist() == rc
+    grew = 0
+    for step in range(256):
+        sizes = np.array([len(s.entries) for s in streams])
+        new = wl.make_step_codes(cfg, sizes, step)
+        _, n_tok, st = gpu_decode(ctx, new.reshape(B, 1), None, out_stride=0, flags=api.APPEND)
+        for b in range(B):
+            rt, rst = streams[b].decode_chunk([int(new[b])])
+            assert int(st[b]) == rst == 0 and int(n_tok[b]) == len(rt)
+            assert 0 <= len(streams[b].entries) - sizes[b] <= 1
+            grew += len(streams[b].entries) - sizes[b]
+        if step % 32 == 31 or step < 3:
+            assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+    assert grew > 0
+    assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+    ctx.close()
+
+
+def test_repeatable_across_runs_and_sequence_order():
+    """No cross-sequence sharing: shuffling the batch permutes the outputs and nothing else."""
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=8, N=2048)
+    tokens = wl.make_tokens(cfg)
+    ctx = _ctx(cfg)
+    c1, n1, _ = gpu_encode(ctx, tokens, None)
+    c2, n2, _ = gpu_encode(ctx, tokens, None)
+    assert (c1 == c2).all() and (n1 == n2).all()
+    perm = np.random.default_rng(1).permutation(cfg["B"])
+    c3, n3, _ = gpu_encode(ctx, np.ascontiguousarray(tokens[perm]), None)
+    assert (n3 == n1[perm]).all()
+    for i, b in enumerate(perm):
+        assert (c3[i, : n3[i]] == c1[b, : n1[b]]).all()
+    ctx.close()
