@@ -1,0 +1,309 @@
+"""Benchmark of the zip2zip dynamic-vocabulary hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of configuration 2 (prefill at Llama-3-8B
+shapes: 8 x 4096 tokens, V = 128256, d = 4096 bf16, M = 3, cap = 2048), inputs resident in HBM:
+
+    lzw_encode (all tokens)  ->  hyper_embed (all entries)  ->  extended_logits (all 32768 rows)
+    ->  one generation step on the same batch: lzw_decode append of one new code per sequence (the
+        argmax of its last position), hyper_embed of the new entry, extended_logits for 8 rows
+    ->  lzw_decode of the whole code stream back to base tokens
+
+`value` is base tokens per second of that whole step.  The decode step of configuration 3 (64 sequences
+with 8192-token histories, HBM-bound) is timed separately in the same run and reported in `decode_step`.
+The CPU oracle is timed on a bounded sample of the same workload as `cpu_baseline`.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def to_device_bf16(torch, bits, dtype="bf16"):
+    """Host uint16 bf16 bit patterns -> device bfloat16 tensor (memory plumbing only)."""
+    import numpy as np
+
+    assert dtype == "bf16"
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+class Stage:
+    """Accumulates the time between two torch events recorded on the current stream."""
+
+    def __init__(self, torch, n):
+        self.torch = torch
+        self.ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        self.i = 0
+
+    def __enter__(self):
+        self.ev[self.i][0].record()
+
+    def __exit__(self, *exc):
+        self.ev[self.i][1].record()
+        self.i += 1
+
+    def total_ms(self):
+        return sum(a.elapsed_time(b) for a, b in self.ev[: self.i])
+
+
+def run_prefill_workload(args, torch, api, wl):
+    cfg = wl.CONFIGS["c2"]
+    B, N, V, M, cap, d = (cfg[k] for k in ("B", "N", "V", "M", "cap", "d"))
+    rows = B * N
+    t0 = time.time()
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    H = wl.make_hidden(cfg, rows)
+    log(f"[bench] c2 inputs generated in {time.time() - t0:.1f}s")
+    d_tok = torch.from_numpy(tokens).cuda()
+    d_E = to_device_bf16(torch, E, "bf16")          # tied: the matrix pooled is the LM head
+    d_H = to_device_bf16(torch, H, "bf16")
+    d_Hdec = d_H[N - 1::N].contiguous()             # one hidden row per sequence for the generation step
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16", pool="mean")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_codes = torch.empty((B, N), **i32)
+    d_ncodes = torch.empty(B, **i32)
+    d_status = torch.empty(B, **i32)
+    d_W = torch.empty((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    d_am = torch.empty(rows, **i32)
+    d_mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    d_lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    d_first = torch.empty(B, **i32)
+    d_one = torch.ones(B, **i32)
+    d_ntok1 = torch.empty(B, **i32)
+    d_st1 = torch.empty(B, **i32)
+    d_am1 = torch.empty(B, **i32)
+    d_mx1 = torch.empty(B, dtype=torch.float32, device="cuda")
+    d_lse1 = torch.empty(B, dtype=torch.float32, device="cuda")
+    d_back = torch.empty((B, N), **i32)
+    d_nback = torch.empty(B, **i32)
+    d_st2 = torch.empty(B, **i32)
+    size_view = ctx.codebook()[2]
+
+    names = ["lzw_encode", "hyper_embed", "extended_logits", "generation_step", "lzw_decode"]
+    stages = None
+
+    def step():
+        with stages["lzw_encode"]:
+            ctx.lzw_encode(d_tok, None, d_codes, d_ncodes, d_status, api.RESET)
+        with stages["hyper_embed"]:
+            ctx.hyper_embed(d_E, d_W)
+        with stages["extended_logits"]:
+            # the library brackets this call's dominant kernel (the base-vocabulary tile kernel) with HIP
+            # events on this stream; the switch is host-side only and does not synchronise
+            ctx.set_option(api.OPT_TIMING, 1)
+            ctx.extended_logits(d_H, N, d_E, d_W, d_am, d_mx, d_lse, None)
+            ctx.set_option(api.OPT_TIMING, 0)
+        with stages["generation_step"]:
+            d_first.copy_(size_view)
+            # code of sequence b = argmax of its last position = element b*N of the view starting at N-1
+            ctx.lzw_decode(d_am[N - 1:], d_one, None, d_ntok1, d_st1, api.APPEND, stride=N)
+            ctx.hyper_embed(d_E, d_W, d_first, max_new=1)
+            ctx.extended_logits(d_Hdec, 1, d_E, d_W, d_am1, d_mx1, d_lse1, None)
+        with stages["lzw_decode"]:
+            ctx.lzw_decode(d_codes, d_ncodes, d_back, d_nback, d_st2, api.RESET)
+
+    stages = {n: Stage(torch, args.warmup) for n in names}
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.read_timing()
+    stages = {n: Stage(torch, args.steps) for n in names}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms, launches = ctx.read_timing()
+
+    # sanity inside the bench: statuses clean, round trip exact
+    assert int(d_status.abs().sum()) == 0 and int(d_st1.abs().sum()) == 0 and int(d_st2.abs().sum()) == 0
+    assert torch.equal(d_back, d_tok), "lzw_decode(lzw_encode(x)) != x"
+    sizes = size_view.cpu().numpy()
+    ncodes = d_ncodes.cpu().numpy()
+
+    ms_per_step = dt * 1e3 / args.steps
+    stage_ms = {n: stages[n].total_ms() / args.steps for n in names}
+    flops_base = 2.0 * rows * d * V
+    flops_all = 2.0 * rows * d * (V + float(sizes.mean()))
+    out = dict(ms_per_step=ms_per_step, stage_ms=stage_ms, kernel_ms_total=kernel_ms, kernel_launches=launches,
+               flops_base=flops_base, flops_all=flops_all, sizes=sizes.tolist(), n_codes=ncodes.tolist(),
+               tokens=B * N, cfg=cfg)
+    host = dict(tokens=tokens, E=E, H=H)
+    ctx.close()
+    return out, host
+
+
+def run_decode_workload(args, torch, api, wl):
+    """Configuration 3: one decode step = codebook update for one new code per sequence, hyper_embed of
+    the new entry, extended_logits for one hidden row per sequence."""
+    cfg = wl.CONFIGS["c3"]
+    B, N, V, M, cap, d = (cfg[k] for k in ("B", "N", "V", "M", "cap", "d"))
+    t0 = time.time()
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    H = wl.make_hidden(cfg, B)
+    log(f"[bench] c3 inputs generated in {time.time() - t0:.1f}s")
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16", pool="mean")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_tok = torch.from_numpy(tokens).cuda()
+    d_codes = torch.empty((B, N), **i32)
+    d_n = torch.empty(B, **i32)
+    d_st = torch.empty(B, **i32)
+    d_E = to_device_bf16(torch, E, "bf16")
+    d_H = to_device_bf16(torch, H, "bf16")
+    d_W = torch.empty((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.lzw_encode(d_tok, None, d_codes, d_n, d_st, api.RESET)     # history (untimed)
+    ctx.hyper_embed(d_E, d_W)
+    torch.cuda.synchronize()
+    size_view = ctx.codebook()[2]
+    sizes = size_view.cpu().numpy()
+    n_steps = args.warmup + args.steps
+    new_codes = [torch.from_numpy(wl.make_step_codes(cfg, sizes, s).reshape(B, 1)).cuda() for s in range(n_steps)]
+    d_first = torch.empty(B, **i32)
+    d_ntok = torch.empty(B, **i32)
+    d_am = torch.empty(B, **i32)
+    d_mx = torch.empty(B, dtype=torch.float32, device="cuda")
+    d_lse = torch.empty(B, dtype=torch.float32, device="cuda")
+
+    def step(s):
+        d_first.copy_(size_view)
+        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
+        ctx.hyper_embed(d_E, d_W, d_first, max_new=1)
+        ctx.extended_logits(d_H, 1, d_E, d_W, d_am, d_mx, d_lse, None)
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, n_steps):
+        step(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(d_st.abs().sum()) == 0
+    sizes = size_view.cpu().numpy()
+    us = dt * 1e6 / args.steps
+    bytes_step = 2.0 * d * (V + float(sizes.sum())) + 2.0 * B * d
+    gbs = bytes_step / (us * 1e-6) / 1e9
+    ctx.close()
+    return dict(workload=cfg["name"], us_per_step=us, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
+                peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()))
+
+
+def cpu_baseline(wl, host, budget_rows=24):
+    """The oracle, as it stands, on the host cores: LZW and pooling on the full configuration-2 batch, the
+    joint logits on a sample of rows of sequence 0 (all columns); combined into tokens/s of the whole step."""
+    import numpy as np
+
+    import oracle
+
+    cfg = wl.CONFIGS["c2"]
+    B, N, V, M, cap = (cfg[k] for k in ("B", "N", "V", "M", "cap"))
+    tokens, E, H = host["tokens"], host["E"], host["H"]
+    t0 = time.perf_counter()
+    enc = [oracle.lzw_encode(tokens[b].tolist(), V, M, cap) for b in range(B)]
+    for b in range(B):
+        back, _, _ = oracle.lzw_decode(enc[b][0], V, M, cap)
+        assert back == tokens[b].tolist()
+    t_lzw = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    W0 = oracle.hyper_embed(E, "bf16", enc[0][1], cap, "mean")
+    t_embed = (time.perf_counter() - t0) * B                      # one sequence timed, B alike
+    t0 = time.perf_counter()
+    oracle.extended_logits(H[:budget_rows], E, W0, len(enc[0][1]), "bf16", return_logits=False)
+    t_rows = time.perf_counter() - t0
+    per_token = (t_lzw + t_embed) / (B * N) + t_rows / budget_rows
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return dict(value=1.0 / per_token, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=(f"config 2: LZW encode+decode of all {B * N} tokens ({t_lzw:.2f}s, 1 thread), mean pooling "
+                        f"of one sequence's {len(enc[0][1])} entries x{B} ({t_embed:.2f}s), joint logits+softmax of "
+                        f"{budget_rows} rows of sequence 0 over all {V + len(enc[0][1])} columns in float64 "
+                        f"({t_rows:.2f}s, BLAS threads); per-token costs summed"),
+                host_cpus=os.cpu_count())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2506_01084_amd import api, workloads as wl
+
+    torch.cuda.set_device(0)
+    api.load_library()
+    res, host = run_prefill_workload(args, torch, api, wl)
+    assert res["kernel_launches"] == args.steps
+    k_ms = res["kernel_ms_total"] / res["kernel_launches"]
+    log(f"[bench] step {res['ms_per_step']:.2f} ms; stages {res['stage_ms']}; base-part kernel {k_ms:.3f} ms")
+    dec = None if args.no_decode else run_decode_workload(args, torch, api, wl)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host)
+
+    cfg = res["cfg"]
+    achieved = res["flops_base"] / (k_ms * 1e-3) / 1e12
+    st = res["stage_ms"]
+    line = {
+        "metric": "base tokens/s LZW+hyper_embed; extended_logits TFLOP/s & decode-step µs",
+        "value": res["tokens"] / (res["ms_per_step"] * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: B={cfg['B']} x N={cfg['N']} tokens, V={cfg['V']}, d={cfg['d']} bf16, "
+                               f"M={cfg['M']}, cap={cfg['cap']}, mean pooling, logits for all {res['tokens']} rows "
+                               f"over V+C_b columns, plus one generation step and the final decompression"},
+        "submetrics": {
+            "lzw_encode_plus_hyper_embed_tokens_per_s": res["tokens"] / ((st["lzw_encode"] + st["hyper_embed"]) * 1e-3),
+            "extended_logits_TFLOPs": res["flops_all"] / (st["extended_logits"] * 1e-3) / 1e12,
+            "decode_step_us": None if dec is None else dec["us_per_step"],
+            "stage_ms": st,
+            "mean_codebook_size": sum(res["sizes"]) / len(res["sizes"]),
+            "compression_rate": sum(res["n_codes"]) / res["tokens"],
+        },
+        "roofline": {"bound": "mfma", "kernel": "logits_tile_kernel (base vocabulary part of the prefill call)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "avg_kernel_ms": k_ms, "flops_per_launch": res["flops_base"]},
+        "cpu_baseline": cpu,
+        "decode_step": dec,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

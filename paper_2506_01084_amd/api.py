@@ -138,11 +138,16 @@ class Context:
                                         _stream()), "z2z_lzw_encode")
 
     def lzw_decode(self, codes: torch.Tensor, n_codes: Optional[torch.Tensor], tokens: Optional[torch.Tensor],
-                   n_tokens: torch.Tensor, status: torch.Tensor, flags: int = RESET) -> None:
-        assert codes.shape[0] == self.B
+                   n_tokens: torch.Tensor, status: torch.Tensor, flags: int = RESET,
+                   stride: Optional[int] = None) -> None:
+        """`codes` is [B, stride]; with an explicit `stride` it may be any contiguous int32 tensor whose
+        element b*stride + i is code i of sequence b (lets a caller point into a larger array)."""
+        if stride is None:
+            assert codes.shape[0] == self.B
+            stride = codes.shape[1]
         out_stride = tokens.shape[1] if tokens is not None else 0
         _check(self._lib.z2z_lzw_decode(self._h, _ptr(codes, torch.int32), _ptr(n_codes, torch.int32),
-                                        codes.shape[1], flags, _ptr(tokens, torch.int32),
+                                        stride, flags, _ptr(tokens, torch.int32),
                                         _ptr(n_tokens, torch.int32), out_stride, _ptr(status, torch.int32),
                                         _stream()), "z2z_lzw_decode")
 
