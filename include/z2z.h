@@ -145,6 +145,10 @@ enum {
   Z2Z_OPT_LOGITS_STRIP = 2,    /* vocabulary tiles swept per workgroup, 0 = automatic               */
   Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant                               */
   Z2Z_OPT_DECODE_KERNEL = 4,   /* 0 = automatic, >0 = force a variant                               */
+  Z2Z_OPT_LOGITS_MAP = 6,      /* workgroup -> tile order of the bf16 MFMA kernel's base part, packed
+                                  lr | ls << 8 | xr << 16 | xs << 24: each of the 8 XCDs walks blocks of
+                                  lr row tiles x ls strips, the XCDs' blocks lie xr x xs (xr * xs = 8)
+                                  inside one super block; 0 = automatic                              */
   Z2Z_OPT_TIMING = 5           /* 1 = bracket the dominant kernel of every z2z_extended_logits call
                                   with HIP events on the call's stream (at most 1024 calls are kept
                                   between two z2z_read_timing calls); 0 = off (default)             */

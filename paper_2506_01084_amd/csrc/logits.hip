@@ -1,282 +1,14 @@
-// extended_logits for gfx950: H x [W_base ; W_hyper]^T on the matrix cores with the joint softmax
-// reduced on the fly (section 2.3 of the zip2zip paper, steps 7-9: the hyper rows are appended to
-// the LM head and one softmax is taken over the union of both vocabularies).
+// extended_logits: launch planning (which tile kernel, strips, workgroup mapping), the merge of the
+// per-strip partial triples, and the scratch buffer that holds them.
 //
-// Both operands are stored with the contraction index k contiguous, so a lane fetches 16 bytes of
-// a row for each MFMA operand.  The vocabulary rows are the MFMA "A" operand and the hidden rows
-// the "B" operand: in the 32x32 result block a lane then holds 16 vocabulary entries of ONE hidden
-// row, so the running (max, sum-exp, argmax) of a row is kept in that lane's registers and crosses
-// lanes only once per strip.  A workgroup owns one tile of hidden rows and sweeps a strip of
-// vocabulary tiles; each strip leaves one partial triple per row, merged by a small second kernel.
-// The logits matrix itself is never stored unless the caller asks for it.
-//
-// The base part (columns < V, shared W_base) and the hyper part (columns V.., one W_hyper per
-// sequence, only the first C_b rows exist) are two launches of the same kernel.
-#include "z2z_internal.h"
-
-#include <math.h>
+// The base part (columns < V, shared W_base) and the hyper part (columns V.., one W_hyper per sequence,
+// only the first C_b rows exist: section 2.3 of the zip2zip paper, "Consistent Vocabulary Updates") are
+// two launches; both leave (max, sum-exp, argmax) triples per (strip, row), merged in column order.
+#include "logits_common.h"
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-constexpr float kNegInf = -INFINITY;
-
-struct Triple {
-  float m;   // running maximum
-  float s;   // sum of exp(x - m)
-  int i;     // column of the maximum
-};
-
-// Merge b into a; equal maxima keep the lower column.
-__device__ __forceinline__ void merge_triple(Triple& a, const Triple& b) {
-  const bool b_wins = (b.m > a.m) || (b.m == a.m && b.i < a.i);
-  const float hi = b_wins ? b.m : a.m;
-  const float lo = b_wins ? a.m : b.m;
-  const float s_hi = b_wins ? b.s : a.s;
-  const float s_lo = b_wins ? a.s : b.s;
-  const float scale = (lo == kNegInf) ? 0.f : __expf(lo - hi);
-  a.s = s_hi + s_lo * scale;
-  a.m = hi;
-  a.i = b_wins ? b.i : a.i;
-}
-
-struct LogitsArgs {
-  const void* H;          // [rows, d]
-  const void* W;          // base: [V, d]; hyper: [B, cap, d]
-  const int32_t* size;    // hyper: [B] C_b; base: nullptr
-  int32_t rows, rows_per_seq, d;
-  int32_t w_rows;         // rows of one W matrix: V (base) or cap (hyper)
-  int32_t col0;           // column of this part's first entry in a logits row: 0 or V
-  int32_t n_vtiles;       // vocabulary tiles of one W matrix
-  int32_t strip;          // vocabulary tiles per workgroup
-  int32_t n_strips;       // strips of one W matrix
-  int32_t part0;          // index of this launch's first partial
-  int32_t row_tiles;      // base: tiles over all rows; hyper: tiles per sequence
-  int32_t hyper;          // 0 / 1
-  float* part_m;          // [parts, rows]
-  float* part_s;
-  int32_t* part_i;
-  float* logits;          // nullptr or [rows, ld]
-  int32_t ld;
-};
-
-// ------------------------------------------------------------------------------------------------
-// Tile kernel, 128 (vocabulary) x 128 (hidden rows) per workgroup, 4 waves of 64 x 64, K slabs of
-// 128 bytes per row.  LDS holds two buffers of (128 + 128) rows x 128 B; the 16-byte chunk c of row
-// r sits at chunk (c ^ (r & 7)) so that the 32 rows a half-wave reads hit all banks.
-// T = bf16 bits (uint16_t) or float.
-// ------------------------------------------------------------------------------------------------
-constexpr int TV = 128;
-constexpr int TR = 128;
-constexpr int SLAB_BYTES = 128;
-constexpr int TILE_BYTES = TV * SLAB_BYTES;   // one operand tile in LDS (16 KiB)
-
-template <typename T>
-__device__ __forceinline__ void mfma_chunk(const uint4& a, const uint4& b, f32x16& acc);
-
-template <>
-__device__ __forceinline__ void mfma_chunk<uint16_t>(const uint4& a, const uint4& b, f32x16& acc) {
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0,
-                                                0, 0);
-}
-
-template <>
-__device__ __forceinline__ void mfma_chunk<float>(const uint4& a, const uint4& b, f32x16& acc) {
-  // a 16-byte chunk holds 4 consecutive k; lanes 0-31 and 32-63 hold different chunks, and the
-  // pairing of k between the two operands is the same, so any order of the 4 steps is a valid sum
-  const f32x4 af = __builtin_bit_cast(f32x4, a);
-  const f32x4 bf = __builtin_bit_cast(f32x4, b);
-#pragma unroll
-  for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], bf[e], acc, 0, 0, 0);
-}
-
-template <typename T>
-__global__ void __launch_bounds__(256) logits_tile_kernel(LogitsArgs a) {
-  __shared__ __align__(16) unsigned char lds[4 * TILE_BYTES];   // [buf][A|B][TILE_BYTES]
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wv = wave & 1;    // which 64 vocabulary rows of the tile
-  const int wr = wave >> 1;   // which 64 hidden rows of the tile
-
-  // ---- which rows, which W, which strip ---------------------------------------------------------
-  const int st = blockIdx.x % a.n_strips;
-  const int rt = blockIdx.x / a.n_strips;
-  int r0, r_end, n_valid;
-  const unsigned char* Wp = reinterpret_cast<const unsigned char*>(a.W);
-  const size_t row_bytes = (size_t)a.d * sizeof(T);
-  if (a.hyper) {
-    const int b = rt / a.row_tiles;
-    r0 = b * a.rows_per_seq + (rt % a.row_tiles) * TR;
-    r_end = (b + 1) * a.rows_per_seq;
-    n_valid = min(max(a.size[b], 0), a.w_rows);
-    Wp += (size_t)b * a.w_rows * row_bytes;
-  } else {
-    r0 = rt * TR;
-    r_end = a.rows;
-    n_valid = a.w_rows;
-  }
-  const unsigned char* Hp = reinterpret_cast<const unsigned char*>(a.H);
-  const int vt0 = st * a.strip;
-  const int vt1 = min(vt0 + a.strip, a.n_vtiles);
-
-  Triple run[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    run[j].m = kNegInf;
-    run[j].s = 0.f;
-    run[j].i = 0x7FFFFFFF;
-  }
-
-  // global -> LDS staging: thread t moves chunks t, t+256, t+512, t+768 of each operand tile
-  const int n_slabs = (int)((row_bytes + SLAB_BYTES - 1) / SLAB_BYTES);
-
-  for (int vt = vt0; vt < vt1; ++vt) {
-    const int v0 = vt * TV;
-    if (v0 >= n_valid) break;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    uint4 stage_a[4], stage_b[4];
-    auto fetch = [&](int slab) {
-      const size_t kb = (size_t)slab * SLAB_BYTES;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i;
-        const int row = id >> 3;
-        const int c = id & 7;
-        const size_t off = kb + (size_t)c * 16;
-        const bool in_k = off < row_bytes;
-        const int wrow = min(v0 + row, n_valid - 1);
-        const int hrow = min(r0 + row, r_end - 1);
-        const uint4 z = {0u, 0u, 0u, 0u};
-        stage_a[i] = in_k ? *reinterpret_cast<const uint4*>(Wp + (size_t)wrow * row_bytes + off) : z;
-        stage_b[i] = in_k ? *reinterpret_cast<const uint4*>(Hp + (size_t)hrow * row_bytes + off) : z;
-      }
-    };
-    auto stash = [&](int buf) {
-      unsigned char* A = lds + (size_t)buf * 2 * TILE_BYTES;
-      unsigned char* Bt = A + TILE_BYTES;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i;
-        const int row = id >> 3;
-        const int c = id & 7;
-        const int o = row * SLAB_BYTES + ((c ^ (row & 7)) << 4);
-        *reinterpret_cast<uint4*>(A + o) = stage_a[i];
-        *reinterpret_cast<uint4*>(Bt + o) = stage_b[i];
-      }
-    };
-
-    fetch(0);
-    __syncthreads();          // the previous tile's readers are done with buffer 0
-    stash(0);
-    __syncthreads();
-    for (int slab = 0; slab < n_slabs; ++slab) {
-      const int buf = slab & 1;
-      if (slab + 1 < n_slabs) fetch(slab + 1);
-      const unsigned char* A = lds + (size_t)buf * 2 * TILE_BYTES;
-      const unsigned char* Bt = A + TILE_BYTES;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int chunk = 2 * q + (lane >> 5);
-        uint4 fa[2], fb[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int row = wv * 64 + i * 32 + (lane & 31);
-          fa[i] = *reinterpret_cast<const uint4*>(A + row * SLAB_BYTES + ((chunk ^ (row & 7)) << 4));
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int row = wr * 64 + j * 32 + (lane & 31);
-          fb[j] = *reinterpret_cast<const uint4*>(Bt + row * SLAB_BYTES + ((chunk ^ (row & 7)) << 4));
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) mfma_chunk<T>(fa[i], fb[j], acc[i][j]);
-      }
-      if (slab + 1 < n_slabs) {
-        stash(buf ^ 1);       // buffer buf^1 was last read two slabs ago, behind the barrier below
-        __syncthreads();
-      }
-    }
-
-    // ---- epilogue of this tile: fold the 128 x 128 logits into the running triples -------------
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int hrow = r0 + wr * 64 + j * 32 + (lane & 31);
-      float tmax = kNegInf;
-      int targ = 0x7FFFFFFF;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int col = v0 + wv * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          float x = acc[i][j][v];
-          if (col >= n_valid) x = kNegInf;
-          acc[i][j][v] = x;
-          if (x > tmax) {
-            tmax = x;
-            targ = col;
-          }
-          if (a.logits != nullptr && col < n_valid && hrow < r_end) a.logits[(size_t)hrow * a.ld + a.col0 + col] = x;
-        }
-      if (tmax > run[j].m) {
-        run[j].s = (run[j].m == kNegInf) ? 0.f : run[j].s * __expf(run[j].m - tmax);
-        run[j].m = tmax;
-        run[j].i = a.col0 + targ;
-      }
-      if (run[j].m != kNegInf) {
-        float add = 0.f;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) add += __expf(acc[i][j][v] - run[j].m);
-        run[j].s += add;
-      }
-    }
-  }
-
-  // ---- end of strip: lanes l and l+32 hold the same hidden row; then the two vocabulary halves ---
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    Triple o;
-    o.m = __shfl_xor(run[j].m, 32);
-    o.s = __shfl_xor(run[j].s, 32);
-    o.i = __shfl_xor(run[j].i, 32);
-    merge_triple(run[j], o);
-  }
-  __syncthreads();            // all waves are done reading the operand tiles
-  Triple* xch = reinterpret_cast<Triple*>(lds);   // [2 row halves][64 rows]
-  if (wv == 1 && lane < 32) {
-    xch[wr * 64 + lane] = run[0];
-    xch[wr * 64 + 32 + lane] = run[1];
-  }
-  __syncthreads();
-  if (wv == 0 && lane < 32) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      merge_triple(run[j], xch[wr * 64 + j * 32 + lane]);
-      const int hrow = r0 + wr * 64 + j * 32 + lane;
-      if (hrow < r_end) {
-        const size_t p = (size_t)(a.part0 + st) * a.rows + hrow;
-        a.part_m[p] = run[j].m;
-        a.part_s[p] = run[j].s;
-        a.part_i[p] = run[j].i;
-      }
-    }
-  }
-}
+using namespace z2z_logits;
 
 // One thread per hidden row: merge the row's partial triples in column order.
 __global__ void __launch_bounds__(256) logits_combine_kernel(const float* part_m, const float* part_s,
@@ -284,10 +16,7 @@ __global__ void __launch_bounds__(256) logits_combine_kernel(const float* part_m
                                                              int32_t* argmax, float* mx, float* lse) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= rows) return;
-  Triple t;
-  t.m = kNegInf;
-  t.s = 0.f;
-  t.i = 0x7FFFFFFF;
+  Triple t = empty_triple();
   for (int p = 0; p < n_parts; ++p) {
     Triple o;
     o.m = part_m[(size_t)p * rows + r];
@@ -327,15 +56,61 @@ int ensure_scratch(z2z_ctx* c, size_t need) {
   return Z2Z_OK;
 }
 
-template <typename T>
-int launch_tiles(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
-                 const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits, hipStream_t s) {
-  const int V = c->cfg.V, cap = c->cfg.cap, B = c->cfg.B;
-  const int base_vtiles = (V + TV - 1) / TV;
-  const int hyp_vtiles = (cap + TV - 1) / TV;
-  int strip = c->opt_logits_strip > 0 ? c->opt_logits_strip : 16;
-  const int base_strips = (base_vtiles + strip - 1) / strip;
-  const int hyp_strips = cap > 0 ? (hyp_vtiles + strip - 1) / strip : 0;
+
+int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, int w_rows, int col0, int part0,
+                int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed, hipStream_t s) {
+  const int tile = fast ? 256 : 128;
+  const int B = c->cfg.B;
+  a.W = W;
+  a.size = hyper ? c->st.size : nullptr;
+  a.w_rows = w_rows;
+  a.col0 = col0;
+  a.n_vtiles = (w_rows + tile - 1) / tile;
+  a.strip = strip;
+  a.n_strips = (a.n_vtiles + strip - 1) / strip;
+  a.part0 = part0;
+  a.row_tiles = hyper ? (rows_per_seq + tile - 1) / tile : (rows + tile - 1) / tile;
+  a.n_work = (hyper ? B : 1) * a.row_tiles * a.n_strips;
+  *n_strips_out = a.n_strips;
+  unsigned grid = (unsigned)a.n_work;
+  if (fast && !hyper) {
+    const int m = c->opt_logits_map;
+    a.map_lr = m ? (m & 0xFF) : 4;
+    a.map_ls = m ? ((m >> 8) & 0xFF) : 8;
+    a.map_xr = m ? ((m >> 16) & 0xFF) : 4;
+    a.map_xs = m ? ((m >> 24) & 0xFF) : 2;
+    const int sb_rows = a.map_xr * a.map_lr, sb_strips = a.map_xs * a.map_ls;
+    a.map_sb_r = (a.row_tiles + sb_rows - 1) / sb_rows;
+    const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;
+    grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
+  }
+  if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
+  int rc = fast ? z2z_launch_logits_fast(hyper, a, grid, s)
+                : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);
+  if (timed) {
+    Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
+    c->n_timed++;
+  }
+  return rc;
+}
+
+}  // namespace
+
+int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                               const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
+                               hipStream_t s) {
+  const int V = c->cfg.V, cap = c->cfg.cap;
+  const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready;
+  bool fast_base = fast_ok && rows > 128;
+  bool fast_hyper = fast_ok && rows_per_seq > 128;
+  if (c->opt_logits_kernel == 1) fast_base = fast_hyper = false;
+  if (c->opt_logits_kernel == 2) fast_base = fast_hyper = fast_ok;
+  const int strip = c->opt_logits_strip > 0 ? c->opt_logits_strip : 8;
+
+  // number of parts (strips of both launches), then the scratch for them
+  const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;
+  const int base_strips = (((V + base_tile - 1) / base_tile) + strip - 1) / strip;
+  const int hyp_strips = cap > 0 ? (((cap + hyp_tile - 1) / hyp_tile) + strip - 1) / strip : 0;
   const int n_parts = base_strips + hyp_strips;
   int rc = ensure_scratch(c, (size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
@@ -345,46 +120,20 @@ int launch_tiles(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, 
   a.rows = rows;
   a.rows_per_seq = rows_per_seq;
   a.d = c->cfg.d;
-  a.strip = strip;
   a.part_m = c->part_m;
   a.part_s = c->part_s;
   a.part_i = c->part_i;
   a.logits = logits;
   a.ld = V + cap;
+  a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
 
-  // base part
-  a.W = W_base;
-  a.size = nullptr;
-  a.w_rows = V;
-  a.col0 = 0;
-  a.n_vtiles = base_vtiles;
-  a.n_strips = base_strips;
-  a.part0 = 0;
-  a.row_tiles = (rows + TR - 1) / TR;
-  a.hyper = 0;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
-  if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  hipLaunchKernelGGL(logits_tile_kernel<T>, dim3((unsigned)a.row_tiles * base_strips), dim3(256), 0, s, a);
-  if (timed) {
-    Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
-    c->n_timed++;
-  }
-  Z2Z_HIP_TRY(hipGetLastError());
-
-  // hyper part
+  int ns = 0;
+  rc = launch_part(c, false, fast_base, a, W_base, V, 0, 0, strip, rows, rows_per_seq, &ns, timed, s);
+  if (rc != Z2Z_OK) return rc;
   if (cap > 0) {
-    a.W = W_hyper;
-    a.size = c->st.size;
-    a.w_rows = cap;
-    a.col0 = V;
-    a.n_vtiles = hyp_vtiles;
-    a.n_strips = hyp_strips;
-    a.part0 = base_strips;
-    a.row_tiles = (rows_per_seq + TR - 1) / TR;
-    a.hyper = 1;
-    // a workgroup whose strip starts beyond C_b leaves its partials untouched: preset them to "empty"
-    hipLaunchKernelGGL(logits_tile_kernel<T>, dim3((unsigned)B * a.row_tiles * hyp_strips), dim3(256), 0, s, a);
-    Z2Z_HIP_TRY(hipGetLastError());
+    rc = launch_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip, rows, rows_per_seq, &ns, false, s);
+    if (rc != Z2Z_OK) return rc;
     if (logits) {
       hipLaunchKernelGGL(logits_mask_kernel, dim3(rows), dim3(256), 0, s, logits, rows, rows_per_seq, V, cap,
                          c->st.size);
@@ -395,14 +144,4 @@ int launch_tiles(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, 
                      c->part_i, n_parts, rows, argmax, mx, lse);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
-}
-
-}  // namespace
-
-int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
-                               const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
-                               hipStream_t s) {
-  if (c->cfg.dtype == Z2Z_BF16)
-    return launch_tiles<uint16_t>(c, H, rows, rows_per_seq, W_base, W_hyper, argmax, mx, lse, logits, s);
-  return launch_tiles<float>(c, H, rows, rows_per_seq, W_base, W_hyper, argmax, mx, lse, logits, s);
 }

@@ -6,6 +6,8 @@
 #include <new>
 #include <string.h>
 
+#include "logits_common.h"
+
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -96,6 +98,7 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
     free_ctx(c);
     return Z2Z_ENOMEM;
   }
+  c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
   if (z2z_lzw_prepare(c) != Z2Z_OK || z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
     free_ctx(c);
@@ -180,6 +183,12 @@ Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {
       return Z2Z_OK;
     case Z2Z_OPT_LZW_KERNEL: ctx->opt_lzw_kernel = value; return Z2Z_OK;
     case Z2Z_OPT_DECODE_KERNEL: ctx->opt_decode_kernel = value; return Z2Z_OK;
+    case Z2Z_OPT_LOGITS_MAP:
+      if (value != 0 && ((value & 0xFF) < 1 || ((value >> 8) & 0xFF) < 1 || ((value >> 16) & 0xFF) < 1 ||
+                         ((value >> 24) & 0xFF) < 1 || ((value >> 16) & 0xFF) * ((value >> 24) & 0xFF) != 8))
+        return Z2Z_EINVAL;
+      ctx->opt_logits_map = value;
+      return Z2Z_OK;
     case Z2Z_OPT_TIMING:
       if (value && !ctx->ev_created) {
         for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {

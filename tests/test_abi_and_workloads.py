@@ -48,7 +48,7 @@ def test_binding_constants_match_header():
     assert api.APPEND == enum_value("Z2Z_APPEND") and api.RESET == enum_value("Z2Z_RESET")
     assert api.ST_BAD_TOKEN == enum_value("Z2Z_ST_BAD_TOKEN") and api.ST_BAD_CODE == enum_value("Z2Z_ST_BAD_CODE")
     assert api.ST_OVERFLOW == enum_value("Z2Z_ST_OVERFLOW")
-    for k in ("LOGITS_KERNEL", "LOGITS_STRIP", "LZW_KERNEL", "DECODE_KERNEL", "TIMING"):
+    for k in ("LOGITS_KERNEL", "LOGITS_STRIP", "LZW_KERNEL", "DECODE_KERNEL", "TIMING", "LOGITS_MAP"):
         assert getattr(api, "OPT_" + k) == enum_value("Z2Z_OPT_" + k)
     assert api.MAX_M == int(re.search(r"#define\s+Z2Z_MAX_M\s+(\d+)", text).group(1))
     # the config struct mirrors the header field for field
