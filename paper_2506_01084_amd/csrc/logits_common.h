@@ -45,6 +45,57 @@ __device__ __forceinline__ void merge_triple(Triple& a, const Triple& b) {
   a.i = b_wins ? b.i : a.i;
 }
 
+// One accumulator element, AGPR -> VGPR.  Spelled as an instruction so that the accumulators stay in
+// the accumulation registers and are fetched block by block: left to itself the compiler copies the whole
+// accumulator tile into VGPRs at the end of the K loop, and what that displaces is spilled inside the loop.
+__device__ __forceinline__ float read_acc(float in_agpr) {
+  float x;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(in_agpr));
+  return x;
+}
+
+// Fold one finished accumulator tile into the running triples.  acc[i][j] is a 32x32 MFMA result block:
+// register v of this lane is the logit of hidden row (j, lane & 31) and vocabulary column
+// col_base + i * 32 + (v >> 2) * 8 + (v & 3), where col_base already holds the tile origin, the wave's
+// offset and (lane >> 5) * 4.  Columns at and beyond n_valid do not exist (read as -inf; only tail tiles
+// pay for that test).  The fold goes block by block (16 values live at a time, the accumulators are
+// only read), in increasing column order per lane, so strict comparisons keep the lowest column among
+// equal maxima.
+template <int NI, int NJ>
+__device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], int col_base, int col0,
+                                          int n_valid, bool tail) {
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float x[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        x[v] = read_acc(acc[i][j][v]);
+        if (tail && col_base + i * 32 + (v >> 2) * 8 + (v & 3) >= n_valid) x[v] = kNegInf;
+      }
+      float gmax = x[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) gmax = fmaxf(gmax, x[v]);
+      if (gmax > run[j].m) {
+        int targ = 15;
+#pragma unroll
+        for (int v = 14; v >= 0; --v) targ = (x[v] == gmax) ? v : targ;
+        run[j].s = (run[j].m == kNegInf) ? 0.f : run[j].s * __expf(run[j].m - gmax);
+        run[j].m = gmax;
+        run[j].i = col0 + col_base + i * 32 + (targ >> 2) * 8 + (targ & 3);
+      }
+      if (run[j].m != kNegInf) {
+        const float m = run[j].m;
+        float add = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) add += __expf(x[v] - m);
+        run[j].s += add;
+      }
+    }
+  }
+}
+
 // Arguments of one tile-kernel launch (base part or hyper part).
 struct LogitsArgs {
   const void* H;          // [rows, d]

@@ -1,18 +1,23 @@
-// extended_logits, bf16 MFMA kernel for gfx950 (d a multiple of 64).
+// extended_logits, bf16 MFMA kernel for gfx950 (d a multiple of 32), one wave per SIMD.
 //
-// Workgroup tile 256 (vocabulary rows, MFMA "A") x 256 (hidden rows, MFMA "B"), 8 waves in a 2 x 4 grid,
-// each wave 128 x 64 = 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers per lane).
-// K advances in slabs of 64 elements (128 bytes per row).  Both operand tiles of a slab (2 x 32 KiB) are
-// written straight from global memory into LDS by 16-byte global_load ... lds instructions, double
-// buffered: slab s+1 streams in while slab s is multiplied, one barrier per slab.  The stream runs on
-// across the vocabulary tiles of a strip, so the first slab of the next tile is in flight during the
-// softmax fold of the current one.  Two waves per SIMD: one wave's LDS reads and its softmax arithmetic
-// overlap the other's MFMAs.
+// Workgroup tile 256 (vocabulary rows, MFMA "A") x 256 (hidden rows, MFMA "B"), 4 waves in a 2 x 2 grid,
+// each wave 128 x 128 = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 accumulator registers per lane):
+// per 16-deep k-step a wave reads 8 operand fragments from LDS for 16 MFMAs, which keeps the LDS read
+// port at about half of its 128 B/clk (a 128 x 64 wave tile needs three quarters of it and starves the
+// matrix cores).  With one wave per SIMD all overlap is inside the instruction stream: the fragments of
+// k-step t+1 are read while the MFMAs of k-step t run, and global->LDS requests are issued three slabs
+// ahead.
 //
-// LDS layout of an operand tile: row r = 128 bytes = 8 chunks of 16 B; chunk c is stored at position
-// c ^ (r & 7).  A wave's direct load writes 1 KiB = 8 rows in lane order, so lane l fetches global chunk
-// (l & 7) ^ (l >> 3) of row l >> 3; the MFMA operand reads (32 rows x one chunk per half-wave) then
-// touch every bank once.
+// K advances in slabs of 32 elements (64 bytes per row, two k-steps).  Both operand tiles of a slab
+// (2 x 16 KiB) go straight from global memory into LDS (16-byte global_load ... lds) into a ring of 4
+// stages.  Once per slab, in the middle of its second k-step, the waves meet at a barrier: at that
+// point everybody has read the slab completely (its stage is refilled with slab s+4) and slab s+1 has
+// landed (its first fragments are read next).  The stream runs on across the vocabulary tiles of a strip.
+//
+// LDS layout of an operand tile: row r = 64 bytes = 4 chunks of 16 B; chunk c is stored at position
+// c ^ ((r >> 2) & 3).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a
+// time; an MFMA operand read has 16 consecutive lanes on 16 consecutive rows at one logical chunk, whose
+// bank group is (r & 3) * 4 + position -- all 16 distinct with this swizzle.
 //
 // In the 32x32 result block a lane holds 16 vocabulary entries of one hidden row, so the running
 // (max, sum-exp, argmax) of the joint softmax (zip2zip paper, section 2.3, step 8) lives in registers
@@ -24,21 +29,22 @@ namespace {
 using namespace z2z_logits;
 
 constexpr int FT = 256;                   // tile edge, vocabulary and hidden rows
-constexpr int F_SLAB = 128;               // bytes per row per K slab
-constexpr int F_OPER = FT * F_SLAB;       // one operand tile of one slab: 32 KiB
+constexpr int F_SLAB = 64;                // bytes per row per K slab (32 bf16)
+constexpr int F_OPER = FT * F_SLAB;       // one operand tile of one slab: 16 KiB
 constexpr int F_STAGE = 2 * F_OPER;       // A + B
-constexpr int F_LDS = 2 * F_STAGE;        // two stages: 128 KiB
-constexpr int F_THREADS = 512;
+constexpr int F_NSTAGE = 4;
+constexpr int F_LDS = F_NSTAGE * F_STAGE; // 128 KiB
+constexpr int F_THREADS = 256;
 
-// 16 bytes per lane, global -> LDS without passing through registers.  The LDS address is the
-// wave-uniform byte offset in M0 plus 16 * lane.  Written as inline assembly on purpose: the compiler
-// cannot tell the two LDS stages apart and would make every LDS read wait for all outstanding direct
-// loads, which serialises the pipeline.  Completion is awaited explicitly (s_waitcnt vmcnt(0)) before
-// the barrier that publishes a stage.  One wait state is required between the write of M0 and its use.
-__device__ __forceinline__ void load16_to_lds(const unsigned char* g, uint32_t lds_byte_offset) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+// 16 bytes per lane, global -> LDS without passing through registers: address = 64-bit scalar base +
+// 32-bit per-lane offset; the LDS address is the wave-uniform byte offset in M0 plus 16 * lane.  Inline
+// assembly on purpose: the compiler cannot tell the LDS stages apart and would make every LDS read wait
+// for all outstanding direct loads.  Completion is awaited explicitly (s_waitcnt vmcnt) before the
+// barrier that publishes a stage.  One wait state is required between the write of M0 and its use.
+__device__ __forceinline__ void load16_to_lds(const unsigned char* base, uint32_t lane_offset, uint32_t lds_byte_offset) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(g), "s"(lds_byte_offset)
+               : "v"(lane_offset), "s"(base), "s"(lds_byte_offset)
                : "memory");   // M0 is reserved: the compiler keeps nothing in it across statements
 }
 
@@ -64,6 +70,11 @@ __device__ __forceinline__ bool map_base(const LogitsArgs& a, int bid, int* rt, 
   return *rt < a.row_tiles && *st < a.n_strips;
 }
 
+struct Frags {
+  uint4 a[4];
+  uint4 b[4];
+};
+
 template <int HYPER>
 __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
@@ -71,7 +82,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wv = wave & 1;    // which 128 vocabulary rows of the tile
-  const int wr = wave >> 1;   // which 64 hidden rows of the tile
+  const int wr = wave >> 1;   // which 128 hidden rows of the tile
 
   int rt, st;
   int r0, r_end, n_valid;
@@ -92,170 +103,150 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     r_end = a.rows;
     n_valid = a.w_rows;
   }
-  const unsigned char* Hp = reinterpret_cast<const unsigned char*>(a.H);
+  const unsigned char* Hp = reinterpret_cast<const unsigned char*>(a.H) + (size_t)r0 * row_bytes;
   const int vt0 = st * a.strip;
   const int vt_end = min(min(vt0 + a.strip, a.n_vtiles), (n_valid + FT - 1) / FT);
   const int n_tiles = vt_end - vt0;          // vocabulary tiles this workgroup sweeps (may be <= 0)
   const int n_slabs = (int)(row_bytes / F_SLAB);
 
-  Triple run[2];
-  run[0] = empty_triple();
-  run[1] = empty_triple();
+  Triple run[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) run[j] = empty_triple();
 
   // ---- loader: lane l of wave w, instruction i moves the chunk that lands at LDS byte
-  //      ((w * 4 + i) * 8 + (l >> 3)) * 128 + (l & 7) * 16 of the operand tile --------------------------
+  //      ((w * 4 + i) * 16 + (l >> 2)) * 64 + (l & 3) * 16 of the operand tile; offsets are relative to
+  //      the first row of the tile, rows past the last valid one are clamped onto it ------------------
   const uint32_t lds_base = lds_offset_of(lds);
-  const int ld_row = lane >> 3;
-  const int ld_chunk = (lane & 7) ^ ld_row;
-  const unsigned char* gB[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (wave * 4 + i) * 8 + ld_row;
-    gB[i] = Hp + (size_t)min(r0 + row, r_end - 1) * row_bytes + ld_chunk * 16;
-  }
-  const unsigned char* gA[4];
+  const int ld_row = lane >> 2;                                  // row inside the 16-row group
+  const int ld_chunk16 = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;  // (row >> 2) & 3 == (lane >> 4) & 3
+  const int limB = r_end - 1 - r0;                               // last valid hidden row of the tile
+  const unsigned char* Wtile = Wp;
+  int limA = 0;                                                  // last valid vocabulary row of the tile
   auto set_tile = [&](int vt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = (wave * 4 + i) * 8 + ld_row;
-      gA[i] = Wp + (size_t)min(vt * FT + row, n_valid - 1) * row_bytes + ld_chunk * 16;
-    }
+    Wtile = Wp + (size_t)vt * FT * row_bytes;
+    limA = n_valid - 1 - vt * FT;
   };
-  auto issue = [&](int slab, int stage) {
-    const uint32_t A = lds_base + stage * F_STAGE + wave * 4096;
-    const uint32_t Bt = A + F_OPER;
-    const size_t kb = (size_t)slab * F_SLAB;
+  // request the slab that follows (lslab, lvt) in the stream, if any, and advance the cursor; the
+  // per-lane offsets are recomputed each time (a few VALU operations) rather than kept in registers
+  int lslab = 0, lvt = vt0;
+  auto issue_next = [&](int stage) {
+    if (lvt < vt_end) {
+      const uint32_t A = lds_base + stage * F_STAGE + wave * 4096;
+      const uint32_t Bt = A + F_OPER;
+      const unsigned char* ga = Wtile + (size_t)lslab * F_SLAB;
+      const unsigned char* gb = Hp + (size_t)lslab * F_SLAB;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      load16_to_lds(gA[i] + kb, A + i * 1024);
-      load16_to_lds(gB[i] + kb, Bt + i * 1024);
+      for (int i = 0; i < 4; ++i) {
+        const int row = (wave * 4 + i) * 16 + ld_row;
+        load16_to_lds(ga, (uint32_t)(min(row, limA) * (int)row_bytes + ld_chunk16), A + i * 1024);
+        load16_to_lds(gb, (uint32_t)(min(row, limB) * (int)row_bytes + ld_chunk16), Bt + i * 1024);
+      }
+      if (++lslab == n_slabs) {
+        lslab = 0;
+        ++lvt;
+        if (lvt < vt_end) set_tile(lvt);
+      }
     }
   };
 
   // ---- MFMA operand addresses (bytes inside an operand tile), swizzle folded in ---------------------
-  const int sw = lane & 7;
+  const int sw = (lane >> 2) & 3;   // ((row >> 2) & 3) of every row this lane reads
   const int half = lane >> 5;
-  int offA[4], offB[2];
+  const int offA0 = (wv * 128 + (lane & 31)) * F_SLAB;
+  const int offB0 = (wr * 128 + (lane & 31)) * F_SLAB;
+  auto read_frags = [&](Frags& f, int stage, int q) {
+    const unsigned char* A = lds + stage * F_STAGE + offA0 + (((2 * q + half) ^ sw) << 4);
+    const unsigned char* Bt = lds + stage * F_STAGE + F_OPER + offB0 + (((2 * q + half) ^ sw) << 4);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) offA[i] = (wv * 128 + i * 32 + (lane & 31)) * F_SLAB;
+    for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const uint4*>(A + i * 32 * F_SLAB);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) offB[j] = (wr * 64 + j * 32 + (lane & 31)) * F_SLAB;
+    for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const uint4*>(Bt + j * 32 * F_SLAB);
+  };
 
-  f32x16 acc[4][2];
+  f32x16 acc[4][4];
   auto zero_acc = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  };
+  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi) {
+#pragma unroll
+    for (int i = i_lo; i < i_hi; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
+                                                            __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
   };
 
   if (n_tiles > 0) {
     zero_acc();
     set_tile(vt0);
-    issue(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's direct loads have landed
-    __syncthreads();
     const int total = n_tiles * n_slabs;
-    int slab = 0, vt = vt0;
-    for (int g = 0; g < total; ++g) {
-      const int stage = g & 1;
-      // stream in the next slab (possibly the first slab of the next vocabulary tile)
-      if (g + 1 < total) {
-        if (slab + 1 == n_slabs) {
-          set_tile(vt + 1);
-          issue(0, stage ^ 1);
-        } else {
-          issue(slab + 1, stage ^ 1);
+    // prologue: slabs 0..3 requested, slab 0 landed and visible, its first fragments on the way
+    issue_next(0);
+    issue_next(1);
+    issue_next(2);
+    issue_next(3);
+    if (total >= 4)
+      __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): all but the youngest three slabs (8 requests each)
+    else
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    Frags f0, f1;
+    read_frags(f0, 0, 0);
+    int g = 0;
+    for (int vt = vt0; vt < vt_end; ++vt) {
+      for (int slab = 0; slab < n_slabs; ++slab, ++g) {
+        const int stage = g & (F_NSTAGE - 1);
+        // k-step 0 of the slab: fragments in f0; fetch k-step 1
+        read_frags(f1, stage, 1);
+        mfma_rows(f0, 0, 4);
+        // k-step 1: fragments in f1.  Half of its MFMAs, then the slab hand-over, then the other half.
+        mfma_rows(f1, 0, 2);
+        if (g + 1 < total) {
+          // slab g+1 must have landed; requests return in order, 8 per slab and wave, and slabs g+2, g+3
+          // may still be in flight
+          if (g + 3 >= total)
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): tail of the stream
+          else
+            __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+          __syncthreads();                        // slab g+1 visible to all; everyone has read slab g
+          issue_next(stage);                      // refill this stage with slab g+4
+          read_frags(f0, (g + 1) & (F_NSTAGE - 1), 0);
         }
+        mfma_rows(f1, 2, 4);
       }
-      const unsigned char* A = lds + stage * F_STAGE;
-      const unsigned char* Bt = A + F_OPER;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int pos = ((2 * q + half) ^ sw) << 4;
-        uint4 fa[4], fb[2];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(A + offA[i] + pos);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const uint4*>(Bt + offB[j] + pos);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-      }
-
-      if (slab + 1 == n_slabs) {
-        // ---- this vocabulary tile is complete: fold its 128 x 64 logits into the running triples -----
-        const int v0 = vt * FT;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int hrow = r0 + wr * 64 + j * 32 + (lane & 31);
-          float tmax = kNegInf;
-          int targ = kNoColumn;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int col = v0 + wv * 128 + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-              float x = acc[i][j][v];
-              if (col >= n_valid) x = kNegInf;
-              acc[i][j][v] = x;
-              if (x > tmax) {
-                tmax = x;
-                targ = col;
-              }
-              if (a.logits != nullptr && col < n_valid && hrow < r_end)
-                a.logits[(size_t)hrow * a.ld + a.col0 + col] = x;
-            }
-          if (tmax > run[j].m) {
-            run[j].s = (run[j].m == kNegInf) ? 0.f : run[j].s * __expf(run[j].m - tmax);
-            run[j].m = tmax;
-            run[j].i = a.col0 + targ;
-          }
-          if (run[j].m != kNegInf) {
-            float add = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) add += __expf(acc[i][j][v] - run[j].m);
-            run[j].s += add;
-          }
-        }
-        zero_acc();
-        slab = 0;
-        ++vt;
-      } else {
-        ++slab;
-      }
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // the next slab is in LDS ...
-      __syncthreads();                      // ... for every wave, and everyone is done with this one
+      // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
+      const int v0 = vt * FT;
+      fold_tile<4, 4>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
+      zero_acc();
     }
   }
 
   // ---- end of strip: lanes l and l+32 hold the same hidden row; then the two vocabulary halves ------
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < 4; ++j) {
     Triple o;
     o.m = __shfl_xor(run[j].m, 32);
     o.s = __shfl_xor(run[j].s, 32);
     o.i = __shfl_xor(run[j].i, 32);
     merge_triple(run[j], o);
   }
-  Triple* xch = reinterpret_cast<Triple*>(lds);   // [4 row quarters][64 rows]; operand tiles are idle now
+  __syncthreads();                                 // every wave is done with the operand stages
+  Triple* xch = reinterpret_cast<Triple*>(lds);    // [2 row halves][128 rows]
   if (wv == 1 && lane < 32) {
-    xch[wr * 64 + lane] = run[0];
-    xch[wr * 64 + 32 + lane] = run[1];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) xch[wr * 128 + j * 32 + lane] = run[j];
   }
   __syncthreads();
   if (wv == 0 && lane < 32) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      merge_triple(run[j], xch[wr * 64 + j * 32 + lane]);
-      const int hrow = r0 + wr * 64 + j * 32 + lane;
+    for (int j = 0; j < 4; ++j) {
+      merge_triple(run[j], xch[wr * 128 + j * 32 + lane]);
+      const int hrow = r0 + wr * 128 + j * 32 + lane;
       if (hrow < r_end) {
         const size_t p = (size_t)(a.part0 + st) * a.rows + hrow;
         a.part_m[p] = run[j].m;

@@ -15,7 +15,7 @@ using namespace z2z_logits;
 // ------------------------------------------------------------------------------------------------
 // Tile kernel, 128 (vocabulary) x 128 (hidden rows) per workgroup, 4 waves of 64 x 64, K slabs of
 // 128 bytes per row.  LDS holds two buffers of (128 + 128) rows x 128 B; the 16-byte chunk c of row
-// r sits at chunk (c ^ (r & 7)) so that the 32 rows a half-wave reads hit all banks.
+// r sits at chunk (c ^ ((r >> 1) & 7)) so that the 16 rows a quarter-wave reads hit all 64 banks.
 // T = bf16 bits (uint16_t) or float.
 // ------------------------------------------------------------------------------------------------
 constexpr int TV = 128;
@@ -118,7 +118,7 @@ __global__ void __launch_bounds__(256) logits_general_kernel(LogitsArgs a) {
         const int id = tid + 256 * i;
         const int row = id >> 3;
         const int c = id & 7;
-        const int o = row * SLAB_BYTES + ((c ^ (row & 7)) << 4);
+        const int o = row * SLAB_BYTES + ((c ^ ((row >> 1) & 7)) << 4);
         *reinterpret_cast<uint4*>(A + o) = stage_a[i];
         *reinterpret_cast<uint4*>(Bt + o) = stage_b[i];
       }
@@ -140,12 +140,12 @@ __global__ void __launch_bounds__(256) logits_general_kernel(LogitsArgs a) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           const int row = wv * 64 + i * 32 + (lane & 31);
-          fa[i] = *reinterpret_cast<const uint4*>(A + row * SLAB_BYTES + ((chunk ^ (row & 7)) << 4));
+          fa[i] = *reinterpret_cast<const uint4*>(A + row * SLAB_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4));
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int row = wr * 64 + j * 32 + (lane & 31);
-          fb[j] = *reinterpret_cast<const uint4*>(Bt + row * SLAB_BYTES + ((chunk ^ (row & 7)) << 4));
+          fb[j] = *reinterpret_cast<const uint4*>(Bt + row * SLAB_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4));
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
