@@ -100,6 +100,21 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
                                hipStream_t s) {
   const int V = c->cfg.V, cap = c->cfg.cap;
+  const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
+
+  // decode step: one hidden row per sequence -> the bandwidth-bound kernel
+  if (rows_per_seq == 1 && logits == nullptr && c->decode_ready && c->opt_decode_kernel != 1) {
+    int n_parts = z2z_logits_decode_parts(c);
+    int rc = ensure_scratch(c, (size_t)n_parts * rows);
+    if (rc != Z2Z_OK) return rc;
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, s);
+    if (rc != Z2Z_OK) return rc;
+    hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, c->part_m, c->part_s,
+                       c->part_i, n_parts, rows, argmax, mx, lse);
+    Z2Z_HIP_TRY(hipGetLastError());
+    return Z2Z_OK;
+  }
+
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
   const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 32 == 0 && c->fast_ready && logits == nullptr;
   bool fast_base = fast_ok && rows > 128;
@@ -128,7 +143,6 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   a.ld = V + cap;
   a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
 
-  const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
   int ns = 0;
   rc = launch_part(c, false, fast_base, a, W_base, V, 0, 0, strip, rows, rows_per_seq, &ns, timed, s);
   if (rc != Z2Z_OK) return rc;

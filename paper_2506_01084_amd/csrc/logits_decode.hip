@@ -1,0 +1,277 @@
+// extended_logits for a decode step (one hidden row per sequence), bf16, gfx950: bound by HBM bandwidth.
+//
+// Per step the path reads W_base once for all sequences and every sequence's own W_hyper once (zip2zip
+// paper, section 2.3 steps 7-9 with the hyper-embedding cache of the same section): the bytes are
+// d * 2 * (V + sum_b C_b) and there are only about 20 flops per byte, so everything is arranged around
+// keeping many wide loads in flight and touching every weight byte exactly once.
+//
+// One launch, two kinds of workgroup (8 waves each), so both streams share the machine:
+//  * base units: 512 rows of W_base against up to 64 hidden rows.  A weight row has to meet 64 hidden
+//    rows, which is matrix-core work (v_mfma_f32_16x16x32_bf16: weight rows are operand A, hidden rows
+//    operand B).  The hidden rows cannot be kept whole near the MFMAs (64 x d x 2 bytes), so K is cut in
+//    slices of 128: a wave holds the 64 x 128 slice of H in 64 registers, streams that slice of the
+//    unit's weight rows through it, and adds its partial products into a [512][64] fp32 tile in LDS
+//    (ds_add_f32, rows padded to 68 floats so that the four row-quads of a result block hit different
+//    banks).  Eight waves take slices w, w+8, ...; after a barrier the tile holds the unit's logits and
+//    is folded into one (max, sum-exp, argmax) triple per hidden row.
+//  * hyper units: 512 rows of one sequence's W_hyper against that sequence's single hidden row: plain
+//    dot products (v_dot2c_f32_bf16), one weight row per wave at a time, 1 KiB per load instruction,
+//    the hidden row held in registers; rows at and beyond C_b are never touched.
+// Each unit leaves one triple per hidden row in the same [part][row] scratch the prefill kernels use.
+#include "logits_common.h"
+
+namespace {
+
+using namespace z2z_logits;
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+constexpr int D_UNIT = 512;            // weight rows per unit
+constexpr int D_THREADS = 512;
+constexpr int D_KSLICE = 128;          // K elements a wave keeps of H
+constexpr int D_QB = D_KSLICE / 32;    // MFMA k-blocks per slice
+constexpr int D_LDROW = 68;            // floats per row of the LDS logit tile
+constexpr int D_TILE_BYTES = D_UNIT * D_LDROW * 4;
+constexpr int D_LDS = D_TILE_BYTES + D_THREADS * (int)sizeof(Triple);
+constexpr int D_MAXQ = 8;              // hyper units: d <= 512 * D_MAXQ
+
+struct DecodeArgs {
+  const uint4* H;         // [B, d] bf16
+  const uint4* W_base;    // [V, d]
+  const uint4* W_hyper;   // [B, cap, d]
+  const int32_t* size;    // [B]
+  int32_t B, V, cap, d;
+  int32_t n_base_units;   // ceil(V / 512)
+  int32_t n_groups;       // ceil(B / 64) groups of hidden rows for the base part
+  int32_t units_per_seq;  // ceil(cap / 512)
+  float* part_m;          // [parts, B]
+  float* part_s;
+  int32_t* part_i;
+};
+
+__device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
+  if (x > t.m) {
+    t.s = (t.m == kNegInf) ? 1.f : t.s * __expf(t.m - x) + 1.f;
+    t.m = x;
+    t.i = col;
+  } else if (x != kNegInf) {
+    t.s += __expf(x - t.m);
+  }
+}
+
+__device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int group, unsigned char* lds) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* tile = reinterpret_cast<float*>(lds);
+  Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);
+  const int v0 = unit * D_UNIT;
+  const int h0 = group * 64;
+  const int n_h = min(64, a.B - h0);               // hidden rows of this group
+  const int n_cg = (n_h + 15) >> 4;                // groups of 16 hidden rows
+  const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
+  const int n_slices = a.d / D_KSLICE;
+
+  for (int i = tid; i < D_UNIT * D_LDROW; i += D_THREADS) tile[i] = 0.f;
+  __syncthreads();
+
+  const int m16 = lane & 15;     // MFMA row (A) / column (B) index of this lane
+  const int kg = lane >> 4;      // which 8 of the 32 k of an MFMA this lane feeds
+  for (int slice = wave; slice < n_slices; slice += 8) {
+    const int c0 = slice * (D_KSLICE / 8) + kg;   // first 16-byte chunk of this lane in the slice
+    // the wave's slice of H: 4 groups of 16 hidden rows x D_QB MFMA k-blocks
+    uint4 hreg[4][D_QB];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int hrow = min(h0 + g * 16 + m16, a.B - 1);
+#pragma unroll
+      for (int q = 0; q < D_QB; ++q) hreg[g][q] = a.H[(size_t)hrow * chunks_per_row + c0 + q * 4];
+    }
+    uint4 cur[D_QB], nxt[D_QB];
+    auto load_block = [&](uint4 (&w)[D_QB], int blk) {
+      const int wrow = min(v0 + blk * 16 + m16, a.V - 1);
+      const uint4* p = a.W_base + (size_t)wrow * chunks_per_row + c0;
+#pragma unroll
+      for (int q = 0; q < D_QB; ++q) w[q] = p[q * 4];
+    };
+    load_block(cur, 0);
+    for (int blk = 0; blk < D_UNIT / 16; ++blk) {
+      if (blk + 1 < D_UNIT / 16) load_block(nxt, blk + 1);
+      f32x4 acc[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int q = 0; q < D_QB; ++q)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (g < n_cg)
+            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[q]),
+                                                             __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (g < n_cg) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            atomicAdd(&tile[(blk * 16 + 4 * kg + v) * D_LDROW + g * 16 + m16], acc[g][v]);
+        }
+#pragma unroll
+      for (int q = 0; q < D_QB; ++q) cur[q] = nxt[q];
+    }
+  }
+  __syncthreads();
+
+  // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 64 .. + 64, in increasing order
+  const int j = tid & 63;
+  const int seg = tid >> 6;
+  Triple t = empty_triple();
+  const int r_hi = min(D_UNIT, a.V - v0);
+  for (int r = seg * 64; r < min(seg * 64 + 64, r_hi); ++r) fold_value(t, tile[r * D_LDROW + j], v0 + r);
+  xch[tid] = t;
+  __syncthreads();
+  if (tid < 64 && j < n_h) {
+    Triple r = xch[j];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) merge_triple(r, xch[s * 64 + j]);
+    const size_t p = (size_t)unit * a.B + h0 + j;
+    a.part_m[p] = r.m;
+    a.part_s[p] = r.s;
+    a.part_i[p] = r.i;
+  }
+}
+
+template <int NQ>
+__device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, int r1, int lane, int wave, Triple& t) {
+  const int chunks_per_row = a.d >> 3;
+  // this lane's part of the hidden row: chunk q * 64 + lane, q < NQ (chunks past the row end are zero)
+  uint4 h[NQ];
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int c = q * 64 + lane;
+    h[q] = c < chunks_per_row ? a.H[(size_t)b * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+  }
+  const uint4* W = a.W_hyper + (size_t)b * a.cap * chunks_per_row;
+  for (int r = r0 + wave; r < r1; r += 16) {
+    // two rows per trip (r and r + 8) keep 2 * NQ KiB of loads in flight per wave
+    const int rb = r + 8;
+    const bool has_b = rb < r1;
+    uint4 wa[NQ], wb[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c = q * 64 + lane;
+      const bool in = c < chunks_per_row;
+      wa[q] = in ? W[(size_t)r * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+      wb[q] = (in && has_b) ? W[(size_t)rb * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+    }
+    float sa = 0.f, sb = 0.f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const uint32_t hw[4] = {h[q].x, h[q].y, h[q].z, h[q].w};
+      const uint32_t xa[4] = {wa[q].x, wa[q].y, wa[q].z, wa[q].w};
+      const uint32_t xb[4] = {wb[q].x, wb[q].y, wb[q].z, wb[q].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sa = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xa[e]), __builtin_bit_cast(bf16x2, hw[e]), sa,
+                                             false);
+        sb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xb[e]), __builtin_bit_cast(bf16x2, hw[e]), sb,
+                                             false);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      sa += __shfl_xor(sa, o);
+      sb += __shfl_xor(sb, o);
+    }
+    fold_value(t, sa, a.V + r);
+    if (has_b) fold_value(t, sb, a.V + rb);
+  }
+}
+
+__device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, unsigned char* lds) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  Triple* xch = reinterpret_cast<Triple*>(lds);
+  const int C = min(max(a.size[b], 0), a.cap);
+  const int r0 = u * D_UNIT;
+  const int r1 = min(C, r0 + D_UNIT);
+  Triple t = empty_triple();
+  if (r0 < r1) {
+    const int nq = (a.d + 511) >> 9;
+    if (nq <= 4)
+      hyper_rows<4>(a, b, r0, r1, lane, wave, t);
+    else
+      hyper_rows<D_MAXQ>(a, b, r0, r1, lane, wave, t);
+  }
+  // every lane of a wave holds the same triple; waves took rows w, w + 8, ...: merging by value and
+  // column restores the lowest-column rule
+  if (lane == 0) xch[wave] = t;
+  __syncthreads();
+  if (tid == 0) {
+    Triple r = xch[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) merge_triple(r, xch[s]);
+    const size_t p = (size_t)(a.n_base_units + u) * a.B + b;
+    a.part_m[p] = r.m;
+    a.part_s[p] = r.s;
+    a.part_i[p] = r.i;
+  }
+}
+
+__global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int n_base = a.n_base_units * a.n_groups;
+  const int bid = blockIdx.x;
+  if (bid < n_base) {
+    base_unit(a, bid % a.n_base_units, bid / a.n_base_units, lds);
+  } else {
+    const int hu = bid - n_base;
+    hyper_unit(a, hu / a.units_per_seq, hu % a.units_per_seq, lds);
+  }
+}
+
+}  // namespace
+
+// Parts written: n_base_units + units_per_seq per hidden row.
+int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
+                             bool timed, hipStream_t s) {
+  DecodeArgs a;
+  a.H = reinterpret_cast<const uint4*>(H);
+  a.W_base = reinterpret_cast<const uint4*>(W_base);
+  a.W_hyper = reinterpret_cast<const uint4*>(W_hyper);
+  a.size = c->st.size;
+  a.B = c->cfg.B;
+  a.V = c->cfg.V;
+  a.cap = c->cfg.cap;
+  a.d = c->cfg.d;
+  a.n_base_units = (a.V + D_UNIT - 1) / D_UNIT;
+  a.n_groups = (a.B + 63) / 64;
+  a.units_per_seq = (a.cap + D_UNIT - 1) / D_UNIT;
+  a.part_m = c->part_m;
+  a.part_s = c->part_s;
+  a.part_i = c->part_i;
+  *n_parts = a.n_base_units + a.units_per_seq;
+  const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
+  if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
+  hipLaunchKernelGGL(logits_decode_kernel, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  if (timed) {
+    Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
+    c->n_timed++;
+  }
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_logits_decode_parts(const z2z_ctx* c) {
+  return (c->cfg.V + D_UNIT - 1) / D_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
+}
+
+bool z2z_logits_decode_ok(const z2z_ctx* c) {
+  return c->cfg.dtype == Z2Z_BF16 && c->cfg.d % D_KSLICE == 0 && c->cfg.d <= 512 * D_MAXQ && c->lds_limit >= D_LDS;
+}
+
+int z2z_logits_decode_prepare(z2z_ctx* c) {
+  if (c->lds_limit < D_LDS) return Z2Z_EUNSUPPORTED;
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
+  return Z2Z_OK;
+}

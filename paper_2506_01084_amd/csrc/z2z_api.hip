@@ -99,6 +99,7 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
     return Z2Z_ENOMEM;
   }
   c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
+  c->decode_ready = z2z_logits_decode_ok(c) && z2z_logits_decode_prepare(c) == Z2Z_OK;
   if (z2z_lzw_prepare(c) != Z2Z_OK || z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
     free_ctx(c);

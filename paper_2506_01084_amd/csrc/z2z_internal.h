@@ -42,6 +42,7 @@ struct z2z_ctx {
   size_t part_capacity;    // elements in each of the three arrays
   // options
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map;
+  int decode_ready;        // the decode-step logits kernel can be launched for this configuration
   int fast_ready;          // the 128 KiB-LDS bf16 logits kernel can be launched on this device
   // timing record
   hipEvent_t ev_start[Z2Z_MAX_TIMED];
