@@ -6,14 +6,16 @@
 // keeping many wide loads in flight and touching every weight byte exactly once.
 //
 // One launch, two kinds of workgroup (8 waves each), so both streams share the machine:
-//  * base units: 512 rows of W_base against up to 64 hidden rows.  A weight row has to meet 64 hidden
+//  * base units: 256 rows of W_base against up to 64 hidden rows.  A weight row has to meet 64 hidden
 //    rows, which is matrix-core work (v_mfma_f32_16x16x32_bf16: weight rows are operand A, hidden rows
 //    operand B).  The hidden rows cannot be kept whole near the MFMAs (64 x d x 2 bytes), so K is cut in
-//    slices of 128: a wave holds the 64 x 128 slice of H in 64 registers, streams that slice of the
-//    unit's weight rows through it, and adds its partial products into a [512][64] fp32 tile in LDS
-//    (ds_add_f32, rows padded to 68 floats so that the four row-quads of a result block hit different
-//    banks).  Eight waves take slices w, w+8, ...; after a barrier the tile holds the unit's logits and
-//    is folded into one (max, sum-exp, argmax) triple per hidden row.
+//    slices of 128: a wave holds the 64 x 128 slice of H in 64 registers and streams that slice of the
+//    unit's weight rows through it, 16 rows at a time.  The eight waves work on eight adjacent slices of
+//    the same 16 rows (2 KiB contiguous per weight row), drop their 16 x 64 partial products into LDS
+//    slots, meet at a barrier, and each wave then sums the slots for two of the 16 rows into the unit's
+//    [256][64] fp32 logit tile in LDS (rows it alone owns: no atomics -- LDS float atomics measured an
+//    order of magnitude too slow for this).  After d / 1024 such phases the tile is folded into one
+//    (max, sum-exp, argmax) triple per hidden row.
 //  * hyper units: 512 rows of one sequence's W_hyper against that sequence's single hidden row: plain
 //    dot products (v_dot2c_f32_bf16), one weight row per wave at a time, 1 KiB per load instruction,
 //    the hidden row held in registers; rows at and beyond C_b are never touched.
@@ -26,13 +28,16 @@ using namespace z2z_logits;
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
-constexpr int D_UNIT = 512;            // weight rows per unit
+constexpr int D_UNIT = 512;            // weight rows per hyper unit
+constexpr int D_BASE_UNIT = 256;       // weight rows per base unit
 constexpr int D_THREADS = 512;
 constexpr int D_KSLICE = 128;          // K elements a wave keeps of H
 constexpr int D_QB = D_KSLICE / 32;    // MFMA k-blocks per slice
-constexpr int D_LDROW = 68;            // floats per row of the LDS logit tile
-constexpr int D_TILE_BYTES = D_UNIT * D_LDROW * 4;
-constexpr int D_LDS = D_TILE_BYTES + D_THREADS * (int)sizeof(Triple);
+constexpr int D_TILE_BYTES = D_BASE_UNIT * 64 * 4;       // [256][64] fp32 logits of a base unit
+constexpr int D_SLOT_STRIDE = 20;                         // floats per hidden-row column of a slot (16 + pad)
+constexpr int D_SLOT_FLOATS = 64 * D_SLOT_STRIDE;         // one wave's 16 x 64 partial block, column-major
+constexpr int D_SLOTS_BYTES = 2 * 8 * D_SLOT_FLOATS * 4;  // two buffers x eight waves
+constexpr int D_LDS = D_TILE_BYTES + D_SLOTS_BYTES;       // 144 KiB (the triple exchange reuses the slots)
 constexpr int D_MAXQ = 8;              // hyper units: d <= 512 * D_MAXQ
 
 struct DecodeArgs {
@@ -41,7 +46,7 @@ struct DecodeArgs {
   const uint4* W_hyper;   // [B, cap, d]
   const int32_t* size;    // [B]
   int32_t B, V, cap, d;
-  int32_t n_base_units;   // ceil(V / 512)
+  int32_t n_base_units;   // ceil(V / 256)
   int32_t n_groups;       // ceil(B / 64) groups of hidden rows for the base part
   int32_t units_per_seq;  // ceil(cap / 512)
   float* part_m;          // [parts, B]
@@ -63,22 +68,25 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float* tile = reinterpret_cast<float*>(lds);
-  Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);
-  const int v0 = unit * D_UNIT;
+  float* tile = reinterpret_cast<float*>(lds);                      // [256][64]
+  float* slots = reinterpret_cast<float*>(lds + D_TILE_BYTES);       // [2][8][64][D_SLOT_STRIDE]
+  const int v0 = unit * D_BASE_UNIT;
   const int h0 = group * 64;
   const int n_h = min(64, a.B - h0);               // hidden rows of this group
-  const int n_cg = (n_h + 15) >> 4;                // groups of 16 hidden rows
   const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
   const int n_slices = a.d / D_KSLICE;
+  const int n_phases = (n_slices + 7) >> 3;
+  constexpr int N_BLK = D_BASE_UNIT / 16;
 
-  for (int i = tid; i < D_UNIT * D_LDROW; i += D_THREADS) tile[i] = 0.f;
-  __syncthreads();
+  for (int i = tid; i < D_BASE_UNIT * 64; i += D_THREADS) tile[i] = 0.f;
 
   const int m16 = lane & 15;     // MFMA row (A) / column (B) index of this lane
   const int kg = lane >> 4;      // which 8 of the 32 k of an MFMA this lane feeds
-  for (int slice = wave; slice < n_slices; slice += 8) {
-    const int c0 = slice * (D_KSLICE / 8) + kg;   // first 16-byte chunk of this lane in the slice
+  int it = 0;
+  for (int phase = 0; phase < n_phases; ++phase) {
+    const int slice = phase * 8 + wave;
+    const bool valid = slice < n_slices;           // wave-uniform
+    const int c0 = (valid ? slice : 0) * (D_KSLICE / 8) + kg;   // first 16-byte chunk of this lane in the slice
     // the wave's slice of H: 4 groups of 16 hidden rows x D_QB MFMA k-blocks
     uint4 hreg[4][D_QB];
 #pragma unroll
@@ -95,37 +103,51 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
       for (int q = 0; q < D_QB; ++q) w[q] = p[q * 4];
     };
     load_block(cur, 0);
-    for (int blk = 0; blk < D_UNIT / 16; ++blk) {
-      if (blk + 1 < D_UNIT / 16) load_block(nxt, blk + 1);
+    for (int blk = 0; blk < N_BLK; ++blk, ++it) {
+      load_block(nxt, min(blk + 1, N_BLK - 1));
       f32x4 acc[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (valid) {
 #pragma unroll
-      for (int q = 0; q < D_QB; ++q)
+        for (int q = 0; q < D_QB; ++q)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          if (g < n_cg)
+          for (int g = 0; g < 4; ++g)
             acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[q]),
                                                              __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
+      }
+      // slot layout: hidden-row column c at c * D_SLOT_STRIDE, its 16 weight rows contiguous; this lane
+      // holds rows 4 * kg .. + 3 of column g * 16 + m16: one 16-byte store per group
+      float* slot = slots + ((it & 1) * 8 + wave) * D_SLOT_FLOATS;
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        if (g < n_cg) {
+        *reinterpret_cast<f32x4*>(slot + (g * 16 + m16) * D_SLOT_STRIDE + 4 * kg) = acc[g];
+      __syncthreads();
+      // this wave owns rows 2 * wave, 2 * wave + 1 of the block; lane = hidden-row column
+      const float* rd = slots + (it & 1) * 8 * D_SLOT_FLOATS + lane * D_SLOT_STRIDE + 2 * wave;
+      float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            atomicAdd(&tile[(blk * 16 + 4 * kg + v) * D_LDROW + g * 16 + m16], acc[g][v]);
-        }
+      for (int s = 0; s < 8; ++s) {
+        const float2 p = *reinterpret_cast<const float2*>(rd + s * D_SLOT_FLOATS);
+        s0 += p.x;
+        s1 += p.y;
+      }
+      float* trow = tile + (blk * 16 + 2 * wave) * 64 + lane;
+      trow[0] += s0;
+      trow[64] += s1;
 #pragma unroll
       for (int q = 0; q < D_QB; ++q) cur[q] = nxt[q];
     }
   }
   __syncthreads();
 
-  // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 64 .. + 64, in increasing order
+  // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 32 .. + 32, in increasing order
+  Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);       // the slots are idle now
   const int j = tid & 63;
   const int seg = tid >> 6;
   Triple t = empty_triple();
-  const int r_hi = min(D_UNIT, a.V - v0);
-  for (int r = seg * 64; r < min(seg * 64 + 64, r_hi); ++r) fold_value(t, tile[r * D_LDROW + j], v0 + r);
+  const int r_hi = min(D_BASE_UNIT, a.V - v0);
+  for (int r = seg * 32; r < min(seg * 32 + 32, r_hi); ++r) fold_value(t, tile[r * 64 + j], v0 + r);
   xch[tid] = t;
   __syncthreads();
   if (tid < 64 && j < n_h) {
@@ -243,7 +265,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.V = c->cfg.V;
   a.cap = c->cfg.cap;
   a.d = c->cfg.d;
-  a.n_base_units = (a.V + D_UNIT - 1) / D_UNIT;
+  a.n_base_units = (a.V + D_BASE_UNIT - 1) / D_BASE_UNIT;
   a.n_groups = (a.B + 63) / 64;
   a.units_per_seq = (a.cap + D_UNIT - 1) / D_UNIT;
   a.part_m = c->part_m;
@@ -262,7 +284,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 }
 
 int z2z_logits_decode_parts(const z2z_ctx* c) {
-  return (c->cfg.V + D_UNIT - 1) / D_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
+  return (c->cfg.V + D_BASE_UNIT - 1) / D_BASE_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
 }
 
 bool z2z_logits_decode_ok(const z2z_ctx* c) {
