@@ -10,23 +10,37 @@ namespace {
 
 using namespace z2z_logits;
 
-// One thread per hidden row: merge the row's partial triples in column order.
+// One wave per hidden row: lanes take the row's partial triples round-robin (contiguous in memory),
+// then merge across lanes; merge_triple keeps the lowest column among equal maxima, so the order of the
+// merges does not matter.
 __global__ void __launch_bounds__(256) logits_combine_kernel(const float* part_m, const float* part_s,
                                                              const int32_t* part_i, int n_parts, int rows,
                                                              int32_t* argmax, float* mx, float* lse) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
   Triple t = empty_triple();
-  for (int p = 0; p < n_parts; ++p) {
+  const size_t base = (size_t)r * n_parts;
+  for (int p = lane; p < n_parts; p += 64) {
     Triple o;
-    o.m = part_m[(size_t)p * rows + r];
-    o.s = part_s[(size_t)p * rows + r];
-    o.i = part_i[(size_t)p * rows + r];
+    o.m = part_m[base + p];
+    o.s = part_s[base + p];
+    o.i = part_i[base + p];
     merge_triple(t, o);
   }
-  if (argmax) argmax[r] = t.i;
-  if (mx) mx[r] = t.m;
-  if (lse) lse[r] = t.m + logf(t.s);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    Triple o;
+    o.m = __shfl_xor(t.m, off);
+    o.s = __shfl_xor(t.s, off);
+    o.i = __shfl_xor(t.i, off);
+    merge_triple(t, o);
+  }
+  if (lane == 0) {
+    if (argmax) argmax[r] = t.i;
+    if (mx) mx[r] = t.m;
+    if (lse) lse[r] = t.m + logf(t.s);
+  }
 }
 
 // Full-logits output only: unused hyper slots read -inf.
@@ -109,7 +123,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     if (rc != Z2Z_OK) return rc;
     rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, s);
     if (rc != Z2Z_OK) return rc;
-    hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, c->part_m, c->part_s,
+    hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
                        c->part_i, n_parts, rows, argmax, mx, lse);
     Z2Z_HIP_TRY(hipGetLastError());
     return Z2Z_OK;
@@ -141,6 +155,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   a.part_i = c->part_i;
   a.logits = logits;
   a.ld = V + cap;
+  a.n_parts = n_parts;
   a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
 
   int ns = 0;
@@ -155,7 +170,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
       Z2Z_HIP_TRY(hipGetLastError());
     }
   }
-  hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, c->part_m, c->part_s,
+  hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
                      c->part_i, n_parts, rows, argmax, mx, lse);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;

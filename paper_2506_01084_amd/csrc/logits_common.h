@@ -108,6 +108,7 @@ struct LogitsArgs {
   int32_t strip;          // vocabulary tiles per workgroup
   int32_t n_strips;       // strips of one W matrix
   int32_t part0;          // index of this launch's first partial
+  int32_t n_parts;        // partials per hidden row (row stride of the part arrays)
   int32_t row_tiles;      // base: tiles over all rows; hyper: tiles per sequence
   int32_t n_work;         // workgroups with work: row tiles (x sequences) x strips
   // workgroup -> (row tile, strip) mapping of the base part: workgroup ids go round-robin over the 8
@@ -115,7 +116,7 @@ struct LogitsArgs {
   // side by side as map_xr x map_xs inside one super block, so that what runs at the same time shares
   // W strips and hidden-row tiles through the XCD's L2 and the memory-side cache.
   int32_t map_lr, map_ls, map_xr, map_xs, map_sb_r;
-  float* part_m;          // [parts, rows]
+  float* part_m;          // [rows, n_parts]
   float* part_s;
   int32_t* part_i;
   float* logits;          // nullptr or [rows, ld]

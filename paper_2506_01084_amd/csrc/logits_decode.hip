@@ -19,7 +19,7 @@
 //  * hyper units: 512 rows of one sequence's W_hyper against that sequence's single hidden row: plain
 //    dot products (v_dot2c_f32_bf16), one weight row per wave at a time, 1 KiB per load instruction,
 //    the hidden row held in registers; rows at and beyond C_b are never touched.
-// Each unit leaves one triple per hidden row in the same [part][row] scratch the prefill kernels use.
+// Each unit leaves one triple per hidden row in the same [row][part] scratch the prefill kernels use.
 #include "logits_common.h"
 
 namespace {
@@ -49,7 +49,8 @@ struct DecodeArgs {
   int32_t n_base_units;   // ceil(V / 256)
   int32_t n_groups;       // ceil(B / 64) groups of hidden rows for the base part
   int32_t units_per_seq;  // ceil(cap / 512)
-  float* part_m;          // [parts, B]
+  int32_t n_parts;        // partials per hidden row
+  float* part_m;          // [B, n_parts]
   float* part_s;
   int32_t* part_i;
 };
@@ -82,62 +83,82 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
 
   const int m16 = lane & 15;     // MFMA row (A) / column (B) index of this lane
   const int kg = lane >> 4;      // which 8 of the 32 k of an MFMA this lane feeds
-  int it = 0;
-  for (int phase = 0; phase < n_phases; ++phase) {
-    const int slice = phase * 8 + wave;
-    const bool valid = slice < n_slices;           // wave-uniform
-    const int c0 = (valid ? slice : 0) * (D_KSLICE / 8) + kg;   // first 16-byte chunk of this lane in the slice
-    // the wave's slice of H: 4 groups of 16 hidden rows x D_QB MFMA k-blocks
-    uint4 hreg[4][D_QB];
+  // One step = one 16-row block of one phase.  Weight blocks are requested three steps ahead into four
+  // register buffers (the loop is unrolled by four so that each buffer has a fixed name); requests past
+  // the end of the unit re-read its last block.
+  const int n_steps = n_phases * N_BLK;
+  auto chunk0 = [&](int phase) {
+    const int slice = min(phase * 8 + wave, n_slices - 1);
+    return slice * (D_KSLICE / 8) + kg;            // first 16-byte chunk of this lane in the slice
+  };
+  auto load_block = [&](uint4 (&w)[D_QB], int step) {
+    step = min(step, n_steps - 1);
+    const int phase = step / N_BLK, blk = step - phase * N_BLK;
+    const int wrow = min(v0 + blk * 16 + m16, a.V - 1);
+    const uint4* p = a.W_base + (size_t)wrow * chunks_per_row + chunk0(phase);
+#pragma unroll
+    for (int q = 0; q < D_QB; ++q) w[q] = p[q * 4];
+  };
+  uint4 hreg[4][D_QB];                             // the wave's slice of H: 4 x 16 hidden rows x D_QB k-blocks
+  auto load_h = [&](int phase) {
+    const int c0 = chunk0(phase);
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int hrow = min(h0 + g * 16 + m16, a.B - 1);
 #pragma unroll
       for (int q = 0; q < D_QB; ++q) hreg[g][q] = a.H[(size_t)hrow * chunks_per_row + c0 + q * 4];
     }
-    uint4 cur[D_QB], nxt[D_QB];
-    auto load_block = [&](uint4 (&w)[D_QB], int blk) {
-      const int wrow = min(v0 + blk * 16 + m16, a.V - 1);
-      const uint4* p = a.W_base + (size_t)wrow * chunks_per_row + c0;
+  };
+  auto compute = [&](const uint4 (&w)[D_QB], int step) {
+    const int phase = step / N_BLK, blk = step - phase * N_BLK;
+    const bool valid = phase * 8 + wave < n_slices;   // wave-uniform
+    f32x4 acc[4];
 #pragma unroll
-      for (int q = 0; q < D_QB; ++q) w[q] = p[q * 4];
-    };
-    load_block(cur, 0);
-    for (int blk = 0; blk < N_BLK; ++blk, ++it) {
-      load_block(nxt, min(blk + 1, N_BLK - 1));
-      f32x4 acc[4];
+    for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (valid) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (valid) {
+      for (int q = 0; q < D_QB; ++q)
 #pragma unroll
-        for (int q = 0; q < D_QB; ++q)
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[q]),
-                                                             __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
-      }
-      // slot layout: hidden-row column c at c * D_SLOT_STRIDE, its 16 weight rows contiguous; this lane
-      // holds rows 4 * kg .. + 3 of column g * 16 + m16: one 16-byte store per group
-      float* slot = slots + ((it & 1) * 8 + wave) * D_SLOT_FLOATS;
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<f32x4*>(slot + (g * 16 + m16) * D_SLOT_STRIDE + 4 * kg) = acc[g];
-      __syncthreads();
-      // this wave owns rows 2 * wave, 2 * wave + 1 of the block; lane = hidden-row column
-      const float* rd = slots + (it & 1) * 8 * D_SLOT_FLOATS + lane * D_SLOT_STRIDE + 2 * wave;
-      float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const float2 p = *reinterpret_cast<const float2*>(rd + s * D_SLOT_FLOATS);
-        s0 += p.x;
-        s1 += p.y;
-      }
-      float* trow = tile + (blk * 16 + 2 * wave) * 64 + lane;
-      trow[0] += s0;
-      trow[64] += s1;
-#pragma unroll
-      for (int q = 0; q < D_QB; ++q) cur[q] = nxt[q];
+        for (int g = 0; g < 4; ++g)
+          acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[q]),
+                                                           __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
     }
+    // slot layout: hidden-row column c at c * D_SLOT_STRIDE, its 16 weight rows contiguous; this lane
+    // holds rows 4 * kg .. + 3 of column g * 16 + m16: one 16-byte store per group
+    float* slot = slots + ((step & 1) * 8 + wave) * D_SLOT_FLOATS;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<f32x4*>(slot + (g * 16 + m16) * D_SLOT_STRIDE + 4 * kg) = acc[g];
+    __syncthreads();
+    // this wave owns rows 2 * wave, 2 * wave + 1 of the block; lane = hidden-row column.  The slot
+    // buffer written at step + 2 is this one again: the barrier of step + 1 lies in between.
+    const float* rd = slots + (step & 1) * 8 * D_SLOT_FLOATS + lane * D_SLOT_STRIDE + 2 * wave;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const float2 p = *reinterpret_cast<const float2*>(rd + s * D_SLOT_FLOATS);
+      s0 += p.x;
+      s1 += p.y;
+    }
+    float* trow = tile + (blk * 16 + 2 * wave) * 64 + lane;
+    trow[0] += s0;
+    trow[64] += s1;
+    if (blk == N_BLK - 1 && phase + 1 < n_phases) load_h(phase + 1);   // next phase: next slice of H
+  };
+  uint4 w0[D_QB], w1[D_QB], w2[D_QB], w3[D_QB];
+  load_h(0);
+  load_block(w0, 0);
+  load_block(w1, 1);
+  load_block(w2, 2);
+  for (int step = 0; step < n_steps; step += 4) {   // N_BLK is a multiple of 4, so is n_steps
+    load_block(w3, step + 3);
+    compute(w0, step);
+    load_block(w0, step + 4);
+    compute(w1, step + 1);
+    load_block(w1, step + 5);
+    compute(w2, step + 2);
+    load_block(w2, step + 6);
+    compute(w3, step + 3);
   }
   __syncthreads();
 
@@ -154,7 +175,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     Triple r = xch[j];
 #pragma unroll
     for (int s = 1; s < 8; ++s) merge_triple(r, xch[s * 64 + j]);
-    const size_t p = (size_t)unit * a.B + h0 + j;
+    const size_t p = (size_t)(h0 + j) * a.n_parts + unit;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
     a.part_i[p] = r.i;
@@ -232,7 +253,7 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
     Triple r = xch[0];
 #pragma unroll
     for (int s = 1; s < 8; ++s) merge_triple(r, xch[s]);
-    const size_t p = (size_t)(a.n_base_units + u) * a.B + b;
+    const size_t p = (size_t)b * a.n_parts + a.n_base_units + u;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
     a.part_i[p] = r.i;
@@ -272,6 +293,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.part_s = c->part_s;
   a.part_i = c->part_i;
   *n_parts = a.n_base_units + a.units_per_seq;
+  a.n_parts = *n_parts;
   const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
   hipLaunchKernelGGL(logits_decode_kernel, dim3(grid), dim3(D_THREADS), D_LDS, s, a);

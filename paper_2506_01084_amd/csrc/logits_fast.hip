@@ -248,7 +248,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       merge_triple(run[j], xch[wr * 128 + j * 32 + lane]);
       const int hrow = r0 + wr * 128 + j * 32 + lane;
       if (hrow < r_end) {
-        const size_t p = (size_t)(a.part0 + st) * a.rows + hrow;
+        const size_t p = (size_t)hrow * a.n_parts + a.part0 + st;
         a.part_m[p] = run[j].m;
         a.part_s[p] = run[j].s;
         a.part_i[p] = run[j].i;
