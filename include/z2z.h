@@ -55,7 +55,7 @@ enum {                                              /* per-sequence data status 
 
 typedef struct {
   int32_t B;      /* sequences served by the context, >= 1                                            */
-  int32_t V;      /* base vocabulary size, >= 1, V + cap < 2^31                                       */
+  int32_t V;      /* base vocabulary size, >= 1, V + cap <= 2^24 (else Z2Z_EUNSUPPORTED)              */
   int32_t M;      /* maximum merge size (base tokens per hypertoken), 1..Z2Z_MAX_M                    */
   int32_t cap;    /* codebook capacity per sequence, 0..Z2Z_MAX_CAP; a full codebook is frozen        */
   int32_t d;      /* embedding width, multiple of 8 (bf16) or 4 (f32)                                 */
@@ -65,7 +65,7 @@ typedef struct {
 } z2z_config;
 
 /* Create / destroy a context on the current HIP device.  Allocates the codebook storage
- * (about cap * (4*M + 16) bytes per sequence) and empties it.  Synchronous. */
+ * (about cap * (4*M + 20) bytes per sequence) and empties it.  Synchronous. */
 int z2z_create(z2z_ctx** out, const z2z_config* cfg);
 int z2z_destroy(z2z_ctx* ctx);
 

@@ -2,16 +2,22 @@
 //
 // The parse of one sequence is a serial dependency chain (section 2.1 of the zip2zip paper: every
 // step looks up "current phrase + next token" in the codebook built so far), so the unit of
-// parallelism is the sequence.  The codebook is a trie stored as a hash table over its edges
-// (parent code, token) -> entry index.  The wave keeps the hash slots -- and, when they fit, the
-// edge keys -- of its sequence in LDS for the whole call; tokens are read 64 at a time with one
-// coalesced load and handed out with readlane; emitted codes are collected in a lane-distributed
-// register and written 64 at a time.  All control flow is wave-uniform.
+// parallelism is the sequence and the cost per token is the latency of one probe.  The codebook is a
+// trie stored as a hash table over its edges: one 64-bit slot = parent code (24 bits) | token (24 bits)
+// | entry index (16 bits), so a probe is a single 8-byte LDS read and compare.  The wave keeps the
+// table of its sequence in LDS for the whole call (up to 20480 slots in the 160 KiB of a CU); the
+// decoder also keeps (length, first token) of every entry there when it fits.  Tokens are read 64 at a
+// time with one coalesced load and handed out with readlane; emitted codes are collected in a
+// lane-distributed register and written 64 at a time; the decoder expands 64 codes at a time, one
+// code per lane, after their lengths are known.  Control flow is wave-uniform and kept in scalar
+// registers (readfirstlane).
 #include "z2z_internal.h"
 
 namespace {
 
 constexpr int kWave = 64;
+typedef unsigned long long u64;
+constexpr u64 kEmpty = ~0ull;
 
 struct LzwArgs {
   LzwState st;
@@ -23,8 +29,7 @@ struct LzwArgs {
   int32_t* out_n;          // [B]
   int32_t out_stride;
   int32_t* status;         // [B]
-  int32_t lds_slots;       // 1: hash slots live in LDS during the call
-  int32_t lds_keys;        // 1: edge keys live in LDS during the call
+  int32_t lds_ef;          // decode, LDS variant: 1 = (length, first token) of the entries live in LDS too
 };
 
 __device__ __forceinline__ uint32_t edge_hash(int32_t parent, int32_t tok) {
@@ -37,86 +42,85 @@ __device__ __forceinline__ uint32_t edge_hash(int32_t parent, int32_t tok) {
   return h;
 }
 
-__device__ __forceinline__ unsigned long long edge_key(int32_t parent, int32_t tok) {
-  return ((unsigned long long)(uint32_t)parent << 32) | (unsigned long long)(uint32_t)tok;
+__device__ __forceinline__ u64 edge_bits(int32_t parent, int32_t tok) {
+  return ((u64)(uint32_t)parent << 40) | ((u64)(uint32_t)tok << 16);
 }
 
+extern __shared__ __align__(16) u64 lds_slots[];   // LDS variant: the sequence's hash table (+ entry info)
+
+// The hash table of one sequence, in LDS (LDS = true; indexes the shared array directly so that probes
+// are ds_read_b64) or in global memory (huge capacities, and short appends that touch a few slots).
+template <bool LDS>
 struct Table {
-  uint16_t* slots;             // LDS or global (generic pointer)
-  unsigned long long* keys;    // LDS or global (generic pointer)
-  uint32_t mask;
+  u64* g;           // global slots of this sequence
+  uint32_t n;       // number of slots
+
+  __device__ __forceinline__ u64 load(uint32_t pos) const {
+    const u64 v = LDS ? lds_slots[pos] : g[pos];
+    // every lane reads the same address; readfirstlane keeps the chain in scalar registers
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((u64)hi << 32) | lo;
+  }
+  __device__ __forceinline__ void store(uint32_t pos, u64 v) const {
+    if (LDS)
+      lds_slots[pos] = v;
+    else
+      g[pos] = v;
+  }
+  // Linear probing.  Returns the entry index, or -1 with *free_pos = the empty slot the probe ended at
+  // (-1 if the table has no empty slot, which cannot happen while n > cap).
+  __device__ __forceinline__ int find(int32_t parent, int32_t tok, int* free_pos) const {
+    const u64 key = edge_bits(parent, tok);
+    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
+    for (uint32_t probe = 0; probe < n; ++probe) {
+      const u64 s = load(pos);
+      if (s == kEmpty) {
+        *free_pos = (int)pos;
+        return -1;
+      }
+      if ((s & ~0xFFFFull) == key) return (int)(s & 0xFFFFull);
+      pos = pos + 1 == n ? 0 : pos + 1;
+    }
+    *free_pos = -1;
+    return -1;
+  }
 };
 
-// Linear probing.  Returns the entry index, or -1 with *free_pos = the empty slot the probe ended
-// at (-1 if the table has no empty slot, which cannot happen while nslots >= 2*cap).
-__device__ __forceinline__ int table_find(const Table& t, int32_t parent, int32_t tok, int* free_pos) {
-  const unsigned long long key = edge_key(parent, tok);
-  uint32_t pos = edge_hash(parent, tok) & t.mask;
-  for (uint32_t probe = 0; probe <= t.mask; ++probe) {
-    // every lane reads the same address; readfirstlane keeps the chain in scalar registers
-    const uint32_t s = __builtin_amdgcn_readfirstlane((uint32_t)t.slots[pos]);
-    if (s == Z2Z_EMPTY_SLOT) {
-      *free_pos = (int)pos;
-      return -1;
-    }
-    if (__builtin_amdgcn_readfirstlane((int)(t.keys[s] == key))) return (int)s;
-    pos = (pos + 1) & t.mask;
-  }
-  *free_pos = -1;
-  return -1;
-}
-
-// Shared set-up: bring the sequence's table into LDS (or clear it on RESET).
-__device__ __forceinline__ void table_open(const LzwArgs& a, int b, int lane, unsigned char* smem, bool reset,
-                                           int C, Table* t) {
+template <bool LDS>
+__device__ __forceinline__ void table_open(const LzwArgs& a, int b, int lane, bool reset, Table<LDS>* t) {
   const LzwState& st = a.st;
-  uint16_t* g_slots = st.slots + (size_t)b * st.nslots;
-  unsigned long long* g_keys = st.keys + (size_t)b * st.cap;
-  uint16_t* l_slots = reinterpret_cast<uint16_t*>(smem);
-  unsigned long long* l_keys = reinterpret_cast<unsigned long long*>(smem + (size_t)st.nslots * sizeof(uint16_t));
-  t->mask = (uint32_t)st.nslots - 1u;
-  t->slots = a.lds_slots ? l_slots : g_slots;
-  t->keys = a.lds_keys ? l_keys : g_keys;
-  // nslots is a power of two >= 64, so the table is a whole number of 4-byte words
-  uint32_t* dst32 = reinterpret_cast<uint32_t*>(t->slots);
-  const int nwords = st.nslots / 2;
-  if (reset) {
-    for (int i = lane; i < nwords; i += kWave) dst32[i] = 0xFFFFFFFFu;
-  } else {
-    if (a.lds_slots) {
-      const uint32_t* src32 = reinterpret_cast<const uint32_t*>(g_slots);
-      for (int i = lane; i < nwords; i += kWave) dst32[i] = src32[i];
+  t->g = st.slots + (size_t)b * st.nslots;
+  t->n = (uint32_t)st.nslots;
+  if (LDS) {
+    if (reset) {
+      for (int i = lane; i < st.nslots; i += kWave) lds_slots[i] = kEmpty;
+    } else {
+      for (int i = lane; i < st.nslots; i += kWave) lds_slots[i] = t->g[i];
     }
-    if (a.lds_keys) {
-      for (int i = lane; i < C; i += kWave) l_keys[i] = g_keys[i];
-    }
-  }
-  __syncthreads();
-}
-
-// Shared tear-down: write the LDS-resident parts back so that later calls see them.
-__device__ __forceinline__ void table_close(const LzwArgs& a, int b, int lane, const Table& t, int C) {
-  const LzwState& st = a.st;
-  __syncthreads();
-  if (a.lds_slots) {
-    uint32_t* g32 = reinterpret_cast<uint32_t*>(st.slots + (size_t)b * st.nslots);
-    const uint32_t* l32 = reinterpret_cast<const uint32_t*>(t.slots);
-    for (int i = lane; i < st.nslots / 2; i += kWave) g32[i] = l32[i];
-  }
-  if (a.lds_keys) {
-    unsigned long long* g_keys = st.keys + (size_t)b * st.cap;
-    for (int i = lane; i < C; i += kWave) g_keys[i] = t.keys[i];
+    __syncthreads();
+  } else if (reset) {
+    for (int i = lane; i < st.nslots; i += kWave) t->g[i] = kEmpty;
+    __syncthreads();
   }
 }
 
-// Add the edge (parent, tok) as entry C.  `ph` holds, in lane j, token j of the parent phrase
-// (plen tokens); the new entry's flattened row is that phrase followed by tok.
-__device__ __forceinline__ void table_insert(const LzwArgs& a, int b, int lane, const Table& t, int free_pos, int C,
-                                             int32_t parent, int32_t tok, int32_t ph, int plen) {
+template <bool LDS>
+__device__ __forceinline__ void table_close(const LzwArgs& a, int lane, const Table<LDS>& t) {
+  if (LDS) {
+    __syncthreads();
+    for (int i = lane; i < a.st.nslots; i += kWave) t.g[i] = lds_slots[i];
+  }
+}
+
+// Add the edge (parent, tok) as entry C.  `ph` holds, in lane j, token j of the parent phrase (plen
+// tokens); the new entry's flattened row is that phrase followed by tok.
+template <bool LDS>
+__device__ __forceinline__ void table_insert(const LzwArgs& a, int b, int lane, const Table<LDS>& t, int free_pos,
+                                             int C, int32_t parent, int32_t tok, int32_t ph, int plen) {
   const LzwState& st = a.st;
   if (lane == 0) {
-    t.slots[free_pos] = (uint16_t)C;
-    t.keys[C] = edge_key(parent, tok);
+    t.store((uint32_t)free_pos, edge_bits(parent, tok) | (u64)(uint32_t)C);
     st.ent_len[(size_t)b * st.cap + C] = plen + 1;
   }
   if (lane < st.M) {
@@ -128,8 +132,8 @@ __device__ __forceinline__ void table_insert(const LzwArgs& a, int b, int lane, 
 // ------------------------------------------------------------------------------------------------
 // encode
 // ------------------------------------------------------------------------------------------------
+template <bool LDS>
 __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
@@ -140,8 +144,8 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
   int prev = reset ? -1 : __builtin_amdgcn_readfirstlane(st.prev_code[b]);
   int prev_len = reset ? 0 : __builtin_amdgcn_readfirstlane(st.prev_len[b]);
 
-  Table t;
-  table_open(a, b, lane, smem, reset, C, &t);
+  Table<LDS> t;
+  table_open<LDS>(a, b, lane, reset, &t);
 
   // tokens of the previous phrase (lane j = token j), needed only for the first entry of an append
   int32_t ph = -1;
@@ -176,7 +180,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
       int free_pos = -1;
       bool emit = false;
       if (w >= 0 && wlen < M) {
-        const int idx = table_find(t, w, c, &free_pos);
+        const int idx = t.find(w, c, &free_pos);
         if (idx >= 0) {               // the match grows
           w = V + idx;
           if (lane == wlen) ph = c;
@@ -188,9 +192,9 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
         emit = true;
       } else if (prev >= 0 && prev_len < M && C < cap) {
         // first token of an appended chunk: the entry the earlier flush could not add
-        const int idx = table_find(t, prev, c, &free_pos);
+        const int idx = t.find(prev, c, &free_pos);
         if (idx < 0 && free_pos >= 0) {
-          table_insert(a, b, lane, t, free_pos, C, prev, c, ph, prev_len);
+          table_insert<LDS>(a, b, lane, t, free_pos, C, prev, c, ph, prev_len);
           ++C;
         }
       }
@@ -207,7 +211,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
         prev = w;
         prev_len = wlen;
         if (wlen < M && C < cap && free_pos >= 0) {
-          table_insert(a, b, lane, t, free_pos, C, w, c, ph, wlen);
+          table_insert<LDS>(a, b, lane, t, free_pos, C, w, c, ph, wlen);
           ++C;
         }
       }
@@ -230,7 +234,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
   const int tail = n_out & (kWave - 1);
   if (tail != 0 && lane < tail) out[n_out - tail + lane] = out_reg;
 
-  table_close(a, b, lane, t, C);
+  table_close<LDS>(a, lane, t);
   if (lane == 0) {
     st.size[b] = C;
     st.prev_code[b] = prev;
@@ -243,29 +247,31 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 // ------------------------------------------------------------------------------------------------
 // decode
 // ------------------------------------------------------------------------------------------------
+// (length, first token) of an entry packed in 32 bits: length in the top 4 bits.
+__device__ __forceinline__ uint32_t pack_ef(int len, int32_t first) { return ((uint32_t)len << 28) | (uint32_t)first; }
+
+template <bool LDS>
 __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   const int V = st.V, M = st.M, cap = st.cap;
   const bool reset = (a.flags & Z2Z_RESET) != 0;
+  const bool ef_lds = LDS && a.lds_ef;
+  uint32_t* ef = reinterpret_cast<uint32_t*>(lds_slots + st.nslots);   // [cap], valid when ef_lds
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
 
   int C = reset ? 0 : __builtin_amdgcn_readfirstlane(st.size[b]);
   int prev = reset ? -1 : __builtin_amdgcn_readfirstlane(st.prev_code[b]);
   int prev_len = reset ? 0 : __builtin_amdgcn_readfirstlane(st.prev_len[b]);
+  int prev_first = prev < 0 ? 0 : (prev < V ? prev : __builtin_amdgcn_readfirstlane(ent_tokens[(size_t)(prev - V) * M]));
 
-  Table t;
-  table_open(a, b, lane, smem, reset, C, &t);
-
-  int32_t ph = -1;                    // tokens of the previous phrase, lane j = token j
-  if (prev >= 0) {
-    if (prev < V) {
-      ph = lane == 0 ? prev : -1;
-    } else if (lane < M) {
-      ph = st.ent_tokens[((size_t)b * cap + (prev - V)) * M + lane];
-    }
+  Table<LDS> t;
+  if (ef_lds && !reset) {
+    for (int i = lane; i < C; i += kWave) ef[i] = pack_ef(ent_len[i], ent_tokens[(size_t)i * M]);
   }
+  table_open<LDS>(a, b, lane, reset, &t);
 
   const int n = a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
   const int32_t* in = a.in + (size_t)b * a.stride;
@@ -278,30 +284,41 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
   for (int base = 0; base < n && !stop; base += kWave) {
     const int cnt = min(kWave, n - base);
     const int32_t code_reg = lane < cnt ? in[base + lane] : 0;
+    // ---- serial part: (length, first token) of each code and the codebook update, all in LDS and
+    //      scalar registers.  Lane j keeps what the parallel part needs for code j: where its tokens
+    //      go, and the entry (if any) that code j caused.
+    int my_off = 0, my_len = 0;
+    int new_idx = -1, new_parent = 0, new_tok = 0, new_plen = 0;
+    int done = 0;                     // codes of this chunk accepted
     for (int j = 0; j < cnt; ++j) {
       const int32_t k = __builtin_amdgcn_readlane(code_reg, j);
-      int32_t cur = -1;               // tokens of this code's phrase, lane j = token j
       int cur_len = 0;
+      int32_t first = 0;
       int free_pos = -1;
-      bool looked_up = false;         // (prev, first) already probed and found absent
+      bool fresh = false;             // the code names the entry made in this very step
       if (k >= 0 && k < V) {
-        cur = lane == 0 ? k : -1;
         cur_len = 1;
+        first = k;
       } else if (k >= V && k - V < C) {
-        if (lane < M) cur = st.ent_tokens[((size_t)b * cap + (k - V)) * M + lane];
-        cur_len = __popcll(__ballot(cur >= 0));
+        uint32_t e;
+        if (ef_lds)
+          e = ef[k - V];
+        else
+          e = pack_ef(ent_len[k - V], ent_tokens[(size_t)(k - V) * M]);
+        e = __builtin_amdgcn_readfirstlane(e);
+        cur_len = (int)(e >> 28);
+        first = (int32_t)(e & 0x0FFFFFFFu);
       } else if (k >= V && k - V == C && prev >= 0 && prev_len < M && C < cap) {
-        // the entry the encoder made in the step just before using it: previous phrase + its first token
-        const int32_t pf = __builtin_amdgcn_readlane(ph, 0);
-        const int idx = table_find(t, prev, pf, &free_pos);
+        // previous phrase + its own first token, which must not exist yet
+        const int idx = t.find(prev, prev_first, &free_pos);
         if (idx >= 0 || free_pos < 0) {
           status |= Z2Z_ST_BAD_CODE;
           stop = true;
           break;
         }
-        cur = lane < prev_len ? ph : (lane == prev_len ? pf : -1);
         cur_len = prev_len + 1;
-        looked_up = true;
+        first = prev_first;
+        fresh = true;
       } else {
         status |= Z2Z_ST_BAD_CODE;
         stop = true;
@@ -312,24 +329,71 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
         stop = true;
         break;
       }
-      const int32_t first = __builtin_amdgcn_readlane(cur, 0);
       if (prev >= 0 && prev_len < M && C < cap) {
         int idx = -1;
-        if (!looked_up) idx = table_find(t, prev, first, &free_pos);
+        if (!fresh) idx = t.find(prev, first, &free_pos);
         if (idx < 0 && free_pos >= 0) {
-          table_insert(a, b, lane, t, free_pos, C, prev, first, ph, prev_len);
+          if (lane == 0) {
+            t.store((uint32_t)free_pos, edge_bits(prev, first) | (u64)(uint32_t)C);
+            if (ef_lds) {
+              ef[C] = pack_ef(prev_len + 1, prev_first);
+            } else {
+              // no LDS copy: a later code of this chunk may already name this entry, and its length
+              // and first token are then read from memory before the rows are completed below
+              ent_len[C] = prev_len + 1;
+              ent_tokens[(size_t)C * M] = prev_first;
+            }
+          }
+          if (lane == j) {
+            new_idx = C;
+            new_parent = prev;
+            new_tok = first;
+            new_plen = prev_len;
+          }
           ++C;
         }
       }
-      if (out != nullptr && lane < cur_len) out[n_out + lane] = cur;
+      if (lane == j) {
+        my_off = n_out;
+        my_len = cur_len;
+      }
       n_out += cur_len;
       prev = k;
       prev_len = cur_len;
-      ph = cur;
+      prev_first = first;
+      ++done;
+    }
+    // ---- parallel part 1: write the flattened rows of the entries made in this chunk, shortest
+    //      parents first (a parent made in this chunk is shorter than its child, so it is complete
+    //      by the time the child copies it)
+    for (int L = 1; L < M; ++L) {
+      if (new_idx >= 0 && new_plen == L) {
+        int32_t* row = ent_tokens + (size_t)new_idx * M;
+        if (new_parent < V) {
+          row[0] = new_parent;
+        } else {
+          const int32_t* prow = ent_tokens + (size_t)(new_parent - V) * M;
+          for (int i = 0; i < L; ++i) row[i] = prow[i];
+        }
+        row[L] = new_tok;
+        for (int i = L + 1; i < M; ++i) row[i] = -1;
+        ent_len[new_idx] = L + 1;
+      }
+      __syncthreads();                // one wave: orders this level's stores before the next level's loads
+    }
+    // ---- parallel part 2: lane j writes the tokens of code j
+    if (out != nullptr && lane < done) {
+      const int32_t k = code_reg;
+      if (k < V) {
+        out[my_off] = k;
+      } else {
+        const int32_t* row = ent_tokens + (size_t)(k - V) * M;
+        for (int i = 0; i < my_len; ++i) out[my_off + i] = row[i];
+      }
     }
   }
 
-  table_close(a, b, lane, t, C);
+  table_close<LDS>(a, lane, t);
   if (lane == 0) {
     st.size[b] = C;
     st.prev_code[b] = prev;
@@ -342,8 +406,7 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
 // Empty every codebook.  grid = B, block = 256.
 __global__ void lzw_reset_kernel(LzwState st) {
   const int b = blockIdx.x;
-  uint32_t* s32 = reinterpret_cast<uint32_t*>(st.slots + (size_t)b * st.nslots);
-  for (int i = threadIdx.x; i < st.nslots / 2; i += blockDim.x) s32[i] = 0xFFFFFFFFu;
+  for (int i = threadIdx.x; i < st.nslots; i += blockDim.x) st.slots[(size_t)b * st.nslots + i] = kEmpty;
   for (int i = threadIdx.x; i < st.cap; i += blockDim.x) st.ent_len[(size_t)b * st.cap + i] = 0;
   for (size_t i = threadIdx.x; i < (size_t)st.cap * st.M; i += blockDim.x)
     st.ent_tokens[(size_t)b * st.cap * st.M + i] = -1;
@@ -354,8 +417,8 @@ __global__ void lzw_reset_kernel(LzwState st) {
   }
 }
 
-// Clear the entry rows of a sequence that a RESET encode/decode is about to refill, so that rows
-// at and beyond the new size read as unused.  grid = B, block = 256.
+// Clear the entry rows of a sequence that a RESET encode/decode is about to refill, so that rows at
+// and beyond the new size read as unused.  grid = B, block = 256.
 __global__ void lzw_clear_entries_kernel(LzwState st) {
   const int b = blockIdx.x;
   const int C = st.size[b];
@@ -364,23 +427,22 @@ __global__ void lzw_clear_entries_kernel(LzwState st) {
     st.ent_tokens[(size_t)b * st.cap * st.M + i] = -1;
 }
 
-void plan_lds(const z2z_ctx* c, int32_t stride, int32_t flags, LzwArgs* a, size_t* smem) {
-  const size_t slot_bytes = (size_t)c->st.nslots * sizeof(uint16_t);
-  const size_t key_bytes = (size_t)c->st.cap * sizeof(unsigned long long);
+// Which table variant a call uses, and how much LDS it needs.
+void plan(const z2z_ctx* c, int32_t stride, int32_t flags, bool decode, bool* lds, LzwArgs* a, size_t* smem) {
+  const size_t slot_bytes = (size_t)c->st.nslots * sizeof(u64);
+  const size_t ef_bytes = (size_t)c->st.cap * sizeof(uint32_t);
   const size_t limit = (size_t)c->lds_limit;
-  a->lds_slots = 0;
-  a->lds_keys = 0;
-  *smem = 0;
-  // a short append (a decode step) touches a handful of slots: probing global memory directly
-  // is cheaper than staging the table
+  // a short append (a decode step) touches a handful of slots: probing global memory directly is
+  // cheaper than staging the table
   const bool tiny_append = !(flags & Z2Z_RESET) && stride <= 64;
-  if (c->opt_lzw_kernel == 2 || tiny_append) return;
-  if (slot_bytes <= limit) {
-    a->lds_slots = 1;
+  *lds = c->st.slots_fit_lds && !tiny_append && c->opt_lzw_kernel != 2;
+  a->lds_ef = 0;
+  *smem = 0;
+  if (*lds) {
     *smem = slot_bytes;
-    if (slot_bytes + key_bytes <= limit) {
-      a->lds_keys = 1;
-      *smem = slot_bytes + key_bytes;
+    if (decode && slot_bytes + ef_bytes <= limit) {
+      a->lds_ef = 1;
+      *smem += ef_bytes;
     }
   }
 }
@@ -406,12 +468,13 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
   a.out_stride = out_stride;
   a.status = status;
   size_t smem = 0;
-  plan_lds(c, stride, flags, &a, &smem);
-  if (flags & Z2Z_RESET) {
-    hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-    if (!a.lds_slots) hipLaunchKernelGGL(lzw_reset_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-  }
-  hipLaunchKernelGGL(lzw_encode_kernel, dim3(c->cfg.B), dim3(kWave), smem, s, a);
+  bool lds = false;
+  plan(c, stride, flags, false, &lds, &a, &smem);
+  if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
+  if (lds)
+    hipLaunchKernelGGL(lzw_encode_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
+  else
+    hipLaunchKernelGGL(lzw_encode_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }
@@ -429,21 +492,38 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
   a.out_stride = out_stride;
   a.status = status;
   size_t smem = 0;
-  plan_lds(c, stride, flags, &a, &smem);
-  if (flags & Z2Z_RESET) {
-    hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-    if (!a.lds_slots) hipLaunchKernelGGL(lzw_reset_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-  }
-  hipLaunchKernelGGL(lzw_decode_kernel, dim3(c->cfg.B), dim3(kWave), smem, s, a);
+  bool lds = false;
+  plan(c, stride, flags, true, &lds, &a, &smem);
+  if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
+  if (lds)
+    hipLaunchKernelGGL(lzw_decode_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
+  else
+    hipLaunchKernelGGL(lzw_decode_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }
 
-// Raise the dynamic-LDS ceiling of the two parse kernels to what the device allows.
+// Size the hash table for the device's LDS and raise the dynamic-LDS ceiling of the parse kernels.
+// Load factor at a full codebook is at most 0.8 (at least 1.25 slots per entry, 2 when LDS allows).
 int z2z_lzw_prepare(z2z_ctx* c) {
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel),
+  LzwState& st = c->st;
+  const int cap = st.cap;
+  const int want = 2 * cap < 64 ? 64 : 2 * cap;
+  const int floor125 = cap + cap / 4 + 1;
+  const int lds_slots = c->lds_limit / (int)sizeof(u64);
+  if (want <= lds_slots) {
+    st.nslots = want;
+    st.slots_fit_lds = 1;
+  } else if (floor125 <= lds_slots) {
+    st.nslots = lds_slots;
+    st.slots_fit_lds = 1;
+  } else {
+    st.nslots = want;
+    st.slots_fit_lds = 0;
+  }
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel),
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
   return Z2Z_OK;
 }

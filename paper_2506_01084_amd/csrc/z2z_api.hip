@@ -12,12 +12,6 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int next_pow2(int x) {
-  int p = 1;
-  while (p < x) p <<= 1;
-  return p;
-}
-
 void free_ctx(z2z_ctx* c) {
   if (!c) return;
   (void)hipFree(c->st.size);
@@ -25,7 +19,6 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->st.prev_len);
   (void)hipFree(c->st.ent_tokens);
   (void)hipFree(c->st.ent_len);
-  (void)hipFree(c->st.keys);
   (void)hipFree(c->st.slots);
   (void)hipFree(c->part_m);
   (void)hipFree(c->part_s);
@@ -48,7 +41,7 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
   *out = nullptr;
   if (cfg->B < 1 || cfg->V < 1 || cfg->M < 1 || cfg->M > Z2Z_MAX_M) return Z2Z_EINVAL;
   if (cfg->cap < 0 || cfg->cap > Z2Z_MAX_CAP) return Z2Z_EINVAL;
-  if ((long long)cfg->V + cfg->cap >= 2147483647LL) return Z2Z_EINVAL;
+  if ((long long)cfg->V + cfg->cap > (1LL << 24)) return Z2Z_EUNSUPPORTED;   // codes are packed in 24 bits
   if (cfg->dtype != Z2Z_F32 && cfg->dtype != Z2Z_BF16) return Z2Z_EUNSUPPORTED;
   if (cfg->pool != Z2Z_POOL_MEAN && cfg->pool != Z2Z_POOL_WEIGHTED) return Z2Z_EUNSUPPORTED;
   const int epc = cfg->dtype == Z2Z_BF16 ? 8 : 4;
@@ -83,7 +76,10 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
   st.V = cfg->V;
   st.M = cfg->M;
   st.cap = cfg->cap;
-  st.nslots = next_pow2(2 * cfg->cap < 64 ? 64 : 2 * cfg->cap);
+  if (z2z_lzw_prepare(c) != Z2Z_OK) {   // sizes the hash table (st.nslots) for this device
+    delete c;
+    return Z2Z_EHIP;
+  }
   const size_t B = (size_t)cfg->B;
   const size_t capn = cfg->cap > 0 ? (size_t)cfg->cap : 1;
   bool ok = true;
@@ -92,15 +88,14 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
   ok = ok && hipMalloc(&st.prev_len, B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.ent_tokens, B * capn * cfg->M * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.ent_len, B * capn * sizeof(int32_t)) == hipSuccess;
-  ok = ok && hipMalloc(&st.keys, B * capn * sizeof(unsigned long long)) == hipSuccess;
-  ok = ok && hipMalloc(&st.slots, B * (size_t)st.nslots * sizeof(uint16_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.slots, B * (size_t)st.nslots * sizeof(unsigned long long)) == hipSuccess;
   if (!ok) {
     free_ctx(c);
     return Z2Z_ENOMEM;
   }
   c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
   c->decode_ready = z2z_logits_decode_ok(c) && z2z_logits_decode_prepare(c) == Z2Z_OK;
-  if (z2z_lzw_prepare(c) != Z2Z_OK || z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
+  if (z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
     free_ctx(c);
     return Z2Z_EHIP;

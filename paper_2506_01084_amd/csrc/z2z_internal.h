@@ -7,7 +7,6 @@
 #include "z2z.h"
 
 #define Z2Z_API __attribute__((visibility("default")))
-#define Z2Z_EMPTY_SLOT 0xFFFFu
 #define Z2Z_MAX_TIMED 1024
 
 // Per-sequence codebook storage, all in device global memory and owned by the context.
@@ -15,17 +14,18 @@
 //   prev_code[b], prev_len[b]  last phrase emitted / consumed (-1, 0 = none)
 //   ent_tokens[b][e][0..M)     flattened base tokens of entry e, -1 padded
 //   ent_len[b][e]              its length (0 = unused)
-//   keys[b][e]                 (parent code << 32) | last token   -- the trie edge that made entry e
-//   slots[b][h]                open-addressing hash table over the trie edges: entry index or EMPTY
+//   slots[b][h]                open-addressing hash table over the trie edges, one 64-bit word per slot:
+//                              parent code (24 bits) | last token (24 bits) | entry index (16 bits); all
+//                              ones = empty.  Hence V + cap <= 2^24.
 struct LzwState {
   int32_t* size;
   int32_t* prev_code;
   int32_t* prev_len;
   int32_t* ent_tokens;
   int32_t* ent_len;
-  unsigned long long* keys;
-  uint16_t* slots;
+  unsigned long long* slots;
   int32_t V, M, cap, nslots;
+  int32_t slots_fit_lds;     // the table of one sequence fits the LDS of a CU
 };
 
 struct z2z_ctx {
