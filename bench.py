@@ -29,6 +29,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
+# HBM-side bytes per launch (fetch + write) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
+# summaries are committed under profiles/ (counter values scaled by a 1 GiB copy of known traffic).
+# They are measurements of these exact workloads, not computed here: a different workload reports null.
+TRAFFIC_BYTES = {
+    "logits_fast_kernel<0>@c2": 66.59e9 + 0.075e9,
+    "logits_decode_kernel@c3": 3.211e9 + 0.003e9,
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -186,24 +194,35 @@ def run_decode_workload(args, torch, api, wl):
         d_first.copy_(size_view)
         ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
         ctx.hyper_embed(d_E, d_W, d_first, max_new=1)
+        ctx.set_option(api.OPT_TIMING, 1)      # HIP events around the decode kernel, on this stream
         ctx.extended_logits(d_H, 1, d_E, d_W, d_am, d_mx, d_lse, None)
+        ctx.set_option(api.OPT_TIMING, 0)
 
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
+    ctx.read_timing()
     t0 = time.perf_counter()
     for s in range(args.warmup, n_steps):
         step(s)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    k_ms, k_n = ctx.read_timing()
+    assert k_n == args.steps
     assert int(d_st.abs().sum()) == 0
     sizes = size_view.cpu().numpy()
     us = dt * 1e6 / args.steps
     bytes_step = 2.0 * d * (V + float(sizes.sum())) + 2.0 * B * d
     gbs = bytes_step / (us * 1e-6) / 1e9
     ctx.close()
+    k_us = k_ms * 1e3 / k_n
+    k_gbs = bytes_step / (k_us * 1e-6) / 1e9
     return dict(workload=cfg["name"], us_per_step=us, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
-                peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()))
+                peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()),
+                roofline={"bound": "hbm", "kernel": "logits_decode_kernel (64 rows, config 3)", "achieved": k_gbs,
+                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": k_gbs / PEAK_HBM_GBS,
+                          "traffic": TRAFFIC_BYTES.get("logits_decode_kernel@c3"), "avg_kernel_us": k_us,
+                          "bytes_per_launch": bytes_step})
 
 
 def cpu_baseline(wl, host, budget_rows=24):
@@ -249,6 +268,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
@@ -261,6 +283,12 @@ def main():
 
     torch.cuda.set_device(0)
     api.load_library()
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     res, host = run_prefill_workload(args, torch, api, wl)
     assert res["kernel_launches"] == args.steps
     k_ms = res["kernel_ms_total"] / res["kernel_launches"]
@@ -295,9 +323,9 @@ def main():
             "mean_codebook_size": sum(res["sizes"]) / len(res["sizes"]),
             "compression_rate": sum(res["n_codes"]) / res["tokens"],
         },
-        "roofline": {"bound": "mfma", "kernel": "logits_tile_kernel (base vocabulary part of the prefill call)",
+        "roofline": {"bound": "mfma", "kernel": "logits_fast_kernel<0> (base-vocabulary part of the prefill extended_logits call)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get("logits_fast_kernel<0>@c2"),
                      "avg_kernel_ms": k_ms, "flops_per_launch": res["flops_base"]},
         "cpu_baseline": cpu,
         "decode_step": dec,
