@@ -130,12 +130,12 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   }
 
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
-  const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 32 == 0 && c->fast_ready && logits == nullptr;
+  const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
   bool fast_base = fast_ok && rows > 128;
   bool fast_hyper = fast_ok && rows_per_seq > 128;
   if (c->opt_logits_kernel == 1) fast_base = fast_hyper = false;
   if (c->opt_logits_kernel >= 2) fast_base = fast_hyper = fast_ok;
-  const int strip = c->opt_logits_strip > 0 ? c->opt_logits_strip : 8;
+  const int strip = c->opt_logits_strip > 0 ? c->opt_logits_strip : 4;
 
   // number of parts (strips of both launches), then the scratch for them
   const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;

@@ -1,23 +1,25 @@
-// extended_logits, bf16 MFMA kernel for gfx950 (d a multiple of 32), one wave per SIMD.
+// extended_logits, bf16 MFMA kernel for gfx950 (d a multiple of 64), one wave per SIMD.
 //
 // Workgroup tile 256 (vocabulary rows, MFMA "A") x 256 (hidden rows, MFMA "B"), 4 waves in a 2 x 2 grid,
 // each wave 128 x 128 = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 accumulator registers per lane):
 // per 16-deep k-step a wave reads 8 operand fragments from LDS for 16 MFMAs, which keeps the LDS read
 // port at about half of its 128 B/clk (a 128 x 64 wave tile needs three quarters of it and starves the
 // matrix cores).  With one wave per SIMD all overlap is inside the instruction stream: the fragments of
-// k-step t+1 are read while the MFMAs of k-step t run, and global->LDS requests are issued three slabs
-// ahead.
+// k-step t+1 are read while the MFMAs of k-step t run, and the global->LDS requests of slab s+2 are issued
+// as soon as slab s has been read.
 //
-// K advances in slabs of 32 elements (64 bytes per row, two k-steps).  Both operand tiles of a slab
-// (2 x 16 KiB) go straight from global memory into LDS (16-byte global_load ... lds) into a ring of 4
-// stages.  Once per slab, in the middle of its second k-step, the waves meet at a barrier: at that
-// point everybody has read the slab completely (its stage is refilled with slab s+4) and slab s+1 has
-// landed (its first fragments are read next).  The stream runs on across the vocabulary tiles of a strip.
+// K advances in slabs of 64 elements (128 bytes per row, four k-steps): the global -> LDS stream moves
+// whole 128-byte lines, which it does markedly faster than half lines (measured on a bare streaming
+// kernel: 14-22 TB/s against 12-15 TB/s out of L2).  Both operand tiles of a slab (2 x 32 KiB) go straight
+// from global memory into LDS (16-byte global_load ... lds), two stages.  Once per slab, in the middle of
+// its last k-step, the waves meet at a barrier: at that point everybody has read the slab completely (its
+// stage is refilled with slab s+2) and slab s+1 has landed (its first fragments are read next).  The stream
+// runs on across the vocabulary tiles of a strip.
 //
-// LDS layout of an operand tile: row r = 64 bytes = 4 chunks of 16 B; chunk c is stored at position
-// c ^ ((r >> 2) & 3).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a
+// LDS layout of an operand tile: row r = 128 bytes = 8 chunks of 16 B; chunk c is stored at position
+// c ^ ((r >> 1) & 7).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a
 // time; an MFMA operand read has 16 consecutive lanes on 16 consecutive rows at one logical chunk, whose
-// bank group is (r & 3) * 4 + position -- all 16 distinct with this swizzle.
+// bank group is (r & 1) * 8 + position -- all 16 distinct with this swizzle.
 //
 // In the 32x32 result block a lane holds 16 vocabulary entries of one hidden row, so the running
 // (max, sum-exp, argmax) of the joint softmax (zip2zip paper, section 2.3, step 8) lives in registers
@@ -29,10 +31,10 @@ namespace {
 using namespace z2z_logits;
 
 constexpr int FT = 256;                   // tile edge, vocabulary and hidden rows
-constexpr int F_SLAB = 64;                // bytes per row per K slab (32 bf16)
-constexpr int F_OPER = FT * F_SLAB;       // one operand tile of one slab: 16 KiB
+constexpr int F_SLAB = 128;               // bytes per row per K slab (64 bf16)
+constexpr int F_OPER = FT * F_SLAB;       // one operand tile of one slab: 32 KiB
 constexpr int F_STAGE = 2 * F_OPER;       // A + B
-constexpr int F_NSTAGE = 4;
+constexpr int F_NSTAGE = 2;
 constexpr int F_LDS = F_NSTAGE * F_STAGE; // 128 KiB
 constexpr int F_THREADS = 256;
 
@@ -114,11 +116,10 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   for (int j = 0; j < 4; ++j) run[j] = empty_triple();
 
   // ---- loader: lane l of wave w, instruction i moves the chunk that lands at LDS byte
-  //      ((w * 4 + i) * 16 + (l >> 2)) * 64 + (l & 3) * 16 of the operand tile; offsets are relative to
+  //      ((w * 8 + i) * 8 + (l >> 3)) * 128 + (l & 7) * 16 of the operand tile; offsets are relative to
   //      the first row of the tile, rows past the last valid one are clamped onto it ------------------
   const uint32_t lds_base = lds_offset_of(lds);
-  const int ld_row = lane >> 2;                                  // row inside the 16-row group
-  const int ld_chunk16 = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;  // (row >> 2) & 3 == (lane >> 4) & 3
+  const int ld_row = lane >> 3;                                  // row inside the 8-row group
   const int limB = r_end - 1 - r0;                               // last valid hidden row of the tile
   const unsigned char* Wtile = Wp;
   int limA = 0;                                                  // last valid vocabulary row of the tile
@@ -127,30 +128,45 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     limA = n_valid - 1 - vt * FT;
   };
   // request the slab that follows (lslab, lvt) in the stream, if any, and advance the cursor; the
-  // per-lane offsets are recomputed each time (a few VALU operations) rather than kept in registers
+  // per-lane offsets are recomputed each time (a few VALU operations) rather than kept in registers.
+  // A request is 16 instructions per wave; issue_rows(i) issues the pair for row group i so that the
+  // caller can place the pairs between MFMAs.
   int lslab = 0, lvt = vt0;
-  auto issue_next = [&](int stage) {
-    if (lvt < vt_end) {
-      const uint32_t A = lds_base + stage * F_STAGE + wave * 4096;
-      const uint32_t Bt = A + F_OPER;
-      const unsigned char* ga = Wtile + (size_t)lslab * F_SLAB;
-      const unsigned char* gb = Hp + (size_t)lslab * F_SLAB;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = (wave * 4 + i) * 16 + ld_row;
-        load16_to_lds(ga, (uint32_t)(min(row, limA) * (int)row_bytes + ld_chunk16), A + i * 1024);
-        load16_to_lds(gb, (uint32_t)(min(row, limB) * (int)row_bytes + ld_chunk16), Bt + i * 1024);
-      }
-      if (++lslab == n_slabs) {
-        lslab = 0;
-        ++lvt;
-        if (lvt < vt_end) set_tile(lvt);
-      }
+  uint32_t isA = 0, isB = 0;                 // LDS destinations of the slab being requested
+  const unsigned char* is_ga = Wp;
+  const unsigned char* is_gb = Hp;
+  bool is_on = false;
+  auto issue_begin = [&](int stage) {
+    is_on = lvt < vt_end;
+    isA = lds_base + stage * F_STAGE + wave * 8192;
+    isB = isA + F_OPER;
+    is_ga = Wtile + (size_t)lslab * F_SLAB;
+    is_gb = Hp + (size_t)lslab * F_SLAB;
+  };
+  auto issue_rows = [&](int i) {
+    if (is_on) {
+      const int row = (wave * 8 + i) * 8 + ld_row;
+      const int chunk16 = ((lane & 7) ^ ((row >> 1) & 7)) * 16;
+      load16_to_lds(is_ga, (uint32_t)(min(row, limA) * (int)row_bytes + chunk16), isA + i * 1024);
+      load16_to_lds(is_gb, (uint32_t)(min(row, limB) * (int)row_bytes + chunk16), isB + i * 1024);
     }
+  };
+  auto issue_end = [&]() {
+    if (is_on && ++lslab == n_slabs) {
+      lslab = 0;
+      ++lvt;
+      if (lvt < vt_end) set_tile(lvt);
+    }
+  };
+  auto issue_next = [&](int stage) {
+    issue_begin(stage);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) issue_rows(i);
+    issue_end();
   };
 
   // ---- MFMA operand addresses (bytes inside an operand tile), swizzle folded in ---------------------
-  const int sw = (lane >> 2) & 3;   // ((row >> 2) & 3) of every row this lane reads
+  const int sw = (lane >> 1) & 7;   // ((row >> 1) & 7) of every row this lane reads
   const int half = lane >> 5;
   const int offA0 = (wv * 128 + (lane & 31)) * F_SLAB;
   const int offB0 = (wr * 128 + (lane & 31)) * F_SLAB;
@@ -185,13 +201,11 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     zero_acc();
     set_tile(vt0);
     const int total = n_tiles * n_slabs;
-    // prologue: slabs 0..3 requested, slab 0 landed and visible, its first fragments on the way
+    // prologue: slabs 0 and 1 requested, slab 0 landed and visible, its first fragments on the way
     issue_next(0);
     issue_next(1);
-    issue_next(2);
-    issue_next(3);
-    if (total >= 4)
-      __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): all but the youngest three slabs (8 requests each)
+    if (total >= 2)
+      __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): all but the youngest slab (16 requests per wave)
     else
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
@@ -200,24 +214,41 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     int g = 0;
     for (int vt = vt0; vt < vt_end; ++vt) {
       for (int slab = 0; slab < n_slabs; ++slab, ++g) {
-        const int stage = g & (F_NSTAGE - 1);
-        // k-step 0 of the slab: fragments in f0; fetch k-step 1
+        const int stage = g & 1;
         read_frags(f1, stage, 1);
         mfma_rows(f0, 0, 4);
-        // k-step 1: fragments in f1.  Half of its MFMAs, then the slab hand-over, then the other half.
-        mfma_rows(f1, 0, 2);
-        if (g + 1 < total) {
-          // slab g+1 must have landed; requests return in order, 8 per slab and wave, and slabs g+2, g+3
-          // may still be in flight
-          if (g + 3 >= total)
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): tail of the stream
-          else
-            __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
-          __syncthreads();                        // slab g+1 visible to all; everyone has read slab g
-          issue_next(stage);                      // refill this stage with slab g+4
-          read_frags(f0, (g + 1) & (F_NSTAGE - 1), 0);
+        read_frags(f0, stage, 2);
+        mfma_rows(f1, 0, 4);
+        read_frags(f1, stage, 3);
+        mfma_rows(f0, 0, 4);
+        // last k-step: a quarter of its MFMAs, then the slab hand-over; the 16 requests for slab g+2
+        // are then issued between the remaining MFMAs (a burst of them would leave the matrix cores
+        // idle for as long as it takes to issue)
+        mfma_rows(f1, 0, 1);
+        const bool more = g + 1 < total;
+        if (more) {
+          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): slab g+1 (the only one in flight) has landed
+          __syncthreads();                      // slab g+1 visible to all; everyone has read slab g
+          read_frags(f0, stage ^ 1, 0);
+          issue_begin(stage);                   // refill this stage with slab g+2
+        } else {
+          is_on = false;
         }
-        mfma_rows(f1, 2, 4);
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1.a[i]),
+                                                                __builtin_bit_cast(bf16x8, f1.b[j]), acc[i][j], 0, 0, 0);
+            if (((i - 1) * 4 + j) % 3 == 2 || (i == 3 && j == 3)) {
+              __builtin_amdgcn_sched_barrier(0);
+              const int grp = ((i - 1) * 4 + j) / 3;          // 0..3 -> row groups 2*grp, 2*grp+1
+              issue_rows(2 * grp);
+              issue_rows(2 * grp + 1);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        if (more) issue_end();
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
       const int v0 = vt * FT;
