@@ -85,6 +85,30 @@ struct Table {
     *free_pos = -1;
     return -1;
   }
+  // The same probe, per lane (each lane looks up its own edge; no scalar broadcast).  The global table
+  // is read past the vector L1: slots are claimed with atomics, which do not update that cache.
+  __device__ __forceinline__ int find_lane(int32_t parent, int32_t tok) const {
+    const u64 key = edge_bits(parent, tok);
+    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
+    for (uint32_t probe = 0; probe < n; ++probe) {
+      const u64 s = LDS ? lds_slots[pos] : __hip_atomic_load(&g[pos], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (s == kEmpty) return -1;
+      if ((s & ~0xFFFFull) == key) return (int)(s & 0xFFFFull);
+      pos = pos + 1 == n ? 0 : pos + 1;
+    }
+    return -1;
+  }
+  // Per-lane insertion of an edge known to be absent: claim the first empty slot of the probe
+  // sequence with a compare-and-swap (several lanes insert at once).
+  __device__ __forceinline__ void insert_lane(int32_t parent, int32_t tok, int idx) const {
+    const u64 val = edge_bits(parent, tok) | (u64)(uint32_t)idx;
+    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
+    for (uint32_t probe = 0; probe < n; ++probe) {
+      u64* slot = LDS ? &lds_slots[pos] : &g[pos];
+      if (atomicCAS(slot, kEmpty, val) == kEmpty) return;
+      pos = pos + 1 == n ? 0 : pos + 1;
+    }
+  }
 };
 
 template <bool LDS>
@@ -131,9 +155,39 @@ __device__ __forceinline__ void table_insert(const LzwArgs& a, int b, int lane, 
 
 // ------------------------------------------------------------------------------------------------
 // encode
+//
+// The serial chain of the parse is cut into rounds of 64 positions whose work is done by the 64 lanes
+// side by side; nothing in a round is a per-token scalar loop.
+//   1. lane j follows, for the phrase that would start at position pos + j, the chain of lookups
+//      token -> (code, next token) -> ... against the table as it stands at the start of the round
+//      (at most M-1 probes, all lanes at once).  This gives L0[j], the length of that match.
+//   2. the true phrase starts are the positions reached from 0 by j -> j + L0[j]; six rounds of pointer
+//      doubling (each lane carries the 64-bit set of positions its chain visits) give lane 0 the set.
+//   3. a start whose match may still grow (length < M, a next token exists) proposes the edge
+//      (its code, next token); the proposals of the round get consecutive entry numbers in position
+//      order while the codebook has room.
+//   4. what step 1 cannot see is an entry made earlier in this same round.  A phrase is longer than
+//      L0 exactly when its proposed edge equals an edge proposed by an earlier start of the round, so
+//      the round is cut at the first such repeat (found with a small LDS hash filter keyed by edge,
+//      keeping the lowest position): everything before the cut is exact, and the next round starts at
+//      the cut with the new entries in the table.  A cut is never at position 0, so every round emits
+//      at least one phrase.
+//   5. the starts before the cut store their codes, insert their edges (compare-and-swap on the slot)
+//      and write their flattened rows from the staged tokens.
+// Greedy longest match and the order of entry creation are those of the one-token-at-a-time parse: a
+// lookup that hit at the start of the round still hits later, and a new entry only matters to later
+// starts.  Tokens are staged in LDS kTokBuf at a time, so a round reads no global memory.
 // ------------------------------------------------------------------------------------------------
+constexpr int kTokBuf = 2048;                 // tokens staged in LDS per refill
+constexpr int kFilter = 128;                  // slots of the per-round repeat filter (<= 64 keys)
+constexpr int kEncStaticLds = kTokBuf * 4 + kFilter * 8;
+
+__device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 template <bool LDS>
 __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
+  __shared__ int32_t tokbuf[kTokBuf];         // token classes: >= 0 valid ID, -2 out of range
+  __shared__ u64 filter[kFilter];
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
@@ -146,93 +200,182 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 
   Table<LDS> t;
   table_open<LDS>(a, b, lane, reset, &t);
-
-  // tokens of the previous phrase (lane j = token j), needed only for the first entry of an append
-  int32_t ph = -1;
-  if (prev >= 0) {
-    if (prev < V) {
-      ph = lane == 0 ? prev : -1;
-    } else if (lane < M) {
-      ph = st.ent_tokens[((size_t)b * cap + (prev - V)) * M + lane];
-    }
-  }
+  filter[lane] = kEmpty;
+  filter[lane + kWave] = kEmpty;
 
   const int n = a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
   const int32_t* in = a.in + (size_t)b * a.stride;
   int32_t* out = a.out + (size_t)b * a.out_stride;
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
 
   int status = 0;
-  int w = -1, wlen = 0;      // current phrase: its code and its length (w < 0: none yet in this call)
   int n_out = 0;
-  int32_t out_reg = 0;       // lane (n_out % 64) holds the code emitted at position n_out
-  bool stop = false;
 
-  for (int base = 0; base < n && !stop; base += kWave) {
-    const int cnt = min(kWave, n - base);
-    const int32_t tok_reg = lane < cnt ? in[base + lane] : 0;
-    for (int j = 0; j < cnt; ++j) {
-      const int32_t c = __builtin_amdgcn_readlane(tok_reg, j);
-      if (c < 0 || c >= V) {
-        status |= Z2Z_ST_BAD_TOKEN;
-        stop = true;
-        break;
-      }
+  // An appended call: the entry "last emitted phrase + first token of this call", which the earlier
+  // flush could not add, is added now if it is legal and absent.
+  if (n > 0 && prev >= 0 && prev_len < M && C < cap) {
+    const int32_t c = __builtin_amdgcn_readfirstlane(in[0]);
+    if (c >= 0 && c < V) {
       int free_pos = -1;
-      bool emit = false;
-      if (w >= 0 && wlen < M) {
-        const int idx = t.find(w, c, &free_pos);
-        if (idx >= 0) {               // the match grows
-          w = V + idx;
-          if (lane == wlen) ph = c;
-          ++wlen;
-          continue;
+      const int idx = t.find(prev, c, &free_pos);
+      if (idx < 0 && free_pos >= 0) {
+        int32_t ph = -1;        // lane j = token j of the previous phrase
+        if (prev < V) {
+          ph = lane == 0 ? prev : -1;
+        } else if (lane < M) {
+          ph = ent_tokens[(size_t)(prev - V) * M + lane];
         }
-        emit = true;
-      } else if (w >= 0) {            // phrase already has M tokens: it ends here, nothing is added
-        emit = true;
-      } else if (prev >= 0 && prev_len < M && C < cap) {
-        // first token of an appended chunk: the entry the earlier flush could not add
-        const int idx = t.find(prev, c, &free_pos);
-        if (idx < 0 && free_pos >= 0) {
-          table_insert<LDS>(a, b, lane, t, free_pos, C, prev, c, ph, prev_len);
-          ++C;
-        }
+        table_insert<LDS>(a, b, lane, t, free_pos, C, prev, c, ph, prev_len);
+        ++C;
       }
-      if (emit) {
-        if (n_out >= a.out_stride) {
-          status |= Z2Z_ST_OVERFLOW;
-          stop = true;
-          w = -1;
-          break;
-        }
-        if (lane == (n_out & (kWave - 1))) out_reg = w;
-        ++n_out;
-        if ((n_out & (kWave - 1)) == 0) out[n_out - kWave + lane] = out_reg;
-        prev = w;
-        prev_len = wlen;
-        if (wlen < M && C < cap && free_pos >= 0) {
-          table_insert<LDS>(a, b, lane, t, free_pos, C, w, c, ph, wlen);
-          ++C;
-        }
-      }
-      w = c;
-      wlen = 1;
-      if (lane == 0) ph = c;
     }
+    __syncthreads();
   }
-  if (w >= 0) {                       // flush the pending phrase; no entry is added
-    if (n_out >= a.out_stride) {
+
+  const u64 lanes_below = (1ull << lane) - 1;
+  int cbase = 0;                      // tokbuf holds positions [cbase, cbase + kTokBuf)
+  bool filled = false;
+  bool stop = false;
+  int pos = 0;                        // first position not yet covered by an emitted phrase
+  while (pos < n && !stop) {
+    // a round touches positions pos .. pos + 63 + M
+    if (!filled || (pos + kWave + M > cbase + kTokBuf && cbase + kTokBuf < n)) {
+      cbase = pos;
+      filled = true;
+      const int cnt = min(kTokBuf, n - cbase);
+      for (int i = lane; i < cnt; i += kWave) {
+        const int32_t v = in[cbase + i];
+        tokbuf[i] = (v >= 0 && v < V) ? v : -2;
+      }
+      lds_order();
+    }
+    const int rel = pos - cbase + lane;
+    auto tk = [&](int d) -> int32_t {           // token class at position pos + lane + d, -1 past the end
+      return pos + lane + d < n ? tokbuf[rel + d] : -1;
+    };
+
+    // ---- 1. chains against the table of the round's start ---------------------------------------
+    const int32_t tok0 = tk(0);
+    int L0 = tok0 >= 0 ? 1 : 0;
+    int32_t cfin = tok0;
+    int32_t nxt = tk(1);              // always the token that follows this lane's match
+    for (int d = 1; d < M; ++d) {
+      int idx = -1;
+      if (L0 == d && nxt >= 0) idx = t.find_lane(cfin, nxt);
+      if (__ballot(idx >= 0) == 0) break;
+      if (idx >= 0) {
+        cfin = V + idx;
+        L0 = d + 1;
+        nxt = tk(d + 1);
+      }
+    }
+
+    // ---- 2. phrase starts: positions reachable from 0 ---------------------------------------------
+    const int avail = min(kWave, n - pos);
+    int jump = (L0 > 0 && lane + L0 < kWave) ? lane + L0 : kWave;
+    uint32_t r_lo = lane < 32 ? 1u << lane : 0u, r_hi = lane < 32 ? 0u : 1u << (lane - 32);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+      const int src = jump & (kWave - 1);
+      const uint32_t o_lo = __shfl(r_lo, src), o_hi = __shfl(r_hi, src);
+      const int o_jump = __shfl(jump, src);
+      if (jump < kWave) {
+        r_lo |= o_lo;
+        r_hi |= o_hi;
+        jump = o_jump;
+      }
+    }
+    const u64 S = ((u64)(uint32_t)__builtin_amdgcn_readfirstlane(r_hi) << 32) |
+                  (u64)(uint32_t)__builtin_amdgcn_readfirstlane(r_lo);
+    const bool start = ((S >> lane) & 1) != 0 && lane < avail;
+    const int prank = __popcll(S & lanes_below);          // phrases of the round before this one
+
+    // ---- 3. limits of the round, proposals -------------------------------------------------------
+    const u64 bad_mask = __ballot(start && tok0 == -2);
+    const u64 ovf_mask = __ballot(start && n_out + prank >= a.out_stride);
+    const int bad_pos = bad_mask ? __builtin_ctzll(bad_mask) : kWave;
+    const int ovf_pos = ovf_mask ? __builtin_ctzll(ovf_mask) : kWave;
+    const bool cand = start && tok0 >= 0 && L0 < M && nxt >= 0;
+    const u64 cand_mask = __ballot(cand);
+    const int rank = __popcll(cand_mask & lanes_below);
+    const int room = cap - C;
+    const bool inserter = cand && rank < room;
+
+    // ---- 4. first repeat of a proposed edge --------------------------------------------------------
+    int cut = kWave;
+    if (room > 0 && (cand_mask & (cand_mask - 1)) != 0) {
+      const u64 key = edge_bits(cfin, nxt);
+      const uint32_t h0 = (edge_hash(cfin, nxt) >> 20) & (kFilter - 1);
+      int own = -1;
+      if (inserter) {
+        const u64 val = key | (u64)lane;
+        uint32_t h = h0;
+        for (int probe = 0; probe < kFilter; ++probe) {
+          const u64 old = atomicCAS(&filter[h], kEmpty, val);
+          if (old == kEmpty) {
+            own = (int)h;
+            break;
+          }
+          if ((old & ~0xFFFFull) == key) {
+            atomicMin(&filter[h], val);             // same edge: keep the lowest position
+            break;
+          }
+          h = (h + 1) & (kFilter - 1);
+        }
+      }
+      lds_order();
+      int fpos = kWave;
+      if (cand) {
+        uint32_t h = h0;
+        for (int probe = 0; probe < kFilter; ++probe) {
+          const u64 sl = filter[h];
+          if (sl == kEmpty) break;
+          if ((sl & ~0xFFFFull) == key) {
+            fpos = (int)(sl & 0xFFFFull);
+            break;
+          }
+          h = (h + 1) & (kFilter - 1);
+        }
+      }
+      const u64 dup_mask = __ballot(cand && fpos < lane);
+      lds_order();
+      if (own >= 0) filter[own] = kEmpty;             // leave the filter empty for the next round
+      if (dup_mask) cut = __builtin_ctzll(dup_mask);
+    }
+
+    // ---- 5. publish ---------------------------------------------------------------------------------
+    const int limit = min(min(avail, cut), min(bad_pos, ovf_pos));
+    if (bad_pos < kWave && limit == bad_pos) {
+      status |= Z2Z_ST_BAD_TOKEN;     // the sequence ends just before this token
+      stop = true;
+    } else if (ovf_pos < kWave && limit == ovf_pos) {
       status |= Z2Z_ST_OVERFLOW;
+      stop = true;
+    }
+    const bool valid = start && lane < limit;
+    const u64 valid_mask = __ballot(valid);
+    if (valid) out[n_out + prank] = cfin;
+    const bool ins = valid && inserter;
+    if (ins) {
+      const int idx = C + rank;
+      t.insert_lane(cfin, nxt, idx);
+      int32_t* row = ent_tokens + (size_t)idx * M;
+      for (int k = 0; k < M; ++k) row[k] = k <= L0 ? tokbuf[rel + k] : -1;
+      ent_len[idx] = L0 + 1;
+    }
+    lds_order();
+    C += __popcll(__ballot(ins));
+    if (valid_mask) {
+      const int last = 63 - __builtin_clzll(valid_mask);
+      prev = __builtin_amdgcn_readlane(cfin, last);
+      prev_len = __builtin_amdgcn_readlane(L0, last);
+      n_out += __popcll(valid_mask);
+      pos += last + prev_len;
     } else {
-      if (lane == (n_out & (kWave - 1))) out_reg = w;
-      ++n_out;
-      if ((n_out & (kWave - 1)) == 0) out[n_out - kWave + lane] = out_reg;
-      prev = w;
-      prev_len = wlen;
+      stop = true;                    // only reached with a limit of 0 (bad token or no room at the first start)
     }
   }
-  const int tail = n_out & (kWave - 1);
-  if (tail != 0 && lane < tail) out[n_out - tail + lane] = out_reg;
 
   table_close<LDS>(a, lane, t);
   if (lane == 0) {
@@ -510,7 +653,7 @@ int z2z_lzw_prepare(z2z_ctx* c) {
   const int cap = st.cap;
   const int want = 2 * cap < 64 ? 64 : 2 * cap;
   const int floor125 = cap + cap / 4 + 1;
-  const int lds_slots = c->lds_limit / (int)sizeof(u64);
+  const int lds_slots = (c->lds_limit - kEncStaticLds) / (int)sizeof(u64);   // the encoder's own LDS comes first
   if (want <= lds_slots) {
     st.nslots = want;
     st.slots_fit_lds = 1;
@@ -522,7 +665,7 @@ int z2z_lzw_prepare(z2z_ctx* c) {
     st.slots_fit_lds = 0;
   }
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
   return Z2Z_OK;
