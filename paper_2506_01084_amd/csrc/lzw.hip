@@ -55,6 +55,22 @@ struct Table {
   u64* g;           // global slots of this sequence
   uint32_t n;       // number of slots
 
+  // Slots are probed in pairs ("buckets", n is even) so that the per-lane lookup tests two slots with
+  // one 16-byte LDS read.  The first kJumps buckets of a probe sequence are `step` buckets apart (a
+  // second hash: no clustering, so the longest of 64 simultaneous probes stays short), the rest follow
+  // one by one, which reaches every bucket whatever n is.  A lookup ends at the first empty slot.
+  static constexpr uint32_t kJumps = 8;
+  __device__ __forceinline__ void probe_init(int32_t parent, int32_t tok, uint32_t* bucket, uint32_t* step) const {
+    const uint32_t h = edge_hash(parent, tok);
+    const uint32_t nb = n >> 1;
+    *bucket = __umulhi(h, nb);
+    *step = 1 + __umulhi(h * 0x9E3779B1u + 0x7F4A7C15u, nb - 1);       // 1 .. nb-1
+  }
+  __device__ __forceinline__ uint32_t probe_next(uint32_t bucket, uint32_t step, uint32_t i) const {
+    const uint32_t nb = n >> 1;
+    bucket += i < kJumps ? step : 1;
+    return bucket >= nb ? bucket - nb : bucket;
+  }
   __device__ __forceinline__ u64 load(uint32_t pos) const {
     const u64 v = LDS ? lds_slots[pos] : g[pos];
     // every lane reads the same address; readfirstlane keeps the chain in scalar registers
@@ -68,19 +84,24 @@ struct Table {
     else
       g[pos] = v;
   }
-  // Linear probing.  Returns the entry index, or -1 with *free_pos = the empty slot the probe ended at
-  // (-1 if the table has no empty slot, which cannot happen while n > cap).
+  // Returns the entry index, or -1 with *free_pos = the empty slot the probe ended at (-1 if the
+  // table has no empty slot, which cannot happen while n > cap).
   __device__ __forceinline__ int find(int32_t parent, int32_t tok, int* free_pos) const {
     const u64 key = edge_bits(parent, tok);
-    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
-    for (uint32_t probe = 0; probe < n; ++probe) {
-      const u64 s = load(pos);
-      if (s == kEmpty) {
-        *free_pos = (int)pos;
-        return -1;
+    uint32_t bucket, step;
+    probe_init(parent, tok, &bucket, &step);
+    const uint32_t n_probe = (n >> 1) + kJumps;
+    for (uint32_t i = 0; i < n_probe; ++i) {
+      for (uint32_t k = 0; k < 2; ++k) {
+        const uint32_t pos = 2 * bucket + k;
+        const u64 s = load(pos);
+        if (s == kEmpty) {
+          *free_pos = (int)pos;
+          return -1;
+        }
+        if ((s & ~0xFFFFull) == key) return (int)(s & 0xFFFFull);
       }
-      if ((s & ~0xFFFFull) == key) return (int)(s & 0xFFFFull);
-      pos = pos + 1 == n ? 0 : pos + 1;
+      bucket = probe_next(bucket, step, i);
     }
     *free_pos = -1;
     return -1;
@@ -89,12 +110,24 @@ struct Table {
   // is read past the vector L1: slots are claimed with atomics, which do not update that cache.
   __device__ __forceinline__ int find_lane(int32_t parent, int32_t tok) const {
     const u64 key = edge_bits(parent, tok);
-    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
-    for (uint32_t probe = 0; probe < n; ++probe) {
-      const u64 s = LDS ? lds_slots[pos] : __hip_atomic_load(&g[pos], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (s == kEmpty) return -1;
-      if ((s & ~0xFFFFull) == key) return (int)(s & 0xFFFFull);
-      pos = pos + 1 == n ? 0 : pos + 1;
+    uint32_t bucket, step;
+    probe_init(parent, tok, &bucket, &step);
+    const uint32_t n_probe = (n >> 1) + kJumps;
+    for (uint32_t i = 0; i < n_probe; ++i) {
+      u64 s0, s1;
+      if (LDS) {
+        const ulonglong2 two = *reinterpret_cast<const ulonglong2*>(&lds_slots[2 * bucket]);
+        s0 = two.x;
+        s1 = two.y;
+      } else {
+        s0 = __hip_atomic_load(&g[2 * bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s1 = __hip_atomic_load(&g[2 * bucket + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (s0 == kEmpty) return -1;
+      if ((s0 & ~0xFFFFull) == key) return (int)(s0 & 0xFFFFull);
+      if (s1 == kEmpty) return -1;
+      if ((s1 & ~0xFFFFull) == key) return (int)(s1 & 0xFFFFull);
+      bucket = probe_next(bucket, step, i);
     }
     return -1;
   }
@@ -102,11 +135,14 @@ struct Table {
   // sequence with a compare-and-swap (several lanes insert at once).
   __device__ __forceinline__ void insert_lane(int32_t parent, int32_t tok, int idx) const {
     const u64 val = edge_bits(parent, tok) | (u64)(uint32_t)idx;
-    uint32_t pos = __umulhi(edge_hash(parent, tok), n);
-    for (uint32_t probe = 0; probe < n; ++probe) {
-      u64* slot = LDS ? &lds_slots[pos] : &g[pos];
+    uint32_t bucket, step;
+    probe_init(parent, tok, &bucket, &step);
+    const uint32_t n_probe = (n >> 1) + kJumps;
+    for (uint32_t i = 0; i < n_probe; ++i) {
+      u64* slot = LDS ? &lds_slots[2 * bucket] : &g[2 * bucket];
       if (atomicCAS(slot, kEmpty, val) == kEmpty) return;
-      pos = pos + 1 == n ? 0 : pos + 1;
+      if (atomicCAS(slot + 1, kEmpty, val) == kEmpty) return;
+      bucket = probe_next(bucket, step, i);
     }
   }
 };
@@ -179,7 +215,7 @@ __device__ __forceinline__ void table_insert(const LzwArgs& a, int b, int lane, 
 // starts.  Tokens are staged in LDS kTokBuf at a time, so a round reads no global memory.
 // ------------------------------------------------------------------------------------------------
 constexpr int kTokBuf = 2048;                 // tokens staged in LDS per refill
-constexpr int kFilter = 128;                  // slots of the per-round repeat filter (<= 64 keys)
+constexpr int kFilter = 512;                  // slots of the per-round repeat filter (<= 64 keys)
 constexpr int kEncStaticLds = kTokBuf * 4 + kFilter * 8;
 
 __device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -200,8 +236,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 
   Table<LDS> t;
   table_open<LDS>(a, b, lane, reset, &t);
-  filter[lane] = kEmpty;
-  filter[lane + kWave] = kEmpty;
+  for (int i = lane; i < kFilter; i += kWave) filter[i] = kEmpty;
 
   const int n = a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
   const int32_t* in = a.in + (size_t)b * a.stride;
@@ -308,6 +343,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
       const u64 key = edge_bits(cfin, nxt);
       const uint32_t h0 = (edge_hash(cfin, nxt) >> 20) & (kFilter - 1);
       int own = -1;
+      bool same = false;                              // met its own edge in the filter
       if (inserter) {
         const u64 val = key | (u64)lane;
         uint32_t h = h0;
@@ -319,27 +355,33 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
           }
           if ((old & ~0xFFFFull) == key) {
             atomicMin(&filter[h], val);             // same edge: keep the lowest position
+            same = true;
             break;
           }
           h = (h + 1) & (kFilter - 1);
         }
       }
       lds_order();
-      int fpos = kWave;
-      if (cand) {
-        uint32_t h = h0;
-        for (int probe = 0; probe < kFilter; ++probe) {
-          const u64 sl = filter[h];
-          if (sl == kEmpty) break;
-          if ((sl & ~0xFFFFull) == key) {
-            fpos = (int)(sl & 0xFFFFull);
-            break;
+      u64 dup_mask = 0;
+      // No inserter met its edge: all inserted edges differ.  A proposal without room can then only
+      // repeat an inserted one, which the lookup below finds; with room for all there is none.
+      if (__ballot(same) != 0 || __ballot(cand && !inserter) != 0) {
+        int fpos = kWave;
+        if (cand) {
+          uint32_t h = h0;
+          for (int probe = 0; probe < kFilter; ++probe) {
+            const u64 sl = filter[h];
+            if (sl == kEmpty) break;
+            if ((sl & ~0xFFFFull) == key) {
+              fpos = (int)(sl & 0xFFFFull);
+              break;
+            }
+            h = (h + 1) & (kFilter - 1);
           }
-          h = (h + 1) & (kFilter - 1);
         }
+        dup_mask = __ballot(cand && fpos < lane);
+        lds_order();
       }
-      const u64 dup_mask = __ballot(cand && fpos < lane);
-      lds_order();
       if (own >= 0) filter[own] = kEmpty;             // leave the filter empty for the next round
       if (dup_mask) cut = __builtin_ctzll(dup_mask);
     }
@@ -647,14 +689,18 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
 }
 
 // Size the hash table for the device's LDS and raise the dynamic-LDS ceiling of the parse kernels.
-// Load factor at a full codebook is at most 0.8 (at least 1.25 slots per entry, 2 when LDS allows).
+// Load factor at a full codebook is at most 0.8 (at least 1.25 slots per entry; 2 or 4 when LDS allows).
 int z2z_lzw_prepare(z2z_ctx* c) {
   LzwState& st = c->st;
   const int cap = st.cap;
+  const int want4 = 4 * cap < 64 ? 64 : 4 * cap;
   const int want = 2 * cap < 64 ? 64 : 2 * cap;
   const int floor125 = cap + cap / 4 + 1;
   const int lds_slots = (c->lds_limit - kEncStaticLds) / (int)sizeof(u64);   // the encoder's own LDS comes first
-  if (want <= lds_slots) {
+  if (want4 + cap / 2 <= lds_slots) {                 // room left for the decoder's entry info
+    st.nslots = want4;
+    st.slots_fit_lds = 1;
+  } else if (want <= lds_slots) {
     st.nslots = want;
     st.slots_fit_lds = 1;
   } else if (floor125 <= lds_slots) {
@@ -664,6 +710,7 @@ int z2z_lzw_prepare(z2z_ctx* c) {
     st.nslots = want;
     st.slots_fit_lds = 0;
   }
+  st.nslots &= ~1;                                     // even: probe sequences start on slot pairs
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
