@@ -2,15 +2,17 @@
 //
 // The parse of one sequence is a serial dependency chain (section 2.1 of the zip2zip paper: every
 // step looks up "current phrase + next token" in the codebook built so far), so the unit of
-// parallelism is the sequence and the cost per token is the latency of one probe.  The codebook is a
-// trie stored as a hash table over its edges: one 64-bit slot = parent code (24 bits) | token (24 bits)
-// | entry index (16 bits), so a probe is a single 8-byte LDS read and compare.  The wave keeps the
-// table of its sequence in LDS for the whole call (up to 20480 slots in the 160 KiB of a CU); the
-// decoder also keeps (length, first token) of every entry there when it fits.  Tokens are read 64 at a
-// time with one coalesced load and handed out with readlane; emitted codes are collected in a
-// lane-distributed register and written 64 at a time; the decoder expands 64 codes at a time, one
-// code per lane, after their lengths are known.  Control flow is wave-uniform and kept in scalar
-// registers (readfirstlane).
+// parallelism across workgroups is the sequence.  Inside a sequence the 64 lanes work on 64 consecutive
+// positions (encoder) or codes (decoder) at once against the codebook as it stood when the round began,
+// and the round is cut short at the first element that depends on an entry made inside the round; the
+// kernels' own comments give the argument why the result is that of the one-element-at-a-time loop.
+//
+// The codebook is a trie stored as a hash table over its edges: one 64-bit slot = parent code (24 bits)
+// | token (24 bits) | entry index (16 bits), two slots per bucket, so a probe is one 16-byte LDS read and
+// two compares.  The wave keeps the table of its sequence in LDS for the whole call (4 slots per entry
+// when the 160 KiB of a CU allow, at least 1.25); the decoder also keeps (length, first token) of every
+// entry there when it fits.  Tokens and codes are staged in LDS 2048 at a time.  Control flow is
+// wave-uniform (ballots, scalar registers).
 #include "z2z_internal.h"
 
 namespace {
@@ -220,6 +222,58 @@ constexpr int kEncStaticLds = kTokBuf * 4 + kFilter * 8;
 
 __device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// The first lane whose proposed edge (parent, tok) repeats the edge of an earlier lane that inserts
+// (kWave if there is none).  `cand` lanes propose, the `inserter` ones among them (a prefix of the
+// candidates in lane order) have room to insert.  `filter` is an empty LDS hash set on entry and on exit.
+__device__ __forceinline__ int first_repeat(u64* filter, int lane, bool cand, bool inserter, int32_t parent,
+                                            int32_t tok) {
+  const u64 key = edge_bits(parent, tok);
+  const uint32_t h0 = (edge_hash(parent, tok) >> 20) & (kFilter - 1);
+  int own = -1;
+  bool same = false;                                // met its own edge in the filter
+  if (inserter) {
+    const u64 val = key | (u64)lane;
+    uint32_t h = h0;
+    for (int probe = 0; probe < kFilter; ++probe) {
+      const u64 old = atomicCAS(&filter[h], kEmpty, val);
+      if (old == kEmpty) {
+        own = (int)h;
+        break;
+      }
+      if ((old & ~0xFFFFull) == key) {
+        atomicMin(&filter[h], val);                 // same edge: keep the lowest lane
+        same = true;
+        break;
+      }
+      h = (h + 1) & (kFilter - 1);
+    }
+  }
+  lds_order();
+  u64 dup_mask = 0;
+  // No inserter met its edge: all inserted edges differ.  A proposal without room can then only
+  // repeat an inserted one, which the lookup below finds; with room for all there is none.
+  if (__ballot(same) != 0 || __ballot(cand && !inserter) != 0) {
+    int fpos = kWave;
+    if (cand) {
+      uint32_t h = h0;
+      for (int probe = 0; probe < kFilter; ++probe) {
+        const u64 sl = filter[h];
+        if (sl == kEmpty) break;
+        if ((sl & ~0xFFFFull) == key) {
+          fpos = (int)(sl & 0xFFFFull);
+          break;
+        }
+        h = (h + 1) & (kFilter - 1);
+      }
+    }
+    dup_mask = __ballot(cand && fpos < lane);
+    lds_order();
+  }
+  if (own >= 0) filter[own] = kEmpty;               // leave the filter empty for the next round
+  lds_order();
+  return dup_mask ? __builtin_ctzll(dup_mask) : kWave;
+}
+
 template <bool LDS>
 __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
   __shared__ int32_t tokbuf[kTokBuf];         // token classes: >= 0 valid ID, -2 out of range
@@ -339,52 +393,7 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 
     // ---- 4. first repeat of a proposed edge --------------------------------------------------------
     int cut = kWave;
-    if (room > 0 && (cand_mask & (cand_mask - 1)) != 0) {
-      const u64 key = edge_bits(cfin, nxt);
-      const uint32_t h0 = (edge_hash(cfin, nxt) >> 20) & (kFilter - 1);
-      int own = -1;
-      bool same = false;                              // met its own edge in the filter
-      if (inserter) {
-        const u64 val = key | (u64)lane;
-        uint32_t h = h0;
-        for (int probe = 0; probe < kFilter; ++probe) {
-          const u64 old = atomicCAS(&filter[h], kEmpty, val);
-          if (old == kEmpty) {
-            own = (int)h;
-            break;
-          }
-          if ((old & ~0xFFFFull) == key) {
-            atomicMin(&filter[h], val);             // same edge: keep the lowest position
-            same = true;
-            break;
-          }
-          h = (h + 1) & (kFilter - 1);
-        }
-      }
-      lds_order();
-      u64 dup_mask = 0;
-      // No inserter met its edge: all inserted edges differ.  A proposal without room can then only
-      // repeat an inserted one, which the lookup below finds; with room for all there is none.
-      if (__ballot(same) != 0 || __ballot(cand && !inserter) != 0) {
-        int fpos = kWave;
-        if (cand) {
-          uint32_t h = h0;
-          for (int probe = 0; probe < kFilter; ++probe) {
-            const u64 sl = filter[h];
-            if (sl == kEmpty) break;
-            if ((sl & ~0xFFFFull) == key) {
-              fpos = (int)(sl & 0xFFFFull);
-              break;
-            }
-            h = (h + 1) & (kFilter - 1);
-          }
-        }
-        dup_mask = __ballot(cand && fpos < lane);
-        lds_order();
-      }
-      if (own >= 0) filter[own] = kEmpty;             // leave the filter empty for the next round
-      if (dup_mask) cut = __builtin_ctzll(dup_mask);
-    }
+    if (room > 0 && (cand_mask & (cand_mask - 1)) != 0) cut = first_repeat(filter, lane, cand, inserter, cfin, nxt);
 
     // ---- 5. publish ---------------------------------------------------------------------------------
     const int limit = min(min(avail, cut), min(bad_pos, ovf_pos));
@@ -435,8 +444,10 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 // (length, first token) of an entry packed in 32 bits: length in the top 4 bits.
 __device__ __forceinline__ uint32_t pack_ef(int len, int32_t first) { return ((uint32_t)len << 28) | (uint32_t)first; }
 
+// One code at a time (the textbook loop, wave-uniform): used for short appended calls, where a
+// round of the kernel below would be mostly empty.
 template <bool LDS>
-__global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
+__global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
@@ -588,6 +599,224 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
   }
 }
 
+// Entry data written earlier in the same launch is read past the vector L1.
+__device__ __forceinline__ int32_t load_fresh(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Rounds of up to 63 codes, one code per lane; lane 0 stands for the code before the round (its phrase
+// is the parent of the entry the first code of the round may cause).
+//   1. (length, first token) of every code whose entry existed when the round began; the round ends
+//      before the first code that names a later entry (or no entry at all).  If that is the very first
+//      code of the round it is taken alone, the textbook way (the one not-yet-defined code, or an error).
+//   2. code i proposes the edge (code i-1, first token of code i) if code i-1 is shorter than M; the
+//      table is probed for all proposals at once; absent ones get consecutive entry numbers while the
+//      codebook has room.  As in the encoder the round is cut at the first proposal that repeats an
+//      earlier one of the same round (only streams that no greedy parse produced have such repeats).
+//   3. token offsets are a prefix sum of the lengths (lengths are < 16: four ballots); the round is cut
+//      before the first code whose tokens do not fit.
+//   4. the lanes before the cut insert their edges, lane i-1 writes the flattened row of the entry that
+//      code i caused (its own tokens + that first token), and every lane writes its tokens.
+template <bool LDS>
+__global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
+  __shared__ int32_t codebuf[kTokBuf];
+  __shared__ u64 filter[kFilter];
+  const LzwState& st = a.st;
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int V = st.V, M = st.M, cap = st.cap;
+  const bool reset = (a.flags & Z2Z_RESET) != 0;
+  const bool ef_lds = LDS && a.lds_ef;
+  uint32_t* ef = reinterpret_cast<uint32_t*>(lds_slots + st.nslots);   // [cap], valid when ef_lds
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
+
+  int C = reset ? 0 : __builtin_amdgcn_readfirstlane(st.size[b]);
+  int prev = reset ? -1 : __builtin_amdgcn_readfirstlane(st.prev_code[b]);
+  int prev_len = reset ? 0 : __builtin_amdgcn_readfirstlane(st.prev_len[b]);
+
+  Table<LDS> t;
+  if (ef_lds && !reset) {
+    for (int i = lane; i < C; i += kWave) ef[i] = pack_ef(ent_len[i], ent_tokens[(size_t)i * M]);
+  }
+  table_open<LDS>(a, b, lane, reset, &t);
+  for (int i = lane; i < kFilter; i += kWave) filter[i] = kEmpty;
+
+  const int n = a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
+  const int32_t* in = a.in + (size_t)b * a.stride;
+  int32_t* out = a.out ? a.out + (size_t)b * a.out_stride : nullptr;
+
+  const u64 lanes_upto = lane == 63 ? ~0ull : (2ull << lane) - 1;     // lanes 0..lane
+  const u64 lanes_below = (1ull << lane) - 1;
+  int status = 0;
+  int n_out = 0;
+  bool stop = false;
+  int cbase = 0;                      // codebuf holds codes [cbase, cbase + kTokBuf)
+  bool filled = false;
+  int cpos = 0;                       // codes consumed
+  while (cpos < n && !stop) {
+    if (!filled || (cpos + kWave > cbase + kTokBuf && cbase + kTokBuf < n)) {
+      cbase = cpos;
+      filled = true;
+      const int cnt = min(kTokBuf, n - cbase);
+      for (int i = lane; i < cnt; i += kWave) codebuf[i] = in[cbase + i];
+      lds_order();
+    }
+    // ---- 1. the codes of the round ------------------------------------------------------------------
+    const int ci = cpos + lane - 1;
+    const bool present = lane == 0 ? prev >= 0 : ci < n;
+    const int32_t k = lane == 0 ? prev : (ci < n ? codebuf[ci - cbase] : -1);
+    int len = 0;
+    int32_t first = 0;
+    bool known = false;
+    if (present && k >= 0 && k < V) {
+      len = 1;
+      first = k;
+      known = true;
+    } else if (present && k >= V && k - V < C) {
+      const uint32_t e = ef_lds ? ef[k - V]
+                                : pack_ef(load_fresh(&ent_len[k - V]), load_fresh(&ent_tokens[(size_t)(k - V) * M]));
+      len = (int)(e >> 28);
+      first = (int32_t)(e & 0x0FFFFFFFu);
+      known = true;
+    }
+    const u64 hard_mask = __ballot(present && !known);          // never lane 0
+    const int hard_pos = hard_mask ? __builtin_ctzll(hard_mask) : kWave;
+
+    if (hard_pos == 1) {
+      // the first code of the round names no entry of the codebook as it stands: it is either
+      // "previous phrase + its own first token", which must be legal and absent, or an error
+      const int32_t k1 = __builtin_amdgcn_readlane(k, 1);
+      bool ok = false;
+      if (k1 >= V && k1 - V == C && prev >= 0 && prev_len < M && C < cap) {
+        const int32_t pf = __builtin_amdgcn_readlane(first, 0);
+        int free_pos = -1;
+        const int idx = t.find(prev, pf, &free_pos);
+        if (idx < 0 && free_pos >= 0) {
+          const int cur_len = prev_len + 1;
+          if (out != nullptr && n_out + cur_len > a.out_stride) {
+            status |= Z2Z_ST_OVERFLOW;
+            stop = true;
+          } else {
+            int32_t tokj = -1;        // lane j: token j of the new phrase
+            if (lane < prev_len) tokj = prev < V ? prev : load_fresh(&ent_tokens[(size_t)(prev - V) * M + lane]);
+            if (lane == prev_len) tokj = pf;
+            if (lane == 0) {
+              t.store((uint32_t)free_pos, edge_bits(prev, pf) | (u64)(uint32_t)C);
+              if (ef_lds) ef[C] = pack_ef(cur_len, pf);
+              ent_len[C] = cur_len;
+            }
+            if (lane < M) ent_tokens[(size_t)C * M + lane] = tokj;
+            if (out != nullptr && lane < cur_len) out[n_out + lane] = tokj;
+            prev = k1;
+            prev_len = cur_len;
+            ++C;
+            n_out += cur_len;
+            ++cpos;
+          }
+          ok = true;
+        }
+      }
+      if (!ok) {
+        status |= Z2Z_ST_BAD_CODE;
+        stop = true;
+      }
+      __syncthreads();                // the new row is in memory before a later round reads it
+      continue;
+    }
+
+    // ---- 2. proposals --------------------------------------------------------------------------------
+    const int limit0 = min(hard_pos, min(kWave, n - cpos + 1));  // lanes 1 .. limit0-1 hold known codes
+    const int32_t pk = __shfl_up(k, 1);
+    const int plen = __shfl_up(len, 1);
+    const int32_t pfirst = __shfl_up(first, 1);
+    const bool pknown = __shfl_up((int)known, 1) != 0;
+    const int room = cap - C;
+    const bool prop = lane >= 1 && lane < limit0 && pknown && plen < M && room > 0;
+    int found = -1;
+    if (prop) found = t.find_lane(pk, first);
+    const bool cand = prop && found < 0;
+    const u64 cand_mask = __ballot(cand);
+    const int rank = __popcll(cand_mask & lanes_below);
+    const bool inserter = cand && rank < room;
+    int cut = kWave;
+    if ((cand_mask & (cand_mask - 1)) != 0) cut = first_repeat(filter, lane, cand, inserter, pk, first);
+
+    // ---- 3. token offsets -------------------------------------------------------------------------------
+    const int mylen = (lane >= 1 && lane < limit0) ? len : 0;
+    int incl = 0;                     // tokens of codes 1 .. lane of the round
+#pragma unroll
+    for (int bit = 0; bit < 4; ++bit) incl += __popcll(__ballot((mylen >> bit) & 1) & lanes_upto) << bit;
+    const u64 ovf_mask = __ballot(out != nullptr && mylen > 0 && n_out + incl > a.out_stride);
+    const int ovf_pos = ovf_mask ? __builtin_ctzll(ovf_mask) : kWave;
+    const int limit = min(limit0, min(cut, ovf_pos));
+    if (ovf_pos < kWave && limit == ovf_pos) {
+      status |= Z2Z_ST_OVERFLOW;
+      stop = true;
+    }
+
+    // ---- 4. publish ---------------------------------------------------------------------------------------
+    const bool valid = lane >= 1 && lane < limit;
+    const bool ins = valid && inserter;
+    const int idx = C + rank;
+    if (ins) {
+      t.insert_lane(pk, first, idx);
+      if (ef_lds) ef[idx] = pack_ef(plen + 1, pfirst);
+    }
+    // the tokens of this lane's own code (lane 0: of the code before the round)
+    int32_t T[Z2Z_MAX_M];
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) T[j] = -1;
+    if (lane < limit && known) {
+      if (k < V) {
+        T[0] = k;
+      } else {
+        const int32_t* row = ent_tokens + (size_t)(k - V) * M;
+#pragma unroll
+        for (int j = 0; j < Z2Z_MAX_M; ++j)
+          if (j < len) T[j] = load_fresh(&row[j]);
+      }
+    }
+    // the entry caused by the next lane's code: this lane's tokens + that code's first token
+    const bool s_ins = __shfl_down((int)ins, 1) != 0 && lane < kWave - 1;
+    const int s_idx = __shfl_down(idx, 1);
+    const int32_t s_first = __shfl_down(first, 1);
+    if (s_ins) {
+      int32_t* row = ent_tokens + (size_t)s_idx * M;
+#pragma unroll
+      for (int j = 0; j < Z2Z_MAX_M; ++j)
+        if (j < M) row[j] = j < len ? T[j] : (j == len ? s_first : -1);
+      ent_len[s_idx] = len + 1;
+    }
+    if (valid && out != nullptr) {
+      int32_t* dst = out + n_out + incl - len;
+#pragma unroll
+      for (int j = 0; j < Z2Z_MAX_M; ++j)
+        if (j < len) dst[j] = T[j];
+    }
+    C += __popcll(__ballot(ins));
+    if (limit >= 2) {
+      const int last = limit - 1;
+      prev = __builtin_amdgcn_readlane(k, last);
+      prev_len = __builtin_amdgcn_readlane(len, last);
+      n_out += __builtin_amdgcn_readlane(incl, last);
+      cpos += last;
+    } else {
+      stop = true;                    // only reached when the first code of the round does not fit
+    }
+    __syncthreads();                  // rows written above are in memory before a later round reads them
+  }
+
+  table_close<LDS>(a, lane, t);
+  if (lane == 0) {
+    st.size[b] = C;
+    st.prev_code[b] = prev;
+    st.prev_len[b] = prev_len;
+    a.out_n[b] = n_out;
+    a.status[b] = status;
+  }
+}
+
 // Empty every codebook.  grid = B, block = 256.
 __global__ void lzw_reset_kernel(LzwState st) {
   const int b = blockIdx.x;
@@ -616,7 +845,7 @@ __global__ void lzw_clear_entries_kernel(LzwState st) {
 void plan(const z2z_ctx* c, int32_t stride, int32_t flags, bool decode, bool* lds, LzwArgs* a, size_t* smem) {
   const size_t slot_bytes = (size_t)c->st.nslots * sizeof(u64);
   const size_t ef_bytes = (size_t)c->st.cap * sizeof(uint32_t);
-  const size_t limit = (size_t)c->lds_limit;
+  const size_t limit = (size_t)c->lds_limit - kEncStaticLds;
   // a short append (a decode step) touches a handful of slots: probing global memory directly is
   // cheaper than staging the table
   const bool tiny_append = !(flags & Z2Z_RESET) && stride <= 64;
@@ -680,7 +909,12 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
   bool lds = false;
   plan(c, stride, flags, true, &lds, &a, &smem);
   if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-  if (lds)
+  const bool serial = stride <= 8 || c->opt_lzw_kernel == 3;
+  if (serial && lds)
+    hipLaunchKernelGGL(lzw_decode_serial_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
+  else if (serial)
+    hipLaunchKernelGGL(lzw_decode_serial_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
+  else if (lds)
     hipLaunchKernelGGL(lzw_decode_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
   else
     hipLaunchKernelGGL(lzw_decode_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
@@ -714,6 +948,8 @@ int z2z_lzw_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_serial_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   return Z2Z_OK;
 }

@@ -67,6 +67,15 @@ def test_global_table_variant_bit_exact(name):
     _check_encode_decode(cfg, tokens, wl.make_lens(cfg), lzw_kernel=2)
 
 
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_serial_decoder_variant_bit_exact(name):
+    """The one-code-at-a-time decoder (the one short appended calls take), forced on long streams."""
+    cfg = wl.scaled(wl.CONFIGS[name], B=3, N=3000)
+    tokens = wl.make_tokens(cfg)
+    print(f"[case] lzw serial-decoder variant {name}", flush=True)
+    _check_encode_decode(cfg, tokens, wl.make_lens(cfg), lzw_kernel=3)
+
+
 def test_ragged_and_degenerate_lengths():
     cfg = wl.scaled(wl.CONFIGS["c1"], B=8, N=777)
     tokens = wl.make_tokens(cfg)
@@ -114,7 +123,8 @@ def test_bad_token_and_short_output():
     ctx.close()
 
 
-def test_decoder_error_paths():
+@pytest.mark.parametrize("width", [8, 100])      # 8: the one-code-at-a-time kernel, 100: the round kernel
+def test_decoder_error_paths(width):
     from paper_2506_01084_amd import api
 
     V, M, cap = 3, 3, 32
@@ -127,7 +137,7 @@ def test_decoder_error_paths():
         [2, 2, 2, 2],           # valid
     ]
     n = np.array([len(s) for s in streams], dtype=np.int32)
-    codes = np.zeros((B, 8), dtype=np.int32)
+    codes = np.zeros((B, width), dtype=np.int32)
     for b, s in enumerate(streams):
         codes[b, : len(s)] = s
     ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
@@ -143,6 +153,91 @@ def test_decoder_error_paths():
     for b, s in enumerate(streams):
         rt, _, rst = oracle.lzw_decode(s, V, M, cap, max_tokens=3)
         assert int(st[b]) == rst and int(n_tok[b]) == len(rt) and toks[b, : len(rt)].tolist() == rt
+    ctx.close()
+
+
+def _model_like_stream(rng, V, M, cap, n, p_fresh=0.05, p_entry=0.5):
+    """Codes a model might emit: any base token or existing entry, now and then the not-yet-defined
+    code; not what a greedy parse would produce (edges repeat, entries go unused)."""
+    s = oracle.LZWStream(V, M, cap)
+    codes = []
+    for _ in range(n):
+        C = len(s.entries)
+        u = rng.random()
+        if u < p_fresh and s.prev is not None:
+            k = V + C                     # may or may not be acceptable: the oracle decides
+        elif u < p_fresh + p_entry and C > 0:
+            # recent entries more often than old ones: names entries made a few codes ago
+            k = V + (C - 1 - int(rng.integers(0, min(C, 6))) if rng.random() < 0.5 else int(rng.integers(0, C)))
+        else:
+            k = int(rng.integers(0, V))
+        _, st = s.decode_chunk([k])
+        if st != 0:
+            continue                      # keep the stream valid; error streams are built separately
+        codes.append(k)
+    return codes
+
+
+@pytest.mark.parametrize("V,M,cap,lzw_kernel", [(3, 3, 40, 0), (6, 4, 300, 0), (50, 5, 2000, 0), (4, 2, 1000, 0),
+                                                (6, 4, 300, 2), (2, 8, 500, 0)])
+def test_decoder_on_streams_no_greedy_parse_produces(V, M, cap, lzw_kernel):
+    """Repeated edges inside a round, codes naming entries a few codes old, the not-yet-defined code,
+    then a bad code in the middle and a short output row: all against the oracle's decoder."""
+    from paper_2506_01084_amd import api
+
+    rng = np.random.default_rng(1000 * V + M)
+    B, n = 6, 700
+    streams = [_model_like_stream(rng, V, M, cap, n - 37 * b) for b in range(B)]
+    streams[4] = streams[4][:300] + [V + cap + 5] + streams[4][300:]          # names nothing
+    streams[5] = streams[5][:129] + [-1] + streams[5][129:]
+    width = max(len(s) for s in streams)
+    codes = np.zeros((B, width), dtype=np.int32)
+    for b, s in enumerate(streams):
+        codes[b, : len(s)] = s
+    n_codes = np.array([len(s) for s in streams], dtype=np.int32)
+    print(f"[case] model-like streams V={V} M={M} cap={cap} kernel={lzw_kernel}", flush=True)
+    for out_stride in (width * M, 333):
+        ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+        ctx.set_option(api.OPT_LZW_KERNEL, lzw_kernel)
+        toks, n_tok, st = gpu_decode(ctx, codes, n_codes, out_stride=out_stride)
+        refs = [oracle.lzw_decode(s, V, M, cap, max_tokens=out_stride) for s in streams]
+        for b, (rt, _, rst) in enumerate(refs):
+            assert int(st[b]) == rst, (b, int(st[b]), rst)
+            assert int(n_tok[b]) == len(rt), (b, int(n_tok[b]), len(rt))
+            assert toks[b, : len(rt)].tolist() == rt, f"seq {b} tokens"
+        assert_codebook_equal(ctx, [r[1] for r in refs], M, cap)
+        ctx.close()
+    assert refs[4][2] & api.ST_BAD_CODE or refs[4][2] & api.ST_OVERFLOW
+
+
+def test_chunked_append_decode_matches_stream_oracle():
+    """Append-mode decode in chunks of mixed sizes (both decoder kernels), with and without a token output."""
+    from paper_2506_01084_amd import api
+
+    V, M, cap = 7, 4, 400
+    B = 3
+    rng = np.random.default_rng(77)
+    streams = [_model_like_stream(rng, V, M, cap, 900) for _ in range(B)]
+    n = min(len(s) for s in streams)
+    codes = np.array([s[:n] for s in streams], dtype=np.int32)
+    ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    ref = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    pos, first = 0, True
+    while pos < n:
+        step = int(rng.choice([1, 5, 9, 63, 64, 200]))
+        chunk = np.ascontiguousarray(codes[:, pos:pos + step])
+        with_out = bool(rng.integers(0, 2))
+        toks, n_tok, st = gpu_decode(ctx, chunk, None, out_stride=chunk.shape[1] * M if with_out else 0,
+                                     flags=api.RESET if first else api.APPEND)
+        for b in range(B):
+            rt, rst = ref[b].decode_chunk(chunk[b].tolist())
+            assert int(st[b]) == rst == 0
+            assert int(n_tok[b]) == len(rt)
+            if with_out:
+                assert toks[b, : len(rt)].tolist() == rt
+        assert_codebook_equal(ctx, [list(r.entries) for r in ref], M, cap)
+        pos += step
+        first = False
     ctx.close()
 
 
