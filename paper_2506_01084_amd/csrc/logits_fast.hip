@@ -2,11 +2,11 @@
 //
 // Workgroup tile 256 (vocabulary rows, MFMA "A") x 256 (hidden rows, MFMA "B"), 4 waves in a 2 x 2 grid,
 // each wave 128 x 128 = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 accumulator registers per lane):
-// per 16-deep k-step a wave reads 8 operand fragments from LDS for 16 MFMAs, which keeps the LDS read
-// port at about half of its 128 B/clk (a 128 x 64 wave tile needs three quarters of it and starves the
-// matrix cores).  With one wave per SIMD all overlap is inside the instruction stream: the fragments of
-// k-step t+1 are read while the MFMAs of k-step t run, and the global->LDS requests of slab s+2 are issued
-// as soon as slab s has been read.
+// per 16-deep k-step a wave reads 8 operand fragments from LDS for 16 MFMAs.  With one wave per SIMD all
+// overlap is inside the instruction stream: the fragments of k-step t+1 are read while the MFMAs of
+// k-step t run, and the global->LDS requests of slab s+2 are handed out one pair at a time between the
+// MFMAs that follow the hand-over of slab s.  (F_WAVES = 8 builds the same kernel with two waves per SIMD,
+// each 128 x 64; measured equal, so the default stays at the layout with the larger register tiles.)
 //
 // K advances in slabs of 64 elements (128 bytes per row, four k-steps): the global -> LDS stream moves
 // whole 128-byte lines, which it does markedly faster than half lines (measured on a bare streaming
@@ -14,7 +14,11 @@
 // from global memory into LDS (16-byte global_load ... lds), two stages.  Once per slab, in the middle of
 // its last k-step, the waves meet at a barrier: at that point everybody has read the slab completely (its
 // stage is refilled with slab s+2) and slab s+1 has landed (its first fragments are read next).  The stream
-// runs on across the vocabulary tiles of a strip.
+// runs on across the vocabulary tiles of a strip.  The refill requests are spread over the following
+// ~35 MFMAs: issued as one burst they back up the memory pipeline, the wave then stalls on its next
+// request, and a stalled wave issues no MFMAs (measured: 28.9 ms as a burst, 26.3 ms spread, 22.9 ms with
+// no requests at all on the 32768 x 4096 x 128256 problem); spread over the whole slab they would land
+// too late for the next hand-over.
 //
 // LDS layout of an operand tile: row r = 128 bytes = 8 chunks of 16 B; chunk c is stored at position
 // c ^ ((r >> 1) & 7).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a
@@ -36,18 +40,41 @@ constexpr int F_OPER = FT * F_SLAB;       // one operand tile of one slab: 32 Ki
 constexpr int F_STAGE = 2 * F_OPER;       // A + B
 constexpr int F_NSTAGE = 2;
 constexpr int F_LDS = F_NSTAGE * F_STAGE; // 128 KiB
-constexpr int F_THREADS = 256;
+#ifndef F_WAVES
+#define F_WAVES 4
+#endif
+constexpr int F_THREADS = 64 * F_WAVES;
+// waves: 2 along the vocabulary rows (128 each: 4 MFMA blocks), F_WAVES / 2 along the hidden rows
+constexpr int F_NI = 4;
+constexpr int F_WR = F_WAVES / 2;
+constexpr int F_NJ = FT / (F_WR * 32);                 // MFMA blocks of a wave along the hidden rows
+constexpr int F_KSTEP = F_NI * F_NJ;                   // MFMAs of a wave per k-step
+constexpr int F_PAIRS = 32 / F_WAVES;                  // request pairs (8 rows of A + 8 rows of B) per wave and slab
+#ifndef F_SPREAD
+#define F_SPREAD (F_WAVES == 4 ? 5 : 4)
+#endif
+// Request pair i goes out after the MFMA with window index 1 + i * F_SPREAD, counted from the slab
+// hand-over: first the rest of the hand-over k-step (F_KSTEP - F_NJ MFMAs), then the first three k-steps
+// of the next slab.
+constexpr int F_REST = F_KSTEP - F_NJ;
+constexpr int F_LAST_IN_HANDOVER = (F_REST - 2) / F_SPREAD;          // last pair issued before the slab ends
+static_assert(F_LAST_IN_HANDOVER < F_PAIRS, "spread too small for this layout");
+static_assert(1 + (F_PAIRS - 1) * F_SPREAD < F_REST + 3 * F_KSTEP, "all pairs must be out before the next hand-over");
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
 
 // 16 bytes per lane, global -> LDS without passing through registers: address = 64-bit scalar base +
 // 32-bit per-lane offset; the LDS address is the wave-uniform byte offset in M0 plus 16 * lane.  Inline
 // assembly on purpose: the compiler cannot tell the LDS stages apart and would make every LDS read wait
 // for all outstanding direct loads.  Completion is awaited explicitly (s_waitcnt vmcnt) before the
 // barrier that publishes a stage.  One wait state is required between the write of M0 and its use.
-__device__ __forceinline__ void load16_to_lds(const unsigned char* base, uint32_t lane_offset, uint32_t lds_byte_offset) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+// M0 is written as stage base + constant in one scalar instruction: with one wave per SIMD every
+// instruction issued between two MFMAs counts, and the request stream is the bulk of them.
+template <int LDS_IMM>
+__device__ __forceinline__ void load16_to_lds(const unsigned char* base, uint32_t lane_offset, uint32_t lds_stage_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(lane_offset), "s"(base), "s"(lds_byte_offset)
-               : "memory");   // M0 is reserved: the compiler keeps nothing in it across statements
+               : "v"(lane_offset), "s"(base), "s"(lds_stage_base), "n"(LDS_IMM)
+               : "memory", "scc");   // M0 is reserved: the compiler keeps nothing in it across statements
 }
 
 __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
@@ -73,8 +100,8 @@ __device__ __forceinline__ bool map_base(const LogitsArgs& a, int bid, int* rt, 
 }
 
 struct Frags {
-  uint4 a[4];
-  uint4 b[4];
+  uint4 a[F_NI];
+  uint4 b[F_NJ];
 };
 
 template <int HYPER>
@@ -84,7 +111,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wv = wave & 1;    // which 128 vocabulary rows of the tile
-  const int wr = wave >> 1;   // which 128 hidden rows of the tile
+  const int wr = wave >> 1;   // which F_NJ * 32 hidden rows of the tile
 
   int rt, st;
   int r0, r_end, n_valid;
@@ -111,103 +138,134 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   const int n_tiles = vt_end - vt0;          // vocabulary tiles this workgroup sweeps (may be <= 0)
   const int n_slabs = (int)(row_bytes / F_SLAB);
 
-  Triple run[4];
+  Triple run[F_NJ];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) run[j] = empty_triple();
+  for (int j = 0; j < F_NJ; ++j) run[j] = empty_triple();
 
   // ---- loader: lane l of wave w, instruction i moves the chunk that lands at LDS byte
-  //      ((w * 8 + i) * 8 + (l >> 3)) * 128 + (l & 7) * 16 of the operand tile; offsets are relative to
+  //      ((w * F_PAIRS + i) * 8 + (l >> 3)) * 128 + (l & 7) * 16 of the operand tile; offsets are relative to
   //      the first row of the tile, rows past the last valid one are clamped onto it ------------------
   const uint32_t lds_base = lds_offset_of(lds);
   const int ld_row = lane >> 3;                                  // row inside the 8-row group
   const int limB = r_end - 1 - r0;                               // last valid hidden row of the tile
   const unsigned char* Wtile = Wp;
   int limA = 0;                                                  // last valid vocabulary row of the tile
+  // per-lane global byte offsets of the 8 row groups a wave requests (swizzled chunk folded in); rows
+  // past the last valid one are clamped onto it.  B's never change, A's change with the tile.
+  auto row_offset = [&](int i, int lim) -> uint32_t {
+    const int row = (wave * F_PAIRS + i) * 8 + ld_row;
+    const int chunk16 = ((lane & 7) ^ ((row >> 1) & 7)) * 16;
+    return (uint32_t)(min(row, lim) * (int)row_bytes + chunk16);
+  };
+  uint32_t voffA[F_PAIRS], voffB[F_PAIRS];
+#pragma unroll
+  for (int i = 0; i < F_PAIRS; ++i) voffB[i] = row_offset(i, limB);
   auto set_tile = [&](int vt) {
     Wtile = Wp + (size_t)vt * FT * row_bytes;
     limA = n_valid - 1 - vt * FT;
+#pragma unroll
+    for (int i = 0; i < F_PAIRS; ++i) voffA[i] = row_offset(i, limA);
   };
-  // request the slab that follows (lslab, lvt) in the stream, if any, and advance the cursor; the
-  // per-lane offsets are recomputed each time (a few VALU operations) rather than kept in registers.
-  // A request is 16 instructions per wave; issue_rows(i) issues the pair for row group i so that the
-  // caller can place the pairs between MFMAs.
+  // request the slab that follows (lslab, lvt) in the stream, if any, and advance the cursor.  A request
+  // is 16 instructions per wave; issue_rows<i>() issues the pair for row group i so that the caller can
+  // place the pairs between MFMAs.
   int lslab = 0, lvt = vt0;
-  uint32_t isA = 0, isB = 0;                 // LDS destinations of the slab being requested
+  uint32_t isA = 0;                          // LDS destination (operand A) of the slab being requested
   const unsigned char* is_ga = Wp;
   const unsigned char* is_gb = Hp;
-  bool is_on = false;
   auto issue_begin = [&](int stage) {
-    is_on = lvt < vt_end;
-    isA = lds_base + stage * F_STAGE + wave * 8192;
-    isB = isA + F_OPER;
-    is_ga = Wtile + (size_t)lslab * F_SLAB;
-    is_gb = Hp + (size_t)lslab * F_SLAB;
-  };
-  auto issue_rows = [&](int i) {
-    if (is_on) {
-      const int row = (wave * 8 + i) * 8 + ld_row;
-      const int chunk16 = ((lane & 7) ^ ((row >> 1) & 7)) * 16;
-      load16_to_lds(is_ga, (uint32_t)(min(row, limA) * (int)row_bytes + chunk16), isA + i * 1024);
-      load16_to_lds(is_gb, (uint32_t)(min(row, limB) * (int)row_bytes + chunk16), isB + i * 1024);
+    isA = lds_base + stage * F_STAGE + wave * (F_PAIRS * 1024);
+    if (lvt < vt_end) {                      // else: keep the last valid source
+      is_ga = Wtile + (size_t)lslab * F_SLAB;
+      is_gb = Hp + (size_t)lslab * F_SLAB;
     }
   };
+#define Z2Z_ISSUE_PAIR(i)                                             \
+  do {                                                                \
+    load16_to_lds<(i) * 1024>(is_ga, voffA[i], isA);                  \
+    load16_to_lds<F_OPER + (i) * 1024>(is_gb, voffB[i], isA);         \
+  } while (0)
   auto issue_end = [&]() {
-    if (is_on && ++lslab == n_slabs) {
+    if (lvt < vt_end && ++lslab == n_slabs) {
       lslab = 0;
       ++lvt;
       if (lvt < vt_end) set_tile(lvt);
     }
   };
-  auto issue_next = [&](int stage) {
-    issue_begin(stage);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) issue_rows(i);
-    issue_end();
-  };
-
   // ---- MFMA operand addresses (bytes inside an operand tile), swizzle folded in ---------------------
   const int sw = (lane >> 1) & 7;   // ((row >> 1) & 7) of every row this lane reads
   const int half = lane >> 5;
   const int offA0 = (wv * 128 + (lane & 31)) * F_SLAB;
-  const int offB0 = (wr * 128 + (lane & 31)) * F_SLAB;
+  const int offB0 = (wr * (F_NJ * 32) + (lane & 31)) * F_SLAB;
   auto read_frags = [&](Frags& f, int stage, int q) {
     const unsigned char* A = lds + stage * F_STAGE + offA0 + (((2 * q + half) ^ sw) << 4);
     const unsigned char* Bt = lds + stage * F_STAGE + F_OPER + offB0 + (((2 * q + half) ^ sw) << 4);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const uint4*>(A + i * 32 * F_SLAB);
+    for (int i = 0; i < F_NI; ++i) f.a[i] = *reinterpret_cast<const uint4*>(A + i * 32 * F_SLAB);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const uint4*>(Bt + j * 32 * F_SLAB);
+    for (int j = 0; j < F_NJ; ++j) f.b[j] = *reinterpret_cast<const uint4*>(Bt + j * 32 * F_SLAB);
   };
 
-  f32x16 acc[4][4];
+  f32x16 acc[F_NI][F_NJ];
   auto zero_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < F_NI; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < F_NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   };
-  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi) {
+  // pair i of the request in progress (switch: the LDS offset is an instruction literal)
+  auto issue_pair = [&](int i) {
+    switch (i) {
+      case 0: Z2Z_ISSUE_PAIR(0); break;
+      case 1: Z2Z_ISSUE_PAIR(1); break;
+      case 2: Z2Z_ISSUE_PAIR(2); break;
+#if F_WAVES == 4
+      case 3: Z2Z_ISSUE_PAIR(3); break;
+      case 4: Z2Z_ISSUE_PAIR(4); break;
+      case 5: Z2Z_ISSUE_PAIR(5); break;
+      case 6: Z2Z_ISSUE_PAIR(6); break;
+      default: Z2Z_ISSUE_PAIR(7); break;
+#else
+      default: Z2Z_ISSUE_PAIR(3); break;
+#endif
+    }
+  };
+  // The MFMAs of blocks [i_lo, i_hi) x [0, F_NJ); w0 = window index of the first one.  After an MFMA
+  // whose window index is 1 + i * F_SPREAD, request pair i is issued (fenced, so that it stays there: a
+  // burst of requests backs up the memory pipeline, and a wave that cannot issue its request cannot issue
+  // MFMAs either).
+  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi, int w0) {
 #pragma unroll
     for (int i = i_lo; i < i_hi; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < F_NJ; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
                                                             __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
+        const int w = w0 + (i - i_lo) * F_NJ + j;
+        if (w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_pair((w - 1) / F_SPREAD);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
   };
 
   if (n_tiles > 0) {
     zero_acc();
     set_tile(vt0);
-    const int total = n_tiles * n_slabs;
-    // prologue: slabs 0 and 1 requested, slab 0 landed and visible, its first fragments on the way
-    issue_next(0);
-    issue_next(1);
-    if (total >= 2)
-      __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): all but the youngest slab (16 requests per wave)
-    else
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    // prologue: slab 0 requested in full, of slab 1 the pairs that a hand-over k-step issues (the rest
+    // follows during the first three k-steps, as for every later slab); slab 0 landed and visible, its
+    // first fragments on the way
+    issue_begin(0);
+#pragma unroll
+    for (int i = 0; i < F_PAIRS; ++i) issue_pair(i);
+    issue_end();
+    issue_begin(1);
+#pragma unroll
+    for (int i = 0; i <= F_LAST_IN_HANDOVER; ++i) issue_pair(i);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (F_LAST_IN_HANDOVER + 1)));   // all of slab 0
     __syncthreads();
     Frags f0, f1;
     read_frags(f0, 0, 0);
@@ -216,68 +274,52 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       for (int slab = 0; slab < n_slabs; ++slab, ++g) {
         const int stage = g & 1;
         read_frags(f1, stage, 1);
-        mfma_rows(f0, 0, 4);
+        mfma_rows(f0, 0, F_NI, F_REST);
         read_frags(f0, stage, 2);
-        mfma_rows(f1, 0, 4);
+        mfma_rows(f1, 0, F_NI, F_REST + F_KSTEP);
         read_frags(f1, stage, 3);
-        mfma_rows(f0, 0, 4);
-        // last k-step: a quarter of its MFMAs, then the slab hand-over; the 16 requests for slab g+2
-        // are then issued between the remaining MFMAs (a burst of them would leave the matrix cores
-        // idle for as long as it takes to issue)
-        mfma_rows(f1, 0, 1);
-        const bool more = g + 1 < total;
-        if (more) {
-          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): slab g+1 (the only one in flight) has landed
-          __syncthreads();                      // slab g+1 visible to all; everyone has read slab g
-          read_frags(f0, stage ^ 1, 0);
-          issue_begin(stage);                   // refill this stage with slab g+2
-        } else {
-          is_on = false;
-        }
-#pragma unroll
-        for (int i = 1; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1.a[i]),
-                                                                __builtin_bit_cast(bf16x8, f1.b[j]), acc[i][j], 0, 0, 0);
-            if (((i - 1) * 4 + j) % 3 == 2 || (i == 3 && j == 3)) {
-              __builtin_amdgcn_sched_barrier(0);
-              const int grp = ((i - 1) * 4 + j) / 3;          // 0..3 -> row groups 2*grp, 2*grp+1
-              issue_rows(2 * grp);
-              issue_rows(2 * grp + 1);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
-        if (more) issue_end();
+        mfma_rows(f0, 0, F_NI, F_REST + 2 * F_KSTEP);
+        issue_end();                            // the request for slab g+1 is out in full
+        // last k-step: a quarter of its MFMAs, then the slab hand-over.  It is the same for every slab,
+        // the last ones included (no test inside the loop): past the end of the stream the requests
+        // re-read the last slab into a stage nobody reads again.
+        mfma_rows(f1, 0, 1, 1000);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // slab g+1 (the only one in flight) has landed
+        __syncthreads();                            // slab g+1 visible to all; everyone has read slab g
+        read_frags(f0, stage ^ 1, 0);
+        issue_begin(stage);                         // refill this stage with slab g+2
+        mfma_rows(f1, 1, F_NI, 0);
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
       const int v0 = vt * FT;
-      fold_tile<4, 4>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
+      fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
       zero_acc();
     }
   }
 
   // ---- end of strip: lanes l and l+32 hold the same hidden row; then the two vocabulary halves ------
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < F_NJ; ++j) {
     Triple o;
     o.m = __shfl_xor(run[j].m, 32);
     o.s = __shfl_xor(run[j].s, 32);
     o.i = __shfl_xor(run[j].i, 32);
     merge_triple(run[j], o);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the requests past the end of the stream too
   __syncthreads();                                 // every wave is done with the operand stages
-  Triple* xch = reinterpret_cast<Triple*>(lds);    // [2 row halves][128 rows]
+  Triple* xch = reinterpret_cast<Triple*>(lds);    // [256 hidden rows of the tile]
+  const int hrow0 = wr * (F_NJ * 32);
   if (wv == 1 && lane < 32) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) xch[wr * 128 + j * 32 + lane] = run[j];
+    for (int j = 0; j < F_NJ; ++j) xch[hrow0 + j * 32 + lane] = run[j];
   }
   __syncthreads();
   if (wv == 0 && lane < 32) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      merge_triple(run[j], xch[wr * 128 + j * 32 + lane]);
-      const int hrow = r0 + wr * 128 + j * 32 + lane;
+    for (int j = 0; j < F_NJ; ++j) {
+      merge_triple(run[j], xch[hrow0 + j * 32 + lane]);
+      const int hrow = r0 + hrow0 + j * 32 + lane;
       if (hrow < r_end) {
         const size_t p = (size_t)hrow * a.n_parts + a.part0 + st;
         a.part_m[p] = run[j].m;
