@@ -275,9 +275,7 @@ __device__ __forceinline__ int first_repeat(u64* filter, int lane, bool cand, bo
 }
 
 template <bool LDS>
-__global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
-  __shared__ int32_t tokbuf[kTokBuf];         // token classes: >= 0 valid ID, -2 out of range
-  __shared__ u64 filter[kFilter];
+__device__ __forceinline__ void lzw_encode_rounds(const LzwArgs& a, int32_t* tokbuf, u64* filter) {
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
@@ -436,6 +434,26 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
+}
+
+// Number of elements of sequence b in this call.
+__device__ __forceinline__ int call_length(const LzwArgs& a, int b) {
+  return a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
+}
+
+// A short appended call touches a handful of slots: probing the table where it lives, in global memory,
+// is cheaper than staging all of it in LDS and writing it back (the length is known only on the device,
+// so the LDS kernels take this decision per sequence).
+constexpr int kShortAppend = 64;
+
+template <bool LDS>
+__global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
+  __shared__ int32_t tokbuf[kTokBuf];         // token classes: >= 0 valid ID, -2 out of range
+  __shared__ u64 filter[kFilter];
+  if (LDS && !(a.flags & Z2Z_RESET) && call_length(a, blockIdx.x) <= kShortAppend)
+    lzw_encode_rounds<false>(a, tokbuf, filter);
+  else
+    lzw_encode_rounds<LDS>(a, tokbuf, filter);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -618,9 +636,7 @@ __device__ __forceinline__ int32_t load_fresh(const int32_t* p) {
 //   4. the lanes before the cut insert their edges, lane i-1 writes the flattened row of the entry that
 //      code i caused (its own tokens + that first token), and every lane writes its tokens.
 template <bool LDS>
-__global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
-  __shared__ int32_t codebuf[kTokBuf];
-  __shared__ u64 filter[kFilter];
+__device__ __forceinline__ void lzw_decode_rounds(const LzwArgs& a, int32_t* codebuf, u64* filter) {
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
@@ -815,6 +831,16 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
+}
+
+template <bool LDS>
+__global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
+  __shared__ int32_t codebuf[kTokBuf];
+  __shared__ u64 filter[kFilter];
+  if (LDS && !(a.flags & Z2Z_RESET) && call_length(a, blockIdx.x) <= kShortAppend)
+    lzw_decode_rounds<false>(a, codebuf, filter);
+  else
+    lzw_decode_rounds<LDS>(a, codebuf, filter);
 }
 
 // Empty every codebook.  grid = B, block = 256.
