@@ -10,37 +10,62 @@ namespace {
 
 using namespace z2z_logits;
 
-// One wave per hidden row: lanes take the row's partial triples round-robin (contiguous in memory),
-// then merge across lanes; merge_triple keeps the lowest column among equal maxima, so the order of the
-// merges does not matter.
+// ROW_THREADS (64 or 256) threads per hidden row: they take the row's partial triples round-robin
+// (contiguous in memory), merge across lanes, then across the waves of the row; merge_triple keeps the
+// lowest column among equal maxima, so the order of the merges does not matter.  A block is 256 threads:
+// four rows with a wave each (few parts per row: prefill), or one row (a thousand parts: decode steps).
+template <int ROW_THREADS>
 __global__ void __launch_bounds__(256) logits_combine_kernel(const float* part_m, const float* part_s,
                                                              const int32_t* part_i, int n_parts, int rows,
                                                              int32_t* argmax, float* mx, float* lse) {
+  constexpr int ROWS_PER_BLOCK = 256 / ROW_THREADS;
   const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= rows) return;
-  Triple t = empty_triple();
-  const size_t base = (size_t)r * n_parts;
-  for (int p = lane; p < n_parts; p += 64) {
-    Triple o;
-    o.m = part_m[base + p];
-    o.s = part_s[base + p];
-    o.i = part_i[base + p];
-    merge_triple(t, o);
+  const int t = threadIdx.x % ROW_THREADS;
+  const int r = blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / ROW_THREADS;
+  Triple tr = empty_triple();
+  if (r < rows) {
+    const size_t base = (size_t)r * n_parts;
+    for (int p = t; p < n_parts; p += ROW_THREADS) {
+      Triple o;
+      o.m = part_m[base + p];
+      o.s = part_s[base + p];
+      o.i = part_i[base + p];
+      merge_triple(tr, o);
+    }
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     Triple o;
-    o.m = __shfl_xor(t.m, off);
-    o.s = __shfl_xor(t.s, off);
-    o.i = __shfl_xor(t.i, off);
-    merge_triple(t, o);
+    o.m = __shfl_xor(tr.m, off);
+    o.s = __shfl_xor(tr.s, off);
+    o.i = __shfl_xor(tr.i, off);
+    merge_triple(tr, o);
   }
-  if (lane == 0) {
-    if (argmax) argmax[r] = t.i;
-    if (mx) mx[r] = t.m;
-    if (lse) lse[r] = t.m + logf(t.s);
+  if (ROW_THREADS > 64) {
+    __shared__ Triple xch[4];
+    if (lane == 0) xch[threadIdx.x >> 6] = tr;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int w = 1; w < 4; ++w) merge_triple(tr, xch[w]);
+    }
   }
+  if (t == 0 && r < rows) {
+    if (argmax) argmax[r] = tr.i;
+    if (mx) mx[r] = tr.m;
+    if (lse) lse[r] = tr.m + logf(tr.s);
+  }
+}
+
+int launch_combine(const z2z_ctx* c, int n_parts, int rows, int32_t* argmax, float* mx, float* lse, hipStream_t s) {
+  if (n_parts > 256)
+    hipLaunchKernelGGL(logits_combine_kernel<256>, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_i,
+                       n_parts, rows, argmax, mx, lse);
+  else
+    hipLaunchKernelGGL(logits_combine_kernel<64>, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
+                       c->part_i, n_parts, rows, argmax, mx, lse);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
 }
 
 // Full-logits output only: unused hyper slots read -inf.
@@ -123,10 +148,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     if (rc != Z2Z_OK) return rc;
     rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, s);
     if (rc != Z2Z_OK) return rc;
-    hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
-                       c->part_i, n_parts, rows, argmax, mx, lse);
-    Z2Z_HIP_TRY(hipGetLastError());
-    return Z2Z_OK;
+    return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
   }
 
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
@@ -170,8 +192,5 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
       Z2Z_HIP_TRY(hipGetLastError());
     }
   }
-  hipLaunchKernelGGL(logits_combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
-                     c->part_i, n_parts, rows, argmax, mx, lse);
-  Z2Z_HIP_TRY(hipGetLastError());
-  return Z2Z_OK;
+  return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
 }

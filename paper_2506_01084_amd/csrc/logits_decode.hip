@@ -262,13 +262,15 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
 
 __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int n_base = a.n_base_units * a.n_groups;
+  // the hyper units come first: they read twice as many weight rows as a base unit, and the workgroups
+  // that finish last should be the short ones
+  const int n_hyper = a.B * a.units_per_seq;
   const int bid = blockIdx.x;
-  if (bid < n_base) {
-    base_unit(a, bid % a.n_base_units, bid / a.n_base_units, lds);
+  if (bid < n_hyper) {
+    hyper_unit(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
-    const int hu = bid - n_base;
-    hyper_unit(a, hu / a.units_per_seq, hu % a.units_per_seq, lds);
+    const int bu = bid - n_hyper;
+    base_unit(a, bu % a.n_base_units, bu / a.n_base_units, lds);
   }
 }
 
