@@ -320,3 +320,49 @@ def test_full_size_decode_step_c3():
         errs = check_logits_rows(r, am_h[b:b + 1], mx_h[b:b + 1], lse_h[b:b + 1], None)
         print(f"  seq {b}: C={len(streams[b].entries)} errors {errs}  {time.time() - t0:.1f}s", flush=True)
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# the one-row-per-sequence kernel at awkward shapes: more than one group of 64 rows, a ragged last group,
+# vocabularies and capacities that are no multiple of a unit, empty and unequal codebooks, every row checked
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,N,V,d,M,cap", [
+    (65, 300, 1000, 3072, 3, 300),      # two row groups, the second with one row
+    (3, 200, 777, 128, 4, 0),           # no codebook at all
+    (130, 400, 513, 3584, 5, 1030),     # three groups; cap spans three hyper units, the last ragged
+    (1, 5000, 50000, 256, 2, 600),      # one row
+    (64, 64, 300, 4096, 3, 512),        # widest d the kernel takes
+])
+def test_decode_kernel_small_shapes_every_row(B, N, V, d, M, cap):
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=B * 1000 + V)
+    print(f"[case] decode kernel B={B} N={N} V={V} d={d} M={M} cap={cap}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    if B > 2:
+        lens[1] = 0                     # an empty codebook next to full ones
+        lens[2] = min(N, 7)
+    E = wl.make_embeddings(cfg)
+    H = wl.make_hidden(cfg, B)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens, lens)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    d_H = torch_storage(H, cfg["dtype"])
+    am = torch.empty(B, dtype=torch.int32, device="cuda")
+    mx = torch.empty(B, dtype=torch.float32, device="cuda")
+    lse = torch.empty(B, dtype=torch.float32, device="cuda")
+    outs = {}
+    for kern in (0, 1):                 # 0: the decode kernel; 1: the general tile kernel on the same call
+        ctx.set_option(api.OPT_DECODE_KERNEL, kern)
+        ctx.extended_logits(d_H, 1, d_E, d_W, am, mx, lse, None)
+        torch.cuda.synchronize()
+        outs[kern] = (am.cpu().numpy().copy(), mx.cpu().numpy().copy(), lse.cpu().numpy().copy())
+    for b in range(B):
+        Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
+        r = oracle.extended_logits(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"], return_logits=True)
+        for kern in (0, 1):
+            a_, m_, l_ = outs[kern]
+            check_logits_rows(r, a_[b:b + 1], m_[b:b + 1], l_[b:b + 1], None)
+    ctx.close()
