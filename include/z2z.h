@@ -115,10 +115,15 @@ int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entr
  * in the divisor.  fp32 accumulation in token order, one round-to-nearest-even to the storage type.
  *   d_E       [V, d]       dtype of the context
  *   d_W_hyper [B, cap, d]  same dtype, out.  This buffer is the hyper-embedding cache.
- *   d_first   [B] int32 or NULL.  NULL: embed entries [0, C_b) and zero rows [C_b, cap).
- *             Otherwise embed only entries [d_first[b], C_b) and leave all other rows untouched.
- *   max_new   upper bound the caller expects for C_b - d_first[b] (sizes the launch; any value
- *             >= 1 is correct, a tight one is faster); ignored when d_first is NULL.
+ *   d_first   [B] int32 or NULL, and max_new, select the rows to (re)compute:
+ *             NULL, max_new <= 0: entries [0, C_b), and rows [C_b, cap) are zeroed;
+ *             NULL, max_new >= 1: the last max_new entries [max(C_b - max_new, 0), C_b) only, all other
+ *                                 rows untouched (recomputing a row gives the same bits, so a decode loop
+ *                                 that adds at most one entry per step keeps the cache current with
+ *                                 max_new = 1 and no snapshot of the sizes);
+ *             non-NULL:           entries [d_first[b], C_b) only, all other rows untouched; max_new is
+ *                                 an upper bound the caller expects for C_b - d_first[b] (it sizes the
+ *                                 launch; any value >= 1 is correct, a tight one is faster, <= 0 = cap).
  */
 int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_t* d_first,
                     int32_t max_new, void* stream);

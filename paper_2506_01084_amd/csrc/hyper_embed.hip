@@ -18,6 +18,7 @@ struct EmbedArgs {
   const int32_t* ent_tokens;  // [B, cap, M]
   const int32_t* ent_len;     // [B, cap]
   const int32_t* first;       // [B] or nullptr
+  int32_t last_n;             // first == nullptr: 0 = all of [0, cap), n > 0 = the last n entries only
   int32_t B, V, M, cap, d;
   int32_t units_per_seq;      // waves assigned to each sequence
   int32_t pool;
@@ -93,7 +94,7 @@ __device__ __forceinline__ void embed_row(const EmbedArgs& a, const int32_t* tok
 
 // grid.x = B * units_per_seq / 4 (4 waves per block); wave u of sequence b walks entries
 // e = e0 + u, e0 + u + units_per_seq, ...  Full mode (first == nullptr) covers [0, cap): rows below C_b
-// are embedded, the others zeroed.  Incremental mode covers [first[b], C_b) only.
+// are embedded, the others zeroed.  Incremental modes cover [first[b], C_b) or the last last_n entries only.
 template <bool BF16>
 __global__ void __launch_bounds__(256) hyper_embed_kernel(EmbedArgs a) {
   const int lane = threadIdx.x & 63;
@@ -102,8 +103,8 @@ __global__ void __launch_bounds__(256) hyper_embed_kernel(EmbedArgs a) {
   const int u = (int)(unit % a.units_per_seq);
   if (b >= a.B) return;
   const int C = min(a.size[b], a.cap);
-  const bool full = a.first == nullptr;
-  const int e0 = full ? 0 : max(a.first[b], 0);
+  const bool full = a.first == nullptr && a.last_n == 0;
+  const int e0 = full ? 0 : (a.first ? max(a.first[b], 0) : max(C - a.last_n, 0));
   const int e1 = full ? a.cap : C;
   constexpr int EPC = BF16 ? 8 : 4;
   const int n_chunks = a.d / EPC;
@@ -131,6 +132,7 @@ int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32
   a.ent_tokens = c->st.ent_tokens;
   a.ent_len = c->st.ent_len;
   a.first = first;
+  a.last_n = (!first && max_new > 0) ? max_new : 0;
   a.B = c->cfg.B;
   a.V = c->cfg.V;
   a.M = c->cfg.M;
@@ -140,7 +142,8 @@ int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32
   for (int L = 0; L <= Z2Z_MAX_M; ++L)
     for (int j = 0; j < Z2Z_MAX_M; ++j) a.coef[L][j] = c->coef[L][j];
   if (c->cfg.cap == 0) return Z2Z_OK;
-  int units = first ? (max_new < 1 ? c->cfg.cap : (max_new < c->cfg.cap ? max_new : c->cfg.cap)) : c->cfg.cap;
+  const bool incremental = first || max_new > 0;
+  int units = incremental ? (max_new < 1 ? c->cfg.cap : (max_new < c->cfg.cap ? max_new : c->cfg.cap)) : c->cfg.cap;
   a.units_per_seq = units;
   const long long total_units = (long long)c->cfg.B * units;
   const unsigned grid = (unsigned)((total_units + 3) / 4);

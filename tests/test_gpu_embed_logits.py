@@ -217,6 +217,15 @@ def test_incremental_hyper_embed_only_touches_new_rows():
         assert torch.equal(d_W[b, f[b]:size[b]], d_W2[b, f[b]:size[b]])
         assert torch.equal(d_W[b, :f[b]], sentinel[b, :f[b]])
         assert torch.equal(d_W[b, size[b]:], sentinel[b, size[b]:])
+    # the snapshot-free form: only the last k entries of each sequence, k larger than some codebooks
+    for k in (1, 5, 4000):
+        d_W3 = torch.full_like(d_W, 3.0)
+        ctx.hyper_embed(d_E, d_W3, None, max_new=k)
+        torch.cuda.synchronize()
+        for b in range(cfg["B"]):
+            lo = max(int(size[b]) - k, 0)
+            assert torch.equal(d_W3[b, lo:size[b]], d_W2[b, lo:size[b]])
+            assert (d_W3[b, :lo] == 3.0).all() and (d_W3[b, size[b]:] == 3.0).all()
     ctx.close()
 
 
@@ -290,13 +299,12 @@ def test_full_size_decode_step_c3():
     print(f"  history encoded and embedded {time.time() - t0:.1f}s", flush=True)
     # one decode step: new code -> codebook update -> embed the new entry -> logits
     sizes = np.array([len(s.entries) for s in streams])
-    first = ctx.codebook()[2].clone()
     new = wl.make_step_codes(cfg, sizes, 0)
     d_new = torch.from_numpy(new.reshape(B, 1)).cuda()
     n_tok = torch.empty(B, dtype=torch.int32, device="cuda")
     st = torch.empty(B, dtype=torch.int32, device="cuda")
     ctx.lzw_decode(d_new, None, None, n_tok, st, api.APPEND)
-    ctx.hyper_embed(d_E, d_W, first, max_new=1)
+    ctx.hyper_embed(d_E, d_W, None, max_new=1)         # at most one new entry per sequence and step
     d_H = torch_storage(H, cfg["dtype"])
     am = torch.empty(B, dtype=torch.int32, device="cuda")
     mx = torch.empty(B, dtype=torch.float32, device="cuda")
