@@ -97,6 +97,25 @@ def test_tiny_alphabets_and_limits(V, M, cap):
     _check_encode_decode(dict(V=V, M=M, cap=cap), tokens, lens)
 
 
+def test_largest_ids_capacity_and_merge_size():
+    """The limits of the ID packing: V + cap = 2^24, cap = 65535, M = 8 (codes and tokens up to 2^24 - 1 in
+    the hash slots, entry indices up to 65534, the table in global memory)."""
+    cap, M = 65535, 8
+    V = (1 << 24) - cap
+    rng = np.random.default_rng(24)
+    B, N = 2, 150000
+    # a few hundred distinct IDs from the top and the bottom of the range, so that the codebook fills up
+    alphabet = np.concatenate([np.arange(V - 200, V), np.arange(0, 200)]).astype(np.int64)
+    tokens = alphabet[rng.integers(0, len(alphabet), size=(B, N))].astype(np.int32)
+    tokens[1, : N // 3] = np.array([V - 1, 0, V - 2])[rng.integers(0, 3, size=N // 3)]   # three IDs: phrases reach M
+    lens = np.array([N, N - 77], dtype=np.int32)
+    print(f"[case] lzw limits V={V} M={M} cap={cap}", flush=True)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    assert all(len(r[1]) == cap for r in ref), "the case must fill the codebooks"
+    assert max(len(e) for e in ref[1][1]) == M, "the case must reach the merge limit"
+    _check_encode_decode(dict(V=V, M=M, cap=cap, d=8), tokens, lens)
+
+
 def test_bad_token_and_short_output():
     from paper_2506_01084_amd import api
 
