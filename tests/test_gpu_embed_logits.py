@@ -374,3 +374,87 @@ def test_decode_kernel_small_shapes_every_row(B, N, V, d, M, cap):
             a_, m_, l_ = outs[kern]
             check_logits_rows(r, a_[b:b + 1], m_[b:b + 1], l_[b:b + 1], None)
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# the generation loop (section 2.3, steps 7-10): pick -> codebook update -> embed the new entry -> logits,
+# with each step's pick fed back as the next step's code on the device; eagerly against the oracle, and
+# captured once in a HIP graph whose replays must reproduce the eager run
+# ---------------------------------------------------------------------------------------------------
+def test_feedback_loop_eager_vs_oracle_and_graph_replays():
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=6, N=400, V=2000, d=256, cap=300, seed=4242)
+    B, V, M, cap, d = (cfg[k] for k in ("B", "V", "M", "cap", "d"))
+    K = 12                                            # steps per graph; two replays = 24 steps
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    H_steps = [wl.make_hidden(wl.scaled(cfg, seed=cfg["seed"] + 10 * t), B) for t in range(K)]
+    d_H = [torch_storage(h, "bf16") for h in H_steps]
+    print("[case] feedback loop, eager and graph", flush=True)
+
+    def fresh():
+        ctx, w = _make_ctx(cfg)
+        gpu_encode(ctx, tokens, None)
+        d_E, d_W = _embed_gpu(ctx, cfg, E)
+        return ctx, w, d_E, d_W
+
+    def make_bufs(n):
+        return (torch.zeros((n, B), dtype=torch.int32, device="cuda"), torch.zeros((n, B), dtype=torch.float32, device="cuda"),
+                torch.zeros((n, B), dtype=torch.float32, device="cuda"), torch.zeros(B, dtype=torch.int32, device="cuda"),
+                torch.zeros(B, dtype=torch.int32, device="cuda"))
+
+    def step(ctx, d_E, d_W, bufs, t, slot):
+        am, mx, lse, ntok, st = bufs
+        ctx.extended_logits(d_H[t % K], 1, d_E, d_W, am[slot], mx[slot], lse[slot], None)
+        ctx.lzw_decode(am[slot], None, None, ntok, st, api.APPEND, stride=1)     # the pick is the next code
+        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+
+    # ---- eager, 2K steps, checked against the oracle step by step (the oracle is fed the GPU's picks) ----
+    ctx, w, d_E, d_W = fresh()
+    bufs = make_bufs(2 * K)
+    streams = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    for b in range(B):
+        streams[b].encode_chunk(tokens[b].tolist())
+    for t in range(2 * K):
+        step(ctx, d_E, d_W, bufs, t, t)
+        torch.cuda.synchronize()
+        assert int(bufs[4].abs().sum()) == 0
+        am_h, mx_h, lse_h = bufs[0][t].cpu().numpy(), bufs[1][t].cpu().numpy(), bufs[2][t].cpu().numpy()
+        for b in range(B):
+            Wr = oracle.hyper_embed(E, "bf16", streams[b].entries, cap, cfg["pool"], w)
+            r = oracle.extended_logits(H_steps[t % K][b:b + 1], E, Wr, len(streams[b].entries), "bf16", return_logits=True)
+            check_logits_rows(r, am_h[b:b + 1], mx_h[b:b + 1], lse_h[b:b + 1], None)
+            _, rst = streams[b].decode_chunk([int(am_h[b])])
+            assert rst == 0
+        size = ctx.codebook()[2].cpu().numpy()
+        assert size.tolist() == [len(s.entries) for s in streams], f"step {t}"
+    eager_am = bufs[0].cpu().numpy()
+    eager_W = d_W.clone()
+    eager_size = ctx.codebook()[2].cpu().numpy().copy()
+    assert (eager_size > 0).all()
+    ctx.close()
+
+    # ---- the same K steps captured once, replayed twice, unrelated eager work in between ----------------
+    ctx, w, d_E, d_W = fresh()
+    gbufs = make_bufs(K)
+    warm = make_bufs(1)
+    ctx.extended_logits(d_H[0], 1, d_E, d_W, warm[0][0], warm[1][0], warm[2][0], None)   # sizes the library's scratch
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for t in range(K):
+            step(ctx, d_E, d_W, gbufs, t, t)
+    for rep in range(2):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = gbufs[0].cpu().numpy()
+        assert (got == eager_am[rep * K:(rep + 1) * K]).all(), f"replay {rep}: picks differ from the eager run"
+        assert int(gbufs[4].abs().sum()) == 0
+        junk = torch.randn(1 << 20, device="cuda").sum().item()                        # eager work between replays
+        assert np.isfinite(junk)
+    assert (ctx.codebook()[2].cpu().numpy() == eager_size).all()
+    assert torch.equal(d_W, eager_W)
+    ctx.close()
