@@ -229,6 +229,24 @@ def run_decode_workload(args, torch, api, wl):
     graph_us = (time.perf_counter() - t0) * 1e6 / timed
     assert int(d_st.abs().sum()) == 0 and torch.equal(d_am, am_eager), "graph replay differs from the eager steps"
 
+    # the same step with the pick drawn at a temperature (z2z_extended_sample) instead of the maximum
+    d_lp = torch.empty(B, dtype=torch.float32, device="cuda")
+
+    def step_sampled(s):
+        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
+        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+        ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 2506, s, d_am, d_lp)
+
+    for s in range(args.warmup):
+        step_sampled(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, n_steps):
+        step_sampled(s)
+    torch.cuda.synchronize()
+    sample_us = (time.perf_counter() - t0) * 1e6 / timed
+    assert int(d_st.abs().sum()) == 0
+
     sizes = size_view.cpu().numpy()
     us = dt * 1e6 / timed
     bytes_step = 2.0 * d * (V + float(sizes.sum())) + 2.0 * B * d
@@ -237,7 +255,8 @@ def run_decode_workload(args, torch, api, wl):
     k_us = k_ms * 1e3 / k_n
     k_gbs = bytes_step / (k_us * 1e-6) / 1e9
     return dict(workload=cfg["name"], steps=timed, us_per_step=us, graph_us_per_step=graph_us,
-                graph_frac=bytes_step / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
+                graph_frac=bytes_step / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                sample_us_per_step=sample_us, sample_frac=bytes_step / (sample_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
                 peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()),
                 roofline={"bound": "hbm", "kernel": "logits_decode_kernel (64 rows, config 3)", "achieved": k_gbs,
                           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": k_gbs / PEAK_HBM_GBS,

@@ -1,13 +1,14 @@
 /*
  * z2z.h -- C ABI of the zip2zip dynamic-vocabulary hot path for AMD MI355X (gfx950).
  *
- * The four operations follow the paper's statement of the method (arxiv 2506.01084):
+ * The operations follow the paper's statement of the method (arxiv 2506.01084):
  *   lzw_encode       section 2.1 "LZW Algorithm"; section 2.3 step 2 (compress base tokens to hypertokens)
  *   lzw_decode       section 2.1 property (2) "self-contained"; section 2.3 steps 11-12 (decompress);
  *                    in append mode it is the per-step codebook update of steps 9-10
  *   hyper_embed      section 2.2 (hyper-encoder over the constituent base embeddings, padded to M);
  *                    "Averaging" row of the hyper-encoder ablation table; "Hyper-Embedding Cache"
  *   extended_logits  section 2.3 steps 7-9 (hyper rows appended to the LM head, joint softmax, pick)
+ *   extended_sample  the same with the pick drawn from the softmax at a temperature (step 9)
  *
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller; it must stay valid until the
@@ -142,6 +143,24 @@ int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_
 int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                         const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
                         float* d_lse, float* d_logits, void* stream);
+
+/* extended_sample.  The generation step's pick when it is a draw rather than the maximum (section 2.3,
+ * steps 8-9: the next token comes from the joint distribution over base tokens and hypertokens):
+ *   d_token[r] ~ softmax(logit[r, :] / temperature), over the same columns as z2z_extended_logits.
+ * Gumbel-max: d_token[r] = argmax_v (logit[r, v] / temperature - ln(-ln u[r, v])) (lowest v among equal
+ * maxima), which has exactly that distribution.  u[r, v] is a pure function of (seed, step, r, v): word
+ * v & 3 of Philox4x32-10 (Salmon et al., SC'11) with counter (v >> 2, r, step low, step high) and key
+ * (seed low, seed high), u = ((word >> 9) + 0.5) * 2^-23.  The same (seed, step) gives the same draws; a
+ * generation loop passes its step number.
+ *   d_token   [rows] int32 out
+ *   d_logprob [rows] float out or NULL: ln of the drawn token's probability under softmax(logit / temperature)
+ *   temperature  > 0 and finite (else Z2Z_EINVAL)
+ * Built for the generation step: rows_per_seq must be 1 and the context bf16 with d a multiple of 128 and
+ * d <= 4096; anything else returns Z2Z_EUNSUPPORTED.  Scratch as for z2z_extended_logits.
+ */
+int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                        const void* d_W_base, const void* d_W_hyper, float temperature, uint64_t seed,
+                        uint64_t step, int32_t* d_token, float* d_logprob, void* stream);
 
 /* Tuning knobs (kernel variants and tile schedule) and instrumentation; unknown keys return
  * Z2Z_EINVAL. */

@@ -79,6 +79,87 @@ __global__ void __launch_bounds__(256) logits_mask_kernel(float* logits, int row
   for (int c = C + threadIdx.x; c < cap; c += blockDim.x) row[c] = kNegInf;
 }
 
+// Sampling: merge the parts of a hidden row into the drawn column (largest perturbed value, lowest column
+// among equals) and its log-probability, scaled logit there minus the log-sum-exp of the scaled logits.
+// One block of 256 threads per row.
+__global__ void __launch_bounds__(256) sample_combine_kernel(const float* part_m, const float* part_s,
+                                                             const float* part_v, const float* part_l,
+                                                             const int32_t* part_i, int n_parts, int rows,
+                                                             int32_t* token, float* logprob) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x;
+  Triple tr = empty_triple();        // .i unused here
+  float bv = kNegInf, bl = 0.f;
+  int bi = kNoColumn;
+  const size_t base = (size_t)r * n_parts;
+  for (int p = threadIdx.x; p < n_parts; p += 256) {
+    Triple o;
+    o.m = part_m[base + p];
+    o.s = part_s[base + p];
+    o.i = kNoColumn;
+    merge_triple(tr, o);
+    const float v = part_v[base + p];
+    const int i = part_i[base + p];
+    if (v > bv || (v == bv && i < bi)) {
+      bv = v;
+      bl = part_l[base + p];
+      bi = i;
+    }
+  }
+  __shared__ Triple xt[4];
+  __shared__ float xv[4], xl[4];
+  __shared__ int xi[4];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    Triple o;
+    o.m = __shfl_xor(tr.m, off);
+    o.s = __shfl_xor(tr.s, off);
+    o.i = kNoColumn;
+    merge_triple(tr, o);
+    const float v = __shfl_xor(bv, off), l = __shfl_xor(bl, off);
+    const int i = __shfl_xor(bi, off);
+    if (v > bv || (v == bv && i < bi)) {
+      bv = v;
+      bl = l;
+      bi = i;
+    }
+  }
+  if (lane == 0) {
+    const int w = threadIdx.x >> 6;
+    xt[w] = tr;
+    xv[w] = bv;
+    xl[w] = bl;
+    xi[w] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      merge_triple(tr, xt[w]);
+      if (xv[w] > bv || (xv[w] == bv && xi[w] < bi)) {
+        bv = xv[w];
+        bl = xl[w];
+        bi = xi[w];
+      }
+    }
+    token[r] = bi;
+    if (logprob) logprob[r] = bl - (tr.m + logf(tr.s));
+  }
+}
+
+int ensure_sample_scratch(z2z_ctx* c, size_t need) {
+  if (need <= c->part_vl_capacity) return Z2Z_OK;
+  if (c->part_v) (void)hipFree(c->part_v);
+  if (c->part_l) (void)hipFree(c->part_l);
+  c->part_v = nullptr;
+  c->part_l = nullptr;
+  c->part_vl_capacity = 0;
+  if (hipMalloc(&c->part_v, need * sizeof(float)) != hipSuccess) return Z2Z_ENOMEM;
+  if (hipMalloc(&c->part_l, need * sizeof(float)) != hipSuccess) return Z2Z_ENOMEM;
+  c->part_vl_capacity = need;
+  return Z2Z_OK;
+}
+
 int ensure_scratch(z2z_ctx* c, size_t need) {
   if (need <= c->part_capacity) return Z2Z_OK;
   if (c->part_m) (void)hipFree(c->part_m);
@@ -146,7 +227,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     int n_parts = z2z_logits_decode_parts(c);
     int rc = ensure_scratch(c, (size_t)n_parts * rows);
     if (rc != Z2Z_OK) return rc;
-    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, s);
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, s);
     if (rc != Z2Z_OK) return rc;
     return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
   }
@@ -193,4 +274,27 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     }
   }
   return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
+}
+
+int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                               const void* W_hyper, float temperature, uint64_t seed, uint64_t step,
+                               int32_t* token, float* logprob, hipStream_t s) {
+  // built for the generation step: one hidden row per sequence, the bandwidth-bound kernel
+  if (rows_per_seq != 1 || !c->decode_ready) return Z2Z_EUNSUPPORTED;
+  int n_parts = z2z_logits_decode_parts(c);
+  int rc = ensure_scratch(c, (size_t)n_parts * rows);
+  if (rc != Z2Z_OK) return rc;
+  rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
+  if (rc != Z2Z_OK) return rc;
+  z2z_sample_params sp;
+  sp.temperature = temperature;
+  sp.seed = seed;
+  sp.step = step;
+  const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
+  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, s);
+  if (rc != Z2Z_OK) return rc;
+  hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v, c->part_l,
+                     c->part_i, n_parts, rows, token, logprob);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
 }

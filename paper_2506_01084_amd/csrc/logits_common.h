@@ -129,8 +129,14 @@ struct LogitsArgs {
 int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 int z2z_launch_logits_fast(bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 int z2z_logits_fast_prepare(z2z_ctx* c);
+// temperature sampling (one-row-per-sequence kernel only): softmax(logit / temperature), generator key and
+// counter words from seed and step
+struct z2z_sample_params {
+  float temperature;
+  uint64_t seed, step;
+};
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
-                             bool timed, hipStream_t s);
+                             bool timed, const z2z_sample_params* sample, hipStream_t s);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 bool z2z_logits_decode_ok(const z2z_ctx* c);
 int z2z_logits_decode_prepare(z2z_ctx* c);

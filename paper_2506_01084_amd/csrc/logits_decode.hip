@@ -53,6 +53,13 @@ struct DecodeArgs {
   float* part_m;          // [B, n_parts]
   float* part_s;
   int32_t* part_i;
+  // sampling variant: the triples are taken over logit / temperature, and next to them the kernel keeps
+  // the largest perturbed value (part_v), the scaled logit there (part_l) and its column (part_i)
+  float* part_v;
+  float* part_l;
+  float inv_temperature;
+  uint32_t key0, key1;    // generator key: the seed
+  uint32_t ctr2, ctr3;    // generator counter words 2, 3: the step
 };
 
 __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
@@ -65,6 +72,81 @@ __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
   }
 }
 
+// ---- sampling (section 2.3 of the zip2zip paper, step 9: the next token is a draw from the joint
+//      softmax).  Gumbel-max: the column that maximises logit / T - ln(-ln u) is distributed as
+//      softmax(logit / T); u comes from Philox4x32-10 (Salmon et al., SC'11) with counter
+//      (column >> 2, hidden row, step) and key = seed, so a draw is a pure function of its coordinates.
+struct Draw {
+  float v;   // largest perturbed value so far
+  float l;   // logit / T at that column
+  int i;     // that column
+};
+
+__device__ __forceinline__ Draw empty_draw() {
+  Draw d;
+  d.v = kNegInf;
+  d.l = 0.f;
+  d.i = kNoColumn;
+  return d;
+}
+
+__device__ __forceinline__ void merge_draw(Draw& a, const Draw& b) {
+  if (b.v > a.v || (b.v == a.v && b.i < a.i)) a = b;
+}
+
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+    c = uint4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
+  }
+  return c;
+}
+
+// Generator words for the columns 4 * group .. 4 * group + 3 of one hidden row are produced together;
+// a thread that walks consecutive columns keeps them until it leaves the group.
+struct Noise {
+  uint4 words;
+  int group;
+};
+
+__device__ __forceinline__ float gumbel_at(const DecodeArgs& a, Noise& n, int hrow, int col) {
+  const int group = col >> 2;
+  if (group != n.group) {
+    n.words = philox4x32_10(uint4{(uint32_t)group, (uint32_t)hrow, a.ctr2, a.ctr3}, a.key0, a.key1);
+    n.group = group;
+  }
+  const int k = col & 3;
+  const uint32_t w = k == 0 ? n.words.x : (k == 1 ? n.words.y : (k == 2 ? n.words.z : n.words.w));
+  // u = ((w >> 9) + 0.5) * 2^-23 and 1 - u are both exact in float; -ln u = -log1p(-(1 - u)) stays accurate
+  // where it matters most, for u next to 1 (the largest perturbations)
+  const float one_minus_u = ((float)(0x7FFFFFu - (w >> 9)) + 0.5f) * 0x1p-23f;
+  return -logf(-log1pf(-one_minus_u));
+}
+
+template <bool SAMPLE>
+__device__ __forceinline__ void fold_logit(const DecodeArgs& a, Triple& t, Draw& dr, Noise& n, float x, int hrow,
+                                           int col) {
+  if (SAMPLE) {
+    const float z = x * a.inv_temperature;
+    fold_value(t, z, col);
+    const float p = z + gumbel_at(a, n, hrow, col);
+    if (p > dr.v) {                 // columns arrive in increasing order: strict comparison keeps the lowest
+      dr.v = p;
+      dr.l = z;
+      dr.i = col;
+    }
+  } else {
+    fold_value(t, x, col);
+  }
+}
+
+template <bool SAMPLE>
 __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int group, unsigned char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -164,12 +246,18 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
 
   // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 32 .. + 32, in increasing order
   Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);       // the slots are idle now
+  Draw* xdr = reinterpret_cast<Draw*>(xch + D_THREADS);
   const int j = tid & 63;
   const int seg = tid >> 6;
   Triple t = empty_triple();
+  Draw dr = empty_draw();
+  Noise noise;
+  noise.group = -1;
   const int r_hi = min(D_BASE_UNIT, a.V - v0);
-  for (int r = seg * 32; r < min(seg * 32 + 32, r_hi); ++r) fold_value(t, tile[r * 64 + j], v0 + r);
+  for (int r = seg * 32; r < min(seg * 32 + 32, r_hi); ++r)
+    fold_logit<SAMPLE>(a, t, dr, noise, tile[r * 64 + j], h0 + j, v0 + r);
   xch[tid] = t;
+  if (SAMPLE) xdr[tid] = dr;
   __syncthreads();
   if (tid < 64 && j < n_h) {
     Triple r = xch[j];
@@ -178,12 +266,24 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     const size_t p = (size_t)(h0 + j) * a.n_parts + unit;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
-    a.part_i[p] = r.i;
+    if (SAMPLE) {
+      Draw d0 = xdr[j];
+#pragma unroll
+      for (int s = 1; s < 8; ++s) merge_draw(d0, xdr[s * 64 + j]);
+      a.part_v[p] = d0.v;
+      a.part_l[p] = d0.l;
+      a.part_i[p] = d0.i;
+    } else {
+      a.part_i[p] = r.i;
+    }
   }
 }
 
-template <int NQ>
-__device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, int r1, int lane, int wave, Triple& t) {
+template <int NQ, bool SAMPLE>
+__device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, int r1, int lane, int wave, Triple& t,
+                                           Draw& dr) {
+  Noise noise;
+  noise.group = -1;
   const int chunks_per_row = a.d >> 3;
   // this lane's part of the hidden row: chunk q * 64 + lane, q < NQ (chunks past the row end are zero)
   uint4 h[NQ];
@@ -224,30 +324,36 @@ __device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, i
       sa += __shfl_xor(sa, o);
       sb += __shfl_xor(sb, o);
     }
-    fold_value(t, sa, a.V + r);
-    if (has_b) fold_value(t, sb, a.V + rb);
+    fold_logit<SAMPLE>(a, t, dr, noise, sa, b, a.V + r);
+    if (has_b) fold_logit<SAMPLE>(a, t, dr, noise, sb, b, a.V + rb);
   }
 }
 
+template <bool SAMPLE>
 __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, unsigned char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Triple* xch = reinterpret_cast<Triple*>(lds);
+  Draw* xdr = reinterpret_cast<Draw*>(xch + 8);
   const int C = min(max(a.size[b], 0), a.cap);
   const int r0 = u * D_UNIT;
   const int r1 = min(C, r0 + D_UNIT);
   Triple t = empty_triple();
+  Draw dr = empty_draw();
   if (r0 < r1) {
     const int nq = (a.d + 511) >> 9;
     if (nq <= 4)
-      hyper_rows<4>(a, b, r0, r1, lane, wave, t);
+      hyper_rows<4, SAMPLE>(a, b, r0, r1, lane, wave, t, dr);
     else
-      hyper_rows<D_MAXQ>(a, b, r0, r1, lane, wave, t);
+      hyper_rows<D_MAXQ, SAMPLE>(a, b, r0, r1, lane, wave, t, dr);
   }
   // every lane of a wave holds the same triple; waves took rows w, w + 8, ...: merging by value and
   // column restores the lowest-column rule
-  if (lane == 0) xch[wave] = t;
+  if (lane == 0) {
+    xch[wave] = t;
+    if (SAMPLE) xdr[wave] = dr;
+  }
   __syncthreads();
   if (tid == 0) {
     Triple r = xch[0];
@@ -256,10 +362,20 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
     const size_t p = (size_t)b * a.n_parts + a.n_base_units + u;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
-    a.part_i[p] = r.i;
+    if (SAMPLE) {
+      Draw d0 = xdr[0];
+#pragma unroll
+      for (int s = 1; s < 8; ++s) merge_draw(d0, xdr[s]);
+      a.part_v[p] = d0.v;
+      a.part_l[p] = d0.l;
+      a.part_i[p] = d0.i;
+    } else {
+      a.part_i[p] = r.i;
+    }
   }
 }
 
+template <bool SAMPLE>
 __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   // the hyper units come first: they read twice as many weight rows as a base unit, and the workgroups
@@ -267,18 +383,19 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
   const int n_hyper = a.B * a.units_per_seq;
   const int bid = blockIdx.x;
   if (bid < n_hyper) {
-    hyper_unit(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
+    hyper_unit<SAMPLE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
     const int bu = bid - n_hyper;
-    base_unit(a, bu % a.n_base_units, bu / a.n_base_units, lds);
+    base_unit<SAMPLE>(a, bu % a.n_base_units, bu / a.n_base_units, lds);
   }
 }
 
 }  // namespace
 
-// Parts written: n_base_units + units_per_seq per hidden row.
+// Parts written: n_base_units + units_per_seq per hidden row.  With `sample` the kernel works on
+// logit / temperature and also leaves the best perturbed value per part (part_v, part_l, part_i).
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
-                             bool timed, hipStream_t s) {
+                             bool timed, const z2z_sample_params* sample, hipStream_t s) {
   DecodeArgs a;
   a.H = reinterpret_cast<const uint4*>(H);
   a.W_base = reinterpret_cast<const uint4*>(W_base);
@@ -294,11 +411,21 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.part_m = c->part_m;
   a.part_s = c->part_s;
   a.part_i = c->part_i;
+  a.part_v = c->part_v;
+  a.part_l = c->part_l;
+  a.inv_temperature = sample ? 1.0f / sample->temperature : 1.0f;
+  a.key0 = sample ? (uint32_t)sample->seed : 0u;
+  a.key1 = sample ? (uint32_t)(sample->seed >> 32) : 0u;
+  a.ctr2 = sample ? (uint32_t)sample->step : 0u;
+  a.ctr3 = sample ? (uint32_t)(sample->step >> 32) : 0u;
   *n_parts = a.n_base_units + a.units_per_seq;
   a.n_parts = *n_parts;
   const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  hipLaunchKernelGGL(logits_decode_kernel, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  if (sample)
+    hipLaunchKernelGGL(logits_decode_kernel<true>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  else
+    hipLaunchKernelGGL(logits_decode_kernel<false>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
     c->n_timed++;
@@ -317,7 +444,9 @@ bool z2z_logits_decode_ok(const z2z_ctx* c) {
 
 int z2z_logits_decode_prepare(z2z_ctx* c) {
   if (c->lds_limit < D_LDS) return Z2Z_EUNSUPPORTED;
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel),
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   return Z2Z_OK;
 }

@@ -23,6 +23,8 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->part_m);
   (void)hipFree(c->part_s);
   (void)hipFree(c->part_i);
+  (void)hipFree(c->part_v);
+  (void)hipFree(c->part_l);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
       (void)hipEventDestroy(c->ev_start[i]);
@@ -167,6 +169,19 @@ Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int
   if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
   return z2z_launch_extended_logits(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_argmax, d_max, d_lse,
                                     d_logits, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                                const void* d_W_base, const void* d_W_hyper, float temperature, uint64_t seed,
+                                uint64_t step, int32_t* d_token, float* d_logprob, void* stream) {
+  if (!ctx || !d_H || !d_W_base || !d_token) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
+  if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
+  if (!(temperature > 0.f) || !(temperature < 3.0e38f)) return Z2Z_EINVAL;
+  if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_extended_sample(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, temperature, seed, step,
+                                    d_token, d_logprob, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {

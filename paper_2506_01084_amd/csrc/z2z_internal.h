@@ -40,6 +40,10 @@ struct z2z_ctx {
   float* part_s;
   int32_t* part_i;
   size_t part_capacity;    // elements in each of the three arrays
+  // extended_sample scratch: best perturbed value and the scaled logit at that column (its column is part_i)
+  float* part_v;
+  float* part_l;
+  size_t part_vl_capacity;
   // options
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map;
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration
@@ -63,6 +67,9 @@ int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
                                hipStream_t s);
+int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                               const void* W_hyper, float temperature, uint64_t seed, uint64_t step,
+                               int32_t* token, float* logprob, hipStream_t s);
 
 #define Z2Z_HIP_TRY(expr)                      \
   do {                                         \
