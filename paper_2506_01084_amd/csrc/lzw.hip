@@ -875,7 +875,11 @@ void plan(const z2z_ctx* c, int32_t stride, int32_t flags, bool decode, bool* ld
   // a short append (a decode step) touches a handful of slots: probing global memory directly is
   // cheaper than staging the table
   const bool tiny_append = !(flags & Z2Z_RESET) && stride <= 64;
-  *lds = c->st.slots_fit_lds && !tiny_append && c->opt_lzw_kernel != 2;
+  // with thousands of sequences the LDS a table takes limits a CU to a few waves; probing the table in
+  // global memory (L2) with the CU full of waves is then faster (measured crossover between 512 and 2048
+  // sequences of 4096 tokens)
+  const bool crowd = c->cfg.B >= 1024;
+  *lds = c->st.slots_fit_lds && !tiny_append && !crowd && c->opt_lzw_kernel != 2;
   a->lds_ef = 0;
   *smem = 0;
   if (*lds) {
@@ -957,7 +961,10 @@ int z2z_lzw_prepare(z2z_ctx* c) {
   const int want = 2 * cap < 64 ? 64 : 2 * cap;
   const int floor125 = cap + cap / 4 + 1;
   const int lds_slots = (c->lds_limit - kEncStaticLds) / (int)sizeof(u64);   // the encoder's own LDS comes first
-  if (want4 + cap / 2 <= lds_slots) {                 // room left for the decoder's entry info
+  // With fewer sequences than CUs a workgroup has its CU to itself and the roomier table (shorter probe
+  // sequences) is free; with many, LDS decides how many sequences a CU works on at once.
+  const bool roomy = c->cfg.B < 256;
+  if (roomy && want4 + cap / 2 <= lds_slots) {        // room left for the decoder's entry info
     st.nslots = want4;
     st.slots_fit_lds = 1;
   } else if (want <= lds_slots) {

@@ -97,6 +97,17 @@ def test_tiny_alphabets_and_limits(V, M, cap):
     _check_encode_decode(dict(V=V, M=M, cap=cap), tokens, lens)
 
 
+@pytest.mark.parametrize("B", [300, 1100])
+def test_many_sequences_per_call(B):
+    """Hundreds and thousands of sequences in one call: the library sizes its tables for occupancy (smaller
+    LDS tables from 256 sequences, the table in global memory from 1024), results unchanged."""
+    cfg = wl.scaled(wl.CONFIGS["c4"], B=B, N=300, V=500, cap=256, seed=B)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    print(f"[case] lzw many sequences B={B}", flush=True)
+    _check_encode_decode(cfg, tokens, lens)
+
+
 def test_largest_ids_capacity_and_merge_size():
     """The limits of the ID packing: V + cap = 2^24, cap = 65535, M = 8 (codes and tokens up to 2^24 - 1 in
     the hash slots, entry indices up to 65534, the table in global memory)."""
