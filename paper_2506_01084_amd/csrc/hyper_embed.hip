@@ -20,7 +20,8 @@ struct EmbedArgs {
   const int32_t* first;       // [B] or nullptr
   int32_t last_n;             // first == nullptr: 0 = all of [0, cap), n > 0 = the last n entries only
   int32_t B, V, M, cap, d;
-  int32_t units_per_seq;      // waves assigned to each sequence
+  int32_t units_per_seq;      // entry walkers assigned to each sequence
+  int32_t split;              // waves that share one entry's row (each takes every split-th group of 64 chunks)
   int32_t pool;
   float coef[Z2Z_MAX_M + 1][Z2Z_MAX_M];
 };
@@ -34,7 +35,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 }
 
 template <bool BF16>
-__device__ __forceinline__ void embed_row(const EmbedArgs& a, const int32_t* toks, int L, size_t out_row, int lane) {
+__device__ __forceinline__ void embed_row(const EmbedArgs& a, const int32_t* toks, int L, size_t out_row, int lane,
+                                          int part) {
   // elements per 16-byte chunk: 8 (bf16) or 4 (f32)
   constexpr int EPC = BF16 ? 8 : 4;
   const int n_chunks = a.d / EPC;
@@ -49,7 +51,7 @@ __device__ __forceinline__ void embed_row(const EmbedArgs& a, const int32_t* tok
   }
   const bool mean = a.pool == Z2Z_POOL_MEAN;
   const float fL = (float)L;
-  for (int c = lane; c < n_chunks; c += 64) {
+  for (int c = part * 64 + lane; c < n_chunks; c += 64 * a.split) {
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
@@ -92,13 +94,17 @@ __device__ __forceinline__ void embed_row(const EmbedArgs& a, const int32_t* tok
   }
 }
 
-// grid.x = B * units_per_seq / 4 (4 waves per block); wave u of sequence b walks entries
-// e = e0 + u, e0 + u + units_per_seq, ...  Full mode (first == nullptr) covers [0, cap): rows below C_b
-// are embedded, the others zeroed.  Incremental modes cover [first[b], C_b) or the last last_n entries only.
+// grid.x = B * units_per_seq * split / 4 (4 waves per block); walker u of sequence b visits entries
+// e = e0 + u, e0 + u + units_per_seq, ...; `split` waves share a walker's rows (a handful of rows, as in a
+// decode step, would otherwise be one long chain of loads per wave).  Full mode (first == nullptr,
+// last_n == 0) covers [0, cap): rows below C_b are embedded, the others zeroed.  Incremental modes cover
+// [first[b], C_b) or the last last_n entries only.
 template <bool BF16>
 __global__ void __launch_bounds__(256) hyper_embed_kernel(EmbedArgs a) {
   const int lane = threadIdx.x & 63;
-  const long long unit = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long wave_id = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int part = (int)(wave_id % a.split);
+  const long long unit = wave_id / a.split;
   const int b = (int)(unit / a.units_per_seq);
   const int u = (int)(unit % a.units_per_seq);
   if (b >= a.B) return;
@@ -112,11 +118,11 @@ __global__ void __launch_bounds__(256) hyper_embed_kernel(EmbedArgs a) {
     const size_t row = (size_t)b * a.cap + e;
     if (e < C) {
       const int L = min(max(a.ent_len[row], 1), a.M);
-      embed_row<BF16>(a, a.ent_tokens + row * a.M, L, row, lane);
+      embed_row<BF16>(a, a.ent_tokens + row * a.M, L, row, lane, part);
     } else {
       uint4* W = reinterpret_cast<uint4*>(a.W) + row * (size_t)n_chunks;
       const uint4 z = {0u, 0u, 0u, 0u};
-      for (int c = lane; c < n_chunks; c += 64) W[c] = z;
+      for (int c = part * 64 + lane; c < n_chunks; c += 64 * a.split) W[c] = z;
     }
   }
 }
@@ -145,7 +151,12 @@ int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32
   const bool incremental = first || max_new > 0;
   int units = incremental ? (max_new < 1 ? c->cfg.cap : (max_new < c->cfg.cap ? max_new : c->cfg.cap)) : c->cfg.cap;
   a.units_per_seq = units;
-  const long long total_units = (long long)c->cfg.B * units;
+  // few rows to embed: several waves per row (one group of 64 chunks each when the row is long enough)
+  const int chunks = c->cfg.d / (c->cfg.dtype == Z2Z_BF16 ? 8 : 4);
+  int split = 1;
+  while (split < 8 && (long long)c->cfg.B * units * split < 1024 && chunks >= 128 * split) split *= 2;
+  a.split = split;
+  const long long total_units = (long long)c->cfg.B * units * split;
   const unsigned grid = (unsigned)((total_units + 3) / 4);
   if (c->cfg.dtype == Z2Z_BF16)
     hipLaunchKernelGGL(hyper_embed_kernel<true>, dim3(grid), dim3(256), 0, s, a);
