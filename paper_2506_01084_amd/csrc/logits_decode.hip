@@ -123,10 +123,13 @@ __device__ __forceinline__ float gumbel_at(const DecodeArgs& a, Noise& n, int hr
   }
   const int k = col & 3;
   const uint32_t w = k == 0 ? n.words.x : (k == 1 ? n.words.y : (k == 2 ? n.words.z : n.words.w));
-  // u = ((w >> 9) + 0.5) * 2^-23 and 1 - u are both exact in float; -ln u = -log1p(-(1 - u)) stays accurate
-  // where it matters most, for u next to 1 (the largest perturbations)
-  const float one_minus_u = ((float)(0x7FFFFFu - (w >> 9)) + 0.5f) * 0x1p-23f;
-  return -logf(-log1pf(-one_minus_u));
+  // u = ((w >> 9) + 0.5) * 2^-23 and 1 - u are both exact in float.  e = -ln u has to be accurate relative
+  // to itself where it is small (u next to 1: the largest perturbations, the ones that win): there it is
+  // the series of -ln(1 - x); elsewhere the hardware logarithm's absolute error of ~1e-7 is relative 1e-5
+  // at worst.  The outer logarithm only needs absolute accuracy.
+  const float x = ((float)(0x7FFFFFu - (w >> 9)) + 0.5f) * 0x1p-23f;        // 1 - u
+  const float e = x < 0.015625f ? x * (1.f + x * (0.5f + x * (0.33333334f + 0.25f * x))) : -__logf(1.f - x);
+  return -__logf(e);
 }
 
 template <bool SAMPLE>
