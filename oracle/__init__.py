@@ -25,4 +25,5 @@ from .lzw import (LZWStream, lzw_encode, lzw_decode, pack_entries,  # noqa: F401
 from .embed import hyper_embed, pool_coefficients  # noqa: F401
 from .logits import extended_logits  # noqa: F401
 from .sampling import extended_sample, philox4x32_10, sample_row  # noqa: F401
+from .loss import extended_nll  # noqa: F401
 from .numfmt import bf16_bits_to_f64, f64_to_bf16_bits, to_f64, round_to_storage  # noqa: F401
