@@ -9,6 +9,7 @@
  *                    "Averaging" row of the hyper-encoder ablation table; "Hyper-Embedding Cache"
  *   extended_logits  section 2.3 steps 7-9 (hyper rows appended to the LM head, joint softmax, pick)
  *   extended_sample  the same with the pick drawn from the softmax at a temperature (step 9)
+ *   extended_nll     section 2.4 (next-token objective over compressed sequences): -log p(target) per row
  *
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller; it must stay valid until the
@@ -161,6 +162,18 @@ int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t row
 int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                         const void* d_W_base, const void* d_W_hyper, float temperature, uint64_t seed,
                         uint64_t step, int32_t* d_token, float* d_logprob, void* stream);
+
+/* extended_nll.  The per-position term of the training objective over compressed sequences (section 2.4,
+ * the next-token loss on z = LZW(y)): for hidden row r with target code t = d_targets[r],
+ *   d_nll[r] = d_lse[r] - logit[r, t],   d_lse[r] = ln sum_v exp(logit[r, v])
+ * over the same columns as z2z_extended_logits.  t < V is a base token, V <= t < V + C_b entry t - V of the
+ * row's sequence; t < 0 marks a position without a target (d_nll = 0); a t that names no existing column
+ * has probability zero (d_nll = +inf).  Any shape and storage type z2z_extended_logits takes.
+ *   d_targets [rows] int32; d_nll [rows] float out; d_lse [rows] float out (both required)
+ */
+int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                     const void* d_W_base, const void* d_W_hyper, const int32_t* d_targets, float* d_nll,
+                     float* d_lse, void* stream);
 
 /* Tuning knobs (kernel variants and tile schedule) and instrumentation; unknown keys return
  * Z2Z_EINVAL. */

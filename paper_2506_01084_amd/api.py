@@ -23,8 +23,8 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 MAX_M = 8
 
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",
-           "z2z_hyper_embed", "z2z_extended_logits", "z2z_extended_sample", "z2z_set_option", "z2z_read_timing",
-           "z2z_strerror"]
+           "z2z_hyper_embed", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_set_option",
+           "z2z_read_timing", "z2z_strerror"]
 
 
 class Config(ctypes.Structure):
@@ -58,6 +58,8 @@ def load_library() -> ctypes.CDLL:
                                         c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float,
                                         ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p, c_void_p]
+    lib.z2z_extended_nll.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_void_p, c_void_p]
     lib.z2z_set_option.argtypes = [c_void_p, c_int32, c_int32]
     lib.z2z_read_timing.argtypes = [c_void_p, POINTER(c_float), P32]
     lib.z2z_strerror.argtypes = [ctypes.c_int]
@@ -198,6 +200,16 @@ class Context:
                                              _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
                                              float(temperature), int(seed), int(step), _ptr(token, torch.int32),
                                              _ptr(logprob, torch.float32), _stream()), "z2z_extended_sample")
+
+    def extended_nll(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
+                     targets: torch.Tensor, nll: torch.Tensor, lse: torch.Tensor) -> None:
+        rows = H.shape[0]
+        assert H.shape[1] == self.d and tuple(W_base.shape) == (self.V, self.d)
+        assert targets.numel() == rows and nll.numel() == rows and lse.numel() == rows
+        _check(self._lib.z2z_extended_nll(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq,
+                                          _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
+                                          _ptr(targets, torch.int32), _ptr(nll, torch.float32),
+                                          _ptr(lse, torch.float32), _stream()), "z2z_extended_nll")
 
 
 class _DevView:

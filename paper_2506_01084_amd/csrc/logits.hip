@@ -147,6 +147,48 @@ __global__ void __launch_bounds__(256) sample_combine_kernel(const float* part_m
   }
 }
 
+// nll[r] = lse[r] - H[r] . W[target[r]] (section 2.4 of the zip2zip paper: the next-token objective taken
+// over the compressed sequence; the target is a base token or a hypertoken of the row's sequence).  One
+// wave per hidden row, 16-byte chunks, fp32 accumulation of the products of the stored values (what the
+// tile kernels compute for that column).  target < 0: no target, 0; a column that does not exist: +inf.
+template <bool BF16>
+__global__ void __launch_bounds__(256) target_nll_kernel(const uint4* H, const uint4* W_base, const uint4* W_hyper,
+                                                         const int32_t* size, const int32_t* targets,
+                                                         const float* lse, float* nll, int rows, int rows_per_seq,
+                                                         int V, int cap, int d) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int b = r / rows_per_seq;
+  const int t = targets[r];
+  const int C = min(max(size[b], 0), cap);
+  if (t < 0 || t >= V + C) {
+    if (lane == 0) nll[r] = t < 0 ? 0.f : INFINITY;
+    return;
+  }
+  constexpr int EPC = BF16 ? 8 : 4;
+  const int n_chunks = d / EPC;
+  const uint4* w = t < V ? W_base + (size_t)t * n_chunks : W_hyper + ((size_t)b * cap + (t - V)) * n_chunks;
+  const uint4* h = H + (size_t)r * n_chunks;
+  float acc = 0.f;
+  for (int c = lane; c < n_chunks; c += 64) {
+    const uint4 x = h[c], y = w[c];
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (BF16) {
+        acc = fmaf(__uint_as_float(xs[e] << 16), __uint_as_float(ys[e] << 16), acc);
+        acc = fmaf(__uint_as_float(xs[e] & 0xFFFF0000u), __uint_as_float(ys[e] & 0xFFFF0000u), acc);
+      } else {
+        acc = fmaf(__uint_as_float(xs[e]), __uint_as_float(ys[e]), acc);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+  if (lane == 0) nll[r] = lse[r] - acc;
+}
+
 int ensure_sample_scratch(z2z_ctx* c, size_t need) {
   if (need <= c->part_vl_capacity) return Z2Z_OK;
   if (c->part_v) (void)hipFree(c->part_v);
@@ -295,6 +337,23 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   if (rc != Z2Z_OK) return rc;
   hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v, c->part_l,
                      c->part_i, n_parts, rows, token, logprob);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                            const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s) {
+  int rc = z2z_launch_extended_logits(c, H, rows, rows_per_seq, W_base, W_hyper, nullptr, nullptr, lse, nullptr, s);
+  if (rc != Z2Z_OK) return rc;
+  const dim3 grid((rows + 3) / 4), block(256);
+  if (c->cfg.dtype == Z2Z_BF16)
+    hipLaunchKernelGGL(target_nll_kernel<true>, grid, block, 0, s, reinterpret_cast<const uint4*>(H),
+                       reinterpret_cast<const uint4*>(W_base), reinterpret_cast<const uint4*>(W_hyper), c->st.size,
+                       targets, lse, nll, rows, rows_per_seq, c->cfg.V, c->cfg.cap, c->cfg.d);
+  else
+    hipLaunchKernelGGL(target_nll_kernel<false>, grid, block, 0, s, reinterpret_cast<const uint4*>(H),
+                       reinterpret_cast<const uint4*>(W_base), reinterpret_cast<const uint4*>(W_hyper), c->st.size,
+                       targets, lse, nll, rows, rows_per_seq, c->cfg.V, c->cfg.cap, c->cfg.d);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

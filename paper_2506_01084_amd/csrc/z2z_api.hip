@@ -184,6 +184,18 @@ Z2Z_API int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int
                                     d_token, d_logprob, static_cast<hipStream_t>(stream));
 }
 
+Z2Z_API int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq, const void* d_W_base,
+                             const void* d_W_hyper, const int32_t* d_targets, float* d_nll, float* d_lse,
+                             void* stream) {
+  if (!ctx || !d_H || !d_W_base || !d_targets || !d_nll || !d_lse) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
+  if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
+  if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_extended_nll(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_targets, d_nll, d_lse,
+                                 static_cast<hipStream_t>(stream));
+}
+
 Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {
   if (!ctx) return Z2Z_EINVAL;
   switch (key) {

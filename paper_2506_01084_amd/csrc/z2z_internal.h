@@ -70,6 +70,8 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
 int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, float temperature, uint64_t seed, uint64_t step,
                                int32_t* token, float* logprob, hipStream_t s);
+int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                            const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s);
 
 #define Z2Z_HIP_TRY(expr)                      \
   do {                                         \
