@@ -264,13 +264,18 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const int V = c->cfg.V, cap = c->cfg.cap;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
 
-  // decode step: one hidden row per sequence -> the bandwidth-bound kernel
-  if (rows_per_seq == 1 && logits == nullptr && c->decode_ready && c->opt_decode_kernel != 1) {
+  // decode step: one hidden row per sequence -> the bandwidth-bound kernel (it can store the logits too)
+  if (rows_per_seq == 1 && c->decode_ready && c->opt_decode_kernel != 1) {
     int n_parts = z2z_logits_decode_parts(c);
     int rc = ensure_scratch(c, (size_t)n_parts * rows);
     if (rc != Z2Z_OK) return rc;
-    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, s);
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, logits, s);
     if (rc != Z2Z_OK) return rc;
+    if (logits && cap > 0) {
+      hipLaunchKernelGGL(logits_mask_kernel, dim3(rows), dim3(256), 0, s, logits, rows, rows_per_seq, V, cap,
+                         c->st.size);
+      Z2Z_HIP_TRY(hipGetLastError());
+    }
     return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
   }
 
@@ -333,7 +338,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   sp.seed = seed;
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
-  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, s);
+  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, nullptr, s);
   if (rc != Z2Z_OK) return rc;
   hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v, c->part_l,
                      c->part_i, n_parts, rows, token, logprob);

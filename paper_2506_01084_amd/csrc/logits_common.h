@@ -136,7 +136,7 @@ struct z2z_sample_params {
   uint64_t seed, step;
 };
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
-                             bool timed, const z2z_sample_params* sample, hipStream_t s);
+                             bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 bool z2z_logits_decode_ok(const z2z_ctx* c);
 int z2z_logits_decode_prepare(z2z_ctx* c);

@@ -58,6 +58,8 @@ struct DecodeArgs {
   float* part_v;
   float* part_l;
   float inv_temperature;
+  float* logits;          // MODE 2: [B, ld] raw logits out (columns at and beyond V + C_b are not written)
+  int32_t ld;
   uint32_t key0, key1;    // generator key: the seed
   uint32_t ctr2, ctr3;    // generator counter words 2, 3: the step
 };
@@ -132,10 +134,10 @@ __device__ __forceinline__ float gumbel_at(const DecodeArgs& a, Noise& n, int hr
   return -__logf(e);
 }
 
-template <bool SAMPLE>
+template <int MODE>
 __device__ __forceinline__ void fold_logit(const DecodeArgs& a, Triple& t, Draw& dr, Noise& n, float x, int hrow,
                                            int col) {
-  if (SAMPLE) {
+  if (MODE == 1) {
     const float z = x * a.inv_temperature;
     fold_value(t, z, col);
     const float p = z + gumbel_at(a, n, hrow, col);
@@ -149,7 +151,7 @@ __device__ __forceinline__ void fold_logit(const DecodeArgs& a, Triple& t, Draw&
   }
 }
 
-template <bool SAMPLE>
+template <int MODE>
 __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int group, unsigned char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -247,6 +249,19 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   }
   __syncthreads();
 
+  if (MODE == 2) {
+    // the unit's logits go out row-major per hidden row: transposed through the (now idle) slot area so
+    // that both the LDS accesses and the global stores run along consecutive addresses
+    constexpr int ST = D_BASE_UNIT + 1;
+    float* stage = slots;                                            // [64][257]
+    for (int i = tid; i < D_BASE_UNIT * 64; i += D_THREADS) stage[(i & 63) * ST + (i >> 6)] = tile[i];
+    __syncthreads();
+    for (int i = tid; i < 64 * D_BASE_UNIT; i += D_THREADS) {
+      const int jj = i / D_BASE_UNIT, r = i - jj * D_BASE_UNIT;
+      if (jj < n_h && v0 + r < a.V) a.logits[(size_t)(h0 + jj) * a.ld + v0 + r] = stage[jj * ST + r];
+    }
+    __syncthreads();
+  }
   // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 32 .. + 32, in increasing order
   Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);       // the slots are idle now
   Draw* xdr = reinterpret_cast<Draw*>(xch + D_THREADS);
@@ -258,9 +273,9 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   noise.group = -1;
   const int r_hi = min(D_BASE_UNIT, a.V - v0);
   for (int r = seg * 32; r < min(seg * 32 + 32, r_hi); ++r)
-    fold_logit<SAMPLE>(a, t, dr, noise, tile[r * 64 + j], h0 + j, v0 + r);
+    fold_logit<MODE>(a, t, dr, noise, tile[r * 64 + j], h0 + j, v0 + r);
   xch[tid] = t;
-  if (SAMPLE) xdr[tid] = dr;
+  if (MODE == 1) xdr[tid] = dr;
   __syncthreads();
   if (tid < 64 && j < n_h) {
     Triple r = xch[j];
@@ -269,7 +284,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     const size_t p = (size_t)(h0 + j) * a.n_parts + unit;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
-    if (SAMPLE) {
+    if (MODE == 1) {
       Draw d0 = xdr[j];
 #pragma unroll
       for (int s = 1; s < 8; ++s) merge_draw(d0, xdr[s * 64 + j]);
@@ -282,7 +297,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   }
 }
 
-template <int NQ, bool SAMPLE>
+template <int NQ, int MODE>
 __device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, int r1, int lane, int wave, Triple& t,
                                            Draw& dr) {
   Noise noise;
@@ -327,12 +342,16 @@ __device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, i
       sa += __shfl_xor(sa, o);
       sb += __shfl_xor(sb, o);
     }
-    fold_logit<SAMPLE>(a, t, dr, noise, sa, b, a.V + r);
-    if (has_b) fold_logit<SAMPLE>(a, t, dr, noise, sb, b, a.V + rb);
+    fold_logit<MODE>(a, t, dr, noise, sa, b, a.V + r);
+    if (has_b) fold_logit<MODE>(a, t, dr, noise, sb, b, a.V + rb);
+    if (MODE == 2 && lane == 0) {
+      a.logits[(size_t)b * a.ld + a.V + r] = sa;
+      if (has_b) a.logits[(size_t)b * a.ld + a.V + rb] = sb;
+    }
   }
 }
 
-template <bool SAMPLE>
+template <int MODE>
 __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, unsigned char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -347,15 +366,15 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
   if (r0 < r1) {
     const int nq = (a.d + 511) >> 9;
     if (nq <= 4)
-      hyper_rows<4, SAMPLE>(a, b, r0, r1, lane, wave, t, dr);
+      hyper_rows<4, MODE>(a, b, r0, r1, lane, wave, t, dr);
     else
-      hyper_rows<D_MAXQ, SAMPLE>(a, b, r0, r1, lane, wave, t, dr);
+      hyper_rows<D_MAXQ, MODE>(a, b, r0, r1, lane, wave, t, dr);
   }
   // every lane of a wave holds the same triple; waves took rows w, w + 8, ...: merging by value and
   // column restores the lowest-column rule
   if (lane == 0) {
     xch[wave] = t;
-    if (SAMPLE) xdr[wave] = dr;
+    if (MODE == 1) xdr[wave] = dr;
   }
   __syncthreads();
   if (tid == 0) {
@@ -365,7 +384,7 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
     const size_t p = (size_t)b * a.n_parts + a.n_base_units + u;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
-    if (SAMPLE) {
+    if (MODE == 1) {
       Draw d0 = xdr[0];
 #pragma unroll
       for (int s = 1; s < 8; ++s) merge_draw(d0, xdr[s]);
@@ -378,7 +397,7 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
   }
 }
 
-template <bool SAMPLE>
+template <int MODE>
 __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   // the hyper units come first: they read twice as many weight rows as a base unit, and the workgroups
@@ -386,19 +405,20 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
   const int n_hyper = a.B * a.units_per_seq;
   const int bid = blockIdx.x;
   if (bid < n_hyper) {
-    hyper_unit<SAMPLE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
+    hyper_unit<MODE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
     const int bu = bid - n_hyper;
-    base_unit<SAMPLE>(a, bu % a.n_base_units, bu / a.n_base_units, lds);
+    base_unit<MODE>(a, bu % a.n_base_units, bu / a.n_base_units, lds);
   }
 }
 
 }  // namespace
 
 // Parts written: n_base_units + units_per_seq per hidden row.  With `sample` the kernel works on
-// logit / temperature and also leaves the best perturbed value per part (part_v, part_l, part_i).
+// logit / temperature and also leaves the best perturbed value per part (part_v, part_l, part_i); with
+// `logits` (and no `sample`) it also stores every logit it computes, row-major [B, V + cap].
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
-                             bool timed, const z2z_sample_params* sample, hipStream_t s) {
+                             bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s) {
   DecodeArgs a;
   a.H = reinterpret_cast<const uint4*>(H);
   a.W_base = reinterpret_cast<const uint4*>(W_base);
@@ -416,6 +436,8 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.part_i = c->part_i;
   a.part_v = c->part_v;
   a.part_l = c->part_l;
+  a.logits = logits;
+  a.ld = a.V + a.cap;
   a.inv_temperature = sample ? 1.0f / sample->temperature : 1.0f;
   a.key0 = sample ? (uint32_t)sample->seed : 0u;
   a.key1 = sample ? (uint32_t)(sample->seed >> 32) : 0u;
@@ -425,10 +447,12 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.n_parts = *n_parts;
   const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  if (sample)
-    hipLaunchKernelGGL(logits_decode_kernel<true>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  if (logits)
+    hipLaunchKernelGGL(logits_decode_kernel<2>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  else if (sample)
+    hipLaunchKernelGGL(logits_decode_kernel<1>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   else
-    hipLaunchKernelGGL(logits_decode_kernel<false>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+    hipLaunchKernelGGL(logits_decode_kernel<0>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
     c->n_timed++;
@@ -447,9 +471,11 @@ bool z2z_logits_decode_ok(const z2z_ctx* c) {
 
 int z2z_logits_decode_prepare(z2z_ctx* c) {
   if (c->lds_limit < D_LDS) return Z2Z_EUNSUPPORTED;
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<false>),
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<0>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<true>),
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   return Z2Z_OK;
 }

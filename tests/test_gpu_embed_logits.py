@@ -366,13 +366,19 @@ def test_decode_kernel_small_shapes_every_row(B, N, V, d, M, cap):
         ctx.set_option(api.OPT_DECODE_KERNEL, kern)
         ctx.extended_logits(d_H, 1, d_E, d_W, am, mx, lse, None)
         torch.cuda.synchronize()
-        outs[kern] = (am.cpu().numpy().copy(), mx.cpu().numpy().copy(), lse.cpu().numpy().copy())
+        outs[kern] = (am.cpu().numpy().copy(), mx.cpu().numpy().copy(), lse.cpu().numpy().copy(), None)
+    # the decode kernel also writes the full logits when asked to
+    ctx.set_option(api.OPT_DECODE_KERNEL, 0)
+    full = torch.full((B, V + cap), 7.0, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, 1, d_E, d_W, am, mx, lse, full)
+    torch.cuda.synchronize()
+    outs[2] = (am.cpu().numpy().copy(), mx.cpu().numpy().copy(), lse.cpu().numpy().copy(), full.cpu().numpy())
     for b in range(B):
         Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
         r = oracle.extended_logits(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"], return_logits=True)
-        for kern in (0, 1):
-            a_, m_, l_ = outs[kern]
-            check_logits_rows(r, a_[b:b + 1], m_[b:b + 1], l_[b:b + 1], None)
+        for kern in (0, 1, 2):
+            a_, m_, l_, f_ = outs[kern]
+            check_logits_rows(r, a_[b:b + 1], m_[b:b + 1], l_[b:b + 1], None if f_ is None else f_[b:b + 1], V=V)
     ctx.close()
 
 
