@@ -19,6 +19,13 @@ while sharing no code.  Layout of one draw:
     word    = output[column & 3]
     u       = ((word >> 9) + 0.5) * 2**-23          (an odd multiple of 2**-24: exact in float32)
 
+Truncation (the usual top-k / nucleus filters, a reading as well): order the columns by logit / T,
+largest first, equal values by lower column.  With q = softmax(logits / T) over all existing columns,
+keep the first n columns of that order, n = min(k, n_p), where n_p is the smallest prefix whose q sums
+to at least p (both filters look at the full distribution; k <= 0 and p >= 1 switch a filter off; at least
+one column is kept).  The draw is the Gumbel-max over the kept columns with the same uniforms, i.e. a
+draw from q renormalised on the kept set.
+
 Besides the drawn column the oracle returns its log-probability under
 softmax(logits / T) and the gap between the two largest perturbed values (a
 draw is only comparable between two implementations when that gap exceeds
@@ -86,6 +93,49 @@ def sample_row(logits: np.ndarray, temperature: float, seed: int, step: int, row
     else:
         gap = float("inf")
     return dict(token=tok, logprob=float(z[tok] - lse), gap=gap, lse=float(lse), perturbed=pert)
+
+
+def kept_prefix(z: np.ndarray, top_k: int, top_p: float) -> dict:
+    """The truncation rule on one row of scaled logits z (float64).  Returns the kept columns (in order),
+    and how close the rule came to deciding otherwise: `order_gap` = z of the last kept column minus z of
+    the first dropped one (inf if nothing is dropped), `mass_gap` = distance of the cumulative probability
+    from top_p at the decisive prefixes (inf when the nucleus filter is off)."""
+    n_cols = z.shape[0]
+    order = np.lexsort((np.arange(n_cols), -z))          # by -z, then by column
+    m = z.max()
+    w = np.exp(z[order] - m)
+    cum = np.cumsum(w) / w.sum()
+    n_k = n_cols if top_k <= 0 else min(int(top_k), n_cols)
+    if top_p >= 1.0:
+        n_p, mass_gap = n_cols, float("inf")
+    else:
+        n_p = int(np.searchsorted(cum, top_p, side="left")) + 1      # smallest n with cum[n-1] >= p
+        n_p = min(n_p, n_cols)
+        below = cum[n_p - 2] if n_p >= 2 else 0.0
+        mass_gap = float(min(cum[n_p - 1] - top_p, top_p - below))
+    n = max(1, min(n_k, n_p))
+    order_gap = float(z[order[n - 1]] - z[order[n]]) if n < n_cols else float("inf")
+    if n_k < n_p:
+        mass_gap = float("inf")                                      # the nucleus filter did not decide
+    return dict(kept=order[:n], n=n, order_gap=order_gap, mass_gap=mass_gap)
+
+
+def sample_row_truncated(logits: np.ndarray, temperature: float, top_k: int, top_p: float, seed: int, step: int,
+                         row: int) -> dict:
+    """One draw from softmax(logits / temperature) truncated by top_k / top_p (see the module text)."""
+    z = logits / float(temperature)
+    kp = kept_prefix(z, top_k, top_p)
+    kept = kp["kept"]
+    pert = z + gumbel(uniforms(seed, step, row, z.shape[0]))
+    pk = pert[kept]
+    best = pk.max()
+    tok = int(kept[pk == best].min())                   # lowest column on exact ties
+    m = z[kept].max()
+    lse = m + np.log(np.exp(z[kept] - m).sum())
+    srt = np.sort(pk)
+    gap = float(srt[-1] - srt[-2]) if len(pk) > 1 else float("inf")
+    return dict(token=tok, logprob=float(z[tok] - lse), gap=gap, n_kept=kp["n"], kept=kept,
+                order_gap=kp["order_gap"], mass_gap=kp["mass_gap"], perturbed=pert)
 
 
 def extended_sample(H: np.ndarray, W_base: np.ndarray, W_hyper: np.ndarray, C: int, dtype: str,

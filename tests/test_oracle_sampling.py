@@ -88,3 +88,64 @@ def test_extended_sample_never_picks_a_missing_column():
         r = sampling.extended_sample(H, Wb, Wh, C, "f32", 1.0, 99, step, row0=8)
         assert (r["token"] < V + C).all() and (r["logprob"] <= 0).all()
         assert r["logits"].shape[1] == V + C
+
+
+# ---- truncation (top-k / nucleus) ----------------------------------------------------------------------
+def _brute_kept(z, k, p):
+    """The rule spelled out with Python sorting and a running sum."""
+    cols = sorted(range(len(z)), key=lambda v: (-z[v], v))
+    q = np.exp(z - z.max())
+    q = q / q.sum()
+    n_p, acc = len(cols), 0.0
+    if p < 1.0:
+        for i, v in enumerate(cols):
+            acc += q[v]
+            if acc >= p:
+                n_p = i + 1
+                break
+    n_k = len(cols) if k <= 0 else min(k, len(cols))
+    return cols[:max(1, min(n_k, n_p))]
+
+
+def test_kept_prefix_against_brute_force_and_ties():
+    rng = np.random.default_rng(2)
+    for trial in range(200):
+        n = int(rng.integers(1, 12))
+        z = np.round(rng.normal(size=n) * 2) / 2            # many exact ties
+        k = int(rng.integers(0, n + 2))
+        p = float(rng.choice([0.05, 0.3, 0.62, 0.9, 0.999, 1.0]))
+        got = sampling.kept_prefix(z, k, p)
+        assert got["kept"].tolist() == _brute_kept(z, k, p), (z, k, p)
+        assert got["n"] == len(got["kept"]) >= 1
+
+
+def test_truncated_draws_limits():
+    rng = np.random.default_rng(4)
+    logits = rng.normal(size=40) * 2
+    am = int(np.argmax(logits))
+    for step in range(30):
+        full = sample_row(logits, 0.9, 3, step, 1)
+        same = sampling.sample_row_truncated(logits, 0.9, 0, 1.0, 3, step, 1)             # both filters off
+        assert same["token"] == full["token"] and abs(same["logprob"] - full["logprob"]) < 1e-12
+        assert sampling.sample_row_truncated(logits, 0.9, 1, 1.0, 3, step, 1)["token"] == am      # k = 1
+        assert sampling.sample_row_truncated(logits, 0.9, 0, 1e-9, 3, step, 1)["token"] == am     # p -> 0
+        r = sampling.sample_row_truncated(logits, 0.9, 5, 0.8, 3, step, 1)
+        assert r["token"] in r["kept"] and r["n_kept"] <= 5 and r["logprob"] <= 0
+
+
+def test_truncated_draws_follow_the_renormalised_distribution():
+    logits = np.array([2.0, 0.5, -1.0, 1.5, 0.0, 3.0, -2.5, 1.0, 0.25, 2.9])
+    T, k, p = 1.3, 6, 0.85
+    z = logits / T
+    kept = sampling.kept_prefix(z, k, p)["kept"]
+    q = np.exp(z[kept] - z[kept].max())
+    q /= q.sum()
+    n = 20000
+    counts = dict.fromkeys(kept.tolist(), 0)
+    for step in range(n):
+        r = sampling.sample_row_truncated(logits, T, k, p, 21, step, 0)
+        counts[r["token"]] += 1                              # a KeyError here would be a draw outside the kept set
+        assert abs(r["logprob"] - np.log(q[kept.tolist().index(r["token"])])) < 1e-12
+    c = np.array([counts[v] for v in kept.tolist()])
+    chi2 = ((c - n * q) ** 2 / (n * q)).sum()
+    assert chi2 < 30.0, chi2                                 # far beyond the 99.9 % point for <= 5 degrees of freedom
