@@ -247,6 +247,22 @@ def run_decode_workload(args, torch, api, wl):
     sample_us = (time.perf_counter() - t0) * 1e6 / timed
     assert int(d_st.abs().sum()) == 0
 
+    # ... and with the top-k / nucleus filters in front of the draw (the logits go through library scratch)
+    def step_filtered(s):
+        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
+        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+        ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 2506, s, d_am, d_lp, top_k=50, top_p=0.9)
+
+    for s in range(args.warmup):
+        step_filtered(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, n_steps):
+        step_filtered(s)
+    torch.cuda.synchronize()
+    filtered_us = (time.perf_counter() - t0) * 1e6 / timed
+    assert int(d_st.abs().sum()) == 0
+
     sizes = size_view.cpu().numpy()
     us = dt * 1e6 / timed
     bytes_step = 2.0 * d * (V + float(sizes.sum())) + 2.0 * B * d
@@ -256,6 +272,7 @@ def run_decode_workload(args, torch, api, wl):
     k_gbs = bytes_step / (k_us * 1e-6) / 1e9
     return dict(workload=cfg["name"], steps=timed, us_per_step=us, graph_us_per_step=graph_us,
                 graph_frac=bytes_step / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                sample_topk50_topp09_us_per_step=filtered_us,
                 sample_us_per_step=sample_us, sample_frac=bytes_step / (sample_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
                 peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()),
                 roofline={"bound": "hbm", "kernel": "logits_decode_kernel (64 rows, config 3)", "achieved": k_gbs,

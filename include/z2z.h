@@ -17,7 +17,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     and return without synchronising, except z2z_create / z2z_destroy.
  *   - One context serves B independent sequences (section 2.4: each document is compressed on its
- *     own).  The context owns each sequence's codebook; all four calls read the same codebook,
+ *     own).  The context owns each sequence's codebook; all calls read the same codebook,
  *     so the embedding side and the unembedding side always see the same hypertoken set
  *     (section 2.3, "Consistent Vocabulary Updates").
  *   - IDs: 0..V-1 are base tokens; V+i is codebook entry i of that sequence, in creation order.
@@ -153,15 +153,23 @@ int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t row
  * v & 3 of Philox4x32-10 (Salmon et al., SC'11) with counter (v >> 2, r, step low, step high) and key
  * (seed low, seed high), u = ((word >> 9) + 0.5) * 2^-23.  The same (seed, step) gives the same draws; a
  * generation loop passes its step number.
+ * Filters (the usual top-k / nucleus truncation): order the columns by logit, largest first, equal logits by
+ * lower column; with q = softmax(logit / temperature) over all existing columns keep the first
+ * n = min(top_k, n_p) columns, n_p the smallest prefix whose q sums to at least top_p (both filters look at the
+ * full distribution; at least one column is kept); the draw is the same argmax restricted to the kept
+ * columns, i.e. a draw from q renormalised on them.  top_k <= 0 and top_p >= 1 switch a filter off; with both
+ * off nothing is stored, otherwise the rows' logits go through rows * (V + cap) floats of library scratch.
  *   d_token   [rows] int32 out
- *   d_logprob [rows] float out or NULL: ln of the drawn token's probability under softmax(logit / temperature)
- *   temperature  > 0 and finite (else Z2Z_EINVAL)
+ *   d_logprob [rows] float out or NULL: ln of the drawn token's probability under the (renormalised)
+ *             distribution it was drawn from
+ *   temperature  > 0 and finite, top_p > 0 (else Z2Z_EINVAL)
  * Built for the generation step: rows_per_seq must be 1 and the context bf16 with d a multiple of 128 and
  * d <= 4096; anything else returns Z2Z_EUNSUPPORTED.  Scratch as for z2z_extended_logits.
  */
 int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
-                        const void* d_W_base, const void* d_W_hyper, float temperature, uint64_t seed,
-                        uint64_t step, int32_t* d_token, float* d_logprob, void* stream);
+                        const void* d_W_base, const void* d_W_hyper, float temperature, int32_t top_k,
+                        float top_p, uint64_t seed, uint64_t step, int32_t* d_token, float* d_logprob,
+                        void* stream);
 
 /* extended_nll.  The per-position term of the training objective over compressed sequences (section 2.4,
  * the next-token loss on z = LZW(y)): for hidden row r with target code t = d_targets[r],

@@ -56,8 +56,8 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_void_p]
-    lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float,
-                                        ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p, c_void_p]
+    lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_int32,
+                                        c_float, ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_nll.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]
     lib.z2z_set_option.argtypes = [c_void_p, c_int32, c_int32]
@@ -192,13 +192,14 @@ class Context:
 
     def extended_sample(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
                         temperature: float, seed: int, step: int, token: torch.Tensor,
-                        logprob: Optional[torch.Tensor] = None) -> None:
+                        logprob: Optional[torch.Tensor] = None, top_k: int = 0, top_p: float = 1.0) -> None:
         rows = H.shape[0]
         assert H.shape[1] == self.d and tuple(W_base.shape) == (self.V, self.d)
         assert token.numel() == rows and (logprob is None or logprob.numel() == rows)
         _check(self._lib.z2z_extended_sample(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq,
                                              _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
-                                             float(temperature), int(seed), int(step), _ptr(token, torch.int32),
+                                             float(temperature), int(top_k), float(top_p), int(seed), int(step),
+                                             _ptr(token, torch.int32),
                                              _ptr(logprob, torch.float32), _stream()), "z2z_extended_sample")
 
     def extended_nll(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,

@@ -324,26 +324,51 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
 }
 
 int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
-                               const void* W_hyper, float temperature, uint64_t seed, uint64_t step,
-                               int32_t* token, float* logprob, hipStream_t s) {
+                               const void* W_hyper, float temperature, int32_t top_k, float top_p, uint64_t seed,
+                               uint64_t step, int32_t* token, float* logprob, hipStream_t s) {
   // built for the generation step: one hidden row per sequence, the bandwidth-bound kernel
   if (rows_per_seq != 1 || !c->decode_ready) return Z2Z_EUNSUPPORTED;
   int n_parts = z2z_logits_decode_parts(c);
   int rc = ensure_scratch(c, (size_t)n_parts * rows);
-  if (rc != Z2Z_OK) return rc;
-  rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
   z2z_sample_params sp;
   sp.temperature = temperature;
   sp.seed = seed;
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
-  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, nullptr, s);
+  if (top_k <= 0 && top_p >= 1.0f) {
+    // no filter: the draw is folded into the kernel that computes the logits, which are never stored
+    rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
+    if (rc != Z2Z_OK) return rc;
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, nullptr, s);
+    if (rc != Z2Z_OK) return rc;
+    hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v,
+                       c->part_l, c->part_i, n_parts, rows, token, logprob);
+    Z2Z_HIP_TRY(hipGetLastError());
+    return Z2Z_OK;
+  }
+  // filters: the kernel stores the rows' logits (rows x (V + cap) floats of library scratch), the merge
+  // gives the row maxima, and one workgroup per row selects the kept prefix and draws
+  if (!c->trunc_ready) return Z2Z_EUNSUPPORTED;
+  const size_t need = (size_t)rows * (size_t)(c->cfg.V + c->cfg.cap);
+  if (need > c->sample_logits_capacity) {
+    if (c->sample_logits) (void)hipFree(c->sample_logits);
+    if (c->row_max) (void)hipFree(c->row_max);
+    c->sample_logits = nullptr;
+    c->row_max = nullptr;
+    c->sample_logits_capacity = 0;
+    if (hipMalloc(&c->sample_logits, need * sizeof(float)) != hipSuccess) return Z2Z_ENOMEM;
+    // the row maxima, followed by the first pass's per-slice bin totals
+    if (hipMalloc(&c->row_max, ((size_t)rows + z2z_sample_truncated_partial_floats(rows)) * sizeof(float)) != hipSuccess)
+      return Z2Z_ENOMEM;
+    c->sample_logits_capacity = need;
+  }
+  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, c->sample_logits, s);
   if (rc != Z2Z_OK) return rc;
-  hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v, c->part_l,
-                     c->part_i, n_parts, rows, token, logprob);
-  Z2Z_HIP_TRY(hipGetLastError());
-  return Z2Z_OK;
+  rc = launch_combine(c, n_parts, rows, nullptr, c->row_max, nullptr, s);
+  if (rc != Z2Z_OK) return rc;
+  return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, c->row_max + rows, &sp, top_k, top_p,
+                                     token, logprob, s);
 }
 
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,

@@ -96,6 +96,32 @@ __device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&
   }
 }
 
+// ---- the counter-based generator of the sampling kernels: Philox4x32-10 (Salmon et al., SC'11) -------
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+    c = uint4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
+  }
+  return c;
+}
+
+// The Gumbel value -ln(-ln u) of one generator word, u = ((w >> 9) + 0.5) * 2^-23.  u and 1 - u are both
+// exact in float.  e = -ln u has to be accurate relative to itself where it is small (u next to 1: the
+// largest perturbations, the ones that win): there it is the series of -ln(1 - x); elsewhere the hardware
+// logarithm's absolute error of ~1e-7 is relative 1e-5 at worst.  The outer logarithm only needs absolute
+// accuracy.
+__device__ __forceinline__ float gumbel_from_word(uint32_t w) {
+  const float x = ((float)(0x7FFFFFu - (w >> 9)) + 0.5f) * 0x1p-23f;        // 1 - u
+  const float e = x < 0.015625f ? x * (1.f + x * (0.5f + x * (0.33333334f + 0.25f * x))) : -__logf(1.f - x);
+  return -__logf(e);
+}
+
 // Arguments of one tile-kernel launch (base part or hyper part).
 struct LogitsArgs {
   const void* H;          // [rows, d]
@@ -137,6 +163,10 @@ struct z2z_sample_params {
 };
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s);
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_max, int32_t rows,
+                                float* partial, const z2z_sample_params* sp, int32_t top_k, float top_p,
+                                int32_t* token, float* logprob, hipStream_t s);
+size_t z2z_sample_truncated_partial_floats(int32_t rows);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 bool z2z_logits_decode_ok(const z2z_ctx* c);
 int z2z_logits_decode_prepare(z2z_ctx* c);

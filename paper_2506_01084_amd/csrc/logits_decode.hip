@@ -96,20 +96,6 @@ __device__ __forceinline__ void merge_draw(Draw& a, const Draw& b) {
   if (b.v > a.v || (b.v == a.v && b.i < a.i)) a = b;
 }
 
-__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    if (r > 0) {
-      k0 += 0x9E3779B9u;
-      k1 += 0xBB67AE85u;
-    }
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
-    c = uint4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
-  }
-  return c;
-}
-
 // Generator words for the columns 4 * group .. 4 * group + 3 of one hidden row are produced together;
 // a thread that walks consecutive columns keeps them until it leaves the group.
 struct Noise {
@@ -125,13 +111,7 @@ __device__ __forceinline__ float gumbel_at(const DecodeArgs& a, Noise& n, int hr
   }
   const int k = col & 3;
   const uint32_t w = k == 0 ? n.words.x : (k == 1 ? n.words.y : (k == 2 ? n.words.z : n.words.w));
-  // u = ((w >> 9) + 0.5) * 2^-23 and 1 - u are both exact in float.  e = -ln u has to be accurate relative
-  // to itself where it is small (u next to 1: the largest perturbations, the ones that win): there it is
-  // the series of -ln(1 - x); elsewhere the hardware logarithm's absolute error of ~1e-7 is relative 1e-5
-  // at worst.  The outer logarithm only needs absolute accuracy.
-  const float x = ((float)(0x7FFFFFu - (w >> 9)) + 0.5f) * 0x1p-23f;        // 1 - u
-  const float e = x < 0.015625f ? x * (1.f + x * (0.5f + x * (0.33333334f + 0.25f * x))) : -__logf(1.f - x);
-  return -__logf(e);
+  return gumbel_from_word(w);
 }
 
 template <int MODE>

@@ -1,0 +1,620 @@
+// Truncated sampling for the generation step (gfx950): top-k / nucleus filters on the joint softmax, then
+// the Gumbel-max draw among the kept columns.
+//
+// Section 2.3 of the zip2zip paper, step 9, draws the next token from the joint distribution over base
+// tokens and hypertokens; the filters are the usual ones and not the paper's.  Order the columns by logit
+// (largest first, equal logits by lower column).  With q = softmax(logit / T) over all existing columns,
+// the kept set is the first n columns of that order, n = min(k, n_p), n_p the smallest prefix whose q sums
+// to at least p.  The draw is argmax over the kept columns of logit / T - ln(-ln u) with the same
+// generator coordinates as the untruncated draw.
+//
+// Input: the row's logits as the decode kernel stored them, and the row maximum.  One workgroup per hidden
+// row finds the last kept element of the order, the "cut", without sorting the row:
+//   1. histogram passes over the row.  The cut lies in a half-open value interval [lo, hi) (at first
+//      everything); the interval is split into 32 bins by value, every lane counts elements and sums
+//      exp((x - max) / T) per bin in its own LDS column (no two lanes share an address, so the LDS adds
+//      never conflict), the columns are added up, and a walk over the 32 bins from the top finds the bin
+//      in which the count reaches k or the mass reaches p * total: that bin is the next interval, what lies
+//      above it is kept for certain.  The first pass uses bins of half a unit of logit / T below the
+//      maximum, which also yields the total mass.
+//   2. once the interval holds at most 4096 elements they are collected into LDS, sorted (bitonic, by value
+//      then column), their masses scanned in that order, and the cut is the first position where count or
+//      mass reaches its target.
+//   3. an interval that cannot shrink (one float value, more than 4096 equal logits) is cut by column: one
+//      ordered pass counts the equal elements up to the number still wanted.
+//   4. the draw: one more pass, Gumbel-max over the elements at or before the cut.
+#include "logits_common.h"
+
+namespace {
+
+using namespace z2z_logits;
+
+constexpr int T_THREADS = 512;
+constexpr int T_WAVES = T_THREADS / 64;
+constexpr int T_BINS = 32;
+constexpr int T_CAND = 4096;
+constexpr int T_SPLIT = 4;                                     // workgroups per row in the first pass
+constexpr int T_CHUNK = T_THREADS * 4;                         // columns per step: 4 consecutive ones per thread
+constexpr int T_HIST_BYTES = T_WAVES * T_BINS * 64 * 4;        // one histogram (counts or masses): 64 KiB
+constexpr int T_LDS = 2 * T_HIST_BYTES + 1024;                 // + edges, bin totals, state
+
+struct TruncArgs {
+  const float* logits;     // [rows, ld]
+  const int32_t* size;     // [B]
+  const float* row_max;    // [rows]
+  int32_t V, cap, ld;
+  float inv_temperature;
+  int32_t top_k;           // <= 0: off
+  float top_p;             // >= 1: off
+  uint32_t key0, key1, ctr2, ctr3;
+  int32_t* token;          // [rows]
+  float* logprob;          // [rows] or nullptr
+};
+
+struct State {              // written by thread 0, read by all after a barrier
+  float lo, hi;             // the cut lies among the elements with lo <= x < hi
+  uint32_t cnt_above;       // elements with x >= hi: kept for certain
+  float mass_above;
+  float total_mass;
+  uint32_t pop;             // elements inside [lo, hi)
+  int next;                 // 0 another histogram pass, 1 collect and sort, 2 cut by column, 3 everything is kept,
+                            // 4 find the interval's smallest and largest element first
+  float cut_x;
+  int cut_c;
+  float kept_mass;
+};
+
+__device__ __forceinline__ bool before(float xa, int ca, float xb, int cb) {   // a precedes b in the order
+  return xa > xb || (xa == xb && ca < cb);
+}
+
+// One histogram pass over the columns [c_begin, c_end) of a row (c_begin a multiple of 4): elements with
+// lo <= x < hi are counted, and their masses summed, per bin of `edges` (edges[0] = hi >= ... >= edges[T_BINS]
+// = lo; edges[T_BINS + 1], edges[T_BINS + 2]: start and density of the inner edges, for a first guess).
+// Ends with the bin totals in bin_c / bin_m (all threads must call it; contains barriers).
+__device__ __forceinline__ void histogram_pass(const float* x, int c_begin, int c_end, float lo, float hi, float m,
+                                               float inv_t, const float* edges, uint32_t* hc, float* hm,
+                                               uint32_t* bin_c, float* bin_m) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < T_WAVES * T_BINS * 64; i += T_THREADS) {
+    hc[i] = 0u;
+    hm[i] = 0.f;
+  }
+  __syncthreads();
+  const float top = edges[T_BINS + 1], inv_w = edges[T_BINS + 2];
+  uint32_t* my_c = hc + wave * T_BINS * 64 + lane;
+  float* my_m = hm + wave * T_BINS * 64 + lane;
+  for (int c0 = c_begin + tid * 4; c0 < c_end; c0 += T_CHUNK) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = c0 + j;
+      if (c < c_end) {
+        const float v = x[c];
+        if (v >= lo && v < hi) {
+          // bin b holds edges[b + 1] <= v < edges[b]: a guess from the spacing, settled by comparing
+          // with the edges themselves (what decides is the same stored values in every pass)
+          int b = (int)fminf(fmaxf((top - v) * inv_w, 0.f), (float)(T_BINS - 1));
+          while (b < T_BINS - 1 && v < edges[b + 1]) ++b;
+          while (b > 0 && v >= edges[b]) --b;
+          atomicAdd(&my_c[b * 64], 1u);            // this lane's own column: never contended
+          atomicAdd(&my_m[b * 64], __expf((v - m) * inv_t));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // bin totals: 16 threads per bin, each adds 32 of the 512 columns
+  {
+    const int b = tid >> 4, part = tid & 15;
+    uint32_t sc = 0;
+    float sm = 0.f;
+    for (int i = part; i < T_WAVES * 64; i += 16) {
+      const int w = i >> 6, l = i & 63;
+      sc += hc[(w * T_BINS + b) * 64 + l];
+      sm += hm[(w * T_BINS + b) * 64 + l];
+    }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+      sc += __shfl_xor(sc, off);
+      sm += __shfl_xor(sm, off);
+    }
+    if (part == 0) {
+      bin_c[b] = sc;
+      bin_m[b] = sm;
+    }
+  }
+  __syncthreads();
+}
+
+// The edges of the first pass: bins of half a unit of logit / T below the maximum, the last bin takes all
+// the rest; the upper end is a finite value no element reaches.  Both kernels below compute them alike.
+__device__ __forceinline__ void first_pass_edges(float m, float inv_t, float* edges) {
+  const float w0 = 0.5f / inv_t;
+  edges[0] = m + fmaxf(fabsf(m), 1.f) * 0x1p-10f;
+  for (int i = 1; i < T_BINS; ++i) edges[i] = m - (float)i * w0;
+  edges[T_BINS] = -INFINITY;
+  edges[T_BINS + 1] = m;
+  edges[T_BINS + 2] = 1.0f / w0;
+}
+
+// First pass, the one that classifies every element, spread over T_SPLIT workgroups per row: each takes a
+// slice of the columns and leaves its bin totals in `partial` [rows][T_SPLIT][2][T_BINS].
+__global__ void __launch_bounds__(T_THREADS) sample_first_pass_kernel(TruncArgs a, float* partial) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  uint32_t* hc = reinterpret_cast<uint32_t*>(lds);
+  float* hm = reinterpret_cast<float*>(lds + T_HIST_BYTES);
+  float* edges = reinterpret_cast<float*>(lds + 2 * T_HIST_BYTES);
+  uint32_t* bin_c = reinterpret_cast<uint32_t*>(edges + 40);
+  float* bin_m = reinterpret_cast<float*>(bin_c + T_BINS);
+  const int r = blockIdx.x / T_SPLIT, part = blockIdx.x % T_SPLIT;
+  const int C = min(max(a.size[r], 0), a.cap);
+  const int n = a.V + C;
+  const float m = a.row_max[r];
+  if (threadIdx.x == 0) first_pass_edges(m, a.inv_temperature, edges);
+  __syncthreads();
+  const int per = ((n + T_SPLIT - 1) / T_SPLIT + 3) & ~3;
+  const int c_begin = min(part * per, n), c_end = min(c_begin + per, n);
+  histogram_pass(a.logits + (size_t)r * a.ld, c_begin, c_end, -INFINITY, edges[0], m, a.inv_temperature, edges, hc,
+                 hm, bin_c, bin_m);
+  float* out = partial + ((size_t)r * T_SPLIT + part) * 2 * T_BINS;
+  if (threadIdx.x < T_BINS) {
+    out[threadIdx.x] = __uint_as_float(bin_c[threadIdx.x]);
+    out[T_BINS + threadIdx.x] = bin_m[threadIdx.x];
+  }
+}
+
+__global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a, const float* partial) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  uint32_t* hc = reinterpret_cast<uint32_t*>(lds);                         // [wave][bin][lane]
+  float* hm = reinterpret_cast<float*>(lds + T_HIST_BYTES);                // [wave][bin][lane]
+  float* edges = reinterpret_cast<float*>(lds + 2 * T_HIST_BYTES);         // [T_BINS + 1]
+  uint32_t* bin_c = reinterpret_cast<uint32_t*>(edges + 40);               // [T_BINS]
+  float* bin_m = reinterpret_cast<float*>(bin_c + T_BINS);                 // [T_BINS]
+  State* st = reinterpret_cast<State*>(bin_m + T_BINS);
+  uint32_t* misc = reinterpret_cast<uint32_t*>(st + 1);                    // counters, wave totals (>= 32 words)
+  // the candidate arrays reuse the histograms
+  float* cand_x = reinterpret_cast<float*>(lds);                           // [T_CAND]
+  int* cand_c = reinterpret_cast<int*>(lds + T_CAND * 4);                  // [T_CAND]
+  float* cand_w = reinterpret_cast<float*>(lds + T_CAND * 8);              // [T_CAND] masses, then their prefix sums
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int r = blockIdx.x;
+  const int C = min(max(a.size[r], 0), a.cap);
+  const int n = a.V + C;
+  const float* x = a.logits + (size_t)r * a.ld;
+  const float m = a.row_max[r];
+  const float inv_t = a.inv_temperature;
+  const uint32_t k_eff = a.top_k > 0 ? (uint32_t)min(a.top_k, n) : (uint32_t)n;
+  const bool use_p = a.top_p < 1.0f;
+
+  if (tid == 0) {
+    first_pass_edges(m, inv_t, edges);
+    st->lo = -INFINITY;
+    st->hi = edges[0];
+    st->cnt_above = 0;
+    st->mass_above = 0.f;
+    st->total_mass = 0.f;
+    st->pop = (uint32_t)n;
+    st->next = 0;
+  }
+  __syncthreads();
+
+  // ---- 1. histogram passes ---------------------------------------------------------------------------
+  for (int pass = 0; pass < 40; ++pass) {
+    if (st->next == 4) {
+      // A pass that put the whole interval into one bin: the elements may be a tight cluster or all equal.
+      // Their smallest and largest value give the next interval, or show that one value is all there is.
+      const float blo = st->lo, bhi = st->hi;
+      float vmin = INFINITY, vmax = -INFINITY;
+      for (int c = tid; c < n; c += T_THREADS) {
+        const float v = x[c];
+        if (v >= blo && v < bhi) {
+          vmin = fminf(vmin, v);
+          vmax = fmaxf(vmax, v);
+        }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        vmin = fminf(vmin, __shfl_xor(vmin, off));
+        vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+      }
+      float* red = reinterpret_cast<float*>(misc + 8);
+      if (lane == 0) {
+        red[wave] = vmin;
+        red[T_WAVES + wave] = vmax;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        for (int w = 1; w < T_WAVES; ++w) {
+          vmin = fminf(vmin, red[w]);
+          vmax = fmaxf(vmax, red[T_WAVES + w]);
+        }
+        if (vmin == vmax) {
+          st->lo = vmin;                             // every element of the interval equals this value
+          st->next = 2;
+        } else {
+          const float nhi = vmax + fmaxf(fabsf(vmax), 1.f) * 0x1p-20f;    // just above the largest element
+          const float w = (nhi - vmin) / (float)T_BINS;
+          st->lo = vmin;
+          st->hi = nhi;
+          edges[0] = nhi;
+          for (int i = 1; i < T_BINS; ++i) edges[i] = fmaxf(nhi - (float)i * w, vmin);
+          edges[T_BINS] = vmin;
+          edges[T_BINS + 1] = nhi;
+          edges[T_BINS + 2] = w > 0.f ? 1.0f / w : 0.f;
+          st->next = 0;
+        }
+      }
+      __syncthreads();
+      continue;
+    }
+    if (st->next != 0) break;                       // uniform: read after a barrier
+    const float lo = st->lo, hi = st->hi;
+    if (pass == 0) {
+      // the first pass was done by sample_first_pass_kernel: add up its slices (fixed order)
+      if (tid < T_BINS) {
+        uint32_t sc = 0;
+        float sm = 0.f;
+        for (int p = 0; p < T_SPLIT; ++p) {
+          const float* in = partial + ((size_t)r * T_SPLIT + p) * 2 * T_BINS;
+          sc += __float_as_uint(in[tid]);
+          sm += in[T_BINS + tid];
+        }
+        bin_c[tid] = sc;
+        bin_m[tid] = sm;
+      }
+      __syncthreads();
+    } else {
+      histogram_pass(x, 0, n, lo, hi, m, inv_t, edges, hc, hm, bin_c, bin_m);
+    }
+    if (tid == 0) {
+      if (pass == 0) {
+        float tot = 0.f;
+        for (int b = 0; b < T_BINS; ++b) tot += bin_m[b];
+        st->total_mass = tot;
+      }
+      const float target = use_p ? a.top_p * st->total_mass : INFINITY;
+      uint32_t cnt = st->cnt_above;
+      float mass = st->mass_above;
+      int hit = -1;
+      for (int b = 0; b < T_BINS; ++b) {
+        if (bin_c[b] == 0) continue;
+        if (cnt + bin_c[b] >= k_eff || mass + bin_m[b] >= target) {
+          hit = b;
+          break;
+        }
+        cnt += bin_c[b];
+        mass += bin_m[b];
+      }
+      if (hit < 0) {
+        // neither target is reached inside the interval (k covers it, and rounding kept the mass below
+        // p * total): everything down to the interval's lower end is kept
+        st->next = 3;
+        st->cnt_above = cnt;
+        st->mass_above = mass;
+      } else {
+        const float nhi = edges[hit];
+        const float nlo = edges[hit + 1];
+        const bool no_progress = bin_c[hit] == st->pop;
+        st->cnt_above = cnt;
+        st->mass_above = mass;
+        st->pop = bin_c[hit];
+        st->hi = nhi;
+        st->lo = nlo;
+        if (bin_c[hit] <= (uint32_t)T_CAND) {
+          st->next = 1;
+        } else if (no_progress && !isinf(nlo)) {
+          st->next = 4;
+        } else {
+          // split [nlo, nhi) again; an open lower end (the far tail) is given a span that grows with every
+          // pass.
+          const float bot = isinf(nlo) ? nhi - 64.f / inv_t * exp2f((float)(2 * pass)) : nlo;
+          const float w = (nhi - bot) / (float)T_BINS;
+          bool shrinks = false;
+          edges[0] = nhi;
+          for (int i = 1; i < T_BINS; ++i) {
+            edges[i] = fmaxf(nhi - (float)i * w, bot);
+            if (edges[i] < nhi && edges[i] > bot) shrinks = true;
+          }
+          edges[T_BINS] = nlo;
+          edges[T_BINS + 1] = nhi;
+          edges[T_BINS + 2] = w > 0.f ? 1.0f / w : 0.f;
+          if (!isinf(nlo) && !shrinks) st->next = 4;   // nothing left to split by value: look at the elements
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (st->next == 0) {                               // pass limit: cannot happen for finite logits; keep the prefix found
+    if (tid == 0) st->next = st->pop <= (uint32_t)T_CAND ? 1 : 2;
+    __syncthreads();
+  }
+
+  const int mode = st->next;
+  const float lo = st->lo, hi = st->hi;
+  const float target = use_p ? a.top_p * st->total_mass : INFINITY;
+
+  bool all_in = false;
+  if (mode == 1) {
+    // ---- 2. collect, sort, scan ------------------------------------------------------------------------
+    // if what lies above the interval fits into the list as well, it is collected too: the sorted list then
+    // holds every kept element and the draw needs no further pass over the row
+    all_in = st->cnt_above + st->pop <= (uint32_t)T_CAND;
+    __syncthreads();
+    if (tid == 0) misc[0] = 0u;
+    __syncthreads();
+    for (int c0 = tid * 4; c0 < n; c0 += T_CHUNK) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = c0 + j;
+        if (c < n) {
+          const float v = x[c];
+          if (v >= lo && (all_in || v < hi)) {
+            const uint32_t slot = atomicAdd(&misc[0], 1u);
+            if (slot < (uint32_t)T_CAND) {
+              cand_x[slot] = v;
+              cand_c[slot] = c;
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const int cnt = (int)min(misc[0], (uint32_t)T_CAND);
+    int n2 = 2;
+    while (n2 < cnt) n2 <<= 1;
+    for (int i = cnt + tid; i < n2; i += T_THREADS) {
+      cand_x[i] = -INFINITY;
+      cand_c[i] = 0x7FFFFFFF;
+    }
+    __syncthreads();
+    for (int k = 2; k <= n2; k <<= 1) {
+      for (int j = k >> 1; j >= 1; j >>= 1) {
+        for (int i = tid; i < n2; i += T_THREADS) {
+          const int p = i ^ j;
+          if (p > i) {
+            const float xa = cand_x[i], xb = cand_x[p];
+            const int ca = cand_c[i], cb = cand_c[p];
+            const bool in_order = ((i & k) == 0) ? !before(xb, cb, xa, ca) : !before(xa, ca, xb, cb);
+            if (!in_order) {
+              cand_x[i] = xb;
+              cand_c[i] = cb;
+              cand_x[p] = xa;
+              cand_c[p] = ca;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+    // masses in sorted order and their inclusive prefix sums: each thread owns a contiguous run
+    const int per = (n2 + T_THREADS - 1) / T_THREADS;
+    const int i0 = tid * per;
+    float run = 0.f;
+    for (int i = i0; i < min(i0 + per, n2); ++i) {
+      run += i < cnt ? __expf((cand_x[i] - m) * inv_t) : 0.f;
+      cand_w[i] = run;
+    }
+    // exclusive prefix of the run totals over the block
+    float incl = run;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const float o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    float* wave_tot = reinterpret_cast<float*>(misc + 8);
+    if (lane == 63) wave_tot[wave] = incl;
+    if (tid == 0) misc[1] = 0x7FFFFFFFu;
+    __syncthreads();
+    float base = incl - run;
+    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+    const uint32_t cnt_above = all_in ? 0u : st->cnt_above;
+    const float mass_above = all_in ? 0.f : st->mass_above;
+    for (int i = i0; i < min(i0 + per, cnt); ++i) {
+      const float cum = mass_above + base + cand_w[i];
+      if (cnt_above + (uint32_t)i + 1u >= k_eff || cum >= target) {
+        atomicMin(&misc[1], (uint32_t)i);
+        break;
+      }
+    }
+    __syncthreads();
+    for (int i = i0; i < min(i0 + per, n2); ++i) cand_w[i] += base;     // now inclusive over the whole list
+    __syncthreads();
+    if (tid == 0) {
+      int idx = misc[1] == 0x7FFFFFFFu ? cnt - 1 : (int)misc[1];       // rounding kept the mass below its target
+      idx = max(idx, 0);
+      st->cut_x = cand_x[idx];
+      st->cut_c = cand_c[idx];
+      st->kept_mass = mass_above + cand_w[idx];
+      misc[5] = (uint32_t)idx;
+    }
+    __syncthreads();
+  } else if (mode == 2) {
+    // ---- 3. more than T_CAND equal logits: the cut is a column among them -------------------------------
+    if (tid == 0) {
+      const float w = __expf((lo - m) * inv_t);
+      uint32_t want = k_eff - st->cnt_above;
+      if (use_p) {
+        const float need = (target - st->mass_above) / w;
+        const uint32_t by_mass = need <= 1.f ? 1u : (need >= 4.0e9f ? 0xFFFFFFFFu : (uint32_t)ceilf(need));
+        want = min(want, by_mass);
+      }
+      want = max(1u, min(want, st->pop));
+      misc[2] = want;
+      misc[3] = 0u;                                  // equal elements seen so far
+      misc[4] = 0u;                                  // done flag
+      st->kept_mass = st->mass_above + (float)want * w;
+      st->cut_x = lo;
+      st->cut_c = n - 1;
+    }
+    __syncthreads();
+    const uint32_t want = misc[2];
+    uint32_t* wave_cnt = misc + 8;
+    for (int c0 = 0; c0 < n; c0 += T_CHUNK) {
+      const int cb = c0 + tid * 4;
+      uint32_t flags = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (cb + j < n && x[cb + j] == lo) flags |= 1u << j;
+      const uint32_t mine = __popc(flags);
+      uint32_t incl = mine;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+      }
+      if (lane == 63) wave_cnt[wave] = incl;
+      __syncthreads();
+      uint32_t before_me = misc[3] + incl - mine;
+      uint32_t chunk_total = 0;
+      for (int w = 0; w < T_WAVES; ++w) {
+        if (w < wave) before_me += wave_cnt[w];
+        chunk_total += wave_cnt[w];
+      }
+      if (before_me < want && before_me + mine >= want) {
+        uint32_t seen = before_me;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (flags & (1u << j)) {
+            if (++seen == want) st->cut_c = cb + j;
+          }
+        misc[4] = 1u;
+      }
+      __syncthreads();
+      if (tid == 0) misc[3] += chunk_total;
+      const bool done = misc[4] != 0u;
+      __syncthreads();
+      if (done) break;
+    }
+    __syncthreads();
+  } else {
+    // ---- everything in and above the interval is kept ---------------------------------------------------
+    if (tid == 0) {
+      st->cut_x = lo;
+      st->cut_c = 0x7FFFFFFF;
+      st->kept_mass = st->mass_above;
+    }
+    __syncthreads();
+  }
+
+  // ---- 4. the draw --------------------------------------------------------------------------------------
+  const float cx = st->cut_x;
+  const int cc = st->cut_c;
+  float bv = kNegInf, bz = 0.f;
+  int bi = kNoColumn;
+  if (all_in) {
+    // every kept element is in the sorted list, positions 0 .. idx
+    const int last = (int)misc[5];
+    for (int i = tid; i <= last; i += T_THREADS) {
+      const float v = cand_x[i];
+      const int c = cand_c[i];
+      const uint4 words = philox4x32_10(uint4{(uint32_t)(c >> 2), (uint32_t)r, a.ctr2, a.ctr3}, a.key0, a.key1);
+      const int j = c & 3;
+      const uint32_t w = j == 0 ? words.x : (j == 1 ? words.y : (j == 2 ? words.z : words.w));
+      const float z = v * inv_t;
+      const float p = z + gumbel_from_word(w);
+      if (p > bv || (p == bv && c < bi)) {          // the list is not in column order
+        bv = p;
+        bz = z;
+        bi = c;
+      }
+    }
+  } else {
+    for (int c0 = tid * 4; c0 < n; c0 += T_CHUNK) {
+      uint4 words = uint4{0u, 0u, 0u, 0u};
+      bool have = false;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = c0 + j;
+        if (c < n) {
+          const float v = x[c];
+          if (v > cx || (v == cx && c <= cc)) {
+            if (!have) {
+              words = philox4x32_10(uint4{(uint32_t)(c0 >> 2), (uint32_t)r, a.ctr2, a.ctr3}, a.key0, a.key1);
+              have = true;
+            }
+            const uint32_t w = j == 0 ? words.x : (j == 1 ? words.y : (j == 2 ? words.z : words.w));
+            const float z = v * inv_t;
+            const float p = z + gumbel_from_word(w);
+            if (p > bv) {                             // increasing columns: strict comparison keeps the lowest
+              bv = p;
+              bz = z;
+              bi = c;
+            }
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float v = __shfl_xor(bv, off), z = __shfl_xor(bz, off);
+    const int i = __shfl_xor(bi, off);
+    if (v > bv || (v == bv && i < bi)) {
+      bv = v;
+      bz = z;
+      bi = i;
+    }
+  }
+  __syncthreads();
+  float* xv = reinterpret_cast<float*>(misc + 8);
+  float* xz = xv + T_WAVES;
+  int* xi = reinterpret_cast<int*>(xz + T_WAVES);
+  if (lane == 0) {
+    xv[wave] = bv;
+    xz[wave] = bz;
+    xi[wave] = bi;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < T_WAVES; ++w) {
+      if (xv[w] > bv || (xv[w] == bv && xi[w] < bi)) {
+        bv = xv[w];
+        bz = xz[w];
+        bi = xi[w];
+      }
+    }
+    a.token[r] = bi;
+    if (a.logprob) a.logprob[r] = (bz - m * inv_t) - logf(st->kept_mass);
+  }
+}
+
+}  // namespace
+
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_max, int32_t rows,
+                                float* partial, const z2z_sample_params* sp, int32_t top_k, float top_p,
+                                int32_t* token, float* logprob, hipStream_t s) {
+  TruncArgs a;
+  a.logits = logits;
+  a.size = c->st.size;
+  a.row_max = row_max;
+  a.V = c->cfg.V;
+  a.cap = c->cfg.cap;
+  a.ld = c->cfg.V + c->cfg.cap;
+  a.inv_temperature = 1.0f / sp->temperature;
+  a.top_k = top_k;
+  a.top_p = top_p;
+  a.key0 = (uint32_t)sp->seed;
+  a.key1 = (uint32_t)(sp->seed >> 32);
+  a.ctr2 = (uint32_t)sp->step;
+  a.ctr3 = (uint32_t)(sp->step >> 32);
+  a.token = token;
+  a.logprob = logprob;
+  hipLaunchKernelGGL(sample_first_pass_kernel, dim3(rows * T_SPLIT), dim3(T_THREADS), T_LDS, s, a, partial);
+  hipLaunchKernelGGL(sample_truncated_kernel, dim3(rows), dim3(T_THREADS), T_LDS, s, a, partial);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+size_t z2z_sample_truncated_partial_floats(int32_t rows) { return (size_t)rows * T_SPLIT * 2 * T_BINS; }
+
+int z2z_sample_truncated_prepare(z2z_ctx* c) {
+  if (c->lds_limit < T_LDS) return Z2Z_EUNSUPPORTED;
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sample_truncated_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sample_first_pass_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS));
+  return Z2Z_OK;
+}

@@ -25,6 +25,8 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->part_i);
   (void)hipFree(c->part_v);
   (void)hipFree(c->part_l);
+  (void)hipFree(c->sample_logits);
+  (void)hipFree(c->row_max);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
       (void)hipEventDestroy(c->ev_start[i]);
@@ -97,6 +99,7 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
   }
   c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
   c->decode_ready = z2z_logits_decode_ok(c) && z2z_logits_decode_prepare(c) == Z2Z_OK;
+  c->trunc_ready = c->decode_ready && z2z_sample_truncated_prepare(c) == Z2Z_OK;
   if (z2z_launch_lzw_reset(c, nullptr) != Z2Z_OK ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
     free_ctx(c);
@@ -172,16 +175,18 @@ Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int
 }
 
 Z2Z_API int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
-                                const void* d_W_base, const void* d_W_hyper, float temperature, uint64_t seed,
-                                uint64_t step, int32_t* d_token, float* d_logprob, void* stream) {
+                                const void* d_W_base, const void* d_W_hyper, float temperature, int32_t top_k,
+                                float top_p, uint64_t seed, uint64_t step, int32_t* d_token, float* d_logprob,
+                                void* stream) {
   if (!ctx || !d_H || !d_W_base || !d_token) return Z2Z_EINVAL;
   if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
   if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
   if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
   if (!(temperature > 0.f) || !(temperature < 3.0e38f)) return Z2Z_EINVAL;
+  if (!(top_p > 0.f)) return Z2Z_EINVAL;          // also rejects NaN; >= 1 switches the filter off
   if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
-  return z2z_launch_extended_sample(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, temperature, seed, step,
-                                    d_token, d_logprob, static_cast<hipStream_t>(stream));
+  return z2z_launch_extended_sample(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, temperature, top_k, top_p,
+                                    seed, step, d_token, d_logprob, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq, const void* d_W_base,

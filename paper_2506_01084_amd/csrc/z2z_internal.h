@@ -44,6 +44,11 @@ struct z2z_ctx {
   float* part_v;
   float* part_l;
   size_t part_vl_capacity;
+  // truncated sampling: the rows' logits as the decode kernel stores them, and the row maxima
+  float* sample_logits;
+  float* row_max;
+  size_t sample_logits_capacity;   // floats
+  int trunc_ready;
   // options
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map;
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration
@@ -68,8 +73,9 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
                                hipStream_t s);
 int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
-                               const void* W_hyper, float temperature, uint64_t seed, uint64_t step,
-                               int32_t* token, float* logprob, hipStream_t s);
+                               const void* W_hyper, float temperature, int32_t top_k, float top_p, uint64_t seed,
+                               uint64_t step, int32_t* token, float* logprob, hipStream_t s);
+int z2z_sample_truncated_prepare(z2z_ctx* c);
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                             const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s);
 

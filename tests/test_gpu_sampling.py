@@ -188,3 +188,122 @@ def test_full_size_decode_step_c3_sampled_sequences():
         _check_draws(r, tok_h[b:b + 1], lp_h[b:b + 1], T)
         print(f"  seq {b}: C={C} token {tok_h[b]} logprob {lp_h[b]:.4f} gap {r['gap'][0]:.4f}  {time.time() - t0:.1f}s", flush=True)
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------------
+# truncation: top-k / nucleus filters in front of the draw
+# ---------------------------------------------------------------------------------------------------------
+def _check_truncated(logits_row, T, k, p, seed, step, row, tok, lp):
+    """The GPU's draw against the oracle's.  Where the oracle's truncation rule came within rounding of keeping
+    one column more or fewer (float32 sums and logits against float64 ones), the draws for those neighbouring
+    prefixes are accepted too.  Returns True when the row was decidable (the perturbed maximum stands clear)."""
+    r = sampling.sample_row_truncated(logits_row, T, k, p, seed, step, row)
+    z = logits_row / T
+    order = np.lexsort((np.arange(len(z)), -z))
+    pert = r["perturbed"]
+    allowed = {}
+    sizes = [r["n_kept"]]
+    if r["order_gap"] < 1e-4 or r["mass_gap"] < 4e-6:
+        sizes += [max(1, r["n_kept"] - 1), min(len(z), r["n_kept"] + 1)]
+    for n in sizes:
+        kept = order[:n]
+        t = int(kept[np.argmax(pert[kept])])
+        mz = z[kept].max()
+        allowed.setdefault(t, []).append(z[t] - (mz + np.log(np.exp(z[kept] - mz).sum())))
+    if r["gap"] < GAP:
+        assert 0 <= tok < len(z) and lp <= 1e-6
+        return False
+    assert tok in allowed, f"row {row}: drew {tok}, oracle {r['token']} (kept {r['n_kept']}, allowed {sorted(allowed)})"
+    assert any(abs(lp - want) <= 2e-2 * max(1.0, abs(want)) for want in allowed[tok]), (row, lp, allowed[tok])
+    return True
+
+
+@pytest.mark.parametrize("B,N,V,d,M,cap", [
+    (65, 300, 1000, 256, 3, 300),
+    (6, 3000, 40000, 512, 3, 700),          # rows long enough for several histogram passes
+])
+def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap):
+    import torch
+
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=3 * B + V)
+    print(f"[case] truncated sampling B={B} V={V} d={d} cap={cap}", flush=True)
+    lens = wl.make_lens(cfg)
+    lens[1] = 0
+    ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, lens)
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    lp = torch.empty(B, dtype=torch.float32, device="cuda")
+    rows_logits = []
+    for b in range(B):
+        Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
+        rows_logits.append(oracle.extended_logits(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"])["logits"][0])
+    settings = [(1.0, 1, 1.0), (0.7, 5, 1.0), (1.0, 50, 1.0), (1.0, 0, 0.3), (0.5, 0, 0.9), (1.3, 40, 0.8),
+                (1.0, 10 ** 9, 0.9999), (2.0, 7000, 1.0), (0.05, 0, 0.5)]
+    for si, (T, k, p) in enumerate(settings):
+        seed, step = 900 + si, (si << 33) | 17
+        ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp, top_k=k, top_p=p)
+        torch.cuda.synchronize()
+        tok_h, lp_h = tok.cpu().numpy(), lp.cpu().numpy()
+        decided = sum(_check_truncated(rows_logits[b], T, k, p, seed, step, b, int(tok_h[b]), float(lp_h[b]))
+                      for b in range(B))
+        assert decided >= 0.8 * B, (T, k, p, decided)
+    ctx.close()
+
+
+def test_truncation_with_equal_logits_is_decided_by_column():
+    """H = 0 makes every logit equal: the order is the column order.  6000 columns exceed what one sort takes,
+    so the cut is found by the by-column pass; 300 columns go through the sort."""
+    import torch
+    from paper_2506_01084_amd import api
+
+    for V in (6000, 300):
+        B, d, cap = 8, 128, 16
+        ctx = api.Context(B=B, V=V, M=3, cap=cap, d=d, dtype="bf16")
+        ctx.reset()
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1)
+        W = torch.randn((V, d), device="cuda", generator=g).to(torch.bfloat16)
+        Wh = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+        H0 = torch.zeros((B, d), dtype=torch.bfloat16, device="cuda")
+        tok = torch.empty(B, dtype=torch.int32, device="cuda")
+        lp = torch.empty(B, dtype=torch.float32, device="cuda")
+        for k, p, n_keep in ((5, 1.0, 5), (0, 0.5, V // 2), (4500, 0.9, min(4500, int(np.ceil(0.9 * V)))), (1, 0.2, 1)):
+            seen = set()
+            for step in range(6):
+                ctx.extended_sample(H0, 1, W, Wh, 1.0, 77, step, tok, lp, top_k=k, top_p=p)
+                torch.cuda.synchronize()
+                t = tok.cpu().numpy()
+                assert (t >= 0).all() and (t < n_keep + 1).all(), (V, k, p, t.max(), n_keep)   # +1: p * total in float
+                assert np.allclose(lp.cpu().numpy(), -np.log(n_keep), atol=2e-2 + 1.0 / n_keep)
+                seen.update(t.tolist())
+                # the draw is the oracle's: all logits 0, the kept columns are 0 .. n_keep - 1
+                for b in range(B):
+                    _check_truncated(np.zeros(V), 1.0, k, p, 77, step, b, int(t[b]), float(lp[b]))
+            assert len(seen) > 1 or n_keep == 1
+        ctx.close()
+
+
+def test_full_size_c3_truncated():
+    import time
+    import torch
+
+    cfg = wl.CONFIGS["c3"]
+    t0 = time.time()
+    print("[case] full size truncated sampling step c3", flush=True)
+    ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, np.full(cfg["B"], cfg["N"], dtype=np.int32))
+    B = cfg["B"]
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    lp = torch.empty(B, dtype=torch.float32, device="cuda")
+    W_host = storage_to_host(d_W, cfg["dtype"])
+    lg = {}
+    for b in (0, 40):
+        lg[b] = oracle.extended_logits(H[b:b + 1], E, W_host[b], len(ref[b][1]), cfg["dtype"])["logits"][0]
+    for T, k, p in ((0.8, 50, 0.9), (1.0, 0, 0.95), (1.0, 20000, 1.0)):
+        seed, step = 4711, 99
+        ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp, top_k=k, top_p=p)
+        torch.cuda.synchronize()
+        tok_h, lp_h = tok.cpu().numpy(), lp.cpu().numpy()
+        for b in (0, 40):
+            ok = _check_truncated(lg[b], T, k, p, seed, step, b, int(tok_h[b]), float(lp_h[b]))
+            print(f"  T={T} k={k} p={p} seq {b}: token {tok_h[b]} logprob {lp_h[b]:.4f} decided {ok}  {time.time() - t0:.1f}s",
+                  flush=True)
+    ctx.close()
