@@ -281,7 +281,7 @@ def run_decode_workload(args, torch, api, wl):
                           "bytes_per_launch": bytes_step})
 
 
-def cpu_baseline(wl, host, budget_rows=24):
+def cpu_baseline(wl, host, budget_rows=4096):
     """The oracle, as it stands, on the host cores: LZW and pooling on the full configuration-2 batch, the
     joint logits on a sample of rows of sequence 0 (all columns); combined into tokens/s of the whole step."""
     import numpy as np
