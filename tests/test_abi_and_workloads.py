@@ -119,3 +119,15 @@ def test_dense_generators_shapes_dtypes_and_thread_independence():
     codes = wl.make_step_codes(wl.CONFIGS["c3"], np.array([0, 5, 4096]), 0)
     V = wl.CONFIGS["c3"]["V"]
     assert codes[0] < V and 0 <= codes[1] < V + 5 and 0 <= codes[2] < V + 4096
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is single-GPU: asking for more exits with a message, before anything touches a device."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in (r.stdout + r.stderr)
