@@ -158,7 +158,8 @@ int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t row
  * n = min(top_k, n_p) columns, n_p the smallest prefix whose q sums to at least top_p (both filters look at the
  * full distribution; at least one column is kept); the draw is the same argmax restricted to the kept
  * columns, i.e. a draw from q renormalised on them.  top_k <= 0 and top_p >= 1 switch a filter off; with both
- * off nothing is stored, otherwise the rows' logits go through rows * (V + cap) floats of library scratch.
+ * off nothing is stored, otherwise the rows' scaled logits go through rows * (V + cap) floats of library
+ * scratch (allocated by the first such call at a size: make one call before capturing into a graph).
  *   d_token   [rows] int32 out
  *   d_logprob [rows] float out or NULL: ln of the drawn token's probability under the (renormalised)
  *             distribution it was drawn from
@@ -194,6 +195,8 @@ enum {
                                   lr | ls << 8 | xr << 16 | xs << 24: each of the 8 XCDs walks blocks of
                                   lr row tiles x ls strips, the XCDs' blocks lie xr x xs (xr * xs = 8)
                                   inside one super block; 0 = automatic                              */
+  Z2Z_OPT_SAMPLE_KERNEL = 7,   /* filtered sampling: 0 = automatic, 1 = always select the kept prefix by
+                                  passes over the whole row (no short list from the largest parts)   */
   Z2Z_OPT_TIMING = 5           /* 1 = bracket the dominant kernel of every z2z_extended_logits call
                                   with HIP events on the call's stream (at most 1024 calls are kept
                                   between two z2z_read_timing calls); 0 = off (default)             */

@@ -20,6 +20,7 @@ POOL_MEAN, POOL_WEIGHTED = 0, 1
 APPEND, RESET = 0, 1
 ST_OK, ST_BAD_TOKEN, ST_BAD_CODE, ST_OVERFLOW = 0, 1, 2, 4
 OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMING, OPT_LOGITS_MAP = 1, 2, 3, 4, 5, 6
+OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",

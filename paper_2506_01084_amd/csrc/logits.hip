@@ -347,8 +347,8 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     Z2Z_HIP_TRY(hipGetLastError());
     return Z2Z_OK;
   }
-  // filters: the kernel stores the rows' logits (rows x (V + cap) floats of library scratch), the merge
-  // gives the row maxima, and one workgroup per row selects the kept prefix and draws
+  // filters: the kernel stores the rows' logits / T (rows x (V + cap) floats of library scratch), the merge
+  // gives the row maxima and log-sum-exps, and one workgroup per row selects the kept prefix and draws
   if (!c->trunc_ready) return Z2Z_EUNSUPPORTED;
   const size_t need = (size_t)rows * (size_t)(c->cfg.V + c->cfg.cap);
   if (need > c->sample_logits_capacity) {
@@ -358,17 +358,17 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     c->row_max = nullptr;
     c->sample_logits_capacity = 0;
     if (hipMalloc(&c->sample_logits, need * sizeof(float)) != hipSuccess) return Z2Z_ENOMEM;
-    // the row maxima, followed by the first pass's per-slice bin totals
-    if (hipMalloc(&c->row_max, ((size_t)rows + z2z_sample_truncated_partial_floats(rows)) * sizeof(float)) != hipSuccess)
+    // the row maxima and log-sum-exps, followed by the selection kernels' scratch
+    if (hipMalloc(&c->row_max, (2 * (size_t)rows + z2z_sample_truncated_work_floats(rows)) * sizeof(float)) != hipSuccess)
       return Z2Z_ENOMEM;
     c->sample_logits_capacity = need;
   }
-  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, c->sample_logits, s);
+  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, c->sample_logits, s);
   if (rc != Z2Z_OK) return rc;
-  rc = launch_combine(c, n_parts, rows, nullptr, c->row_max, nullptr, s);
+  rc = launch_combine(c, n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
   if (rc != Z2Z_OK) return rc;
-  return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, c->row_max + rows, &sp, top_k, top_p,
-                                     token, logprob, s);
+  return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, n_parts, c->row_max + 2 * (size_t)rows, &sp,
+                                     top_k, top_p, token, logprob, s);
 }
 
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,

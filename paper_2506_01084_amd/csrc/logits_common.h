@@ -163,10 +163,13 @@ struct z2z_sample_params {
 };
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s);
-int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_max, int32_t rows,
-                                float* partial, const z2z_sample_params* sp, int32_t top_k, float top_p,
+// `logits` hold logit / temperature as the decode kernel stored them, `row_stat` the rows' maxima, then their
+// log-sum-exps, of those values; `work` is scratch of z2z_sample_truncated_work_floats(rows) floats.
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
+                                float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
                                 int32_t* token, float* logprob, hipStream_t s);
-size_t z2z_sample_truncated_partial_floats(int32_t rows);
+size_t z2z_sample_truncated_work_floats(int32_t rows);
 int z2z_logits_decode_parts(const z2z_ctx* c);
+void z2z_logits_decode_units(int* base_columns, int* hyper_columns);
 bool z2z_logits_decode_ok(const z2z_ctx* c);
 int z2z_logits_decode_prepare(z2z_ctx* c);

@@ -58,7 +58,7 @@ struct DecodeArgs {
   float* part_v;
   float* part_l;
   float inv_temperature;
-  float* logits;          // MODE 2: [B, ld] raw logits out (columns at and beyond V + C_b are not written)
+  float* logits;          // MODE 2: [B, ld] logits * inv_temperature out (columns at and beyond V + C_b are not written)
   int32_t ld;
   uint32_t key0, key1;    // generator key: the seed
   uint32_t ctr2, ctr3;    // generator counter words 2, 3: the step
@@ -126,6 +126,8 @@ __device__ __forceinline__ void fold_logit(const DecodeArgs& a, Triple& t, Draw&
       dr.l = z;
       dr.i = col;
     }
+  } else if (MODE == 2) {
+    fold_value(t, x * a.inv_temperature, col);       // what is stored is folded: logit / T (T = 1 for plain logits)
   } else {
     fold_value(t, x, col);
   }
@@ -238,7 +240,8 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     __syncthreads();
     for (int i = tid; i < 64 * D_BASE_UNIT; i += D_THREADS) {
       const int jj = i / D_BASE_UNIT, r = i - jj * D_BASE_UNIT;
-      if (jj < n_h && v0 + r < a.V) a.logits[(size_t)(h0 + jj) * a.ld + v0 + r] = stage[jj * ST + r];
+      if (jj < n_h && v0 + r < a.V)
+        a.logits[(size_t)(h0 + jj) * a.ld + v0 + r] = stage[jj * ST + r] * a.inv_temperature;
     }
     __syncthreads();
   }
@@ -325,8 +328,8 @@ __device__ __forceinline__ void hyper_rows(const DecodeArgs& a, int b, int r0, i
     fold_logit<MODE>(a, t, dr, noise, sa, b, a.V + r);
     if (has_b) fold_logit<MODE>(a, t, dr, noise, sb, b, a.V + rb);
     if (MODE == 2 && lane == 0) {
-      a.logits[(size_t)b * a.ld + a.V + r] = sa;
-      if (has_b) a.logits[(size_t)b * a.ld + a.V + rb] = sb;
+      a.logits[(size_t)b * a.ld + a.V + r] = sa * a.inv_temperature;
+      if (has_b) a.logits[(size_t)b * a.ld + a.V + rb] = sb * a.inv_temperature;
     }
   }
 }
@@ -396,7 +399,8 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
 
 // Parts written: n_base_units + units_per_seq per hidden row.  With `sample` the kernel works on
 // logit / temperature and also leaves the best perturbed value per part (part_v, part_l, part_i); with
-// `logits` (and no `sample`) it also stores every logit it computes, row-major [B, V + cap].
+// `logits` it stores every logit it computes, row-major [B, V + cap] (divided by the temperature when `sample`
+// is given as well: the partials are then those of the scaled logits, and nothing is drawn).
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s) {
   DecodeArgs a;
@@ -427,7 +431,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.n_parts = *n_parts;
   const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  if (logits)
+  if (logits)                                         // with `sample`: stored and folded as logit / temperature
     hipLaunchKernelGGL(logits_decode_kernel<2>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   else if (sample)
     hipLaunchKernelGGL(logits_decode_kernel<1>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
@@ -443,6 +447,11 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 
 int z2z_logits_decode_parts(const z2z_ctx* c) {
   return (c->cfg.V + D_BASE_UNIT - 1) / D_BASE_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
+}
+
+void z2z_logits_decode_units(int* base_columns, int* hyper_columns) {
+  *base_columns = D_BASE_UNIT;
+  *hyper_columns = D_UNIT;
 }
 
 bool z2z_logits_decode_ok(const z2z_ctx* c) {

@@ -8,8 +8,11 @@
 // to at least p.  The draw is argmax over the kept columns of logit / T - ln(-ln u) with the same
 // generator coordinates as the untruncated draw.
 //
-// Input: the row's logits as the decode kernel stored them, and the row maximum.  One workgroup per hidden
-// row finds the last kept element of the order, the "cut", without sorting the row:
+// Input: the row's logits / T as the decode kernel stored them, the row's maximum and log-sum-exp, and the
+// maxima of the row's parts.  Rows with a short prefix (k up to 256, or a nucleus that closes within a few
+// hundred columns) are settled by sample_list_kernel from the parts with the largest maxima alone (see
+// there).  For the others one workgroup per hidden row finds the last kept element of the order, the "cut",
+// without sorting the row:
 //   1. histogram passes over the row.  The cut lies in a half-open value interval [lo, hi) (at first
 //      everything); the interval is split into 32 bins by value, every lane counts elements and sums
 //      exp((x - max) / T) per bin in its own LDS column (no two lanes share an address, so the LDS adds
@@ -33,17 +36,26 @@ constexpr int T_THREADS = 512;
 constexpr int T_WAVES = T_THREADS / 64;
 constexpr int T_BINS = 32;
 constexpr int T_CAND = 4096;
+constexpr int L_PARTS = 2048;                                  // list kernel: most parts per row it takes
+constexpr int L_DEPTH = 256;                                   // list kernel: largest k, and the depth tried for a nucleus alone
+static_assert(2 * L_PARTS <= T_CAND, "the list kernel keeps two runs per part in one candidate array");
 constexpr int T_SPLIT = 4;                                     // workgroups per row in the first pass
 constexpr int T_CHUNK = T_THREADS * 4;                         // columns per step: 4 consecutive ones per thread
 constexpr int T_HIST_BYTES = T_WAVES * T_BINS * 64 * 4;        // one histogram (counts or masses): 64 KiB
 constexpr int T_LDS = 2 * T_HIST_BYTES + 1024;                 // + edges, bin totals, state
 
 struct TruncArgs {
-  const float* logits;     // [rows, ld]
+  const float* logits;     // [rows, ld]: logit / T as the decode kernel stored them
   const int32_t* size;     // [B]
-  const float* row_max;    // [rows]
+  const float* row_max;    // [rows] largest stored value of the row
+  const float* row_lse;    // [rows] log-sum-exp of the row's stored values
+  const float* part_m;     // [rows, n_parts] largest stored value per part of the row (the decode kernel's units)
+  int32_t n_parts, n_base_parts, base_columns, hyper_columns;
+  int32_t list_depth;      // list kernel: how many of the row's largest parts bound the list
+  int32_t* redo;           // [rows] list kernel out: 1 = this row is left to the passes over the whole row;
+                           // the other kernels skip rows with 0 (nullptr: they take every row)
   int32_t V, cap, ld;
-  float inv_temperature;
+  float inv_temperature;   // applied to the stored values (1: they are scaled already)
   int32_t top_k;           // <= 0: off
   float top_p;             // >= 1: off
   uint32_t key0, key1, ctr2, ctr3;
@@ -66,6 +78,135 @@ struct State {              // written by thread 0, read by all after a barrier
 
 __device__ __forceinline__ bool before(float xa, int ca, float xb, int cb) {   // a precedes b in the order
   return xa > xb || (xa == xb && ca < cb);
+}
+
+// The candidate list (cnt <= T_CAND entries: value, column) is sorted into the order of the rule (bitonic, in
+// LDS), the masses exp((x - m) * inv_t) are scanned in that order (cand_w: inclusive prefix sums), and misc[1]
+// receives the first position at which the count (cnt_above + position + 1) reaches k_eff or the mass
+// (mass_above + prefix) reaches target, 0x7FFFFFFF if none does.  All threads call it; misc[8..16) is scratch.
+__device__ __forceinline__ void sort_and_scan(float* cand_x, int* cand_c, float* cand_w, int cnt, float m, float inv_t,
+                                              uint32_t cnt_above, float mass_above, uint32_t k_eff, float target,
+                                              uint32_t* misc) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int n2 = 2;
+  while (n2 < cnt) n2 <<= 1;
+  for (int i = cnt + tid; i < n2; i += T_THREADS) {
+    cand_x[i] = -INFINITY;
+    cand_c[i] = 0x7FFFFFFF;
+  }
+  __syncthreads();
+  for (int k = 2; k <= n2; k <<= 1) {
+    for (int j = k >> 1; j >= 1; j >>= 1) {
+      for (int i = tid; i < n2; i += T_THREADS) {
+        const int p = i ^ j;
+        if (p > i) {
+          const float xa = cand_x[i], xb = cand_x[p];
+          const int ca = cand_c[i], cb = cand_c[p];
+          const bool in_order = ((i & k) == 0) ? !before(xb, cb, xa, ca) : !before(xa, ca, xb, cb);
+          if (!in_order) {
+            cand_x[i] = xb;
+            cand_c[i] = cb;
+            cand_x[p] = xa;
+            cand_c[p] = ca;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // masses in sorted order and their inclusive prefix sums: each thread owns a contiguous run
+  const int per = (n2 + T_THREADS - 1) / T_THREADS;
+  const int i0 = tid * per;
+  float run = 0.f;
+  for (int i = i0; i < min(i0 + per, n2); ++i) {
+    run += i < cnt ? __expf((cand_x[i] - m) * inv_t) : 0.f;
+    cand_w[i] = run;
+  }
+  // exclusive prefix of the run totals over the block
+  float incl = run;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  float* wave_tot = reinterpret_cast<float*>(misc + 8);
+  if (lane == 63) wave_tot[wave] = incl;
+  if (tid == 0) misc[1] = 0x7FFFFFFFu;
+  __syncthreads();
+  float base = incl - run;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  for (int i = i0; i < min(i0 + per, cnt); ++i) {
+    const float cum = mass_above + base + cand_w[i];
+    if (cnt_above + (uint32_t)i + 1u >= k_eff || cum >= target) {
+      atomicMin(&misc[1], (uint32_t)i);
+      break;
+    }
+  }
+  __syncthreads();
+  for (int i = i0; i < min(i0 + per, n2); ++i) cand_w[i] += base;     // now inclusive over the whole list
+  __syncthreads();
+}
+
+struct Best {               // the largest perturbed value so far: value, scaled logit and column
+  float v, z;
+  int i;
+};
+
+// Gumbel-max over the sorted list's positions 0 .. last (this thread's share).
+__device__ __forceinline__ Best draw_from_list(const float* cand_x, const int* cand_c, int last, float inv_t, int r,
+                                               uint32_t key0, uint32_t key1, uint32_t ctr2, uint32_t ctr3) {
+  Best b{kNegInf, 0.f, kNoColumn};
+  for (int i = threadIdx.x; i <= last; i += T_THREADS) {
+    const float v = cand_x[i];
+    const int c = cand_c[i];
+    const uint4 words = philox4x32_10(uint4{(uint32_t)(c >> 2), (uint32_t)r, ctr2, ctr3}, key0, key1);
+    const int j = c & 3;
+    const uint32_t w = j == 0 ? words.x : (j == 1 ? words.y : (j == 2 ? words.z : words.w));
+    const float z = v * inv_t;
+    const float p = z + gumbel_from_word(w);
+    if (p > b.v || (p == b.v && c < b.i)) {          // the list is not in column order
+      b.v = p;
+      b.z = z;
+      b.i = c;
+    }
+  }
+  return b;
+}
+
+// The block's best draw (lowest column among equal perturbed values), valid in thread 0.  All threads call
+// it; `red` is scratch for 3 * T_WAVES words.
+__device__ __forceinline__ Best block_best(Best b, uint32_t* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float v = __shfl_xor(b.v, off), z = __shfl_xor(b.z, off);
+    const int i = __shfl_xor(b.i, off);
+    if (v > b.v || (v == b.v && i < b.i)) {
+      b.v = v;
+      b.z = z;
+      b.i = i;
+    }
+  }
+  __syncthreads();
+  float* xv = reinterpret_cast<float*>(red);
+  float* xz = xv + T_WAVES;
+  int* xi = reinterpret_cast<int*>(xz + T_WAVES);
+  if (lane == 0) {
+    xv[wave] = b.v;
+    xz[wave] = b.z;
+    xi[wave] = b.i;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < T_WAVES; ++w) {
+      if (xv[w] > b.v || (xv[w] == b.v && xi[w] < b.i)) {
+        b.v = xv[w];
+        b.z = xz[w];
+        b.i = xi[w];
+      }
+    }
+  }
+  return b;
 }
 
 // One histogram pass over the columns [c_begin, c_end) of a row (c_begin a multiple of 4): elements with
@@ -147,6 +288,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_first_pass_kernel(TruncArgs 
   uint32_t* bin_c = reinterpret_cast<uint32_t*>(edges + 40);
   float* bin_m = reinterpret_cast<float*>(bin_c + T_BINS);
   const int r = blockIdx.x / T_SPLIT, part = blockIdx.x % T_SPLIT;
+  if (a.redo && a.redo[r] == 0) return;             // drawn by the list kernel
   const int C = min(max(a.size[r], 0), a.cap);
   const int n = a.V + C;
   const float m = a.row_max[r];
@@ -181,6 +323,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int r = blockIdx.x;
+  if (a.redo && a.redo[r] == 0) return;             // drawn by the list kernel
   const int C = min(max(a.size[r], 0), a.cap);
   const int n = a.V + C;
   const float* x = a.logits + (size_t)r * a.ld;
@@ -363,65 +506,9 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
     }
     __syncthreads();
     const int cnt = (int)min(misc[0], (uint32_t)T_CAND);
-    int n2 = 2;
-    while (n2 < cnt) n2 <<= 1;
-    for (int i = cnt + tid; i < n2; i += T_THREADS) {
-      cand_x[i] = -INFINITY;
-      cand_c[i] = 0x7FFFFFFF;
-    }
-    __syncthreads();
-    for (int k = 2; k <= n2; k <<= 1) {
-      for (int j = k >> 1; j >= 1; j >>= 1) {
-        for (int i = tid; i < n2; i += T_THREADS) {
-          const int p = i ^ j;
-          if (p > i) {
-            const float xa = cand_x[i], xb = cand_x[p];
-            const int ca = cand_c[i], cb = cand_c[p];
-            const bool in_order = ((i & k) == 0) ? !before(xb, cb, xa, ca) : !before(xa, ca, xb, cb);
-            if (!in_order) {
-              cand_x[i] = xb;
-              cand_c[i] = cb;
-              cand_x[p] = xa;
-              cand_c[p] = ca;
-            }
-          }
-        }
-        __syncthreads();
-      }
-    }
-    // masses in sorted order and their inclusive prefix sums: each thread owns a contiguous run
-    const int per = (n2 + T_THREADS - 1) / T_THREADS;
-    const int i0 = tid * per;
-    float run = 0.f;
-    for (int i = i0; i < min(i0 + per, n2); ++i) {
-      run += i < cnt ? __expf((cand_x[i] - m) * inv_t) : 0.f;
-      cand_w[i] = run;
-    }
-    // exclusive prefix of the run totals over the block
-    float incl = run;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const float o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
-    float* wave_tot = reinterpret_cast<float*>(misc + 8);
-    if (lane == 63) wave_tot[wave] = incl;
-    if (tid == 0) misc[1] = 0x7FFFFFFFu;
-    __syncthreads();
-    float base = incl - run;
-    for (int w = 0; w < wave; ++w) base += wave_tot[w];
     const uint32_t cnt_above = all_in ? 0u : st->cnt_above;
     const float mass_above = all_in ? 0.f : st->mass_above;
-    for (int i = i0; i < min(i0 + per, cnt); ++i) {
-      const float cum = mass_above + base + cand_w[i];
-      if (cnt_above + (uint32_t)i + 1u >= k_eff || cum >= target) {
-        atomicMin(&misc[1], (uint32_t)i);
-        break;
-      }
-    }
-    __syncthreads();
-    for (int i = i0; i < min(i0 + per, n2); ++i) cand_w[i] += base;     // now inclusive over the whole list
-    __syncthreads();
+    sort_and_scan(cand_x, cand_c, cand_w, cnt, m, inv_t, cnt_above, mass_above, k_eff, target, misc);
     if (tid == 0) {
       int idx = misc[1] == 0x7FFFFFFFu ? cnt - 1 : (int)misc[1];       // rounding kept the mass below its target
       idx = max(idx, 0);
@@ -502,25 +589,10 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
   // ---- 4. the draw --------------------------------------------------------------------------------------
   const float cx = st->cut_x;
   const int cc = st->cut_c;
-  float bv = kNegInf, bz = 0.f;
-  int bi = kNoColumn;
+  Best best{kNegInf, 0.f, kNoColumn};
   if (all_in) {
     // every kept element is in the sorted list, positions 0 .. idx
-    const int last = (int)misc[5];
-    for (int i = tid; i <= last; i += T_THREADS) {
-      const float v = cand_x[i];
-      const int c = cand_c[i];
-      const uint4 words = philox4x32_10(uint4{(uint32_t)(c >> 2), (uint32_t)r, a.ctr2, a.ctr3}, a.key0, a.key1);
-      const int j = c & 3;
-      const uint32_t w = j == 0 ? words.x : (j == 1 ? words.y : (j == 2 ? words.z : words.w));
-      const float z = v * inv_t;
-      const float p = z + gumbel_from_word(w);
-      if (p > bv || (p == bv && c < bi)) {          // the list is not in column order
-        bv = p;
-        bz = z;
-        bi = c;
-      }
-    }
+    best = draw_from_list(cand_x, cand_c, (int)misc[5], inv_t, r, a.key0, a.key1, a.ctr2, a.ctr3);
   } else {
     for (int c0 = tid * 4; c0 < n; c0 += T_CHUNK) {
       uint4 words = uint4{0u, 0u, 0u, 0u};
@@ -538,62 +610,203 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
             const uint32_t w = j == 0 ? words.x : (j == 1 ? words.y : (j == 2 ? words.z : words.w));
             const float z = v * inv_t;
             const float p = z + gumbel_from_word(w);
-            if (p > bv) {                             // increasing columns: strict comparison keeps the lowest
-              bv = p;
-              bz = z;
-              bi = c;
+            if (p > best.v) {                         // increasing columns: strict comparison keeps the lowest
+              best.v = p;
+              best.z = z;
+              best.i = c;
             }
           }
         }
       }
     }
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const float v = __shfl_xor(bv, off), z = __shfl_xor(bz, off);
-    const int i = __shfl_xor(bi, off);
-    if (v > bv || (v == bv && i < bi)) {
-      bv = v;
-      bz = z;
-      bi = i;
-    }
-  }
-  __syncthreads();
-  float* xv = reinterpret_cast<float*>(misc + 8);
-  float* xz = xv + T_WAVES;
-  int* xi = reinterpret_cast<int*>(xz + T_WAVES);
-  if (lane == 0) {
-    xv[wave] = bv;
-    xz[wave] = bz;
-    xi[wave] = bi;
-  }
-  __syncthreads();
+  best = block_best(best, misc + 8);
   if (tid == 0) {
-    for (int w = 1; w < T_WAVES; ++w) {
-      if (xv[w] > bv || (xv[w] == bv && xi[w] < bi)) {
-        bv = xv[w];
-        bz = xz[w];
-        bi = xi[w];
+    a.token[r] = best.i;
+    if (a.logprob) a.logprob[r] = (best.z - m * inv_t) - logf(st->kept_mass);
+  }
+}
+
+// The short way, for a prefix of at most a few hundred columns.  The decode kernel left the largest value of
+// every part of the row (256 base columns, 512 hyper columns).  Let L be the j-th largest of them: j different
+// columns reach L, so the j-th element of the order is >= L, and every element >= L lies in a part whose
+// largest value is >= L.  Only those parts are read again, their elements >= L collected, and the sorted list
+// is then a prefix of the row's order that is at least j long: a top-k cut with k <= j, or a nucleus that
+// closes inside the list, is decided on it exactly as on the whole row (total mass: from the row's
+// log-sum-exp).  A row whose list overflows, or whose nucleus does not close inside it, sets redo[row].
+__global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
+  __shared__ __align__(16) float pm[L_PARTS];
+  __shared__ float cand_x[T_CAND];
+  __shared__ int cand_c[T_CAND];
+  __shared__ float cand_w[T_CAND];
+  __shared__ uint32_t misc[48];
+  __shared__ float level;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = blockIdx.x;
+  const int C = min(max(a.size[r], 0), a.cap);
+  const int n = a.V + C;
+  const float* x = a.logits + (size_t)r * a.ld;
+  const int n_parts = a.n_parts;
+  const int depth = min(a.list_depth, n);
+  const int n4 = (n_parts + 3) & ~3;
+
+  for (int i = tid; i < n4; i += T_THREADS) pm[i] = i < n_parts ? a.part_m[(size_t)r * n_parts + i] : -INFINITY;
+  if (tid == 0) {
+    misc[0] = 0u;            // list length
+    misc[2] = 0u;            // level found
+    misc[3] = 0u;            // work items
+    misc[4] = 0u;            // mass of the list (float)
+  }
+  __syncthreads();
+  // the depth-th largest part maximum: the value v with (number of maxima > v) < depth <= (number >= v)
+  if (depth <= n_parts) {
+    const float4* pm4 = reinterpret_cast<const float4*>(pm);
+    for (int i = tid; i < n_parts; i += T_THREADS) {
+      const float v = pm[i];
+      int gt = 0, ge = 0;
+      for (int j = 0; j < n4 / 4; ++j) {
+        const float4 q = pm4[j];
+        gt += (q.x > v) + (q.y > v) + (q.z > v) + (q.w > v);
+        ge += (q.x >= v) + (q.y >= v) + (q.z >= v) + (q.w >= v);
+      }
+      if (gt < depth && depth <= ge) {               // equal maxima all write the same value
+        level = v;
+        misc[2] = 1u;
       }
     }
-    a.token[r] = bi;
-    if (a.logprob) a.logprob[r] = (bz - m * inv_t) - logf(st->kept_mass);
+  }
+  __syncthreads();
+  bool ok = misc[2] != 0u && level > -INFINITY;      // uniform
+  // no element weighs more than the largest one, exp(0) = 1 in the units of the masses, and the list comes out
+  // about list_depth long: a nucleus alone that needs more mass than twice that many elements could carry
+  // is not tried (a flat distribution; the passes over the whole row take it)
+  if (a.top_k <= 0 && a.top_p * __expf((a.row_lse[r] - a.row_max[r]) * a.inv_temperature) > (float)(2 * a.list_depth))
+    ok = false;
+  const float L = ok ? level : INFINITY;
+  // work items: runs of at most 256 columns of the parts that reach L (cand_c is free until the appends start,
+  // and they start after the barrier; items are kept in cand_w, which the scan fills later)
+  int* item_c0 = reinterpret_cast<int*>(cand_w);  // [<= 2 * L_PARTS = T_CAND]: a part has at most two runs
+  if (ok) {
+    for (int p = tid; p < n_parts; p += T_THREADS) {
+      if (!(pm[p] >= L)) continue;
+      int c0, c1;
+      if (p < a.n_base_parts) {
+        c0 = p * a.base_columns;
+        c1 = min(c0 + a.base_columns, a.V);
+      } else {
+        c0 = a.V + (p - a.n_base_parts) * a.hyper_columns;
+        c1 = min(c0 + a.hyper_columns, n);
+      }
+      const int pieces = (c1 - c0 + 255) >> 8;
+      if (pieces > 0) {
+        const uint32_t at = atomicAdd(&misc[3], (uint32_t)pieces);
+        for (int q = 0; q < pieces; ++q) item_c0[at + q] = c0 + 256 * q;
+      }
+    }
+  }
+  __syncthreads();
+  if (ok) {
+    const int n_items = (int)misc[3];
+    const float m0 = a.row_max[r];
+    float mass = 0.f;                                // of what this lane appends
+    for (int it = wave * 4; it < n_items; it += T_WAVES * 4) {     // 16 independent loads in flight per wave
+      float v[16];
+      int cc[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const bool have = it + q < n_items;          // wave-uniform
+        const int c0 = have ? item_c0[it + q] : 0;
+        int c1 = 0;                                  // the run ends with its part, after 256 columns at most
+        if (have) {
+          const int part_end = c0 < a.V ? min((c0 / a.base_columns + 1) * a.base_columns, a.V)
+                                        : min(a.V + ((c0 - a.V) / a.hyper_columns + 1) * a.hyper_columns, n);
+          c1 = min(c0 + 256, part_end);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int c = c0 + j * 64 + lane;
+          cc[q * 4 + j] = c < c1 ? c : -1;
+          v[q * 4 + j] = c < c1 ? x[c] : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const bool take = cc[j] >= 0 && v[j] >= L;
+        const uint64_t mask = __ballot(take);
+        if (mask != 0ull) {
+          uint32_t first = 0;
+          if (lane == 0) first = atomicAdd(&misc[0], (uint32_t)__popcll(mask));
+          first = __shfl(first, 0);
+          const uint32_t slot = first + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+          if (take && slot < (uint32_t)T_CAND) {
+            cand_x[slot] = v[j];
+            cand_c[slot] = cc[j];
+            mass += __expf((v[j] - m0) * a.inv_temperature);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
+    if (lane == 0) atomicAdd(reinterpret_cast<float*>(&misc[4]), mass);
+  }
+  __syncthreads();
+  const uint32_t found = misc[0];
+  ok = ok && found <= (uint32_t)T_CAND && found >= 1u;
+  if (!ok) {
+    if (tid == 0) a.redo[r] = 1;
+    return;
+  }
+  const int cnt = (int)found;
+  const float m = a.row_max[r];
+  const float inv_t = a.inv_temperature;
+  const uint32_t k_eff = a.top_k > 0 ? (uint32_t)min(a.top_k, n) : (uint32_t)n;
+  const float target = a.top_p < 1.0f ? a.top_p * __expf((a.row_lse[r] - m) * inv_t) : INFINITY;
+  if (a.top_k <= 0 && cnt < n && __uint_as_float(misc[4]) < 0.999f * target) {
+    if (tid == 0) a.redo[r] = 1;                     // a nucleus alone, and the whole list weighs too little
+    return;
+  }
+  sort_and_scan(cand_x, cand_c, cand_w, cnt, m, inv_t, 0u, 0.f, k_eff, target, misc);
+  int idx;
+  if (misc[1] != 0x7FFFFFFFu)
+    idx = (int)misc[1];
+  else if (cnt == n)
+    idx = cnt - 1;                                   // the whole row is in the list and rounding kept the mass below p
+  else {
+    if (tid == 0) a.redo[r] = 1;                     // the cut lies beyond the list
+    return;
+  }
+  Best best = draw_from_list(cand_x, cand_c, idx, inv_t, r, a.key0, a.key1, a.ctr2, a.ctr3);
+  best = block_best(best, misc + 8);
+  if (tid == 0) {
+    a.redo[r] = 0;
+    a.token[r] = best.i;
+    if (a.logprob) a.logprob[r] = (best.z - m * inv_t) - logf(cand_w[idx]);
   }
 }
 
 }  // namespace
 
-int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_max, int32_t rows,
-                                float* partial, const z2z_sample_params* sp, int32_t top_k, float top_p,
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
+                                float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
                                 int32_t* token, float* logprob, hipStream_t s) {
+  (void)sp->temperature;                             // the stored values are scaled already
   TruncArgs a;
   a.logits = logits;
   a.size = c->st.size;
-  a.row_max = row_max;
+  a.row_max = row_stat;
+  a.row_lse = row_stat + rows;
+  a.part_m = c->part_m;
+  a.n_parts = n_parts;
+  z2z_logits_decode_units(&a.base_columns, &a.hyper_columns);
+  a.n_base_parts = (c->cfg.V + a.base_columns - 1) / a.base_columns;
   a.V = c->cfg.V;
   a.cap = c->cfg.cap;
   a.ld = c->cfg.V + c->cfg.cap;
-  a.inv_temperature = 1.0f / sp->temperature;
+  a.inv_temperature = 1.0f;
   a.top_k = top_k;
   a.top_p = top_p;
   a.key0 = (uint32_t)sp->seed;
@@ -602,13 +815,24 @@ int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* ro
   a.ctr3 = (uint32_t)(sp->step >> 32);
   a.token = token;
   a.logprob = logprob;
+  a.redo = nullptr;
+  a.list_depth = 0;
+  float* partial = work + rows;                      // work: [rows] redo flags, then the first pass's bin totals
+  // a short prefix first: rows it cannot settle are flagged, and only those take the passes over the whole row
+  const bool list_first = c->opt_sample_kernel != 1 && n_parts <= L_PARTS && top_k <= L_DEPTH &&
+                          a.base_columns <= 512 && a.hyper_columns <= 512;
+  if (list_first) {
+    a.redo = reinterpret_cast<int32_t*>(work);
+    a.list_depth = top_k > 0 ? top_k : L_DEPTH;
+    hipLaunchKernelGGL(sample_list_kernel, dim3(rows), dim3(T_THREADS), 0, s, a);
+  }
   hipLaunchKernelGGL(sample_first_pass_kernel, dim3(rows * T_SPLIT), dim3(T_THREADS), T_LDS, s, a, partial);
   hipLaunchKernelGGL(sample_truncated_kernel, dim3(rows), dim3(T_THREADS), T_LDS, s, a, partial);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }
 
-size_t z2z_sample_truncated_partial_floats(int32_t rows) { return (size_t)rows * T_SPLIT * 2 * T_BINS; }
+size_t z2z_sample_truncated_work_floats(int32_t rows) { return (size_t)rows * (1 + T_SPLIT * 2 * T_BINS); }
 
 int z2z_sample_truncated_prepare(z2z_ctx* c) {
   if (c->lds_limit < T_LDS) return Z2Z_EUNSUPPORTED;

@@ -50,7 +50,8 @@ struct z2z_ctx {
   size_t sample_logits_capacity;   // floats
   int trunc_ready;
   // options
-  int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map;
+  int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map,
+      opt_sample_kernel;
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration
   int fast_ready;          // the 128 KiB-LDS bf16 logits kernel can be launched on this device
   // timing record

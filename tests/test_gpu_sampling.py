@@ -218,18 +218,25 @@ def _check_truncated(logits_row, T, k, p, seed, step, row, tok, lp):
     return True
 
 
+@pytest.mark.parametrize("whole_row_only", [0, 1])
 @pytest.mark.parametrize("B,N,V,d,M,cap", [
     (65, 300, 1000, 256, 3, 300),
-    (6, 3000, 40000, 512, 3, 700),          # rows long enough for several histogram passes
+    (6, 3000, 40000, 512, 3, 700),          # rows long enough for several histogram passes; 159 parts
+    (9, 2000, 9000, 256, 3, 1500),          # 36 base parts and 3 hyper parts
 ])
-def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap):
+def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_only):
+    """Both ways of finding the kept prefix: the short list built from the parts with the largest maxima
+    (settings with k up to 256 on rows with at least k parts, or a nucleus that closes early), and the passes
+    over the whole row (everything else; all settings when whole_row_only)."""
     import torch
+    from paper_2506_01084_amd import api
 
     cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=3 * B + V)
     print(f"[case] truncated sampling B={B} V={V} d={d} cap={cap}", flush=True)
     lens = wl.make_lens(cfg)
     lens[1] = 0
     ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, lens)
+    ctx.set_option(api.OPT_SAMPLE_KERNEL, whole_row_only)
     tok = torch.empty(B, dtype=torch.int32, device="cuda")
     lp = torch.empty(B, dtype=torch.float32, device="cuda")
     rows_logits = []
@@ -237,7 +244,8 @@ def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap):
         Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
         rows_logits.append(oracle.extended_logits(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"])["logits"][0])
     settings = [(1.0, 1, 1.0), (0.7, 5, 1.0), (1.0, 50, 1.0), (1.0, 0, 0.3), (0.5, 0, 0.9), (1.3, 40, 0.8),
-                (1.0, 10 ** 9, 0.9999), (2.0, 7000, 1.0), (0.05, 0, 0.5)]
+                (1.0, 10 ** 9, 0.9999), (2.0, 7000, 1.0), (0.05, 0, 0.5), (1.0, 2, 0.99), (0.9, 36, 1.0),
+                (1.1, 39, 0.97), (1.0, 256, 1.0), (0.3, 257, 0.9)]
     for si, (T, k, p) in enumerate(settings):
         seed, step = 900 + si, (si << 33) | 17
         ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp, top_k=k, top_p=p)
