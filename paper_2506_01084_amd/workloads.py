@@ -188,6 +188,38 @@ def make_pool_weights(cfg: dict) -> np.ndarray:
     return w
 
 
+def make_encoder(cfg: dict, n_layers: int = 2, n_heads: int = 32, d_ff: int = 0, attention_only: bool = False,
+                 with_pos: bool = True) -> dict:
+    """Random-init parameters of a learned hyper-encoder (trained weights are not available here).
+
+    Matrices [out, in] in the configuration's storage format, N(0, 1/in) (the projections behind the residual
+    sum, w_o and w_2, N(0, 1/(4 in)) so that the residual stream keeps the scale of the embeddings' sum);
+    biases N(0, 0.02), LayerNorm scales 1 + N(0, 0.1) and shifts N(0, 0.05), float32; slot positions [M, d]
+    N(0, 0.02) like the embedding table.  d_ff = 0 means 4 d."""
+    d, dtype, M = cfg["d"], cfg["dtype"], cfg["M"]
+    d_ff = d_ff or 4 * d
+    seed = cfg["seed"] + 100
+    rng = np.random.Generator(np.random.PCG64(seed))
+
+    def vec(n, mean, std):
+        return (mean + std * rng.standard_normal(n)).astype(np.float32)
+
+    layers = []
+    for li in range(n_layers):
+        s = seed + 10 * (li + 1)
+        lay = dict(ln1_g=vec(d, 1.0, 0.1), ln1_b=vec(d, 0.0, 0.05),
+                   w_qkv=normal_matrix(s + 1, 3 * d, d, d ** -0.5, dtype), b_qkv=vec(3 * d, 0.0, 0.02),
+                   w_o=normal_matrix(s + 2, d, d, 0.5 * d ** -0.5, dtype), b_o=vec(d, 0.0, 0.02))
+        if not attention_only:
+            lay.update(ln2_g=vec(d, 1.0, 0.1), ln2_b=vec(d, 0.0, 0.05),
+                       w_1=normal_matrix(s + 3, d_ff, d, d ** -0.5, dtype), b_1=vec(d_ff, 0.0, 0.02),
+                       w_2=normal_matrix(s + 4, d, d_ff, 0.5 * d_ff ** -0.5, dtype), b_2=vec(d, 0.0, 0.02))
+        layers.append(lay)
+    pos = normal_matrix(seed + 5, M, d, 0.02, dtype) if with_pos else None
+    return dict(n_heads=n_heads, attention_only=attention_only, d_ff=0 if attention_only else d_ff, pos=pos,
+                layers=layers)
+
+
 def make_step_codes(cfg: dict, sizes: np.ndarray, step: int) -> np.ndarray:
     """int32 [B] one new code per sequence for decode step `step`, uniform over the valid IDs
     [0, V + sizes[b]) with half of the draws forced into the hypertoken range when it is non-empty."""
