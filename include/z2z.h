@@ -130,6 +130,49 @@ int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entr
 int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_t* d_first,
                     int32_t max_new, void* stream);
 
+/* hyper_encode: the learned hyper-encoder f_phi of section 2.2 (the attention and transformer rows of the
+ * hyper-encoder ablation table; the training setup uses two transformer layers, M = 3).  The paper names the
+ * architectures only; computed here is the standard pre-norm encoder over an entry's M padded slots:
+ *   X_i = E[y_i] + pos[i]                                   (real slots i < L; pos may be NULL)
+ *   A = LayerNorm(X; ln1);  q|k|v = A w_qkv^T + b_qkv;  per head: O = softmax(q k^T / sqrt(d / n_heads)) v,
+ *   padding slots masked out as keys;  Y = X + O w_o^T + b_o                       (an attention layer)
+ *   Z = Y + GELU(LayerNorm(Y; ln2) w_1^T + b_1) w_2^T + b_2   (GELU with erf)      (a transformer layer)
+ *   W_hyper[b, e, :] = mean over the real slots of the last layer's output.
+ * LayerNorm: over the d features, biased variance, eps = 1e-5.  Matrices are bf16 [out, in] row-major, vectors
+ * float; every pointer is a device pointer, 16-byte aligned, borrowed for the call; the structs themselves
+ * are host memory.  Activations between the layers' steps are rounded to bf16, sums are fp32.
+ *   d_E, d_W_hyper, d_first, max_new: as for z2z_hyper_embed, except that with d_first the entries
+ *   [d_first[b], min(C_b, d_first[b] + max_new)) are computed (max_new <= 0: up to cap).
+ * Requires a bf16 context, d a multiple of 64 and at most 4096, d / n_heads a power of two in [8, 512], d_ff a
+ * multiple of 64, 1 <= n_layers <= Z2Z_MAX_ENCODER_LAYERS; anything else returns Z2Z_EUNSUPPORTED or
+ * Z2Z_EINVAL.  Work space (activations of up to 65536 slot rows) is library scratch, allocated by the first
+ * call at a size. */
+#define Z2Z_MAX_ENCODER_LAYERS 8
+typedef struct z2z_encoder_layer {
+  const float* ln1_g;   /* [d]  */
+  const float* ln1_b;   /* [d]  */
+  const void* w_qkv;    /* [3d, d]: rows 0..d-1 query, d..2d-1 key, 2d..3d-1 value projections */
+  const float* b_qkv;   /* [3d] */
+  const void* w_o;      /* [d, d] */
+  const float* b_o;     /* [d]  */
+  const float* ln2_g;   /* [d]      transformer layers only (ignored when attention_only) */
+  const float* ln2_b;   /* [d]      */
+  const void* w_1;      /* [d_ff, d] */
+  const float* b_1;     /* [d_ff]   */
+  const void* w_2;      /* [d, d_ff] */
+  const float* b_2;     /* [d]      */
+} z2z_encoder_layer;
+typedef struct z2z_encoder {
+  int32_t n_layers;
+  int32_t n_heads;
+  int32_t d_ff;             /* width of the feed-forward block (ignored when attention_only) */
+  int32_t attention_only;   /* 1: every layer is the attention layer alone */
+  const void* pos;          /* [M, d] bf16 learned slot positions, or NULL */
+  const z2z_encoder_layer* layers;   /* host array of n_layers */
+} z2z_encoder;
+int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, void* d_W_hyper,
+                     const int32_t* d_first, int32_t max_new, void* stream);
+
 /* extended_logits.  For row r of sequence b = r / rows_per_seq:
  *   logit[r, v] = sum_k H[r,k] * W[v,k],  W = W_base for v < V, W_hyper[b, v-V] for V <= v < V + C_b;
  * slots at and beyond C_b are not columns (never predicted).  Products of the stored values,

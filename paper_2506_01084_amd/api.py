@@ -24,13 +24,50 @@ OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",
-           "z2z_hyper_embed", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_set_option",
+           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
 
 class Config(ctypes.Structure):
     _fields_ = [("B", c_int32), ("V", c_int32), ("M", c_int32), ("cap", c_int32), ("d", c_int32),
                 ("dtype", c_int32), ("pool", c_int32), ("w", c_float * MAX_M)]
+
+
+class EncoderLayer(ctypes.Structure):
+    _fields_ = [(n, c_void_p) for n in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1",
+                                        "b_1", "w_2", "b_2")]
+
+
+class EncoderDesc(ctypes.Structure):
+    _fields_ = [("n_layers", c_int32), ("n_heads", c_int32), ("d_ff", c_int32), ("attention_only", c_int32),
+                ("pos", c_void_p), ("layers", ctypes.POINTER(EncoderLayer))]
+
+
+class Encoder:
+    """Device-resident parameters of a learned hyper-encoder, marshalled into the C structs.
+
+    `params`: n_heads, attention_only, d_ff, pos ([M, d] tensor or None) and layers, a list of dicts of
+    device tensors named as the fields of z2z_encoder_layer (matrices in the context's dtype, vectors float32).
+    The object keeps the tensors alive."""
+
+    def __init__(self, params: dict, torch_dtype):
+        self.params = params
+        layers = params["layers"]
+        self._arr = (EncoderLayer * len(layers))()
+        for l, lay in enumerate(layers):
+            for name, _ in EncoderLayer._fields_:
+                t = lay.get(name)
+                if t is None:
+                    setattr(self._arr[l], name, None)
+                else:
+                    setattr(self._arr[l], name, _ptr(t, torch_dtype if name.startswith("w_") else torch.float32))
+        self.desc = EncoderDesc()
+        self.desc.n_layers = len(layers)
+        self.desc.n_heads = int(params["n_heads"])
+        self.desc.d_ff = int(params.get("d_ff", 0))
+        self.desc.attention_only = 1 if params["attention_only"] else 0
+        self.desc.pos = _ptr(params.get("pos"), torch_dtype)
+        self.desc.layers = ctypes.cast(self._arr, ctypes.POINTER(EncoderLayer))
 
 
 _lib = None
@@ -55,6 +92,7 @@ def load_library() -> ctypes.CDLL:
                                    c_void_p, c_void_p]
     lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
+    lib.z2z_hyper_encode.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_int32,
@@ -176,6 +214,13 @@ class Context:
         assert tuple(E.shape) == (self.V, self.d) and tuple(W_hyper.shape) == (self.B, self.cap, self.d)
         _check(self._lib.z2z_hyper_embed(self._h, _ptr(E, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
                                          _ptr(first, torch.int32), max_new, _stream()), "z2z_hyper_embed")
+
+    def hyper_encode(self, E: torch.Tensor, encoder: "Encoder", W_hyper: torch.Tensor,
+                     first: Optional[torch.Tensor] = None, max_new: int = 0) -> None:
+        assert tuple(E.shape) == (self.V, self.d) and tuple(W_hyper.shape) == (self.B, self.cap, self.d)
+        _check(self._lib.z2z_hyper_encode(self._h, _ptr(E, self.torch_dtype), byref(encoder.desc),
+                                          _ptr(W_hyper, self.torch_dtype), _ptr(first, torch.int32), max_new,
+                                          _stream()), "z2z_hyper_encode")
 
     def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
                         argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,

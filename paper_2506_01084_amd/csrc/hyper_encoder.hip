@@ -1,0 +1,358 @@
+// Learned hyper-encoder for gfx950 (bf16): the network that turns the embeddings of a hypertoken's constituent
+// base tokens, padded to M slots, into the hypertoken's vector (zip2zip paper, section 2.2; the attention and
+// transformer rows of the hyper-encoder ablation table; the two-layer transformer of the training setup).
+// The paper names the architectures only; what is computed here is the standard pre-norm encoder over the M
+// slots, padding masked out as keys, mean of the real slots at the end:
+//
+//   X_i = E[y_i] + P_i;  A = LN1(X);  QKV = A Wqkv^T + b;  O = softmax(Q K^T / sqrt(d_head)) V per head;
+//   Y = X + O Wo^T + bo;  Z = Y + GELU(LN2(Y) W1^T + b1) W2^T + b2  (transformer layers);  h = mean_i Z_i.
+//
+// All entries of a pass are batched: row (b, u, i) = slot i of the u-th entry taken from sequence b, so every
+// dense layer is one [rows, K] x [N, K]^T product on the bf16 MFMA kernel with bias / GELU / residual in its
+// epilogue.  The kernels in this file are the bandwidth-bound rest: gather + LayerNorm (one wave per row, the
+// row held in registers: read once), the M x M attention per entry and head (a wave per entry and 512
+// features: 64 lanes x 16 bytes, a head's dot products reduced across its lanes), and the final mean.  Padding
+// slots and missing entries are zero rows: they cost their share of the products but never reach a result.
+// Activations between kernels are bf16, accumulation and statistics fp32.
+#include "logits_common.h"
+
+namespace {
+
+using z2z_logits::bf16_bits_rne;
+
+constexpr int E_KCH = 8;             // 16-byte chunks per lane of one row: d <= 64 * 8 * E_KCH = 4096
+constexpr float E_EPS = 1e-5f;
+
+struct RowMap {                      // which entries a pass covers, and where their rows sit
+  const int32_t* size;               // [B] C_b
+  const int32_t* ent_tokens;         // [B, cap, M]
+  const int32_t* ent_len;            // [B, cap]
+  const int32_t* first;              // [B] or nullptr
+  int32_t last_n;                    // first == nullptr: 0 = entries from 0, n > 0 = the last n entries
+  int32_t B, V, M, cap, d;
+  int32_t u0, un;                    // entry units [u0, u0 + un) of every sequence; rows = B * un * M
+};
+
+__device__ __forceinline__ int entry_of(const RowMap& m, int b, int u, int* C_out) {
+  const int C = min(max(m.size[b], 0), m.cap);
+  *C_out = C;
+  const int base = m.first ? max(m.first[b], 0) : (m.last_n > 0 ? max(C - m.last_n, 0) : 0);
+  return base + m.u0 + u;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& x, float (&f)[8]) {
+  f[0] = __uint_as_float(x.x << 16);
+  f[1] = __uint_as_float(x.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(x.y << 16);
+  f[3] = __uint_as_float(x.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(x.z << 16);
+  f[5] = __uint_as_float(x.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(x.w << 16);
+  f[7] = __uint_as_float(x.w & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  uint4 o;
+  o.x = bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16);
+  o.y = bf16_bits_rne(f[2]) | (bf16_bits_rne(f[3]) << 16);
+  o.z = bf16_bits_rne(f[4]) | (bf16_bits_rne(f[5]) << 16);
+  o.w = bf16_bits_rne(f[6]) | (bf16_bits_rne(f[7]) << 16);
+  return o;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// One wave per row.  GATHER: X[r] = bf16(E[token] + P[slot]) is formed and stored first (zero for padding
+// slots and missing entries, whose A row is zero as well).  Then A[r] = LN(X[r]) * gamma + beta, statistics
+// over the stored (rounded) values in two steps: mean, then the mean of the squared deviations.
+template <bool GATHER>
+__global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E, const uint4* P, uint4* X, uint4* A,
+                                                       const float* gamma, const float* beta, int rows) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int n_chunks = m.d / 8;
+  uint4* xr = X + (size_t)r * n_chunks;
+  uint4* ar = A + (size_t)r * n_chunks;
+  float x[E_KCH][8];
+  if (GATHER) {
+    const int i = r % m.M;
+    const int bu = r / m.M;
+    const int b = bu / m.un, u = bu % m.un;
+    int C;
+    const int e = entry_of(m, b, u, &C);
+    const int L = e < C ? min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M) : 0;
+    if (i >= L) {
+      const uint4 z = {0u, 0u, 0u, 0u};
+      for (int c = lane; c < n_chunks; c += 64) {
+        xr[c] = z;
+        ar[c] = z;
+      }
+      return;
+    }
+    const int tok = min(max(m.ent_tokens[((size_t)b * m.cap + e) * m.M + i], 0), m.V - 1);
+    const uint4* er = E + (size_t)tok * n_chunks;
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k) {
+      const int c = lane + 64 * k;
+      if (c < n_chunks) {
+        float ev[8];
+        unpack8(er[c], ev);
+        if (P) {
+          float pv[8];
+          unpack8(P[(size_t)i * n_chunks + c], pv);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) ev[t] += pv[t];
+        }
+        const uint4 st = pack8(ev);
+        xr[c] = st;
+        unpack8(st, x[k]);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k) {
+      const int c = lane + 64 * k;
+      if (c < n_chunks) unpack8(xr[c], x[k]);
+    }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k)
+    if (lane + 64 * k < n_chunks) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) sum += x[k][t];
+    }
+  const float mean = wave_sum(sum) / (float)m.d;
+  float sq = 0.f;
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k)
+    if (lane + 64 * k < n_chunks) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float dv = x[k][t] - mean;
+        sq += dv * dv;
+      }
+    }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)m.d + E_EPS);
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k) {
+    const int c = lane + 64 * k;
+    if (c < n_chunks) {
+      const float4 g0 = *reinterpret_cast<const float4*>(gamma + c * 8), g1 = *reinterpret_cast<const float4*>(gamma + c * 8 + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(beta + c * 8), b1 = *reinterpret_cast<const float4*>(beta + c * 8 + 4);
+      const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float bt[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      float y[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) y[t] = (x[k][t] - mean) * rstd * g[t] + bt[t];
+      ar[c] = pack8(y);
+    }
+  }
+}
+
+// Attention among the slots of one entry.  QKV [rows, 3d] holds q | k | v of every slot; a wave takes one
+// entry and 512 consecutive features (whole heads: the head width is a power of two of at most 512), lane l
+// the 8 features of chunk l.  Scores are reduced over the lanes_per_head lanes of a head; the softmax runs
+// over the entry's real slots only; O rows of padding slots and missing entries are zero.
+__global__ void __launch_bounds__(256) enc_attention_kernel(RowMap m, const uint4* QKV, uint4* O, int lanes_per_head,
+                                                            float scale, int groups, int n_units) {
+  const int lane = threadIdx.x & 63;
+  const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int g = (int)(wid % groups);
+  const long long bu = wid / groups;
+  if (bu >= n_units) return;
+  const int b = (int)(bu / m.un), u = (int)(bu % m.un);
+  const int n_chunks = m.d / 8;
+  const int c = g * 64 + lane;
+  const bool active = c < n_chunks;
+  int C;
+  const int e = entry_of(m, b, u, &C);
+  const int L = e < C ? min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M) : 0;
+  const size_t r0 = (size_t)bu * m.M;
+  const uint4 zero = {0u, 0u, 0u, 0u};
+  for (int i = 0; i < m.M; ++i) {
+    uint4* orow = O + (r0 + i) * n_chunks;
+    if (i >= L) {
+      if (active) orow[c] = zero;
+      continue;
+    }
+    float q[8];
+    unpack8(active ? QKV[(r0 + i) * 3 * n_chunks + c] : zero, q);
+    float s[Z2Z_MAX_M];
+    float smax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      s[j] = -INFINITY;
+      if (j < L) {
+        float k[8];
+        unpack8(active ? QKV[(r0 + j) * 3 * n_chunks + n_chunks + c] : zero, k);
+        float dot = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) dot += q[t] * k[t];
+        for (int off = 1; off < lanes_per_head; off <<= 1) dot += __shfl_xor(dot, off);
+        s[j] = dot * scale;
+        smax = fmaxf(smax, s[j]);
+      }
+    }
+    float den = 0.f;
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      s[j] = j < L ? __expf(s[j] - smax) : 0.f;
+      den += s[j];
+    }
+    const float inv = 1.0f / den;
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      if (j < L) {
+        float v[8];
+        unpack8(active ? QKV[(r0 + j) * 3 * n_chunks + 2 * n_chunks + c] : zero, v);
+        const float p = s[j] * inv;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) o[t] += p * v[t];
+      }
+    }
+    if (active) orow[c] = pack8(o);
+  }
+}
+
+// h = mean of the entry's real slots of Z -> W_hyper[b, e]; one wave per entry.  Passes that start at entry 0
+// (full mode) also zero the rows of missing entries.
+__global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const uint4* Z, uint4* W, int n_units, int zero_missing) {
+  const int lane = threadIdx.x & 63;
+  const long long bu = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (bu >= n_units) return;
+  const int b = (int)(bu / m.un), u = (int)(bu % m.un);
+  const int n_chunks = m.d / 8;
+  int C;
+  const int e = entry_of(m, b, u, &C);
+  if (e >= m.cap) return;
+  uint4* wrow = W + ((size_t)b * m.cap + e) * n_chunks;
+  if (e >= C) {
+    if (zero_missing) {
+      const uint4 z = {0u, 0u, 0u, 0u};
+      for (int c = lane; c < n_chunks; c += 64) wrow[c] = z;
+    }
+    return;
+  }
+  const int L = min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M);
+  const float invL = 1.0f / (float)L;
+  const size_t r0 = (size_t)bu * m.M;
+  for (int c = lane; c < n_chunks; c += 64) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < L; ++i) {
+      float z[8];
+      unpack8(Z[(r0 + i) * n_chunks + c], z);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc[t] += z[t];
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] *= invL;
+    wrow[c] = pack8(acc);
+  }
+}
+
+}  // namespace
+
+bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc) {
+  const int d = c->cfg.d;
+  if (c->cfg.dtype != Z2Z_BF16 || !c->fast_ready || d % 64 != 0 || d > 64 * 8 * E_KCH) return false;
+  if (enc->n_heads < 1 || d % enc->n_heads != 0) return false;
+  const int dh = d / enc->n_heads;
+  if (dh < 8 || dh > 512 || (dh & (dh - 1)) != 0) return false;
+  if (!enc->attention_only && (enc->d_ff < 64 || enc->d_ff % 64 != 0)) return false;
+  return true;
+}
+
+int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, void* W_hyper, const int32_t* first,
+                            int32_t max_new, hipStream_t s) {
+  const int B = c->cfg.B, M = c->cfg.M, cap = c->cfg.cap, d = c->cfg.d;
+  if (cap == 0) return Z2Z_OK;
+  const bool incremental = first || max_new > 0;
+  const int units = incremental ? (max_new < 1 ? cap : (max_new < cap ? max_new : cap)) : cap;
+  const int dff = enc->attention_only ? 0 : enc->d_ff;
+  // rows per pass: all sequences, u_step entries each, M slots per entry
+  long long u_step = 65536 / ((long long)B * M);
+  if (u_step < 1) u_step = 1;
+  if (u_step > units) u_step = units;
+  const size_t R_max = (size_t)B * (size_t)u_step * M;
+  const size_t need = R_max * ((size_t)4 * d + (size_t)3 * d + (size_t)dff) * 2;
+  if (need > c->enc_ws_bytes) {
+    if (c->enc_ws) (void)hipFree(c->enc_ws);
+    c->enc_ws = nullptr;
+    c->enc_ws_bytes = 0;
+    if (hipMalloc(&c->enc_ws, need) != hipSuccess) return Z2Z_ENOMEM;
+    c->enc_ws_bytes = need;
+  }
+  uint16_t* ws = reinterpret_cast<uint16_t*>(c->enc_ws);
+  uint16_t* X = ws;
+  uint16_t* A = X + R_max * d;
+  uint16_t* O = A + R_max * d;
+  uint16_t* Y = O + R_max * d;
+  uint16_t* QKV = Y + R_max * d;
+  uint16_t* F = QKV + R_max * 3 * d;
+
+  RowMap m;
+  m.size = c->st.size;
+  m.ent_tokens = c->st.ent_tokens;
+  m.ent_len = c->st.ent_len;
+  m.first = first;
+  m.last_n = (!first && max_new > 0) ? max_new : 0;
+  m.B = B;
+  m.V = c->cfg.V;
+  m.M = M;
+  m.cap = cap;
+  m.d = d;
+  const int dh = d / enc->n_heads;
+  const int groups = (d + 511) / 512;
+  const float scale = 1.0f / sqrtf((float)dh);
+  for (int u0 = 0; u0 < units; u0 += (int)u_step) {
+    m.u0 = u0;
+    m.un = (int)(u0 + u_step <= units ? u_step : units - u0);
+    const int n_units = B * m.un;
+    const int R = n_units * M;
+    const unsigned row_blocks = (unsigned)((R + 3) / 4);
+    uint16_t* x = X;
+    uint16_t* y = Y;
+    for (int l = 0; l < enc->n_layers; ++l) {
+      const z2z_encoder_layer& lay = enc->layers[l];
+      if (l == 0)
+        hipLaunchKernelGGL(enc_norm_kernel<true>, dim3(row_blocks), dim3(256), 0, s, m,
+                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos),
+                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, R);
+      else
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
+                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, R);
+      int rc = z2z_launch_linear(c, A, lay.w_qkv, lay.b_qkv, nullptr, 0, QKV, R, 3 * d, d, s);
+      if (rc != Z2Z_OK) return rc;
+      const long long att_waves = (long long)n_units * groups;
+      hipLaunchKernelGGL(enc_attention_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
+                         reinterpret_cast<const uint4*>(QKV), reinterpret_cast<uint4*>(O), dh / 8, scale, groups,
+                         n_units);
+      rc = z2z_launch_linear(c, O, lay.w_o, lay.b_o, x, 0, y, R, d, d, s);
+      if (rc != Z2Z_OK) return rc;
+      if (enc->attention_only) {
+        uint16_t* t = x;
+        x = y;
+        y = t;
+      } else {
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
+                           reinterpret_cast<uint4*>(y), reinterpret_cast<uint4*>(A), lay.ln2_g, lay.ln2_b, R);
+        rc = z2z_launch_linear(c, A, lay.w_1, lay.b_1, nullptr, 1, F, R, dff, d, s);
+        if (rc != Z2Z_OK) return rc;
+        rc = z2z_launch_linear(c, F, lay.w_2, lay.b_2, y, 0, x, R, d, dff, s);
+        if (rc != Z2Z_OK) return rc;
+      }
+    }
+    hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
+                       reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(W_hyper), n_units,
+                       incremental ? 0 : 1);
+  }
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}

@@ -6,6 +6,8 @@
 // two launches; both leave (max, sum-exp, argmax) triples per (strip, row), merged in column order.
 #include "logits_common.h"
 
+#include <string.h>
+
 namespace {
 
 using namespace z2z_logits;
@@ -247,7 +249,7 @@ int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, 
     grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
   }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  int rc = fast ? z2z_launch_logits_fast(hyper, a, grid, s)
+  int rc = fast ? z2z_launch_logits_fast(hyper ? 1 : 0, a, grid, s)
                 : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
@@ -257,6 +259,38 @@ int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, 
 }
 
 }  // namespace
+
+int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
+                      void* out, int R, int N, int K, hipStream_t s) {
+  if (!c->fast_ready || K % 64 != 0 || N % 8 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
+  LogitsArgs a;
+  memset(&a, 0, sizeof(a));
+  a.H = A;
+  a.W = W;
+  a.rows = R;
+  a.rows_per_seq = R;
+  a.d = K;
+  a.w_rows = N;
+  a.n_vtiles = (N + 255) / 256;
+  a.row_tiles = (R + 255) / 256;
+  a.strip = (long long)a.row_tiles * a.n_vtiles >= 2048 ? 4 : 1;
+  a.n_strips = (a.n_vtiles + a.strip - 1) / a.strip;
+  a.n_work = a.row_tiles * a.n_strips;
+  a.out = out;
+  a.bias = bias;
+  a.residual = residual;
+  a.act = act;
+  a.ldo = N;
+  a.map_lr = 4;
+  a.map_ls = a.n_strips >= 8 ? 4 : 1;
+  a.map_xr = 4;
+  a.map_xs = 2;
+  const int sb_rows = a.map_xr * a.map_lr, sb_strips = a.map_xs * a.map_ls;
+  a.map_sb_r = (a.row_tiles + sb_rows - 1) / sb_rows;
+  const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;
+  const unsigned grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
+  return z2z_launch_logits_fast(2, a, grid, s);
+}
 
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,

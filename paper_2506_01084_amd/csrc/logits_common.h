@@ -96,6 +96,14 @@ __device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&
   }
 }
 
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678f)); }
+
 // ---- the counter-based generator of the sampling kernels: Philox4x32-10 (Salmon et al., SC'11) -------
 __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
 #pragma unroll
@@ -147,13 +155,72 @@ struct LogitsArgs {
   int32_t* part_i;
   float* logits;          // nullptr or [rows, ld]
   int32_t ld;
+  // linear mode of the bf16 MFMA kernel (a dense layer instead of a softmax fold):
+  // out[r, n] = act(H[r, :] . W[n, :] + bias[n]) + residual[r, n], bf16, row stride ldo
+  void* out;
+  const float* bias;      // [w_rows] or nullptr
+  const void* residual;   // [rows, ldo] bf16 or nullptr
+  int32_t act;            // 0 none, 1 GELU (erf)
+  int32_t ldo;
 };
+
+// Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
+// out[row, col] = act(acc + bias[col]) + residual[row, col], rounded once to bf16.  A lane holds runs of 4
+// consecutive columns of one row: 8-byte stores.  Columns come in fours, so n_valid must be a multiple of 4.
+template <int NI, int NJ>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const LogitsArgs& a, int row_base, int r_end,
+                                           int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = col_base + i * 32 + g * 8;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = read_acc(acc[i][j][g * 4 + e]);
+        if (row < r_end && col < n_valid) {
+          if (a.bias) {
+            const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
+            x[0] += bv.x;
+            x[1] += bv.y;
+            x[2] += bv.z;
+            x[3] += bv.w;
+          }
+          if (a.act == 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = gelu_erf(x[e]);
+          }
+          const size_t at = (size_t)row * a.ldo + col;
+          if (a.residual) {
+            const uint2 rv = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.residual) + at);
+            x[0] += __uint_as_float(rv.x << 16);
+            x[1] += __uint_as_float(rv.x & 0xFFFF0000u);
+            x[2] += __uint_as_float(rv.y << 16);
+            x[3] += __uint_as_float(rv.y & 0xFFFF0000u);
+          }
+          uint2 o;
+          o.x = bf16_bits_rne(x[0]) | (bf16_bits_rne(x[1]) << 16);
+          o.y = bf16_bits_rne(x[2]) | (bf16_bits_rne(x[3]) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = o;
+        }
+      }
+    }
+  }
+}
 
 }  // namespace z2z_logits
 
 // kernel launchers, one per translation unit
 int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
-int z2z_launch_logits_fast(bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
+// mode: 0 base part, 1 hyper part (both fold the joint softmax), 2 dense layer (stores the tile)
+int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
+// out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
+int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
+                      void* out, int R, int N, int K, hipStream_t s);
 int z2z_logits_fast_prepare(z2z_ctx* c);
 // temperature sampling (one-row-per-sequence kernel only): softmax(logit / temperature), generator key and
 // counter words from seed and step

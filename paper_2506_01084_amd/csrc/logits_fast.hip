@@ -104,7 +104,7 @@ struct Frags {
   uint4 b[F_NJ];
 };
 
-template <int HYPER>
+template <int MODE>
 __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
   const int tid = threadIdx.x;
@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   int r0, r_end, n_valid;
   const unsigned char* Wp = reinterpret_cast<const unsigned char*>(a.W);
   const size_t row_bytes = (size_t)a.d * 2;
-  if (HYPER) {
+  if (MODE == 1) {
     if ((int)blockIdx.x >= a.n_work) return;
     st = blockIdx.x % a.n_strips;
     rt = blockIdx.x / a.n_strips;
@@ -292,11 +292,18 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
       const int v0 = vt * FT;
-      fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
+      if (MODE == 2)
+        store_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      else
+        fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
       zero_acc();
     }
   }
 
+  if (MODE == 2) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the requests past the end of the stream land in LDS
+    return;
+  }
   // ---- end of strip: lanes l and l+32 hold the same hidden row; then the two vocabulary halves ------
 #pragma unroll
   for (int j = 0; j < F_NJ; ++j) {
@@ -332,8 +339,10 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 
 }  // namespace
 
-int z2z_launch_logits_fast(bool hyper, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (hyper)
+int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
+  if (mode == 2)
+    hipLaunchKernelGGL(logits_fast_kernel<2>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 1)
     hipLaunchKernelGGL(logits_fast_kernel<1>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else
     hipLaunchKernelGGL(logits_fast_kernel<0>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -346,6 +355,8 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<0>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

@@ -27,6 +27,7 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->part_l);
   (void)hipFree(c->sample_logits);
   (void)hipFree(c->row_max);
+  (void)hipFree(c->enc_ws);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
       (void)hipEventDestroy(c->ev_start[i]);
@@ -160,6 +161,27 @@ Z2Z_API int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, cons
   if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
   if (!aligned16(d_E) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
   return z2z_launch_hyper_embed(ctx, d_E, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, void* d_W_hyper,
+                             const int32_t* d_first, int32_t max_new, void* stream) {
+  if (!ctx || !d_E || !enc || !enc->layers) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (enc->n_layers < 1 || enc->n_layers > Z2Z_MAX_ENCODER_LAYERS) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_W_hyper) || !aligned16(enc->pos)) return Z2Z_EINVAL;
+  for (int l = 0; l < enc->n_layers; ++l) {
+    const z2z_encoder_layer& y = enc->layers[l];
+    const void* always[] = {y.ln1_g, y.ln1_b, y.w_qkv, y.b_qkv, y.w_o, y.b_o};
+    for (const void* p : always)
+      if (!p || !aligned16(p)) return Z2Z_EINVAL;
+    if (!enc->attention_only) {
+      const void* ffn[] = {y.ln2_g, y.ln2_b, y.w_1, y.b_1, y.w_2, y.b_2};
+      for (const void* p : ffn)
+        if (!p || !aligned16(p)) return Z2Z_EINVAL;
+    }
+  }
+  if (!z2z_hyper_encode_ok(ctx, enc)) return Z2Z_EUNSUPPORTED;
+  return z2z_launch_hyper_encode(ctx, d_E, enc, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,

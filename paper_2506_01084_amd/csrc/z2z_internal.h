@@ -49,6 +49,9 @@ struct z2z_ctx {
   float* row_max;
   size_t sample_logits_capacity;   // floats
   int trunc_ready;
+  // hyper_encode work space: the activations of one pass (bf16)
+  void* enc_ws;
+  size_t enc_ws_bytes;
   // options
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map,
       opt_sample_kernel;
@@ -77,6 +80,9 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
                                const void* W_hyper, float temperature, int32_t top_k, float top_p, uint64_t seed,
                                uint64_t step, int32_t* token, float* logprob, hipStream_t s);
 int z2z_sample_truncated_prepare(z2z_ctx* c);
+bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc);
+int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, void* W_hyper, const int32_t* first,
+                            int32_t max_new, hipStream_t s);
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                             const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s);
 

@@ -119,3 +119,17 @@ def check_logits_rows(ref: dict, argmax, mx, lse, logits=None, tol=2e-2, margin_
             C = n - V
             assert np.isneginf(logits[:, V + C:]).all(), "unused hyper slots must read -inf"
     return dict(max=float(e_max.max()), lse=float(e_lse.max()), logits=e_log)
+
+
+def encoder_to_device(enc: dict, dtype: str):
+    """Host encoder parameters (workloads.make_encoder) -> the binding's Encoder over device tensors."""
+    import torch
+    from paper_2506_01084_amd import api
+
+    layers = []
+    for lay in enc["layers"]:
+        layers.append({k: (torch_storage(v, dtype) if k.startswith("w_") else torch.from_numpy(v).cuda())
+                       for k, v in lay.items()})
+    params = dict(n_heads=enc["n_heads"], attention_only=enc["attention_only"], d_ff=enc["d_ff"],
+                  pos=None if enc["pos"] is None else torch_storage(enc["pos"], dtype), layers=layers)
+    return api.Encoder(params, torch.float32 if dtype == "f32" else torch.bfloat16)

@@ -1,0 +1,129 @@
+"""GPU parity: hyper_encode (the learned hyper-encoder of section 2.2: attention / transformer layers over an
+entry's padded slots, mean of the real slots) through the C ABI against the float64 oracle.
+
+Bar.  The HIP path keeps activations in bf16 between the steps of a layer (LayerNorm output, q|k|v, attention
+output, the residual stream after each block, the GELU output) and accumulates in fp32; the oracle computes in
+float64 from the same stored parameters and rounds once.  Each rounding is a relative 2^-9 of the rounded
+value; with random-init parameters of the scale used here (activations of order 1 entering every product, the
+residual stream of order 1) a layer adds about six such roundings that reach the output with weight of order
+1, so the tolerance is 4e-2 * max(1, largest |h| of the row) per element for up to two transformer layers,
+and the mean absolute error per row has to stay below a quarter of that.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_01084_amd import workloads as wl
+
+from helpers import encoder_to_device, gpu_encode, oracle_encode_batch, storage_to_host, torch_storage
+
+pytestmark = pytest.mark.gpu
+
+TOL = 4e-2
+
+
+def _compare(got_bits, ref64, label):
+    got = oracle.bf16_bits_to_f64(got_bits)
+    scale = np.maximum(1.0, np.abs(ref64).max(axis=-1, keepdims=True))
+    err = np.abs(got - ref64) / scale
+    assert err.max() <= TOL, f"{label}: max error {err.max():.4f}"
+    assert err.mean(axis=-1).max() <= TOL / 4, f"{label}: mean row error {err.mean(axis=-1).max():.4f}"
+    return float(err.max()), float(err.mean())
+
+
+def _setup(cfg, lens):
+    import torch
+    from paper_2506_01084_amd import api
+
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    ctx = api.Context(B=cfg["B"], V=cfg["V"], M=cfg["M"], cap=cfg["cap"], d=cfg["d"], dtype="bf16")
+    gpu_encode(ctx, tokens, lens)
+    ref = oracle_encode_batch(tokens, lens, cfg["V"], cfg["M"], cfg["cap"])
+    d_E = torch_storage(E, "bf16")
+    torch.cuda.synchronize()
+    return ctx, ref, E, d_E
+
+
+@pytest.mark.parametrize("B,N,V,d,M,cap,n_layers,n_heads,d_ff,attn_only,with_pos", [
+    (3, 300, 1000, 256, 3, 200, 2, 4, 512, False, True),       # two transformer layers, the paper's M
+    (2, 200, 500, 128, 5, 90, 1, 2, 0, True, True),            # one attention layer, deeper merges
+    (2, 260, 700, 512, 3, 130, 1, 1, 192, False, False),       # one head as wide as a wave's 512 features
+    (5, 150, 400, 64, 4, 64, 3, 8, 64, False, True),           # heads of 8 features (one lane each)
+    (1, 900, 3000, 1024, 3, 600, 1, 8, 1024, False, True),     # rows spanning several 256-row tiles
+])
+def test_hyper_encode_matches_oracle_every_entry(B, N, V, d, M, cap, n_layers, n_heads, d_ff, attn_only, with_pos):
+    import torch
+
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=11 * B + d)
+    print(f"[case] hyper_encode B={B} d={d} M={M} cap={cap} layers={n_layers} heads={n_heads} d_ff={d_ff} "
+          f"attention_only={attn_only}", flush=True)
+    lens = wl.make_lens(cfg, ragged=True)
+    if B > 1:
+        lens[1] = 0
+    ctx, ref, E, d_E = _setup(cfg, lens)
+    enc = wl.make_encoder(cfg, n_layers=n_layers, n_heads=n_heads, d_ff=d_ff, attention_only=attn_only,
+                          with_pos=with_pos)
+    d_enc = encoder_to_device(enc, "bf16")
+    d_W = torch.full((B, cap, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, d_W)
+    torch.cuda.synchronize()
+    W = storage_to_host(d_W, "bf16")
+    worst = 0.0
+    for b in range(B):
+        entries = ref[b][1]
+        want = oracle.hyper_encode(E, "bf16", entries, cap, enc, rounded=False)
+        if entries:
+            worst = max(worst, _compare(W[b, :len(entries)], want[:len(entries)], f"seq {b}")[0])
+        assert (W[b, len(entries):] == 0).all(), f"seq {b}: rows of missing entries must be zero"
+    print(f"  worst relative error {worst:.4f}", flush=True)
+    ctx.close()
+
+
+def test_incremental_modes_recompute_the_same_bits():
+    """A row's result depends on that entry alone, so recomputing a range of entries (from d_first, or the last
+    n) gives the bits of the full pass and leaves every other row untouched."""
+    import torch
+
+    B, N, V, d, M, cap = 4, 400, 800, 256, 3, 256
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=5)
+    lens = wl.make_lens(cfg, ragged=True)
+    ctx, ref, E, d_E = _setup(cfg, lens)
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=4, d_ff=256)
+    d_enc = encoder_to_device(enc, "bf16")
+    full = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, full)
+    sizes = np.array([len(r[1]) for r in ref])
+    # from d_first
+    first = np.maximum(sizes - np.array([3, 50, 0, 7]), 0).astype(np.int32)
+    part = torch.full((B, cap, d), -3.0, dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, part, torch.from_numpy(first).cuda(), 50)
+    # the last 2
+    last = torch.full((B, cap, d), -3.0, dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, last, None, 2)
+    torch.cuda.synchronize()
+    f, p, l = (storage_to_host(t, "bf16") for t in (full, part, last))
+    untouched = oracle.f64_to_bf16_bits(np.array([-3.0]))[0]
+    for b in range(B):
+        C = sizes[b]
+        assert np.array_equal(p[b, first[b]:C], f[b, first[b]:C])
+        assert (p[b, :first[b]] == untouched).all() and (p[b, C:] == untouched).all()
+        lo = max(C - 2, 0)
+        assert np.array_equal(l[b, lo:C], f[b, lo:C])
+        assert (l[b, :lo] == untouched).all() and (l[b, C:] == untouched).all()
+    ctx.close()
+
+
+def test_unsupported_shapes_are_refused():
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=1, N=64, V=100, d=192, M=3, cap=16)
+    ctx = api.Context(B=1, V=100, M=3, cap=16, d=192, dtype="bf16")
+    ctx.reset()
+    E = torch.zeros((100, 192), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((1, 16, 192), dtype=torch.bfloat16, device="cuda")
+    enc = encoder_to_device(wl.make_encoder(cfg, n_layers=1, n_heads=4, d_ff=64), "bf16")     # heads of 48 features
+    with pytest.raises(api.Z2ZError):
+        ctx.hyper_encode(E, enc, W)
+    ctx.close()
