@@ -262,6 +262,10 @@ int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, 
 
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, int N, int K, hipStream_t s) {
+  // few rows: bound by the weight bytes, which the decode-step kernel streams at HBM rate (it re-reads them
+  // once per 64 rows, so it loses to the tile kernel beyond a few hundred rows)
+  if (R <= 512 && c->skinny_ready && K % 128 == 0 && N % 2 == 0 && c->opt_logits_kernel != 2)
+    return z2z_launch_linear_skinny(c, A, W, bias, residual, act, out, R, N, K, s);
   if (!c->fast_ready || K % 64 != 0 || N % 8 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
   LogitsArgs a;
   memset(&a, 0, sizeof(a));
@@ -281,10 +285,39 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.residual = residual;
   a.act = act;
   a.ldo = N;
-  a.map_lr = 4;
-  a.map_ls = a.n_strips >= 8 ? 4 : 1;
-  a.map_xr = 4;
-  a.map_xs = 2;
+  // Workgroup ids go round-robin over the 8 XCDs and the mapping gives XCD (xr_i, xs_i) the row tiles whose
+  // block index is xr_i mod map_xr and the strips whose block index is xs_i mod map_xs: an XCD's share is the
+  // product of the two counts.  Take the mapping with the smallest largest share (nobody waits for one XCD),
+  // and among equals the one with the largest blocks (what runs together shares operand tiles through L2).
+  {
+    long long best_load = -1;
+    int best_area = 0;
+    const int xrs[4] = {8, 4, 2, 1};
+    for (int xi = 0; xi < 4; ++xi)
+      for (int lr = 4; lr >= 1; lr >>= 1)
+        for (int ls = 8; ls >= 1; ls >>= 1) {
+          const int xr = xrs[xi], xs = 8 / xr;
+          long long worst = 0;
+          for (int i = 0; i < xr; ++i) {
+            long long rows_i = 0;
+            for (int blk = i; blk * lr < a.row_tiles; blk += xr) rows_i += (blk + 1) * lr <= a.row_tiles ? lr : a.row_tiles - blk * lr;
+            for (int j = 0; j < xs; ++j) {
+              long long strips_j = 0;
+              for (int blk = j; blk * ls < a.n_strips; blk += xs) strips_j += (blk + 1) * ls <= a.n_strips ? ls : a.n_strips - blk * ls;
+              if (rows_i * strips_j > worst) worst = rows_i * strips_j;
+            }
+          }
+          const int area = lr * ls;
+          if (best_load < 0 || worst < best_load || (worst == best_load && area > best_area)) {
+            best_load = worst;
+            best_area = area;
+            a.map_lr = lr;
+            a.map_ls = ls;
+            a.map_xr = xr;
+            a.map_xs = xs;
+          }
+        }
+  }
   const int sb_rows = a.map_xr * a.map_lr, sb_strips = a.map_xs * a.map_ls;
   a.map_sb_r = (a.row_tiles + sb_rows - 1) / sb_rows;
   const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;

@@ -102,7 +102,19 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
   return u >> 16;
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678f)); }
+// GELU(x) = x * Phi(x) with the exact (erf) Phi.  erf by the rational approximation 7.1.26 of Abramowitz and
+// Stegun, erf(z) = 1 - (a1 t + ... + a5 t^5) exp(-z^2), t = 1 / (1 + p z), z >= 0: absolute error below
+// 1.5e-7, far inside the bf16 rounding of the result, at a third of the instructions of the library erff (the
+// epilogue of a dense layer evaluates it 65536 times per tile with the matrix cores waiting).
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float z = fabsf(x) * 0.70710678f;
+  const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));
+  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f),
+                              0.254829592f);
+  const float erf_abs = 1.0f - poly * __expf(-z * z);
+  const float phi = 0.5f * (1.0f + copysignf(erf_abs, x));
+  return x * phi;
+}
 
 // ---- the counter-based generator of the sampling kernels: Philox4x32-10 (Salmon et al., SC'11) -------
 __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
@@ -167,13 +179,36 @@ struct LogitsArgs {
 // Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
 // out[row, col] = act(acc + bias[col]) + residual[row, col], rounded once to bf16.  A lane holds runs of 4
 // consecutive columns of one row: 8-byte stores.  Columns come in fours, so n_valid must be a multiple of 4.
+// The loads the epilogue needs are issued in batches ahead of their use (the bias of all the lane's columns
+// once, the residual of a whole 32-row block at a time): one memory round trip per batch instead of one per
+// run, during which the matrix cores have nothing to do.
 template <int NI, int NJ>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const LogitsArgs& a, int row_base, int r_end,
                                            int col_base, int n_valid) {
   const int lane31 = threadIdx.x & 31;
+  float4 bias[NI][4];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int col = col_base + i * 32 + g * 8;
+      bias[i][g] = (a.bias && col < n_valid) ? *reinterpret_cast<const float4*>(a.bias + col) : float4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int row = row_base + j * 32 + lane31;
+    const bool row_ok = row < r_end;
+    uint2 res[NI][4];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = col_base + i * 32 + g * 8;
+        res[i][g] = (a.residual && row_ok && col < n_valid)
+                        ? *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.residual) +
+                                                          (size_t)row * a.ldo + col)
+                        : uint2{0u, 0u};
+      }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
 #pragma unroll
@@ -182,30 +217,23 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const Lo
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) x[e] = read_acc(acc[i][j][g * 4 + e]);
-        if (row < r_end && col < n_valid) {
-          if (a.bias) {
-            const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
-            x[0] += bv.x;
-            x[1] += bv.y;
-            x[2] += bv.z;
-            x[3] += bv.w;
-          }
-          if (a.act == 1) {
+        x[0] += bias[i][g].x;
+        x[1] += bias[i][g].y;
+        x[2] += bias[i][g].z;
+        x[3] += bias[i][g].w;
+        if (a.act == 1) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x[e] = gelu_erf(x[e]);
-          }
-          const size_t at = (size_t)row * a.ldo + col;
-          if (a.residual) {
-            const uint2 rv = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.residual) + at);
-            x[0] += __uint_as_float(rv.x << 16);
-            x[1] += __uint_as_float(rv.x & 0xFFFF0000u);
-            x[2] += __uint_as_float(rv.y << 16);
-            x[3] += __uint_as_float(rv.y & 0xFFFF0000u);
-          }
+          for (int e = 0; e < 4; ++e) x[e] = gelu_erf(x[e]);
+        }
+        x[0] += __uint_as_float(res[i][g].x << 16);
+        x[1] += __uint_as_float(res[i][g].x & 0xFFFF0000u);
+        x[2] += __uint_as_float(res[i][g].y << 16);
+        x[3] += __uint_as_float(res[i][g].y & 0xFFFF0000u);
+        if (row_ok && col < n_valid) {
           uint2 o;
           o.x = bf16_bits_rne(x[0]) | (bf16_bits_rne(x[1]) << 16);
           o.y = bf16_bits_rne(x[2]) | (bf16_bits_rne(x[3]) << 16);
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = o;
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + (size_t)row * a.ldo + col) = o;
         }
       }
     }
@@ -236,6 +264,10 @@ int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* ro
                                 float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
                                 int32_t* token, float* logprob, hipStream_t s);
 size_t z2z_sample_truncated_work_floats(int32_t rows);
+// the same layer on the bandwidth-bound kernel of the decode step (few rows: every weight byte is read once per
+// 64 rows); K a multiple of 128, N even
+int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
+                             int act, void* out, int R, int N, int K, hipStream_t s);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 void z2z_logits_decode_units(int* base_columns, int* hyper_columns);
 bool z2z_logits_decode_ok(const z2z_ctx* c);

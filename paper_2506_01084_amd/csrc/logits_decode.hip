@@ -22,6 +22,8 @@
 // Each unit leaves one triple per hidden row in the same [row][part] scratch the prefill kernels use.
 #include "logits_common.h"
 
+#include <string.h>
+
 namespace {
 
 using namespace z2z_logits;
@@ -30,6 +32,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 constexpr int D_UNIT = 512;            // weight rows per hyper unit
 constexpr int D_BASE_UNIT = 256;       // weight rows per base unit
+constexpr int D_LINEAR_UNIT = 64;      // output features per unit of a dense layer (MODE 3)
 constexpr int D_THREADS = 512;
 constexpr int D_KSLICE = 128;          // K elements a wave keeps of H
 constexpr int D_QB = D_KSLICE / 32;    // MFMA k-blocks per slice
@@ -62,6 +65,13 @@ struct DecodeArgs {
   int32_t ld;
   uint32_t key0, key1;    // generator key: the seed
   uint32_t ctr2, ctr3;    // generator counter words 2, 3: the step
+  // MODE 3, a dense layer on a few rows: out[h, v] = act(H[h, :] . W_base[v, :] + bias[v]) + residual[h, v],
+  // bf16, row stride ldo; no triples are kept
+  uint16_t* out;
+  const float* bias;
+  const uint16_t* residual;
+  int32_t act;            // 0 none, 1 GELU (erf)
+  int32_t ldo;
 };
 
 __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
@@ -138,17 +148,20 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float* tile = reinterpret_cast<float*>(lds);                      // [256][64]
+  // weight rows per unit: 256 for the vocabulary; a dense layer has few output rows and needs many
+  // workgroups to fill the machine, so its units are 64 rows
+  constexpr int UNIT = MODE == 3 ? D_LINEAR_UNIT : D_BASE_UNIT;
+  float* tile = reinterpret_cast<float*>(lds);                      // [UNIT][64]
   float* slots = reinterpret_cast<float*>(lds + D_TILE_BYTES);       // [2][8][64][D_SLOT_STRIDE]
-  const int v0 = unit * D_BASE_UNIT;
+  const int v0 = unit * UNIT;
   const int h0 = group * 64;
   const int n_h = min(64, a.B - h0);               // hidden rows of this group
   const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
   const int n_slices = a.d / D_KSLICE;
   const int n_phases = (n_slices + 7) >> 3;
-  constexpr int N_BLK = D_BASE_UNIT / 16;
+  constexpr int N_BLK = UNIT / 16;
 
-  for (int i = tid; i < D_BASE_UNIT * 64; i += D_THREADS) tile[i] = 0.f;
+  for (int i = tid; i < UNIT * 64; i += D_THREADS) tile[i] = 0.f;
 
   const int m16 = lane & 15;     // MFMA row (A) / column (B) index of this lane
   const int kg = lane >> 4;      // which 8 of the 32 k of an MFMA this lane feeds
@@ -244,6 +257,35 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
         a.logits[(size_t)(h0 + jj) * a.ld + v0 + r] = stage[jj * ST + r] * a.inv_temperature;
     }
     __syncthreads();
+  }
+  if (MODE == 3) {
+    // dense layer: the same transposition, then bias, activation, residual and one rounding per element
+    constexpr int ST = UNIT + 1;
+    float* stage = slots;                                            // [64][UNIT + 1]
+    for (int i = tid; i < UNIT * 64; i += D_THREADS) stage[(i & 63) * ST + (i >> 6)] = tile[i];
+    __syncthreads();
+    for (int i = tid; i < 64 * (UNIT / 2); i += D_THREADS) {
+      const int jj = i / (UNIT / 2), r = 2 * (i - jj * (UNIT / 2));     // a pair of columns
+      if (jj < n_h && v0 + r < a.V) {                                                 // V is even
+        float x0 = stage[jj * ST + r], x1 = stage[jj * ST + r + 1];
+        if (a.bias) {
+          x0 += a.bias[v0 + r];
+          x1 += a.bias[v0 + r + 1];
+        }
+        if (a.act == 1) {
+          x0 = gelu_erf(x0);
+          x1 = gelu_erf(x1);
+        }
+        const size_t at = (size_t)(h0 + jj) * a.ldo + v0 + r;
+        if (a.residual) {
+          const uint32_t rv = *reinterpret_cast<const uint32_t*>(a.residual + at);
+          x0 += __uint_as_float(rv << 16);
+          x1 += __uint_as_float(rv & 0xFFFF0000u);
+        }
+        *reinterpret_cast<uint32_t*>(a.out + at) = bf16_bits_rne(x0) | (bf16_bits_rne(x1) << 16);
+      }
+    }
+    return;
   }
   // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 32 .. + 32, in increasing order
   Triple* xch = reinterpret_cast<Triple*>(lds + D_TILE_BYTES);       // the slots are idle now
@@ -445,6 +487,33 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   return Z2Z_OK;
 }
 
+// A dense layer on few rows (R up to a few hundred) is bound by the weight bytes like the decode step: the
+// base-unit workgroups of the kernel above, with the layer's epilogue instead of the softmax fold.
+int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
+                             int act, void* out, int R, int N, int K, hipStream_t s) {
+  if (c->lds_limit < D_LDS || K % D_KSLICE != 0 || N % 2 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
+  DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.H = reinterpret_cast<const uint4*>(A);
+  a.W_base = reinterpret_cast<const uint4*>(W);
+  a.B = R;
+  a.V = N;
+  a.cap = 0;
+  a.d = K;
+  a.n_base_units = (N + D_LINEAR_UNIT - 1) / D_LINEAR_UNIT;
+  a.n_groups = (R + 63) / 64;
+  a.units_per_seq = 0;
+  a.out = reinterpret_cast<uint16_t*>(out);
+  a.bias = bias;
+  a.residual = reinterpret_cast<const uint16_t*>(residual);
+  a.act = act;
+  a.ldo = N;
+  const unsigned grid = (unsigned)(a.n_base_units * a.n_groups);
+  hipLaunchKernelGGL(logits_decode_kernel<3>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
 int z2z_logits_decode_parts(const z2z_ctx* c) {
   return (c->cfg.V + D_BASE_UNIT - 1) / D_BASE_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
 }
@@ -465,6 +534,8 @@ int z2z_logits_decode_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   return Z2Z_OK;
 }

@@ -56,6 +56,7 @@ struct z2z_ctx {
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map,
       opt_sample_kernel;
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration
+  int skinny_ready;        // the decode-step kernel's LDS fits this device (dense layers on few rows use it)
   int fast_ready;          // the 128 KiB-LDS bf16 logits kernel can be launched on this device
   // timing record
   hipEvent_t ev_start[Z2Z_MAX_TIMED];

@@ -6,7 +6,7 @@ output, the residual stream after each block, the GELU output) and accumulates i
 float64 from the same stored parameters and rounds once.  Each rounding is a relative 2^-9 of the rounded
 value; with random-init parameters of the scale used here (activations of order 1 entering every product, the
 residual stream of order 1) a layer adds about six such roundings that reach the output with weight of order
-1, so the tolerance is 4e-2 * max(1, largest |h| of the row) per element for up to two transformer layers,
+1, so the tolerance is 2e-2 * max(1, largest |h| of the row) per element for up to two transformer layers,
 and the mean absolute error per row has to stay below a quarter of that.
 """
 import numpy as np
@@ -19,7 +19,7 @@ from helpers import encoder_to_device, gpu_encode, oracle_encode_batch, storage_
 
 pytestmark = pytest.mark.gpu
 
-TOL = 4e-2
+TOL = 2e-2
 
 
 def _compare(got_bits, ref64, label):
@@ -51,6 +51,8 @@ def _setup(cfg, lens):
     (2, 260, 700, 512, 3, 130, 1, 1, 192, False, False),       # one head as wide as a wave's 512 features
     (5, 150, 400, 64, 4, 64, 3, 8, 64, False, True),           # heads of 8 features (one lane each)
     (1, 900, 3000, 1024, 3, 600, 1, 8, 1024, False, True),     # rows spanning several 256-row tiles
+    (2, 150, 400, 256, 3, 64, 2, 4, 512, False, True),         # 384 slot rows: the few-rows kernel for the layers
+    (1, 100, 300, 384, 4, 20, 1, 6, 1152, False, True),        # 80 rows, K = 384 and 1152 (3 and 9 slices of 128)
 ])
 def test_hyper_encode_matches_oracle_every_entry(B, N, V, d, M, cap, n_layers, n_heads, d_ff, attn_only, with_pos):
     import torch
@@ -80,9 +82,11 @@ def test_hyper_encode_matches_oracle_every_entry(B, N, V, d, M, cap, n_layers, n
     ctx.close()
 
 
-def test_incremental_modes_recompute_the_same_bits():
+def test_incremental_modes_recompute_the_same_rows():
     """A row's result depends on that entry alone, so recomputing a range of entries (from d_first, or the last
-    n) gives the bits of the full pass and leaves every other row untouched."""
+    n) reproduces the rows of the full pass and leaves every other row untouched.  With the same kernels the
+    bits are the same; a pass of few rows takes its dense layers on another kernel (another summation order),
+    and then the rows agree to the rounding of the bf16 activations."""
     import torch
 
     B, N, V, d, M, cap = 4, 400, 800, 256, 3, 256
@@ -109,7 +113,8 @@ def test_incremental_modes_recompute_the_same_bits():
         assert np.array_equal(p[b, first[b]:C], f[b, first[b]:C])
         assert (p[b, :first[b]] == untouched).all() and (p[b, C:] == untouched).all()
         lo = max(C - 2, 0)
-        assert np.array_equal(l[b, lo:C], f[b, lo:C])
+        if C > lo:
+            _compare(l[b, lo:C], oracle.bf16_bits_to_f64(f[b, lo:C]), f"last two of seq {b}")
         assert (l[b, :lo] == untouched).all() and (l[b, C:] == untouched).all()
     ctx.close()
 
