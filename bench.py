@@ -10,6 +10,8 @@ shapes: 8 x 4096 tokens, V = 128256, d = 4096 bf16, M = 3, cap = 2048), inputs r
 
 `value` is base tokens per second of that whole step.  The decode step of configuration 3 (64 sequences
 with 8192-token histories, HBM-bound) is timed separately in the same run and reported in `decode_step`.
+The learned hyper-encoder (a two-layer transformer over every entry's slots, in place of the averaging one) is
+timed on configuration 2's codebooks and reported in `hyper_encode`.
 The CPU oracle is timed on a bounded sample of the same workload as `cpu_baseline`.
 
 Prints ONE JSON line on stdout.
@@ -281,6 +283,55 @@ def run_decode_workload(args, torch, api, wl):
                           "bytes_per_launch": bytes_step})
 
 
+def run_encoder_workload(args, torch, api, wl):
+    """Configuration 2 with the learned hyper-encoder in place of the averaging one: all 8 x 2048 entries
+    through a two-layer transformer encoder (32 heads, d_ff = 4 d, random-init parameters), then the update of
+    a generation step (the newest entry of every sequence only)."""
+    cfg = wl.CONFIGS["c2"]
+    B, N, V, M, cap, d = (cfg[k] for k in ("B", "N", "V", "M", "cap", "d"))
+    t0 = time.time()
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=32)
+    log(f"[bench] encoder parameters generated in {time.time() - t0:.1f}s")
+    layers = [{k: (to_device_bf16(torch, v) if k.startswith("w_") else torch.from_numpy(v).cuda()) for k, v in lay.items()}
+              for lay in enc["layers"]]
+    d_enc = api.Encoder(dict(n_heads=enc["n_heads"], attention_only=False, d_ff=enc["d_ff"],
+                             pos=to_device_bf16(torch, enc["pos"]), layers=layers), torch.bfloat16)
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_tok = torch.from_numpy(wl.make_tokens(cfg)).cuda()
+    d_codes, d_n, d_st = torch.empty((B, N), **i32), torch.empty(B, **i32), torch.empty(B, **i32)
+    ctx.lzw_encode(d_tok, None, d_codes, d_n, d_st, api.RESET)
+    d_E = to_device_bf16(torch, wl.make_embeddings(cfg))
+    d_W = torch.empty((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    sizes = ctx.codebook()[2].cpu().numpy()
+
+    def timed(reps, **kw):
+        ctx.hyper_encode(d_E, d_enc, d_W, **kw)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            ctx.hyper_encode(d_E, d_enc, d_W, **kw)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    ms_full = timed(3)
+    ms_inc = timed(20, first=None, max_new=1)
+    rows = int(sizes.sum()) * M                       # slot rows of existing entries (padding slots included)
+    flops = 2.0 * rows * 2 * (4 * d * d + 2 * d * enc["d_ff"])
+    weight_bytes = 2 * 2.0 * (4 * d * d + 2 * d * enc["d_ff"])
+    ctx.close()
+    return {
+        "workload": f"c2 codebooks ({int(sizes.sum())} entries x M={M} slots), learned hyper-encoder: 2 pre-norm "
+                    f"transformer layers, 32 heads, d_ff={enc['d_ff']}, d={d} bf16",
+        "full_ms": ms_full, "dense_flops": flops, "TFLOPs": flops / (ms_full * 1e-3) / 1e12,
+        "frac_of_bf16_peak": flops / (ms_full * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "newest_entry_us": ms_inc * 1e3, "newest_entry_weight_bytes": weight_bytes,
+        "newest_entry_GBs": weight_bytes / (ms_inc * 1e-3) / 1e9,
+    }
+
+
 def cpu_baseline(wl, host, budget_rows=4096):
     """The oracle, as it stands, on the host cores: LZW and pooling on the full configuration-2 batch, the
     joint logits on a sample of rows of sequence 0 (all columns); combined into tokens/s of the whole step."""
@@ -324,6 +375,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-encoder", action="store_true", help="skip the learned hyper-encoder measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -350,6 +402,7 @@ def main():
     k_ms = res["kernel_ms_total"] / res["kernel_launches"]
     log(f"[bench] step {res['ms_per_step']:.2f} ms; stages {res['stage_ms']}; base-part kernel {k_ms:.3f} ms")
     dec = None if args.no_decode else run_decode_workload(args, torch, api, wl)
+    enc = None if args.no_encoder else run_encoder_workload(args, torch, api, wl)
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host)
 
     cfg = res["cfg"]
@@ -385,6 +438,7 @@ def main():
                      "avg_kernel_ms": k_ms, "flops_per_launch": res["flops_base"]},
         "cpu_baseline": cpu,
         "decode_step": dec,
+        "hyper_encode": enc,
     }
     print(json.dumps(line), flush=True)
 

@@ -132,3 +132,43 @@ def test_unsupported_shapes_are_refused():
     with pytest.raises(api.Z2ZError):
         ctx.hyper_encode(E, enc, W)
     ctx.close()
+
+
+def test_full_size_c2_two_layer_transformer_sampled_entries():
+    """Configuration 2's codebooks through the encoder the benchmark times (two transformer layers, 32 heads,
+    d_ff = 4 d): sampled entries against the oracle, for the full pass (tile kernel) and for the newest entry of
+    every sequence recomputed alone (the few-rows kernel, K up to 16384)."""
+    import time
+    import torch
+
+    cfg = wl.CONFIGS["c2"]
+    B, cap, d = cfg["B"], cfg["cap"], cfg["d"]
+    t0 = time.time()
+    print("[case] full size hyper_encode c2", flush=True)
+    ctx, ref, E, d_E = _setup(cfg, np.full(B, cfg["N"], dtype=np.int32))
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=32)
+    d_enc = encoder_to_device(enc, "bf16")
+    d_W = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, d_W)
+    torch.cuda.synchronize()
+    full = storage_to_host(d_W, "bf16")
+    d_W2 = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, d_W2, None, 1)
+    torch.cuda.synchronize()
+    newest = storage_to_host(d_W2, "bf16")
+    print(f"  GPU passes done {time.time() - t0:.1f}s", flush=True)
+    picks = []
+    for b in (0, 3, 7):
+        C = len(ref[b][1])
+        picks += [(b, i) for i in (0, 1, C // 3, C - 1)]
+    want = oracle.hyper_encode(E, "bf16", [ref[b][1][i] for b, i in picks], len(picks), enc, rounded=False)
+    print(f"  oracle done {time.time() - t0:.1f}s", flush=True)
+    for k, (b, i) in enumerate(picks):
+        e_full = _compare(full[b, i:i + 1], want[k:k + 1], f"full pass, seq {b} entry {i}")
+        if i == len(ref[b][1]) - 1:
+            e_new = _compare(newest[b, i:i + 1], want[k:k + 1], f"newest entry, seq {b}")
+            print(f"  seq {b} entry {i} (len {len(ref[b][1][i])}): full {e_full[0]:.4f}, alone {e_new[0]:.4f}", flush=True)
+    for b in range(B):
+        C = len(ref[b][1])
+        assert (newest[b, :C - 1] == 0).all() and (newest[b, C:] == 0).all()
+    ctx.close()
