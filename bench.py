@@ -318,12 +318,12 @@ def run_encoder_workload(args, torch, api, wl):
 
     ms_full = timed(3)
     ms_inc = timed(20, first=None, max_new=1)
-    rows = int(sizes.sum()) * M                       # slot rows of existing entries (padding slots included)
+    rows = int(ctx.codebook()[1].sum().item())        # real slots of the existing entries = rows of the dense layers
     flops = 2.0 * rows * 2 * (4 * d * d + 2 * d * enc["d_ff"])
     weight_bytes = 2 * 2.0 * (4 * d * d + 2 * d * enc["d_ff"])
     ctx.close()
     return {
-        "workload": f"c2 codebooks ({int(sizes.sum())} entries x M={M} slots), learned hyper-encoder: 2 pre-norm "
+        "workload": f"c2 codebooks ({int(sizes.sum())} entries, {rows} real slots of M={M}), learned hyper-encoder: 2 pre-norm "
                     f"transformer layers, 32 heads, d_ff={enc['d_ff']}, d={d} bf16",
         "full_ms": ms_full, "dense_flops": flops, "TFLOPs": flops / (ms_full * 1e-3) / 1e12,
         "frac_of_bf16_peak": flops / (ms_full * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

@@ -7,13 +7,14 @@
 //   X_i = E[y_i] + P_i;  A = LN1(X);  QKV = A Wqkv^T + b;  O = softmax(Q K^T / sqrt(d_head)) V per head;
 //   Y = X + O Wo^T + bo;  Z = Y + GELU(LN2(Y) W1^T + b1) W2^T + b2  (transformer layers);  h = mean_i Z_i.
 //
-// All entries of a pass are batched: row (b, u, i) = slot i of the u-th entry taken from sequence b, so every
-// dense layer is one [rows, K] x [N, K]^T product on the bf16 MFMA kernel with bias / GELU / residual in its
-// epilogue.  The kernels in this file are the bandwidth-bound rest: gather + LayerNorm (one wave per row, the
-// row held in registers: read once), the M x M attention per entry and head (a wave per entry and 512
-// features: 64 lanes x 16 bytes, a head's dot products reduced across its lanes), and the final mean.  Padding
-// slots and missing entries are zero rows: they cost their share of the products but never reach a result.
-// Activations between kernels are bf16, accumulation and statistics fp32.
+// All entries of a pass are batched, and only their real slots are rows: a one-workgroup scan over the entry
+// lengths gives every entry its first row (padding slots and missing entries take no rows at all; a quarter
+// of the M slots of a typical codebook is padding), the number of rows stays on the device and the kernels
+// read it there.  Every dense layer is then one [rows, K] x [N, K]^T product on the bf16 MFMA kernel with
+// bias / GELU / residual in its epilogue.  The kernels in this file are the bandwidth-bound rest: gather +
+// LayerNorm (one wave per row, the row held in registers: read once), the L x L attention per entry and head
+// (a wave per entry and 512 features: 64 lanes x 16 bytes, a head's dot products reduced across its lanes),
+// and the final mean.  Activations between kernels are bf16, accumulation and statistics fp32.
 #include "logits_common.h"
 
 namespace {
@@ -30,7 +31,11 @@ struct RowMap {                      // which entries a pass covers, and where t
   const int32_t* first;              // [B] or nullptr
   int32_t last_n;                    // first == nullptr: 0 = entries from 0, n > 0 = the last n entries
   int32_t B, V, M, cap, d;
-  int32_t u0, un;                    // entry units [u0, u0 + un) of every sequence; rows = B * un * M
+  int32_t u0, un;                    // entry units [u0, u0 + un) of every sequence
+  // packed rows of this pass: entry unit bu = b * un + u owns rows [row0[bu], row0[bu + 1]), one per real slot;
+  // row0[B * un] is the number of rows; row_slot[r] = bu * 8 + slot of row r
+  int32_t* row0;
+  int32_t* row_slot;
 };
 
 __device__ __forceinline__ int entry_of(const RowMap& m, int b, int u, int* C_out) {
@@ -66,34 +71,63 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One wave per row.  GATHER: X[r] = bf16(E[token] + P[slot]) is formed and stored first (zero for padding
-// slots and missing entries, whose A row is zero as well).  Then A[r] = LN(X[r]) * gamma + beta, statistics
+__device__ __forceinline__ int entry_len(const RowMap& m, int b, int u) {
+  int C;
+  const int e = entry_of(m, b, u, &C);
+  return e < C ? min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M) : 0;
+}
+
+// Rows of the pass: exclusive scan of the entry lengths over all entry units, one workgroup of 1024 threads,
+// each taking a run of consecutive units.
+__global__ void __launch_bounds__(1024) enc_rows_kernel(RowMap m, int n_units) {
+  __shared__ int wave_tot[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (n_units + 1023) / 1024;
+  const int b0 = tid * per, b1 = min(b0 + per, n_units);
+  int mine = 0;
+  for (int bu = b0; bu < b1; ++bu) mine += entry_len(m, bu / m.un, bu % m.un);
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  int base = incl - mine;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  for (int bu = b0; bu < b1; ++bu) {
+    const int L = entry_len(m, bu / m.un, bu % m.un);
+    m.row0[bu] = base;
+    for (int i = 0; i < L; ++i) m.row_slot[base + i] = bu * 8 + i;
+    base += L;
+  }
+  if (tid == 1023) {
+    int total = 0;
+    for (int w = 0; w < 16; ++w) total += wave_tot[w];
+    m.row0[n_units] = total;
+  }
+}
+
+// One wave per row.  GATHER: X[r] = bf16(E[token] + P[slot]) is formed and stored first.  Then A[r] = LN(X[r]) * gamma + beta, statistics
 // over the stored (rounded) values in two steps: mean, then the mean of the squared deviations.
 template <bool GATHER>
 __global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E, const uint4* P, uint4* X, uint4* A,
-                                                       const float* gamma, const float* beta, int rows) {
+                                                       const float* gamma, const float* beta, int n_units) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= rows) return;
+  if (r >= m.row0[n_units]) return;
   const int n_chunks = m.d / 8;
   uint4* xr = X + (size_t)r * n_chunks;
   uint4* ar = A + (size_t)r * n_chunks;
   float x[E_KCH][8];
   if (GATHER) {
-    const int i = r % m.M;
-    const int bu = r / m.M;
+    const int rs = m.row_slot[r];
+    const int i = rs & 7;
+    const int bu = rs >> 3;
     const int b = bu / m.un, u = bu % m.un;
     int C;
     const int e = entry_of(m, b, u, &C);
-    const int L = e < C ? min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M) : 0;
-    if (i >= L) {
-      const uint4 z = {0u, 0u, 0u, 0u};
-      for (int c = lane; c < n_chunks; c += 64) {
-        xr[c] = z;
-        ar[c] = z;
-      }
-      return;
-    }
     const int tok = min(max(m.ent_tokens[((size_t)b * m.cap + e) * m.M + i], 0), m.V - 1);
     const uint4* er = E + (size_t)tok * n_chunks;
 #pragma unroll
@@ -155,10 +189,10 @@ __global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E,
   }
 }
 
-// Attention among the slots of one entry.  QKV [rows, 3d] holds q | k | v of every slot; a wave takes one
-// entry and 512 consecutive features (whole heads: the head width is a power of two of at most 512), lane l
-// the 8 features of chunk l.  Scores are reduced over the lanes_per_head lanes of a head; the softmax runs
-// over the entry's real slots only; O rows of padding slots and missing entries are zero.
+// Attention among the slots of one entry.  QKV [rows, 3d] holds q | k | v of every real slot; a wave takes
+// one entry and 512 consecutive features (whole heads: the head width is a power of two of at most 512), lane
+// l the 8 features of chunk l.  Scores are reduced over the lanes_per_head lanes of a head; the softmax runs
+// over the entry's L rows.
 __global__ void __launch_bounds__(256) enc_attention_kernel(RowMap m, const uint4* QKV, uint4* O, int lanes_per_head,
                                                             float scale, int groups, int n_units) {
   const int lane = threadIdx.x & 63;
@@ -166,21 +200,13 @@ __global__ void __launch_bounds__(256) enc_attention_kernel(RowMap m, const uint
   const int g = (int)(wid % groups);
   const long long bu = wid / groups;
   if (bu >= n_units) return;
-  const int b = (int)(bu / m.un), u = (int)(bu % m.un);
   const int n_chunks = m.d / 8;
   const int c = g * 64 + lane;
   const bool active = c < n_chunks;
-  int C;
-  const int e = entry_of(m, b, u, &C);
-  const int L = e < C ? min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M) : 0;
-  const size_t r0 = (size_t)bu * m.M;
+  const size_t r0 = (size_t)m.row0[bu];
+  const int L = m.row0[bu + 1] - m.row0[bu];
   const uint4 zero = {0u, 0u, 0u, 0u};
-  for (int i = 0; i < m.M; ++i) {
-    uint4* orow = O + (r0 + i) * n_chunks;
-    if (i >= L) {
-      if (active) orow[c] = zero;
-      continue;
-    }
+  for (int i = 0; i < L; ++i) {
     float q[8];
     unpack8(active ? QKV[(r0 + i) * 3 * n_chunks + c] : zero, q);
     float s[Z2Z_MAX_M];
@@ -217,7 +243,7 @@ __global__ void __launch_bounds__(256) enc_attention_kernel(RowMap m, const uint
         for (int t = 0; t < 8; ++t) o[t] += p * v[t];
       }
     }
-    if (active) orow[c] = pack8(o);
+    if (active) O[(r0 + i) * n_chunks + c] = pack8(o);
   }
 }
 
@@ -240,9 +266,9 @@ __global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const uint4* Z,
     }
     return;
   }
-  const int L = min(max(m.ent_len[(size_t)b * m.cap + e], 1), m.M);
+  const int L = m.row0[bu + 1] - m.row0[bu];
   const float invL = 1.0f / (float)L;
-  const size_t r0 = (size_t)bu * m.M;
+  const size_t r0 = (size_t)m.row0[bu];
   for (int c = lane; c < n_chunks; c += 64) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < L; ++i) {
@@ -281,7 +307,9 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
   if (u_step < 1) u_step = 1;
   if (u_step > units) u_step = units;
   const size_t R_max = (size_t)B * (size_t)u_step * M;
-  const size_t need = R_max * ((size_t)4 * d + (size_t)3 * d + (size_t)dff) * 2;
+  const size_t n_units_max = (size_t)B * (size_t)u_step;
+  const size_t index_bytes = ((n_units_max + 1 + R_max) * sizeof(int32_t) + 255) & ~(size_t)255;
+  const size_t need = R_max * ((size_t)4 * d + (size_t)3 * d + (size_t)dff) * 2 + index_bytes;
   if (need > c->enc_ws_bytes) {
     if (c->enc_ws) (void)hipFree(c->enc_ws);
     c->enc_ws = nullptr;
@@ -289,7 +317,8 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
     if (hipMalloc(&c->enc_ws, need) != hipSuccess) return Z2Z_ENOMEM;
     c->enc_ws_bytes = need;
   }
-  uint16_t* ws = reinterpret_cast<uint16_t*>(c->enc_ws);
+  int32_t* index = reinterpret_cast<int32_t*>(c->enc_ws);
+  uint16_t* ws = reinterpret_cast<uint16_t*>(reinterpret_cast<unsigned char*>(c->enc_ws) + index_bytes);
   uint16_t* X = ws;
   uint16_t* A = X + R_max * d;
   uint16_t* O = A + R_max * d;
@@ -308,6 +337,8 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
   m.M = M;
   m.cap = cap;
   m.d = d;
+  m.row0 = index;
+  m.row_slot = index + n_units_max + 1;
   const int dh = d / enc->n_heads;
   const int groups = (d + 511) / 512;
   const float scale = 1.0f / sqrtf((float)dh);
@@ -315,8 +346,10 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
     m.u0 = u0;
     m.un = (int)(u0 + u_step <= units ? u_step : units - u0);
     const int n_units = B * m.un;
-    const int R = n_units * M;
+    const int R = n_units * M;                      // upper bound; the pass's row count is row0[n_units], on the device
+    const int32_t* rows_dev = m.row0 + n_units;
     const unsigned row_blocks = (unsigned)((R + 3) / 4);
+    hipLaunchKernelGGL(enc_rows_kernel, dim3(1), dim3(1024), 0, s, m, n_units);
     uint16_t* x = X;
     uint16_t* y = Y;
     for (int l = 0; l < enc->n_layers; ++l) {
@@ -324,17 +357,17 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
       if (l == 0)
         hipLaunchKernelGGL(enc_norm_kernel<true>, dim3(row_blocks), dim3(256), 0, s, m,
                            reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos),
-                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, R);
+                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
       else
         hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, R);
-      int rc = z2z_launch_linear(c, A, lay.w_qkv, lay.b_qkv, nullptr, 0, QKV, R, 3 * d, d, s);
+                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
+      int rc = z2z_launch_linear(c, A, lay.w_qkv, lay.b_qkv, nullptr, 0, QKV, R, rows_dev, 3 * d, d, s);
       if (rc != Z2Z_OK) return rc;
       const long long att_waves = (long long)n_units * groups;
       hipLaunchKernelGGL(enc_attention_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
                          reinterpret_cast<const uint4*>(QKV), reinterpret_cast<uint4*>(O), dh / 8, scale, groups,
                          n_units);
-      rc = z2z_launch_linear(c, O, lay.w_o, lay.b_o, x, 0, y, R, d, d, s);
+      rc = z2z_launch_linear(c, O, lay.w_o, lay.b_o, x, 0, y, R, rows_dev, d, d, s);
       if (rc != Z2Z_OK) return rc;
       if (enc->attention_only) {
         uint16_t* t = x;
@@ -342,10 +375,10 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
         y = t;
       } else {
         hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(y), reinterpret_cast<uint4*>(A), lay.ln2_g, lay.ln2_b, R);
-        rc = z2z_launch_linear(c, A, lay.w_1, lay.b_1, nullptr, 1, F, R, dff, d, s);
+                           reinterpret_cast<uint4*>(y), reinterpret_cast<uint4*>(A), lay.ln2_g, lay.ln2_b, n_units);
+        rc = z2z_launch_linear(c, A, lay.w_1, lay.b_1, nullptr, 1, F, R, rows_dev, dff, d, s);
         if (rc != Z2Z_OK) return rc;
-        rc = z2z_launch_linear(c, F, lay.w_2, lay.b_2, y, 0, x, R, d, dff, s);
+        rc = z2z_launch_linear(c, F, lay.w_2, lay.b_2, y, 0, x, R, rows_dev, d, dff, s);
         if (rc != Z2Z_OK) return rc;
       }
     }

@@ -261,11 +261,11 @@ int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, 
 }  // namespace
 
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, int N, int K, hipStream_t s) {
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s) {
   // few rows: bound by the weight bytes, which the decode-step kernel streams at HBM rate (it re-reads them
   // once per 64 rows, so it loses to the tile kernel beyond a few hundred rows)
   if (R <= 512 && c->skinny_ready && K % 128 == 0 && N % 2 == 0 && c->opt_logits_kernel != 2)
-    return z2z_launch_linear_skinny(c, A, W, bias, residual, act, out, R, N, K, s);
+    return z2z_launch_linear_skinny(c, A, W, bias, residual, act, out, R, rows_dev, N, K, s);
   if (!c->fast_ready || K % 64 != 0 || N % 8 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
   LogitsArgs a;
   memset(&a, 0, sizeof(a));
@@ -277,7 +277,9 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.w_rows = N;
   a.n_vtiles = (N + 255) / 256;
   a.row_tiles = (R + 255) / 256;
-  a.strip = (long long)a.row_tiles * a.n_vtiles >= 2048 ? 4 : 1;
+  // one tile per workgroup when the row count is only known on the device: the launch cannot be shaped to
+  // it, and the finer the grain, the less of the last round of workgroups is wasted
+  a.strip = (!rows_dev && (long long)a.row_tiles * a.n_vtiles >= 2048) ? 4 : 1;
   a.n_strips = (a.n_vtiles + a.strip - 1) / a.strip;
   a.n_work = a.row_tiles * a.n_strips;
   a.out = out;
@@ -285,6 +287,19 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.residual = residual;
   a.act = act;
   a.ldo = N;
+  a.rows_dev = nullptr;
+  if (rows_dev && a.row_tiles >= 16) {
+    // the real row count is on the device: row tiles are dealt to the XCDs one by one (see map_rows_dev)
+    a.rows_dev = rows_dev;
+    a.map_lr = 4;
+    a.map_ls = a.n_strips >= 8 ? 8 : (a.n_strips >= 4 ? 4 : (a.n_strips >= 2 ? 2 : 1));
+    a.strip_blocks = (a.n_strips + a.map_ls - 1) / a.map_ls;
+    const int tiles_per_xcd = (a.row_tiles + 7) / 8;
+    const int row_blocks = (tiles_per_xcd + a.map_lr - 1) / a.map_lr;
+    const unsigned grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)row_blocks * (unsigned)a.strip_blocks;
+    return z2z_launch_logits_fast(2, a, grid, s);
+  }
+  // (fewer row tiles than that: the tiles beyond the real rows only exit early)
   // Workgroup ids go round-robin over the 8 XCDs and the mapping gives XCD (xr_i, xs_i) the row tiles whose
   // block index is xr_i mod map_xr and the strips whose block index is xs_i mod map_xs: an XCD's share is the
   // product of the two counts.  Take the mapping with the smallest largest share (nobody waits for one XCD),
@@ -322,6 +337,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.map_sb_r = (a.row_tiles + sb_rows - 1) / sb_rows;
   const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;
   const unsigned grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
+  a.rows_dev = rows_dev;
   return z2z_launch_logits_fast(2, a, grid, s);
 }
 

@@ -174,6 +174,8 @@ struct LogitsArgs {
   const void* residual;   // [rows, ldo] bf16 or nullptr
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
+  const int32_t* rows_dev;  // nullptr, or the number of rows that exist (<= rows), known on the device only
+  int32_t strip_blocks;     // > 0: linear mode with the XCD-per-row-tile mapping, = ceil(n_strips / map_ls)
 };
 
 // Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
@@ -247,8 +249,10 @@ int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArg
 // mode: 0 base part, 1 hyper part (both fold the joint softmax), 2 dense layer (stores the tile)
 int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 // out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
+// (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor
+// written)
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, int N, int K, hipStream_t s);
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s);
 int z2z_logits_fast_prepare(z2z_ctx* c);
 // temperature sampling (one-row-per-sequence kernel only): softmax(logit / temperature), generator key and
 // counter words from seed and step
@@ -267,7 +271,7 @@ size_t z2z_sample_truncated_work_floats(int32_t rows);
 // the same layer on the bandwidth-bound kernel of the decode step (few rows: every weight byte is read once per
 // 64 rows); K a multiple of 128, N even
 int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
-                             int act, void* out, int R, int N, int K, hipStream_t s);
+                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 void z2z_logits_decode_units(int* base_columns, int* hyper_columns);
 bool z2z_logits_decode_ok(const z2z_ctx* c);

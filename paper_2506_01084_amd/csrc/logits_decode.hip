@@ -72,6 +72,7 @@ struct DecodeArgs {
   const uint16_t* residual;
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
+  const int32_t* rows_dev;  // MODE 3: nullptr, or the number of hidden rows that exist (<= B), on the device
 };
 
 __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
@@ -155,7 +156,9 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   float* slots = reinterpret_cast<float*>(lds + D_TILE_BYTES);       // [2][8][64][D_SLOT_STRIDE]
   const int v0 = unit * UNIT;
   const int h0 = group * 64;
-  const int n_h = min(64, a.B - h0);               // hidden rows of this group
+  const int n_rows = (MODE == 3 && a.rows_dev) ? min(a.B, *a.rows_dev) : a.B;
+  if (h0 >= n_rows) return;                        // (the whole workgroup: nothing is shared yet)
+  const int n_h = min(64, n_rows - h0);            // hidden rows of this group
   const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
   const int n_slices = a.d / D_KSLICE;
   const int n_phases = (n_slices + 7) >> 3;
@@ -186,7 +189,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     const int c0 = chunk0(phase);
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int hrow = min(h0 + g * 16 + m16, a.B - 1);
+      const int hrow = min(h0 + g * 16 + m16, n_rows - 1);
 #pragma unroll
       for (int q = 0; q < D_QB; ++q) hreg[g][q] = a.H[(size_t)hrow * chunks_per_row + c0 + q * 4];
     }
@@ -490,7 +493,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 // A dense layer on few rows (R up to a few hundred) is bound by the weight bytes like the decode step: the
 // base-unit workgroups of the kernel above, with the layer's epilogue instead of the softmax fold.
 int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
-                             int act, void* out, int R, int N, int K, hipStream_t s) {
+                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s) {
   if (c->lds_limit < D_LDS || K % D_KSLICE != 0 || N % 2 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
   DecodeArgs a;
   memset(&a, 0, sizeof(a));
@@ -508,6 +511,7 @@ int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const flo
   a.residual = reinterpret_cast<const uint16_t*>(residual);
   a.act = act;
   a.ldo = N;
+  a.rows_dev = rows_dev;
   const unsigned grid = (unsigned)(a.n_base_units * a.n_groups);
   hipLaunchKernelGGL(logits_decode_kernel<3>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   Z2Z_HIP_TRY(hipGetLastError());

@@ -99,6 +99,24 @@ __device__ __forceinline__ bool map_base(const LogitsArgs& a, int bid, int* rt, 
   return *rt < a.row_tiles && *st < a.n_strips;
 }
 
+// Linear mode when the number of rows is known on the device only: row tile t belongs to XCD t mod 8 (shares
+// differ by one tile at most, whatever the count turns out to be); inside an XCD the workgroups walk blocks of
+// map_lr of its row tiles x map_ls strips, strips outermost.  The grid is sized for the rows laid out.
+__device__ __forceinline__ bool map_rows_dev(const LogitsArgs& a, int bid, int row_tiles_now, int* rt, int* st) {
+  const int xcd = bid & 7;
+  const int j = bid >> 3;
+  const int per = a.map_lr * a.map_ls;
+  const int blk = j / per;
+  const int within = j - blk * per;
+  const int lr = within % a.map_lr;
+  const int ls = within / a.map_lr;
+  const int sblk = blk % a.strip_blocks;          // strip blocks innermost among blocks: an XCD's row block
+  const int rblk = blk / a.strip_blocks;          // meets all strips before the next row block starts
+  *rt = (rblk * a.map_lr + lr) * 8 + xcd;
+  *st = sblk * a.map_ls + ls;
+  return *rt < row_tiles_now && *st < a.n_strips;
+}
+
 struct Frags {
   uint4 a[F_NI];
   uint4 b[F_NJ];
@@ -127,9 +145,15 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     n_valid = min(max(a.size[b], 0), a.w_rows);
     Wp += (size_t)b * a.w_rows * row_bytes;
   } else {
-    if (!map_base(a, blockIdx.x, &rt, &st)) return;
-    r0 = rt * FT;
     r_end = a.rows;
+    if (MODE == 2 && a.rows_dev) r_end = min(r_end, *a.rows_dev);
+    if (MODE == 2 && a.strip_blocks > 0) {
+      if (!map_rows_dev(a, blockIdx.x, (r_end + FT - 1) / FT, &rt, &st)) return;
+    } else {
+      if (!map_base(a, blockIdx.x, &rt, &st)) return;
+    }
+    r0 = rt * FT;
+    if (r0 >= r_end) return;                       // a tile beyond the rows that exist
     n_valid = a.w_rows;
   }
   const unsigned char* Hp = reinterpret_cast<const unsigned char*>(a.H) + (size_t)r0 * row_bytes;
