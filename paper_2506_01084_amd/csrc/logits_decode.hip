@@ -73,6 +73,10 @@ struct DecodeArgs {
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
   const int32_t* rows_dev;  // MODE 3: nullptr, or the number of hidden rows that exist (<= B), on the device
+  // MODE 3, K split over ksplit workgroups per unit (layers with few units would leave most CUs idle): each
+  // leaves its partial tile in `partial`; linear_reduce_kernel adds them up and runs the epilogue
+  int32_t ksplit;
+  float* partial;           // [n_groups * n_base_units][ksplit][unit rows * 64]
 };
 
 __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
@@ -144,8 +148,41 @@ __device__ __forceinline__ void fold_logit(const DecodeArgs& a, Triple& t, Draw&
   }
 }
 
+// The epilogue of a dense layer on one unit: tile [D_LINEAR_UNIT][64] (output feature, row of the group) is
+// transposed through `stage` [64][D_LINEAR_UNIT + 1] so that LDS accesses and global stores both run along
+// consecutive addresses; then bias, activation, residual and one rounding per element.  All threads call it.
+__device__ __forceinline__ void linear_epilogue(const DecodeArgs& a, const float* tile, float* stage, int v0, int h0,
+                                                int n_h) {
+  constexpr int UNIT = D_LINEAR_UNIT;
+  constexpr int ST = UNIT + 1;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < UNIT * 64; i += D_THREADS) stage[(i & 63) * ST + (i >> 6)] = tile[i];
+  __syncthreads();
+  for (int i = tid; i < 64 * (UNIT / 2); i += D_THREADS) {
+    const int jj = i / (UNIT / 2), r = 2 * (i - jj * (UNIT / 2));     // a pair of columns
+    if (jj < n_h && v0 + r < a.V) {                                   // V is even
+      float x0 = stage[jj * ST + r], x1 = stage[jj * ST + r + 1];
+      if (a.bias) {
+        x0 += a.bias[v0 + r];
+        x1 += a.bias[v0 + r + 1];
+      }
+      if (a.act == 1) {
+        x0 = gelu_erf(x0);
+        x1 = gelu_erf(x1);
+      }
+      const size_t at = (size_t)(h0 + jj) * a.ldo + v0 + r;
+      if (a.residual) {
+        const uint32_t rv = *reinterpret_cast<const uint32_t*>(a.residual + at);
+        x0 += __uint_as_float(rv << 16);
+        x1 += __uint_as_float(rv & 0xFFFF0000u);
+      }
+      *reinterpret_cast<uint32_t*>(a.out + at) = bf16_bits_rne(x0) | (bf16_bits_rne(x1) << 16);
+    }
+  }
+}
+
 template <int MODE>
-__device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int group, unsigned char* lds) {
+__device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int group, int ks, unsigned char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -161,7 +198,11 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   const int n_h = min(64, n_rows - h0);            // hidden rows of this group
   const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
   const int n_slices = a.d / D_KSLICE;
-  const int n_phases = (n_slices + 7) >> 3;
+  const int n_phases_all = (n_slices + 7) >> 3;
+  // this workgroup's share of K: phases [phase0, phase0 + n_phases) (all of them unless MODE 3 splits K)
+  const int per_part = (MODE == 3 && a.ksplit > 1) ? (n_phases_all + a.ksplit - 1) / a.ksplit : n_phases_all;
+  const int phase0 = ks * per_part;
+  const int n_phases = min(per_part, n_phases_all - phase0);
   constexpr int N_BLK = UNIT / 16;
 
   for (int i = tid; i < UNIT * 64; i += D_THREADS) tile[i] = 0.f;
@@ -173,7 +214,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   // the end of the unit re-read its last block.
   const int n_steps = n_phases * N_BLK;
   auto chunk0 = [&](int phase) {
-    const int slice = min(phase * 8 + wave, n_slices - 1);
+    const int slice = min((phase0 + phase) * 8 + wave, n_slices - 1);
     return slice * (D_KSLICE / 8) + kg;            // first 16-byte chunk of this lane in the slice
   };
   auto load_block = [&](uint4 (&w)[D_QB], int step) {
@@ -196,7 +237,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   };
   auto compute = [&](const uint4 (&w)[D_QB], int step) {
     const int phase = step / N_BLK, blk = step - phase * N_BLK;
-    const bool valid = phase * 8 + wave < n_slices;   // wave-uniform
+    const bool valid = (phase0 + phase) * 8 + wave < n_slices;   // wave-uniform
     f32x4 acc[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -261,33 +302,17 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     }
     __syncthreads();
   }
+  if (MODE == 3 && a.ksplit > 1) {
+    // K is split over several workgroups: leave the partial tile; linear_reduce_kernel adds them up (in a
+    // launch of its own: making them visible to one another inside this launch takes device-wide fences,
+    // which cost more than the launch)
+    const size_t slot = (size_t)group * a.n_base_units + unit;
+    float* mine = a.partial + (slot * a.ksplit + ks) * (size_t)(UNIT * 64);
+    for (int i = tid; i < UNIT * 64; i += D_THREADS) mine[i] = tile[i];
+    return;
+  }
   if (MODE == 3) {
-    // dense layer: the same transposition, then bias, activation, residual and one rounding per element
-    constexpr int ST = UNIT + 1;
-    float* stage = slots;                                            // [64][UNIT + 1]
-    for (int i = tid; i < UNIT * 64; i += D_THREADS) stage[(i & 63) * ST + (i >> 6)] = tile[i];
-    __syncthreads();
-    for (int i = tid; i < 64 * (UNIT / 2); i += D_THREADS) {
-      const int jj = i / (UNIT / 2), r = 2 * (i - jj * (UNIT / 2));     // a pair of columns
-      if (jj < n_h && v0 + r < a.V) {                                                 // V is even
-        float x0 = stage[jj * ST + r], x1 = stage[jj * ST + r + 1];
-        if (a.bias) {
-          x0 += a.bias[v0 + r];
-          x1 += a.bias[v0 + r + 1];
-        }
-        if (a.act == 1) {
-          x0 = gelu_erf(x0);
-          x1 = gelu_erf(x1);
-        }
-        const size_t at = (size_t)(h0 + jj) * a.ldo + v0 + r;
-        if (a.residual) {
-          const uint32_t rv = *reinterpret_cast<const uint32_t*>(a.residual + at);
-          x0 += __uint_as_float(rv << 16);
-          x1 += __uint_as_float(rv & 0xFFFF0000u);
-        }
-        *reinterpret_cast<uint32_t*>(a.out + at) = bf16_bits_rne(x0) | (bf16_bits_rne(x1) << 16);
-      }
-    }
+    linear_epilogue(a, tile, slots, v0, h0, n_h);
     return;
   }
   // fold: thread t takes hidden row t & 63 and weight rows (t >> 6) * 32 .. + 32, in increasing order
@@ -436,8 +461,45 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
     hyper_unit<MODE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
     const int bu = bid - n_hyper;
-    base_unit<MODE>(a, bu % a.n_base_units, bu / a.n_base_units, lds);
+    if (MODE == 3) {
+      // workgroup ids go round-robin over the 8 XCDs: the row groups of one unit get ids 8 apart, so they run
+      // on one XCD at about the same time and its L2 serves the unit's weights to all but the first of them
+      const int units8 = (a.n_base_units + 7) >> 3;
+      const int q = bu >> 3;
+      const int group = q % a.n_groups;
+      const int rest = q / a.n_groups;
+      const int unit = (rest % units8) * 8 + (bu & 7);
+      if (unit >= a.n_base_units) return;
+      base_unit<MODE>(a, unit, group, rest / units8, lds);
+    } else {
+      base_unit<MODE>(a, bu % a.n_base_units, bu / a.n_base_units, 0, lds);
+    }
   }
+}
+
+// Dense layer with K split: one workgroup per (unit, group) adds the ksplit partial tiles in a fixed order and
+// runs the layer's epilogue.
+__global__ void __launch_bounds__(D_THREADS) linear_reduce_kernel(DecodeArgs a) {
+  __shared__ float tile[D_LINEAR_UNIT * 64];
+  __shared__ float stage[64 * (D_LINEAR_UNIT + 1)];
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x % a.n_base_units, group = blockIdx.x / a.n_base_units;
+  const int h0 = group * 64;
+  const int n_rows = a.rows_dev ? min(a.B, *a.rows_dev) : a.B;
+  if (h0 >= n_rows) return;
+  const float* all = a.partial + (size_t)blockIdx.x * a.ksplit * (D_LINEAR_UNIT * 64);
+  constexpr int PER_THREAD = D_LINEAR_UNIT * 64 / D_THREADS;
+  float sum[PER_THREAD];
+#pragma unroll
+  for (int e = 0; e < PER_THREAD; ++e) sum[e] = 0.f;
+  for (int k = 0; k < a.ksplit; ++k) {
+#pragma unroll
+    for (int e = 0; e < PER_THREAD; ++e) sum[e] += all[(size_t)k * (D_LINEAR_UNIT * 64) + e * D_THREADS + tid];
+  }
+#pragma unroll
+  for (int e = 0; e < PER_THREAD; ++e) tile[e * D_THREADS + tid] = sum[e];
+  __syncthreads();
+  linear_epilogue(a, tile, stage, unit * D_LINEAR_UNIT, h0, min(64, n_rows - h0));
 }
 
 }  // namespace
@@ -512,8 +574,30 @@ int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const flo
   a.act = act;
   a.ldo = N;
   a.rows_dev = rows_dev;
-  const unsigned grid = (unsigned)(a.n_base_units * a.n_groups);
+  // enough workgroups for every CU: split K (in phases of 1024) where the units alone are too few
+  const int n_phases_all = (K / D_KSLICE + 7) / 8;
+  int ksplit = 1;
+  while (a.n_base_units * a.n_groups * ksplit <= 128 && ksplit * 2 <= n_phases_all) ksplit *= 2;
+  const int per_part = (n_phases_all + ksplit - 1) / ksplit;
+  ksplit = (n_phases_all + per_part - 1) / per_part;          // no empty parts
+  a.ksplit = ksplit;
+  if (ksplit > 1) {
+    const size_t slots = (size_t)a.n_base_units * a.n_groups;
+    const size_t need = slots * ksplit * D_LINEAR_UNIT * 64 * sizeof(float);
+    if (need > c->skinny_partial_bytes) {
+      if (c->skinny_partial) (void)hipFree(c->skinny_partial);
+      c->skinny_partial = nullptr;
+      c->skinny_partial_bytes = 0;
+      const size_t want_bytes = need > ((size_t)16 << 20) ? need : ((size_t)16 << 20);
+      if (hipMalloc(&c->skinny_partial, want_bytes) != hipSuccess) return Z2Z_ENOMEM;
+      c->skinny_partial_bytes = want_bytes;
+    }
+    a.partial = reinterpret_cast<float*>(c->skinny_partial);
+  }
+  const unsigned grid = 8u * (unsigned)((a.n_base_units + 7) / 8) * (unsigned)(a.n_groups * ksplit);
   hipLaunchKernelGGL(logits_decode_kernel<3>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+  if (ksplit > 1)
+    hipLaunchKernelGGL(linear_reduce_kernel, dim3((unsigned)(a.n_base_units * a.n_groups)), dim3(D_THREADS), 0, s, a);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

@@ -28,6 +28,7 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->sample_logits);
   (void)hipFree(c->row_max);
   (void)hipFree(c->enc_ws);
+  (void)hipFree(c->skinny_partial);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
       (void)hipEventDestroy(c->ev_start[i]);

@@ -52,6 +52,9 @@ struct z2z_ctx {
   // hyper_encode work space: the activations of one pass (bf16)
   void* enc_ws;
   size_t enc_ws_bytes;
+  // dense layers on few rows with K split over workgroups: the partial tiles
+  void* skinny_partial;
+  size_t skinny_partial_bytes;
   // options
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map,
       opt_sample_kernel;
