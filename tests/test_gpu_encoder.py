@@ -172,3 +172,119 @@ def test_full_size_c2_two_layer_transformer_sampled_entries():
         C = len(ref[b][1])
         assert (newest[b, :C - 1] == 0).all() and (newest[b, C:] == 0).all()
     ctx.close()
+
+
+def test_codebooks_larger_than_one_pass_and_edge_shapes():
+    """More slot rows than the work space of one pass holds (65536): the entries go in several passes over
+    entry ranges.  Also M = 8 (the largest), an empty batch of codebooks, and cap = 0."""
+    import torch
+    from paper_2506_01084_amd import api
+
+    # 40 x 600 x 3 = 72000 slot rows -> two passes of 546 and 54 entries per sequence
+    B, N, V, d, M, cap = 40, 1500, 3000, 128, 3, 600
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.2, seed=77)
+    lens = wl.make_lens(cfg, ragged=True)
+    ctx, ref, E, d_E = _setup(cfg, lens)
+    enc = wl.make_encoder(cfg, n_layers=1, n_heads=2, d_ff=128)
+    d_enc = encoder_to_device(enc, "bf16")
+    d_W = torch.full((B, cap, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, d_W)
+    torch.cuda.synchronize()
+    W = storage_to_host(d_W, "bf16")
+    assert max(len(r[1]) for r in ref) > 546, "the case must reach the second pass"
+    for b in (0, 7, 39):
+        entries = ref[b][1]
+        want = oracle.hyper_encode(E, "bf16", entries, cap, enc, rounded=False)
+        _compare(W[b, :len(entries)], want[:len(entries)], f"two passes, seq {b}")
+        assert (W[b, len(entries):] == 0).all()
+    ctx.close()
+
+    # M = 8
+    B, N, V, d, M, cap = 2, 600, 40, 64, 8, 120
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.0, seed=78)
+    tokens = np.empty((B, N), dtype=np.int32)           # repetitive streams: entries grow to the full M slots
+    tokens[0] = 5
+    tokens[1] = np.tile(np.array([1, 2, 3], dtype=np.int32), N // 3)
+    E = wl.make_embeddings(cfg)
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    gpu_encode(ctx, tokens, None)
+    ref = oracle_encode_batch(tokens, np.full(B, N, dtype=np.int32), V, M, cap)
+    d_E = torch_storage(E, "bf16")
+    assert max(len(e) for e in ref[0][1]) == 8
+    enc = wl.make_encoder(cfg, n_layers=1, n_heads=4, d_ff=64)
+    d_W = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, encoder_to_device(enc, "bf16"), d_W)
+    torch.cuda.synchronize()
+    W = storage_to_host(d_W, "bf16")
+    for b in range(B):
+        want = oracle.hyper_encode(E, "bf16", ref[b][1], cap, enc, rounded=False)
+        _compare(W[b, :len(ref[b][1])], want[:len(ref[b][1])], f"M = 8, seq {b}")
+    # no entries at all (fresh codebooks): every row zero, nothing faults
+    ctx.reset()
+    d_W.fill_(5.0)
+    ctx.hyper_encode(d_E, encoder_to_device(enc, "bf16"), d_W)
+    ctx.hyper_encode(d_E, encoder_to_device(enc, "bf16"), d_W, None, 1)
+    torch.cuda.synchronize()
+    assert (storage_to_host(d_W, "bf16") == 0).all()
+    ctx.close()
+
+    # cap = 0: nothing to do
+    ctx = api.Context(B=2, V=40, M=3, cap=0, d=64, dtype="bf16")
+    ctx.reset()
+    cfg0 = wl.scaled(cfg, M=3)
+    ctx.hyper_encode(d_E, encoder_to_device(wl.make_encoder(cfg0, n_layers=1, n_heads=4, d_ff=64), "bf16"),
+                     torch.zeros((2, 0, 64), dtype=torch.bfloat16, device="cuda"))
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+def test_hyper_encode_replays_in_a_graph():
+    """After one eager call (which allocates the work space) the call enqueues kernels only, with the row count
+    read on the device: a captured graph replays it on codebooks that grew in between."""
+    import torch
+    from paper_2506_01084_amd import api
+
+    B, N, V, d, M, cap = 4, 300, 500, 256, 3, 400
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=21)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    d_E = torch_storage(E, "bf16")
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=4, d_ff=256)
+    d_enc = encoder_to_device(enc, "bf16")
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    half = np.full(B, N // 2, dtype=np.int32)
+    gpu_encode(ctx, tokens[:, :N // 2].copy(), half)
+    d_W = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode(d_E, d_enc, d_W)                    # eager: sizes the work space
+    torch.cuda.synchronize()
+    eager_half = storage_to_host(d_W, "bf16").copy()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            ctx.hyper_encode(d_E, d_enc, d_W)
+    torch.cuda.current_stream().wait_stream(side)
+    d_W.zero_()
+    g.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(storage_to_host(d_W, "bf16"), eager_half)
+    # the codebooks grow (second half of the tokens appended), the same graph is replayed
+    gpu_encode(ctx, tokens[:, N // 2:].copy(), half, flags=api.APPEND)
+    ref = []
+    for b in range(B):                                  # the oracle's chunked encoder: same two chunks
+        st = oracle.LZWStream(V, M, cap)
+        st.encode_chunk(tokens[b, :N // 2].tolist())
+        st.encode_chunk(tokens[b, N // 2:].tolist())
+        ref.append((None, list(st.entries)))
+    for rep in range(2):
+        d_W.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        W = storage_to_host(d_W, "bf16")
+        for b in range(B):
+            entries = ref[b][1]
+            want = oracle.hyper_encode(E, "bf16", entries, cap, enc, rounded=False)
+            _compare(W[b, :len(entries)], want[:len(entries)], f"replay {rep}, seq {b}")
+            assert (W[b, len(entries):] == 0).all()
+    ctx.close()
