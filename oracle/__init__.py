@@ -29,6 +29,6 @@ from .embed import hyper_embed, pool_coefficients  # noqa: F401
 from .logits import extended_logits  # noqa: F401
 from .sampling import (extended_sample, kept_prefix, philox4x32_10, sample_row,  # noqa: F401
                        sample_row_truncated)
-from .loss import extended_nll  # noqa: F401
+from .loss import extended_nll, extended_nll_backward, hyper_embed_backward  # noqa: F401
 from .encoder import hyper_encode  # noqa: F401
 from .numfmt import bf16_bits_to_f64, f64_to_bf16_bits, to_f64, round_to_storage  # noqa: F401
