@@ -227,6 +227,29 @@ int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_p
                      const void* d_W_base, const void* d_W_hyper, const int32_t* d_targets, float* d_nll,
                      float* d_lse, void* stream);
 
+/* Backward of z2z_extended_nll (the training objective of section 2.4, second displayed equation, over the
+ * compressed sequence): the gradient of  L = sum_r grad_nll[r] * nll[r]  with respect to the hidden rows and
+ * both unembedding matrices.  With p = softmax(logit[r, :]) over the existing columns and t = target[r],
+ *   dZ[r, v] = grad_nll[r] * (p[v] - [v == t]);   dH = dZ [W_base ; W_hyper[b]];   dW_base = dZ[:, :V]^T H;
+ *   dW_hyper[b] = dZ[rows of b, V:]^T H[rows of b]   (rows at and beyond C_b: 0).
+ * Rows without a target (t < 0) and rows whose target names no existing column contribute nothing.
+ *   d_lse      [rows] float: the log-sum-exp z2z_extended_nll returned for the same inputs
+ *   d_grad_nll [rows] float or NULL (= 1 for every row)
+ *   d_dH [rows, d], d_dW_base [V, d], d_dW_hyper [B, cap, d]: out, bf16 (overwritten, not accumulated)
+ * dZ is rounded to bf16 once and the four products accumulate in fp32.  bf16 contexts with d a multiple of 64;
+ * anything else returns Z2Z_EUNSUPPORTED.  Work space: 2 * rows * (V + cap) bf16 for dZ and its transpose plus
+ * one transposed copy of H, W_base and W_hyper, library scratch (Z2Z_ENOMEM beyond 200 GB). */
+int z2z_extended_nll_backward(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                              const void* d_W_base, const void* d_W_hyper, const int32_t* d_targets,
+                              const float* d_lse, const float* d_grad_nll, void* d_dH, void* d_dW_base,
+                              void* d_dW_hyper, void* stream);
+
+/* Backward of z2z_hyper_embed (the pooling is linear in E):  dE[t_j, :] += a_j * dW_hyper[b, e, :]  for every
+ * token t_j of every existing entry, with the coefficients a_j of the forward pass.
+ *   d_dW_hyper [B, cap, d] bf16;  d_dE [V, d] float, ACCUMULATED into (zero it first for the plain gradient).
+ * Float atomics: the order of the additions, and so the last bits, vary from run to run.  bf16 contexts. */
+int z2z_hyper_embed_backward(z2z_ctx* ctx, const void* d_dW_hyper, float* d_dE, void* stream);
+
 /* Tuning knobs (kernel variants and tile schedule) and instrumentation; unknown keys return
  * Z2Z_EINVAL. */
 enum {

@@ -24,7 +24,7 @@ OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",
-           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_set_option",
+           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
 
@@ -99,6 +99,9 @@ def load_library() -> ctypes.CDLL:
                                         c_float, ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_nll.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p, c_void_p]
+    lib.z2z_extended_nll_backward.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                              c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.z2z_hyper_embed_backward.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_set_option.argtypes = [c_void_p, c_int32, c_int32]
     lib.z2z_read_timing.argtypes = [c_void_p, POINTER(c_float), P32]
     lib.z2z_strerror.argtypes = [ctypes.c_int]
@@ -257,6 +260,26 @@ class Context:
                                           _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
                                           _ptr(targets, torch.int32), _ptr(nll, torch.float32),
                                           _ptr(lse, torch.float32), _stream()), "z2z_extended_nll")
+
+    def extended_nll_backward(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
+                              targets: torch.Tensor, lse: torch.Tensor, grad_nll: Optional[torch.Tensor],
+                              dH: torch.Tensor, dW_base: torch.Tensor, dW_hyper: torch.Tensor) -> None:
+        rows = H.shape[0]
+        assert H.shape[1] == self.d and tuple(W_base.shape) == (self.V, self.d)
+        assert targets.numel() == rows and lse.numel() == rows and (grad_nll is None or grad_nll.numel() == rows)
+        assert tuple(dH.shape) == tuple(H.shape) and tuple(dW_base.shape) == tuple(W_base.shape)
+        assert tuple(dW_hyper.shape) == (self.B, self.cap, self.d)
+        _check(self._lib.z2z_extended_nll_backward(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq,
+                                                   _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
+                                                   _ptr(targets, torch.int32), _ptr(lse, torch.float32),
+                                                   _ptr(grad_nll, torch.float32), _ptr(dH, self.torch_dtype),
+                                                   _ptr(dW_base, self.torch_dtype), _ptr(dW_hyper, self.torch_dtype),
+                                                   _stream()), "z2z_extended_nll_backward")
+
+    def hyper_embed_backward(self, dW_hyper: torch.Tensor, dE: torch.Tensor) -> None:
+        assert tuple(dW_hyper.shape) == (self.B, self.cap, self.d) and tuple(dE.shape) == (self.V, self.d)
+        _check(self._lib.z2z_hyper_embed_backward(self._h, _ptr(dW_hyper, self.torch_dtype), _ptr(dE, torch.float32),
+                                                  _stream()), "z2z_hyper_embed_backward")
 
 
 class _DevView:

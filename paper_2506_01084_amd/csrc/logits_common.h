@@ -174,6 +174,11 @@ struct LogitsArgs {
   const void* residual;   // [rows, ldo] bf16 or nullptr
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
+  // probability mode (the backward pass of the loss): out[r, c] = g[r] * (exp(logit - lse[r]) - [col0 + c == target[r]])
+  // for the existing columns c < n_valid, 0 for the other columns below ldo; bf16, row stride ldo
+  const float* lse;       // [rows]
+  const float* row_grad;  // [rows] g: the upstream gradient, 0 for rows without a usable target
+  const int32_t* targets; // [rows]
   const int32_t* rows_dev;  // nullptr, or the number of rows that exist (<= rows), known on the device only
   int32_t strip_blocks;     // > 0: linear mode with the XCD-per-row-tile mapping, = ceil(n_strips / map_ls)
 };
@@ -242,11 +247,54 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const Lo
   }
 }
 
+// Store one finished accumulator tile as the gradient of the loss with respect to the logits (same register
+// layout as fold_tile; see LogitsArgs, probability mode).  Columns come in fours; ldo is a multiple of 4.
+template <int NI, int NJ>
+__device__ __forceinline__ void store_prob_tile(const f32x16 (&acc)[NI][NJ], const LogitsArgs& a, int row_base, int r_end,
+                                                int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+  float lse[NJ], g[NJ];
+  int tgt[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+    const bool ok = row < r_end;
+    lse[j] = ok ? a.lse[row] : 0.f;
+    g[j] = ok ? a.row_grad[row] : 0.f;
+    tgt[j] = ok ? a.targets[row] - a.col0 : -1;
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = col_base + i * 32 + q * 8;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float z = read_acc(acc[i][j][q * 4 + e]);
+          const float p = __expf(z - lse[j]) - (col + e == tgt[j] ? 1.f : 0.f);
+          x[e] = col + e < n_valid ? g[j] * p : 0.f;
+        }
+        if (row < r_end && col < a.ldo) {
+          uint2 o;
+          o.x = bf16_bits_rne(x[0]) | (bf16_bits_rne(x[1]) << 16);
+          o.y = bf16_bits_rne(x[2]) | (bf16_bits_rne(x[3]) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + (size_t)row * a.ldo + col) = o;
+        }
+      }
+    }
+  }
+}
+
 }  // namespace z2z_logits
 
 // kernel launchers, one per translation unit
 int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
-// mode: 0 base part, 1 hyper part (both fold the joint softmax), 2 dense layer (stores the tile)
+// mode: 0 base part, 1 hyper part (both fold the joint softmax), 2 dense layer (stores the tile),
+// 3 base part, 4 hyper part storing the gradient with respect to the logits
 int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 // out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
 // (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor

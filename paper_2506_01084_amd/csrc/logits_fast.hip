@@ -135,7 +135,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   int r0, r_end, n_valid;
   const unsigned char* Wp = reinterpret_cast<const unsigned char*>(a.W);
   const size_t row_bytes = (size_t)a.d * 2;
-  if (MODE == 1) {
+  if (MODE == 1 || MODE == 4) {
     if ((int)blockIdx.x >= a.n_work) return;
     st = blockIdx.x % a.n_strips;
     rt = blockIdx.x / a.n_strips;
@@ -318,13 +318,15 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       const int v0 = vt * FT;
       if (MODE == 2)
         store_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      else if (MODE >= 3)
+        store_prob_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
       else
         fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
       zero_acc();
     }
   }
 
-  if (MODE == 2) {
+  if (MODE >= 2) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the requests past the end of the stream land in LDS
     return;
   }
@@ -364,7 +366,11 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 2)
+  if (mode == 4)
+    hipLaunchKernelGGL(logits_fast_kernel<4>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 3)
+    hipLaunchKernelGGL(logits_fast_kernel<3>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 2)
     hipLaunchKernelGGL(logits_fast_kernel<2>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 1)
     hipLaunchKernelGGL(logits_fast_kernel<1>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -381,6 +387,10 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<4>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

@@ -28,6 +28,8 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->sample_logits);
   (void)hipFree(c->row_max);
   (void)hipFree(c->enc_ws);
+  (void)hipFree(c->bwd_ws);
+  (void)hipFree(c->coef_dev);
   (void)hipFree(c->skinny_partial);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
@@ -223,6 +225,28 @@ Z2Z_API int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_
   if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
   return z2z_launch_extended_nll(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_targets, d_nll, d_lse,
                                  static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_extended_nll_backward(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                                      const void* d_W_base, const void* d_W_hyper, const int32_t* d_targets,
+                                      const float* d_lse, const float* d_grad_nll, void* d_dH, void* d_dW_base,
+                                      void* d_dW_hyper, void* stream) {
+  if (!ctx || !d_H || !d_W_base || !d_targets || !d_lse || !d_dH || !d_dW_base) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && (!d_W_hyper || !d_dW_hyper)) return Z2Z_EINVAL;
+  if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
+  if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
+  if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper) || !aligned16(d_dH) || !aligned16(d_dW_base) ||
+      !aligned16(d_dW_hyper))
+    return Z2Z_EINVAL;
+  return z2z_launch_extended_nll_backward(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_targets, d_lse,
+                                          d_grad_nll, d_dH, d_dW_base, d_dW_hyper, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_hyper_embed_backward(z2z_ctx* ctx, const void* d_dW_hyper, float* d_dE, void* stream) {
+  if (!ctx || !d_dE) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_dW_hyper) return Z2Z_EINVAL;
+  if (ctx->cfg.dtype != Z2Z_BF16) return Z2Z_EUNSUPPORTED;
+  return z2z_launch_hyper_embed_backward(ctx, d_dW_hyper, d_dE, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {

@@ -52,6 +52,10 @@ struct z2z_ctx {
   // hyper_encode work space: the activations of one pass (bf16)
   void* enc_ws;
   size_t enc_ws_bytes;
+  // backward pass of the loss: dZ, the transposed operand copies (bf16), the row gradients
+  void* bwd_ws;
+  size_t bwd_ws_bytes;
+  void* coef_dev;          // the pooling coefficients on the device (pooling backward)
   // dense layers on few rows with K split over workgroups: the partial tiles
   void* skinny_partial;
   size_t skinny_partial_bytes;
@@ -84,6 +88,10 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
                                const void* W_hyper, float temperature, int32_t top_k, float top_p, uint64_t seed,
                                uint64_t step, int32_t* token, float* logprob, hipStream_t s);
 int z2z_sample_truncated_prepare(z2z_ctx* c);
+int z2z_launch_extended_nll_backward(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
+                                     const void* W_hyper, const int32_t* targets, const float* lse,
+                                     const float* grad_nll, void* dH, void* dW_base, void* dW_hyper, hipStream_t s);
+int z2z_launch_hyper_embed_backward(z2z_ctx* c, const void* dW_hyper, float* dE, hipStream_t s);
 bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc);
 int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, void* W_hyper, const int32_t* first,
                             int32_t max_new, hipStream_t s);
