@@ -11,7 +11,8 @@ shapes: 8 x 4096 tokens, V = 128256, d = 4096 bf16, M = 3, cap = 2048), inputs r
 `value` is base tokens per second of that whole step.  The decode step of configuration 3 (64 sequences
 with 8192-token histories, HBM-bound) is timed separately in the same run and reported in `decode_step`.
 The learned hyper-encoder (a two-layer transformer over every entry's slots, in place of the averaging one) is
-timed on configuration 2's codebooks and reported in `hyper_encode`.
+timed on configuration 2's codebooks and reported in `hyper_encode`; the training-side loss over the extended
+vocabulary and its gradient, on configuration 2, in `nll_backward`.
 The CPU oracle is timed on a bounded sample of the same workload as `cpu_baseline`.
 
 Prints ONE JSON line on stdout.
@@ -332,6 +333,60 @@ def run_encoder_workload(args, torch, api, wl):
     }
 
 
+def run_backward_workload(args, torch, api, wl):
+    """Configuration 2 as a training step of the unembedding: the loss of every position's next code
+    (extended_nll), its gradient into H, W_base, W_hyper (extended_nll_backward) and through the pooling."""
+    cfg = wl.CONFIGS["c2"]
+    B, N, V, M, cap, d = (cfg[k] for k in ("B", "N", "V", "M", "cap", "d"))
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_tok = torch.from_numpy(wl.make_tokens(cfg)).cuda()
+    d_codes, d_n, d_st = torch.full((B, N), -1, **i32), torch.empty(B, **i32), torch.empty(B, **i32)
+    ctx.lzw_encode(d_tok, None, d_codes, d_n, d_st, api.RESET)
+    d_E = to_device_bf16(torch, wl.make_embeddings(cfg))
+    d_H = to_device_bf16(torch, wl.make_hidden(cfg, B * N))
+    d_W = torch.empty((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_embed(d_E, d_W)
+    # row i of a sequence is asked for code i + 1 of its compressed stream; rows past the stream have no target
+    d_t = torch.roll(d_codes, -1, dims=1).contiguous()
+    d_t[:, -1] = -1
+    d_t = d_t.reshape(-1)
+    nll = torch.empty(B * N, dtype=torch.float32, device="cuda")
+    lse = torch.empty_like(nll)
+    dH, dWb, dWh = torch.empty_like(d_H), torch.empty_like(d_E), torch.empty_like(d_W)
+    dE = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    fwd, bwd, pool = [], [], []
+    for rep in range(4):                               # the first one sizes the work space
+        ev[0].record()
+        ctx.extended_nll(d_H, N, d_E, d_W, d_t, nll, lse)
+        ev[1].record()
+        ctx.extended_nll_backward(d_H, N, d_E, d_W, d_t, lse, None, dH, dWb, dWh)
+        ev[2].record()
+        ctx.hyper_embed_backward(dWh, dE)
+        ev[3].record()
+        torch.cuda.synchronize()
+        if rep > 0:
+            fwd.append(ev[0].elapsed_time(ev[1]))
+            bwd.append(ev[1].elapsed_time(ev[2]))
+            pool.append(ev[2].elapsed_time(ev[3]))
+    sizes = ctx.codebook()[2].cpu().numpy()
+    cols = V + float(sizes.mean())
+    flops_bwd = 3 * 2.0 * B * N * d * cols           # the logits again, dH, dW
+    n_targets = int((d_t >= 0).sum().item())
+    mean_nll = float(nll[torch.isfinite(nll) & (d_t >= 0)].mean().item())
+    ctx.close()
+    ms = lambda v: sum(v) / len(v)
+    return {
+        "workload": f"c2: {B * N} rows x {int(cols)} columns, d={d} bf16; targets = the next code of the compressed stream "
+                    f"({n_targets} rows with a target)",
+        "forward_nll_ms": ms(fwd), "backward_ms": ms(bwd), "pooling_backward_ms": ms(pool),
+        "backward_flops": flops_bwd, "backward_TFLOPs": flops_bwd / (ms(bwd) * 1e-3) / 1e12,
+        "backward_frac_of_bf16_peak": flops_bwd / (ms(bwd) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mean_nll": mean_nll,
+    }
+
+
 def cpu_baseline(wl, host, budget_rows=4096):
     """The oracle, as it stands, on the host cores: LZW and pooling on the full configuration-2 batch, the
     joint logits on a sample of rows of sequence 0 (all columns); combined into tokens/s of the whole step."""
@@ -376,6 +431,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-encoder", action="store_true", help="skip the learned hyper-encoder measurement")
+    ap.add_argument("--no-backward", action="store_true", help="skip the loss forward + backward measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -403,6 +459,7 @@ def main():
     log(f"[bench] step {res['ms_per_step']:.2f} ms; stages {res['stage_ms']}; base-part kernel {k_ms:.3f} ms")
     dec = None if args.no_decode else run_decode_workload(args, torch, api, wl)
     enc = None if args.no_encoder else run_encoder_workload(args, torch, api, wl)
+    bwd = None if args.no_backward else run_backward_workload(args, torch, api, wl)
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host)
 
     cfg = res["cfg"]
@@ -439,6 +496,7 @@ def main():
         "cpu_baseline": cpu,
         "decode_step": dec,
         "hyper_encode": enc,
+        "nll_backward": bwd,
     }
     print(json.dumps(line), flush=True)
 

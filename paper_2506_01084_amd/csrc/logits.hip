@@ -494,22 +494,34 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(uint4* p, size_t n16) {
 }
 
 // out[b][c][r] = in[b][r][c] (bf16) for r < R, c < C; columns R .. ld_out - 1 of out are zero.  64 x 64 tiles
-// through LDS, 256 threads; grid (ceil(ld_out / 64), ceil(C / 64), batch).
+// through LDS, 256 threads, 16 bytes per lane on both sides (ld_in and ld_out are multiples of 8, the bases
+// 16-byte aligned); grid (ceil(ld_out / 64), ceil(C / 64), batch).
 __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* in, uint16_t* out, int R, int C, int ld_in,
                                                              int ld_out, size_t in_batch, size_t out_batch) {
-  __shared__ uint16_t t[64][66];
+  __shared__ uint16_t t[64][72];                     // [column of the tile][row of the tile], rows padded
   const uint16_t* src = in + (size_t)blockIdx.z * in_batch;
   uint16_t* dst = out + (size_t)blockIdx.z * out_batch;
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
-    const int r = r0 + i, c = c0 + tx;
-    t[i][tx] = (r < R && c < C) ? src[(size_t)r * ld_in + c] : (uint16_t)0;
+  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;       // 8 chunks of 8 elements per line, 32 lines
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;                     // row of the tile
+    const int r = r0 + i, c = c0 + chunk * 8;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (r < R && c < ld_in) v = *reinterpret_cast<const uint4*>(src + (size_t)r * ld_in + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      t[chunk * 8 + 2 * e][i] = (uint16_t)(w[e] & 0xFFFFu);
+      t[chunk * 8 + 2 * e + 1][i] = (uint16_t)(w[e] >> 16);
+    }
   }
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int c = c0 + i, r = r0 + tx;
-    if (c < C && r < ld_out) dst[(size_t)c * ld_out + r] = t[tx][i];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;                     // column of the tile = row of the output
+    const int c = c0 + i, r = r0 + chunk * 8;
+    if (c < C && r < ld_out) *reinterpret_cast<uint4*>(dst + (size_t)c * ld_out + r) = *reinterpret_cast<const uint4*>(&t[i][chunk * 8]);
   }
 }
 
