@@ -112,6 +112,22 @@ int z2z_lzw_decode(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_code
 int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entry_len,
                  const int32_t** d_size);
 
+/* Codebook prefilling (the paper's discussion, "Codebook Management Strategy", item 2: seeding the codebook
+ * with phrases expected to occur, ahead of the input).  The paper names the idea only; the operation here:
+ * phrase i of sequence b becomes entry C_b (ID V + C_b) if it has 2..M tokens, all in [0, V), its prefix
+ * without the last token is a base token or an entry already (the codebook stays prefix-closed, which the
+ * parse relies on), it is not an entry yet, and the codebook is not full.  The first phrase that fails ends
+ * that sequence's prefill: BAD_TOKEN (length or token out of range), BAD_CODE (prefix unknown, or a
+ * duplicate), OVERFLOW (codebook full); entries added before it stay.  Afterwards no phrase is pending:
+ * z2z_lzw_encode / z2z_lzw_decode continue with Z2Z_APPEND, and both sides of a round trip must prefill alike.
+ *   d_phrases    [B, n_max, M] int32 (tokens beyond a phrase's length are ignored)
+ *   d_phrase_len [B, n_max] int32;  d_counts [B] int32 or NULL (= n_max phrases for every sequence)
+ *   flags        Z2Z_RESET: start from empty codebooks; Z2Z_APPEND: add to what is there
+ *   d_n_added    [B] int32 out;  d_status [B] int32 out */
+int z2z_codebook_prefill(z2z_ctx* ctx, const int32_t* d_phrases, const int32_t* d_phrase_len,
+                         const int32_t* d_counts, int32_t n_max, int32_t flags, int32_t* d_n_added,
+                         int32_t* d_status, void* stream);
+
 /* hyper_embed.  W_hyper[b, e, :] = sum_j a_j * E[t_j, :] over the L tokens of entry e of sequence b,
  * a_j = 1/L (MEAN) or softmax(w[0..L))_j (WEIGHTED); padding slots contribute nothing and are not
  * in the divisor.  fp32 accumulation in token order, one round-to-nearest-even to the storage type.

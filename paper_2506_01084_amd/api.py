@@ -23,7 +23,7 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
-EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook",
+EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill",
            "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
@@ -91,6 +91,8 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_lzw_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32,
                                    c_void_p, c_void_p]
     lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
+    lib.z2z_codebook_prefill.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
+                                         c_void_p]
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_hyper_encode.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
@@ -197,6 +199,15 @@ class Context:
                                         stride, flags, _ptr(tokens, torch.int32),
                                         _ptr(n_tokens, torch.int32), out_stride, _ptr(status, torch.int32),
                                         _stream()), "z2z_lzw_decode")
+
+    def codebook_prefill(self, phrases: torch.Tensor, phrase_len: torch.Tensor, counts: Optional[torch.Tensor],
+                         n_added: torch.Tensor, status: torch.Tensor, flags: int = RESET) -> None:
+        assert phrases.dim() == 3 and phrases.shape[0] == self.B and phrases.shape[2] == self.M
+        assert tuple(phrase_len.shape) == tuple(phrases.shape[:2])
+        _check(self._lib.z2z_codebook_prefill(self._h, _ptr(phrases, torch.int32), _ptr(phrase_len, torch.int32),
+                                              _ptr(counts, torch.int32), phrases.shape[1], flags,
+                                              _ptr(n_added, torch.int32), _ptr(status, torch.int32), _stream()),
+               "z2z_codebook_prefill")
 
     def codebook_ptrs(self):
         e, l, s = c_void_p(), c_void_p(), c_void_p()

@@ -891,10 +891,92 @@ void plan(const z2z_ctx* c, int32_t stride, int32_t flags, bool decode, bool* ld
   }
 }
 
+// Codebook prefilling: the given phrases become entries, in order, before any input is parsed (zip2zip
+// paper, discussion, "Codebook Management Strategy", item 2).  A phrase is taken if it keeps the codebook what
+// the parse kernels rely on: 2..M tokens, all in [0, V), its prefix without the last token a base token or an
+// entry already, itself not an entry yet, and the codebook not full; the first phrase that is not ends the
+// sequence's prefill with a status bit.  One wave per sequence, wave-uniform scalar walk of the trie in the
+// global table.  a.in = phrases [B, stride, M], a.in_len = [B] counts or nullptr, a.out = phrase lengths
+// [B, stride], a.out_n = [B] entries added.
+__global__ void __launch_bounds__(kWave) lzw_prefill_kernel(LzwArgs a) {
+  const LzwState& st = a.st;
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int V = st.V, M = st.M, cap = st.cap;
+  const bool reset = (a.flags & Z2Z_RESET) != 0;
+  int C = reset ? 0 : __builtin_amdgcn_readfirstlane(st.size[b]);
+  Table<false> t;
+  table_open<false>(a, b, lane, reset, &t);
+  const int n = call_length(a, b);
+  const int32_t* phrases = a.in + (size_t)b * a.stride * M;
+  const int32_t* lens = a.out + (size_t)b * a.stride;
+  int status = 0, added = 0;
+  for (int i = 0; i < n; ++i) {
+    const int L = __builtin_amdgcn_readfirstlane(lens[i]);
+    if (L < 2 || L > M) {
+      status |= Z2Z_ST_BAD_TOKEN;
+      break;
+    }
+    const int32_t tok = lane < L ? phrases[(size_t)i * M + lane] : 0;      // lane j = token j
+    if (__any(lane < L && (tok < 0 || tok >= V))) {
+      status |= Z2Z_ST_BAD_TOKEN;
+      break;
+    }
+    int32_t code = __builtin_amdgcn_readlane(tok, 0);
+    bool known = true;
+    for (int j = 1; j < L - 1 && known; ++j) {
+      int fp;
+      const int idx = t.find(code, __builtin_amdgcn_readlane(tok, j), &fp);
+      known = idx >= 0;
+      code = V + idx;
+    }
+    int free_pos = -1;
+    const int32_t last = __builtin_amdgcn_readlane(tok, L - 1);
+    if (!known || t.find(code, last, &free_pos) >= 0 || free_pos < 0) {
+      status |= Z2Z_ST_BAD_CODE;                     // prefix unknown, or the phrase is an entry already
+      break;
+    }
+    if (C >= cap) {
+      status |= Z2Z_ST_OVERFLOW;
+      break;
+    }
+    table_insert<false>(a, b, lane, t, free_pos, C, code, last, tok, L - 1);
+    ++C;
+    ++added;
+    __syncthreads();                                 // the slot is visible to the next phrase's walk
+  }
+  if (lane == 0) {
+    st.size[b] = C;
+    st.prev_code[b] = -1;                            // the parse starts afresh: no pending phrase
+    st.prev_len[b] = 0;
+    a.out_n[b] = added;
+    a.status[b] = status;
+  }
+}
+
 }  // namespace
 
 int z2z_launch_lzw_reset(z2z_ctx* c, hipStream_t s) {
   hipLaunchKernelGGL(lzw_reset_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_t* phrase_len, const int32_t* counts,
+                                int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s) {
+  LzwArgs a;
+  a.st = c->st;
+  a.in = phrases;
+  a.in_len = counts;
+  a.stride = n_max;
+  a.flags = flags;
+  a.out = const_cast<int32_t*>(phrase_len);          // read only
+  a.out_n = n_added;
+  a.out_stride = n_max;
+  a.status = status;
+  a.lds_ef = 0;
+  if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
+  hipLaunchKernelGGL(lzw_prefill_kernel, dim3(c->cfg.B), dim3(kWave), 0, s, a);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

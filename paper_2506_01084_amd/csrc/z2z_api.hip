@@ -159,6 +159,16 @@ Z2Z_API int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t*
   return Z2Z_OK;
 }
 
+Z2Z_API int z2z_codebook_prefill(z2z_ctx* ctx, const int32_t* d_phrases, const int32_t* d_phrase_len,
+                                 const int32_t* d_counts, int32_t n_max, int32_t flags, int32_t* d_n_added,
+                                 int32_t* d_status, void* stream) {
+  if (!ctx || !d_n_added || !d_status || n_max < 0) return Z2Z_EINVAL;
+  if (n_max > 0 && (!d_phrases || !d_phrase_len)) return Z2Z_EINVAL;
+  if (flags != Z2Z_RESET && flags != Z2Z_APPEND) return Z2Z_EINVAL;
+  return z2z_launch_codebook_prefill(ctx, d_phrases, d_phrase_len, d_counts, n_max, flags, d_n_added, d_status,
+                                     static_cast<hipStream_t>(stream));
+}
+
 Z2Z_API int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, const int32_t* d_first,
                             int32_t max_new, void* stream) {
   if (!ctx || !d_E) return Z2Z_EINVAL;

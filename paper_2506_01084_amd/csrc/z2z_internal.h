@@ -79,6 +79,8 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
                           int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s);
 int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t flags,
                           int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s);
+int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_t* phrase_len, const int32_t* counts,
+                                int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s);
 int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32_t* first, int32_t max_new,
                            hipStream_t s);
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,

@@ -355,3 +355,71 @@ def test_pack_entries_layout():
     assert C == 2 and ln.tolist() == [2, 3, 0, 0]
     assert tok.tolist() == [[5, 6, -1], [5, 6, 7], [-1, -1, -1], [-1, -1, -1]]
     assert tok.dtype == np.int32 and ln.dtype == np.int32
+
+
+# ---------------------------------------------------------------------------
+# codebook prefilling (discussion section, "Codebook Management Strategy", item 2)
+# ---------------------------------------------------------------------------
+def _greedy_with_seed(x, V, M, cap, seed):
+    """The set-of-tuples parse of P7, started from a given list of entries."""
+    known = list(seed)
+    codes, i, n = [], 0, len(x)
+    while i < n:
+        best = 1
+        for L in range(2, min(M, n - i) + 1):
+            if tuple(x[i:i + L]) in known:
+                best = L
+            else:
+                break
+        ph = tuple(x[i:i + best])
+        codes.append(ph[0] if best == 1 else V + known.index(ph))
+        i += best
+        cand = ph + (x[i],) if i < n else None
+        if cand is not None and best + 1 <= M and len(known) < cap and cand not in known:
+            known.append(cand)
+    return codes, known
+
+
+def test_prefill_then_parse_equals_seeded_brute_force_and_round_trips():
+    rnd = random.Random(11)
+    for trial in range(300):
+        V = rnd.choice([2, 3, 5])
+        M, cap = rnd.choice([2, 3, 4]), rnd.choice([3, 8, 40])
+        warm = [rnd.randrange(V) for _ in range(rnd.randint(0, 40))]
+        seed = lzw_encode(warm, V, M, cap)[1][: rnd.randint(0, cap)]       # a prefix of a real codebook: prefix-closed
+        x = [rnd.randrange(V) for _ in range(rnd.randint(0, 60))]
+        enc = LZWStream(V, M, cap)
+        added, st = enc.prefill(seed)
+        assert st == ST_OK and added == len(seed) and enc.entries == list(seed)
+        codes, st = enc.encode_chunk(x)
+        ref_codes, ref_known = _greedy_with_seed(x, V, M, cap, seed)
+        assert st == ST_OK and codes == ref_codes and enc.entries == ref_known
+        dec = LZWStream(V, M, cap)
+        dec.prefill(seed)
+        toks, st = dec.decode_chunk(codes)
+        assert st == ST_OK and toks == x and dec.entries == enc.entries
+        if seed and x:
+            assert len(codes) <= len(lzw_encode(x, V, M, cap)[0]) + len(x)      # sanity: still a parse of x
+    # an empty prefill changes nothing
+    s = LZWStream(4, 3, 10)
+    assert s.prefill([]) == (0, ST_OK)
+    assert s.encode_chunk([1, 2, 1, 2, 1, 2])[0] == lzw_encode([1, 2, 1, 2, 1, 2], 4, 3, 10)[0]
+
+
+def test_prefill_rejects_what_would_break_the_codebook():
+    def run(phrases, V=5, M=3, cap=4):
+        s = LZWStream(V, M, cap)
+        return s.prefill(phrases), s.entries
+    assert run([(1, 2), (1, 2, 3)]) == ((2, ST_OK), [(1, 2), (1, 2, 3)])
+    assert run([(1, 2, 3)]) == ((0, ST_BAD_CODE), [])                         # prefix (1, 2) unknown
+    assert run([(1, 2), (1, 2)]) == ((1, ST_BAD_CODE), [(1, 2)])              # duplicate
+    assert run([(1,)]) == ((0, ST_BAD_TOKEN), [])                             # too short
+    assert run([(1, 2), (1, 2, 3), (1, 2, 3, 4)])[0] == (2, ST_BAD_TOKEN)     # longer than M
+    assert run([(1, 7)]) == ((0, ST_BAD_TOKEN), [])                           # token out of range
+    assert run([(0, 1), (0, 2), (0, 3), (0, 4), (1, 1)])[0] == (4, ST_OVERFLOW)
+    # a pending phrase is dropped: the next chunk starts afresh (no entry from the old phrase)
+    s = LZWStream(5, 3, 10)
+    s.encode_chunk([1, 2])
+    s.prefill([(3, 4)])
+    s.encode_chunk([0])
+    assert s.entries == [(1, 2), (3, 4)]
