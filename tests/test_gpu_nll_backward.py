@@ -147,3 +147,54 @@ def test_full_size_c2_sampled_rows():
         _close(dWh_h[b, e:e + 1], (dz @ H64[sl])[None, :], f"dW_hyper ({b}, {e})")
     print(f"  dW rows checked {time.time() - t0:.1f}s", flush=True)
     ctx.close()
+
+
+def test_edge_cases_no_hypertokens_no_targets_and_odd_row_counts():
+    import torch
+    from paper_2506_01084_amd import api
+
+    # cap = 0: base vocabulary only; 77 rows per sequence (not a multiple of 64), V not a multiple of 64
+    B, N, V, d = 3, 77, 333, 64
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=3, cap=0, seed=31)
+    E = wl.make_embeddings(cfg)
+    H = wl.make_hidden(cfg, B * N)
+    rng = np.random.default_rng(2)
+    targets = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    targets[1] = -1                                            # a sequence without any target
+    targets[2, ::2] = V + 5                                    # names no column
+    ctx = api.Context(B=B, V=V, M=3, cap=0, d=d, dtype="bf16")
+    ctx.reset()
+    d_E, d_H = torch_storage(E, "bf16"), torch_storage(H, "bf16")
+    d_W = torch.zeros((B, 0, d), dtype=torch.bfloat16, device="cuda")
+    d_t = torch.from_numpy(targets.reshape(-1)).cuda()
+    nll = torch.empty(B * N, dtype=torch.float32, device="cuda")
+    lse = torch.empty_like(nll)
+    ctx.extended_nll(d_H, N, d_E, d_W, d_t, nll, lse)
+    dH = torch.full((B * N, d), 9.0, dtype=torch.bfloat16, device="cuda")
+    dWb = torch.full((V, d), 9.0, dtype=torch.bfloat16, device="cuda")
+    dWh = torch.zeros((B, 0, d), dtype=torch.bfloat16, device="cuda")
+    for rep in range(2):                                       # the second call reuses the work space
+        ctx.extended_nll_backward(d_H, N, d_E, d_W, d_t, lse, None, dH, dWb, dWh)
+    dE = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    ctx.hyper_embed_backward(dWh, dE)
+    torch.cuda.synchronize()
+    assert (dE == 0).all()
+    dH_h, dWb_h = storage_to_host(dH, "bf16"), storage_to_host(dWb, "bf16")
+    want_dWb = np.zeros((V, d))
+    for b in range(B):
+        sl = slice(b * N, (b + 1) * N)
+        r = oracle.extended_nll_backward(H[sl], E, np.zeros((0, d), dtype=np.uint16), 0, "bf16", targets[b], np.ones(N))
+        _close(dH_h[sl], r["dH"], f"dH seq {b}")
+        want_dWb += r["dW_base"]
+    _close(dWb_h, want_dWb, "dW_base")
+    assert (oracle.bf16_bits_to_f64(dH_h[N:2 * N]) == 0).all()
+    ctx.close()
+
+    # fp32 contexts are refused, not silently served by something else
+    ctx = api.Context(B=1, V=100, M=3, cap=8, d=64, dtype="f32")
+    ctx.reset()
+    z = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
+    with pytest.raises(api.Z2ZError):
+        ctx.extended_nll_backward(z(4, 64), 4, z(100, 64), z(1, 8, 64), torch.zeros(4, dtype=torch.int32, device="cuda"),
+                                  z(4), None, z(4, 64), z(100, 64), z(1, 8, 64))
+    ctx.close()
