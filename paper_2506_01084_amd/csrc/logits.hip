@@ -263,8 +263,104 @@ int launch_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, 
 
 }  // namespace
 
+namespace {
+
+// Dense layer with K split over workgroups of the tile kernel: out = act(sum_ks partial[ks] + bias) + residual,
+// the parts added in a fixed order; one thread per run of 4 columns.
+__global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, int ksplit, int rows, const int32_t* rows_dev,
+                                                         int N, const float* bias, int act, const uint16_t* residual,
+                                                         uint16_t* out) {
+  const int n4 = N >> 2;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int r_end = rows_dev ? min(rows, *rows_dev) : rows;
+  if (i >= (long long)r_end * n4) return;
+  const int row = (int)(i / n4), col = (int)(i % n4) * 4;
+  const size_t at = (size_t)row * N + col;
+  float4 x = *reinterpret_cast<const float4*>(partial + at);
+  for (int k = 1; k < ksplit; ++k) {
+    const float4 y = *reinterpret_cast<const float4*>(partial + (size_t)k * rows * N + at);
+    x.x += y.x;
+    x.y += y.y;
+    x.z += y.z;
+    x.w += y.w;
+  }
+  if (bias) {
+    const float4 b = *reinterpret_cast<const float4*>(bias + col);
+    x.x += b.x;
+    x.y += b.y;
+    x.z += b.z;
+    x.w += b.w;
+  }
+  if (act == 1) {
+    x.x = gelu_erf(x.x);
+    x.y = gelu_erf(x.y);
+    x.z = gelu_erf(x.z);
+    x.w = gelu_erf(x.w);
+  }
+  if (residual) {
+    const uint2 rv = *reinterpret_cast<const uint2*>(residual + at);
+    x.x += __uint_as_float(rv.x << 16);
+    x.y += __uint_as_float(rv.x & 0xFFFF0000u);
+    x.z += __uint_as_float(rv.y << 16);
+    x.w += __uint_as_float(rv.y & 0xFFFF0000u);
+  }
+  uint2 o;
+  o.x = bf16_bits_rne(x.x) | (bf16_bits_rne(x.y) << 16);
+  o.y = bf16_bits_rne(x.z) | (bf16_bits_rne(x.w) << 16);
+  *reinterpret_cast<uint2*>(out + at) = o;
+}
+
+}  // namespace
+
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s) {
+  // between one and a few hundred rows (more than the 64 the decode-step kernel serves per pass over the
+  // weights, too few for the tile kernel to have a tile per CU): the tile kernel with K split over workgroups,
+  // so that the weights stream once for all rows and every CU has a part
+  if (R > 64 && R <= 512 && c->fast_ready && K % 64 == 0 && N % 8 == 0 && c->opt_logits_kernel != 1) {
+    const int row_tiles = (R + 255) / 256, n_vt = (N + 255) / 256, tiles = row_tiles * n_vt;
+    const int n_slabs = K / 64;
+    int ksplit = 1;
+    while (tiles * ksplit < 192 && n_slabs / (ksplit * 2) >= 8) ksplit *= 2;
+    if (ksplit > 1) {
+      const int per = (n_slabs + ksplit - 1) / ksplit;
+      ksplit = (n_slabs + per - 1) / per;
+      const size_t need = (size_t)ksplit * R * N * sizeof(float);
+      if (need > c->skinny_partial_bytes) {
+        if (c->skinny_partial) (void)hipFree(c->skinny_partial);
+        c->skinny_partial = nullptr;
+        c->skinny_partial_bytes = 0;
+        const size_t want = need > ((size_t)64 << 20) ? need : ((size_t)64 << 20);
+        if (hipMalloc(&c->skinny_partial, want) != hipSuccess) return Z2Z_ENOMEM;
+        c->skinny_partial_bytes = want;
+      }
+      LogitsArgs a;
+      memset(&a, 0, sizeof(a));
+      a.H = A;
+      a.W = W;
+      a.rows = R;
+      a.rows_per_seq = R;
+      a.d = K;
+      a.w_rows = N;
+      a.n_vtiles = n_vt;
+      a.row_tiles = row_tiles;
+      a.strip = 1;
+      a.n_strips = n_vt;
+      a.ldo = N;
+      a.rows_dev = rows_dev;
+      a.ksplit = ksplit;
+      a.slabs_per_part = per;
+      a.partial = reinterpret_cast<float*>(c->skinny_partial);
+      int rc = z2z_launch_logits_fast(5, a, (unsigned)(tiles * ksplit), s);
+      if (rc != Z2Z_OK) return rc;
+      const long long n_threads = (long long)R * (N / 4);
+      hipLaunchKernelGGL(linear_sum_kernel, dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, s,
+                         reinterpret_cast<const float*>(c->skinny_partial), ksplit, R, rows_dev, N, bias, act,
+                         reinterpret_cast<const uint16_t*>(residual), reinterpret_cast<uint16_t*>(out));
+      Z2Z_HIP_TRY(hipGetLastError());
+      return Z2Z_OK;
+    }
+  }
   // few rows: bound by the weight bytes, which the decode-step kernel streams at HBM rate (it re-reads them
   // once per 64 rows, so it loses to the tile kernel beyond a few hundred rows)
   if (R <= 512 && c->skinny_ready && K % 128 == 0 && N % 2 == 0 && c->opt_logits_kernel != 2)

@@ -181,6 +181,10 @@ struct LogitsArgs {
   const int32_t* targets; // [rows]
   const int32_t* rows_dev;  // nullptr, or the number of rows that exist (<= rows), known on the device only
   int32_t strip_blocks;     // > 0: linear mode with the XCD-per-row-tile mapping, = ceil(n_strips / map_ls)
+  // linear mode with K split over ksplit workgroups per tile (few rows: too few tiles to fill the machine):
+  // part ks covers K slabs [ks * slabs_per_part, ...) and leaves its fp32 tile in partial[ks][row][col]
+  int32_t ksplit, slabs_per_part;
+  float* partial;           // [ksplit][rows][ldo]
 };
 
 // Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
@@ -247,6 +251,31 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const Lo
   }
 }
 
+// Store one finished accumulator tile as it is (fp32), for a dense layer whose K range is split over several
+// workgroups: 16-byte stores.
+template <int NI, int NJ>
+__device__ __forceinline__ void store_partial_tile(const f32x16 (&acc)[NI][NJ], float* part, int ld, int row_base,
+                                                   int r_end, int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = col_base + i * 32 + q * 8;
+        float4 x;
+        x.x = read_acc(acc[i][j][q * 4 + 0]);
+        x.y = read_acc(acc[i][j][q * 4 + 1]);
+        x.z = read_acc(acc[i][j][q * 4 + 2]);
+        x.w = read_acc(acc[i][j][q * 4 + 3]);
+        if (row < r_end && col < n_valid) *reinterpret_cast<float4*>(part + (size_t)row * ld + col) = x;
+      }
+    }
+  }
+}
+
 // Store one finished accumulator tile as the gradient of the loss with respect to the logits (same register
 // layout as fold_tile; see LogitsArgs, probability mode).  Columns come in fours; ldo is a multiple of 4.
 template <int NI, int NJ>
@@ -294,7 +323,8 @@ __device__ __forceinline__ void store_prob_tile(const f32x16 (&acc)[NI][NJ], con
 // kernel launchers, one per translation unit
 int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 // mode: 0 base part, 1 hyper part (both fold the joint softmax), 2 dense layer (stores the tile),
-// 3 base part, 4 hyper part storing the gradient with respect to the logits
+// 3 base part, 4 hyper part storing the gradient with respect to the logits, 5 dense layer with K split
+// (fp32 partial tiles)
 int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 // out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
 // (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor

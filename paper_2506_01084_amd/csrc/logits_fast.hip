@@ -144,6 +144,16 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     r_end = (b + 1) * a.rows_per_seq;
     n_valid = min(max(a.size[b], 0), a.w_rows);
     Wp += (size_t)b * a.w_rows * row_bytes;
+  } else if (MODE == 5) {
+    // few tiles, K split: workgroup -> (K part, row tile, weight tile)
+    r_end = a.rows_dev ? min(a.rows, *a.rows_dev) : a.rows;
+    const int t = blockIdx.x / a.ksplit;
+    rt = t % a.row_tiles;
+    st = t / a.row_tiles;
+    if (st >= a.n_strips) return;
+    r0 = rt * FT;
+    if (r0 >= r_end) return;
+    n_valid = a.w_rows;
   } else {
     r_end = a.rows;
     if (MODE == 2 && a.rows_dev) r_end = min(r_end, *a.rows_dev);
@@ -157,10 +167,16 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     n_valid = a.w_rows;
   }
   const unsigned char* Hp = reinterpret_cast<const unsigned char*>(a.H) + (size_t)r0 * row_bytes;
+  const int ks = MODE == 5 ? (int)(blockIdx.x % a.ksplit) : 0;
+  if (MODE == 5) {                                   // this part's slabs start here in every row
+    Wp += (size_t)ks * a.slabs_per_part * F_SLAB;
+    Hp += (size_t)ks * a.slabs_per_part * F_SLAB;
+  }
   const int vt0 = st * a.strip;
   const int vt_end = min(min(vt0 + a.strip, a.n_vtiles), (n_valid + FT - 1) / FT);
   const int n_tiles = vt_end - vt0;          // vocabulary tiles this workgroup sweeps (may be <= 0)
-  const int n_slabs = (int)(row_bytes / F_SLAB);
+  const int n_slabs = MODE == 5 ? min(a.slabs_per_part, (int)(row_bytes / F_SLAB) - ks * a.slabs_per_part)
+                                : (int)(row_bytes / F_SLAB);
 
   Triple run[F_NJ];
 #pragma unroll
@@ -318,6 +334,9 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       const int v0 = vt * FT;
       if (MODE == 2)
         store_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      else if (MODE == 5)
+        store_partial_tile<F_NI, F_NJ>(acc, a.partial + (size_t)ks * a.rows * a.ldo, a.ldo, r0 + wr * (F_NJ * 32), r_end,
+                                       v0 + wv * 128 + half * 4, n_valid);
       else if (MODE >= 3)
         store_prob_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
       else
@@ -366,7 +385,9 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 4)
+  if (mode == 5)
+    hipLaunchKernelGGL(logits_fast_kernel<5>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 4)
     hipLaunchKernelGGL(logits_fast_kernel<4>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 3)
     hipLaunchKernelGGL(logits_fast_kernel<3>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -391,6 +412,8 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<5>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

@@ -53,6 +53,7 @@ def _setup(cfg, lens):
     (1, 900, 3000, 1024, 3, 600, 1, 8, 1024, False, True),     # rows spanning several 256-row tiles
     (2, 150, 400, 256, 3, 64, 2, 4, 512, False, True),         # 384 slot rows: the few-rows kernel for the layers
     (1, 100, 300, 384, 4, 20, 1, 6, 1152, False, True),        # 80 rows, K = 384 and 1152 (3 and 9 slices of 128)
+    (2, 300, 600, 1024, 3, 40, 2, 8, 2048, False, True),       # 240 rows, K = 1024 and 2048: the tile kernel with K split
 ])
 def test_hyper_encode_matches_oracle_every_entry(B, N, V, d, M, cap, n_layers, n_heads, d_ff, attn_only, with_pos):
     import torch
