@@ -332,6 +332,9 @@ int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned g
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s);
 int z2z_logits_fast_prepare(z2z_ctx* c);
+int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, z2z_logits::LogitsArgs a, const void* W, int w_rows, int col0,
+                           int part0, int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed,
+                           hipStream_t s, bool prob = false);
 // temperature sampling (one-row-per-sequence kernel only): softmax(logit / temperature), generator key and
 // counter words from seed and step
 struct z2z_sample_params {
