@@ -134,14 +134,28 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.ldo = N;
   a.rows_dev = nullptr;
   if (rows_dev && a.row_tiles >= 16) {
-    // the real row count is on the device: row tiles are dealt to the XCDs one by one (see map_rows_dev)
+    // the real row count is on the device: what an XCD owns is settled there (see map_rows_dev)
     a.rows_dev = rows_dev;
     a.map_lr = 4;
-    a.map_ls = a.n_strips >= 8 ? 8 : (a.n_strips >= 4 ? 4 : (a.n_strips >= 2 ? 2 : 1));
-    a.strip_blocks = (a.n_strips + a.map_ls - 1) / a.map_ls;
-    const int tiles_per_xcd = (a.row_tiles + 7) / 8;
-    const int row_blocks = (tiles_per_xcd + a.map_lr - 1) / a.map_lr;
-    const unsigned grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)row_blocks * (unsigned)a.strip_blocks;
+    unsigned grid;
+    if (a.n_strips % 8 == 0) {
+      // every XCD takes an eighth of the weight tiles and all row tiles
+      const int strips_per_xcd = a.n_strips / 8;
+      a.map_xs = 8;
+      a.map_xr = 1;
+      a.map_ls = strips_per_xcd >= 8 ? 8 : (strips_per_xcd >= 4 ? 4 : (strips_per_xcd >= 2 ? 2 : 1));
+      a.strip_blocks = (strips_per_xcd + a.map_ls - 1) / a.map_ls;
+      const int row_blocks = (a.row_tiles + a.map_lr - 1) / a.map_lr;
+      grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)row_blocks * (unsigned)a.strip_blocks;
+    } else {
+      a.map_xs = 1;
+      a.map_xr = 8;
+      a.map_ls = a.n_strips >= 8 ? 8 : (a.n_strips >= 4 ? 4 : (a.n_strips >= 2 ? 2 : 1));
+      a.strip_blocks = (a.n_strips + a.map_ls - 1) / a.map_ls;
+      const int tiles_per_xcd = (a.row_tiles + 7) / 8;
+      const int row_blocks = (tiles_per_xcd + a.map_lr - 1) / a.map_lr;
+      grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)row_blocks * (unsigned)a.strip_blocks;
+    }
     return z2z_launch_logits_fast(2, a, grid, s);
   }
   // (fewer row tiles than that: the tiles beyond the real rows only exit early)

@@ -99,9 +99,12 @@ __device__ __forceinline__ bool map_base(const LogitsArgs& a, int bid, int* rt, 
   return *rt < a.row_tiles && *st < a.n_strips;
 }
 
-// Linear mode when the number of rows is known on the device only: row tile t belongs to XCD t mod 8 (shares
-// differ by one tile at most, whatever the count turns out to be); inside an XCD the workgroups walk blocks of
-// map_lr of its row tiles x map_ls strips, strips outermost.  The grid is sized for the rows laid out.
+// Linear mode when the number of rows is known on the device only.  Workgroup ids go round-robin over the 8
+// XCDs; an XCD walks blocks of map_lr row tiles x map_ls weight tiles ("strips" of one tile), the weight
+// tiles of a row block before the next row block.  What an XCD owns is decided here, on the device, from the
+// row count: if the weight tiles divide evenly among the XCDs (map_xs = 8), XCD x owns the weight tiles
+// x, x + 8, ... and every row tile -- equal shares whatever the count is; otherwise row tile t belongs to XCD
+// t mod 8 (shares differ by one row tile at most).  The grid is sized for the rows laid out.
 __device__ __forceinline__ bool map_rows_dev(const LogitsArgs& a, int bid, int row_tiles_now, int* rt, int* st) {
   const int xcd = bid & 7;
   const int j = bid >> 3;
@@ -110,10 +113,15 @@ __device__ __forceinline__ bool map_rows_dev(const LogitsArgs& a, int bid, int r
   const int within = j - blk * per;
   const int lr = within % a.map_lr;
   const int ls = within / a.map_lr;
-  const int sblk = blk % a.strip_blocks;          // strip blocks innermost among blocks: an XCD's row block
-  const int rblk = blk / a.strip_blocks;          // meets all strips before the next row block starts
-  *rt = (rblk * a.map_lr + lr) * 8 + xcd;
-  *st = sblk * a.map_ls + ls;
+  const int sblk = blk % a.strip_blocks;
+  const int rblk = blk / a.strip_blocks;
+  if (a.map_xs == 8) {
+    *rt = rblk * a.map_lr + lr;
+    *st = (sblk * a.map_ls + ls) * 8 + xcd;
+  } else {
+    *rt = (rblk * a.map_lr + lr) * 8 + xcd;
+    *st = sblk * a.map_ls + ls;
+  }
   return *rt < row_tiles_now && *st < a.n_strips;
 }
 
