@@ -289,3 +289,44 @@ def test_hyper_encode_replays_in_a_graph():
             _compare(W[b, :len(entries)], want[:len(entries)], f"replay {rep}, seq {b}")
             assert (W[b, len(entries):] == 0).all()
     ctx.close()
+
+
+def test_argument_errors_of_the_newer_entry_points():
+    """Bad arguments are refused on the host, before anything is enqueued."""
+    import ctypes
+    import torch
+    from paper_2506_01084_amd import api
+
+    lib = api.load_library()
+    ctx = api.Context(B=1, V=100, M=3, cap=8, d=64, dtype="bf16")
+    ctx.reset()
+    E = torch.zeros((100, 64), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((1, 8, 64), dtype=torch.bfloat16, device="cuda")
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=1, N=8, V=100, d=64, M=3, cap=8)
+    enc = encoder_to_device(wl.make_encoder(cfg, n_layers=1, n_heads=2, d_ff=64), "bf16")
+    EINVAL = -1
+    h = ctx._h
+    # no encoder, no layers, too many layers, a missing matrix
+    assert lib.z2z_hyper_encode(h, E.data_ptr(), None, W.data_ptr(), None, 0, None) == EINVAL
+    desc = api.EncoderDesc.from_buffer_copy(enc.desc)
+    desc.n_layers = 9
+    assert lib.z2z_hyper_encode(h, E.data_ptr(), ctypes.byref(desc), W.data_ptr(), None, 0, None) == EINVAL
+    arr = (api.EncoderLayer * 1)()
+    ctypes.memmove(arr, enc._arr, ctypes.sizeof(arr))
+    arr[0].w_o = None
+    desc = api.EncoderDesc.from_buffer_copy(enc.desc)
+    desc.layers = ctypes.cast(arr, ctypes.POINTER(api.EncoderLayer))
+    assert lib.z2z_hyper_encode(h, E.data_ptr(), ctypes.byref(desc), W.data_ptr(), None, 0, None) == EINVAL
+    # backward: rows must be B * rows_per_seq; the lse of the forward pass is required
+    z = torch.zeros(8, dtype=torch.float32, device="cuda")
+    t = torch.zeros(8, dtype=torch.int32, device="cuda")
+    Hh = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    assert lib.z2z_extended_nll_backward(h, Hh.data_ptr(), 8, 3, E.data_ptr(), W.data_ptr(), t.data_ptr(), z.data_ptr(),
+                                         None, Hh.data_ptr(), E.data_ptr(), W.data_ptr(), None) == EINVAL
+    assert lib.z2z_extended_nll_backward(h, Hh.data_ptr(), 8, 8, E.data_ptr(), W.data_ptr(), t.data_ptr(), None, None,
+                                         Hh.data_ptr(), E.data_ptr(), W.data_ptr(), None) == EINVAL
+    # prefill: flags must be RESET or APPEND, outputs required
+    i32 = torch.zeros(8, dtype=torch.int32, device="cuda")
+    assert lib.z2z_codebook_prefill(h, i32.data_ptr(), i32.data_ptr(), None, 1, 7, i32.data_ptr(), i32.data_ptr(), None) == EINVAL
+    assert lib.z2z_codebook_prefill(h, i32.data_ptr(), i32.data_ptr(), None, 1, api.RESET, None, i32.data_ptr(), None) == EINVAL
+    ctx.close()
