@@ -48,13 +48,38 @@ def test_binding_constants_match_header():
     assert api.APPEND == enum_value("Z2Z_APPEND") and api.RESET == enum_value("Z2Z_RESET")
     assert api.ST_BAD_TOKEN == enum_value("Z2Z_ST_BAD_TOKEN") and api.ST_BAD_CODE == enum_value("Z2Z_ST_BAD_CODE")
     assert api.ST_OVERFLOW == enum_value("Z2Z_ST_OVERFLOW")
-    for k in ("LOGITS_KERNEL", "LOGITS_STRIP", "LZW_KERNEL", "DECODE_KERNEL", "TIMING", "LOGITS_MAP"):
+    for k in ("LOGITS_KERNEL", "LOGITS_STRIP", "LZW_KERNEL", "DECODE_KERNEL", "TIMING", "LOGITS_MAP", "SAMPLE_KERNEL"):
         assert getattr(api, "OPT_" + k) == enum_value("Z2Z_OPT_" + k)
     assert api.MAX_M == int(re.search(r"#define\s+Z2Z_MAX_M\s+(\d+)", text).group(1))
     # the config struct mirrors the header field for field
     fields = [f[0] for f in api.Config._fields_]
     assert fields == ["B", "V", "M", "cap", "d", "dtype", "pool", "w"]
     assert ctypes.sizeof(api.Config) == 7 * 4 + 4 * api.MAX_M
+    # the encoder structs: field names and order as in the header
+    body = re.search(r"typedef struct z2z_encoder_layer \{(.*?)\} z2z_encoder_layer;", text, re.S).group(1)
+    names = re.findall(r"\*\s*(\w+);", body)
+    assert names == [f[0] for f in api.EncoderLayer._fields_]
+    body = re.search(r"typedef struct z2z_encoder \{(.*?)\} z2z_encoder;", text, re.S).group(1)
+    names = re.findall(r"(\w+);", body)
+    assert names == [f[0] for f in api.EncoderDesc._fields_]
+    assert ctypes.sizeof(api.EncoderLayer) == 12 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(api.EncoderDesc) == 4 * 4 + 2 * ctypes.sizeof(ctypes.c_void_p)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, and the structs have the binding's sizes."""
+    import subprocess
+
+    src = tmp_path / "t.c"
+    src.write_text('#include "z2z.h"\n#include <stdio.h>\nint main(void) { printf("%zu %zu %zu\\n", sizeof(z2z_config), '
+                   'sizeof(z2z_encoder_layer), sizeof(z2z_encoder)); return 0; }\n')
+    exe = tmp_path / "t"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.dirname(HEADER), str(src), "-o",
+                    str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    from paper_2506_01084_amd import api
+
+    assert [int(x) for x in out] == [ctypes.sizeof(api.Config), ctypes.sizeof(api.EncoderLayer), ctypes.sizeof(api.EncoderDesc)]
 
 
 def test_product_path_does_not_import_the_oracle():
