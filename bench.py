@@ -146,6 +146,10 @@ def run_prefill_workload(args, torch, api, wl):
     assert torch.equal(d_back, d_tok), "lzw_decode(lzw_encode(x)) != x"
     sizes = size_view.cpu().numpy()
     ncodes = d_ncodes.cpu().numpy()
+    # how many of the entries the code stream ever names (the paper's discussion: about a quarter on its data)
+    d_usage = torch.zeros((B, cap), **i32)
+    ctx.codebook_usage(d_codes, d_ncodes, d_usage)
+    reused = float((d_usage > 0).sum().item()) / max(1.0, float(sizes.sum()))
 
     ms_per_step = dt * 1e3 / args.steps
     stage_ms = {n: stages[n].total_ms() / args.steps for n in names}
@@ -153,7 +157,7 @@ def run_prefill_workload(args, torch, api, wl):
     flops_all = 2.0 * rows * d * (V + float(sizes.mean()))
     out = dict(ms_per_step=ms_per_step, stage_ms=stage_ms, kernel_ms_total=kernel_ms, kernel_launches=launches,
                flops_base=flops_base, flops_all=flops_all, sizes=sizes.tolist(), n_codes=ncodes.tolist(),
-               tokens=B * N, cfg=cfg)
+               tokens=B * N, cfg=cfg, entries_reused_frac=reused)
     host = dict(tokens=tokens, E=E, H=H)
     ctx.close()
     return out, host
@@ -511,6 +515,7 @@ def main():
             "stage_ms": st,
             "mean_codebook_size": sum(res["sizes"]) / len(res["sizes"]),
             "compression_rate": sum(res["n_codes"]) / res["tokens"],
+            "entries_reused_frac": res["entries_reused_frac"],
         },
         "roofline": {"bound": "mfma", "kernel": "logits_fast_kernel<0> (base-vocabulary part of the prefill extended_logits call)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

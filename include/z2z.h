@@ -128,6 +128,23 @@ int z2z_codebook_prefill(z2z_ctx* ctx, const int32_t* d_phrases, const int32_t* 
                          const int32_t* d_counts, int32_t n_max, int32_t flags, int32_t* d_n_added,
                          int32_t* d_status, void* stream);
 
+/* Entry usage: d_usage[b, e] += the number of codes of sequence b's stream that name entry e (the statistic
+ * behind the paper's remark that only about a quarter of the hypertokens are reused; what a retention policy
+ * looks at).  d_codes [B, stride], d_n_codes [B] or NULL, d_usage [B, cap] int32, accumulated (zero it first). */
+int z2z_codebook_usage(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_codes, int32_t stride,
+                       int32_t* d_usage, void* stream);
+
+/* Pruning / selective retention (the paper's discussion, "Codebook Management Strategy", item 1; the idea is
+ * named, no rule is given).  The operation here: entry e of sequence b stays iff d_keep[b, e] != 0 and its
+ * prefix without the last token is a base token or an entry that stays (the codebook remains prefix-closed:
+ * dropping an entry drops its extensions).  The survivors keep their order and are renumbered from V; no phrase
+ * is pending afterwards.  Codes emitted before the call name the old numbering: d_new_id maps them.  Both sides
+ * of a round trip must prune alike, and the hyper-embedding cache has to be rebuilt (z2z_hyper_embed).
+ *   d_keep   [B, cap] int32 (entries at and beyond C_b are ignored)
+ *   d_new_id [B, cap] int32 out: new entry index of old entry e, -1 = dropped (entries beyond C_b: untouched)
+ *   d_n_kept [B] int32 out: the new C_b */
+int z2z_codebook_prune(z2z_ctx* ctx, const int32_t* d_keep, int32_t* d_new_id, int32_t* d_n_kept, void* stream);
+
 /* hyper_embed.  W_hyper[b, e, :] = sum_j a_j * E[t_j, :] over the L tokens of entry e of sequence b,
  * a_j = 1/L (MEAN) or softmax(w[0..L))_j (WEIGHTED); padding slots contribute nothing and are not
  * in the divisor.  fp32 accumulation in token order, one round-to-nearest-even to the storage type.

@@ -23,7 +23,7 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
-EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill",
+EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
            "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
     lib.z2z_codebook_prefill.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
                                          c_void_p]
+    lib.z2z_codebook_usage.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+    lib.z2z_codebook_prune.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_hyper_encode.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
@@ -208,6 +210,16 @@ class Context:
                                               _ptr(counts, torch.int32), phrases.shape[1], flags,
                                               _ptr(n_added, torch.int32), _ptr(status, torch.int32), _stream()),
                "z2z_codebook_prefill")
+
+    def codebook_usage(self, codes: torch.Tensor, n_codes: Optional[torch.Tensor], usage: torch.Tensor) -> None:
+        assert codes.dim() == 2 and codes.shape[0] == self.B and tuple(usage.shape) == (self.B, self.cap)
+        _check(self._lib.z2z_codebook_usage(self._h, _ptr(codes, torch.int32), _ptr(n_codes, torch.int32),
+                                            codes.shape[1], _ptr(usage, torch.int32), _stream()), "z2z_codebook_usage")
+
+    def codebook_prune(self, keep: torch.Tensor, new_id: torch.Tensor, n_kept: torch.Tensor) -> None:
+        assert tuple(keep.shape) == (self.B, self.cap) and tuple(new_id.shape) == (self.B, self.cap)
+        _check(self._lib.z2z_codebook_prune(self._h, _ptr(keep, torch.int32), _ptr(new_id, torch.int32),
+                                            _ptr(n_kept, torch.int32), _stream()), "z2z_codebook_prune")
 
     def codebook_ptrs(self):
         e, l, s = c_void_p(), c_void_p(), c_void_p()

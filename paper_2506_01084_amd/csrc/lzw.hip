@@ -15,6 +15,8 @@
 // wave-uniform (ballots, scalar registers).
 #include "z2z_internal.h"
 
+#include <string.h>
+
 namespace {
 
 constexpr int kWave = 64;
@@ -891,6 +893,88 @@ void plan(const z2z_ctx* c, int32_t stride, int32_t flags, bool decode, bool* ld
   }
 }
 
+// How often each entry is named by a code stream: usage[b][e] += number of codes equal to V + e (codes of base
+// tokens and codes that name no entry are skipped).  One workgroup per sequence.
+__global__ void __launch_bounds__(256) lzw_usage_kernel(LzwState st, const int32_t* codes, const int32_t* n_codes,
+                                                        int stride, int32_t* usage) {
+  const int b = blockIdx.x;
+  const int n = n_codes ? min(max(n_codes[b], 0), stride) : stride;
+  const int C = min(max(st.size[b], 0), st.cap);
+  for (int i = threadIdx.x; i < n; i += 256) {
+    const int e = codes[(size_t)b * stride + i] - st.V;
+    if (e >= 0 && e < C) atomicAdd(&usage[(size_t)b * st.cap + e], 1);
+  }
+}
+
+// Pruning / selective retention (zip2zip paper, discussion, "Codebook Management Strategy", item 1): entry e
+// stays iff keep[e] != 0 and its prefix without the last token is a base token or an entry that stays; the
+// survivors keep their order and are renumbered.  One wave per sequence, wave-uniform, in two sweeps over the
+// entries in creation order (a prefix is always older than its extensions): the first walks the trie as it
+// is to find every entry's prefix and decides who stays (new_id: new index or -1; prefix: scratch); the
+// second empties the table, moves the survivors' rows down and inserts their edges under the new numbers.
+__global__ void __launch_bounds__(kWave) lzw_prune_kernel(LzwArgs a, const int32_t* keep, int32_t* new_id, int32_t* prefix) {
+  const LzwState& st = a.st;
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int V = st.V, M = st.M, cap = st.cap;
+  const int C = min(max(__builtin_amdgcn_readfirstlane(st.size[b]), 0), cap);
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
+  const int32_t* kp = keep + (size_t)b * cap;
+  int32_t* nid = new_id + (size_t)b * cap;
+  int32_t* pre = prefix + (size_t)b * cap;
+  Table<false> t;
+  table_open<false>(a, b, lane, false, &t);
+  int kept = 0;
+  for (int e = 0; e < C; ++e) {
+    const int L = min(max(__builtin_amdgcn_readfirstlane(ent_len[e]), 2), M);
+    const int32_t tok = lane < L ? ent_tokens[(size_t)e * M + lane] : 0;
+    int32_t code = __builtin_amdgcn_readlane(tok, 0);
+    for (int j = 1; j < L - 1; ++j) {
+      int fp;
+      code = V + t.find(code, __builtin_amdgcn_readlane(tok, j), &fp);     // exists: the codebook is prefix-closed
+    }
+    const int p = L == 2 ? -1 : code - V;
+    // (read past the vector L1: the line may have been cached before lane 0 wrote this element)
+    const int pn = p < 0 ? 0 : __builtin_amdgcn_readfirstlane(__hip_atomic_load(&nid[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const bool stays = __builtin_amdgcn_readfirstlane(kp[e]) != 0 && pn >= 0;
+    if (lane == 0) {
+      nid[e] = stays ? kept : -1;
+      pre[e] = p;
+    }
+    kept += stays ? 1 : 0;
+    __syncthreads();                                 // nid[e] is read by the entries that extend e
+  }
+  for (int i = lane; i < st.nslots; i += kWave) t.g[i] = kEmpty;
+  __syncthreads();
+  for (int e = 0; e < C; ++e) {
+    const int n = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&nid[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (n < 0) continue;
+    const int L = min(max(__builtin_amdgcn_readfirstlane(ent_len[e]), 2), M);
+    const int32_t tok = lane < M ? ent_tokens[(size_t)e * M + lane] : -1;
+    const int p = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&pre[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const int32_t parent = p < 0 ? __builtin_amdgcn_readlane(tok, 0)
+                                 : V + __builtin_amdgcn_readfirstlane(__hip_atomic_load(&nid[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    int free_pos = -1;
+    t.find(parent, __builtin_amdgcn_readlane(tok, L - 1), &free_pos);
+    __syncthreads();                                 // row e is read before row n <= e is overwritten
+    if (lane == 0) {
+      t.store((uint32_t)free_pos, edge_bits(parent, __builtin_amdgcn_readlane(tok, L - 1)) | (u64)(uint32_t)n);
+      ent_len[n] = L;
+    }
+    if (lane < M) ent_tokens[(size_t)n * M + lane] = tok;
+    __syncthreads();
+  }
+  for (int e = kept + lane; e < C; e += kWave) ent_len[e] = 0;            // the rows above the survivors are unused again
+  for (int i = kept * M + lane; i < C * M; i += kWave) ent_tokens[i] = -1;
+  if (lane == 0) {
+    st.size[b] = kept;
+    st.prev_code[b] = -1;
+    st.prev_len[b] = 0;
+    a.out_n[b] = kept;
+  }
+}
+
 // Codebook prefilling: the given phrases become entries, in order, before any input is parsed (zip2zip
 // paper, discussion, "Codebook Management Strategy", item 2).  A phrase is taken if it keeps the codebook what
 // the parse kernels rely on: 2..M tokens, all in [0, V), its prefix without the last token a base token or an
@@ -958,6 +1042,27 @@ __global__ void __launch_bounds__(kWave) lzw_prefill_kernel(LzwArgs a) {
 
 int z2z_launch_lzw_reset(z2z_ctx* c, hipStream_t s) {
   hipLaunchKernelGGL(lzw_reset_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_launch_codebook_usage(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t* usage,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(lzw_usage_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st, codes, n_codes, stride, usage);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_launch_codebook_prune(z2z_ctx* c, const int32_t* keep, int32_t* new_id, int32_t* n_kept, hipStream_t s) {
+  if (!c->prune_prefix && c->cfg.cap > 0) {
+    if (hipMalloc(&c->prune_prefix, (size_t)c->cfg.B * c->cfg.cap * sizeof(int32_t)) != hipSuccess) return Z2Z_ENOMEM;
+  }
+  LzwArgs a;
+  memset(&a, 0, sizeof(a));
+  a.st = c->st;
+  a.out_n = n_kept;
+  hipLaunchKernelGGL(lzw_prune_kernel, dim3(c->cfg.B), dim3(kWave), 0, s, a, keep, new_id,
+                     reinterpret_cast<int32_t*>(c->prune_prefix));
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

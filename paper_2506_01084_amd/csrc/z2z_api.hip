@@ -30,6 +30,7 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->enc_ws);
   (void)hipFree(c->bwd_ws);
   (void)hipFree(c->coef_dev);
+  (void)hipFree(c->prune_prefix);
   (void)hipFree(c->skinny_partial);
   if (c->ev_created) {
     for (int i = 0; i < Z2Z_MAX_TIMED; ++i) {
@@ -157,6 +158,21 @@ Z2Z_API int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t*
   if (d_entry_len) *d_entry_len = ctx->st.ent_len;
   if (d_size) *d_size = ctx->st.size;
   return Z2Z_OK;
+}
+
+Z2Z_API int z2z_codebook_usage(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_codes, int32_t stride,
+                               int32_t* d_usage, void* stream) {
+  if (!ctx || stride < 0 || (stride > 0 && !d_codes)) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_usage) return Z2Z_EINVAL;
+  if (ctx->cfg.cap == 0 || stride == 0) return Z2Z_OK;
+  return z2z_launch_codebook_usage(ctx, d_codes, d_n_codes, stride, d_usage, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_codebook_prune(z2z_ctx* ctx, const int32_t* d_keep, int32_t* d_new_id, int32_t* d_n_kept,
+                               void* stream) {
+  if (!ctx || !d_n_kept) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && (!d_keep || !d_new_id)) return Z2Z_EINVAL;
+  return z2z_launch_codebook_prune(ctx, d_keep, d_new_id, d_n_kept, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_codebook_prefill(z2z_ctx* ctx, const int32_t* d_phrases, const int32_t* d_phrase_len,

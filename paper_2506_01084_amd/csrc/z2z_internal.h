@@ -55,6 +55,7 @@ struct z2z_ctx {
   // backward pass of the loss: dZ, the transposed operand copies (bf16), the row gradients
   void* bwd_ws;
   size_t bwd_ws_bytes;
+  void* prune_prefix;      // codebook pruning: every entry's prefix entry (scratch, [B, cap] int32)
   void* coef_dev;          // the pooling coefficients on the device (pooling backward)
   // dense layers on few rows with K split over workgroups: the partial tiles
   void* skinny_partial;
@@ -79,6 +80,9 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
                           int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s);
 int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t flags,
                           int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s);
+int z2z_launch_codebook_usage(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t* usage,
+                              hipStream_t s);
+int z2z_launch_codebook_prune(z2z_ctx* c, const int32_t* keep, int32_t* new_id, int32_t* n_kept, hipStream_t s);
 int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_t* phrase_len, const int32_t* counts,
                                 int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s);
 int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32_t* first, int32_t max_new,

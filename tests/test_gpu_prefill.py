@@ -110,3 +110,61 @@ def test_prefill_statuses_and_append():
         assert (added[b], status[b]) == (a, st), b
     assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
     ctx.close()
+
+
+@pytest.mark.parametrize("B,N,V,M,cap", [(5, 500, 40, 3, 200), (3, 1200, 300, 5, 150), (130, 150, 20, 4, 64)])
+def test_usage_and_prune_match_oracle_and_the_parse_goes_on(B, N, V, M, cap):
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, M=M, cap=cap, d=64, zipf_s=1.1, seed=3 * B + V)
+    print(f"[case] prune B={B} N={N} V={V} M={M} cap={cap}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg, ragged=True)
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=64, dtype="bf16")
+    codes, n_codes, st = gpu_encode(ctx, tokens, lens)
+    streams = [LZWStream(V, M, cap) for _ in range(B)]
+    ref_codes = [streams[b].encode_chunk(tokens[b, :lens[b]].tolist())[0] for b in range(B)]
+    # usage
+    usage = torch.zeros((B, cap), dtype=torch.int32, device="cuda")
+    ctx.codebook_usage(torch.from_numpy(codes).cuda(), torch.from_numpy(n_codes).cuda(), usage)
+    torch.cuda.synchronize()
+    use_h = usage.cpu().numpy()
+    rng = np.random.default_rng(5)
+    keep = np.zeros((B, cap), dtype=np.int32)
+    for b in range(B):
+        want = streams[b].usage(ref_codes[b])
+        assert use_h[b, :len(want)].tolist() == want and (use_h[b, len(want):] == 0).all(), f"usage seq {b}"
+        # retention policy of the test: entries that were used, plus a random few
+        keep[b, :len(want)] = (np.array(want) > 0) | (rng.random(len(want)) < 0.2) if want else 0
+    keep[0] = 1                                            # one sequence keeps everything
+    if B > 1:
+        keep[1] = 0                                        # one keeps nothing
+    # prune
+    new_id = torch.full((B, cap), -9, dtype=torch.int32, device="cuda")
+    n_kept = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    ctx.codebook_prune(torch.from_numpy(keep).cuda(), new_id, n_kept)
+    torch.cuda.synchronize()
+    nid_h, nk_h = new_id.cpu().numpy(), n_kept.cpu().numpy()
+    for b in range(B):
+        C_old = len(streams[b].entries)
+        want_map = streams[b].prune(keep[b, :C_old].tolist())
+        assert nid_h[b, :C_old].tolist() == want_map and (nid_h[b, C_old:] == -9).all(), f"map seq {b}"
+        assert nk_h[b] == len(streams[b].entries)
+    assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+    # the parse goes on from the pruned codebooks, and a decoder that holds the same codebooks follows it
+    more = wl.make_tokens(wl.scaled(cfg, seed=cfg["seed"] + 1))
+    codes2, n2, st2 = gpu_encode(ctx, more, lens, flags=api.APPEND)
+    kept_entries = [list(s.entries) for s in streams]
+    for b in range(B):
+        c, s_ = streams[b].encode_chunk(more[b, :lens[b]].tolist())
+        assert st2[b] == s_ and codes2[b, :n2[b]].tolist() == c, f"parse after prune, seq {b}"
+    assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+    from test_gpu_prefill import _prefill as prefill    # the decoder side: prefill the survivors, then decode
+    n_max = max(len(k) for k in kept_entries) + 1
+    added, status = prefill(ctx, kept_entries, n_max, M, api.RESET)
+    assert (status == 0).all()
+    toks, n_tok, st3 = gpu_decode(ctx, codes2, n2, out_stride=N, flags=api.APPEND)
+    for b in range(B):
+        assert st3[b] == 0 and n_tok[b] == lens[b] and (toks[b, :lens[b]] == more[b, :lens[b]]).all(), f"round trip seq {b}"
+    ctx.close()

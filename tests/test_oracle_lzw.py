@@ -423,3 +423,55 @@ def test_prefill_rejects_what_would_break_the_codebook():
     s.prefill([(3, 4)])
     s.encode_chunk([0])
     assert s.entries == [(1, 2), (3, 4)]
+
+
+# ---------------------------------------------------------------------------
+# pruning / selective retention (discussion section, "Codebook Management Strategy", item 1)
+# ---------------------------------------------------------------------------
+def test_prune_equals_prefill_of_the_survivors_and_round_trips():
+    rnd = random.Random(12)
+    for trial in range(300):
+        V = rnd.choice([2, 3, 5])
+        M, cap = rnd.choice([2, 3, 4]), rnd.choice([4, 10, 40])
+        warm = [rnd.randrange(V) for _ in range(rnd.randint(0, 60))]
+        s = LZWStream(V, M, cap)
+        codes, _ = s.encode_chunk(warm)
+        old = list(s.entries)
+        use = s.usage(codes)
+        assert sum(use) == sum(1 for c in codes if c >= V) and len(use) == len(old)
+        keep = [rnd.random() < 0.6 for _ in old]
+        new_index = s.prune(keep)
+        # survivors: flagged, and so is every prefix (computed here from the definition, by fixed point)
+        alive = set(i for i, k in enumerate(keep) if k)
+        changed = True
+        while changed:
+            changed = False
+            for i in list(alive):
+                e = old[i]
+                if len(e) > 2 and old.index(e[:-1]) not in alive:
+                    alive.discard(i)
+                    changed = True
+        want = [e for i, e in enumerate(old) if i in alive]
+        assert s.entries == want
+        assert [i for i, n in enumerate(new_index) if n >= 0] == sorted(alive)
+        assert [n for n in new_index if n >= 0] == list(range(len(want)))
+        # the pruned codebook is the one a fresh stream gets by prefilling the survivors
+        f = LZWStream(V, M, cap)
+        assert f.prefill(want) == (len(want), ST_OK) and f.entries == s.entries and f.book == s.book
+        # and the parse goes on from it, decodable by a decoder that pruned alike
+        x = [rnd.randrange(V) for _ in range(rnd.randint(0, 50))]
+        c2, st = s.encode_chunk(x)
+        d = LZWStream(V, M, cap)
+        d.prefill(want)
+        toks, st2 = d.decode_chunk(c2)
+        assert st == ST_OK and st2 == ST_OK and toks == x and d.entries == s.entries
+    # keep everything: nothing changes; keep nothing: empty
+    s = LZWStream(3, 3, 20)
+    s.encode_chunk([0, 1, 0, 1, 0, 1, 2, 2, 2, 2])
+    e = list(s.entries)
+    assert s.prune([True] * len(e)) == list(range(len(e))) and s.entries == e
+    assert s.prune([False] * len(e)) == [-1] * len(e) and s.entries == [] and s.book == {}
+    # dropping (0, 1) drops its extension (0, 1, 0) although that one is flagged
+    s = LZWStream(3, 3, 20)
+    s.prefill([(0, 1), (0, 1, 0), (1, 1)])
+    assert s.prune([False, True, True]) == [-1, -1, 0] and s.entries == [(1, 1)]
