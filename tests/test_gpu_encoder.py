@@ -1,13 +1,15 @@
 """GPU parity: hyper_encode (the learned hyper-encoder of section 2.2: attention / transformer layers over an
 entry's padded slots, mean of the real slots) through the C ABI against the float64 oracle.
 
-Bar.  The HIP path keeps activations in bf16 between the steps of a layer (LayerNorm output, q|k|v, attention
-output, the residual stream after each block, the GELU output) and accumulates in fp32; the oracle computes in
-float64 from the same stored parameters and rounds once.  Each rounding is a relative 2^-9 of the rounded
-value; with random-init parameters of the scale used here (activations of order 1 entering every product, the
-residual stream of order 1) a layer adds about six such roundings that reach the output with weight of order
-1, so the tolerance is 2e-2 * max(1, largest |h| of the row) per element for up to two transformer layers,
-and the mean absolute error per row has to stay below a quarter of that.
+Bar.  The HIP path keeps activations in bf16 between the steps of a layer (the slot inputs, LayerNorm outputs,
+q|k|v, attention output, the residual stream after each block, the GELU output) and accumulates in fp32; the
+oracle computes in float64 from the same stored parameters and rounds once.  Each rounding is a relative 2^-9 of
+the rounded value; with random-init parameters of the scale used here every product maps order-1 activations to
+order-1 activations, so each of the 6 L + 1 roundings of an L-layer encoder reaches the output with weight of
+order 1.  If they all pushed the same way that would be 13 * 2^-9 = 2.5e-2 for two layers; the tolerance is
+3e-2 * max(1, largest |h| of the row) per element, and a row's mean error has to stay below a quarter of that
+(errors of independent roundings add in quadrature: typical worst elements are near 1e-2; the largest seen over
+2600 random shapes and modes was 2.04e-2, at d = 64 with two layers).
 """
 import numpy as np
 import pytest
@@ -19,7 +21,7 @@ from helpers import encoder_to_device, gpu_encode, oracle_encode_batch, storage_
 
 pytestmark = pytest.mark.gpu
 
-TOL = 2e-2
+TOL = 3e-2
 
 
 def _compare(got_bits, ref64, label):
