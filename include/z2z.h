@@ -288,7 +288,8 @@ int z2z_hyper_embed_backward(z2z_ctx* ctx, const void* d_dW_hyper, float* d_dE, 
 enum {
   Z2Z_OPT_LOGITS_KERNEL = 1,   /* 0 = automatic, >0 = force a variant (see the implementation notes) */
   Z2Z_OPT_LOGITS_STRIP = 2,    /* vocabulary tiles swept per workgroup, 0 = automatic               */
-  Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant                               */
+  Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant (2: table in global memory, 3: one
+                                  code per step in the decoder, 4: one wave per sequence in the encoder) */
   Z2Z_OPT_DECODE_KERNEL = 4,   /* 0 = automatic, >0 = force a variant                               */
   Z2Z_OPT_LOGITS_MAP = 6,      /* workgroup -> tile order of the bf16 MFMA kernel's base part, packed
                                   lr | ls << 8 | xr << 16 | xs << 24: each of the 8 XCDs walks blocks of

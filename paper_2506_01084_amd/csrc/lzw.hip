@@ -459,6 +459,299 @@ __global__ void __launch_bounds__(kWave) lzw_encode_kernel(LzwArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// encode, four waves per sequence
+//
+// With few sequences in a call the machine is nearly empty and a sequence's parse time is what counts: the
+// same rounds, 256 positions wide.  Each of the four waves takes a window of 64 positions and does steps 1
+// and 2 of the round on it, now keeping for every lane also where its chain leaves the window (the offset at
+// which it enters the next one, or "it ends here").  The per-lane (visited set, exit) pairs go to LDS; after a
+// barrier every wave walks the four windows from position 0 (four dependent LDS reads) and knows the phrase
+// starts of the whole round.  Limits, proposal ranks and the publishing of codes are the same with prefix
+// counts over the waves' ballots (exchanged through LDS), the repeat filter is one LDS hash set for all 256
+// positions (insert, barrier, look up, barrier; the first repeat by an LDS atomic minimum), and the table
+// insertions of a round are visible to the next round's chains after the round's last barrier.
+// ------------------------------------------------------------------------------------------------
+constexpr int kWide = 4;
+constexpr int kWideLanes = kWide * kWave;
+constexpr int kWideFilter = 2048;             // slots of the repeat filter (<= 64 * kWide keys)
+struct WideShared {
+  u64 sets[kWide][kWave];
+  int32_t exits[kWide][kWave];
+  u64 cand_mask[kWide], valid_mask[kWide], ins_mask[kWide];
+  int32_t bad_pos[kWide], ovf_pos[kWide], last_code[kWide], last_len[kWide];
+  int32_t cut;
+};
+constexpr int kWideStaticLds = kTokBuf * 4 + kWideFilter * 8 + (int)sizeof(WideShared) + 512;   // + alignment slack
+
+template <bool LDS>
+__global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) {
+  __shared__ int32_t tokbuf[kTokBuf];
+  __shared__ u64 filter[kWideFilter];
+  __shared__ WideShared sh;
+  const LzwState& st = a.st;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int V = st.V, M = st.M, cap = st.cap;
+  const bool reset = (a.flags & Z2Z_RESET) != 0;
+
+  int C = reset ? 0 : __builtin_amdgcn_readfirstlane(st.size[b]);
+  int prev = reset ? -1 : __builtin_amdgcn_readfirstlane(st.prev_code[b]);
+  int prev_len = reset ? 0 : __builtin_amdgcn_readfirstlane(st.prev_len[b]);
+
+  Table<LDS> t;
+  t.g = st.slots + (size_t)b * st.nslots;
+  t.n = (uint32_t)st.nslots;
+  if (LDS) {
+    for (int i = tid; i < st.nslots; i += kWideLanes) lds_slots[i] = reset ? kEmpty : t.g[i];
+  } else if (reset) {
+    for (int i = tid; i < st.nslots; i += kWideLanes) t.g[i] = kEmpty;
+  }
+  for (int i = tid; i < kWideFilter; i += kWideLanes) filter[i] = kEmpty;
+  if (tid == 0) sh.cut = kWideLanes;
+  __syncthreads();
+
+  const int n = call_length(a, b);
+  const int32_t* in = a.in + (size_t)b * a.stride;
+  int32_t* out = a.out + (size_t)b * a.out_stride;
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
+
+  int status = 0;
+  int n_out = 0;
+
+  // an appended call: the entry "last emitted phrase + first token of this call" (see lzw_encode_rounds)
+  if (n > 0 && prev >= 0 && prev_len < M && C < cap) {
+    const int32_t c = __builtin_amdgcn_readfirstlane(in[0]);
+    if (c >= 0 && c < V) {
+      int free_pos = -1;
+      const int idx = t.find(prev, c, &free_pos);              // every wave finds the same
+      if (idx < 0 && free_pos >= 0) {
+        if (w == 0) {
+          int32_t ph = -1;
+          if (prev < V) {
+            ph = lane == 0 ? prev : -1;
+          } else if (lane < M) {
+            ph = ent_tokens[(size_t)(prev - V) * M + lane];
+          }
+          table_insert<LDS>(a, b, lane, t, free_pos, C, prev, c, ph, prev_len);
+        }
+        ++C;
+      }
+    }
+    __syncthreads();
+  }
+
+  const u64 lanes_below = (1ull << lane) - 1;
+  const int gpos = w * kWave + lane;      // position of this thread in the round
+  int cbase = 0;
+  bool filled = false;
+  bool stop = false;
+  int pos = 0;
+  while (pos < n && !stop) {
+    if (!filled || (pos + kWideLanes + M > cbase + kTokBuf && cbase + kTokBuf < n)) {
+      cbase = pos;
+      filled = true;
+      const int cnt = min(kTokBuf, n - cbase);
+      for (int i = tid; i < cnt; i += kWideLanes) {
+        const int32_t v = in[cbase + i];
+        tokbuf[i] = (v >= 0 && v < V) ? v : -2;
+      }
+      __syncthreads();
+    }
+    const int rel = pos - cbase + gpos;
+    auto tk = [&](int d) -> int32_t { return pos + gpos + d < n ? tokbuf[rel + d] : -1; };
+
+    // ---- 1. chains against the table of the round's start ---------------------------------------
+    const int32_t tok0 = tk(0);
+    int L0 = tok0 >= 0 ? 1 : 0;
+    int32_t cfin = tok0;
+    int32_t nxt = tk(1);
+    for (int d = 1; d < M; ++d) {
+      int idx = -1;
+      if (L0 == d && nxt >= 0) idx = t.find_lane(cfin, nxt);
+      if (__ballot(idx >= 0) == 0) break;
+      if (idx >= 0) {
+        cfin = V + idx;
+        L0 = d + 1;
+        nxt = tk(d + 1);
+      }
+    }
+
+    // ---- 2. the window's chains: visited positions and where they leave the window ----------------
+    int jump = (L0 > 0 && lane + L0 < kWave) ? lane + L0 : kWave;
+    int ex = (L0 > 0 && lane + L0 >= kWave) ? lane + L0 - kWave : -1;
+    uint32_t r_lo = lane < 32 ? 1u << lane : 0u, r_hi = lane < 32 ? 0u : 1u << (lane - 32);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+      const int src = jump & (kWave - 1);
+      const uint32_t o_lo = __shfl(r_lo, src), o_hi = __shfl(r_hi, src);
+      const int o_jump = __shfl(jump, src), o_ex = __shfl(ex, src);
+      if (jump < kWave) {
+        r_lo |= o_lo;
+        r_hi |= o_hi;
+        ex = o_ex;
+        jump = o_jump;
+      }
+    }
+    sh.sets[w][lane] = ((u64)r_hi << 32) | r_lo;
+    sh.exits[w][lane] = ex;
+    __syncthreads();
+    // the round's phrase starts: walk the windows from position 0
+    u64 S_mine = 0;
+    int starts_before = 0;                      // phrase starts in the windows before this wave's
+    {
+      int e = 0;
+      for (int ww = 0; ww < kWide; ++ww) {
+        u64 S = 0;
+        if (e >= 0) {
+          S = sh.sets[ww][e];
+          e = sh.exits[ww][e];
+        }
+        const int avail_w = min(kWave, n - pos - ww * kWave);      // positions of window ww that exist
+        if (avail_w < kWave) S = avail_w <= 0 ? 0 : (S & ((1ull << avail_w) - 1));
+        if (ww < w) starts_before += __popcll(S);
+        if (ww == w) S_mine = S;
+      }
+    }
+    const int avail = min(kWideLanes, n - pos);
+    const bool start = ((S_mine >> lane) & 1) != 0;
+    const int prank = starts_before + __popcll(S_mine & lanes_below);
+
+    // ---- 3. limits of the round, proposals -------------------------------------------------------
+    const u64 bad_mask = __ballot(start && tok0 == -2);
+    const u64 ovf_mask = __ballot(start && n_out + prank >= a.out_stride);
+    const bool cand = start && tok0 >= 0 && L0 < M && nxt >= 0;
+    const u64 cand_mask = __ballot(cand);
+    if (lane == 0) {
+      sh.bad_pos[w] = bad_mask ? w * kWave + __builtin_ctzll(bad_mask) : kWideLanes;
+      sh.ovf_pos[w] = ovf_mask ? w * kWave + __builtin_ctzll(ovf_mask) : kWideLanes;
+      sh.cand_mask[w] = cand_mask;
+    }
+    __syncthreads();
+    int bad_pos = kWideLanes, ovf_pos = kWideLanes, cand_before = 0, cand_total = 0;
+    for (int ww = 0; ww < kWide; ++ww) {
+      bad_pos = min(bad_pos, sh.bad_pos[ww]);
+      ovf_pos = min(ovf_pos, sh.ovf_pos[ww]);
+      const int cnt = __popcll(sh.cand_mask[ww]);
+      if (ww < w) cand_before += cnt;
+      cand_total += cnt;
+    }
+    const int rank = cand_before + __popcll(cand_mask & lanes_below);
+    const int room = cap - C;
+    const bool inserter = cand && rank < room;
+
+    // ---- 4. first repeat of a proposed edge (one filter for the whole round) ------------------------
+    int cut = kWideLanes;
+    if (room > 0 && cand_total >= 2) {              // uniform over the workgroup
+      const u64 key = edge_bits(cfin, nxt);
+      const uint32_t h0 = (edge_hash(cfin, nxt) >> 20) & (kWideFilter - 1);
+      int own = -1;
+      if (inserter) {
+        const u64 val = key | (u64)gpos;
+        uint32_t h = h0;
+        for (int probe = 0; probe < kWideFilter; ++probe) {
+          const u64 old = atomicCAS(&filter[h], kEmpty, val);
+          if (old == kEmpty) {
+            own = (int)h;
+            break;
+          }
+          if ((old & ~0xFFFFull) == key) {
+            atomicMin(&filter[h], val);             // same edge: keep the lowest position
+            break;
+          }
+          h = (h + 1) & (kWideFilter - 1);
+        }
+      }
+      __syncthreads();
+      int fpos = kWideLanes;
+      if (cand) {
+        uint32_t h = h0;
+        for (int probe = 0; probe < kWideFilter; ++probe) {
+          const u64 sl = filter[h];
+          if (sl == kEmpty) break;
+          if ((sl & ~0xFFFFull) == key) {
+            fpos = (int)(sl & 0xFFFFull);
+            break;
+          }
+          h = (h + 1) & (kWideFilter - 1);
+        }
+      }
+      const u64 dup_mask = __ballot(cand && fpos < gpos);
+      if (dup_mask && lane == 0) atomicMin(&sh.cut, w * kWave + __builtin_ctzll(dup_mask));
+      __syncthreads();
+      cut = sh.cut;
+      if (own >= 0) filter[own] = kEmpty;           // leave the filter empty for the next round
+    }
+
+    // ---- 5. publish ---------------------------------------------------------------------------------
+    const int limit = min(min(avail, cut), min(bad_pos, ovf_pos));
+    if (bad_pos < kWideLanes && limit == bad_pos) {
+      status |= Z2Z_ST_BAD_TOKEN;
+      stop = true;
+    } else if (ovf_pos < kWideLanes && limit == ovf_pos) {
+      status |= Z2Z_ST_OVERFLOW;
+      stop = true;
+    }
+    const bool valid = start && gpos < limit;
+    const u64 valid_mask = __ballot(valid);
+    if (valid) out[n_out + prank] = cfin;
+    const bool ins = valid && inserter;
+    if (ins) {
+      const int idx = C + rank;
+      t.insert_lane(cfin, nxt, idx);
+      int32_t* row = ent_tokens + (size_t)idx * M;
+      for (int k = 0; k < M; ++k) row[k] = k <= L0 ? tokbuf[rel + k] : -1;
+      ent_len[idx] = L0 + 1;
+    }
+    const u64 ins_mask = __ballot(ins);
+    if (valid_mask) {
+      const int last = 63 - __builtin_clzll(valid_mask);
+      const int lc = __builtin_amdgcn_readlane(cfin, last), ll = __builtin_amdgcn_readlane(L0, last);
+      if (lane == 0) {
+        sh.last_code[w] = lc;
+        sh.last_len[w] = ll;
+      }
+    }
+    if (lane == 0) {
+      sh.valid_mask[w] = valid_mask;
+      sh.ins_mask[w] = ins_mask;
+    }
+    __syncthreads();
+    if (tid == 0) sh.cut = kWideLanes;              // everybody has read it; next written after two more barriers
+    int last_w = -1;
+    for (int ww = 0; ww < kWide; ++ww) {
+      const u64 vm = sh.valid_mask[ww];
+      C += __popcll(sh.ins_mask[ww]);
+      n_out += __popcll(vm);
+      if (vm) last_w = ww;
+    }
+    if (last_w >= 0) {
+      const int last = 63 - __builtin_clzll(sh.valid_mask[last_w]);
+      prev = sh.last_code[last_w];
+      prev_len = sh.last_len[last_w];
+      pos += last_w * kWave + last + prev_len;
+    } else {
+      stop = true;
+    }
+    __syncthreads();                                // the exchange arrays are free for the next round
+  }
+
+  if (LDS) {
+    __syncthreads();
+    for (int i = tid; i < st.nslots; i += kWideLanes) t.g[i] = lds_slots[i];
+  }
+  if (tid == 0) {
+    st.size[b] = C;
+    st.prev_code[b] = prev;
+    st.prev_len[b] = prev_len;
+    a.out_n[b] = n_out;
+    a.status[b] = status;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // decode
 // ------------------------------------------------------------------------------------------------
 // (length, first token) of an entry packed in 32 bits: length in the top 4 bits.
@@ -1102,7 +1395,14 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
   bool lds = false;
   plan(c, stride, flags, false, &lds, &a, &smem);
   if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
-  if (lds)
+  // few long sequences: four waves per sequence (the machine is nearly empty, a sequence's parse time counts)
+  const bool wide = c->cfg.B <= 64 && stride >= 512 && c->opt_lzw_kernel != 4 &&
+                    (!lds || smem + kWideStaticLds <= (size_t)c->lds_limit);
+  if (wide && lds)
+    hipLaunchKernelGGL(lzw_encode_wide_kernel<true>, dim3(c->cfg.B), dim3(kWideLanes), smem, s, a);
+  else if (wide)
+    hipLaunchKernelGGL(lzw_encode_wide_kernel<false>, dim3(c->cfg.B), dim3(kWideLanes), 0, s, a);
+  else if (lds)
     hipLaunchKernelGGL(lzw_encode_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
   else
     hipLaunchKernelGGL(lzw_encode_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
@@ -1167,6 +1467,8 @@ int z2z_lzw_prepare(z2z_ctx* c) {
   st.nslots &= ~1;                                     // even: probe sequences start on slot pairs
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_wide_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kWideStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_serial_kernel<true>),

@@ -347,3 +347,68 @@ def test_repeatable_across_runs_and_sequence_order():
     for i, b in enumerate(perm):
         assert (c3[i, : n3[i]] == c1[b, : n1[b]]).all()
     ctx.close()
+
+
+@pytest.mark.parametrize("narrow_only", [0, 4])      # 0: four waves per sequence for long calls; 4: one wave always
+def test_long_calls_errors_appends_and_repeats_both_encoders(narrow_only):
+    """Calls of 512 tokens and more with few sequences take the encoder with four waves per sequence (rounds of
+    256 positions); everything a round can meet, against the oracle, for both encoders: an out-of-range token in
+    any of the four windows, an output row that ends in any window, long appended chunks, streams that repeat
+    their proposals (runs, short periods: rounds cut at the first repeat), the merge limit M = 8, a codebook
+    that fills in the middle of a round."""
+    from paper_2506_01084_amd import api
+
+    rng = np.random.default_rng(17)
+    V, M, cap = 40, 4, 300
+    B, N = 6, 1500
+    tokens = rng.integers(0, 7, size=(B, N)).astype(np.int32)
+    for b, at in enumerate((3, 70, 130, 200, 700, 1499)):         # windows 0..3 of the first round, later rounds
+        tokens[b, at] = V + b
+    lens = np.full(B, N, dtype=np.int32)
+    ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    ctx.set_option(api.OPT_LZW_KERNEL, narrow_only)
+    codes, n_codes, status = gpu_encode(ctx, tokens, lens)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    for b, (rc, rentries, rst) in enumerate(ref):
+        assert int(status[b]) == rst == api.ST_BAD_TOKEN
+        assert int(n_codes[b]) == len(rc) and codes[b, :len(rc)].tolist() == rc, f"bad token, seq {b}"
+    assert_codebook_equal(ctx, [r[1] for r in ref], M, cap)
+    # output rows that end after 1, 40, 100, 170, 230 and 600 codes
+    tokens = rng.integers(0, 7, size=(B, N)).astype(np.int32)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    for short in (1, 40, 100, 170, 230, 600):
+        codes, n_codes, status = gpu_encode(ctx, tokens, lens, out_stride=short)
+        for b in range(B):
+            assert int(status[b]) & api.ST_OVERFLOW and int(n_codes[b]) == short
+            assert codes[b, :short].tolist() == ref[b][0][:short], f"short output {short}, seq {b}"
+    ctx.close()
+
+    # repetitive streams, deep merges, a codebook that fills mid-round; long appended chunks
+    for V, M, cap, kind in ((1, 8, 100, "constant"), (3, 8, 40, "period"), (5, 3, 25, "runs"), (200, 5, 4000, "zipf")):
+        B, N = 4, 2600
+        if kind == "constant":
+            tokens = np.zeros((B, N), dtype=np.int32)
+        elif kind == "period":
+            tokens = np.tile(rng.integers(0, V, size=(B, 5)), (1, N // 5 + 1))[:, :N].astype(np.int32)
+        elif kind == "runs":
+            tokens = np.repeat(rng.integers(0, V, size=(B, N // 7 + 1)), 7, axis=1)[:, :N].astype(np.int32)
+        else:
+            tokens = np.minimum(rng.zipf(1.2, size=(B, N)) - 1, V - 1).astype(np.int32)
+        tokens = np.ascontiguousarray(tokens)
+        ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+        ctx.set_option(api.OPT_LZW_KERNEL, narrow_only)
+        streams = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+        pos, first = 0, True
+        for step in (700, 513, 1, 900, 486):
+            chunk = np.ascontiguousarray(tokens[:, pos:pos + step])
+            lens = rng.integers(0, step + 1, size=B).astype(np.int32)
+            lens[0] = step
+            codes, n_codes, status = gpu_encode(ctx, chunk, lens, flags=api.RESET if first else api.APPEND)
+            for b in range(B):
+                rc, rst = streams[b].encode_chunk(chunk[b, :lens[b]].tolist())
+                assert int(status[b]) == rst == 0
+                assert codes[b, :int(n_codes[b])].tolist() == rc, (kind, b, pos, step)
+            assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+            pos += step
+            first = False
+        ctx.close()
