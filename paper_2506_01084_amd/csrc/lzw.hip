@@ -1138,6 +1138,310 @@ __global__ void __launch_bounds__(kWave) lzw_decode_kernel(LzwArgs a) {
     lzw_decode_rounds<LDS>(a, codebuf, filter);
 }
 
+// ------------------------------------------------------------------------------------------------
+// decode, four waves per sequence (few long sequences: see the encoder's counterpart)
+//
+// A round takes up to 255 codes: global lane g = 64 * wave + lane holds code cpos + g - 1, global lane 0 the code
+// before the round.  The steps are those of lzw_decode_rounds; what crosses a window boundary goes through LDS:
+// the first code that names no entry yet (minimum over the waves), the (code, length, first token) of every
+// window's last lane for the next window's first proposal, proposal ranks and token offsets as prefix counts
+// over the waves, one repeat filter for the round.  A lane that inserts writes the new entry's row itself (the
+// previous code's tokens, which are older than the round, plus its own first token), so no registers cross
+// the boundary.  The one code that may name the entry it creates is taken alone at the head of a round by
+// every wave alike, wave 0 doing the stores.
+// ------------------------------------------------------------------------------------------------
+struct WideDecShared {
+  int32_t hard[kWide], edge_k[kWide], edge_len[kWide], edge_first[kWide], edge_known[kWide];
+  int32_t k1, first0;
+  u64 cand_mask[kWide];
+  int32_t lensum[kWide], ovf[kWide], ins_cnt[kWide];
+  int32_t last_k, last_len, last_incl;
+  int32_t cut;
+};
+static_assert(sizeof(WideDecShared) <= sizeof(WideShared), "the decoder's exchange area fits the encoder's LDS budget");
+
+template <bool LDS>
+__global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) {
+  __shared__ int32_t codebuf[kTokBuf];
+  __shared__ u64 filter[kWideFilter];
+  __shared__ WideDecShared sh;
+  const LzwState& st = a.st;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = tid;                                 // global lane of the round
+  const int V = st.V, M = st.M, cap = st.cap;
+  const bool reset = (a.flags & Z2Z_RESET) != 0;
+  const bool ef_lds = LDS && a.lds_ef;
+  uint32_t* ef = reinterpret_cast<uint32_t*>(lds_slots + st.nslots);
+  int32_t* ent_tokens = st.ent_tokens + (size_t)b * cap * M;
+  int32_t* ent_len = st.ent_len + (size_t)b * cap;
+
+  int C = reset ? 0 : __builtin_amdgcn_readfirstlane(st.size[b]);
+  int prev = reset ? -1 : __builtin_amdgcn_readfirstlane(st.prev_code[b]);
+  int prev_len = reset ? 0 : __builtin_amdgcn_readfirstlane(st.prev_len[b]);
+
+  Table<LDS> t;
+  t.g = st.slots + (size_t)b * st.nslots;
+  t.n = (uint32_t)st.nslots;
+  if (ef_lds && !reset) {
+    for (int i = tid; i < C; i += kWideLanes) ef[i] = pack_ef(ent_len[i], ent_tokens[(size_t)i * M]);
+  }
+  if (LDS) {
+    for (int i = tid; i < st.nslots; i += kWideLanes) lds_slots[i] = reset ? kEmpty : t.g[i];
+  } else if (reset) {
+    for (int i = tid; i < st.nslots; i += kWideLanes) t.g[i] = kEmpty;
+  }
+  for (int i = tid; i < kWideFilter; i += kWideLanes) filter[i] = kEmpty;
+  if (tid == 0) sh.cut = kWideLanes;
+  __syncthreads();
+
+  const int n = call_length(a, b);
+  const int32_t* in = a.in + (size_t)b * a.stride;
+  int32_t* out = a.out ? a.out + (size_t)b * a.out_stride : nullptr;
+
+  const u64 lanes_upto = lane == 63 ? ~0ull : (2ull << lane) - 1;
+  const u64 lanes_below = (1ull << lane) - 1;
+  int status = 0;
+  int n_out = 0;
+  bool stop = false;
+  int cbase = 0;
+  bool filled = false;
+  int cpos = 0;
+  while (cpos < n && !stop) {
+    if (!filled || (cpos + kWideLanes > cbase + kTokBuf && cbase + kTokBuf < n)) {
+      cbase = cpos;
+      filled = true;
+      const int cnt = min(kTokBuf, n - cbase);
+      for (int i = tid; i < cnt; i += kWideLanes) codebuf[i] = in[cbase + i];
+      __syncthreads();
+    }
+    // ---- 1. the codes of the round ------------------------------------------------------------------
+    const int ci = cpos + g - 1;
+    const bool present = g == 0 ? prev >= 0 : ci < n;
+    const int32_t k = g == 0 ? prev : (ci < n ? codebuf[ci - cbase] : -1);
+    int len = 0;
+    int32_t first = 0;
+    bool known = false;
+    if (present && k >= 0 && k < V) {
+      len = 1;
+      first = k;
+      known = true;
+    } else if (present && k >= V && k - V < C) {
+      const uint32_t e = ef_lds ? ef[k - V]
+                                : pack_ef(load_fresh(&ent_len[k - V]), load_fresh(&ent_tokens[(size_t)(k - V) * M]));
+      len = (int)(e >> 28);
+      first = (int32_t)(e & 0x0FFFFFFFu);
+      known = true;
+    }
+    const u64 hard_mask = __ballot(present && !known);            // never global lane 0
+    if (lane == 0) sh.hard[w] = hard_mask ? w * kWave + __builtin_ctzll(hard_mask) : kWideLanes;
+    if (lane == kWave - 1) {
+      sh.edge_k[w] = k;
+      sh.edge_len[w] = len;
+      sh.edge_first[w] = first;
+      sh.edge_known[w] = known ? 1 : 0;
+    }
+    if (tid == 0) sh.first0 = first;
+    if (tid == 1) sh.k1 = k;
+    __syncthreads();
+    int hard_pos = kWideLanes;
+    for (int ww = 0; ww < kWide; ++ww) hard_pos = min(hard_pos, sh.hard[ww]);
+
+    if (hard_pos == 1) {
+      // the first code of the round names no entry of the codebook as it stands: "previous phrase + its own
+      // first token", legal and absent, or an error.  Every wave takes the same decisions; wave 0 stores.
+      const int32_t k1 = sh.k1;
+      bool ok = false;
+      if (k1 >= V && k1 - V == C && prev >= 0 && prev_len < M && C < cap) {
+        const int32_t pf = sh.first0;
+        int free_pos = -1;
+        const int idx = t.find(prev, pf, &free_pos);
+        if (idx < 0 && free_pos >= 0) {
+          const int cur_len = prev_len + 1;
+          if (out != nullptr && n_out + cur_len > a.out_stride) {
+            status |= Z2Z_ST_OVERFLOW;
+            stop = true;
+          } else {
+            if (w == 0) {
+              int32_t tokj = -1;        // lane j: token j of the new phrase
+              if (lane < prev_len) tokj = prev < V ? prev : load_fresh(&ent_tokens[(size_t)(prev - V) * M + lane]);
+              if (lane == prev_len) tokj = pf;
+              if (lane == 0) {
+                t.store((uint32_t)free_pos, edge_bits(prev, pf) | (u64)(uint32_t)C);
+                if (ef_lds) ef[C] = pack_ef(cur_len, pf);
+                ent_len[C] = cur_len;
+              }
+              if (lane < M) ent_tokens[(size_t)C * M + lane] = tokj;
+              if (out != nullptr && lane < cur_len) out[n_out + lane] = tokj;
+            }
+            prev = k1;
+            prev_len = cur_len;
+            ++C;
+            n_out += cur_len;
+            ++cpos;
+          }
+          ok = true;
+        }
+      }
+      if (!ok) {
+        status |= Z2Z_ST_BAD_CODE;
+        stop = true;
+      }
+      __syncthreads();
+      continue;
+    }
+
+    // ---- 2. proposals --------------------------------------------------------------------------------
+    const int limit0 = min(hard_pos, min(kWideLanes, n - cpos + 1));   // global lanes 1 .. limit0-1 hold known codes
+    int32_t pk = __shfl_up(k, 1);
+    int plen = __shfl_up(len, 1);
+    int32_t pfirst = __shfl_up(first, 1);
+    bool pknown = __shfl_up((int)known, 1) != 0;
+    if (lane == 0 && w > 0) {
+      pk = sh.edge_k[w - 1];
+      plen = sh.edge_len[w - 1];
+      pfirst = sh.edge_first[w - 1];
+      pknown = sh.edge_known[w - 1] != 0;
+    }
+    const int room = cap - C;
+    const bool prop = g >= 1 && g < limit0 && pknown && plen < M && room > 0;
+    int found = -1;
+    if (prop) found = t.find_lane(pk, first);
+    const bool cand = prop && found < 0;
+    const u64 cand_mask = __ballot(cand);
+    // token offsets inside the window
+    const int mylen = (g >= 1 && g < limit0) ? len : 0;
+    int incl = 0;
+#pragma unroll
+    for (int bit = 0; bit < 4; ++bit) incl += __popcll(__ballot((mylen >> bit) & 1) & lanes_upto) << bit;
+    if (lane == 0) sh.cand_mask[w] = cand_mask;
+    if (lane == kWave - 1) sh.lensum[w] = incl;
+    __syncthreads();
+    int cand_before = 0, cand_total = 0, len_before = 0;
+    for (int ww = 0; ww < kWide; ++ww) {
+      const int cnt = __popcll(sh.cand_mask[ww]);
+      if (ww < w) {
+        cand_before += cnt;
+        len_before += sh.lensum[ww];
+      }
+      cand_total += cnt;
+    }
+    const int rank = cand_before + __popcll(cand_mask & lanes_below);
+    const bool inserter = cand && rank < room;
+    incl += len_before;                               // tokens of codes 1 .. g of the round
+    const u64 ovf_mask = __ballot(out != nullptr && mylen > 0 && n_out + incl > a.out_stride);
+    if (lane == 0) sh.ovf[w] = ovf_mask ? w * kWave + __builtin_ctzll(ovf_mask) : kWideLanes;
+    // first repeat of a proposed edge: insert phase
+    const bool filtering = cand_total >= 2;           // uniform
+    const u64 key = edge_bits(pk, first);
+    const uint32_t h0 = (edge_hash(pk, first) >> 20) & (kWideFilter - 1);
+    int own = -1;
+    if (filtering && inserter) {
+      const u64 val = key | (u64)g;
+      uint32_t h = h0;
+      for (int probe = 0; probe < kWideFilter; ++probe) {
+        const u64 old = atomicCAS(&filter[h], kEmpty, val);
+        if (old == kEmpty) {
+          own = (int)h;
+          break;
+        }
+        if ((old & ~0xFFFFull) == key) {
+          atomicMin(&filter[h], val);
+          break;
+        }
+        h = (h + 1) & (kWideFilter - 1);
+      }
+    }
+    __syncthreads();
+    if (filtering) {
+      int fpos = kWideLanes;
+      if (cand) {
+        uint32_t h = h0;
+        for (int probe = 0; probe < kWideFilter; ++probe) {
+          const u64 sl = filter[h];
+          if (sl == kEmpty) break;
+          if ((sl & ~0xFFFFull) == key) {
+            fpos = (int)(sl & 0xFFFFull);
+            break;
+          }
+          h = (h + 1) & (kWideFilter - 1);
+        }
+      }
+      const u64 dup_mask = __ballot(cand && fpos < g);
+      if (dup_mask && lane == 0) atomicMin(&sh.cut, w * kWave + __builtin_ctzll(dup_mask));
+    }
+    __syncthreads();
+    const int cut = sh.cut;
+    if (own >= 0) filter[own] = kEmpty;
+    int ovf_pos = kWideLanes;
+    for (int ww = 0; ww < kWide; ++ww) ovf_pos = min(ovf_pos, sh.ovf[ww]);
+    const int limit = min(limit0, min(cut, ovf_pos));
+    if (ovf_pos < kWideLanes && limit == ovf_pos) {
+      status |= Z2Z_ST_OVERFLOW;
+      stop = true;
+    }
+
+    // ---- 3. publish ---------------------------------------------------------------------------------------
+    const bool valid = g >= 1 && g < limit;
+    const bool ins = valid && inserter;
+    if (ins) {
+      const int idx = C + rank;
+      t.insert_lane(pk, first, idx);
+      if (ef_lds) ef[idx] = pack_ef(plen + 1, pfirst);
+      // the new entry's row: the previous code's tokens (older than the round) and this code's first token
+      int32_t* row = ent_tokens + (size_t)idx * M;
+      for (int j = 0; j < M; ++j) {
+        int32_t v = -1;
+        if (j < plen) v = pk < V ? pk : load_fresh(&ent_tokens[(size_t)(pk - V) * M + j]);
+        if (j == plen) v = first;
+        row[j] = v;
+      }
+      ent_len[idx] = plen + 1;
+    }
+    if (valid && out != nullptr) {
+      int32_t* dst = out + n_out + incl - len;
+      if (k < V) {
+        dst[0] = k;
+      } else {
+        const int32_t* row = ent_tokens + (size_t)(k - V) * M;
+        for (int j = 0; j < len; ++j) dst[j] = load_fresh(&row[j]);
+      }
+    }
+    const u64 ins_mask = __ballot(ins);
+    if (lane == 0) sh.ins_cnt[w] = __popcll(ins_mask);
+    if (limit >= 2 && g == limit - 1) {
+      sh.last_k = k;
+      sh.last_len = len;
+      sh.last_incl = incl;
+    }
+    __syncthreads();
+    for (int ww = 0; ww < kWide; ++ww) C += sh.ins_cnt[ww];
+    if (limit >= 2) {
+      prev = sh.last_k;
+      prev_len = sh.last_len;
+      n_out += sh.last_incl;
+      cpos += limit - 1;
+    } else {
+      stop = true;
+    }
+    if (tid == 0) sh.cut = kWideLanes;
+    __syncthreads();                  // rows written above are in memory, the exchange area is free
+  }
+
+  if (LDS) {
+    for (int i = tid; i < st.nslots; i += kWideLanes) t.g[i] = lds_slots[i];
+  }
+  if (tid == 0) {
+    st.size[b] = C;
+    st.prev_code[b] = prev;
+    st.prev_len[b] = prev_len;
+    a.out_n[b] = n_out;
+    a.status[b] = status;
+  }
+}
+
 // Empty every codebook.  grid = B, block = 256.
 __global__ void lzw_reset_kernel(LzwState st) {
   const int b = blockIdx.x;
@@ -1427,7 +1731,13 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
   plan(c, stride, flags, true, &lds, &a, &smem);
   if (flags & Z2Z_RESET) hipLaunchKernelGGL(lzw_clear_entries_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
   const bool serial = stride <= 8 || c->opt_lzw_kernel == 3;
-  if (serial && lds)
+  const bool wide = !serial && c->cfg.B <= 64 && stride >= 512 && c->opt_lzw_kernel != 4 &&
+                    (!lds || smem + kWideStaticLds <= (size_t)c->lds_limit);
+  if (wide && lds)
+    hipLaunchKernelGGL(lzw_decode_wide_kernel<true>, dim3(c->cfg.B), dim3(kWideLanes), smem, s, a);
+  else if (wide)
+    hipLaunchKernelGGL(lzw_decode_wide_kernel<false>, dim3(c->cfg.B), dim3(kWideLanes), 0, s, a);
+  else if (serial && lds)
     hipLaunchKernelGGL(lzw_decode_serial_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
   else if (serial)
     hipLaunchKernelGGL(lzw_decode_serial_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
@@ -1468,6 +1778,8 @@ int z2z_lzw_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_encode_wide_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kWideStaticLds));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_wide_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kWideStaticLds));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(lzw_decode_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->lds_limit - kEncStaticLds));

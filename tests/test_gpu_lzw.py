@@ -67,6 +67,17 @@ def test_global_table_variant_bit_exact(name):
     _check_encode_decode(cfg, tokens, wl.make_lens(cfg), lzw_kernel=2)
 
 
+@pytest.mark.parametrize("name", ["c2", "c4", "c5"])
+def test_one_wave_per_sequence_variant_bit_exact(name):
+    """Few long sequences take the kernels with four waves per sequence by default; the one-wave kernels (what
+    calls with many sequences run) on the same inputs."""
+    cfg = wl.CONFIGS[name]
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    print(f"[case] lzw one wave per sequence {name}", flush=True)
+    _check_encode_decode(cfg, tokens, lens, lzw_kernel=4)
+
+
 @pytest.mark.parametrize("name", ["c2", "c4"])
 def test_serial_decoder_variant_bit_exact(name):
     """The one-code-at-a-time decoder (the one short appended calls take), forced on long streams."""
@@ -209,7 +220,7 @@ def _model_like_stream(rng, V, M, cap, n, p_fresh=0.05, p_entry=0.5):
 
 
 @pytest.mark.parametrize("V,M,cap,lzw_kernel", [(3, 3, 40, 0), (6, 4, 300, 0), (50, 5, 2000, 0), (4, 2, 1000, 0),
-                                                (6, 4, 300, 2), (2, 8, 500, 0)])
+                                                (6, 4, 300, 2), (2, 8, 500, 0), (6, 4, 300, 4), (50, 5, 2000, 4)])
 def test_decoder_on_streams_no_greedy_parse_produces(V, M, cap, lzw_kernel):
     """Repeated edges inside a round, codes naming entries a few codes old, the not-yet-defined code,
     then a bad code in the middle and a short output row: all against the oracle's decoder."""
