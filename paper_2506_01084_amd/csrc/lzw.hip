@@ -488,6 +488,12 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
   __shared__ int32_t tokbuf[kTokBuf];
   __shared__ u64 filter[kWideFilter];
   __shared__ WideShared sh;
+  // a short appended call (its length is known on the device only): one wave, probing the table where it
+  // lives; the other waves leave (a barrier does not wait for waves that have ended)
+  if (!(a.flags & Z2Z_RESET) && call_length(a, blockIdx.x) <= kShortAppend) {
+    if (threadIdx.x < kWave) lzw_encode_rounds<false>(a, tokbuf, filter);
+    return;
+  }
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
@@ -1165,6 +1171,10 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
   __shared__ int32_t codebuf[kTokBuf];
   __shared__ u64 filter[kWideFilter];
   __shared__ WideDecShared sh;
+  if (!(a.flags & Z2Z_RESET) && call_length(a, blockIdx.x) <= kShortAppend) {      // see the encoder
+    if (threadIdx.x < kWave) lzw_decode_rounds<false>(a, codebuf, filter);
+    return;
+  }
   const LzwState& st = a.st;
   const int b = blockIdx.x;
   const int tid = threadIdx.x;

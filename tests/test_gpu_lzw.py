@@ -423,3 +423,51 @@ def test_long_calls_errors_appends_and_repeats_both_encoders(narrow_only):
             pos += step
             first = False
         ctx.close()
+
+
+def test_short_appended_calls_in_wide_rows():
+    """A call whose rows are long (so the launch picks the four-wave kernels) but whose sequences hold only a
+    few elements this time: the length is known on the device only, and the kernel takes the short path."""
+    from paper_2506_01084_amd import api
+
+    V, M, cap = 30, 4, 500
+    B, N = 5, 900
+    rng = np.random.default_rng(23)
+    tokens = rng.integers(0, 6, size=(B, N)).astype(np.int32)
+    ctx = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    streams = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    full = np.full(B, N, dtype=np.int32)
+    codes, n_codes, st = gpu_encode(ctx, tokens, full)                       # a long call: four waves
+    for b in range(B):
+        assert codes[b, :n_codes[b]].tolist() == streams[b].encode_chunk(tokens[b].tolist())[0]
+    for rep in range(4):                                                     # short ones in rows of 900
+        more = rng.integers(0, 6, size=(B, N)).astype(np.int32)
+        lens = rng.integers(0, 8, size=B).astype(np.int32)
+        lens[0] = 64
+        codes, n_codes, st = gpu_encode(ctx, more, lens, flags=api.APPEND)
+        for b in range(B):
+            rc, rst = streams[b].encode_chunk(more[b, :lens[b]].tolist())
+            assert int(st[b]) == rst == 0 and codes[b, :n_codes[b]].tolist() == rc, (rep, b)
+        assert_codebook_equal(ctx, [s.entries for s in streams], M, cap)
+    # the same for the decoder: a second context follows the first one's code streams
+    ctx2 = _ctx(dict(B=B, V=V, M=M, cap=cap))
+    dec = [oracle.LZWStream(V, M, cap) for _ in range(B)]
+    codes, n_codes, st = gpu_encode(ctx, tokens, full)                       # fresh long stream (RESET)
+    toks, n_tok, st = gpu_decode(ctx2, codes, n_codes, out_stride=N)
+    for b in range(B):
+        rt, rst = dec[b].decode_chunk(codes[b, :n_codes[b]].tolist())
+        assert int(st[b]) == rst == 0 and toks[b, :n_tok[b]].tolist() == rt == tokens[b].tolist()
+    for rep in range(4):
+        wide_rows = np.zeros((B, N), dtype=np.int32)
+        cnt = rng.integers(0, 5, size=B).astype(np.int32)
+        for b in range(B):
+            C = len(dec[b].entries)
+            for i in range(cnt[b]):
+                wide_rows[b, i] = int(rng.integers(0, V + C))
+        toks, n_tok, st = gpu_decode(ctx2, wide_rows, cnt, out_stride=64, flags=api.APPEND)
+        for b in range(B):
+            rt, rst = dec[b].decode_chunk(wide_rows[b, :cnt[b]].tolist())
+            assert int(st[b]) == rst and toks[b, :n_tok[b]].tolist() == rt, (rep, b)
+        assert_codebook_equal(ctx2, [s.entries for s in dec], M, cap)
+    ctx.close()
+    ctx2.close()
