@@ -36,7 +36,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # summaries are committed under profiles/ (counter values scaled by a 1 GiB copy of known traffic).
 # They are measurements of these exact workloads, not computed here: a different workload reports null.
 TRAFFIC_BYTES = {
-    "logits_fast_kernel<0>@c2": 53.93e9 + 0.066e9,
+    "logits_fast_kernel<0>@c2": 53.88e9 + 0.070e9,
     "logits_decode_kernel@c3": 3.211e9 + 0.003e9,
 }
 
