@@ -19,7 +19,9 @@ closed form on a constant sequence, structural codebook invariants, brute
 force over all tiny inputs, exact-rational rounding checks, pooling closed
 forms, logit linearity and log-sum-exp bounds, the generator's published
 known-answer vectors and a chi-square test of the draws, the library's
-transformer encoder layer and multi-head attention for the learned hyper-encoder.  The only unpinned item is the
+transformer encoder layer and multi-head attention for the learned hyper-encoder
+(its gradient: the library's reverse-mode differentiation of the same modules and
+finite differences of the forward pass).  The only unpinned item is the
 literal content of Fig. 1's table, which is absent from the paper's text: the
 fixture for it is a reconstruction from the captions.
 """
@@ -30,5 +32,5 @@ from .logits import extended_logits  # noqa: F401
 from .sampling import (extended_sample, kept_prefix, philox4x32_10, sample_row,  # noqa: F401
                        sample_row_truncated)
 from .loss import extended_nll, extended_nll_backward, hyper_embed_backward  # noqa: F401
-from .encoder import hyper_encode  # noqa: F401
+from .encoder import hyper_encode, hyper_encode_backward  # noqa: F401
 from .numfmt import bf16_bits_to_f64, f64_to_bf16_bits, to_f64, round_to_storage  # noqa: F401

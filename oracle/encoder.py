@@ -104,3 +104,127 @@ def hyper_encode(E: np.ndarray, dtype: str, entries: Sequence[Tuple[int, ...]], 
             X = X + e64["pos"][:len(e)]
         out64[i] = encode_entry(X, e64)
     return round_to_storage(out64, dtype) if rounded else out64
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Gradient of the learned hyper-encoder (training f_phi together with the model, section 2.4: the loss over
+# the compressed sequence reaches phi through every hypertoken vector it produced).  Plain reverse-mode
+# differentiation of encode_entry, step by step in the reverse order of the forward pass.
+# ---------------------------------------------------------------------------------------------------------
+
+def layer_norm_backward(dN: np.ndarray, x: np.ndarray, gamma: np.ndarray, eps: float = EPS):
+    """N = (x - mu) / sqrt(var + eps) * gamma + beta  ->  (dx, dgamma, dbeta)."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xh = (x - mu) * rstd
+    g = dN * gamma
+    dx = rstd * (g - g.mean(axis=-1, keepdims=True) - xh * (g * xh).mean(axis=-1, keepdims=True))
+    return dx, (dN * xh).sum(axis=0), dN.sum(axis=0)
+
+
+def gelu_grad(x: np.ndarray) -> np.ndarray:
+    """d/dx of 0.5 x (1 + erf(x / sqrt 2)) = Phi(x) + x phi(x)."""
+    return 0.5 * (1.0 + erf(x / np.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / np.sqrt(2.0 * np.pi)
+
+
+def attention_backward(dOut: np.ndarray, A: np.ndarray, w_qkv: np.ndarray, b_qkv: np.ndarray, w_o: np.ndarray,
+                       n_heads: int):
+    """Backward of attention(): dOut [L, d] -> (dA, dw_qkv, db_qkv, dw_o, db_o)."""
+    L, d = A.shape
+    dh = d // n_heads
+    qkv = A @ w_qkv.T + b_qkv
+    Q, K, V = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
+    O = np.empty((L, d), dtype=np.float64)
+    P_all = []
+    for h in range(n_heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        S = Q[:, sl] @ K[:, sl].T / np.sqrt(dh)
+        S = S - S.max(axis=1, keepdims=True)
+        Pm = np.exp(S)
+        Pm /= Pm.sum(axis=1, keepdims=True)
+        P_all.append(Pm)
+        O[:, sl] = Pm @ V[:, sl]
+    dw_o = dOut.T @ O
+    db_o = dOut.sum(axis=0)
+    dO = dOut @ w_o
+    dqkv = np.zeros_like(qkv)
+    for h in range(n_heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        Pm = P_all[h]
+        dP = dO[:, sl] @ V[:, sl].T
+        dV = Pm.T @ dO[:, sl]
+        dS = Pm * (dP - (dP * Pm).sum(axis=1, keepdims=True))
+        dqkv[:, sl] = dS @ K[:, sl] / np.sqrt(dh)
+        dqkv[:, d + h * dh:d + (h + 1) * dh] = dS.T @ Q[:, sl] / np.sqrt(dh)
+        dqkv[:, 2 * d + h * dh:2 * d + (h + 1) * dh] = dV
+    return dqkv @ w_qkv, dqkv.T @ A, dqkv.sum(axis=0), dw_o, db_o
+
+
+def zero_grads(enc64: dict) -> dict:
+    return dict(pos=None if enc64["pos"] is None else np.zeros_like(enc64["pos"]),
+                layers=[{k: np.zeros_like(v) for k, v in lay.items()} for lay in enc64["layers"]])
+
+
+def encode_entry_backward(X0: np.ndarray, enc64: dict, dh_out: np.ndarray, grads: dict) -> np.ndarray:
+    """Adds the entry's parameter gradients to `grads` (as made by zero_grads) and returns dX0 [L, d], given
+    dh_out = dLoss / d encode_entry(X0)."""
+    xs = []                      # forward, keeping each layer's input and middle state
+    X = X0
+    for lay in enc64["layers"]:
+        A = layer_norm(X, lay["ln1_g"], lay["ln1_b"])
+        Y = X + attention(A, lay["w_qkv"], lay["b_qkv"], lay["w_o"], lay["b_o"], enc64["n_heads"])
+        xs.append((X, A, Y))
+        X = Y
+        if not enc64["attention_only"]:
+            N2 = layer_norm(Y, lay["ln2_g"], lay["ln2_b"])
+            U = N2 @ lay["w_1"].T + lay["b_1"]
+            X = Y + gelu(U) @ lay["w_2"].T + lay["b_2"]
+    L = X0.shape[0]
+    dX = np.tile(dh_out / L, (L, 1))             # h = mean over the L real slots
+    for lay, g, (Xin, A, Y) in zip(reversed(enc64["layers"]), reversed(grads["layers"]), reversed(xs)):
+        dY = dX
+        if not enc64["attention_only"]:
+            N2 = layer_norm(Y, lay["ln2_g"], lay["ln2_b"])
+            U = N2 @ lay["w_1"].T + lay["b_1"]
+            F = gelu(U)
+            g["w_2"] += dX.T @ F
+            g["b_2"] += dX.sum(axis=0)
+            dU = (dX @ lay["w_2"]) * gelu_grad(U)
+            g["w_1"] += dU.T @ N2
+            g["b_1"] += dU.sum(axis=0)
+            dYn, dg, db = layer_norm_backward(dU @ lay["w_1"], Y, lay["ln2_g"])
+            g["ln2_g"] += dg
+            g["ln2_b"] += db
+            dY = dX + dYn
+        dA, dwqkv, dbqkv, dwo, dbo = attention_backward(dY, A, lay["w_qkv"], lay["b_qkv"], lay["w_o"],
+                                                        enc64["n_heads"])
+        g["w_qkv"] += dwqkv
+        g["b_qkv"] += dbqkv
+        g["w_o"] += dwo
+        g["b_o"] += dbo
+        dXn, dg, db = layer_norm_backward(dA, Xin, lay["ln1_g"])
+        g["ln1_g"] += dg
+        g["ln1_b"] += db
+        dX = dY + dXn
+    return dX
+
+
+def hyper_encode_backward(E: np.ndarray, dtype: str, entries: Sequence[Tuple[int, ...]], enc: dict,
+                          dW_hyper: np.ndarray) -> dict:
+    """Gradient of  sum_{i, k} dW_hyper[i, k] * f_phi(entries[i])[k]  for ONE sequence's entries (float64, taken
+    at the unrounded forward values): dict(dE [V, d], pos [M, d] or None, layers: list of dicts keyed like the
+    encoder's layers).  A token that occurs in several slots receives every slot's gradient."""
+    e64 = widen_encoder(enc, dtype)
+    grads = zero_grads(e64)
+    dE = np.zeros((E.shape[0], E.shape[1]), dtype=np.float64)
+    for i, e in enumerate(entries):
+        X = np.stack([to_f64(E[t], dtype) for t in e])
+        if e64["pos"] is not None:
+            X = X + e64["pos"][:len(e)]
+        dX0 = encode_entry_backward(X, e64, np.asarray(dW_hyper[i], dtype=np.float64), grads)
+        for j, t in enumerate(e):
+            dE[t] += dX0[j]
+        if grads["pos"] is not None:
+            grads["pos"][:len(e)] += dX0
+    return dict(dE=dE, pos=grads["pos"], layers=grads["layers"])
