@@ -206,6 +206,24 @@ typedef struct z2z_encoder {
 int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, void* d_W_hyper,
                      const int32_t* d_first, int32_t max_new, void* stream);
 
+/* Backward of z2z_hyper_encode over ALL existing entries (training f_phi, section 2.4: the loss over the
+ * compressed sequence reaches the hyper-encoder through every hypertoken vector): the gradient of
+ *   L = sum_{b, e < C_b, k} d_dW_hyper[b, e, k] * W_hyper[b, e, k]
+ * with respect to every parameter of the encoder, the slot positions and the embedding rows.
+ *   d_dW_hyper [B, cap, d] bf16: dL / dW_hyper (e.g. from z2z_extended_nll_backward); rows >= C_b are ignored
+ *   grad       a second description with the shape of `encoder` whose pointers name the device buffers that
+ *              RECEIVE the gradients (the call writes through them although the struct declares them const):
+ *              matrices and pos bf16, vectors float, all overwritten; n_heads, d_ff, attention_only of `grad`
+ *              are not read; grad->pos is required when encoder->pos is given
+ *   d_dE       [V, d] float, ACCUMULATED into (tokens recur across entries; the caller clears it)
+ * The call runs the forward pass again, keeping every layer's rows, then reverse mode over the same steps;
+ * activations and gradients between kernels are bf16, sums fp32; passes of up to 65536 slot rows (matrix
+ * gradients of later passes add to the bf16 result of the earlier ones).  Work space (about
+ * 2 * (n_layers * (8 d + 2 d_ff) + 8 d + d_ff + 2 max(3 d, d_ff)) bytes per slot row) is library scratch,
+ * Z2Z_ENOMEM beyond 200 GB.  Restrictions and errors as for z2z_hyper_encode. */
+int z2z_hyper_encode_backward(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, const void* d_dW_hyper,
+                              const z2z_encoder* grad, float* d_dE, void* stream);
+
 /* extended_logits.  For row r of sequence b = r / rows_per_seq:
  *   logit[r, v] = sum_k H[r,k] * W[v,k],  W = W_base for v < V, W_hyper[b, v-V] for V <= v < V + C_b;
  * slots at and beyond C_b are not columns (never predicted).  Products of the stored values,

@@ -24,7 +24,7 @@ OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
-           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
+           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_codebook_prune.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_hyper_encode.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p, c_int32, c_void_p]
+    lib.z2z_hyper_encode_backward.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p,
+                                              POINTER(EncoderDesc), c_void_p, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_int32,
@@ -247,6 +249,15 @@ class Context:
         _check(self._lib.z2z_hyper_encode(self._h, _ptr(E, self.torch_dtype), byref(encoder.desc),
                                           _ptr(W_hyper, self.torch_dtype), _ptr(first, torch.int32), max_new,
                                           _stream()), "z2z_hyper_encode")
+
+    def hyper_encode_backward(self, E: torch.Tensor, encoder: "Encoder", dW_hyper: torch.Tensor, grad: "Encoder",
+                              dE: torch.Tensor) -> None:
+        """`grad`: an Encoder built over tensors of the parameters' shapes, which receive the gradients."""
+        assert tuple(E.shape) == (self.V, self.d) and tuple(dW_hyper.shape) == (self.B, self.cap, self.d)
+        assert tuple(dE.shape) == (self.V, self.d)
+        _check(self._lib.z2z_hyper_encode_backward(self._h, _ptr(E, self.torch_dtype), byref(encoder.desc),
+                                                   _ptr(dW_hyper, self.torch_dtype), byref(grad.desc),
+                                                   _ptr(dE, torch.float32), _stream()), "z2z_hyper_encode_backward")
 
     def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
                         argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,

@@ -283,6 +283,357 @@ __global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const uint4* Z,
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Backward pass (training f_phi: the loss reaches the encoder through every hypertoken vector, section 2.4).
+// Reverse mode over the forward steps above.  Every product with a weight matrix, and every weight gradient
+// (a product over the rows of the pass), runs on the same MFMA kernels from transposed bf16 copies; the kernels
+// below are the bandwidth-bound rest.  Gradients between kernels are bf16, sums fp32.
+// ---------------------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) enc_fill_kernel(float* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+// dX[r] = dW_hyper[b, e] / L for the L rows of every entry (h = mean of the real slots); one wave per entry.
+__global__ void __launch_bounds__(256) enc_pool_backward_kernel(RowMap m, const uint4* dW, uint4* dX, int n_units) {
+  const int lane = threadIdx.x & 63;
+  const long long bu = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (bu >= n_units) return;
+  const int L = m.row0[bu + 1] - m.row0[bu];
+  if (L < 1) return;
+  const int b = (int)(bu / m.un), u = (int)(bu % m.un);
+  const int n_chunks = m.d / 8;
+  int C;
+  const int e = entry_of(m, b, u, &C);
+  const uint4* wrow = dW + ((size_t)b * m.cap + e) * n_chunks;
+  const float invL = 1.0f / (float)L;
+  const size_t r0 = (size_t)m.row0[bu];
+  for (int c = lane; c < n_chunks; c += 64) {
+    float g[8];
+    unpack8(wrow[c], g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) g[t] *= invL;
+    const uint4 o = pack8(g);
+    for (int i = 0; i < L; ++i) dX[(r0 + i) * n_chunks + c] = o;
+  }
+}
+
+// out[n] += sum over the pass's rows of G[r, n] (bias gradients).  A thread owns 8 columns and every fourth
+// row of a stripe of 256 rows; grid (ceil(N / 512), ceil(max rows / 256)).
+__global__ void __launch_bounds__(256) enc_colsum_kernel(const uint4* G, int n_chunks, const int32_t* rows_dev,
+                                                         float* out) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rows = *rows_dev;
+  const int r_begin = blockIdx.y * 256 + (threadIdx.x >> 6), r_end = min(rows, (int)(blockIdx.y + 1) * 256);
+  if (c >= n_chunks || r_begin >= r_end) return;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r_begin; r < r_end; r += 4) {
+    float g[8];
+    unpack8(G[(size_t)r * n_chunks + c], g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] += g[t];
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) atomicAdd(out + (size_t)c * 8 + t, acc[t]);
+}
+
+__device__ __forceinline__ float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_slope(float x) {
+  return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+}
+
+// F = GELU(U) over the pass's rows (the training pass keeps U for the slope).
+__global__ void __launch_bounds__(256) enc_gelu_kernel(const uint4* U, uint4* F, int n_chunks, const int32_t* rows_dev) {
+  const size_t n = (size_t)*rows_dev * n_chunks;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    float u[8];
+    unpack8(U[i], u);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) u[t] = gelu_exact(u[t]);
+    F[i] = pack8(u);
+  }
+}
+
+// dU = dF * GELU'(U), in place over dF.
+__global__ void __launch_bounds__(256) enc_gelu_backward_kernel(uint4* dF, const uint4* U, int n_chunks,
+                                                                const int32_t* rows_dev) {
+  const size_t n = (size_t)*rows_dev * n_chunks;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    float u[8], g[8];
+    unpack8(U[i], u);
+    unpack8(dF[i], g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) g[t] *= gelu_slope(u[t]);
+    dF[i] = pack8(g);
+  }
+}
+
+// LayerNorm backward: N = (x - mean) * rstd * gamma + beta.  out[r] = dres[r] + dx[r] with
+//   g = dN * gamma;  dx = rstd * (g - mean(g) - xh * mean(g * xh)),  xh = (x - mean) * rstd;
+// dgamma += sum_r dN * xh,  dbeta += sum_r dN.  A wave takes E_NB_ROWS consecutive rows, one at a time (the row
+// held in registers as in the forward kernel), and keeps its share of dgamma / dbeta in registers until the end.
+constexpr int E_NB_ROWS = 16;
+__global__ void __launch_bounds__(256) enc_norm_backward_kernel(const int32_t* rows_dev, int d, const uint4* dN,
+                                                                const uint4* X, const float* gamma, const uint4* dres,
+                                                                uint4* out, float* dgamma, float* dbeta) {
+  const int lane = threadIdx.x & 63;
+  const int rows = *rows_dev;
+  const int r_begin = (blockIdx.x * 4 + (threadIdx.x >> 6)) * E_NB_ROWS;
+  if (r_begin >= rows) return;
+  const int r_end = min(rows, r_begin + E_NB_ROWS);
+  const int n_chunks = d / 8;
+  const float inv_d = 1.0f / (float)d;
+  float ag[E_KCH][8], ab[E_KCH][8], gm[E_KCH][8];
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k) {
+    const int c = lane + 64 * k;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      ag[k][t] = 0.f;
+      ab[k][t] = 0.f;
+      gm[k][t] = c < n_chunks ? gamma[c * 8 + t] : 0.f;
+    }
+  }
+  for (int r = r_begin; r < r_end; ++r) {
+    float x[E_KCH][8], g[E_KCH][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k) {
+      const int c = lane + 64 * k;
+      if (c < n_chunks) {
+        unpack8(X[(size_t)r * n_chunks + c], x[k]);
+        unpack8(dN[(size_t)r * n_chunks + c], g[k]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) sum += x[k][t];
+      }
+    }
+    const float mean = wave_sum(sum) * inv_d;
+    float sq = 0.f;
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k)
+      if (lane + 64 * k < n_chunks) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const float dv = x[k][t] - mean;
+          sq += dv * dv;
+        }
+      }
+    const float rstd = rsqrtf(wave_sum(sq) * inv_d + E_EPS);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k)
+      if (lane + 64 * k < n_chunks) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const float xh = (x[k][t] - mean) * rstd;
+          ag[k][t] += g[k][t] * xh;
+          ab[k][t] += g[k][t];
+          x[k][t] = xh;
+          g[k][t] *= gm[k][t];
+          s1 += g[k][t];
+          s2 += g[k][t] * xh;
+        }
+      }
+    const float m1 = wave_sum(s1) * inv_d, m2 = wave_sum(s2) * inv_d;
+#pragma unroll
+    for (int k = 0; k < E_KCH; ++k) {
+      const int c = lane + 64 * k;
+      if (c < n_chunks) {
+        float o[8];
+        unpack8(dres[(size_t)r * n_chunks + c], o);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) o[t] += rstd * (g[k][t] - m1 - x[k][t] * m2);
+        out[(size_t)r * n_chunks + c] = pack8(o);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k) {
+    const int c = lane + 64 * k;
+    if (c < n_chunks) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        atomicAdd(dgamma + c * 8 + t, ag[k][t]);
+        atomicAdd(dbeta + c * 8 + t, ab[k][t]);
+      }
+    }
+  }
+}
+
+// Attention backward for one entry and 512 features (same split as the forward kernel).  Per query row i the
+// probabilities p[i][.] are formed again from q and k; with dP[i][j] = dO_i . v_j and
+// dS[i][j] = p[i][j] (dP[i][j] - sum_j' dP[i][j'] p[i][j']):  dq_i = scale * sum_j dS[i][j] k_j;
+// dk_j += scale * dS[i][j] q_i;  dv_j += p[i][j] dO_i.  dQKV has the layout of QKV.
+__global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, const uint4* QKV, const uint4* dO,
+                                                                     uint4* dQKV, int lanes_per_head, float scale,
+                                                                     int groups, int n_units) {
+  const int lane = threadIdx.x & 63;
+  const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int g = (int)(wid % groups);
+  const long long bu = wid / groups;
+  if (bu >= n_units) return;
+  const int n_chunks = m.d / 8;
+  const int c = g * 64 + lane;
+  const bool active = c < n_chunks;
+  const size_t r0 = (size_t)m.row0[bu];
+  const int L = m.row0[bu + 1] - m.row0[bu];
+  const uint4 zero = {0u, 0u, 0u, 0u};
+  float dk[Z2Z_MAX_M][8], dv[Z2Z_MAX_M][8];
+#pragma unroll
+  for (int j = 0; j < Z2Z_MAX_M; ++j)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      dk[j][t] = 0.f;
+      dv[j][t] = 0.f;
+    }
+  for (int i = 0; i < L; ++i) {
+    float q[8], go[8];
+    unpack8(active ? QKV[(r0 + i) * 3 * n_chunks + c] : zero, q);
+    unpack8(active ? dO[(r0 + i) * n_chunks + c] : zero, go);
+    float s[Z2Z_MAX_M], dp[Z2Z_MAX_M];
+    float smax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      s[j] = -INFINITY;
+      dp[j] = 0.f;
+      if (j < L) {
+        float k[8], v[8];
+        unpack8(active ? QKV[(r0 + j) * 3 * n_chunks + n_chunks + c] : zero, k);
+        unpack8(active ? QKV[(r0 + j) * 3 * n_chunks + 2 * n_chunks + c] : zero, v);
+        float dot = 0.f, dot2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          dot += q[t] * k[t];
+          dot2 += go[t] * v[t];
+        }
+        for (int off = 1; off < lanes_per_head; off <<= 1) {
+          dot += __shfl_xor(dot, off);
+          dot2 += __shfl_xor(dot2, off);
+        }
+        s[j] = dot * scale;
+        dp[j] = dot2;
+        smax = fmaxf(smax, s[j]);
+      }
+    }
+    float den = 0.f;
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      s[j] = j < L ? __expf(s[j] - smax) : 0.f;
+      den += s[j];
+    }
+    const float inv = 1.0f / den;
+    float dot_pp = 0.f;
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      s[j] *= inv;                                   // p[i][j]
+      dot_pp += s[j] * dp[j];
+    }
+    float dq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+      if (j < L) {
+        const float ds = s[j] * (dp[j] - dot_pp) * scale;
+        float k[8];
+        unpack8(active ? QKV[(r0 + j) * 3 * n_chunks + n_chunks + c] : zero, k);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          dq[t] += ds * k[t];
+          dk[j][t] += ds * q[t];
+          dv[j][t] += s[j] * go[t];
+        }
+      }
+    }
+    if (active) dQKV[(r0 + i) * 3 * n_chunks + c] = pack8(dq);
+  }
+#pragma unroll
+  for (int j = 0; j < Z2Z_MAX_M; ++j) {
+    if (j < L && active) {
+      dQKV[(r0 + j) * 3 * n_chunks + n_chunks + c] = pack8(dk[j]);
+      dQKV[(r0 + j) * 3 * n_chunks + 2 * n_chunks + c] = pack8(dv[j]);
+    }
+  }
+}
+
+// The gradient at the encoder's input: dE[token of row r] += dX[r] (float atomics: tokens recur), and
+// dP[slot of row r] += dX[r], the latter summed per slot over a stripe of 256 rows in registers first.
+// Grid (ceil(d / 512), ceil(max rows / 256)); a thread owns 8 features and every fourth row of the stripe.
+__global__ void __launch_bounds__(256) enc_input_backward_kernel(RowMap m, const uint4* dX, float* dE, float* dP,
+                                                                 int n_units) {
+  const int n_chunks = m.d / 8;
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rows = m.row0[n_units];
+  const int r_begin = blockIdx.y * 256 + (threadIdx.x >> 6), r_end = min(rows, (int)(blockIdx.y + 1) * 256);
+  if (c >= n_chunks || r_begin >= r_end) return;
+  float acc[Z2Z_MAX_M][8];
+#pragma unroll
+  for (int j = 0; j < Z2Z_MAX_M; ++j)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[j][t] = 0.f;
+  for (int r = r_begin; r < r_end; r += 4) {
+    const int rs = m.row_slot[r];
+    const int i = rs & 7;
+    const int bu = rs >> 3;
+    const int b = bu / m.un, u = bu % m.un;
+    int C;
+    const int e = entry_of(m, b, u, &C);
+    const int tok = min(max(m.ent_tokens[((size_t)b * m.cap + e) * m.M + i], 0), m.V - 1);
+    float g[8];
+    unpack8(dX[(size_t)r * n_chunks + c], g);
+    float* er = dE + (size_t)tok * m.d + (size_t)c * 8;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) atomicAdd(er + t, g[t]);
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc[j][t] += (i == j) ? g[t] : 0.f;
+  }
+  if (dP) {
+#pragma unroll
+    for (int j = 0; j < Z2Z_MAX_M; ++j)
+      if (j < m.M) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) atomicAdd(dP + ((size_t)j * n_chunks + c) * 8 + t, acc[j][t]);
+      }
+  }
+}
+
+__global__ void __launch_bounds__(256) enc_to_bf16_kernel(const float* in, uint16_t* out, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+    out[i] = (uint16_t)bf16_bits_rne(in[i]);
+}
+
+// out[c][r] = in[r][c] (bf16) for r < min(R, *rows_dev), c < C; columns up to ld_out of out beyond that are
+// zero (they pad the contraction of a weight-gradient product).  64 x 64 tiles through LDS, 16 bytes per lane
+// on both sides; grid (ceil(ld_out / 64), ceil(C / 64)).
+__global__ void __launch_bounds__(256) enc_transpose_kernel(const uint16_t* in, uint16_t* out, int R, const int32_t* rows_dev,
+                                                            int C, int ld_in, int ld_out) {
+  __shared__ uint16_t t[64][72];
+  if (rows_dev) R = min(R, *rows_dev);
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;
+    const int r = r0 + i, c = c0 + chunk * 8;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (r < R && c < ld_in) v = *reinterpret_cast<const uint4*>(in + (size_t)r * ld_in + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      t[chunk * 8 + 2 * e][i] = (uint16_t)(w[e] & 0xFFFFu);
+      t[chunk * 8 + 2 * e + 1][i] = (uint16_t)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;
+    const int c = c0 + i, r = r0 + chunk * 8;
+    if (c < C && r < ld_out)
+      *reinterpret_cast<uint4*>(out + (size_t)c * ld_out + r) = *reinterpret_cast<const uint4*>(&t[i][chunk * 8]);
+  }
+}
+
 }  // namespace
 
 bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc) {
@@ -386,6 +737,243 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
                        reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(W_hyper), n_units,
                        incremental ? 0 : 1);
   }
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+namespace {
+
+struct LayerSave {                   // what the training pass keeps of one layer, [rows, .] bf16 each
+  uint16_t *Xin, *A, *QKV, *O, *Y, *N2, *U, *F;
+};
+
+int transpose_to(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out, hipStream_t s) {
+  hipLaunchKernelGGL(enc_transpose_kernel, dim3((ld_out + 63) / 64, (C + 63) / 64), dim3(256), 0, s,
+                     reinterpret_cast<const uint16_t*>(in), reinterpret_cast<uint16_t*>(out), R, rows_dev, C, ld_in,
+                     ld_out);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+void colsum_to(const void* G, int N, int R, const int32_t* rows_dev, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(enc_colsum_kernel, dim3((N / 8 + 63) / 64, (R + 255) / 256), dim3(256), 0, s,
+                     reinterpret_cast<const uint4*>(G), N / 8, rows_dev, out);
+}
+
+unsigned flat_grid(size_t n) {
+  const size_t blocks = (n + 255) / 256;
+  return (unsigned)(blocks < 1 ? 1 : (blocks > 65536 ? 65536 : blocks));
+}
+
+}  // namespace
+
+int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encoder* enc, const void* dW_hyper,
+                                     const z2z_encoder* grad, float* dE, hipStream_t s) {
+  const int B = c->cfg.B, M = c->cfg.M, cap = c->cfg.cap, d = c->cfg.d;
+  if (cap == 0) return Z2Z_OK;
+  const int nl = enc->n_layers;
+  const bool ffn = !enc->attention_only;
+  const int dff = ffn ? enc->d_ff : 0;
+  const int wide = 3 * d > dff ? 3 * d : dff;                   // widest activation
+  long long u_step = 65536 / ((long long)B * M);
+  if (u_step < 1) u_step = 1;
+  if (u_step > cap) u_step = cap;
+  const size_t R_max = (size_t)B * (size_t)u_step * M;
+  const size_t Rp = (R_max + 127) / 128 * 128;                  // contraction length of the weight-gradient products
+  const size_t n_units_max = (size_t)B * (size_t)u_step;
+  const size_t index_bytes = ((n_units_max + 1 + R_max) * sizeof(int32_t) + 255) & ~(size_t)255;
+  const size_t pos_bytes = ((size_t)Z2Z_MAX_M * d * sizeof(float) + 255) & ~(size_t)255;
+  // bf16 elements: per layer what LayerSave names; the running gradients dX dY dN dO (d each), dQKV (3d), dF
+  // (d_ff); two transposed operands [wide, Rp]; one transposed weight
+  const size_t per_layer = R_max * ((size_t)8 * d + (size_t)2 * dff);
+  const size_t elems = (size_t)nl * per_layer + R_max * ((size_t)7 * d + dff) + R_max * d + 2 * (size_t)wide * Rp +
+                       (size_t)wide * d;
+  const size_t need = index_bytes + pos_bytes + elems * 2;
+  if (need > ((size_t)200 << 30)) return Z2Z_ENOMEM;
+  if (need > c->enc_bwd_ws_bytes) {
+    if (c->enc_bwd_ws) (void)hipFree(c->enc_bwd_ws);
+    c->enc_bwd_ws = nullptr;
+    c->enc_bwd_ws_bytes = 0;
+    if (hipMalloc(&c->enc_bwd_ws, need) != hipSuccess) return Z2Z_ENOMEM;
+    c->enc_bwd_ws_bytes = need;
+  }
+  unsigned char* base = reinterpret_cast<unsigned char*>(c->enc_bwd_ws);
+  int32_t* index = reinterpret_cast<int32_t*>(base);
+  float* dP = reinterpret_cast<float*>(base + index_bytes);
+  uint16_t* p = reinterpret_cast<uint16_t*>(base + index_bytes + pos_bytes);
+  auto take = [&](size_t n) {
+    uint16_t* r = p;
+    p += n;
+    return r;
+  };
+  LayerSave sv[Z2Z_MAX_ENCODER_LAYERS];
+  for (int l = 0; l < nl; ++l) {
+    sv[l].Xin = take(R_max * d);
+    sv[l].A = take(R_max * d);
+    sv[l].QKV = take(R_max * 3 * d);
+    sv[l].O = take(R_max * d);
+    sv[l].Y = take(R_max * d);
+    sv[l].N2 = take(R_max * d);
+    sv[l].U = take(R_max * (size_t)dff);
+    sv[l].F = take(R_max * (size_t)dff);
+  }
+  uint16_t* Xout = take(R_max * d);
+  uint16_t* dX = take(R_max * d);
+  uint16_t* dY = take(R_max * d);
+  uint16_t* dN = take(R_max * d);
+  uint16_t* dO = take(R_max * d);
+  uint16_t* dQKV = take(R_max * 3 * d);
+  uint16_t* dF = take(R_max * (size_t)dff);
+  uint16_t* TA = take((size_t)wide * Rp);
+  uint16_t* TB = take((size_t)wide * Rp);
+  uint16_t* WT = take((size_t)wide * d);
+
+  RowMap m;
+  m.size = c->st.size;
+  m.ent_tokens = c->st.ent_tokens;
+  m.ent_len = c->st.ent_len;
+  m.first = nullptr;
+  m.last_n = 0;
+  m.B = B;
+  m.V = c->cfg.V;
+  m.M = M;
+  m.cap = cap;
+  m.d = d;
+  m.row0 = index;
+  m.row_slot = index + n_units_max + 1;
+  const int dh = d / enc->n_heads;
+  const int groups = (d + 511) / 512;
+  const float scale = 1.0f / sqrtf((float)dh);
+
+  // vector gradients are sums over all passes: cleared once, added to by every pass
+  auto clear = [&](const float* q, size_t n) {
+    hipLaunchKernelGGL(enc_fill_kernel, dim3(flat_grid(n)), dim3(256), 0, s, const_cast<float*>(q), n);
+  };
+  for (int l = 0; l < nl; ++l) {
+    const z2z_encoder_layer& g = grad->layers[l];
+    clear(g.ln1_g, d);
+    clear(g.ln1_b, d);
+    clear(g.b_qkv, (size_t)3 * d);
+    clear(g.b_o, d);
+    if (ffn) {
+      clear(g.ln2_g, d);
+      clear(g.ln2_b, d);
+      clear(g.b_1, dff);
+      clear(g.b_2, d);
+    }
+  }
+  clear(dP, (size_t)Z2Z_MAX_M * d);
+
+  int rc;
+#define Z2Z_TRY_RC(expr)      \
+  do {                        \
+    rc = (expr);              \
+    if (rc != Z2Z_OK) return rc; \
+  } while (0)
+
+  int pass = 0;
+  for (int u0 = 0; u0 < cap; u0 += (int)u_step, ++pass) {
+    m.u0 = u0;
+    m.un = (int)(u0 + u_step <= cap ? u_step : cap - u0);
+    const int n_units = B * m.un;
+    const int R = n_units * M;                       // upper bound; the real count is on the device
+    const int Rk = (R + 127) / 128 * 128;            // contraction length of this pass's weight-gradient products
+    const int32_t* rows_dev = m.row0 + n_units;
+    const unsigned row_blocks = (unsigned)((R + 3) / 4);
+    hipLaunchKernelGGL(enc_rows_kernel, dim3(1), dim3(1024), 0, s, m, n_units);
+
+    // ---- forward, keeping every layer's intermediate rows ----
+    for (int l = 0; l < nl; ++l) {
+      const z2z_encoder_layer& lay = enc->layers[l];
+      const LayerSave& v = sv[l];
+      uint16_t* next = l + 1 < nl ? sv[l + 1].Xin : Xout;
+      if (l == 0)
+        hipLaunchKernelGGL(enc_norm_kernel<true>, dim3(row_blocks), dim3(256), 0, s, m,
+                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos),
+                           reinterpret_cast<uint4*>(v.Xin), reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
+      else
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
+                           reinterpret_cast<uint4*>(v.Xin), reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
+      Z2Z_TRY_RC(z2z_launch_linear(c, v.A, lay.w_qkv, lay.b_qkv, nullptr, 0, v.QKV, R, rows_dev, 3 * d, d, s));
+      const long long att_waves = (long long)n_units * groups;
+      hipLaunchKernelGGL(enc_attention_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
+                         reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<uint4*>(v.O), dh / 8, scale, groups,
+                         n_units);
+      uint16_t* y = ffn ? v.Y : next;
+      Z2Z_TRY_RC(z2z_launch_linear(c, v.O, lay.w_o, lay.b_o, v.Xin, 0, y, R, rows_dev, d, d, s));
+      if (ffn) {
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
+                           reinterpret_cast<uint4*>(v.Y), reinterpret_cast<uint4*>(v.N2), lay.ln2_g, lay.ln2_b, n_units);
+        Z2Z_TRY_RC(z2z_launch_linear(c, v.N2, lay.w_1, lay.b_1, nullptr, 0, v.U, R, rows_dev, dff, d, s));
+        hipLaunchKernelGGL(enc_gelu_kernel, dim3(flat_grid((size_t)R * dff / 8)), dim3(256), 0, s,
+                           reinterpret_cast<const uint4*>(v.U), reinterpret_cast<uint4*>(v.F), dff / 8, rows_dev);
+        Z2Z_TRY_RC(z2z_launch_linear(c, v.F, lay.w_2, lay.b_2, v.Y, 0, next, R, rows_dev, d, dff, s));
+      }
+    }
+
+    // ---- backward ----
+    hipLaunchKernelGGL(enc_pool_backward_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
+                       reinterpret_cast<const uint4*>(dW_hyper), reinterpret_cast<uint4*>(dX), n_units);
+    const unsigned nb_blocks = (unsigned)((R + 4 * E_NB_ROWS - 1) / (4 * E_NB_ROWS));
+    for (int l = nl - 1; l >= 0; --l) {
+      const z2z_encoder_layer& lay = enc->layers[l];
+      const z2z_encoder_layer& g = grad->layers[l];
+      const LayerSave& v = sv[l];
+      const void* acc = nullptr;                     // weight gradients of later passes add to the earlier ones
+      uint16_t* dy = dX;                             // gradient at Y (attention layers: the layer's output)
+      if (ffn) {
+        colsum_to(dX, d, R, rows_dev, const_cast<float*>(g.b_2), s);
+        Z2Z_TRY_RC(transpose_to(lay.w_2, WT, d, nullptr, dff, dff, d, s));                        // [dff, d]
+        Z2Z_TRY_RC(z2z_launch_linear(c, dX, WT, nullptr, nullptr, 0, dF, R, rows_dev, dff, d, s));
+        Z2Z_TRY_RC(transpose_to(dX, TA, R, rows_dev, d, d, Rk, s));
+        Z2Z_TRY_RC(transpose_to(v.F, TB, R, rows_dev, dff, dff, Rk, s));
+        acc = pass > 0 ? g.w_2 : nullptr;
+        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_2), d, nullptr, dff, Rk, s));
+        hipLaunchKernelGGL(enc_gelu_backward_kernel, dim3(flat_grid((size_t)R * dff / 8)), dim3(256), 0, s,
+                           reinterpret_cast<uint4*>(dF), reinterpret_cast<const uint4*>(v.U), dff / 8, rows_dev);
+        colsum_to(dF, dff, R, rows_dev, const_cast<float*>(g.b_1), s);
+        Z2Z_TRY_RC(transpose_to(dF, TA, R, rows_dev, dff, dff, Rk, s));
+        Z2Z_TRY_RC(transpose_to(v.N2, TB, R, rows_dev, d, d, Rk, s));
+        acc = pass > 0 ? g.w_1 : nullptr;
+        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_1), dff, nullptr, d, Rk, s));
+        Z2Z_TRY_RC(transpose_to(lay.w_1, WT, dff, nullptr, d, d, dff, s));                        // [d, dff]
+        Z2Z_TRY_RC(z2z_launch_linear(c, dF, WT, nullptr, nullptr, 0, dN, R, rows_dev, d, dff, s));
+        hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(nb_blocks), dim3(256), 0, s, rows_dev, d,
+                           reinterpret_cast<const uint4*>(dN), reinterpret_cast<const uint4*>(v.Y), lay.ln2_g,
+                           reinterpret_cast<const uint4*>(dX), reinterpret_cast<uint4*>(dY),
+                           const_cast<float*>(g.ln2_g), const_cast<float*>(g.ln2_b));
+        dy = dY;
+      }
+      colsum_to(dy, d, R, rows_dev, const_cast<float*>(g.b_o), s);
+      Z2Z_TRY_RC(transpose_to(lay.w_o, WT, d, nullptr, d, d, d, s));
+      Z2Z_TRY_RC(z2z_launch_linear(c, dy, WT, nullptr, nullptr, 0, dO, R, rows_dev, d, d, s));
+      Z2Z_TRY_RC(transpose_to(dy, TA, R, rows_dev, d, d, Rk, s));
+      Z2Z_TRY_RC(transpose_to(v.O, TB, R, rows_dev, d, d, Rk, s));
+      acc = pass > 0 ? g.w_o : nullptr;
+      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_o), d, nullptr, d, Rk, s));
+      const long long att_waves = (long long)n_units * groups;
+      hipLaunchKernelGGL(enc_attention_backward_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
+                         reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<const uint4*>(dO),
+                         reinterpret_cast<uint4*>(dQKV), dh / 8, scale, groups, n_units);
+      colsum_to(dQKV, 3 * d, R, rows_dev, const_cast<float*>(g.b_qkv), s);
+      Z2Z_TRY_RC(transpose_to(dQKV, TA, R, rows_dev, 3 * d, 3 * d, Rk, s));
+      Z2Z_TRY_RC(transpose_to(v.A, TB, R, rows_dev, d, d, Rk, s));
+      acc = pass > 0 ? g.w_qkv : nullptr;
+      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_qkv), 3 * d, nullptr, d, Rk, s));
+      Z2Z_TRY_RC(transpose_to(lay.w_qkv, WT, 3 * d, nullptr, d, d, 3 * d, s));                    // [d, 3d]
+      Z2Z_TRY_RC(z2z_launch_linear(c, dQKV, WT, nullptr, nullptr, 0, dN, R, rows_dev, d, 3 * d, s));
+      hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(nb_blocks), dim3(256), 0, s, rows_dev, d,
+                         reinterpret_cast<const uint4*>(dN), reinterpret_cast<const uint4*>(v.Xin), lay.ln1_g,
+                         reinterpret_cast<const uint4*>(dy), reinterpret_cast<uint4*>(dX),
+                         const_cast<float*>(g.ln1_g), const_cast<float*>(g.ln1_b));
+    }
+    hipLaunchKernelGGL(enc_input_backward_kernel, dim3((d / 8 + 63) / 64, (R + 255) / 256), dim3(256), 0, s, m,
+                       reinterpret_cast<const uint4*>(dX), dE, enc->pos ? dP : nullptr, n_units);
+  }
+#undef Z2Z_TRY_RC
+  if (enc->pos)
+    hipLaunchKernelGGL(enc_to_bf16_kernel, dim3(flat_grid((size_t)M * d)), dim3(256), 0, s, dP,
+                       reinterpret_cast<uint16_t*>(const_cast<void*>(grad->pos)), (size_t)M * d);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

@@ -28,6 +28,7 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->sample_logits);
   (void)hipFree(c->row_max);
   (void)hipFree(c->enc_ws);
+  (void)hipFree(c->enc_bwd_ws);
   (void)hipFree(c->bwd_ws);
   (void)hipFree(c->coef_dev);
   (void)hipFree(c->prune_prefix);
@@ -193,25 +194,46 @@ Z2Z_API int z2z_hyper_embed(z2z_ctx* ctx, const void* d_E, void* d_W_hyper, cons
   return z2z_launch_hyper_embed(ctx, d_E, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
 }
 
-Z2Z_API int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, void* d_W_hyper,
-                             const int32_t* d_first, int32_t max_new, void* stream) {
-  if (!ctx || !d_E || !enc || !enc->layers) return Z2Z_EINVAL;
-  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
-  if (enc->n_layers < 1 || enc->n_layers > Z2Z_MAX_ENCODER_LAYERS) return Z2Z_EINVAL;
-  if (!aligned16(d_E) || !aligned16(d_W_hyper) || !aligned16(enc->pos)) return Z2Z_EINVAL;
+namespace {
+
+// every pointer a layer of the description must carry, present and 16-byte aligned
+bool encoder_pointers_ok(const z2z_encoder* enc) {
+  if (!enc || !enc->layers) return false;
+  if (enc->n_layers < 1 || enc->n_layers > Z2Z_MAX_ENCODER_LAYERS) return false;
+  if (!aligned16(enc->pos)) return false;
   for (int l = 0; l < enc->n_layers; ++l) {
     const z2z_encoder_layer& y = enc->layers[l];
     const void* always[] = {y.ln1_g, y.ln1_b, y.w_qkv, y.b_qkv, y.w_o, y.b_o};
     for (const void* p : always)
-      if (!p || !aligned16(p)) return Z2Z_EINVAL;
+      if (!p || !aligned16(p)) return false;
     if (!enc->attention_only) {
       const void* ffn[] = {y.ln2_g, y.ln2_b, y.w_1, y.b_1, y.w_2, y.b_2};
       for (const void* p : ffn)
-        if (!p || !aligned16(p)) return Z2Z_EINVAL;
+        if (!p || !aligned16(p)) return false;
     }
   }
+  return true;
+}
+
+}  // namespace
+
+Z2Z_API int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, void* d_W_hyper,
+                             const int32_t* d_first, int32_t max_new, void* stream) {
+  if (!ctx || !d_E || !encoder_pointers_ok(enc)) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
   if (!z2z_hyper_encode_ok(ctx, enc)) return Z2Z_EUNSUPPORTED;
   return z2z_launch_hyper_encode(ctx, d_E, enc, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
+}
+
+Z2Z_API int z2z_hyper_encode_backward(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, const void* d_dW_hyper,
+                                      const z2z_encoder* grad, float* d_dE, void* stream) {
+  if (!ctx || !d_E || !d_dE || !encoder_pointers_ok(enc) || !encoder_pointers_ok(grad)) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_dW_hyper) return Z2Z_EINVAL;
+  if (grad->n_layers != enc->n_layers || (enc->pos && !grad->pos)) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_dW_hyper) || !aligned16(d_dE)) return Z2Z_EINVAL;
+  if (!z2z_hyper_encode_ok(ctx, enc)) return Z2Z_EUNSUPPORTED;
+  return z2z_launch_hyper_encode_backward(ctx, d_E, enc, d_dW_hyper, grad, d_dE, static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
