@@ -349,6 +349,23 @@ def run_encoder_workload(args, torch, api, wl):
     rows = int(ctx.codebook()[1].sum().item())        # real slots of the existing entries = rows of the dense layers
     flops = 2.0 * rows * 2 * (4 * d * d + 2 * d * enc["d_ff"])
     weight_bytes = 2 * 2.0 * (4 * d * d + 2 * d * enc["d_ff"])
+    # the encoder's gradient (training f_phi): forward again with every layer's rows kept, then reverse mode;
+    # three dense products per dense layer (forward, input gradient, weight gradient)
+    d_grad = api.Encoder(dict(n_heads=enc["n_heads"], attention_only=False, d_ff=enc["d_ff"],
+                              pos=torch.empty_like(d_enc.params["pos"]),
+                              layers=[{k: torch.empty_like(v) for k, v in lay.items()} for lay in layers]),
+                         torch.bfloat16)
+    d_dW = torch.randn((B, cap, d), device="cuda").to(torch.bfloat16)
+    d_dE = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    ctx.hyper_encode_backward(d_E, d_enc, d_dW, d_grad, d_dE)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(3):
+        ctx.hyper_encode_backward(d_E, d_enc, d_dW, d_grad, d_dE)
+    b.record()
+    torch.cuda.synchronize()
+    ms_bwd = a.elapsed_time(b) / 3
     ctx.close()
     return {
         "workload": f"c2 codebooks ({int(sizes.sum())} entries, {rows} real slots of M={M}), learned hyper-encoder: 2 pre-norm "
@@ -357,6 +374,8 @@ def run_encoder_workload(args, torch, api, wl):
         "frac_of_bf16_peak": flops / (ms_full * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "newest_entry_us": ms_inc * 1e3, "newest_entry_weight_bytes": weight_bytes,
         "newest_entry_GBs": weight_bytes / (ms_inc * 1e-3) / 1e9,
+        "backward_ms": ms_bwd, "backward_dense_flops": 3 * flops,
+        "backward_TFLOPs": 3 * flops / (ms_bwd * 1e-3) / 1e12,
     }
 
 

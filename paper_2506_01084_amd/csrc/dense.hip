@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, i
 }  // namespace
 
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s) {
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev) {
   // between one and a few hundred rows (more than the 64 the decode-step kernel serves per pass over the
   // weights, too few for the tile kernel to have a tile per CU): the tile kernel with K split over workgroups,
   // so that the weights stream once for all rows and every CU has a part
@@ -133,6 +133,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.act = act;
   a.ldo = N;
   a.rows_dev = nullptr;
+  a.k_dev = k_dev;
   if (rows_dev && a.row_tiles >= 16) {
     // the real row count is on the device: what an XCD owns is settled there (see map_rows_dev)
     a.rows_dev = rows_dev;

@@ -318,23 +318,40 @@ __global__ void __launch_bounds__(256) enc_pool_backward_kernel(RowMap m, const 
   }
 }
 
-// out[n] += sum over the pass's rows of G[r, n] (bias gradients).  A thread owns 8 columns and every fourth
-// row of a stripe of 256 rows; grid (ceil(N / 512), ceil(max rows / 256)).
+// (Float sums that several workgroups add to go through the hardware's float atomic add: every target here is
+// ordinary device memory.)
+// out[n] += sum over the pass's rows of G[r, n] (bias gradients).  A thread owns 8 columns and the rows
+// stripe + E_CS_STRIPES * (lane group + 4 i); grid (ceil(N / 512), E_CS_STRIPES): few adds per address.
+constexpr int E_CS_STRIPES = 32;
 __global__ void __launch_bounds__(256) enc_colsum_kernel(const uint4* G, int n_chunks, const int32_t* rows_dev,
                                                          float* out) {
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int rows = *rows_dev;
-  const int r_begin = blockIdx.y * 256 + (threadIdx.x >> 6), r_end = min(rows, (int)(blockIdx.y + 1) * 256);
-  if (c >= n_chunks || r_begin >= r_end) return;
+  if (c >= n_chunks) return;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int r = r_begin; r < r_end; r += 4) {
+  const uint4 zero = {0u, 0u, 0u, 0u};
+  const int step = 4 * E_CS_STRIPES;
+  for (int r = blockIdx.y + E_CS_STRIPES * (threadIdx.x >> 6); r < rows; r += 4 * step) {   // four loads in flight
+    const uint4 q0 = G[(size_t)r * n_chunks + c];
+    const uint4 q1 = r + step < rows ? G[(size_t)(r + step) * n_chunks + c] : zero;
+    const uint4 q2 = r + 2 * step < rows ? G[(size_t)(r + 2 * step) * n_chunks + c] : zero;
+    const uint4 q3 = r + 3 * step < rows ? G[(size_t)(r + 3 * step) * n_chunks + c] : zero;
     float g[8];
-    unpack8(G[(size_t)r * n_chunks + c], g);
+    unpack8(q0, g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] += g[t];
+    unpack8(q1, g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] += g[t];
+    unpack8(q2, g);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] += g[t];
+    unpack8(q3, g);
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] += g[t];
   }
 #pragma unroll
-  for (int t = 0; t < 8; ++t) atomicAdd(out + (size_t)c * 8 + t, acc[t]);
+  for (int t = 0; t < 8; ++t) unsafeAtomicAdd(out + (size_t)c * 8 + t, acc[t]);
 }
 
 __device__ __forceinline__ float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
@@ -369,94 +386,114 @@ __global__ void __launch_bounds__(256) enc_gelu_backward_kernel(uint4* dF, const
 }
 
 // LayerNorm backward: N = (x - mean) * rstd * gamma + beta.  out[r] = dres[r] + dx[r] with
-//   g = dN * gamma;  dx = rstd * (g - mean(g) - xh * mean(g * xh)),  xh = (x - mean) * rstd;
-// dgamma += sum_r dN * xh,  dbeta += sum_r dN.  A wave takes E_NB_ROWS consecutive rows, one at a time (the row
-// held in registers as in the forward kernel), and keeps its share of dgamma / dbeta in registers until the end.
-constexpr int E_NB_ROWS = 16;
+//   g = dN * gamma;  dx = rstd * (g - mean(g) - xh * mean(g * xh)),  xh = (x - mean) * rstd.
+// One wave per row as in the forward kernel: the row of X stays in registers, dN is streamed twice (the second
+// time from cache).  The row's mean and rstd are left in stats[r] for the parameter gradients.
 __global__ void __launch_bounds__(256) enc_norm_backward_kernel(const int32_t* rows_dev, int d, const uint4* dN,
                                                                 const uint4* X, const float* gamma, const uint4* dres,
-                                                                uint4* out, float* dgamma, float* dbeta) {
+                                                                uint4* out, float2* stats) {
   const int lane = threadIdx.x & 63;
-  const int rows = *rows_dev;
-  const int r_begin = (blockIdx.x * 4 + (threadIdx.x >> 6)) * E_NB_ROWS;
-  if (r_begin >= rows) return;
-  const int r_end = min(rows, r_begin + E_NB_ROWS);
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= *rows_dev) return;
   const int n_chunks = d / 8;
   const float inv_d = 1.0f / (float)d;
-  float ag[E_KCH][8], ab[E_KCH][8], gm[E_KCH][8];
-#pragma unroll
-  for (int k = 0; k < E_KCH; ++k) {
-    const int c = lane + 64 * k;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      ag[k][t] = 0.f;
-      ab[k][t] = 0.f;
-      gm[k][t] = c < n_chunks ? gamma[c * 8 + t] : 0.f;
-    }
-  }
-  for (int r = r_begin; r < r_end; ++r) {
-    float x[E_KCH][8], g[E_KCH][8];
-    float sum = 0.f;
-#pragma unroll
-    for (int k = 0; k < E_KCH; ++k) {
-      const int c = lane + 64 * k;
-      if (c < n_chunks) {
-        unpack8(X[(size_t)r * n_chunks + c], x[k]);
-        unpack8(dN[(size_t)r * n_chunks + c], g[k]);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) sum += x[k][t];
-      }
-    }
-    const float mean = wave_sum(sum) * inv_d;
-    float sq = 0.f;
-#pragma unroll
-    for (int k = 0; k < E_KCH; ++k)
-      if (lane + 64 * k < n_chunks) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const float dv = x[k][t] - mean;
-          sq += dv * dv;
-        }
-      }
-    const float rstd = rsqrtf(wave_sum(sq) * inv_d + E_EPS);
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int k = 0; k < E_KCH; ++k)
-      if (lane + 64 * k < n_chunks) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const float xh = (x[k][t] - mean) * rstd;
-          ag[k][t] += g[k][t] * xh;
-          ab[k][t] += g[k][t];
-          x[k][t] = xh;
-          g[k][t] *= gm[k][t];
-          s1 += g[k][t];
-          s2 += g[k][t] * xh;
-        }
-      }
-    const float m1 = wave_sum(s1) * inv_d, m2 = wave_sum(s2) * inv_d;
-#pragma unroll
-    for (int k = 0; k < E_KCH; ++k) {
-      const int c = lane + 64 * k;
-      if (c < n_chunks) {
-        float o[8];
-        unpack8(dres[(size_t)r * n_chunks + c], o);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) o[t] += rstd * (g[k][t] - m1 - x[k][t] * m2);
-        out[(size_t)r * n_chunks + c] = pack8(o);
-      }
-    }
-  }
+  float x[E_KCH][8];
+  float sum = 0.f;
 #pragma unroll
   for (int k = 0; k < E_KCH; ++k) {
     const int c = lane + 64 * k;
     if (c < n_chunks) {
+      unpack8(X[(size_t)r * n_chunks + c], x[k]);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) sum += x[k][t];
+    }
+  }
+  const float mean = wave_sum(sum) * inv_d;
+  float sq = 0.f;
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k)
+    if (lane + 64 * k < n_chunks) {
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        atomicAdd(dgamma + c * 8 + t, ag[k][t]);
-        atomicAdd(dbeta + c * 8 + t, ab[k][t]);
+        const float dv = x[k][t] - mean;
+        sq += dv * dv;
       }
     }
+  const float rstd = rsqrtf(wave_sum(sq) * inv_d + E_EPS);
+  if (lane == 0) stats[r] = float2{mean, rstd};
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k) {
+    const int c = lane + 64 * k;
+    if (c < n_chunks) {
+      float g[8];
+      unpack8(dN[(size_t)r * n_chunks + c], g);
+      const float4 g0 = *reinterpret_cast<const float4*>(gamma + c * 8), g1 = *reinterpret_cast<const float4*>(gamma + c * 8 + 4);
+      const float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float xh = (x[k][t] - mean) * rstd;
+        x[k][t] = xh;
+        s1 += g[t] * gm[t];
+        s2 += g[t] * gm[t] * xh;
+      }
+    }
+  }
+  const float m1 = wave_sum(s1) * inv_d, m2 = wave_sum(s2) * inv_d;
+#pragma unroll
+  for (int k = 0; k < E_KCH; ++k) {
+    const int c = lane + 64 * k;
+    if (c < n_chunks) {
+      float g[8], o[8];
+      unpack8(dN[(size_t)r * n_chunks + c], g);
+      unpack8(dres[(size_t)r * n_chunks + c], o);
+      const float4 g0 = *reinterpret_cast<const float4*>(gamma + c * 8), g1 = *reinterpret_cast<const float4*>(gamma + c * 8 + 4);
+      const float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+      for (int t = 0; t < 8; ++t) o[t] += rstd * (g[t] * gm[t] - m1 - x[k][t] * m2);
+      out[(size_t)r * n_chunks + c] = pack8(o);
+    }
+  }
+}
+
+// dgamma[n] += sum_r dN[r, n] * xh[r, n],  dbeta[n] += sum_r dN[r, n],  xh = (X - mean[r]) * rstd[r]: column sums
+// in the shape of enc_colsum_kernel (a thread owns 8 columns and a strided set of rows).
+__global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* dN, const uint4* X, const float2* stats,
+                                                                  int n_chunks, const int32_t* rows_dev, float* dgamma,
+                                                                  float* dbeta) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rows = *rows_dev;
+  if (c >= n_chunks) return;
+  float ag[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, ab[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int step = 4 * E_CS_STRIPES;
+  for (int r = blockIdx.y + E_CS_STRIPES * (threadIdx.x >> 6); r < rows; r += 2 * step) {   // two rows in flight
+    const bool two = r + step < rows;
+    const int r2 = two ? r + step : r;
+    const uint4 qg0 = dN[(size_t)r * n_chunks + c], qx0 = X[(size_t)r * n_chunks + c];
+    const uint4 qg1 = dN[(size_t)r2 * n_chunks + c], qx1 = X[(size_t)r2 * n_chunks + c];
+    const float2 st0 = stats[r], st1 = stats[r2];
+    float g[8], x[8];
+    unpack8(qg0, g);
+    unpack8(qx0, x);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      ag[t] += g[t] * ((x[t] - st0.x) * st0.y);
+      ab[t] += g[t];
+    }
+    if (two) {
+      unpack8(qg1, g);
+      unpack8(qx1, x);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        ag[t] += g[t] * ((x[t] - st1.x) * st1.y);
+        ab[t] += g[t];
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    unsafeAtomicAdd(dgamma + (size_t)c * 8 + t, ag[t]);
+    unsafeAtomicAdd(dbeta + (size_t)c * 8 + t, ab[t]);
   }
 }
 
@@ -556,14 +593,14 @@ __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, c
 
 // The gradient at the encoder's input: dE[token of row r] += dX[r] (float atomics: tokens recur), and
 // dP[slot of row r] += dX[r], the latter summed per slot over a stripe of 256 rows in registers first.
-// Grid (ceil(d / 512), ceil(max rows / 256)); a thread owns 8 features and every fourth row of the stripe.
-__global__ void __launch_bounds__(256) enc_input_backward_kernel(RowMap m, const uint4* dX, float* dE, float* dP,
+// Grid (ceil(d / 512), ceil(max rows / 256)); a thread owns features f0 + lane + 64 t (t < 8) of a block of 512,
+// so that the 64 lanes of one atomic instruction cover 256 consecutive bytes, and every fourth row of the stripe.
+__global__ void __launch_bounds__(256) enc_input_backward_kernel(RowMap m, const uint16_t* dX, float* dE, float* dP,
                                                                  int n_units) {
-  const int n_chunks = m.d / 8;
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int f0 = blockIdx.x * 512 + (threadIdx.x & 63);
   const int rows = m.row0[n_units];
   const int r_begin = blockIdx.y * 256 + (threadIdx.x >> 6), r_end = min(rows, (int)(blockIdx.y + 1) * 256);
-  if (c >= n_chunks || r_begin >= r_end) return;
+  if (r_begin >= r_end) return;
   float acc[Z2Z_MAX_M][8];
 #pragma unroll
   for (int j = 0; j < Z2Z_MAX_M; ++j)
@@ -578,10 +615,15 @@ __global__ void __launch_bounds__(256) enc_input_backward_kernel(RowMap m, const
     const int e = entry_of(m, b, u, &C);
     const int tok = min(max(m.ent_tokens[((size_t)b * m.cap + e) * m.M + i], 0), m.V - 1);
     float g[8];
-    unpack8(dX[(size_t)r * n_chunks + c], g);
-    float* er = dE + (size_t)tok * m.d + (size_t)c * 8;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) atomicAdd(er + t, g[t]);
+    for (int t = 0; t < 8; ++t) {
+      const int f = f0 + 64 * t;
+      g[t] = f < m.d ? __uint_as_float((uint32_t)dX[(size_t)r * m.d + f] << 16) : 0.f;
+    }
+    float* er = dE + (size_t)tok * m.d;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (f0 + 64 * t < m.d) unsafeAtomicAdd(er + f0 + 64 * t, g[t]);
 #pragma unroll
     for (int j = 0; j < Z2Z_MAX_M; ++j)
 #pragma unroll
@@ -592,7 +634,8 @@ __global__ void __launch_bounds__(256) enc_input_backward_kernel(RowMap m, const
     for (int j = 0; j < Z2Z_MAX_M; ++j)
       if (j < m.M) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) atomicAdd(dP + ((size_t)j * n_chunks + c) * 8 + t, acc[j][t]);
+        for (int t = 0; t < 8; ++t)
+          if (f0 + 64 * t < m.d) unsafeAtomicAdd(dP + (size_t)j * m.d + f0 + 64 * t, acc[j][t]);
       }
   }
 }
@@ -756,7 +799,8 @@ int transpose_to(const void* in, void* out, int R, const int32_t* rows_dev, int 
 }
 
 void colsum_to(const void* G, int N, int R, const int32_t* rows_dev, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(enc_colsum_kernel, dim3((N / 8 + 63) / 64, (R + 255) / 256), dim3(256), 0, s,
+  (void)R;
+  hipLaunchKernelGGL(enc_colsum_kernel, dim3((N / 8 + 63) / 64, E_CS_STRIPES), dim3(256), 0, s,
                      reinterpret_cast<const uint4*>(G), N / 8, rows_dev, out);
 }
 
@@ -788,7 +832,8 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
   const size_t per_layer = R_max * ((size_t)8 * d + (size_t)2 * dff);
   const size_t elems = (size_t)nl * per_layer + R_max * ((size_t)7 * d + dff) + R_max * d + 2 * (size_t)wide * Rp +
                        (size_t)wide * d;
-  const size_t need = index_bytes + pos_bytes + elems * 2;
+  const size_t nb_bytes = (R_max * sizeof(float2) + 255) & ~(size_t)255;   // mean and rstd of every row of a LayerNorm
+  const size_t need = index_bytes + pos_bytes + nb_bytes + elems * 2;
   if (need > ((size_t)200 << 30)) return Z2Z_ENOMEM;
   if (need > c->enc_bwd_ws_bytes) {
     if (c->enc_bwd_ws) (void)hipFree(c->enc_bwd_ws);
@@ -800,7 +845,8 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
   unsigned char* base = reinterpret_cast<unsigned char*>(c->enc_bwd_ws);
   int32_t* index = reinterpret_cast<int32_t*>(base);
   float* dP = reinterpret_cast<float*>(base + index_bytes);
-  uint16_t* p = reinterpret_cast<uint16_t*>(base + index_bytes + pos_bytes);
+  float2* ln_stats = reinterpret_cast<float2*>(base + index_bytes + pos_bytes);
+  uint16_t* p = reinterpret_cast<uint16_t*>(base + index_bytes + pos_bytes + nb_bytes);
   auto take = [&](size_t n) {
     uint16_t* r = p;
     p += n;
@@ -914,7 +960,15 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
     // ---- backward ----
     hipLaunchKernelGGL(enc_pool_backward_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
                        reinterpret_cast<const uint4*>(dW_hyper), reinterpret_cast<uint4*>(dX), n_units);
-    const unsigned nb_blocks = (unsigned)((R + 4 * E_NB_ROWS - 1) / (4 * E_NB_ROWS));
+    auto norm_backward = [&](const uint16_t* dn, const uint16_t* x, const float* gamma, const uint16_t* dres,
+                             uint16_t* out, const float* dgamma, const float* dbeta) {
+      hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(row_blocks), dim3(256), 0, s, rows_dev, d,
+                         reinterpret_cast<const uint4*>(dn), reinterpret_cast<const uint4*>(x), gamma,
+                         reinterpret_cast<const uint4*>(dres), reinterpret_cast<uint4*>(out), ln_stats);
+      hipLaunchKernelGGL(enc_norm_param_grad_kernel, dim3((d / 8 + 63) / 64, E_CS_STRIPES), dim3(256), 0, s,
+                         reinterpret_cast<const uint4*>(dn), reinterpret_cast<const uint4*>(x), ln_stats, d / 8, rows_dev,
+                         const_cast<float*>(dgamma), const_cast<float*>(dbeta));
+    };
     for (int l = nl - 1; l >= 0; --l) {
       const z2z_encoder_layer& lay = enc->layers[l];
       const z2z_encoder_layer& g = grad->layers[l];
@@ -928,20 +982,17 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
         Z2Z_TRY_RC(transpose_to(dX, TA, R, rows_dev, d, d, Rk, s));
         Z2Z_TRY_RC(transpose_to(v.F, TB, R, rows_dev, dff, dff, Rk, s));
         acc = pass > 0 ? g.w_2 : nullptr;
-        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_2), d, nullptr, dff, Rk, s));
+        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_2), d, nullptr, dff, Rk, s, rows_dev));
         hipLaunchKernelGGL(enc_gelu_backward_kernel, dim3(flat_grid((size_t)R * dff / 8)), dim3(256), 0, s,
                            reinterpret_cast<uint4*>(dF), reinterpret_cast<const uint4*>(v.U), dff / 8, rows_dev);
         colsum_to(dF, dff, R, rows_dev, const_cast<float*>(g.b_1), s);
         Z2Z_TRY_RC(transpose_to(dF, TA, R, rows_dev, dff, dff, Rk, s));
         Z2Z_TRY_RC(transpose_to(v.N2, TB, R, rows_dev, d, d, Rk, s));
         acc = pass > 0 ? g.w_1 : nullptr;
-        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_1), dff, nullptr, d, Rk, s));
+        Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_1), dff, nullptr, d, Rk, s, rows_dev));
         Z2Z_TRY_RC(transpose_to(lay.w_1, WT, dff, nullptr, d, d, dff, s));                        // [d, dff]
         Z2Z_TRY_RC(z2z_launch_linear(c, dF, WT, nullptr, nullptr, 0, dN, R, rows_dev, d, dff, s));
-        hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(nb_blocks), dim3(256), 0, s, rows_dev, d,
-                           reinterpret_cast<const uint4*>(dN), reinterpret_cast<const uint4*>(v.Y), lay.ln2_g,
-                           reinterpret_cast<const uint4*>(dX), reinterpret_cast<uint4*>(dY),
-                           const_cast<float*>(g.ln2_g), const_cast<float*>(g.ln2_b));
+        norm_backward(dN, v.Y, lay.ln2_g, dX, dY, g.ln2_g, g.ln2_b);
         dy = dY;
       }
       colsum_to(dy, d, R, rows_dev, const_cast<float*>(g.b_o), s);
@@ -950,7 +1001,7 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
       Z2Z_TRY_RC(transpose_to(dy, TA, R, rows_dev, d, d, Rk, s));
       Z2Z_TRY_RC(transpose_to(v.O, TB, R, rows_dev, d, d, Rk, s));
       acc = pass > 0 ? g.w_o : nullptr;
-      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_o), d, nullptr, d, Rk, s));
+      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_o), d, nullptr, d, Rk, s, rows_dev));
       const long long att_waves = (long long)n_units * groups;
       hipLaunchKernelGGL(enc_attention_backward_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
                          reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<const uint4*>(dO),
@@ -959,16 +1010,13 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
       Z2Z_TRY_RC(transpose_to(dQKV, TA, R, rows_dev, 3 * d, 3 * d, Rk, s));
       Z2Z_TRY_RC(transpose_to(v.A, TB, R, rows_dev, d, d, Rk, s));
       acc = pass > 0 ? g.w_qkv : nullptr;
-      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_qkv), 3 * d, nullptr, d, Rk, s));
+      Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_qkv), 3 * d, nullptr, d, Rk, s, rows_dev));
       Z2Z_TRY_RC(transpose_to(lay.w_qkv, WT, 3 * d, nullptr, d, d, 3 * d, s));                    // [d, 3d]
       Z2Z_TRY_RC(z2z_launch_linear(c, dQKV, WT, nullptr, nullptr, 0, dN, R, rows_dev, d, 3 * d, s));
-      hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(nb_blocks), dim3(256), 0, s, rows_dev, d,
-                         reinterpret_cast<const uint4*>(dN), reinterpret_cast<const uint4*>(v.Xin), lay.ln1_g,
-                         reinterpret_cast<const uint4*>(dy), reinterpret_cast<uint4*>(dX),
-                         const_cast<float*>(g.ln1_g), const_cast<float*>(g.ln1_b));
+      norm_backward(dN, v.Xin, lay.ln1_g, dy, dX, g.ln1_g, g.ln1_b);
     }
-    hipLaunchKernelGGL(enc_input_backward_kernel, dim3((d / 8 + 63) / 64, (R + 255) / 256), dim3(256), 0, s, m,
-                       reinterpret_cast<const uint4*>(dX), dE, enc->pos ? dP : nullptr, n_units);
+    hipLaunchKernelGGL(enc_input_backward_kernel, dim3((d + 511) / 512, (R + 255) / 256), dim3(256), 0, s, m, dX, dE,
+                       enc->pos ? dP : nullptr, n_units);
   }
 #undef Z2Z_TRY_RC
   if (enc->pos)

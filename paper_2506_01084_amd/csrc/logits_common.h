@@ -185,6 +185,9 @@ struct LogitsArgs {
   // part ks covers K slabs [ks * slabs_per_part, ...) and leaves its fp32 tile in partial[ks][row][col]
   int32_t ksplit, slabs_per_part;
   float* partial;           // [ksplit][rows][ldo]
+  // dense layer whose contraction length is only known on the device (a product over the rows of a pass):
+  // K beyond *k_dev, up to the next multiple of 64, holds zeros and the slabs after that are not read
+  const int32_t* k_dev;
 };
 
 // Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
@@ -330,7 +333,7 @@ int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned g
 // (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor
 // written)
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s);
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev = nullptr);
 int z2z_logits_fast_prepare(z2z_ctx* c);
 int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, z2z_logits::LogitsArgs a, const void* W, int w_rows, int col0,
                            int part0, int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed,

@@ -183,8 +183,9 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   const int vt0 = st * a.strip;
   const int vt_end = min(min(vt0 + a.strip, a.n_vtiles), (n_valid + FT - 1) / FT);
   const int n_tiles = vt_end - vt0;          // vocabulary tiles this workgroup sweeps (may be <= 0)
-  const int n_slabs = MODE == 5 ? min(a.slabs_per_part, (int)(row_bytes / F_SLAB) - ks * a.slabs_per_part)
-                                : (int)(row_bytes / F_SLAB);
+  int n_slabs = MODE == 5 ? min(a.slabs_per_part, (int)(row_bytes / F_SLAB) - ks * a.slabs_per_part)
+                          : (int)(row_bytes / F_SLAB);
+  if (MODE == 2 && a.k_dev) n_slabs = max(1, min(n_slabs, (*a.k_dev * 2 + F_SLAB - 1) / F_SLAB));
 
   Triple run[F_NJ];
 #pragma unroll

@@ -152,3 +152,60 @@ def test_backward_accumulates_into_dE_and_overwrites_the_rest():
     assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(),
                                          ctypes.byref(two.desc), dE.data_ptr(), None) == -1
     ctx.close()
+
+
+def test_full_size_c2_two_layer_transformer_sampled_entries():
+    """Configuration 2's codebooks through the backward pass of the encoder the benchmark times (two transformer
+    layers, 32 heads, d_ff = 4 d), in the launch shapes of the full call: dW_hyper is zero except at a few
+    sampled entries, so the gradients are sums over those entries alone, which the oracle computes one by
+    one."""
+    import time
+    import torch
+    from paper_2506_01084_amd import api
+
+    cfg = wl.CONFIGS["c2"]
+    B, V, M, cap, d = cfg["B"], cfg["V"], cfg["M"], cfg["cap"], cfg["d"]
+    t0 = time.time()
+    print("[case] full size hyper_encode_backward c2", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    gpu_encode(ctx, tokens, None)
+    ref = oracle_encode_batch(tokens, np.full(B, cfg["N"], dtype=np.int32), V, M, cap)
+    d_E = torch_storage(E, "bf16")
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=32)
+    d_enc = encoder_to_device(enc, "bf16")
+    d_grad = _grad_buffers(enc)
+    picks = []
+    for b in (0, 3, 7):
+        C = len(ref[b][1])
+        picks += [(b, i) for i in (0, C // 3, C - 1)]
+    dW = np.zeros((B, cap, d), dtype=np.uint16)
+    rows = wl.normal_matrix(31, len(picks), d, 1.0, "bf16")
+    for k, (b, i) in enumerate(picks):
+        dW[b, i] = rows[k]
+    d_dW = torch_storage(dW, "bf16")
+    dE = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    ctx.hyper_encode_backward(d_E, d_enc, d_dW, d_grad, dE)
+    torch.cuda.synchronize()
+    print(f"  GPU pass done {time.time() - t0:.1f}s", flush=True)
+    want = oracle.hyper_encode_backward(E, "bf16", [ref[b][1][i] for b, i in picks], enc,
+                                        oracle.bf16_bits_to_f64(rows))
+    print(f"  oracle done {time.time() - t0:.1f}s", flush=True)
+    worst = {}
+    touched = sorted({t for b, i in picks for t in ref[b][1][i]})
+    got_dE = dE.cpu().numpy()
+    _check("dE rows of the entries' tokens", got_dE[touched], want["dE"][touched], worst)
+    untouched = np.ones(V, dtype=bool)
+    untouched[touched] = False
+    assert (got_dE[untouched] == 0).all()
+    _check("pos", oracle.bf16_bits_to_f64(storage_to_host(d_grad.params["pos"], "bf16")), want["pos"], worst)
+    for l, gl in enumerate(want["layers"]):
+        for k, w in gl.items():
+            t = d_grad.params["layers"][l][k]
+            got = oracle.bf16_bits_to_f64(storage_to_host(t, "bf16")) if k.startswith("w_") else t.cpu().numpy()
+            _check(f"layer {l} {k}", got, w, worst)
+    top = sorted(worst.items(), key=lambda kv: -kv[1][0])[:4]
+    print("  worst tensors (max, mean): " + ", ".join(f"{k} {a:.4f} {m:.5f}" for k, (a, m) in top), flush=True)
+    print(f"  compared {time.time() - t0:.1f}s", flush=True)
+    ctx.close()
