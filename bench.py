@@ -366,6 +366,21 @@ def run_encoder_workload(args, torch, api, wl):
     b.record()
     torch.cuda.synchronize()
     ms_bwd = a.elapsed_time(b) / 3
+    # the same with the rows of a keeping forward call (a training step runs the forward once)
+    ctx.hyper_encode_keep(d_E, d_enc, d_W)
+    ctx.hyper_encode_backward(d_E, d_enc, d_dW, d_grad, d_dE, kept=True)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ms_keep = ms_kept_bwd = 0.0
+    for _ in range(3):
+        ev[0].record()
+        ctx.hyper_encode_keep(d_E, d_enc, d_W)
+        ev[1].record()
+        ctx.hyper_encode_backward(d_E, d_enc, d_dW, d_grad, d_dE, kept=True)
+        ev[2].record()
+        torch.cuda.synchronize()
+        ms_keep += ev[0].elapsed_time(ev[1]) / 3
+        ms_kept_bwd += ev[1].elapsed_time(ev[2]) / 3
     ctx.close()
     return {
         "workload": f"c2 codebooks ({int(sizes.sum())} entries, {rows} real slots of M={M}), learned hyper-encoder: 2 pre-norm "
@@ -376,6 +391,8 @@ def run_encoder_workload(args, torch, api, wl):
         "newest_entry_GBs": weight_bytes / (ms_inc * 1e-3) / 1e9,
         "backward_ms": ms_bwd, "backward_dense_flops": 3 * flops,
         "backward_TFLOPs": 3 * flops / (ms_bwd * 1e-3) / 1e12,
+        "keeping_forward_ms": ms_keep, "backward_on_kept_rows_ms": ms_kept_bwd,
+        "backward_on_kept_rows_TFLOPs": 2 * flops / (ms_kept_bwd * 1e-3) / 1e12,
     }
 
 

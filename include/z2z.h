@@ -216,13 +216,27 @@ int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, 
  *              matrices and pos bf16, vectors float, all overwritten; n_heads, d_ff, attention_only of `grad`
  *              are not read; grad->pos is required when encoder->pos is given
  *   d_dE       [V, d] float, ACCUMULATED into (tokens recur across entries; the caller clears it)
- * The call runs the forward pass again, keeping every layer's rows, then reverse mode over the same steps;
- * activations and gradients between kernels are bf16, sums fp32; passes of up to 65536 slot rows (matrix
- * gradients of later passes add to the bf16 result of the earlier ones).  Work space (about
+ *   flags      0, or Z2Z_ENC_KEPT: use the rows the latest z2z_hyper_encode_keep call on this context left
+ *              instead of running the forward pass again.  The caller guarantees that the codebooks, d_E's
+ *              contents and the encoder's parameters are unchanged since that call; the library checks only that
+ *              such a call was the context's latest use of this work space, with the same d_E and an encoder of
+ *              the same shape (else Z2Z_EINVAL).  A backward call consumes the kept rows.
+ * Without the flag the call runs the forward pass again, keeping every layer's rows, then reverse mode over the
+ * same steps; activations and gradients between kernels are bf16, sums fp32; passes of up to 65536 slot rows
+ * (matrix gradients of later passes add to the bf16 result of the earlier ones).  Work space (about
  * 2 * (n_layers * (8 d + 2 d_ff) + 8 d + d_ff + 2 max(3 d, d_ff)) bytes per slot row) is library scratch,
  * Z2Z_ENOMEM beyond 200 GB.  Restrictions and errors as for z2z_hyper_encode. */
+#define Z2Z_ENC_KEPT 1
 int z2z_hyper_encode_backward(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, const void* d_dW_hyper,
-                              const z2z_encoder* grad, float* d_dE, void* stream);
+                              const z2z_encoder* grad, float* d_dE, int32_t flags, void* stream);
+
+/* z2z_hyper_encode over all entries (d_first = NULL, max_new = 0) for a training step: same network, and the rows
+ * of every layer stay in the work space of z2z_hyper_encode_backward, whose Z2Z_ENC_KEPT flag then skips the
+ * forward pass (a third of its time).  The feed-forward pre-activation is rounded to bf16 before the GELU here
+ * (it is kept for the slope), so results can differ from z2z_hyper_encode's in the last bf16 bit.  Needs all
+ * slot rows in one pass: B * cap * M <= 65536, else Z2Z_EUNSUPPORTED.  Other restrictions, errors and the work
+ * space as for z2z_hyper_encode_backward. */
+int z2z_hyper_encode_keep(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, void* d_W_hyper, void* stream);
 
 /* extended_logits.  For row r of sequence b = r / rows_per_seq:
  *   logit[r, v] = sum_k H[r,k] * W[v,k],  W = W_base for v < V, W_hyper[b, v-V] for V <= v < V + C_b;

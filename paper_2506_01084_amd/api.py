@@ -23,8 +23,9 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 OPT_SAMPLE_KERNEL = 7
 MAX_M = 8
 
+ENC_KEPT = 1
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
-           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
+           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_strerror"]
 
 
@@ -98,7 +99,8 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_hyper_embed.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_hyper_encode.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p, c_int32, c_void_p]
     lib.z2z_hyper_encode_backward.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p,
-                                              POINTER(EncoderDesc), c_void_p, c_void_p]
+                                              POINTER(EncoderDesc), c_void_p, c_int32, c_void_p]
+    lib.z2z_hyper_encode_keep.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_int32,
@@ -250,14 +252,21 @@ class Context:
                                           _ptr(W_hyper, self.torch_dtype), _ptr(first, torch.int32), max_new,
                                           _stream()), "z2z_hyper_encode")
 
+    def hyper_encode_keep(self, E: torch.Tensor, encoder: "Encoder", W_hyper: torch.Tensor) -> None:
+        assert tuple(E.shape) == (self.V, self.d) and tuple(W_hyper.shape) == (self.B, self.cap, self.d)
+        _check(self._lib.z2z_hyper_encode_keep(self._h, _ptr(E, self.torch_dtype), byref(encoder.desc),
+                                               _ptr(W_hyper, self.torch_dtype), _stream()), "z2z_hyper_encode_keep")
+
     def hyper_encode_backward(self, E: torch.Tensor, encoder: "Encoder", dW_hyper: torch.Tensor, grad: "Encoder",
-                              dE: torch.Tensor) -> None:
-        """`grad`: an Encoder built over tensors of the parameters' shapes, which receive the gradients."""
+                              dE: torch.Tensor, kept: bool = False) -> None:
+        """`grad`: an Encoder built over tensors of the parameters' shapes, which receive the gradients.
+        kept=True: use the rows of the preceding hyper_encode_keep call."""
         assert tuple(E.shape) == (self.V, self.d) and tuple(dW_hyper.shape) == (self.B, self.cap, self.d)
         assert tuple(dE.shape) == (self.V, self.d)
         _check(self._lib.z2z_hyper_encode_backward(self._h, _ptr(E, self.torch_dtype), byref(encoder.desc),
                                                    _ptr(dW_hyper, self.torch_dtype), byref(grad.desc),
-                                                   _ptr(dE, torch.float32), _stream()), "z2z_hyper_encode_backward")
+                                                   _ptr(dE, torch.float32), ENC_KEPT if kept else 0, _stream()),
+               "z2z_hyper_encode_backward")
 
     def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
                         argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,

@@ -811,10 +811,14 @@ unsigned flat_grid(size_t n) {
 
 }  // namespace
 
-int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encoder* enc, const void* dW_hyper,
-                                     const z2z_encoder* grad, float* dE, hipStream_t s) {
+// mode 0: forward (rows kept) + backward, pass by pass; mode 1: the forward alone, W_hyper written and the rows
+// left in the work space; mode 2: the backward alone on the rows mode 1 left.  Modes 1 and 2 need all slot rows
+// in one pass.
+int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z_encoder* enc, void* W_hyper,
+                                  const void* dW_hyper, const z2z_encoder* grad, float* dE, hipStream_t s) {
   const int B = c->cfg.B, M = c->cfg.M, cap = c->cfg.cap, d = c->cfg.d;
   if (cap == 0) return Z2Z_OK;
+  if (mode != 0 && (long long)B * cap * M > 65536) return Z2Z_EUNSUPPORTED;
   const int nl = enc->n_layers;
   const bool ffn = !enc->attention_only;
   const int dff = ffn ? enc->d_ff : 0;
@@ -835,6 +839,9 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
   const size_t nb_bytes = (R_max * sizeof(float2) + 255) & ~(size_t)255;   // mean and rstd of every row of a LayerNorm
   const size_t need = index_bytes + pos_bytes + nb_bytes + elems * 2;
   if (need > ((size_t)200 << 30)) return Z2Z_ENOMEM;
+  // the rows a mode-1 call left are those of this encoder's shape only if the layout is the same
+  if (mode == 2 && (!c->enc_kept || c->enc_kept_need != need || c->enc_kept_E != E)) return Z2Z_EINVAL;
+  c->enc_kept = false;
   if (need > c->enc_bwd_ws_bytes) {
     if (c->enc_bwd_ws) (void)hipFree(c->enc_bwd_ws);
     c->enc_bwd_ws = nullptr;
@@ -895,7 +902,7 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
   auto clear = [&](const float* q, size_t n) {
     hipLaunchKernelGGL(enc_fill_kernel, dim3(flat_grid(n)), dim3(256), 0, s, const_cast<float*>(q), n);
   };
-  for (int l = 0; l < nl; ++l) {
+  for (int l = 0; l < nl && mode != 1; ++l) {
     const z2z_encoder_layer& g = grad->layers[l];
     clear(g.ln1_g, d);
     clear(g.ln1_b, d);
@@ -908,7 +915,7 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
       clear(g.b_2, d);
     }
   }
-  clear(dP, (size_t)Z2Z_MAX_M * d);
+  if (mode != 1) clear(dP, (size_t)Z2Z_MAX_M * d);
 
   int rc;
 #define Z2Z_TRY_RC(expr)      \
@@ -926,10 +933,10 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
     const int Rk = (R + 127) / 128 * 128;            // contraction length of this pass's weight-gradient products
     const int32_t* rows_dev = m.row0 + n_units;
     const unsigned row_blocks = (unsigned)((R + 3) / 4);
-    hipLaunchKernelGGL(enc_rows_kernel, dim3(1), dim3(1024), 0, s, m, n_units);
+    if (mode != 2) hipLaunchKernelGGL(enc_rows_kernel, dim3(1), dim3(1024), 0, s, m, n_units);
 
     // ---- forward, keeping every layer's intermediate rows ----
-    for (int l = 0; l < nl; ++l) {
+    for (int l = 0; l < nl && mode != 2; ++l) {
       const z2z_encoder_layer& lay = enc->layers[l];
       const LayerSave& v = sv[l];
       uint16_t* next = l + 1 < nl ? sv[l + 1].Xin : Xout;
@@ -955,6 +962,12 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
                            reinterpret_cast<const uint4*>(v.U), reinterpret_cast<uint4*>(v.F), dff / 8, rows_dev);
         Z2Z_TRY_RC(z2z_launch_linear(c, v.F, lay.w_2, lay.b_2, v.Y, 0, next, R, rows_dev, d, dff, s));
       }
+    }
+
+    if (mode == 1) {
+      hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
+                         reinterpret_cast<const uint4*>(Xout), reinterpret_cast<uint4*>(W_hyper), n_units, 1);
+      continue;
     }
 
     // ---- backward ----
@@ -1019,6 +1032,13 @@ int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encode
                        enc->pos ? dP : nullptr, n_units);
   }
 #undef Z2Z_TRY_RC
+  if (mode == 1) {
+    Z2Z_HIP_TRY(hipGetLastError());
+    c->enc_kept = true;
+    c->enc_kept_need = need;
+    c->enc_kept_E = E;
+    return Z2Z_OK;
+  }
   if (enc->pos)
     hipLaunchKernelGGL(enc_to_bf16_kernel, dim3(flat_grid((size_t)M * d)), dim3(256), 0, s, dP,
                        reinterpret_cast<uint16_t*>(const_cast<void*>(grad->pos)), (size_t)M * d);

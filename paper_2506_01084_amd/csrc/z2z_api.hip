@@ -226,14 +226,25 @@ Z2Z_API int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* e
   return z2z_launch_hyper_encode(ctx, d_E, enc, d_W_hyper, d_first, max_new, static_cast<hipStream_t>(stream));
 }
 
+Z2Z_API int z2z_hyper_encode_keep(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, void* d_W_hyper, void* stream) {
+  if (!ctx || !d_E || !encoder_pointers_ok(enc)) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  if (!z2z_hyper_encode_ok(ctx, enc)) return Z2Z_EUNSUPPORTED;
+  return z2z_launch_hyper_encode_train(ctx, 1, d_E, enc, d_W_hyper, nullptr, nullptr, nullptr,
+                                       static_cast<hipStream_t>(stream));
+}
+
 Z2Z_API int z2z_hyper_encode_backward(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enc, const void* d_dW_hyper,
-                                      const z2z_encoder* grad, float* d_dE, void* stream) {
+                                      const z2z_encoder* grad, float* d_dE, int32_t flags, void* stream) {
   if (!ctx || !d_E || !d_dE || !encoder_pointers_ok(enc) || !encoder_pointers_ok(grad)) return Z2Z_EINVAL;
   if (ctx->cfg.cap > 0 && !d_dW_hyper) return Z2Z_EINVAL;
   if (grad->n_layers != enc->n_layers || (enc->pos && !grad->pos)) return Z2Z_EINVAL;
+  if (flags & ~Z2Z_ENC_KEPT) return Z2Z_EINVAL;
   if (!aligned16(d_E) || !aligned16(d_dW_hyper) || !aligned16(d_dE)) return Z2Z_EINVAL;
   if (!z2z_hyper_encode_ok(ctx, enc)) return Z2Z_EUNSUPPORTED;
-  return z2z_launch_hyper_encode_backward(ctx, d_E, enc, d_dW_hyper, grad, d_dE, static_cast<hipStream_t>(stream));
+  return z2z_launch_hyper_encode_train(ctx, (flags & Z2Z_ENC_KEPT) ? 2 : 0, d_E, enc, nullptr, d_dW_hyper, grad, d_dE,
+                                       static_cast<hipStream_t>(stream));
 }
 
 Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,

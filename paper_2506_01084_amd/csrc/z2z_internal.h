@@ -55,6 +55,9 @@ struct z2z_ctx {
   // backward pass of the loss: dZ, the transposed operand copies (bf16), the row gradients
   void* enc_bwd_ws;        // saved activations and gradients of the learned encoder's backward pass
   size_t enc_bwd_ws_bytes;
+  bool enc_kept;           // the work space holds the rows of a z2z_hyper_encode_keep call ...
+  size_t enc_kept_need;    // ... laid out for this size ...
+  const void* enc_kept_E;  // ... computed from this embedding matrix
   void* bwd_ws;
   size_t bwd_ws_bytes;
   void* prune_prefix;      // codebook pruning: every entry's prefix entry (scratch, [B, cap] int32)
@@ -103,8 +106,8 @@ int z2z_launch_hyper_embed_backward(z2z_ctx* c, const void* dW_hyper, float* dE,
 bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc);
 int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, void* W_hyper, const int32_t* first,
                             int32_t max_new, hipStream_t s);
-int z2z_launch_hyper_encode_backward(z2z_ctx* c, const void* E, const z2z_encoder* enc, const void* dW_hyper,
-                                     const z2z_encoder* grad, float* dE, hipStream_t s);
+int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z_encoder* enc, void* W_hyper,
+                                  const void* dW_hyper, const z2z_encoder* grad, float* dE, hipStream_t s);
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                             const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s);
 

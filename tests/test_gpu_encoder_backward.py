@@ -145,12 +145,86 @@ def test_backward_accumulates_into_dE_and_overwrites_the_rest():
     lib, h = ctx._lib, ctx._h
     import ctypes
     assert lib.z2z_hyper_encode_backward(h, None, ctypes.byref(d_enc.desc), d_dW.data_ptr(),
-                                         ctypes.byref(g1.desc), dE.data_ptr(), None) == -1
+                                         ctypes.byref(g1.desc), dE.data_ptr(), 0, None) == -1
     assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(),
-                                         ctypes.byref(g1.desc), None, None) == -1
+                                         ctypes.byref(g1.desc), None, 0, None) == -1
+    assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(),
+                                         ctypes.byref(g1.desc), dE.data_ptr(), 2, None) == -1        # unknown flag
+    # the kept-rows flag without a preceding hyper_encode_keep
+    assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(),
+                                         ctypes.byref(g1.desc), dE.data_ptr(), api.ENC_KEPT, None) == -1
     two = _grad_buffers(wl.make_encoder(cfg, n_layers=2, n_heads=2, d_ff=128))
     assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(),
-                                         ctypes.byref(two.desc), dE.data_ptr(), None) == -1
+                                         ctypes.byref(two.desc), dE.data_ptr(), 0, None) == -1
+    ctx.close()
+
+
+def test_backward_on_the_rows_a_keeping_forward_left():
+    """hyper_encode_keep writes the same W_hyper as hyper_encode (to the oracle's tolerance; the feed-forward
+    pre-activation is rounded once more) and leaves the rows; backward with the flag gives what backward without
+    it gives (the same kernels on the same rows: equal bits for the matrices), and consumes the rows."""
+    import ctypes
+    import torch
+    from paper_2506_01084_amd import api
+
+    B, N, V, d, M, cap = 3, 300, 1000, 256, 3, 200
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=41)
+    print("[case] hyper_encode_keep + backward on kept rows", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    lens = np.full(B, N, dtype=np.int32)
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16")
+    gpu_encode(ctx, tokens, lens)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    d_E = torch_storage(E, "bf16")
+    enc = wl.make_encoder(cfg, n_layers=2, n_heads=4, d_ff=512)
+    d_enc = encoder_to_device(enc, "bf16")
+    d_dW = torch_storage(wl.normal_matrix(9, B * cap, d, 1.0, "bf16").reshape(B, cap, d), "bf16")
+    g_plain, g_kept = _grad_buffers(enc), _grad_buffers(enc)
+    dE_plain = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    dE_kept = torch.zeros((V, d), dtype=torch.float32, device="cuda")
+    ctx.hyper_encode_backward(d_E, d_enc, d_dW, g_plain, dE_plain)
+    d_W = torch.full((B, cap, d), 5.0, dtype=torch.bfloat16, device="cuda")
+    ctx.hyper_encode_keep(d_E, d_enc, d_W)
+    ctx.hyper_encode_backward(d_E, d_enc, d_dW, g_kept, dE_kept, kept=True)
+    torch.cuda.synchronize()
+    W = storage_to_host(d_W, "bf16")
+    for b in range(B):
+        entries = ref[b][1]
+        want = oracle.hyper_encode(E, "bf16", entries, cap, enc, rounded=False)
+        got = oracle.bf16_bits_to_f64(W[b])
+        scale = np.maximum(1.0, np.abs(want).max(axis=-1, keepdims=True))
+        assert (np.abs(got - want) / scale).max() <= 3e-2                  # the forward test's bar
+        assert (W[b, len(entries):] == 0).all()
+    assert torch.allclose(dE_kept, dE_plain, rtol=1e-3, atol=1e-5)
+    assert torch.equal(g_kept.params["pos"], g_plain.params["pos"]) or torch.allclose(
+        g_kept.params["pos"].float(), g_plain.params["pos"].float(), rtol=2e-2, atol=1e-3)     # (float atomics)
+    for l in range(2):
+        for k in g_plain.params["layers"][l]:
+            a, b_ = g_kept.params["layers"][l][k], g_plain.params["layers"][l][k]
+            if k.startswith("w_"):
+                assert torch.equal(a, b_), (l, k)
+            else:
+                assert torch.allclose(a, b_, rtol=1e-3, atol=1e-4), (l, k)
+    # the rows are consumed: a second backward with the flag is refused; so is one after another encoder shape
+    lib, h = ctx._lib, ctx._h
+    args = (h, d_E.data_ptr(), ctypes.byref(d_enc.desc), d_dW.data_ptr(), ctypes.byref(g_kept.desc),
+            dE_kept.data_ptr(), api.ENC_KEPT, None)
+    assert lib.z2z_hyper_encode_backward(*args) == -1
+    ctx.hyper_encode_keep(d_E, d_enc, d_W)
+    one = wl.make_encoder(cfg, n_layers=1, n_heads=4, d_ff=512)
+    d_one, g_one = encoder_to_device(one, "bf16"), _grad_buffers(one)
+    assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_one.desc), d_dW.data_ptr(),
+                                         ctypes.byref(g_one.desc), dE_kept.data_ptr(), api.ENC_KEPT, None) == -1
+    ctx.close()
+    # more slot rows than one pass holds: keeping is refused (the plain backward takes passes)
+    ctx = api.Context(B=40, V=V, M=3, cap=600, d=64, dtype="bf16")
+    small = wl.make_encoder(dict(cfg, d=64), n_layers=1, n_heads=2, d_ff=64)
+    d_small = encoder_to_device(small, "bf16")
+    E64 = torch.zeros((V, 64), dtype=torch.bfloat16, device="cuda")
+    W64 = torch.zeros((40, 600, 64), dtype=torch.bfloat16, device="cuda")
+    assert ctx._lib.z2z_hyper_encode_keep(ctx._h, E64.data_ptr(), ctypes.byref(d_small.desc), W64.data_ptr(),
+                                          None) == -4        # Z2Z_EUNSUPPORTED
     ctx.close()
 
 
