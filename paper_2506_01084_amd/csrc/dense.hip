@@ -56,7 +56,53 @@ __global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, i
   *reinterpret_cast<uint2*>(out + at) = o;
 }
 
+// out[b][c][r] = in[b][r][c] (bf16) for r < R (and r < *rows_dev when given), c < C; columns up to ld_out of out
+// beyond that are zero (they pad the contraction of a product over rows).  64 x 64 tiles through LDS, 256
+// threads, 16 bytes per lane on both sides (ld_in and ld_out are multiples of 8, the bases 16-byte aligned); grid
+// (ceil(ld_out / 64), ceil(C / 64), batch).
+__global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* in, uint16_t* out, int R, const int32_t* rows_dev,
+                                                             int C, int ld_in, int ld_out, size_t in_batch,
+                                                             size_t out_batch) {
+  __shared__ uint16_t t[64][72];                     // [column of the tile][row of the tile], rows padded
+  if (rows_dev) R = min(R, *rows_dev);
+  const uint16_t* src = in + (size_t)blockIdx.z * in_batch;
+  uint16_t* dst = out + (size_t)blockIdx.z * out_batch;
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;       // 8 chunks of 8 elements per line, 32 lines
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;                     // row of the tile
+    const int r = r0 + i, c = c0 + chunk * 8;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (r < R && c < ld_in) v = *reinterpret_cast<const uint4*>(src + (size_t)r * ld_in + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      t[chunk * 8 + 2 * e][i] = (uint16_t)(w[e] & 0xFFFFu);
+      t[chunk * 8 + 2 * e + 1][i] = (uint16_t)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int i = line + 32 * h;                     // column of the tile = row of the output
+    const int c = c0 + i, r = r0 + chunk * 8;
+    if (c < C && r < ld_out)
+      *reinterpret_cast<uint4*>(dst + (size_t)c * ld_out + r) = *reinterpret_cast<const uint4*>(&t[i][chunk * 8]);
+  }
+}
+
 }  // namespace
+
+int z2z_launch_transpose(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out,
+                         int batch, size_t in_batch, size_t out_batch, hipStream_t s) {
+  if (R < 1 || C < 1 || batch < 1) return Z2Z_OK;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((ld_out + 63) / 64, (C + 63) / 64, batch), dim3(256), 0, s,
+                     reinterpret_cast<const uint16_t*>(in), reinterpret_cast<uint16_t*>(out), R, rows_dev, C, ld_in,
+                     ld_out, in_batch, out_batch);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
 
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev) {

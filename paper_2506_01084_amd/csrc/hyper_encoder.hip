@@ -645,38 +645,6 @@ __global__ void __launch_bounds__(256) enc_to_bf16_kernel(const float* in, uint1
     out[i] = (uint16_t)bf16_bits_rne(in[i]);
 }
 
-// out[c][r] = in[r][c] (bf16) for r < min(R, *rows_dev), c < C; columns up to ld_out of out beyond that are
-// zero (they pad the contraction of a weight-gradient product).  64 x 64 tiles through LDS, 16 bytes per lane
-// on both sides; grid (ceil(ld_out / 64), ceil(C / 64)).
-__global__ void __launch_bounds__(256) enc_transpose_kernel(const uint16_t* in, uint16_t* out, int R, const int32_t* rows_dev,
-                                                            int C, int ld_in, int ld_out) {
-  __shared__ uint16_t t[64][72];
-  if (rows_dev) R = min(R, *rows_dev);
-  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = line + 32 * h;
-    const int r = r0 + i, c = c0 + chunk * 8;
-    uint4 v = {0u, 0u, 0u, 0u};
-    if (r < R && c < ld_in) v = *reinterpret_cast<const uint4*>(in + (size_t)r * ld_in + c);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      t[chunk * 8 + 2 * e][i] = (uint16_t)(w[e] & 0xFFFFu);
-      t[chunk * 8 + 2 * e + 1][i] = (uint16_t)(w[e] >> 16);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = line + 32 * h;
-    const int c = c0 + i, r = r0 + chunk * 8;
-    if (c < C && r < ld_out)
-      *reinterpret_cast<uint4*>(out + (size_t)c * ld_out + r) = *reinterpret_cast<const uint4*>(&t[i][chunk * 8]);
-  }
-}
-
 }  // namespace
 
 bool z2z_hyper_encode_ok(const z2z_ctx* c, const z2z_encoder* enc) {
@@ -791,11 +759,7 @@ struct LayerSave {                   // what the training pass keeps of one laye
 };
 
 int transpose_to(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out, hipStream_t s) {
-  hipLaunchKernelGGL(enc_transpose_kernel, dim3((ld_out + 63) / 64, (C + 63) / 64), dim3(256), 0, s,
-                     reinterpret_cast<const uint16_t*>(in), reinterpret_cast<uint16_t*>(out), R, rows_dev, C, ld_in,
-                     ld_out);
-  Z2Z_HIP_TRY(hipGetLastError());
-  return Z2Z_OK;
+  return z2z_launch_transpose(in, out, R, rows_dev, C, ld_in, ld_out, 1, 0, 0, s);
 }
 
 void colsum_to(const void* G, int N, int R, const int32_t* rows_dev, float* out, hipStream_t s) {

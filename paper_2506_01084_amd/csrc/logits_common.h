@@ -332,6 +332,9 @@ int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned g
 // out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
 // (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor
 // written)
+// bf16 transpose with zero padding of the output rows (see dense.hip)
+int z2z_launch_transpose(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out,
+                         int batch, size_t in_batch, size_t out_batch, hipStream_t s);
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev = nullptr);
 int z2z_logits_fast_prepare(z2z_ctx* c);

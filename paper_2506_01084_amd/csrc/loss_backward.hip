@@ -27,48 +27,6 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(uint4* p, size_t n16) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = z;
 }
 
-// out[b][c][r] = in[b][r][c] (bf16) for r < R, c < C; columns R .. ld_out - 1 of out are zero.  64 x 64 tiles
-// through LDS, 256 threads, 16 bytes per lane on both sides (ld_in and ld_out are multiples of 8, the bases
-// 16-byte aligned); grid (ceil(ld_out / 64), ceil(C / 64), batch).
-__global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* in, uint16_t* out, int R, int C, int ld_in,
-                                                             int ld_out, size_t in_batch, size_t out_batch) {
-  __shared__ uint16_t t[64][72];                     // [column of the tile][row of the tile], rows padded
-  const uint16_t* src = in + (size_t)blockIdx.z * in_batch;
-  uint16_t* dst = out + (size_t)blockIdx.z * out_batch;
-  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;       // 8 chunks of 8 elements per line, 32 lines
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = line + 32 * h;                     // row of the tile
-    const int r = r0 + i, c = c0 + chunk * 8;
-    uint4 v = {0u, 0u, 0u, 0u};
-    if (r < R && c < ld_in) v = *reinterpret_cast<const uint4*>(src + (size_t)r * ld_in + c);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      t[chunk * 8 + 2 * e][i] = (uint16_t)(w[e] & 0xFFFFu);
-      t[chunk * 8 + 2 * e + 1][i] = (uint16_t)(w[e] >> 16);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = line + 32 * h;                     // column of the tile = row of the output
-    const int c = c0 + i, r = r0 + chunk * 8;
-    if (c < C && r < ld_out) *reinterpret_cast<uint4*>(dst + (size_t)c * ld_out + r) = *reinterpret_cast<const uint4*>(&t[i][chunk * 8]);
-  }
-}
-
-int launch_transpose(const void* in, void* out, int R, int C, int ld_in, int ld_out, int batch, size_t in_batch,
-                     size_t out_batch, hipStream_t s) {
-  if (R < 1 || C < 1 || batch < 1) return Z2Z_OK;
-  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((ld_out + 63) / 64, (C + 63) / 64, batch), dim3(256), 0, s,
-                     reinterpret_cast<const uint16_t*>(in), reinterpret_cast<uint16_t*>(out), R, C, ld_in, ld_out,
-                     in_batch, out_batch);
-  Z2Z_HIP_TRY(hipGetLastError());
-  return Z2Z_OK;
-}
-
 // dE[t_j] += a_j * dW_hyper[b, e] for the tokens of every existing entry: one wave per entry, float atomics
 // (tokens recur across entries and sequences).
 __global__ void __launch_bounds__(256) pool_backward_kernel(const uint16_t* dW, float* dE, const int32_t* size,
@@ -175,13 +133,13 @@ int z2z_launch_extended_nll_backward(z2z_ctx* c, const void* H, int32_t rows, in
     if (rc != Z2Z_OK) return rc;
   }
   // ---- transposed copies -------------------------------------------------------------------------------------
-  if ((rc = launch_transpose(W_base, WbT, V, d, d, (int)Vp, 1, 0, 0, s)) != Z2Z_OK) return rc;
-  if ((rc = launch_transpose(H, HT, rows, d, d, (int)rows_p, 1, 0, 0, s)) != Z2Z_OK) return rc;
-  if ((rc = launch_transpose(Pb, PbT, rows, V, (int)Vp, (int)rows_p, 1, 0, 0, s)) != Z2Z_OK) return rc;
+  if ((rc = z2z_launch_transpose(W_base, WbT, V, nullptr, d, d, (int)Vp, 1, 0, 0, s)) != Z2Z_OK) return rc;
+  if ((rc = z2z_launch_transpose(H, HT, rows, nullptr, d, d, (int)rows_p, 1, 0, 0, s)) != Z2Z_OK) return rc;
+  if ((rc = z2z_launch_transpose(Pb, PbT, rows, nullptr, V, (int)Vp, (int)rows_p, 1, 0, 0, s)) != Z2Z_OK) return rc;
   if (cap > 0) {
-    if ((rc = launch_transpose(W_hyper, WhT, cap, d, d, (int)capp, B, (size_t)cap * d, (size_t)d * capp, s)) != Z2Z_OK) return rc;
-    if ((rc = launch_transpose(H, HTs, rows_per_seq, d, d, (int)Np, B, (size_t)rows_per_seq * d, (size_t)d * Np, s)) != Z2Z_OK) return rc;
-    if ((rc = launch_transpose(Ph, PhT, rows_per_seq, cap, (int)capp, (int)Np, B, (size_t)rows_per_seq * capp, (size_t)cap * Np, s)) != Z2Z_OK) return rc;
+    if ((rc = z2z_launch_transpose(W_hyper, WhT, cap, nullptr, d, d, (int)capp, B, (size_t)cap * d, (size_t)d * capp, s)) != Z2Z_OK) return rc;
+    if ((rc = z2z_launch_transpose(H, HTs, rows_per_seq, nullptr, d, d, (int)Np, B, (size_t)rows_per_seq * d, (size_t)d * Np, s)) != Z2Z_OK) return rc;
+    if ((rc = z2z_launch_transpose(Ph, PhT, rows_per_seq, nullptr, cap, (int)capp, (int)Np, B, (size_t)rows_per_seq * capp, (size_t)cap * Np, s)) != Z2Z_OK) return rc;
   }
   // ---- the products --------------------------------------------------------------------------------------------
   if ((rc = z2z_launch_linear(c, Pb, WbT, nullptr, nullptr, 0, dH, rows, nullptr, d, (int)Vp, s)) != Z2Z_OK) return rc;
