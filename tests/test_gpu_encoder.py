@@ -56,6 +56,7 @@ def _setup(cfg, lens):
     (2, 150, 400, 256, 3, 64, 2, 4, 512, False, True),         # 384 slot rows: the few-rows kernel for the layers
     (1, 100, 300, 384, 4, 20, 1, 6, 1152, False, True),        # 80 rows, K = 384 and 1152 (3 and 9 slices of 128)
     (2, 300, 600, 1024, 3, 40, 2, 8, 2048, False, True),       # 240 rows, K = 1024 and 2048: the tile kernel with K split
+    (4, 400, 800, 512, 3, 70, 1, 4, 1024, False, True),        # 840 slot rows at most, few tiles: K split beyond 512 rows
 ])
 def test_hyper_encode_matches_oracle_every_entry(B, N, V, d, M, cap, n_layers, n_heads, d_ff, attn_only, with_pos):
     import torch
