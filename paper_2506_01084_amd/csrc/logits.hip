@@ -251,6 +251,12 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
     a.map_ls = m ? ((m >> 8) & 0xFF) : 8;
     a.map_xr = m ? ((m >> 16) & 0xFF) : 4;
     a.map_xs = m ? ((m >> 24) & 0xFF) : 2;
+    if (!m && a.row_tiles < 16) {
+      // few row tiles: the XCDs share out the strips alone (split over row tiles, most of them would idle)
+      a.map_xr = 1;
+      a.map_xs = 8;
+      a.map_lr = a.row_tiles >= 4 ? 4 : (a.row_tiles >= 2 ? 2 : 1);
+    }
     const int sb_rows = a.map_xr * a.map_lr, sb_strips = a.map_xs * a.map_ls;
     a.map_sb_r = (a.row_tiles + sb_rows - 1) / sb_rows;
     const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;
@@ -291,16 +297,25 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
 
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
   const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
-  bool fast_base = fast_ok && rows > 128;
-  bool fast_hyper = fast_ok && rows_per_seq > 128;
+  // (the general kernel is many times slower per tile: even a tile with a few valid rows goes to the tile kernel)
+  bool fast_base = fast_ok, fast_hyper = fast_ok;
   if (c->opt_logits_kernel == 1) fast_base = fast_hyper = false;
-  if (c->opt_logits_kernel >= 2) fast_base = fast_hyper = fast_ok;
-  const int strip = c->opt_logits_strip > 0 ? c->opt_logits_strip : 4;
 
-  // number of parts (strips of both launches), then the scratch for them
+  // number of parts (strips of both launches), then the scratch for them.  A workgroup sweeps a strip of 4
+  // weight tiles with its rows' tile resident; with few row tiles that leaves CUs idle, so the strips shorten
+  // until there are two workgroups per CU (or one tile per workgroup)
   const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;
-  const int base_strips = (((V + base_tile - 1) / base_tile) + strip - 1) / strip;
-  const int hyp_strips = cap > 0 ? (((cap + hyp_tile - 1) / hyp_tile) + strip - 1) / strip : 0;
+  const int base_vt = (V + base_tile - 1) / base_tile, hyp_vt = (cap + hyp_tile - 1) / hyp_tile;
+  auto pick_strip = [&](long long row_tiles, int n_vt) {
+    if (c->opt_logits_strip > 0) return c->opt_logits_strip;
+    int st = 4;
+    while (st > 1 && row_tiles * ((n_vt + st - 1) / st) < 512) st >>= 1;
+    return st;
+  };
+  const int strip_b = pick_strip((rows + base_tile - 1) / base_tile, base_vt);
+  const int strip_h = pick_strip((long long)c->cfg.B * ((rows_per_seq + hyp_tile - 1) / hyp_tile), hyp_vt);
+  const int base_strips = (base_vt + strip_b - 1) / strip_b;
+  const int hyp_strips = cap > 0 ? (hyp_vt + strip_h - 1) / strip_h : 0;
   const int n_parts = base_strips + hyp_strips;
   int rc = ensure_scratch(c, (size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
@@ -319,10 +334,10 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
 
   int ns = 0;
-  rc = z2z_launch_logits_part(c, false, fast_base, a, W_base, V, 0, 0, strip, rows, rows_per_seq, &ns, timed, s);
+  rc = z2z_launch_logits_part(c, false, fast_base, a, W_base, V, 0, 0, strip_b, rows, rows_per_seq, &ns, timed, s);
   if (rc != Z2Z_OK) return rc;
   if (cap > 0) {
-    rc = z2z_launch_logits_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip, rows, rows_per_seq, &ns, false, s);
+    rc = z2z_launch_logits_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip_h, rows, rows_per_seq, &ns, false, s);
     if (rc != Z2Z_OK) return rc;
     if (logits) {
       hipLaunchKernelGGL(logits_mask_kernel, dim3(rows), dim3(256), 0, s, logits, rows, rows_per_seq, V, cap,

@@ -278,6 +278,47 @@ def test_full_size_prefill_sampled_rows(name, per_seq):
     ctx.close()
 
 
+@pytest.mark.parametrize("rows_per_seq", [2, 5, 40])
+def test_full_size_few_rows_per_sequence_c3(rows_per_seq):
+    """Config 3's codebooks with a few hidden rows per sequence (a verification step of several drafted codes, a
+    chunk of a prefill): the tile kernels with short strips and the few-row-tile workgroup mapping.  Sampled rows
+    over all columns against the oracle, size-independent properties on every row."""
+    import torch
+
+    cfg = wl.CONFIGS["c3"]
+    t0 = time.time()
+    print(f"[case] full size c3 codebooks, {rows_per_seq} rows per sequence", flush=True)
+    tokens = wl.make_tokens(cfg)
+    E = wl.make_embeddings(cfg)
+    B = cfg["B"]
+    rows = B * rows_per_seq
+    H = wl.make_hidden(cfg, rows)
+    ctx, w = _make_ctx(cfg)
+    ref = _encode(ctx, cfg, tokens)
+    d_E, d_W = _embed_gpu(ctx, cfg, E)
+    seqs = [0, 17, B - 1]
+    refW, worst = _check_embed(cfg, ref, E, d_W, w, seqs=seqs)
+    d_H = torch_storage(H, cfg["dtype"])
+    am = torch.empty(rows, dtype=torch.int32, device="cuda")
+    mx = torch.empty(rows, dtype=torch.float32, device="cuda")
+    lse = torch.empty(rows, dtype=torch.float32, device="cuda")
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_W, am, mx, lse, None)
+    torch.cuda.synchronize()
+    am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(mx_h).all() and np.isfinite(lse_h).all() and (lse_h >= mx_h - 1e-4).all()
+    size = ctx.codebook()[2].cpu().numpy()
+    for b in range(B):
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        assert (am_h[sl] >= 0).all() and (am_h[sl] < cfg["V"] + size[b]).all()
+        assert (lse_h[sl] <= mx_h[sl] + np.log(cfg["V"] + size[b]) + 1e-3).all()
+    for b in seqs:
+        pick = np.arange(b * rows_per_seq, (b + 1) * rows_per_seq)[[0, rows_per_seq - 1]]
+        r = oracle.extended_logits(H[pick], E, refW[b], len(ref[b][1]), cfg["dtype"], return_logits=True)
+        errs = check_logits_rows(r, am_h[pick], mx_h[pick], lse_h[pick], None)
+        print(f"  seq {b}: first and last row, errors {errs}  {time.time() - t0:.1f}s", flush=True)
+    ctx.close()
+
+
 def test_full_size_decode_step_c3():
     """Config 3: 64 sequences with an 8192-token history, one code per sequence, one hidden row each."""
     import torch
