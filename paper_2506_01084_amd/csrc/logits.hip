@@ -280,8 +280,14 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const int V = c->cfg.V, cap = c->cfg.cap;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
 
-  // decode step: one hidden row per sequence -> the bandwidth-bound kernel (it can store the logits too)
-  if (rows_per_seq == 1 && c->decode_ready && c->opt_decode_kernel != 1) {
+  // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
+  const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
+  // decode step: one hidden row per sequence -> the bandwidth-bound kernel (it can store the logits too).
+  // Its base units serve 64 rows per pass over W_base, each pass at about the cost of the first; beyond two
+  // passes the tile kernel takes the base vocabulary (all rows at once) and only the hyper units run here
+  const bool decode_step = rows_per_seq == 1 && c->decode_ready && c->opt_decode_kernel != 1;
+  const bool decode_split = decode_step && fast_ok && rows > 128 && c->opt_logits_kernel != 1;
+  if (decode_step && !decode_split) {
     int n_parts = z2z_logits_decode_parts(c);
     int rc = ensure_scratch(c, (size_t)n_parts * rows);
     if (rc != Z2Z_OK) return rc;
@@ -295,8 +301,6 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
   }
 
-  // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
-  const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
   // (the general kernel is many times slower per tile: even a tile with a few valid rows goes to the tile kernel)
   bool fast_base = fast_ok, fast_hyper = fast_ok;
   if (c->opt_logits_kernel == 1) fast_base = fast_hyper = false;
@@ -315,7 +319,12 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const int strip_b = pick_strip((rows + base_tile - 1) / base_tile, base_vt);
   const int strip_h = pick_strip((long long)c->cfg.B * ((rows_per_seq + hyp_tile - 1) / hyp_tile), hyp_vt);
   const int base_strips = (base_vt + strip_b - 1) / strip_b;
-  const int hyp_strips = cap > 0 ? (hyp_vt + strip_h - 1) / strip_h : 0;
+  int hyp_strips = cap > 0 ? (hyp_vt + strip_h - 1) / strip_h : 0;
+  if (decode_split) {
+    int base_columns, hyper_columns;
+    z2z_logits_decode_units(&base_columns, &hyper_columns);
+    hyp_strips = (cap + hyper_columns - 1) / hyper_columns;
+  }
   const int n_parts = base_strips + hyp_strips;
   int rc = ensure_scratch(c, (size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
@@ -336,7 +345,11 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   int ns = 0;
   rc = z2z_launch_logits_part(c, false, fast_base, a, W_base, V, 0, 0, strip_b, rows, rows_per_seq, &ns, timed, s);
   if (rc != Z2Z_OK) return rc;
-  if (cap > 0) {
+  if (cap > 0 && decode_split) {
+    int np = 0;
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, nullptr, nullptr, s, base_strips);
+    if (rc != Z2Z_OK) return rc;
+  } else if (cap > 0) {
     rc = z2z_launch_logits_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip_h, rows, rows_per_seq, &ns, false, s);
     if (rc != Z2Z_OK) return rc;
     if (logits) {

@@ -461,19 +461,16 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
     hyper_unit<MODE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
     const int bu = bid - n_hyper;
-    if (MODE == 3) {
-      // workgroup ids go round-robin over the 8 XCDs: the row groups of one unit get ids 8 apart, so they run
-      // on one XCD at about the same time and its L2 serves the unit's weights to all but the first of them
-      const int units8 = (a.n_base_units + 7) >> 3;
-      const int q = bu >> 3;
-      const int group = q % a.n_groups;
-      const int rest = q / a.n_groups;
-      const int unit = (rest % units8) * 8 + (bu & 7);
-      if (unit >= a.n_base_units) return;
-      base_unit<MODE>(a, unit, group, rest / units8, lds);
-    } else {
-      base_unit<MODE>(a, bu % a.n_base_units, bu / a.n_base_units, 0, lds);
-    }
+    // workgroup ids go round-robin over the 8 XCDs: the row groups of one unit get ids 8 apart, so they run
+    // on one XCD at about the same time and its L2 serves the unit's weights to all but the first of them
+    // (one group, i.e. up to 64 rows: unit = bu)
+    const int units8 = (a.n_base_units + 7) >> 3;
+    const int q = bu >> 3;
+    const int group = q % a.n_groups;
+    const int rest = q / a.n_groups;
+    const int unit = (rest % units8) * 8 + (bu & 7);
+    if (unit >= a.n_base_units) return;
+    base_unit<MODE>(a, unit, group, MODE == 3 ? rest / units8 : 0, lds);
   }
 }
 
@@ -509,7 +506,8 @@ __global__ void __launch_bounds__(D_THREADS) linear_reduce_kernel(DecodeArgs a) 
 // `logits` it stores every logit it computes, row-major [B, V + cap] (divided by the temperature when `sample`
 // is given as well: the partials are then those of the scaled logits, and nothing is drawn).
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
-                             bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s) {
+                             bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s,
+                             int hyper_only_base_parts) {
   DecodeArgs a;
   a.H = reinterpret_cast<const uint4*>(H);
   a.W_base = reinterpret_cast<const uint4*>(W_base);
@@ -536,7 +534,15 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.ctr3 = sample ? (uint32_t)(sample->step >> 32) : 0u;
   *n_parts = a.n_base_units + a.units_per_seq;
   a.n_parts = *n_parts;
-  const unsigned grid = (unsigned)(a.n_base_units * a.n_groups + a.B * a.units_per_seq);
+  unsigned grid = (unsigned)(8 * ((a.n_base_units + 7) / 8) * a.n_groups + a.B * a.units_per_seq);
+  if (hyper_only_base_parts >= 0) {
+    // the hyper units alone: workgroup ids below B * units_per_seq; their parts start behind the base parts
+    a.n_base_units = hyper_only_base_parts;
+    *n_parts = a.n_base_units + a.units_per_seq;
+    a.n_parts = *n_parts;
+    grid = (unsigned)(a.B * a.units_per_seq);
+    if (grid == 0) return Z2Z_OK;
+  }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
   if (logits)                                         // with `sample`: stored and folded as logit / temperature
     hipLaunchKernelGGL(logits_decode_kernel<2>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);

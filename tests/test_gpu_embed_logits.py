@@ -378,7 +378,10 @@ def test_full_size_decode_step_c3():
 @pytest.mark.parametrize("B,N,V,d,M,cap", [
     (65, 300, 1000, 3072, 3, 300),      # two row groups, the second with one row
     (3, 200, 777, 128, 4, 0),           # no codebook at all
-    (130, 400, 513, 3584, 5, 1030),     # three groups; cap spans three hyper units, the last ragged
+    (130, 400, 513, 3584, 5, 1030),     # three groups; cap spans three hyper units, the last ragged (beyond 128
+                                        # rows the base vocabulary goes to the tile kernel, the hyper units stay)
+    (140, 100, 400, 256, 3, 0),         # the same split with no codebook at all
+    (300, 120, 2000, 512, 3, 100),      # two row tiles of the tile kernel, 300 hyper units
     (1, 5000, 50000, 256, 2, 600),      # one row
     (64, 64, 300, 4096, 3, 512),        # widest d the kernel takes
 ])
