@@ -119,6 +119,18 @@ def test_many_sequences_per_call(B):
     _check_encode_decode(cfg, tokens, lens)
 
 
+@pytest.mark.parametrize("B,N", [(200, 700), (700, 2100)])
+def test_many_long_sequences_on_the_four_wave_kernels(B, N):
+    """Hundreds of sequences of 512 tokens or more still take four waves each (several workgroups per CU, the
+    smaller tables): ragged lengths across every window boundary, results unchanged."""
+    cfg = wl.scaled(wl.CONFIGS["c4"], B=B, N=N, V=900, cap=700, seed=B + N)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg, ragged=True)
+    lens[:8] = [N, 0, 1, 255, 256, 257, 512, min(N, 1025)]
+    print(f"[case] lzw four-wave kernels B={B} N={N}", flush=True)
+    _check_encode_decode(cfg, tokens, lens)
+
+
 def test_largest_ids_capacity_and_merge_size():
     """The limits of the ID packing: V + cap = 2^24, cap = 65535, M = 8 (codes and tokens up to 2^24 - 1 in
     the hash slots, entry indices up to 65534, the table in global memory)."""
