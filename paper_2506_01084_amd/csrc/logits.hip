@@ -263,7 +263,7 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
     grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
   }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (hyper ? 1 : 0), a, grid, s)
+  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? 6 : (hyper ? 1 : 0)), a, grid, s)
                 : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
@@ -272,6 +272,16 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
   return rc;
 }
 
+
+
+// A workgroup sweeps a strip of 4 weight tiles with its rows' tile resident; with few row tiles that leaves CUs
+// idle, so the strips shorten until there are two workgroups per CU (or one tile per workgroup).
+static int pick_strip_for(const z2z_ctx* c, long long row_tiles, int n_vt) {
+  if (c->opt_logits_strip > 0) return c->opt_logits_strip;
+  int st = 4;
+  while (st > 1 && row_tiles * ((n_vt + st - 1) / st) < 512) st >>= 1;
+  return st;
+}
 
 
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
@@ -310,12 +320,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   // until there are two workgroups per CU (or one tile per workgroup)
   const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;
   const int base_vt = (V + base_tile - 1) / base_tile, hyp_vt = (cap + hyp_tile - 1) / hyp_tile;
-  auto pick_strip = [&](long long row_tiles, int n_vt) {
-    if (c->opt_logits_strip > 0) return c->opt_logits_strip;
-    int st = 4;
-    while (st > 1 && row_tiles * ((n_vt + st - 1) / st) < 512) st >>= 1;
-    return st;
-  };
+  auto pick_strip = [&](long long row_tiles, int n_vt) { return pick_strip_for(c, row_tiles, n_vt); };
   const int strip_b = pick_strip((rows + base_tile - 1) / base_tile, base_vt);
   const int strip_h = pick_strip((long long)c->cfg.B * ((rows_per_seq + hyp_tile - 1) / hyp_tile), hyp_vt);
   const int base_strips = (base_vt + strip_b - 1) / strip_b;
@@ -330,6 +335,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   if (rc != Z2Z_OK) return rc;
 
   LogitsArgs a;
+  memset(&a, 0, sizeof(a));
   a.H = H;
   a.rows = rows;
   a.rows_per_seq = rows_per_seq;
@@ -374,6 +380,51 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   sp.seed = seed;
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
+  if (top_k <= 0 && top_p >= 1.0f && rows > 128 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
+    // no filter, more than two passes of the decode kernel's base units: as for the argmax, the tile kernel takes
+    // the base vocabulary (with the draw folded into its epilogue) and the hyper units run alone
+    const int base_vt = (c->cfg.V + 255) / 256;
+    const int strip_b = pick_strip_for(c, (rows + 255) / 256, base_vt);
+    const int base_strips = (base_vt + strip_b - 1) / strip_b;
+    int base_columns, hyper_columns;
+    z2z_logits_decode_units(&base_columns, &hyper_columns);
+    n_parts = base_strips + (c->cfg.cap + hyper_columns - 1) / hyper_columns;
+    rc = ensure_scratch(c, (size_t)n_parts * rows);
+    if (rc != Z2Z_OK) return rc;
+    rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
+    if (rc != Z2Z_OK) return rc;
+    LogitsArgs a;
+    memset(&a, 0, sizeof(a));
+    a.H = H;
+    a.rows = rows;
+    a.rows_per_seq = 1;
+    a.d = c->cfg.d;
+    a.part_m = c->part_m;
+    a.part_s = c->part_s;
+    a.part_i = c->part_i;
+    a.part_v = c->part_v;
+    a.part_l = c->part_l;
+    a.n_parts = n_parts;
+    a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
+    a.sample = 1;
+    a.inv_temperature = 1.0f / temperature;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.ctr2 = (uint32_t)step;
+    a.ctr3 = (uint32_t)(step >> 32);
+    int ns = 0;
+    rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
+    if (rc != Z2Z_OK) return rc;
+    if (c->cfg.cap > 0) {
+      int np = 0;
+      rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, &sp, nullptr, s, base_strips);
+      if (rc != Z2Z_OK) return rc;
+    }
+    hipLaunchKernelGGL(sample_combine_kernel, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_v,
+                       c->part_l, c->part_i, n_parts, rows, token, logprob);
+    Z2Z_HIP_TRY(hipGetLastError());
+    return Z2Z_OK;
+  }
   if (top_k <= 0 && top_p >= 1.0f) {
     // no filter: the draw is folded into the kernel that computes the logits, which are never stored
     rc = ensure_sample_scratch(c, (size_t)n_parts * rows);

@@ -45,6 +45,25 @@ __device__ __forceinline__ void merge_triple(Triple& a, const Triple& b) {
   a.i = b_wins ? b.i : a.i;
 }
 
+// The running best of a Gumbel-max draw.
+struct Draw {
+  float v;   // largest perturbed value so far
+  float l;   // logit / T at that column
+  int i;     // that column
+};
+
+__device__ __forceinline__ Draw empty_draw() {
+  Draw d;
+  d.v = kNegInf;
+  d.l = 0.f;
+  d.i = kNoColumn;
+  return d;
+}
+
+__device__ __forceinline__ void merge_draw(Draw& a, const Draw& b) {
+  if (b.v > a.v || (b.v == a.v && b.i < a.i)) a = b;
+}
+
 // One accumulator element, AGPR -> VGPR.  Spelled as an instruction so that the accumulators stay in
 // the accumulation registers and are fetched block by block: left to itself the compiler copies the whole
 // accumulator tile into VGPRs at the end of the K loop, and what that displaces is spilled inside the loop.
@@ -185,10 +204,70 @@ struct LogitsArgs {
   // part ks covers K slabs [ks * slabs_per_part, ...) and leaves its fp32 tile in partial[ks][row][col]
   int32_t ksplit, slabs_per_part;
   float* partial;           // [ksplit][rows][ldo]
+  // sampling fold (base part of a sampled decode step with many rows): the triples are taken over
+  // logit * inv_temperature, and next to them the largest perturbed value (part_v), the scaled logit there
+  // (part_l) and its column (part_i, instead of the maximum's); generator key and counter words as in the
+  // decode kernel: word col & 3 of Philox4x32-10 at counter (col >> 2, row, ctr2, ctr3)
+  int32_t sample;
+  float inv_temperature;
+  uint32_t key0, key1, ctr2, ctr3;
+  float* part_v;
+  float* part_l;
   // dense layer whose contraction length is only known on the device (a product over the rows of a pass):
   // K beyond *k_dev, up to the next multiple of 64, holds zeros and the slabs after that are not read
   const int32_t* k_dev;
 };
+
+// fold_tile for a sampled pick: the same register layout; x = logit * inv_temperature enters the running triple,
+// and x + Gumbel(u[row, col]) the running draw.  A lane's columns come in aligned fours (one generator call
+// each) and in increasing order, so a strict comparison keeps the lowest column among equal values.  The four
+// groups of a 32 x 32 block are a real loop (the generator is long: unrolled 256 times per tile it would not fit
+// the register file next to the accumulators).
+template <int NI, int NJ>
+__device__ __forceinline__ void fold_tile_sample(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], Draw (&draw)[NJ],
+                                                 const LogitsArgs& a, int row_base, int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const uint32_t row = (uint32_t)(row_base + j * 32 + lane31);
+    Triple t = run[j];
+    Draw dr = draw[j];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float x[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) x[v] = read_acc(acc[i][j][v]);
+#pragma unroll 1
+      for (int q = 0; q < 4; ++q) {
+        const int c0 = a.col0 + col_base + i * 32 + q * 8;
+        const uint4 w = philox4x32_10(uint4{(uint32_t)(c0 >> 2), row, a.ctr2, a.ctr3}, a.key0, a.key1);
+        const uint32_t word[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float xv = q == 0 ? x[k] : (q == 1 ? x[4 + k] : (q == 2 ? x[8 + k] : x[12 + k]));
+          // (columns past the last valid one: -inf never enters the triple or wins the draw)
+          const bool ok = c0 - a.col0 + k < n_valid;
+          const float z = ok ? xv * a.inv_temperature : kNegInf;
+          if (z > t.m) {
+            t.s = (t.m == kNegInf) ? 1.f : t.s * __expf(t.m - z) + 1.f;
+            t.m = z;
+            t.i = c0 + k;
+          } else if (ok) {
+            t.s += __expf(z - t.m);
+          }
+          const float pv = z + gumbel_from_word(word[k]);
+          if (pv > dr.v) {
+            dr.v = pv;
+            dr.l = z;
+            dr.i = c0 + k;
+          }
+        }
+      }
+    }
+    run[j] = t;
+    draw[j] = dr;
+  }
+}
 
 // Store one finished accumulator tile as a dense layer's output (same register layout as fold_tile):
 // out[row, col] = act(acc + bias[col]) + residual[row, col], rounded once to bf16.  A lane holds runs of 4

@@ -93,24 +93,6 @@ __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
 //      softmax).  Gumbel-max: the column that maximises logit / T - ln(-ln u) is distributed as
 //      softmax(logit / T); u comes from Philox4x32-10 (Salmon et al., SC'11) with counter
 //      (column >> 2, hidden row, step) and key = seed, so a draw is a pure function of its coordinates.
-struct Draw {
-  float v;   // largest perturbed value so far
-  float l;   // logit / T at that column
-  int i;     // that column
-};
-
-__device__ __forceinline__ Draw empty_draw() {
-  Draw d;
-  d.v = kNegInf;
-  d.l = 0.f;
-  d.i = kNoColumn;
-  return d;
-}
-
-__device__ __forceinline__ void merge_draw(Draw& a, const Draw& b) {
-  if (b.v > a.v || (b.v == a.v && b.i < a.i)) a = b;
-}
-
 // Generator words for the columns 4 * group .. 4 * group + 3 of one hidden row are produced together;
 // a thread that walks consecutive columns keeps them until it leaves the group.
 struct Noise {

@@ -188,8 +188,12 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   if (MODE == 2 && a.k_dev) n_slabs = max(1, min(n_slabs, (*a.k_dev * 2 + F_SLAB - 1) / F_SLAB));
 
   Triple run[F_NJ];
+  Draw draw[F_NJ];                                   // MODE 6 only
 #pragma unroll
-  for (int j = 0; j < F_NJ; ++j) run[j] = empty_triple();
+  for (int j = 0; j < F_NJ; ++j) {
+    run[j] = empty_triple();
+    draw[j] = empty_draw();
+  }
 
   // ---- loader: lane l of wave w, instruction i moves the chunk that lands at LDS byte
   //      ((w * F_PAIRS + i) * 8 + (l >> 3)) * 128 + (l & 7) * 16 of the operand tile; offsets are relative to
@@ -346,15 +350,17 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       else if (MODE == 5)
         store_partial_tile<F_NI, F_NJ>(acc, a.partial + (size_t)ks * a.rows * a.ldo, a.ldo, r0 + wr * (F_NJ * 32), r_end,
                                        v0 + wv * 128 + half * 4, n_valid);
-      else if (MODE >= 3)
+      else if (MODE == 3 || MODE == 4)
         store_prob_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      else if (MODE == 6)
+        fold_tile_sample<F_NI, F_NJ>(acc, run, draw, a, r0 + wr * (F_NJ * 32), v0 + wv * 128 + half * 4, n_valid);
       else
         fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
       zero_acc();
     }
   }
 
-  if (MODE >= 2) {
+  if (MODE >= 2 && MODE <= 5) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the requests past the end of the stream land in LDS
     return;
   }
@@ -366,14 +372,25 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     o.s = __shfl_xor(run[j].s, 32);
     o.i = __shfl_xor(run[j].i, 32);
     merge_triple(run[j], o);
+    if (MODE == 6) {
+      Draw od;
+      od.v = __shfl_xor(draw[j].v, 32);
+      od.l = __shfl_xor(draw[j].l, 32);
+      od.i = __shfl_xor(draw[j].i, 32);
+      merge_draw(draw[j], od);
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the requests past the end of the stream too
   __syncthreads();                                 // every wave is done with the operand stages
   Triple* xch = reinterpret_cast<Triple*>(lds);    // [256 hidden rows of the tile]
+  Draw* xdr = reinterpret_cast<Draw*>(xch + FT);
   const int hrow0 = wr * (F_NJ * 32);
   if (wv == 1 && lane < 32) {
 #pragma unroll
-    for (int j = 0; j < F_NJ; ++j) xch[hrow0 + j * 32 + lane] = run[j];
+    for (int j = 0; j < F_NJ; ++j) {
+      xch[hrow0 + j * 32 + lane] = run[j];
+      if (MODE == 6) xdr[hrow0 + j * 32 + lane] = draw[j];
+    }
   }
   __syncthreads();
   if (wv == 0 && lane < 32) {
@@ -385,7 +402,14 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         const size_t p = (size_t)hrow * a.n_parts + a.part0 + st;
         a.part_m[p] = run[j].m;
         a.part_s[p] = run[j].s;
-        a.part_i[p] = run[j].i;
+        if (MODE == 6) {
+          merge_draw(draw[j], xdr[hrow0 + j * 32 + lane]);
+          a.part_v[p] = draw[j].v;
+          a.part_l[p] = draw[j].l;
+          a.part_i[p] = draw[j].i;
+        } else {
+          a.part_i[p] = run[j].i;
+        }
       }
     }
   }
@@ -394,7 +418,9 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 5)
+  if (mode == 6)
+    hipLaunchKernelGGL(logits_fast_kernel<6>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 5)
     hipLaunchKernelGGL(logits_fast_kernel<5>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 4)
     hipLaunchKernelGGL(logits_fast_kernel<4>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -423,6 +449,8 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<4>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<5>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<6>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

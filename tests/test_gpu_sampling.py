@@ -58,7 +58,9 @@ def _setup(cfg, lens=None):
 @pytest.mark.parametrize("B,N,V,d,M,cap", [
     (65, 300, 1000, 256, 3, 300),
     (5, 200, 777, 128, 4, 0),
-    (130, 400, 513, 384, 5, 1030),
+    (130, 400, 513, 384, 5, 1030),      # beyond 128 rows: the draw folded into the tile kernel (base), hyper units
+    (300, 150, 2300, 256, 3, 90),       # two row tiles, ragged column tail, every sequence one hyper unit
+    (140, 100, 700, 128, 3, 0),         # the same with no codebook
     (2, 3000, 40000, 4096, 3, 700),
 ])
 def test_draws_match_oracle_every_row(B, N, V, d, M, cap):
