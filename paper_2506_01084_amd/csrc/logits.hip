@@ -263,7 +263,7 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
     grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
   }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? 6 : (hyper ? 1 : 0)), a, grid, s)
+  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? (a.sample == 2 ? 7 : 6) : (hyper ? 1 : 0)), a, grid, s)
                 : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
@@ -452,12 +452,50 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
       return Z2Z_ENOMEM;
     c->sample_logits_capacity = need;
   }
-  rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, c->sample_logits, s);
-  if (rc != Z2Z_OK) return rc;
+  int base_columns = 0;                              // of a base part: the decode kernel's unit unless set
+  if (rows > 128 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
+    // more than two passes of the decode kernel's base units: the tile kernel stores and folds the base
+    // vocabulary's scaled logits, the hyper units run alone (strips of at most 2 tiles: the selection kernels'
+    // short-list pass takes parts of up to 512 columns)
+    const int base_vt = (c->cfg.V + 255) / 256;
+    int strip_b = pick_strip_for(c, (rows + 255) / 256, base_vt);
+    if (strip_b > 2) strip_b = 2;
+    const int base_strips = (base_vt + strip_b - 1) / strip_b;
+    int unit_base, unit_hyper;
+    z2z_logits_decode_units(&unit_base, &unit_hyper);
+    n_parts = base_strips + (c->cfg.cap + unit_hyper - 1) / unit_hyper;
+    base_columns = strip_b * 256;
+    LogitsArgs a;
+    memset(&a, 0, sizeof(a));
+    a.H = H;
+    a.rows = rows;
+    a.rows_per_seq = 1;
+    a.d = c->cfg.d;
+    a.part_m = c->part_m;
+    a.part_s = c->part_s;
+    a.part_i = c->part_i;
+    a.n_parts = n_parts;
+    a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
+    a.sample = 2;
+    a.inv_temperature = 1.0f / temperature;
+    a.logits = c->sample_logits;
+    a.ld = c->cfg.V + c->cfg.cap;
+    int ns = 0;
+    rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
+    if (rc != Z2Z_OK) return rc;
+    if (c->cfg.cap > 0) {
+      int np = 0;
+      rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, &sp, c->sample_logits, s, base_strips);
+      if (rc != Z2Z_OK) return rc;
+    }
+  } else {
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, c->sample_logits, s);
+    if (rc != Z2Z_OK) return rc;
+  }
   rc = launch_combine(c, n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
   if (rc != Z2Z_OK) return rc;
   return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, n_parts, c->row_max + 2 * (size_t)rows, &sp,
-                                     top_k, top_p, token, logprob, s);
+                                     top_k, top_p, token, logprob, s, base_columns);
 }
 
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,

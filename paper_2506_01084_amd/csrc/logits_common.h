@@ -208,7 +208,7 @@ struct LogitsArgs {
   // logit * inv_temperature, and next to them the largest perturbed value (part_v), the scaled logit there
   // (part_l) and its column (part_i, instead of the maximum's); generator key and counter words as in the
   // decode kernel: word col & 3 of Philox4x32-10 at counter (col >> 2, row, ctr2, ctr3)
-  int32_t sample;
+  int32_t sample;         // 1: fold the draw (part_v, part_l); 2: store logit * inv_temperature in `logits` and fold
   float inv_temperature;
   uint32_t key0, key1, ctr2, ctr3;
   float* part_v;
@@ -217,6 +217,61 @@ struct LogitsArgs {
   // K beyond *k_dev, up to the next multiple of 64, holds zeros and the slabs after that are not read
   const int32_t* k_dev;
 };
+
+// fold_tile for a filtered sampled pick: x = logit * inv_temperature enters the running triple and is stored,
+// fp32, at logits[row, col0 + column] (the selection kernels read the rows back); 16-byte stores where the four
+// columns of a group all exist.
+template <int NI, int NJ>
+__device__ __forceinline__ void fold_tile_store(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], const LogitsArgs& a,
+                                                int row_base, int r_end, int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+    float* out = a.logits + (size_t)min(row, r_end - 1) * a.ld + a.col0;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float x[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = col_base + i * 32 + (v >> 2) * 8 + (v & 3);
+        x[v] = col < n_valid ? read_acc(acc[i][j][v]) * a.inv_temperature : kNegInf;
+      }
+      float gmax = x[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) gmax = fmaxf(gmax, x[v]);
+      if (gmax > run[j].m) {
+        int targ = 15;
+#pragma unroll
+        for (int v = 14; v >= 0; --v) targ = (x[v] == gmax) ? v : targ;
+        run[j].s = (run[j].m == kNegInf) ? 0.f : run[j].s * __expf(run[j].m - gmax);
+        run[j].m = gmax;
+        run[j].i = a.col0 + col_base + i * 32 + (targ >> 2) * 8 + (targ & 3);
+      }
+      if (run[j].m != kNegInf) {
+        const float m = run[j].m;
+        float add = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) add += __expf(x[v] - m);
+        run[j].s += add;
+      }
+      if (row < r_end) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = col_base + i * 32 + q * 8;
+          // (a row of the logits starts 4-byte aligned only: ld = V + cap is any number)
+          if (col + 3 < n_valid && ((((size_t)row * a.ld + a.col0 + col) & 3) == 0)) {
+            *reinterpret_cast<float4*>(out + col) = float4{x[q * 4], x[q * 4 + 1], x[q * 4 + 2], x[q * 4 + 3]};
+          } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              if (col + k < n_valid) out[col + k] = x[q * 4 + k];
+          }
+        }
+      }
+    }
+  }
+}
 
 // fold_tile for a sampled pick: the same register layout; x = logit * inv_temperature enters the running triple,
 // and x + Gumbel(u[row, col]) the running draw.  A lane's columns come in aligned fours (one generator call
@@ -435,7 +490,7 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 // log-sum-exps, of those values; `work` is scratch of z2z_sample_truncated_work_floats(rows) floats.
 int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
                                 float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
-                                int32_t* token, float* logprob, hipStream_t s);
+                                int32_t* token, float* logprob, hipStream_t s, int base_columns = 0);
 size_t z2z_sample_truncated_work_floats(int32_t rows);
 // the same layer on the bandwidth-bound kernel of the decode step (few rows: every weight byte is read once per
 // 64 rows); K a multiple of 128, N even

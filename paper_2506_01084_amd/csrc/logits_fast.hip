@@ -354,6 +354,8 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         store_prob_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
       else if (MODE == 6)
         fold_tile_sample<F_NI, F_NJ>(acc, run, draw, a, r0 + wr * (F_NJ * 32), v0 + wv * 128 + half * 4, n_valid);
+      else if (MODE == 7)
+        fold_tile_store<F_NI, F_NJ>(acc, run, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
       else
         fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
       zero_acc();
@@ -418,7 +420,9 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 6)
+  if (mode == 7)
+    hipLaunchKernelGGL(logits_fast_kernel<7>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 6)
     hipLaunchKernelGGL(logits_fast_kernel<6>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 5)
     hipLaunchKernelGGL(logits_fast_kernel<5>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -451,6 +455,8 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<5>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<6>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<7>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

@@ -792,7 +792,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
 
 int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
                                 float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
-                                int32_t* token, float* logprob, hipStream_t s) {
+                                int32_t* token, float* logprob, hipStream_t s, int base_columns) {
   (void)sp->temperature;                             // the stored values are scaled already
   TruncArgs a;
   a.logits = logits;
@@ -802,6 +802,7 @@ int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* ro
   a.part_m = c->part_m;
   a.n_parts = n_parts;
   z2z_logits_decode_units(&a.base_columns, &a.hyper_columns);
+  if (base_columns > 0) a.base_columns = base_columns;   // the base parts came from another kernel's strips
   a.n_base_parts = (c->cfg.V + a.base_columns - 1) / a.base_columns;
   a.V = c->cfg.V;
   a.cap = c->cfg.cap;

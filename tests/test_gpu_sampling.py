@@ -246,6 +246,8 @@ def _check_truncated(logits_row, T, k, p, seed, step, row, tok, lp):
     (65, 300, 1000, 256, 3, 300),
     (6, 3000, 40000, 512, 3, 700),          # rows long enough for several histogram passes; 159 parts
     (9, 2000, 9000, 256, 3, 1500),          # 36 base parts and 3 hyper parts
+    (150, 200, 3001, 256, 3, 200),          # beyond 128 rows: the tile kernel stores the base vocabulary's logits
+    (700, 60, 2100, 128, 3, 40),            # three row tiles: base parts of two tiles (512 columns) each
 ])
 def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_only):
     """Both ways of finding the kept prefix: the short list built from the parts with the largest maxima
