@@ -293,10 +293,10 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
   const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
   // decode step: one hidden row per sequence -> the bandwidth-bound kernel (it can store the logits too).
-  // Its base units serve 64 rows per pass over W_base, each pass at about the cost of the first; beyond two
-  // passes the tile kernel takes the base vocabulary (all rows at once) and only the hyper units run here
+  // Its base units serve 64 rows per pass over W_base, each pass at about the cost of the first; from the second
+  // pass on the tile kernel takes the base vocabulary (all rows at once) and only the hyper units run here
   const bool decode_step = rows_per_seq == 1 && c->decode_ready && c->opt_decode_kernel != 1;
-  const bool decode_split = decode_step && fast_ok && rows > 128 && c->opt_logits_kernel != 1;
+  const bool decode_split = decode_step && fast_ok && rows > 64 && c->opt_logits_kernel != 1;
   if (decode_step && !decode_split) {
     int n_parts = z2z_logits_decode_parts(c);
     int rc = ensure_scratch(c, (size_t)n_parts * rows);
@@ -381,8 +381,9 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
   if (top_k <= 0 && top_p >= 1.0f && rows > 128 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
-    // no filter, more than two passes of the decode kernel's base units: as for the argmax, the tile kernel takes
-    // the base vocabulary (with the draw folded into its epilogue) and the hyper units run alone
+    // no filter, more than two passes of the decode kernel's base units (the generator in the tile kernel's
+    // epilogue costs more than the second pass): as for the argmax, the tile kernel takes the base vocabulary
+    // (with the draw folded into its epilogue) and the hyper units run alone
     const int base_vt = (c->cfg.V + 255) / 256;
     const int strip_b = pick_strip_for(c, (rows + 255) / 256, base_vt);
     const int base_strips = (base_vt + strip_b - 1) / strip_b;
@@ -453,8 +454,8 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     c->sample_logits_capacity = need;
   }
   int base_columns = 0;                              // of a base part: the decode kernel's unit unless set
-  if (rows > 128 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
-    // more than two passes of the decode kernel's base units: the tile kernel stores and folds the base
+  if (rows > 64 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
+    // more than one pass of the decode kernel's base units: the tile kernel stores and folds the base
     // vocabulary's scaled logits, the hyper units run alone (strips of at most 2 tiles: the selection kernels'
     // short-list pass takes parts of up to 512 columns)
     const int base_vt = (c->cfg.V + 255) / 256;
