@@ -340,3 +340,46 @@ def test_full_size_c3_truncated():
             print(f"  T={T} k={k} p={p} seq {b}: token {tok_h[b]} logprob {lp_h[b]:.4f} decided {ok}  {time.time() - t0:.1f}s",
                   flush=True)
     ctx.close()
+
+
+def test_many_sequences_picks_replay_in_a_graph():
+    """Beyond 128 sequences the pick runs as tile kernel (base vocabulary) + hyper units + merge: the three picks
+    (argmax, draw, filtered draw) captured once after an eager call, replayed three times with eager work in
+    between, give the eager results every time (nothing is allocated or cleared by the host in between)."""
+    import torch
+
+    B, N, V, d, M, cap = 200, 120, 3001, 256, 3, 70
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=77)
+    print("[case] picks for 200 sequences, eager and graph", flush=True)
+    ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, wl.make_lens(cfg))
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+
+    def bufs():
+        return (torch.empty(B, **i32), torch.empty(B, **f32), torch.empty(B, **f32), torch.empty(B, **i32),
+                torch.empty(B, **f32), torch.empty(B, **i32), torch.empty(B, **f32))
+
+    def picks(o):
+        ctx.extended_logits(d_H, 1, d_E, d_W, o[0], o[1], o[2], None)
+        ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 11, 5, o[3], o[4])
+        ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 11, 6, o[5], o[6], top_k=40, top_p=0.9)
+
+    eager = bufs()
+    picks(eager)
+    torch.cuda.synchronize()
+    out = bufs()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        picks(out)
+    for rep in range(3):
+        for t in out:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in (0, 3, 5):
+            assert torch.equal(out[k], eager[k]), f"replay {rep}: pick {k} differs from the eager call"
+        for k in (1, 2, 4, 6):
+            assert torch.equal(out[k], eager[k]), f"replay {rep}: value {k} differs from the eager call"
+        assert np.isfinite(torch.randn(1 << 18, device="cuda").sum().item())        # eager work between replays
+    ctx.close()
