@@ -292,6 +292,20 @@ def run_decode_workload(args, torch, api, wl):
     torch.cuda.synchronize()
     learned_us = (time.perf_counter() - t0) * 1e6 / timed
     assert int(d_st.abs().sum()) == 0
+    # the same steps as one HIP graph (the newest-entry pass of the encoder is some 25 short kernels per step)
+    am_learned = d_am.clone()
+    side2 = torch.cuda.Stream()
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph2, stream=side2):
+        for s in range(args.warmup, n_steps):
+            step_learned(s)
+    graph2.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    graph2.replay()
+    torch.cuda.synchronize()
+    learned_graph_us = (time.perf_counter() - t0) * 1e6 / timed
+    assert int(d_st.abs().sum()) == 0 and torch.equal(d_am, am_learned), "graph replay differs from the eager steps"
 
     sizes = size_view.cpu().numpy()
     us = dt * 1e6 / timed
@@ -302,7 +316,7 @@ def run_decode_workload(args, torch, api, wl):
     k_gbs = bytes_step / (k_us * 1e-6) / 1e9
     return dict(workload=cfg["name"], steps=timed, us_per_step=us, graph_us_per_step=graph_us,
                 graph_frac=bytes_step / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
-                sample_topk50_topp09_us_per_step=filtered_us, learned_encoder_us_per_step=learned_us,
+                sample_topk50_topp09_us_per_step=filtered_us, learned_encoder_us_per_step=learned_us, learned_encoder_graph_us_per_step=learned_graph_us,
                 sample_us_per_step=sample_us, sample_frac=bytes_step / (sample_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
                 peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()),
                 roofline={"bound": "hbm", "kernel": "logits_decode_kernel (64 rows, config 3)", "achieved": k_gbs,
