@@ -76,7 +76,9 @@ struct Table {
     return bucket >= nb ? bucket - nb : bucket;
   }
   __device__ __forceinline__ u64 load(uint32_t pos) const {
-    const u64 v = LDS ? lds_slots[pos] : g[pos];
+    // (the global table is read past the vector L1 everywhere: slots are claimed with atomics, which do not
+    // update that cache, so a line it holds can be stale)
+    const u64 v = LDS ? lds_slots[pos] : __hip_atomic_load(&g[pos], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // every lane reads the same address; readfirstlane keeps the chain in scalar registers
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
@@ -86,7 +88,7 @@ struct Table {
     if (LDS)
       lds_slots[pos] = v;
     else
-      g[pos] = v;
+      __hip_atomic_store(&g[pos], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   // Returns the entry index, or -1 with *free_pos = the empty slot the probe ended at (-1 if the
   // table has no empty slot, which cannot happen while n > cap).
@@ -483,6 +485,15 @@ struct WideShared {
 };
 constexpr int kWideStaticLds = kTokBuf * 4 + kWideFilter * 8 + (int)sizeof(WideShared) + 512;   // + alignment slack
 
+// A workgroup barrier that other waves' reads PAST the vector L1 may rely on.  Between the waves of a workgroup
+// plain stores and plain loads are ordered by the L1 they share, and the barrier does not wait for the stores
+// to leave it; a load that goes straight to L2 (load_fresh, the table's atomic loads) could overtake a store of
+// another wave that is still on its way there.  So the stores are awaited before the barrier.
+__device__ __forceinline__ void sync_after_global_stores() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
 template <bool LDS>
 __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) {
   __shared__ int32_t tokbuf[kTokBuf];
@@ -516,7 +527,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
   }
   for (int i = tid; i < kWideFilter; i += kWideLanes) filter[i] = kEmpty;
   if (tid == 0) sh.cut = kWideLanes;
-  __syncthreads();
+  sync_after_global_stores();        // (the table cleared in global memory is read past the L1)
 
   const int n = call_length(a, b);
   const int32_t* in = a.in + (size_t)b * a.stride;
@@ -532,7 +543,8 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
     const int32_t c = __builtin_amdgcn_readfirstlane(in[0]);
     if (c >= 0 && c < V) {
       int free_pos = -1;
-      const int idx = t.find(prev, c, &free_pos);              // every wave finds the same
+      const int idx = t.find(prev, c, &free_pos);
+      __syncthreads();     // every wave has looked before wave 0 inserts (else a late wave finds the new edge)
       if (idx < 0 && free_pos >= 0) {
         if (w == 0) {
           int32_t ph = -1;
@@ -546,7 +558,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
         ++C;
       }
     }
-    __syncthreads();
+    sync_after_global_stores();
   }
 
   const u64 lanes_below = (1ull << lane) - 1;
@@ -724,7 +736,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
       sh.valid_mask[w] = valid_mask;
       sh.ins_mask[w] = ins_mask;
     }
-    __syncthreads();
+    sync_after_global_stores();
     if (tid == 0) sh.cut = kWideLanes;              // everybody has read it; next written after two more barriers
     int last_w = -1;
     for (int ww = 0; ww < kWide; ++ww) {
@@ -1205,7 +1217,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
   }
   for (int i = tid; i < kWideFilter; i += kWideLanes) filter[i] = kEmpty;
   if (tid == 0) sh.cut = kWideLanes;
-  __syncthreads();
+  sync_after_global_stores();        // (the table cleared in global memory is read past the L1)
 
   const int n = call_length(a, b);
   const int32_t* in = a.in + (size_t)b * a.stride;
@@ -1261,13 +1273,15 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
 
     if (hard_pos == 1) {
       // the first code of the round names no entry of the codebook as it stands: "previous phrase + its own
-      // first token", legal and absent, or an error.  Every wave takes the same decisions; wave 0 stores.
+      // first token", legal and absent, or an error.  Every wave takes the same decisions (hence the barrier between the
+      // lookup and the store); wave 0 stores.
       const int32_t k1 = sh.k1;
       bool ok = false;
       if (k1 >= V && k1 - V == C && prev >= 0 && prev_len < M && C < cap) {
         const int32_t pf = sh.first0;
         int free_pos = -1;
         const int idx = t.find(prev, pf, &free_pos);
+        __syncthreads();   // every wave has looked before wave 0 stores (else a late wave finds the new edge)
         if (idx < 0 && free_pos >= 0) {
           const int cur_len = prev_len + 1;
           if (out != nullptr && n_out + cur_len > a.out_stride) {
@@ -1299,7 +1313,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
         status |= Z2Z_ST_BAD_CODE;
         stop = true;
       }
-      __syncthreads();
+      sync_after_global_stores();
       continue;
     }
 
@@ -1426,7 +1440,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
       sh.last_len = len;
       sh.last_incl = incl;
     }
-    __syncthreads();
+    sync_after_global_stores();
     for (int ww = 0; ww < kWide; ++ww) C += sh.ins_cnt[ww];
     if (limit >= 2) {
       prev = sh.last_k;
@@ -1437,7 +1451,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
       stop = true;
     }
     if (tid == 0) sh.cut = kWideLanes;
-    __syncthreads();                  // rows written above are in memory, the exchange area is free
+    sync_after_global_stores();                  // rows written above are in memory, the exchange area is free
   }
 
   if (LDS) {

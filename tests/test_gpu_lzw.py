@@ -131,6 +131,44 @@ def test_many_long_sequences_on_the_four_wave_kernels(B, N):
     _check_encode_decode(cfg, tokens, lens)
 
 
+@pytest.mark.parametrize("B,V,M,cap,N", [(700, 300, 3, 500, 2100), (1024, 70000, 8, 3000, 4097)])
+def test_four_wave_kernels_with_many_workgroups_in_flight_are_deterministic(B, V, M, cap, N):
+    """Hundreds of four-wave workgroups at once (table in LDS for 700 sequences, in global memory for 1024), on
+    streams of short runs whose codebooks fill up early: the code of the round that names the entry being made
+    is handled by all four waves together, and a wave that looked the edge up after wave 0 had stored it used
+    to take the other branch.  Eight decodes of the same codes and three encodes must agree with the input and
+    with one another."""
+    from paper_2506_01084_amd import api
+
+    rng = np.random.default_rng(B)
+    tokens = np.ascontiguousarray(np.repeat(rng.integers(0, V, size=(B, N // 5 + 1)), 5, axis=1)[:, :N].astype(np.int32))
+    lens = rng.integers(0, N + 1, size=B).astype(np.int32)
+    lens[0] = N
+    print(f"[case] lzw four-wave kernels, {B} workgroups in flight", flush=True)
+    cfg = dict(V=V, M=M, cap=cap)
+    ctx = _ctx(cfg, B=B)
+    first = None
+    for rep in range(3):
+        codes, n_codes, status = gpu_encode(ctx, tokens, lens)
+        assert (status == 0).all()
+        if first is None:
+            first = (codes.copy(), n_codes.copy())
+        else:
+            assert (n_codes == first[1]).all()
+            assert all((codes[b, :n_codes[b]] == first[0][b, :n_codes[b]]).all() for b in range(B)), f"encode run {rep}"
+    for b in rng.choice(B, size=16, replace=False):
+        rc, _, rst = oracle.lzw_encode(tokens[b, :int(lens[b])].tolist(), V, M, cap)
+        assert rst == 0 and int(n_codes[b]) == len(rc) and (codes[b, :len(rc)] == np.asarray(rc, dtype=np.int32)).all()
+    for rep in range(8):
+        ctx2 = _ctx(cfg, B=B)
+        toks, n_tok, st = gpu_decode(ctx2, codes, n_codes, out_stride=N)
+        bad = [b for b in range(B)
+               if int(st[b]) != 0 or int(n_tok[b]) != int(lens[b]) or not (toks[b, :lens[b]] == tokens[b, :lens[b]]).all()]
+        assert not bad, f"decode run {rep}: sequences {bad[:8]}"
+        ctx2.close()
+    ctx.close()
+
+
 def test_largest_ids_capacity_and_merge_size():
     """The limits of the ID packing: V + cap = 2^24, cap = 65535, M = 8 (codes and tokens up to 2^24 - 1 in
     the hash slots, entry indices up to 65534, the table in global memory)."""
