@@ -303,7 +303,9 @@ int z2z_extended_nll(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_p
  *   d_dH [rows, d], d_dW_base [V, d], d_dW_hyper [B, cap, d]: out, bf16 (overwritten, not accumulated)
  * dZ is rounded to bf16 once and the four products accumulate in fp32.  bf16 contexts with d a multiple of 64;
  * anything else returns Z2Z_EUNSUPPORTED.  Work space: 2 * rows * (V + cap) bf16 for dZ and its transpose plus
- * one transposed copy of H, W_base and W_hyper, library scratch (Z2Z_ENOMEM beyond 200 GB). */
+ * one transposed copy of H, W_base and W_hyper, library scratch.  Beyond 200 GB the sequences go in chunks (halved
+ * until a chunk fits; dW_base of a later chunk adds to the bf16 result of the earlier ones); Z2Z_ENOMEM if one
+ * sequence alone does not fit. */
 int z2z_extended_nll_backward(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                               const void* d_W_base, const void* d_W_hyper, const int32_t* d_targets,
                               const float* d_lse, const float* d_grad_nll, void* d_dH, void* d_dW_base,
@@ -329,6 +331,8 @@ enum {
                                   inside one super block; 0 = automatic                              */
   Z2Z_OPT_SAMPLE_KERNEL = 7,   /* filtered sampling: 0 = automatic, 1 = always select the kept prefix by
                                   passes over the whole row (no short list from the largest parts)   */
+  Z2Z_OPT_BACKWARD_CHUNK = 8,  /* z2z_extended_nll_backward: at most this many sequences per pass, 0 = as many as
+                                  the 200 GB work-space limit allows                                  */
   Z2Z_OPT_TIMING = 5           /* 1 = bracket the dominant kernel of every z2z_extended_logits call
                                   with HIP events on the call's stream (at most 1024 calls are kept
                                   between two z2z_read_timing calls); 0 = off (default)             */

@@ -21,6 +21,7 @@ APPEND, RESET = 0, 1
 ST_OK, ST_BAD_TOKEN, ST_BAD_CODE, ST_OVERFLOW = 0, 1, 2, 4
 OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMING, OPT_LOGITS_MAP = 1, 2, 3, 4, 5, 6
 OPT_SAMPLE_KERNEL = 7
+OPT_BACKWARD_CHUNK = 8
 MAX_M = 8
 
 ENC_KEPT = 1

@@ -230,11 +230,13 @@ int ensure_scratch(z2z_ctx* c, size_t need) {
 // epilogue that stores the gradient with respect to the logits (the backward pass of the loss).
 int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, const void* W, int w_rows, int col0,
                            int part0, int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed,
-                           hipStream_t s, bool prob) {
+                           hipStream_t s, bool prob, int seq0, int n_seq) {
+  // (seq0, n_seq: the hyper part of a sub-range of the sequences -- the caller passes that range's rows and
+  // its W_hyper; n_seq = 0 means all of them)
   const int tile = fast ? 256 : 128;
-  const int B = c->cfg.B;
+  const int B = n_seq > 0 ? n_seq : c->cfg.B;
   a.W = W;
-  a.size = hyper ? c->st.size : nullptr;
+  a.size = hyper ? c->st.size + seq0 : nullptr;
   a.w_rows = w_rows;
   a.col0 = col0;
   a.n_vtiles = (w_rows + tile - 1) / tile;

@@ -474,7 +474,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
 int z2z_logits_fast_prepare(z2z_ctx* c);
 int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, z2z_logits::LogitsArgs a, const void* W, int w_rows, int col0,
                            int part0, int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed,
-                           hipStream_t s, bool prob = false);
+                           hipStream_t s, bool prob = false, int seq0 = 0, int n_seq = 0);
 // temperature sampling (one-row-per-sequence kernel only): softmax(logit / temperature), generator key and
 // counter words from seed and step
 struct z2z_sample_params {

@@ -319,6 +319,10 @@ Z2Z_API int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value) {
     case Z2Z_OPT_LZW_KERNEL: ctx->opt_lzw_kernel = value; return Z2Z_OK;
     case Z2Z_OPT_DECODE_KERNEL: ctx->opt_decode_kernel = value; return Z2Z_OK;
     case Z2Z_OPT_SAMPLE_KERNEL: ctx->opt_sample_kernel = value; return Z2Z_OK;
+    case Z2Z_OPT_BACKWARD_CHUNK:
+      if (value < 0) return Z2Z_EINVAL;
+      ctx->opt_backward_chunk = value;
+      return Z2Z_OK;
     case Z2Z_OPT_LOGITS_MAP:
       if (value != 0 && ((value & 0xFF) < 1 || ((value >> 8) & 0xFF) < 1 || ((value >> 16) & 0xFF) < 1 ||
                          ((value >> 24) & 0xFF) < 1 || ((value >> 16) & 0xFF) * ((value >> 24) & 0xFF) != 8))

@@ -66,6 +66,7 @@ struct z2z_ctx {
   void* skinny_partial;
   size_t skinny_partial_bytes;
   // options
+  int opt_backward_chunk;
   int opt_logits_kernel, opt_logits_strip, opt_lzw_kernel, opt_decode_kernel, opt_timing, opt_logits_map,
       opt_sample_kernel;
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration

@@ -56,14 +56,16 @@ def _setup(cfg, lens):
     return ctx, ref, E, H, w, targets, grad, d_E, d_W, d_H, d_t, lse
 
 
+@pytest.mark.parametrize("chunk", [0, 1, 2])          # sequences per pass of the backward (0: all at once)
 @pytest.mark.parametrize("B,N,V,d,M,cap,pool,use_grad", [
     (3, 150, 500, 64, 3, 64, "mean", True),
     (2, 300, 700, 128, 4, 200, "weighted", False),
     (5, 333, 1000, 192, 3, 100, "mean", True),          # ragged tiles in every product
     (1, 700, 2100, 256, 3, 300, "mean", True),          # several row tiles per sequence
 ])
-def test_gradients_match_oracle(B, N, V, d, M, cap, pool, use_grad):
+def test_gradients_match_oracle(B, N, V, d, M, cap, pool, use_grad, chunk):
     import torch
+    from paper_2506_01084_amd import api
 
     cfg = wl.scaled(wl.CONFIGS["c2"], B=B, N=N, V=V, d=d, M=M, cap=cap, pool=pool, zipf_s=1.3, seed=13 * B + d)
     print(f"[case] nll backward B={B} N={N} V={V} d={d} cap={cap}", flush=True)
@@ -73,6 +75,7 @@ def test_gradients_match_oracle(B, N, V, d, M, cap, pool, use_grad):
     dH = torch.full((B * N, d), 9.0, dtype=torch.bfloat16, device="cuda")
     dWb = torch.full((V, d), 9.0, dtype=torch.bfloat16, device="cuda")
     dWh = torch.full((B, cap, d), 9.0, dtype=torch.bfloat16, device="cuda")
+    ctx.set_option(api.OPT_BACKWARD_CHUNK, chunk)      # dW_base of a later chunk adds to the earlier ones' bf16 sum
     ctx.extended_nll_backward(d_H, N, d_E, d_W, d_t, lse, d_g, dH, dWb, dWh)
     dE = torch.zeros((V, d), dtype=torch.float32, device="cuda")
     ctx.hyper_embed_backward(dWh, dE)
