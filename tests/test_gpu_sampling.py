@@ -383,3 +383,44 @@ def test_many_sequences_picks_replay_in_a_graph():
             assert torch.equal(out[k], eager[k]), f"replay {rep}: value {k} differs from the eager call"
         assert np.isfinite(torch.randn(1 << 18, device="cuda").sum().item())        # eager work between replays
     ctx.close()
+
+
+def test_filtered_draws_with_base_parts_of_two_tiles():
+    """600 sequences over the full 128256-token vocabulary: three row tiles of the tile kernel, so its strips (the
+    base parts the selection kernels' short list is built from) span two tiles = 512 columns.  Sampled rows
+    against the oracle, every row valid."""
+    import torch
+
+    B, N, V, d, M, cap = 600, 40, 128256, 128, 3, 30
+    cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=5)
+    print("[case] filtered sampling, 600 rows x 128256 columns", flush=True)
+    ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, wl.make_lens(cfg))
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    lp = torch.empty(B, dtype=torch.float32, device="cuda")
+    picks = [0, 1, 255, 256, 300, 511, 512, 599]
+    rows_logits = {}
+    for b in picks:
+        Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
+        rows_logits[b] = oracle.extended_logits(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"])["logits"][0]
+    for si, (T, k, p) in enumerate([(1.0, 50, 0.9), (0.7, 5, 1.0), (1.0, 0, 0.5), (1.2, 256, 0.95), (1.0, 1000, 1.0)]):
+        seed, step = 40 + si, 7 * si
+        ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp, top_k=k, top_p=p)
+        torch.cuda.synchronize()
+        tok_h, lp_h = tok.cpu().numpy(), lp.cpu().numpy()
+        assert (tok_h >= 0).all() and all(tok_h[b] < V + len(ref[b][1]) for b in range(B))
+        assert np.isfinite(lp_h).all() and (lp_h <= 1e-5).all()
+        decided = sum(_check_truncated(rows_logits[b], T, k, p, seed, step, b, int(tok_h[b]), float(lp_h[b]))
+                      for b in picks)
+        assert decided >= len(picks) - 2, (T, k, p, decided)
+    # the unfiltered draw at the same shape: the tile kernel's sampling epilogue with strips of two tiles
+    for T, seed, step in ((1.0, 321, 0), (0.6, (9 << 32) | 4, 12)):
+        ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp)
+        torch.cuda.synchronize()
+        tok_h, lp_h = tok.cpu().numpy(), lp.cpu().numpy()
+        assert (tok_h >= 0).all() and all(tok_h[b] < V + len(ref[b][1]) for b in range(B))
+        for b in picks:
+            Wr = oracle.hyper_embed(E, cfg["dtype"], ref[b][1], cap, cfg["pool"], w)
+            r = sampling.extended_sample(H[b:b + 1], E, Wr, len(ref[b][1]), cfg["dtype"], T, seed, step, row0=b)
+            r["coords"] = [(seed, step, b)]
+            _check_draws(r, tok_h[b:b + 1], lp_h[b:b + 1], T)
+    ctx.close()
