@@ -501,6 +501,7 @@ __global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* d
 // probabilities p[i][.] are formed again from q and k; with dP[i][j] = dO_i . v_j and
 // dS[i][j] = p[i][j] (dP[i][j] - sum_j' dP[i][j'] p[i][j']):  dq_i = scale * sum_j dS[i][j] k_j;
 // dk_j += scale * dS[i][j] q_i;  dv_j += p[i][j] dO_i.  dQKV has the layout of QKV.
+template <int MM>          // slots per entry the registers are sized for: 4 (the usual M = 3) or Z2Z_MAX_M
 __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, const uint4* QKV, const uint4* dO,
                                                                      uint4* dQKV, int lanes_per_head, float scale,
                                                                      int groups, int n_units) {
@@ -515,9 +516,9 @@ __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, c
   const size_t r0 = (size_t)m.row0[bu];
   const int L = m.row0[bu + 1] - m.row0[bu];
   const uint4 zero = {0u, 0u, 0u, 0u};
-  float dk[Z2Z_MAX_M][8], dv[Z2Z_MAX_M][8];
+  float dk[MM][8], dv[MM][8];
 #pragma unroll
-  for (int j = 0; j < Z2Z_MAX_M; ++j)
+  for (int j = 0; j < MM; ++j)
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       dk[j][t] = 0.f;
@@ -527,10 +528,10 @@ __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, c
     float q[8], go[8];
     unpack8(active ? QKV[(r0 + i) * 3 * n_chunks + c] : zero, q);
     unpack8(active ? dO[(r0 + i) * n_chunks + c] : zero, go);
-    float s[Z2Z_MAX_M], dp[Z2Z_MAX_M];
+    float s[MM], dp[MM];
     float smax = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+    for (int j = 0; j < MM; ++j) {
       s[j] = -INFINITY;
       dp[j] = 0.f;
       if (j < L) {
@@ -554,20 +555,20 @@ __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, c
     }
     float den = 0.f;
 #pragma unroll
-    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+    for (int j = 0; j < MM; ++j) {
       s[j] = j < L ? __expf(s[j] - smax) : 0.f;
       den += s[j];
     }
     const float inv = 1.0f / den;
     float dot_pp = 0.f;
 #pragma unroll
-    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+    for (int j = 0; j < MM; ++j) {
       s[j] *= inv;                                   // p[i][j]
       dot_pp += s[j] * dp[j];
     }
     float dq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < Z2Z_MAX_M; ++j) {
+    for (int j = 0; j < MM; ++j) {
       if (j < L) {
         const float ds = s[j] * (dp[j] - dot_pp) * scale;
         float k[8];
@@ -583,7 +584,7 @@ __global__ void __launch_bounds__(256) enc_attention_backward_kernel(RowMap m, c
     if (active) dQKV[(r0 + i) * 3 * n_chunks + c] = pack8(dq);
   }
 #pragma unroll
-  for (int j = 0; j < Z2Z_MAX_M; ++j) {
+  for (int j = 0; j < MM; ++j) {
     if (j < L && active) {
       dQKV[(r0 + j) * 3 * n_chunks + n_chunks + c] = pack8(dk[j]);
       dQKV[(r0 + j) * 3 * n_chunks + 2 * n_chunks + c] = pack8(dv[j]);
@@ -980,9 +981,14 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
       acc = pass > 0 ? g.w_o : nullptr;
       Z2Z_TRY_RC(z2z_launch_linear(c, TA, TB, nullptr, acc, 0, const_cast<void*>(g.w_o), d, nullptr, d, Rk, s, rows_dev));
       const long long att_waves = (long long)n_units * groups;
-      hipLaunchKernelGGL(enc_attention_backward_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
-                         reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<const uint4*>(dO),
-                         reinterpret_cast<uint4*>(dQKV), dh / 8, scale, groups, n_units);
+      if (M <= 4)
+        hipLaunchKernelGGL(enc_attention_backward_kernel<4>, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
+                           reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<const uint4*>(dO),
+                           reinterpret_cast<uint4*>(dQKV), dh / 8, scale, groups, n_units);
+      else
+        hipLaunchKernelGGL(enc_attention_backward_kernel<Z2Z_MAX_M>, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0,
+                           s, m, reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<const uint4*>(dO),
+                           reinterpret_cast<uint4*>(dQKV), dh / 8, scale, groups, n_units);
       colsum_to(dQKV, 3 * d, R, rows_dev, const_cast<float*>(g.b_qkv), s);
       Z2Z_TRY_RC(transpose_to(dQKV, TA, R, rows_dev, 3 * d, 3 * d, Rk, s));
       Z2Z_TRY_RC(transpose_to(v.A, TB, R, rows_dev, d, d, Rk, s));
