@@ -344,6 +344,18 @@ int z2z_set_option(z2z_ctx* ctx, int32_t key, int32_t value);
  * clears the record.  `total_ms` / `launches` are host pointers. */
 int z2z_read_timing(z2z_ctx* ctx, float* total_ms, int32_t* launches);
 
+/* Instrumentation: how many launches of each logits kernel family this context has enqueued since it
+ * was created (host-side counters; nothing is read from the device).  Tests use it to make sure that a
+ * call ran on the kernel they mean to check; a profile can be matched against it.
+ *   counts[Z2Z_KERNEL_TILE_BASE]   bf16 MFMA tile kernel, base-vocabulary launches (any epilogue)
+ *   counts[Z2Z_KERNEL_TILE_HYPER]  bf16 MFMA tile kernel, per-sequence hyper-vocabulary launches
+ *   counts[Z2Z_KERNEL_GENERAL]     the general tile kernel (fp32, d not a multiple of 64, full logits)
+ *   counts[Z2Z_KERNEL_DECODE]      the one-row-per-sequence (bandwidth-bound) kernel
+ * `counts` is a host array of Z2Z_N_KERNEL_FAMILIES elements. */
+enum { Z2Z_KERNEL_TILE_BASE = 0, Z2Z_KERNEL_TILE_HYPER = 1, Z2Z_KERNEL_GENERAL = 2, Z2Z_KERNEL_DECODE = 3,
+       Z2Z_N_KERNEL_FAMILIES = 4 };
+int z2z_read_launches(const z2z_ctx* ctx, int64_t* counts);
+
 const char* z2z_strerror(int code);
 
 #ifdef __cplusplus

@@ -27,7 +27,7 @@ MAX_M = 8
 ENC_KEPT = 1
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
            "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
-           "z2z_read_timing", "z2z_strerror"]
+           "z2z_read_timing", "z2z_read_launches", "z2z_strerror"]
 
 
 class Config(ctypes.Structure):
@@ -113,6 +113,7 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_hyper_embed_backward.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_set_option.argtypes = [c_void_p, c_int32, c_int32]
     lib.z2z_read_timing.argtypes = [c_void_p, POINTER(c_float), P32]
+    lib.z2z_read_launches.argtypes = [c_void_p, POINTER(ctypes.c_int64)]
     lib.z2z_strerror.argtypes = [ctypes.c_int]
     lib.z2z_strerror.restype = c_char_p
     for name in EXPORTS:
@@ -183,6 +184,12 @@ class Context:
         ms, n = c_float(), c_int32()
         _check(self._lib.z2z_read_timing(self._h, byref(ms), byref(n)), "z2z_read_timing")
         return ms.value, n.value
+
+    def read_launches(self) -> dict:
+        """Launches enqueued so far per logits kernel family (host-side counters)."""
+        arr = (ctypes.c_int64 * 4)()
+        _check(self._lib.z2z_read_launches(self._h, arr), "z2z_read_launches")
+        return dict(tile_base=arr[0], tile_hyper=arr[1], general=arr[2], decode=arr[3])
 
     # -- the four operations ------------------------------------------------------------------------
     def lzw_encode(self, tokens: torch.Tensor, lens: Optional[torch.Tensor], codes: torch.Tensor,

@@ -264,6 +264,7 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
     const int sb_s = (a.n_strips + sb_strips - 1) / sb_strips;
     grid = 8u * (unsigned)(a.map_lr * a.map_ls) * (unsigned)a.map_sb_r * (unsigned)sb_s;
   }
+  c->n_launch[fast ? (hyper ? Z2Z_KERNEL_TILE_HYPER : Z2Z_KERNEL_TILE_BASE) : Z2Z_KERNEL_GENERAL]++;
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
   int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? (a.sample == 2 ? 7 : 6) : (hyper ? 1 : 0)), a, grid, s)
                 : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);

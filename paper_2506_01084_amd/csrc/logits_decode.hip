@@ -490,6 +490,7 @@ __global__ void __launch_bounds__(D_THREADS) linear_reduce_kernel(DecodeArgs a) 
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s,
                              int hyper_only_base_parts) {
+  c->n_launch[Z2Z_KERNEL_DECODE]++;
   DecodeArgs a;
   a.H = reinterpret_cast<const uint4*>(H);
   a.W_base = reinterpret_cast<const uint4*>(W_base);

@@ -358,6 +358,12 @@ Z2Z_API int z2z_read_timing(z2z_ctx* ctx, float* total_ms, int32_t* launches) {
   return Z2Z_OK;
 }
 
+Z2Z_API int z2z_read_launches(const z2z_ctx* ctx, int64_t* counts) {
+  if (!ctx || !counts) return Z2Z_EINVAL;
+  for (int i = 0; i < Z2Z_N_KERNEL_FAMILIES; ++i) counts[i] = ctx->n_launch[i];
+  return Z2Z_OK;
+}
+
 Z2Z_API const char* z2z_strerror(int code) {
   switch (code) {
     case Z2Z_OK: return "ok";

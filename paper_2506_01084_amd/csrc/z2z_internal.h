@@ -77,6 +77,7 @@ struct z2z_ctx {
   hipEvent_t ev_stop[Z2Z_MAX_TIMED];
   int n_timed;
   int ev_created;
+  long long n_launch[Z2Z_N_KERNEL_FAMILIES];   // launches enqueued per logits kernel family
 };
 
 // launchers (each validates nothing: the C-ABI layer has done so)
