@@ -43,7 +43,8 @@ enum { Z2Z_POOL_MEAN = 0, Z2Z_POOL_WEIGHTED = 1 };  /* hyper_embed pooling kind 
 enum { Z2Z_APPEND = 0, Z2Z_RESET = 1 };             /* lzw_* flags: continue, or empty codebook first */
 
 enum {                                              /* host-side argument errors                      */
-  Z2Z_OK = 0, Z2Z_EINVAL = -1, Z2Z_ENOMEM = -2, Z2Z_EHIP = -3, Z2Z_EUNSUPPORTED = -4
+  Z2Z_OK = 0, Z2Z_EINVAL = -1, Z2Z_ENOMEM = -2, Z2Z_EHIP = -3, Z2Z_EUNSUPPORTED = -4,
+  Z2Z_ELIMIT = -5                                   /* beyond a fixed limit of an allocation-free call */
 };
 enum {                                              /* per-sequence data status bits                  */
   Z2Z_ST_OK = 0,
@@ -252,6 +253,22 @@ int z2z_hyper_encode_keep(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enco
 int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                         const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
                         float* d_lse, float* d_logits, void* stream);
+
+/* z2z_extended_logits for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results;
+ * the difference is where the partial reductions go: into a static device array of the library
+ * (3 * Z2Z_STATIC_PARTS * 4 bytes = 48 MiB, held by every GPU the library runs on until the process ends)
+ * instead of the context's growable buffer.  The call allocates and frees nothing, on the device or through
+ * any library.  A call needs parts * rows elements, parts = strips of the base vocabulary + strips (or units)
+ * of the hyper vocabulary as the launch plan cuts them (one decode step at V = 128256, cap = 4096, 64
+ * sequences: 509 * 64; a prefill of 32768 rows at V = 128256, cap = 2048: 128 * 32768 = Z2Z_STATIC_PARTS);
+ * a call that needs more returns Z2Z_ELIMIT and enqueues nothing.  Nothing in the array has to start at zero
+ * (every element a call reads it has written before).  All contexts on one GPU share that GPU's array: calls
+ * that may overlap in time on one GPU (different streams, different contexts) race -- order them. */
+#define Z2Z_STATIC_PARTS (1 << 22)
+int z2z_extended_logits_static(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                               const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
+                               float* d_lse, float* d_logits, void* stream);
 
 /* extended_sample.  The generation step's pick when it is a draw rather than the maximum (section 2.3,
  * steps 8-9: the next token comes from the joint distribution over base tokens and hypertokens):

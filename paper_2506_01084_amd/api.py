@@ -23,10 +23,12 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 OPT_SAMPLE_KERNEL = 7
 OPT_BACKWARD_CHUNK = 8
 MAX_M = 8
+E_INVAL, E_NOMEM, E_HIP, E_UNSUPPORTED, E_LIMIT = -1, -2, -3, -4, -5
+STATIC_PARTS = 1 << 22
 
 ENC_KEPT = 1
 EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
-           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
+           "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_logits_static", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_read_launches", "z2z_strerror"]
 
 
@@ -104,6 +106,7 @@ def load_library() -> ctypes.CDLL:
     lib.z2z_hyper_encode_keep.argtypes = [c_void_p, c_void_p, POINTER(EncoderDesc), c_void_p, c_void_p]
     lib.z2z_extended_logits.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.z2z_extended_logits_static.argtypes = lib.z2z_extended_logits.argtypes
     lib.z2z_extended_sample.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_int32,
                                         c_float, ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p, c_void_p]
     lib.z2z_extended_nll.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -129,7 +132,9 @@ class Z2ZError(RuntimeError):
 
 def _check(rc: int, what: str) -> None:
     if rc != 0:
-        raise Z2ZError(f"{what}: {load_library().z2z_strerror(rc).decode()} ({rc})")
+        err = Z2ZError(f"{what}: {load_library().z2z_strerror(rc).decode()} ({rc})")
+        err.code = rc
+        raise err
 
 
 def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
@@ -276,19 +281,28 @@ class Context:
                                                    _ptr(dE, torch.float32), ENC_KEPT if kept else 0, _stream()),
                "z2z_hyper_encode_backward")
 
-    def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
-                        argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,
-                        logits: Optional[torch.Tensor] = None) -> None:
+    def _extended_logits(self, fn, what, H, rows_per_seq, W_base, W_hyper, argmax, mx, lse, logits) -> None:
         rows = H.shape[0]
         assert H.shape[1] == self.d and tuple(W_base.shape) == (self.V, self.d)
         assert argmax.numel() == rows and mx.numel() == rows and lse.numel() == rows
         if logits is not None:
             assert tuple(logits.shape) == (rows, self.V + self.cap)
-        _check(self._lib.z2z_extended_logits(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq,
-                                             _ptr(W_base, self.torch_dtype), _ptr(W_hyper, self.torch_dtype),
-                                             _ptr(argmax, torch.int32), _ptr(mx, torch.float32),
-                                             _ptr(lse, torch.float32), _ptr(logits, torch.float32), _stream()),
-               "z2z_extended_logits")
+        _check(fn(self._h, _ptr(H, self.torch_dtype), rows, rows_per_seq, _ptr(W_base, self.torch_dtype),
+                  _ptr(W_hyper, self.torch_dtype), _ptr(argmax, torch.int32), _ptr(mx, torch.float32),
+                  _ptr(lse, torch.float32), _ptr(logits, torch.float32), _stream()), what)
+
+    def extended_logits(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
+                        argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,
+                        logits: Optional[torch.Tensor] = None) -> None:
+        self._extended_logits(self._lib.z2z_extended_logits, "z2z_extended_logits", H, rows_per_seq, W_base, W_hyper,
+                              argmax, mx, lse, logits)
+
+    def extended_logits_static(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
+                               argmax: torch.Tensor, mx: torch.Tensor, lse: torch.Tensor,
+                               logits: Optional[torch.Tensor] = None) -> None:
+        """The allocation-free entry point: partial reductions in the library's static device array."""
+        self._extended_logits(self._lib.z2z_extended_logits_static, "z2z_extended_logits_static", H, rows_per_seq,
+                              W_base, W_hyper, argmax, mx, lse, logits)
 
     def extended_sample(self, H: torch.Tensor, rows_per_seq: int, W_base: torch.Tensor, W_hyper: torch.Tensor,
                         temperature: float, seed: int, step: int, token: torch.Tensor,

@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 
 namespace {
 
@@ -61,13 +62,13 @@ __global__ void __launch_bounds__(256) logits_combine_kernel(const float* part_m
   }
 }
 
-int launch_combine(const z2z_ctx* c, int n_parts, int rows, int32_t* argmax, float* mx, float* lse, hipStream_t s) {
+int launch_combine(const z2z_parts& p, int n_parts, int rows, int32_t* argmax, float* mx, float* lse, hipStream_t s) {
   if (n_parts > 256)
-    hipLaunchKernelGGL(logits_combine_kernel<256>, dim3(rows), dim3(256), 0, s, c->part_m, c->part_s, c->part_i,
-                       n_parts, rows, argmax, mx, lse);
+    hipLaunchKernelGGL(logits_combine_kernel<256>, dim3(rows), dim3(256), 0, s, p.m, p.s, p.i, n_parts, rows, argmax,
+                       mx, lse);
   else
-    hipLaunchKernelGGL(logits_combine_kernel<64>, dim3((rows + 3) / 4), dim3(256), 0, s, c->part_m, c->part_s,
-                       c->part_i, n_parts, rows, argmax, mx, lse);
+    hipLaunchKernelGGL(logits_combine_kernel<64>, dim3((rows + 3) / 4), dim3(256), 0, s, p.m, p.s, p.i, n_parts, rows,
+                       argmax, mx, lse);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }
@@ -222,6 +223,52 @@ int ensure_scratch(z2z_ctx* c, size_t need) {
   return Z2Z_OK;
 }
 
+z2z_parts ctx_parts(const z2z_ctx* c) { return z2z_parts{c->part_m, c->part_s, c->part_i, c->part_capacity}; }
+
+}  // namespace
+
+// ---- the allocation-free entry point's scratch ------------------------------------------------------------
+// One array per device (every GPU that loads the library holds its own copy, at its own address, until the
+// process ends): three runs of Z2Z_STATIC_PARTS four-byte elements, the (max, sum-exp, argmax) partials.  In
+// host code the array's name is a stand-in, not a device address: its address on a device is asked for once
+// per device (with that device current) and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[3 * (size_t)Z2Z_STATIC_PARTS * 4];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // nullptr: not looked up yet on that device
+static std::mutex g_scratch_mutex;
+
+int z2z_static_scratch_prepare(z2z_ctx* c) {
+  if (c->device < 0 || c->device >= kMaxDevices) return Z2Z_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[c->device]) return Z2Z_OK;
+  int cur = -1;
+  Z2Z_HIP_TRY(hipGetDevice(&cur));
+  if (cur != c->device) return Z2Z_EHIP;   // the symbol's address is that of the current device's copy
+  void* ptr = nullptr;
+  Z2Z_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+  if (!ptr) return Z2Z_EHIP;
+  g_scratch_ptr[c->device] = ptr;
+  return Z2Z_OK;
+}
+
+namespace {
+
+// The static array of the context's device as three part arrays; false if its address is not known.
+bool static_parts(const z2z_ctx* c, z2z_parts* out) {
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (c->device >= 0 && c->device < kMaxDevices) ptr = g_scratch_ptr[c->device];
+  }
+  if (!ptr) return false;
+  float* f = reinterpret_cast<float*>(ptr);
+  out->m = f;
+  out->s = f + Z2Z_STATIC_PARTS;
+  out->i = reinterpret_cast<int32_t*>(f + 2 * (size_t)Z2Z_STATIC_PARTS);
+  out->capacity = Z2Z_STATIC_PARTS;
+  return true;
+}
 
 }  // namespace
 
@@ -289,9 +336,19 @@ static int pick_strip_for(const z2z_ctx* c, long long row_tiles, int n_vt) {
 
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
-                               hipStream_t s) {
+                               hipStream_t s, bool use_static) {
   const int V = c->cfg.V, cap = c->cfg.cap;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
+  z2z_parts parts;
+  if (use_static && !static_parts(c, &parts)) return Z2Z_EHIP;
+  // the partial triples of this call: the device's static array must hold them as it is, the context's
+  // buffers grow to hold them
+  auto reserve = [&](size_t need) -> int {
+    if (use_static) return need <= parts.capacity ? Z2Z_OK : Z2Z_ELIMIT;
+    const int rc = ensure_scratch(c, need);
+    parts = ctx_parts(c);
+    return rc;
+  };
 
   // the fast kernels never store logits: the full-logits output (small shapes) takes the general kernel
   const bool fast_ok = c->cfg.dtype == Z2Z_BF16 && c->cfg.d % 64 == 0 && c->fast_ready && logits == nullptr;
@@ -302,16 +359,16 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const bool decode_split = decode_step && fast_ok && rows > 64 && c->opt_logits_kernel != 1;
   if (decode_step && !decode_split) {
     int n_parts = z2z_logits_decode_parts(c);
-    int rc = ensure_scratch(c, (size_t)n_parts * rows);
+    int rc = reserve((size_t)n_parts * rows);
     if (rc != Z2Z_OK) return rc;
-    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, logits, s);
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, nullptr, logits, s, -1, &parts);
     if (rc != Z2Z_OK) return rc;
     if (logits && cap > 0) {
       hipLaunchKernelGGL(logits_mask_kernel, dim3(rows), dim3(256), 0, s, logits, rows, rows_per_seq, V, cap,
                          c->st.size);
       Z2Z_HIP_TRY(hipGetLastError());
     }
-    return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
+    return launch_combine(parts, n_parts, rows, argmax, mx, lse, s);
   }
 
   // (the general kernel is many times slower per tile: even a tile with a few valid rows goes to the tile kernel)
@@ -334,7 +391,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     hyp_strips = (cap + hyper_columns - 1) / hyper_columns;
   }
   const int n_parts = base_strips + hyp_strips;
-  int rc = ensure_scratch(c, (size_t)n_parts * rows);
+  int rc = reserve((size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
 
   LogitsArgs a;
@@ -343,9 +400,9 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   a.rows = rows;
   a.rows_per_seq = rows_per_seq;
   a.d = c->cfg.d;
-  a.part_m = c->part_m;
-  a.part_s = c->part_s;
-  a.part_i = c->part_i;
+  a.part_m = parts.m;
+  a.part_s = parts.s;
+  a.part_i = parts.i;
   a.logits = logits;
   a.ld = V + cap;
   a.n_parts = n_parts;
@@ -356,7 +413,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   if (rc != Z2Z_OK) return rc;
   if (cap > 0 && decode_split) {
     int np = 0;
-    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, nullptr, nullptr, s, base_strips);
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, nullptr, nullptr, s, base_strips, &parts);
     if (rc != Z2Z_OK) return rc;
   } else if (cap > 0) {
     rc = z2z_launch_logits_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip_h, rows, rows_per_seq, &ns, false, s);
@@ -367,7 +424,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
       Z2Z_HIP_TRY(hipGetLastError());
     }
   }
-  return launch_combine(c, n_parts, rows, argmax, mx, lse, s);
+  return launch_combine(parts, n_parts, rows, argmax, mx, lse, s);
 }
 
 int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
@@ -496,7 +553,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, c->sample_logits, s);
     if (rc != Z2Z_OK) return rc;
   }
-  rc = launch_combine(c, n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
+  rc = launch_combine(ctx_parts(c), n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
   if (rc != Z2Z_OK) return rc;
   return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, n_parts, c->row_max + 2 * (size_t)rows, &sp,
                                      top_k, top_p, token, logprob, s, base_columns);

@@ -489,7 +489,7 @@ __global__ void __launch_bounds__(D_THREADS) linear_reduce_kernel(DecodeArgs a) 
 // is given as well: the partials are then those of the scaled logits, and nothing is drawn).
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s,
-                             int hyper_only_base_parts) {
+                             int hyper_only_base_parts, const z2z_parts* parts) {
   c->n_launch[Z2Z_KERNEL_DECODE]++;
   DecodeArgs a;
   a.H = reinterpret_cast<const uint4*>(H);
@@ -503,9 +503,9 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
   a.n_base_units = (a.V + D_BASE_UNIT - 1) / D_BASE_UNIT;
   a.n_groups = (a.B + 63) / 64;
   a.units_per_seq = (a.cap + D_UNIT - 1) / D_UNIT;
-  a.part_m = c->part_m;
-  a.part_s = c->part_s;
-  a.part_i = c->part_i;
+  a.part_m = parts ? parts->m : c->part_m;
+  a.part_s = parts ? parts->s : c->part_s;
+  a.part_i = parts ? parts->i : c->part_i;
   a.part_v = c->part_v;
   a.part_l = c->part_l;
   a.logits = logits;

@@ -103,6 +103,10 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
     free_ctx(c);
     return Z2Z_ENOMEM;
   }
+  if (z2z_static_scratch_prepare(c) != Z2Z_OK) {   // the allocation-free entry point's array on this device
+    free_ctx(c);
+    return Z2Z_EHIP;
+  }
   c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
   c->skinny_ready = z2z_logits_decode_prepare(c) == Z2Z_OK;      // the kernel itself; decode_ready: for this shape
   c->decode_ready = z2z_logits_decode_ok(c) && c->skinny_ready;
@@ -259,6 +263,18 @@ Z2Z_API int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int
                                     d_logits, static_cast<hipStream_t>(stream));
 }
 
+Z2Z_API int z2z_extended_logits_static(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
+                                       const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax,
+                                       float* d_max, float* d_lse, float* d_logits, void* stream) {
+  if (!ctx || !d_H || !d_W_base) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && !d_W_hyper) return Z2Z_EINVAL;
+  if (rows_per_seq < 1 || rows < 1) return Z2Z_EINVAL;
+  if ((long long)rows_per_seq * ctx->cfg.B != (long long)rows) return Z2Z_EINVAL;
+  if (!aligned16(d_H) || !aligned16(d_W_base) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_extended_logits(ctx, d_H, rows, rows_per_seq, d_W_base, d_W_hyper, d_argmax, d_max, d_lse,
+                                    d_logits, static_cast<hipStream_t>(stream), true);
+}
+
 Z2Z_API int z2z_extended_sample(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                                 const void* d_W_base, const void* d_W_hyper, float temperature, int32_t top_k,
                                 float top_p, uint64_t seed, uint64_t step, int32_t* d_token, float* d_logprob,
@@ -371,6 +387,7 @@ Z2Z_API const char* z2z_strerror(int code) {
     case Z2Z_ENOMEM: return "out of device or host memory";
     case Z2Z_EHIP: return "HIP runtime error";
     case Z2Z_EUNSUPPORTED: return "unsupported dtype or pooling kind";
+    case Z2Z_ELIMIT: return "beyond the fixed scratch size of the allocation-free entry point";
     default: return "unknown error";
   }
 }

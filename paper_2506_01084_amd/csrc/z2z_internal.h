@@ -28,6 +28,15 @@ struct LzwState {
   int32_t slots_fit_lds;     // the table of one sequence fits the LDS of a CU
 };
 
+// Where the tile kernels leave their partial (max, sum-exp, argmax) triples: three arrays of `capacity`
+// elements each.  Either the context's growable buffers or a device's static array.
+struct z2z_parts {
+  float* m;
+  float* s;
+  int32_t* i;
+  size_t capacity;
+};
+
 struct z2z_ctx {
   z2z_config cfg;
   int device;
@@ -94,9 +103,12 @@ int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_
                                 int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s);
 int z2z_launch_hyper_embed(z2z_ctx* c, const void* E, void* W_hyper, const int32_t* first, int32_t max_new,
                            hipStream_t s);
+// use_static: the partial triples go to the device's static array (nothing is allocated; Z2Z_ELIMIT when they
+// do not fit) instead of the context's growable buffers
 int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, int32_t* argmax, float* mx, float* lse, float* logits,
-                               hipStream_t s);
+                               hipStream_t s, bool use_static = false);
+int z2z_static_scratch_prepare(z2z_ctx* c);   // z2z_create: look up the static array's address on c->device
 int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                                const void* W_hyper, float temperature, int32_t top_k, float top_p, uint64_t seed,
                                uint64_t step, int32_t* token, float* logprob, hipStream_t s);
