@@ -13,6 +13,10 @@ with 8192-token histories, HBM-bound) is timed separately in the same run and re
 The learned hyper-encoder (a two-layer transformer over every entry's slots, in place of the averaging one) is
 timed on configuration 2's codebooks and reported in `hyper_encode`; the training-side loss over the extended
 vocabulary and its gradient, on configuration 2, in `nll_backward`.
+The other prefill configurations (1: tiny fp32; 4: long code-like context; 5: large vocabulary, deep merges,
+weighted pooling) run the same stages a few times each and are reported in `prefill_configs`, with a roofline
+object per extended_logits kernel; configuration 2 is also run with one hidden row per compressed position
+(`c2_compressed_rows`).
 The CPU oracle is timed on a bounded sample of the same workload as `cpu_baseline`.
 
 Prints ONE JSON line on stdout.
@@ -32,13 +36,34 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
-# HBM-side bytes per launch (fetch + write) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
-# summaries are committed under profiles/ (counter values scaled by a 1 GiB copy of known traffic).
-# They are measurements of these exact workloads, not computed here: a different workload reports null.
-TRAFFIC_BYTES = {
-    "logits_fast_kernel<0>@c2": 53.88e9 + 0.070e9,
-    "logits_decode_kernel@c3": 3.211e9 + 0.003e9,
-}
+PEAK_F32_TFLOPS = 157.3        # MI355X dense fp32 MFMA
+
+
+def load_traffic_table():
+    """HBM bytes per launch (fetch + write) of the dominant kernels, measured by the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE runs summarised under profiles/.  profiles/hbm_traffic.txt holds one line per kernel and workload:
+    key, bytes, the sha256 (first 16 hex digits) of the kernel's sources at the time of the run, the commit and
+    the summary file.  A line whose source hash no longer matches the tree is stale and reads as None."""
+    import hashlib
+
+    table = {}
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return table
+    for line in open(path):
+        line = line.split("#", 1)[0].strip()
+        if not line:
+            continue
+        key, nbytes, digest, sources = line.split()[:4]
+        h = hashlib.sha256()
+        for src in sources.split(","):
+            with open(os.path.join(ROOT, "paper_2506_01084_amd", "csrc", src), "rb") as f:
+                h.update(f.read())
+        table[key] = float(nbytes) if h.hexdigest()[:16] == digest else None
+    return table
+
+
+TRAFFIC_BYTES = load_traffic_table()
 
 
 def log(*a):
@@ -46,10 +71,12 @@ def log(*a):
 
 
 def to_device_bf16(torch, bits, dtype="bf16"):
-    """Host uint16 bf16 bit patterns -> device bfloat16 tensor (memory plumbing only)."""
+    """Host array in the storage format (uint16 bf16 bit patterns, or float32) -> device tensor (memory plumbing
+    only)."""
     import numpy as np
 
-    assert dtype == "bf16"
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.float32)).cuda()
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
 
 
@@ -72,25 +99,37 @@ class Stage:
         return sum(a.elapsed_time(b) for a, b in self.ev[: self.i])
 
 
-def run_prefill_workload(args, torch, api, wl):
-    cfg = wl.CONFIGS["c2"]
+def run_prefill_workload(args, torch, api, wl, name="c2", steps=None, warmup=None, compressed_rows=False):
+    """One configuration through the whole path, `steps` times after `warmup`; stage times from events on the
+    stream, the base-vocabulary logits kernel bracketed by the library's own events.  compressed_rows: afterwards
+    also time extended_logits with one hidden row per compressed position (max_b n_codes rows per sequence)."""
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
+    cfg = wl.CONFIGS[name]
     B, N, V, M, cap, d = (cfg[k] for k in ("B", "N", "V", "M", "cap", "d"))
+    dt_name = cfg["dtype"]
+    tdt = torch.float32 if dt_name == "f32" else torch.bfloat16
     rows = B * N
     t0 = time.time()
     tokens = wl.make_tokens(cfg)
     E = wl.make_embeddings(cfg)
     H = wl.make_hidden(cfg, rows)
-    log(f"[bench] c2 inputs generated in {time.time() - t0:.1f}s")
+    log(f"[bench] {name} inputs generated in {time.time() - t0:.1f}s")
     d_tok = torch.from_numpy(tokens).cuda()
-    d_E = to_device_bf16(torch, E, "bf16")          # tied: the matrix pooled is the LM head
-    d_H = to_device_bf16(torch, H, "bf16")
+    d_E = to_device_bf16(torch, E, dt_name)         # tied: the matrix pooled is the LM head
+    d_H = to_device_bf16(torch, H, dt_name)
     d_Hdec = d_H[N - 1::N].contiguous()             # one hidden row per sequence for the generation step
-    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype="bf16", pool="mean")
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=d, dtype=dt_name, pool=cfg["pool"],
+                      w=wl.make_pool_weights(cfg).tolist())
+    if getattr(args, "probe", "none") != "none":
+        ctx.set_option(api.OPT_LOGITS_KERNEL, {"noreq": 2, "mfma": 3}[args.probe])
+    if getattr(args, "logits_map", 0):
+        ctx.set_option(api.OPT_LOGITS_MAP, args.logits_map)
     i32 = dict(dtype=torch.int32, device="cuda")
     d_codes = torch.empty((B, N), **i32)
     d_ncodes = torch.empty(B, **i32)
     d_status = torch.empty(B, **i32)
-    d_W = torch.empty((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    d_W = torch.empty((B, cap, d), dtype=tdt, device="cuda")
     d_am = torch.empty(rows, **i32)
     d_mx = torch.empty(rows, dtype=torch.float32, device="cuda")
     d_lse = torch.empty(rows, dtype=torch.float32, device="cuda")
@@ -127,19 +166,20 @@ def run_prefill_workload(args, torch, api, wl):
         with stages["lzw_decode"]:
             ctx.lzw_decode(d_codes, d_ncodes, d_back, d_nback, d_st2, api.RESET)
 
-    stages = {n: Stage(torch, args.warmup) for n in names}
-    for _ in range(args.warmup):
+    stages = {n: Stage(torch, warmup) for n in names}
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     ctx.read_timing()
-    stages = {n: Stage(torch, args.steps) for n in names}
+    stages = {n: Stage(torch, steps) for n in names}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kernel_ms, launches = ctx.read_timing()
+    counts = ctx.read_launches()
 
     # sanity inside the bench: statuses clean, round trip exact
     assert int(d_status.abs().sum()) == 0 and int(d_st1.abs().sum()) == 0 and int(d_st2.abs().sum()) == 0
@@ -151,16 +191,82 @@ def run_prefill_workload(args, torch, api, wl):
     ctx.codebook_usage(d_codes, d_ncodes, d_usage)
     reused = float((d_usage > 0).sum().item()) / max(1.0, float(sizes.sum()))
 
-    ms_per_step = dt * 1e3 / args.steps
-    stage_ms = {n: stages[n].total_ms() / args.steps for n in names}
+    # rounds of the parse kernels (the serial chain of a call), read from the library's own counters
+    ctx.lzw_encode(d_tok, None, d_codes, d_ncodes, d_status, api.RESET)
+    torch.cuda.synchronize()
+    rounds_enc = ctx.lzw_rounds().cpu().numpy().copy()
+    ctx.lzw_decode(d_codes, d_ncodes, d_back, d_nback, d_st2, api.RESET)
+    torch.cuda.synchronize()
+    rounds_dec = ctx.lzw_rounds().cpu().numpy().copy()
+
+    ms_per_step = dt * 1e3 / steps
+    stage_ms = {n: stages[n].total_ms() / steps for n in names}
     flops_base = 2.0 * rows * d * V
-    flops_all = 2.0 * rows * d * (V + float(sizes.mean()))
+    flops_all = 2.0 * rows * d * (V + float(sizes.mean()))        # the columns that exist: V + C_b, not V + cap
+    # bytes hyper_embed has to move: every entry's constituent rows in and its pooled row out
+    ent_len = ctx.codebook()[1]
+    embed_bytes = float((ent_len.sum().item() + int(sizes.sum())) * d * (4 if dt_name == "f32" else 2))
     out = dict(ms_per_step=ms_per_step, stage_ms=stage_ms, kernel_ms_total=kernel_ms, kernel_launches=launches,
                flops_base=flops_base, flops_all=flops_all, sizes=sizes.tolist(), n_codes=ncodes.tolist(),
-               tokens=B * N, cfg=cfg, entries_reused_frac=reused)
+               tokens=B * N, cfg=cfg, entries_reused_frac=reused, steps=steps, embed_bytes=embed_bytes,
+               tile_kernel=counts["tile_base"] > 0, rounds_enc=rounds_enc.tolist(), rounds_dec=rounds_dec.tolist())
+    if compressed_rows:
+        # one hidden row per compressed position: what a model running on the compressed sequence would hand
+        # over (section 2.4).  Rows per sequence are uniform in the call, so the longest code stream sets them.
+        rps = int(ncodes.max())
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ctx.extended_logits(d_H[:B * rps], rps, d_E, d_W, d_am[:B * rps], d_mx[:B * rps], d_lse[:B * rps], None)
+        ev[0].record()
+        for _ in range(steps):
+            ctx.extended_logits(d_H[:B * rps], rps, d_E, d_W, d_am[:B * rps], d_mx[:B * rps], d_lse[:B * rps], None)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / steps
+        fl = 2.0 * B * rps * d * (V + float(sizes.mean()))
+        out["compressed_rows"] = dict(rows_per_seq=rps, rows=B * rps, sum_n_codes=int(ncodes.sum()),
+                                      extended_logits_ms=ms, flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12,
+                                      frac_of_bf16_peak=fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
     host = dict(tokens=tokens, E=E, H=H)
     ctx.close()
     return out, host
+
+
+def config_report(res):
+    """The per-configuration object of the JSON line: stage times, the metric's rates, and the roofline of the
+    extended_logits base-vocabulary kernel of that configuration."""
+    cfg, st = res["cfg"], res["stage_ms"]
+    k_ms = res["kernel_ms_total"] / max(res["kernel_launches"], 1)
+    bf16 = cfg["dtype"] == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    achieved = res["flops_base"] / (k_ms * 1e-3) / 1e12
+    whole = res["flops_all"] / (st["extended_logits"] * 1e-3) / 1e12
+    kernel = ("logits_fast_kernel<0>" if res["tile_kernel"] else
+              "logits_general_kernel (fp32 MFMA)" if not bf16 else "logits_general_kernel")
+    return {
+        "workload": f"{cfg['name']}: B={cfg['B']} x N={cfg['N']}, V={cfg['V']}, d={cfg['d']} {cfg['dtype']}, M={cfg['M']}, "
+                    f"cap={cfg['cap']}, {cfg['pool']} pooling",
+        "steps": res["steps"], "tokens": res["tokens"], "stage_ms": st,
+        "lzw_encode_tokens_per_s": res["tokens"] / (st["lzw_encode"] * 1e-3),
+        "lzw_decode_tokens_per_s": res["tokens"] / (st["lzw_decode"] * 1e-3),
+        "lzw_encode_plus_hyper_embed_tokens_per_s": res["tokens"] / ((st["lzw_encode"] + st["hyper_embed"]) * 1e-3),
+        # the parse is a serial chain per sequence: its time is (rounds of the longest sequence) x (time per round);
+        # cycles are quoted at the 2.4 GHz peak clock
+        "lzw": {"encode_rounds_max": max(res["rounds_enc"]), "decode_rounds_max": max(res["rounds_dec"]),
+                "encode_us_per_round": st["lzw_encode"] * 1e3 / max(res["rounds_enc"]),
+                "decode_us_per_round": st["lzw_decode"] * 1e3 / max(res["rounds_dec"]),
+                "encode_cycles_per_token_of_a_sequence_at_2p4GHz": st["lzw_encode"] * 1e-3 * 2.4e9 / cfg["N"],
+                "decode_cycles_per_token_of_a_sequence_at_2p4GHz": st["lzw_decode"] * 1e-3 * 2.4e9 / cfg["N"],
+                "tokens_per_round_encode": cfg["N"] / (sum(res["rounds_enc"]) / len(res["rounds_enc"]))},
+        "hyper_embed_algorithmic_bytes": res["embed_bytes"],
+        "hyper_embed_algorithmic_GBs": res["embed_bytes"] / (st["hyper_embed"] * 1e-3) / 1e9,
+        "sum_codebook_sizes": int(sum(res["sizes"])), "compression_rate": sum(res["n_codes"]) / res["tokens"],
+        "extended_logits_ms": st["extended_logits"], "extended_logits_TFLOPs": whole,
+        "roofline": {"bound": "mfma", "kernel": kernel + " (base-vocabulary part)", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "avg_kernel_ms": k_ms,
+                     "flops_per_launch": res["flops_base"], "whole_call_achieved": whole,
+                     "whole_call_frac": whole / peak,
+                     "traffic": TRAFFIC_BYTES.get(f"logits_fast_kernel<0>@{cfg['name'][:2]}")},
+    }
 
 
 def run_decode_workload(args, torch, api, wl):
@@ -464,7 +570,73 @@ def run_backward_workload(args, torch, api, wl):
     }
 
 
-def cpu_baseline(wl, host, budget_rows=4096):
+def run_lzw_batch(args, torch, api, wl, B=2048):
+    """Many documents per call (the preprocessing case): B sequences of configuration 2's kind through
+    lzw_encode and lzw_decode; one wave per sequence, tables in global memory."""
+    cfg = wl.scaled(wl.CONFIGS["c2"], B=B, seed=2900)
+    N, V, M, cap = cfg["N"], cfg["V"], cfg["M"], cfg["cap"]
+    t0 = time.time()
+    d_tok = torch.from_numpy(wl.make_tokens(cfg)).cuda()
+    log(f"[bench] {B} x {N} tokens generated in {time.time() - t0:.1f}s")
+    ctx = api.Context(B=B, V=V, M=M, cap=cap, d=64, dtype="bf16", pool="mean")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_codes, d_n, d_st = torch.empty((B, N), **i32), torch.empty(B, **i32), torch.empty(B, **i32)
+    d_back, d_nb, d_st2 = torch.empty((B, N), **i32), torch.empty(B, **i32), torch.empty(B, **i32)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    enc, dec = [], []
+    for rep in range(6):
+        ev[0].record()
+        ctx.lzw_encode(d_tok, None, d_codes, d_n, d_st, api.RESET)
+        ev[1].record()
+        ctx.lzw_decode(d_codes, d_n, d_back, d_nb, d_st2, api.RESET)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if rep:
+            enc.append(ev[0].elapsed_time(ev[1]))
+            dec.append(ev[1].elapsed_time(ev[2]))
+    assert int(d_st.abs().sum()) == 0 and int(d_st2.abs().sum()) == 0 and torch.equal(d_back, d_tok)
+    rounds_dec = int(ctx.lzw_rounds().max().item())
+    ctx.lzw_encode(d_tok, None, d_codes, d_n, d_st, api.RESET)
+    torch.cuda.synchronize()
+    rounds_enc = int(ctx.lzw_rounds().max().item())
+    ctx.close()
+    e, d_ = sum(enc) / len(enc), sum(dec) / len(dec)
+    return dict(workload=f"{B} sequences x {N} tokens, V={V}, M={M}, cap={cap} (configuration 2's generator)",
+                tokens=B * N, encode_ms=e, decode_ms=d_, encode_tokens_per_s=B * N / (e * 1e-3),
+                decode_tokens_per_s=B * N / (d_ * 1e-3), encode_rounds_max=rounds_enc, decode_rounds_max=rounds_dec,
+                encode_us_per_round=e * 1e3 / rounds_enc, decode_us_per_round=d_ * 1e3 / rounds_dec)
+
+
+def _oracle_lzw_one(job):
+    """Worker of the process-per-sequence oracle timing (imports the oracle only)."""
+    import oracle
+
+    toks, V, M, cap = job
+    codes, entries, _ = oracle.lzw_encode(toks, V, M, cap)
+    back, _, _ = oracle.lzw_decode(codes, V, M, cap)
+    assert back == toks
+    return len(codes)
+
+
+def cpu_lzw_parallel(wl):
+    """The LZW oracle on all of configuration 2, one process per sequence (up to the host's cores).  Runs before
+    the GPU is touched: the workers are forked from a process that holds no GPU state."""
+    import multiprocessing as mp
+
+    cfg = wl.CONFIGS["c2"]
+    tokens = wl.make_tokens(cfg)
+    jobs = [(tokens[b].tolist(), cfg["V"], cfg["M"], cfg["cap"]) for b in range(cfg["B"])]
+    n = max(1, min(cfg["B"], os.cpu_count() or 1))
+    with mp.get_context("fork").Pool(n) as pool:
+        pool.map(_oracle_lzw_one, jobs[:n])            # start-up and imports outside the timed part
+        reps = 8                                       # each sequence several times: a single parse is ~2 ms
+        t0 = time.perf_counter()
+        pool.map(_oracle_lzw_one, jobs * reps, chunksize=reps)
+        dt = time.perf_counter() - t0
+    return dict(seconds=dt, processes=n, tokens=reps * cfg["B"] * cfg["N"])
+
+
+def cpu_baseline(wl, host, lzw_par, budget_rows=4096):
     """The oracle, as it stands, on the host cores: LZW and pooling on the full configuration-2 batch, the
     joint logits on a sample of rows of sequence 0 (all columns); combined into tokens/s of the whole step."""
     import numpy as np
@@ -492,12 +664,17 @@ def cpu_baseline(wl, host, budget_rows=4096):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    return dict(value=1.0 / per_token, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=(f"config 2: LZW encode+decode of all {B * N} tokens ({t_lzw:.2f}s, 1 thread), mean pooling "
-                        f"of one sequence's {len(enc[0][1])} entries x{B} ({t_embed:.2f}s), joint logits+softmax of "
-                        f"{budget_rows} rows of sequence 0 over all {V + len(enc[0][1])} columns in float64 "
-                        f"({t_rows:.2f}s, BLAS threads); per-token costs summed"),
-                host_cpus=os.cpu_count())
+    out = dict(value=1.0 / per_token, unit="tokens/s", cores=int(threads), kind="oracle",
+               sample=(f"config 2: LZW encode+decode of all {B * N} tokens ({t_lzw:.2f}s, 1 thread), mean pooling "
+                       f"of one sequence's {len(enc[0][1])} entries x{B} ({t_embed:.2f}s), joint logits+softmax of "
+                       f"{budget_rows} rows of sequence 0 over all {V + len(enc[0][1])} columns in float64 "
+                       f"({t_rows:.2f}s, BLAS threads); per-token costs summed"),
+               host_cpus=os.cpu_count(),
+               lzw_tokens_per_s_one_thread=B * N / t_lzw)
+    if lzw_par is not None:
+        out["lzw_tokens_per_s_process_per_sequence"] = lzw_par["tokens"] / lzw_par["seconds"]
+        out["lzw_processes"] = lzw_par["processes"]
+    return out
 
 
 def main():
@@ -509,6 +686,15 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-encoder", action="store_true", help="skip the learned hyper-encoder measurement")
     ap.add_argument("--no-backward", action="store_true", help="skip the loss forward + backward measurement")
+    ap.add_argument("--no-configs", action="store_true", help="skip configurations 1, 4 and 5")
+    ap.add_argument("--only", default="", help="comma-separated configurations for the per-configuration part "
+                                               "(default c1,c4,c5)")
+    ap.add_argument("--probe", choices=["none", "noreq", "mfma"], default="none",
+                    help="MEASUREMENT PROBE, not a benchmark: run configuration 2's base-vocabulary logits kernel "
+                         "without operand requests (noreq) or as the MFMA stream alone (mfma); its outputs are not "
+                         "the logits' reduction and the JSON line says so")
+    ap.add_argument("--logits-map", type=lambda v: int(v, 0), default=0,
+                    help="workgroup -> tile order of the base-vocabulary logits kernel (Z2Z_OPT_LOGITS_MAP), for sweeps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -518,9 +704,18 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    from paper_2506_01084_amd import workloads as wl
+
+    if args.probe != "none":
+        args.no_cpu_baseline = True
+    lzw_par = None if args.no_cpu_baseline else cpu_lzw_parallel(wl)     # forks workers: before any GPU call
+
+    if args.probe != "none":
+        args.no_configs = args.no_decode = args.no_encoder = args.no_backward = True
+
     import torch
 
-    from paper_2506_01084_amd import api, workloads as wl
+    from paper_2506_01084_amd import api
 
     torch.cuda.set_device(0)
     api.load_library()
@@ -530,21 +725,36 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    res, host = run_prefill_workload(args, torch, api, wl)
-    assert res["kernel_launches"] == args.steps
+    res, host = run_prefill_workload(args, torch, api, wl, "c2", compressed_rows=True)
+    assert res["kernel_launches"] == args.steps and res["tile_kernel"]
     k_ms = res["kernel_ms_total"] / res["kernel_launches"]
     log(f"[bench] step {res['ms_per_step']:.2f} ms; stages {res['stage_ms']}; base-part kernel {k_ms:.3f} ms")
     dec = None if args.no_decode else run_decode_workload(args, torch, api, wl)
     enc = None if args.no_encoder else run_encoder_workload(args, torch, api, wl)
     bwd = None if args.no_backward else run_backward_workload(args, torch, api, wl)
-    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host)
+    lzw_batch = None if args.no_configs else run_lzw_batch(args, torch, api, wl)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host, lzw_par)
+    del host
+    per_config = {"c2": config_report(res)}
+    per_config["c2"]["compressed_rows"] = res.get("compressed_rows")
+    if not args.no_configs:
+        # the other prefill configurations: a few passes each (config 5's logits alone are ~0.25 s per pass)
+        for name in [n for n in (args.only.split(",") if args.only else ["c1", "c4", "c5"]) if n]:
+            n_steps = {"c1": 20, "c4": 5, "c5": 3}.get(name, 3)
+            r, h = run_prefill_workload(args, torch, api, wl, name, steps=n_steps, warmup=1)
+            del h
+            per_config[name] = config_report(r)
+            log(f"[bench] {name}: stages {r['stage_ms']}; logits {per_config[name]['extended_logits_TFLOPs']:.1f} TFLOP/s")
+            torch.cuda.empty_cache()
 
     cfg = res["cfg"]
     achieved = res["flops_base"] / (k_ms * 1e-3) / 1e12
     st = res["stage_ms"]
+    probe = args.probe != "none"
     line = {
-        "metric": "base tokens/s LZW+hyper_embed; extended_logits TFLOP/s & decode-step µs",
-        "value": res["tokens"] / (res["ms_per_step"] * 1e-3),
+        "metric": ("PROBE (not a result): the logits kernel ran in measurement mode '%s'" % args.probe) if probe else
+                  "base tokens/s LZW+hyper_embed; extended_logits TFLOP/s & decode-step µs",
+        "value": None if probe else res["tokens"] / (res["ms_per_step"] * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -570,7 +780,11 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "logits_fast_kernel<0> (base-vocabulary part of the prefill extended_logits call)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get("logits_fast_kernel<0>@c2"),
-                     "avg_kernel_ms": k_ms, "flops_per_launch": res["flops_base"]},
+                     "avg_kernel_ms": k_ms, "flops_per_launch": res["flops_base"],
+                     "whole_call_achieved": res["flops_all"] / (st["extended_logits"] * 1e-3) / 1e12,
+                     "whole_call_frac": res["flops_all"] / (st["extended_logits"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "prefill_configs": per_config,
+        "lzw_batch": lzw_batch,
         "cpu_baseline": cpu,
         "decode_step": dec,
         "hyper_encode": enc,

@@ -24,6 +24,14 @@
  *   - Return value: 0 on success, a negative Z2Z_E* code when an argument is rejected on the host
  *     (nothing is enqueued then).  Data errors are reported per sequence in d_status (bit flags);
  *     a sequence with an error stops at the offending element, the others are unaffected.
+ *   - Work buffers.  Some calls keep library-owned work space in the context (the partial reductions of
+ *     extended_logits / extended_sample, the stored logits of filtered sampling, the learned encoder's
+ *     activations, the backward passes' work space).  Each is allocated by the first call that needs it and
+ *     grows when a later call needs more: such a call frees and allocates on the device (hipFree / hipMalloc,
+ *     which synchronise the device that once) before it enqueues; every other call only enqueues.  While
+ *     `stream` is being captured into a graph a buffer cannot grow: the call returns Z2Z_ECAPTURE and
+ *     enqueues nothing -- make one eager call at the same shape before capturing, or use
+ *     z2z_extended_logits_static, which never allocates.
  *   - Calls on one context must be issued from one host thread at a time, and work of one context
  *     must be ordered (same stream, or synchronised by the caller).
  */
@@ -44,7 +52,8 @@ enum { Z2Z_APPEND = 0, Z2Z_RESET = 1 };             /* lzw_* flags: continue, or
 
 enum {                                              /* host-side argument errors                      */
   Z2Z_OK = 0, Z2Z_EINVAL = -1, Z2Z_ENOMEM = -2, Z2Z_EHIP = -3, Z2Z_EUNSUPPORTED = -4,
-  Z2Z_ELIMIT = -5                                   /* beyond a fixed limit of an allocation-free call */
+  Z2Z_ELIMIT = -5,                                  /* beyond a fixed limit of an allocation-free call */
+  Z2Z_ECAPTURE = -6                                 /* a work buffer would have to grow under stream capture */
 };
 enum {                                              /* per-sequence data status bits                  */
   Z2Z_ST_OK = 0,
@@ -112,6 +121,13 @@ int z2z_lzw_decode(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_code
  * Any of the three out-pointers may be NULL. */
 int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entry_len,
                  const int32_t** d_size);
+
+/* Instrumentation: a borrowed device view [B] int32 of how many rounds the latest z2z_lzw_encode or
+ * z2z_lzw_decode call took for each sequence.  The parse kernels (section 2.1's sequential loop, restructured)
+ * take the elements of a sequence in rounds of up to 64 (one wave) or 256 (four waves) and cut a round at the
+ * first element that depends on an entry made inside it; the serial chain of a call is its rounds, so
+ * kernel time / rounds is the latency the parse is bound by.  Valid until z2z_destroy. */
+int z2z_lzw_rounds(z2z_ctx* ctx, const int32_t** d_rounds);
 
 /* Codebook prefilling (the paper's discussion, "Codebook Management Strategy", item 2: seeding the codebook
  * with phrases expected to occur, ahead of the input).  The paper names the idea only; the operation here:
@@ -218,10 +234,11 @@ int z2z_hyper_encode(z2z_ctx* ctx, const void* d_E, const z2z_encoder* encoder, 
  *              are not read; grad->pos is required when encoder->pos is given
  *   d_dE       [V, d] float, ACCUMULATED into (tokens recur across entries; the caller clears it)
  *   flags      0, or Z2Z_ENC_KEPT: use the rows the latest z2z_hyper_encode_keep call on this context left
- *              instead of running the forward pass again.  The caller guarantees that the codebooks, d_E's
- *              contents and the encoder's parameters are unchanged since that call; the library checks only that
- *              such a call was the context's latest use of this work space, with the same d_E and an encoder of
- *              the same shape (else Z2Z_EINVAL).  A backward call consumes the kept rows.
+ *              instead of running the forward pass again.  The caller guarantees that d_E's contents and the
+ *              encoder's parameters are unchanged since that call; the library checks that such a call was the
+ *              context's latest use of this work space, with the same d_E and an encoder of the same shape, and
+ *              that no call that can change a codebook (lzw_encode / lzw_decode / reset / prefill / prune) was
+ *              made since (else Z2Z_EINVAL).  A backward call consumes the kept rows.
  * Without the flag the call runs the forward pass again, keeping every layer's rows, then reverse mode over the
  * same steps; activations and gradients between kernels are bf16, sums fp32; passes of up to 65536 slot rows
  * (matrix gradients of later passes add to the bf16 result of the earlier ones).  Work space (about
@@ -247,8 +264,8 @@ int z2z_hyper_encode_keep(z2z_ctx* ctx, const void* d_E, const z2z_encoder* enco
  *   d_H [rows, d]; rows must be B * rows_per_seq; d_W_base [V, d]; d_W_hyper [B, cap, d]
  *   d_logits  NULL, or [rows, V + cap] float32 out: the full logits, -inf in unused slots
  *             (for small shapes only: the reduction above never needs it).
- * The context keeps a scratch buffer for partial reductions; it is (re)allocated when a call
- * needs more than any earlier one (hipMalloc, which synchronises the device that once).
+ * The partial reductions go through a work buffer of the context (see "Work buffers" above: it grows when a
+ * call needs more than any earlier one, Z2Z_ECAPTURE if that happens under stream capture).
  */
 int z2z_extended_logits(z2z_ctx* ctx, const void* d_H, int32_t rows, int32_t rows_per_seq,
                         const void* d_W_base, const void* d_W_hyper, int32_t* d_argmax, float* d_max,
@@ -337,7 +354,10 @@ int z2z_hyper_embed_backward(z2z_ctx* ctx, const void* d_dW_hyper, float* d_dE, 
 /* Tuning knobs (kernel variants and tile schedule) and instrumentation; unknown keys return
  * Z2Z_EINVAL. */
 enum {
-  Z2Z_OPT_LOGITS_KERNEL = 1,   /* 0 = automatic, >0 = force a variant (see the implementation notes) */
+  Z2Z_OPT_LOGITS_KERNEL = 1,   /* 0 = automatic; 1 = the general tile kernel everywhere; 2, 3 = MEASUREMENT
+                                  PROBES of the bf16 MFMA tile kernel's base part, whose outputs are not the
+                                  logits' reduction: 2 = no operand requests after the first two K slabs,
+                                  3 = the MFMA stream alone (no requests, no LDS reads, one fold per strip) */
   Z2Z_OPT_LOGITS_STRIP = 2,    /* vocabulary tiles swept per workgroup, 0 = automatic               */
   Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant (2: table in global memory, 3: one
                                   code per step in the decoder, 4: one wave per sequence in the encoder) */

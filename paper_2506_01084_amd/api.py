@@ -23,11 +23,11 @@ OPT_LOGITS_KERNEL, OPT_LOGITS_STRIP, OPT_LZW_KERNEL, OPT_DECODE_KERNEL, OPT_TIMI
 OPT_SAMPLE_KERNEL = 7
 OPT_BACKWARD_CHUNK = 8
 MAX_M = 8
-E_INVAL, E_NOMEM, E_HIP, E_UNSUPPORTED, E_LIMIT = -1, -2, -3, -4, -5
+E_INVAL, E_NOMEM, E_HIP, E_UNSUPPORTED, E_LIMIT, E_CAPTURE = -1, -2, -3, -4, -5, -6
 STATIC_PARTS = 1 << 22
 
 ENC_KEPT = 1
-EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
+EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_lzw_rounds", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
            "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_logits_static", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_read_launches", "z2z_strerror"]
 
@@ -94,6 +94,7 @@ def load_library() -> ctypes.CDLL:
                                    c_void_p, c_void_p]
     lib.z2z_lzw_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32,
                                    c_void_p, c_void_p]
+    lib.z2z_lzw_rounds.argtypes = [c_void_p, POINTER(c_void_p)]
     lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
     lib.z2z_codebook_prefill.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
                                          c_void_p]
@@ -237,6 +238,12 @@ class Context:
         assert tuple(keep.shape) == (self.B, self.cap) and tuple(new_id.shape) == (self.B, self.cap)
         _check(self._lib.z2z_codebook_prune(self._h, _ptr(keep, torch.int32), _ptr(new_id, torch.int32),
                                             _ptr(n_kept, torch.int32), _stream()), "z2z_codebook_prune")
+
+    def lzw_rounds(self):
+        """Zero-copy int32 [B] device tensor: rounds of the latest parse call per sequence (instrumentation)."""
+        r = c_void_p()
+        _check(self._lib.z2z_lzw_rounds(self._h, byref(r)), "z2z_lzw_rounds")
+        return _device_view(r.value, (self.B,))
 
     def codebook_ptrs(self):
         e, l, s = c_void_p(), c_void_p(), c_void_p()

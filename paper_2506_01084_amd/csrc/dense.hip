@@ -120,6 +120,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
       ksplit = (n_slabs + per - 1) / per;
       const size_t need = (size_t)ksplit * R * N * sizeof(float);
       if (need > c->skinny_partial_bytes) {
+        Z2Z_TRY_GROW(s);
         if (c->skinny_partial) (void)hipFree(c->skinny_partial);
         c->skinny_partial = nullptr;
         c->skinny_partial_bytes = 0;

@@ -674,6 +674,7 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
   const size_t index_bytes = ((n_units_max + 1 + R_max) * sizeof(int32_t) + 255) & ~(size_t)255;
   const size_t need = R_max * ((size_t)4 * d + (size_t)3 * d + (size_t)dff) * 2 + index_bytes;
   if (need > c->enc_ws_bytes) {
+    Z2Z_TRY_GROW(s);
     if (c->enc_ws) (void)hipFree(c->enc_ws);
     c->enc_ws = nullptr;
     c->enc_ws_bytes = 0;
@@ -808,6 +809,7 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
   if (mode == 2 && (!c->enc_kept || c->enc_kept_need != need || c->enc_kept_E != E)) return Z2Z_EINVAL;
   c->enc_kept = false;
   if (need > c->enc_bwd_ws_bytes) {
+    Z2Z_TRY_GROW(s);
     if (c->enc_bwd_ws) (void)hipFree(c->enc_bwd_ws);
     c->enc_bwd_ws = nullptr;
     c->enc_bwd_ws_bytes = 0;

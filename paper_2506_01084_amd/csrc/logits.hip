@@ -194,8 +194,9 @@ __global__ void __launch_bounds__(256) target_nll_kernel(const uint4* H, const u
   if (lane == 0) nll[r] = lse[r] - acc;
 }
 
-int ensure_sample_scratch(z2z_ctx* c, size_t need) {
+int ensure_sample_scratch(z2z_ctx* c, size_t need, hipStream_t s) {
   if (need <= c->part_vl_capacity) return Z2Z_OK;
+  Z2Z_TRY_GROW(s);
   if (c->part_v) (void)hipFree(c->part_v);
   if (c->part_l) (void)hipFree(c->part_l);
   c->part_v = nullptr;
@@ -207,8 +208,9 @@ int ensure_sample_scratch(z2z_ctx* c, size_t need) {
   return Z2Z_OK;
 }
 
-int ensure_scratch(z2z_ctx* c, size_t need) {
+int ensure_scratch(z2z_ctx* c, size_t need, hipStream_t s) {
   if (need <= c->part_capacity) return Z2Z_OK;
+  Z2Z_TRY_GROW(s);
   if (c->part_m) (void)hipFree(c->part_m);
   if (c->part_s) (void)hipFree(c->part_s);
   if (c->part_i) (void)hipFree(c->part_i);
@@ -313,7 +315,9 @@ int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, LogitsArgs a, cons
   }
   c->n_launch[fast ? (hyper ? Z2Z_KERNEL_TILE_HYPER : Z2Z_KERNEL_TILE_BASE) : Z2Z_KERNEL_GENERAL]++;
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? (a.sample == 2 ? 7 : 6) : (hyper ? 1 : 0)), a, grid, s)
+  // (measurement probes of the base part: see logits_fast_kernel, modes 8 and 9)
+  const int plain_base = c->opt_logits_kernel == 2 ? 8 : (c->opt_logits_kernel == 3 ? 9 : 0);
+  int rc = fast ? z2z_launch_logits_fast(prob ? (hyper ? 4 : 3) : (a.sample && !hyper ? (a.sample == 2 ? 7 : 6) : (hyper ? 1 : plain_base)), a, grid, s)
                 : z2z_launch_logits_general(c->cfg.dtype == Z2Z_BF16, hyper, a, grid, s);
   if (timed) {
     Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
@@ -345,7 +349,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   // buffers grow to hold them
   auto reserve = [&](size_t need) -> int {
     if (use_static) return need <= parts.capacity ? Z2Z_OK : Z2Z_ELIMIT;
-    const int rc = ensure_scratch(c, need);
+    const int rc = ensure_scratch(c, need, s);
     parts = ctx_parts(c);
     return rc;
   };
@@ -433,7 +437,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   // built for the generation step: one hidden row per sequence, the bandwidth-bound kernel
   if (rows_per_seq != 1 || !c->decode_ready) return Z2Z_EUNSUPPORTED;
   int n_parts = z2z_logits_decode_parts(c);
-  int rc = ensure_scratch(c, (size_t)n_parts * rows);
+  int rc = ensure_scratch(c, (size_t)n_parts * rows, s);
   if (rc != Z2Z_OK) return rc;
   z2z_sample_params sp;
   sp.temperature = temperature;
@@ -450,9 +454,9 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     int base_columns, hyper_columns;
     z2z_logits_decode_units(&base_columns, &hyper_columns);
     n_parts = base_strips + (c->cfg.cap + hyper_columns - 1) / hyper_columns;
-    rc = ensure_scratch(c, (size_t)n_parts * rows);
+    rc = ensure_scratch(c, (size_t)n_parts * rows, s);
     if (rc != Z2Z_OK) return rc;
-    rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
+    rc = ensure_sample_scratch(c, (size_t)n_parts * rows, s);
     if (rc != Z2Z_OK) return rc;
     LogitsArgs a;
     memset(&a, 0, sizeof(a));
@@ -488,7 +492,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   }
   if (top_k <= 0 && top_p >= 1.0f) {
     // no filter: the draw is folded into the kernel that computes the logits, which are never stored
-    rc = ensure_sample_scratch(c, (size_t)n_parts * rows);
+    rc = ensure_sample_scratch(c, (size_t)n_parts * rows, s);
     if (rc != Z2Z_OK) return rc;
     rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, nullptr, s);
     if (rc != Z2Z_OK) return rc;
@@ -502,6 +506,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   if (!c->trunc_ready) return Z2Z_EUNSUPPORTED;
   const size_t need = (size_t)rows * (size_t)(c->cfg.V + c->cfg.cap);
   if (need > c->sample_logits_capacity) {
+    Z2Z_TRY_GROW(s);
     if (c->sample_logits) (void)hipFree(c->sample_logits);
     if (c->row_max) (void)hipFree(c->row_max);
     c->sample_logits = nullptr;

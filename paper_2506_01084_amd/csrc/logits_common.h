@@ -73,16 +73,27 @@ __device__ __forceinline__ float read_acc(float in_agpr) {
   return x;
 }
 
+// Largest of three in one instruction.  (Spelled as an instruction: on values that come out of read_acc the
+// compiler knows nothing about, fmaxf costs a quieting instruction per operand.)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Fold one finished accumulator tile into the running triples.  acc[i][j] is a 32x32 MFMA result block:
 // register v of this lane is the logit of hidden row (j, lane & 31) and vocabulary column
 // col_base + i * 32 + (v >> 2) * 8 + (v & 3), where col_base already holds the tile origin, the wave's
-// offset and (lane >> 5) * 4.  Columns at and beyond n_valid do not exist (read as -inf; only tail tiles
-// pay for that test).  The fold goes block by block (16 values live at a time, the accumulators are
-// only read), in increasing column order per lane, so strict comparisons keep the lowest column among
-// equal maxima.
-template <int NI, int NJ>
-__device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], int col_base, int col0,
-                                          int n_valid, bool tail) {
+// offset and (lane >> 5) * 4.  Columns at and beyond n_valid do not exist (read as -inf; TAIL = false is the
+// instance for tiles that lie wholly below n_valid, which is all but the last tile of a matrix: it carries no
+// column tests at all).  The fold goes block by block (16 values live at a time, the accumulators are only
+// read), in increasing column order per lane, so strict comparisons keep the lowest column among equal
+// maxima.  The running sum is kept against the running maximum in base-2 units: exp(x - m) is one
+// multiply-add and one hardware exponential per logit.
+template <int NI, int NJ, bool TAIL>
+__device__ __forceinline__ void fold_tile_impl(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], int col_base, int col0,
+                                               int n_valid) {
+  constexpr float kLog2e = 1.4426950408889634f;
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
 #pragma unroll
@@ -91,11 +102,12 @@ __device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         x[v] = read_acc(acc[i][j][v]);
-        if (tail && col_base + i * 32 + (v >> 2) * 8 + (v & 3) >= n_valid) x[v] = kNegInf;
+        if (TAIL && col_base + i * 32 + (v >> 2) * 8 + (v & 3) >= n_valid) x[v] = kNegInf;
       }
-      float gmax = x[0];
+      float gmax = max3(x[0], x[1], x[2]);
 #pragma unroll
-      for (int v = 1; v < 16; ++v) gmax = fmaxf(gmax, x[v]);
+      for (int v = 3; v < 15; v += 2) gmax = max3(gmax, x[v], x[v + 1]);
+      gmax = max3(gmax, x[15], x[15]);
       if (gmax > run[j].m) {
         int targ = 15;
 #pragma unroll
@@ -104,15 +116,28 @@ __device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&
         run[j].m = gmax;
         run[j].i = col0 + col_base + i * 32 + (targ >> 2) * 8 + (targ & 3);
       }
-      if (run[j].m != kNegInf) {
-        const float m = run[j].m;
-        float add = 0.f;
+      if (!TAIL || run[j].m != kNegInf) {
+        // (without a tail every logit is finite, so the running maximum is finite from the first block on)
+        const float m2 = -run[j].m * kLog2e;
+        float add0 = 0.f, add1 = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) add += __expf(x[v] - m);
-        run[j].s += add;
+        for (int v = 0; v < 16; v += 2) {
+          add0 += __builtin_amdgcn_exp2f(fmaf(x[v], kLog2e, m2));
+          add1 += __builtin_amdgcn_exp2f(fmaf(x[v + 1], kLog2e, m2));
+        }
+        run[j].s += add0 + add1;
       }
     }
   }
+}
+
+template <int NI, int NJ>
+__device__ __forceinline__ void fold_tile(const f32x16 (&acc)[NI][NJ], Triple (&run)[NJ], int col_base, int col0,
+                                          int n_valid, bool tail) {
+  if (tail)
+    fold_tile_impl<NI, NJ, true>(acc, run, col_base, col0, n_valid);
+  else
+    fold_tile_impl<NI, NJ, false>(acc, run, col_base, col0, n_valid);
 }
 
 __device__ __forceinline__ uint32_t bf16_bits_rne(float f) {

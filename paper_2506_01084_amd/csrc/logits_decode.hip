@@ -574,6 +574,7 @@ int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const flo
     const size_t slots = (size_t)a.n_base_units * a.n_groups;
     const size_t need = slots * ksplit * D_LINEAR_UNIT * 64 * sizeof(float);
     if (need > c->skinny_partial_bytes) {
+      Z2Z_TRY_GROW(s);
       if (c->skinny_partial) (void)hipFree(c->skinny_partial);
       c->skinny_partial = nullptr;
       c->skinny_partial_bytes = 0;

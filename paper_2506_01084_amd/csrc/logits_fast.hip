@@ -130,8 +130,14 @@ struct Frags {
   uint4 b[F_NJ];
 };
 
+// MODE 8 and 9 are measurement probes of the base part (their results are NOT the logits' reduction): 8 stops
+// requesting operands after the first two slabs (the matrix cores, the LDS reads and the fold run as usual on
+// those two slabs' values), 9 also stops reading LDS and folds once per strip -- the MFMA stream alone.  They
+// bracket what the operand stream costs and give the clock the matrix cores alone are left with.
 template <int MODE>
 __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
+  constexpr bool PROBE_NOREQ = MODE == 8 || MODE == 9;
+  constexpr bool PROBE_MFMA = MODE == 9;
   extern __shared__ __align__(1024) unsigned char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -297,7 +303,7 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
                                                             __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
         const int w = w0 + (i - i_lo) * F_NJ + j;
-        if (w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
+        if (!PROBE_NOREQ && w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
           __builtin_amdgcn_sched_barrier(0);
           issue_pair((w - 1) / F_SPREAD);
           __builtin_amdgcn_sched_barrier(0);
@@ -317,30 +323,34 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     issue_end();
     issue_begin(1);
 #pragma unroll
-    for (int i = 0; i <= F_LAST_IN_HANDOVER; ++i) issue_pair(i);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (F_LAST_IN_HANDOVER + 1)));   // all of slab 0
+    for (int i = 0; i <= (PROBE_NOREQ ? F_PAIRS - 1 : F_LAST_IN_HANDOVER); ++i) issue_pair(i);
+    if (PROBE_NOREQ)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (F_LAST_IN_HANDOVER + 1)));   // all of slab 0
     __syncthreads();
     Frags f0, f1;
     read_frags(f0, 0, 0);
+    if (PROBE_MFMA) read_frags(f1, 0, 1);
     int g = 0;
     for (int vt = vt0; vt < vt_end; ++vt) {
       for (int slab = 0; slab < n_slabs; ++slab, ++g) {
         const int stage = g & 1;
-        read_frags(f1, stage, 1);
+        if (!PROBE_MFMA) read_frags(f1, stage, 1);
         mfma_rows(f0, 0, F_NI, F_REST);
-        read_frags(f0, stage, 2);
+        if (!PROBE_MFMA) read_frags(f0, stage, 2);
         mfma_rows(f1, 0, F_NI, F_REST + F_KSTEP);
-        read_frags(f1, stage, 3);
+        if (!PROBE_MFMA) read_frags(f1, stage, 3);
         mfma_rows(f0, 0, F_NI, F_REST + 2 * F_KSTEP);
-        issue_end();                            // the request for slab g+1 is out in full
+        if (!PROBE_NOREQ) issue_end();          // the request for slab g+1 is out in full
         // last k-step: a quarter of its MFMAs, then the slab hand-over.  It is the same for every slab,
         // the last ones included (no test inside the loop): past the end of the stream the requests
         // re-read the last slab into a stage nobody reads again.
         mfma_rows(f1, 0, 1, 1000);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // slab g+1 (the only one in flight) has landed
         __syncthreads();                            // slab g+1 visible to all; everyone has read slab g
-        read_frags(f0, stage ^ 1, 0);
-        issue_begin(stage);                         // refill this stage with slab g+2
+        if (!PROBE_MFMA) read_frags(f0, stage ^ 1, 0);
+        if (!PROBE_NOREQ) issue_begin(stage);       // refill this stage with slab g+2
         mfma_rows(f1, 1, F_NI, 0);
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
@@ -356,10 +366,11 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         fold_tile_sample<F_NI, F_NJ>(acc, run, draw, a, r0 + wr * (F_NJ * 32), v0 + wv * 128 + half * 4, n_valid);
       else if (MODE == 7)
         fold_tile_store<F_NI, F_NJ>(acc, run, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
-      else
+      else if (!PROBE_MFMA)
         fold_tile<F_NI, F_NJ>(acc, run, v0 + wv * 128 + half * 4, a.col0, n_valid, v0 + FT > n_valid);
-      zero_acc();
+      if (!PROBE_MFMA) zero_acc();
     }
+    if (PROBE_MFMA) fold_tile_impl<F_NI, F_NJ, false>(acc, run, vt0 * FT + wv * 128 + half * 4, a.col0, n_valid);
   }
 
   if (MODE >= 2 && MODE <= 5) {
@@ -420,7 +431,11 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 7)
+  if (mode == 9)
+    hipLaunchKernelGGL(logits_fast_kernel<9>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 8)
+    hipLaunchKernelGGL(logits_fast_kernel<8>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 7)
     hipLaunchKernelGGL(logits_fast_kernel<7>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 6)
     hipLaunchKernelGGL(logits_fast_kernel<6>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -457,6 +472,10 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<6>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<7>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<8>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<9>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

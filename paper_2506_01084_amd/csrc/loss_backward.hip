@@ -54,10 +54,7 @@ size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 int z2z_launch_hyper_embed_backward(z2z_ctx* c, const void* dW_hyper, float* dE, hipStream_t s) {
   const int B = c->cfg.B, cap = c->cfg.cap;
   if (cap == 0) return Z2Z_OK;
-  if (!c->coef_dev) {
-    if (hipMalloc(&c->coef_dev, sizeof(c->coef)) != hipSuccess) return Z2Z_ENOMEM;
-    Z2Z_HIP_TRY(hipMemcpyAsync(c->coef_dev, c->coef, sizeof(c->coef), hipMemcpyHostToDevice, s));
-  }
+  if (!c->coef_dev) return Z2Z_EHIP;       // (allocated and filled by z2z_create)
   const long long rows = (long long)B * cap;
   hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
                      reinterpret_cast<const uint16_t*>(dW_hyper), dE, c->st.size, c->st.ent_tokens, c->st.ent_len, B,
@@ -106,6 +103,7 @@ int z2z_launch_extended_nll_backward(z2z_ctx* c, const void* H, int32_t rows, in
   while (n_seq > 1 && layout(n_seq) > limit) n_seq = (n_seq + 1) / 2;
   if (layout(n_seq) > limit) return Z2Z_ENOMEM;      // one sequence alone does not fit
   if (off > c->bwd_ws_bytes) {
+    Z2Z_TRY_GROW(s);
     if (c->bwd_ws) (void)hipFree(c->bwd_ws);
     c->bwd_ws = nullptr;
     c->bwd_ws_bytes = 0;

@@ -153,6 +153,26 @@ struct Table {
   }
 };
 
+// A workgroup barrier that other waves' reads PAST the vector L1 may rely on.  Between the waves of a workgroup
+// plain stores and plain loads are ordered by the L1 they share, and the barrier does not wait for the stores
+// to leave it; a load that goes straight to L2 (load_fresh, the table's atomic loads) could overtake a store of
+// another wave that is still on its way there.  So the stores are awaited before the barrier.
+__device__ __forceinline__ void sync_after_global_stores() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
+// The one-wave helpers (table_open / table_close, lzw_encode_rounds, lzw_decode_rounds) are run by exactly one
+// wave: the whole workgroup of the 64-thread kernels, or wave 0 of a four-wave kernel on a short appended call
+// after the other three have returned.  What they need between their steps is that the lanes' earlier LDS and
+// global accesses have completed, not a meeting of waves, so they never execute a workgroup barrier: a fence at
+// workgroup scope (the waits for the outstanding memory operations) and a wave barrier (keeps the compiler from
+// moving memory operations across).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+}
+
 template <bool LDS>
 __device__ __forceinline__ void table_open(const LzwArgs& a, int b, int lane, bool reset, Table<LDS>* t) {
   const LzwState& st = a.st;
@@ -164,17 +184,19 @@ __device__ __forceinline__ void table_open(const LzwArgs& a, int b, int lane, bo
     } else {
       for (int i = lane; i < st.nslots; i += kWave) lds_slots[i] = t->g[i];
     }
-    __syncthreads();
+    wave_sync();
   } else if (reset) {
+    // plain stores; the probes read past the L1 (atomic loads), so the stores are awaited first
     for (int i = lane; i < st.nslots; i += kWave) t->g[i] = kEmpty;
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wave_sync();
   }
 }
 
 template <bool LDS>
 __device__ __forceinline__ void table_close(const LzwArgs& a, int lane, const Table<LDS>& t) {
   if (LDS) {
-    __syncthreads();
+    wave_sync();
     for (int i = lane; i < a.st.nslots; i += kWave) t.g[i] = lds_slots[i];
   }
 }
@@ -321,7 +343,7 @@ __device__ __forceinline__ void lzw_encode_rounds(const LzwArgs& a, int32_t* tok
         ++C;
       }
     }
-    __syncthreads();
+    wave_sync();
   }
 
   const u64 lanes_below = (1ull << lane) - 1;
@@ -329,7 +351,9 @@ __device__ __forceinline__ void lzw_encode_rounds(const LzwArgs& a, int32_t* tok
   bool filled = false;
   bool stop = false;
   int pos = 0;                        // first position not yet covered by an emitted phrase
+  int n_rounds = 0;
   while (pos < n && !stop) {
+    ++n_rounds;
     // a round touches positions pos .. pos + 63 + M
     if (!filled || (pos + kWave + M > cbase + kTokBuf && cbase + kTokBuf < n)) {
       cbase = pos;
@@ -435,6 +459,7 @@ __device__ __forceinline__ void lzw_encode_rounds(const LzwArgs& a, int32_t* tok
     st.size[b] = C;
     st.prev_code[b] = prev;
     st.prev_len[b] = prev_len;
+    st.rounds[b] = n_rounds;
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
@@ -485,22 +510,13 @@ struct WideShared {
 };
 constexpr int kWideStaticLds = kTokBuf * 4 + kWideFilter * 8 + (int)sizeof(WideShared) + 512;   // + alignment slack
 
-// A workgroup barrier that other waves' reads PAST the vector L1 may rely on.  Between the waves of a workgroup
-// plain stores and plain loads are ordered by the L1 they share, and the barrier does not wait for the stores
-// to leave it; a load that goes straight to L2 (load_fresh, the table's atomic loads) could overtake a store of
-// another wave that is still on its way there.  So the stores are awaited before the barrier.
-__device__ __forceinline__ void sync_after_global_stores() {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-}
-
 template <bool LDS>
 __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) {
   __shared__ int32_t tokbuf[kTokBuf];
   __shared__ u64 filter[kWideFilter];
   __shared__ WideShared sh;
   // a short appended call (its length is known on the device only): one wave, probing the table where it
-  // lives; the other waves leave (a barrier does not wait for waves that have ended)
+  // lives; the other waves leave (the one-wave helper executes no workgroup barrier: see wave_sync)
   if (!(a.flags & Z2Z_RESET) && call_length(a, blockIdx.x) <= kShortAppend) {
     if (threadIdx.x < kWave) lzw_encode_rounds<false>(a, tokbuf, filter);
     return;
@@ -567,7 +583,9 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
   bool filled = false;
   bool stop = false;
   int pos = 0;
+  int n_rounds = 0;
   while (pos < n && !stop) {
+    ++n_rounds;
     if (!filled || (pos + kWideLanes + M > cbase + kTokBuf && cbase + kTokBuf < n)) {
       cbase = pos;
       filled = true;
@@ -764,6 +782,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_encode_wide_kernel(LzwArgs a) 
     st.size[b] = C;
     st.prev_code[b] = prev;
     st.prev_len[b] = prev_len;
+    st.rounds[b] = n_rounds;
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
@@ -925,6 +944,7 @@ __global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
     st.size[b] = C;
     st.prev_code[b] = prev;
     st.prev_len[b] = prev_len;
+    st.rounds[b] = n;                 // one code per step
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
@@ -983,7 +1003,9 @@ __device__ __forceinline__ void lzw_decode_rounds(const LzwArgs& a, int32_t* cod
   int cbase = 0;                      // codebuf holds codes [cbase, cbase + kTokBuf)
   bool filled = false;
   int cpos = 0;                       // codes consumed
+  int n_rounds = 0;
   while (cpos < n && !stop) {
+    ++n_rounds;
     if (!filled || (cpos + kWave > cbase + kTokBuf && cbase + kTokBuf < n)) {
       cbase = cpos;
       filled = true;
@@ -1050,7 +1072,7 @@ __device__ __forceinline__ void lzw_decode_rounds(const LzwArgs& a, int32_t* cod
         status |= Z2Z_ST_BAD_CODE;
         stop = true;
       }
-      __syncthreads();                // the new row is in memory before a later round reads it
+      wave_sync();                    // the new row is in memory before a later round reads it
       continue;
     }
 
@@ -1133,7 +1155,7 @@ __device__ __forceinline__ void lzw_decode_rounds(const LzwArgs& a, int32_t* cod
     } else {
       stop = true;                    // only reached when the first code of the round does not fit
     }
-    __syncthreads();                  // rows written above are in memory before a later round reads them
+    wave_sync();                      // rows written above are in memory before a later round reads them
   }
 
   table_close<LDS>(a, lane, t);
@@ -1141,6 +1163,7 @@ __device__ __forceinline__ void lzw_decode_rounds(const LzwArgs& a, int32_t* cod
     st.size[b] = C;
     st.prev_code[b] = prev;
     st.prev_len[b] = prev_len;
+    st.rounds[b] = n_rounds;
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
@@ -1231,7 +1254,9 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
   int cbase = 0;
   bool filled = false;
   int cpos = 0;
+  int n_rounds = 0;
   while (cpos < n && !stop) {
+    ++n_rounds;
     if (!filled || (cpos + kWideLanes > cbase + kTokBuf && cbase + kTokBuf < n)) {
       cbase = cpos;
       filled = true;
@@ -1461,6 +1486,7 @@ __global__ void __launch_bounds__(kWideLanes) lzw_decode_wide_kernel(LzwArgs a) 
     st.size[b] = C;
     st.prev_code[b] = prev;
     st.prev_len[b] = prev_len;
+    st.rounds[b] = n_rounds;
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
@@ -1567,7 +1593,7 @@ __global__ void __launch_bounds__(kWave) lzw_prune_kernel(LzwArgs a, const int32
     __syncthreads();                                 // nid[e] is read by the entries that extend e
   }
   for (int i = lane; i < st.nslots; i += kWave) t.g[i] = kEmpty;
-  __syncthreads();
+  sync_after_global_stores();                        // the re-insert sweep probes the cleared table past the L1
   for (int e = 0; e < C; ++e) {
     const int n = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&nid[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     if (n < 0) continue;
@@ -1662,6 +1688,7 @@ __global__ void __launch_bounds__(kWave) lzw_prefill_kernel(LzwArgs a) {
 }  // namespace
 
 int z2z_launch_lzw_reset(z2z_ctx* c, hipStream_t s) {
+  c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   hipLaunchKernelGGL(lzw_reset_kernel, dim3(c->cfg.B), dim3(256), 0, s, c->st);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
@@ -1675,9 +1702,8 @@ int z2z_launch_codebook_usage(z2z_ctx* c, const int32_t* codes, const int32_t* n
 }
 
 int z2z_launch_codebook_prune(z2z_ctx* c, const int32_t* keep, int32_t* new_id, int32_t* n_kept, hipStream_t s) {
-  if (!c->prune_prefix && c->cfg.cap > 0) {
-    if (hipMalloc(&c->prune_prefix, (size_t)c->cfg.B * c->cfg.cap * sizeof(int32_t)) != hipSuccess) return Z2Z_ENOMEM;
-  }
+  c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
+  if (!c->prune_prefix && c->cfg.cap > 0) return Z2Z_EHIP;       // (allocated by z2z_create)
   LzwArgs a;
   memset(&a, 0, sizeof(a));
   a.st = c->st;
@@ -1690,6 +1716,7 @@ int z2z_launch_codebook_prune(z2z_ctx* c, const int32_t* keep, int32_t* new_id, 
 
 int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_t* phrase_len, const int32_t* counts,
                                 int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s) {
+  c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
   a.st = c->st;
   a.in = phrases;
@@ -1716,6 +1743,7 @@ static bool wide_pays(int B, int stride) {
 
 int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens, int32_t stride, int32_t flags,
                           int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s) {
+  c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
   a.st = c->st;
   a.in = tokens;
@@ -1747,6 +1775,7 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
 
 int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t flags,
                           int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s) {
+  c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
   a.st = c->st;
   a.in = codes;

@@ -17,6 +17,7 @@ void free_ctx(z2z_ctx* c) {
   (void)hipFree(c->st.size);
   (void)hipFree(c->st.prev_code);
   (void)hipFree(c->st.prev_len);
+  (void)hipFree(c->st.rounds);
   (void)hipFree(c->st.ent_tokens);
   (void)hipFree(c->st.ent_len);
   (void)hipFree(c->st.slots);
@@ -96,9 +97,16 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
   ok = ok && hipMalloc(&st.size, B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.prev_code, B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.prev_len, B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&st.rounds, B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMemset(st.rounds, 0, B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.ent_tokens, B * capn * cfg->M * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.ent_len, B * capn * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&st.slots, B * (size_t)st.nslots * sizeof(unsigned long long)) == hipSuccess;
+  // fixed-size work buffers of calls that must not allocate on a stream: pruning's prefix map, and the pooling
+  // coefficients on the device (the pooling's backward pass)
+  ok = ok && hipMalloc(&c->prune_prefix, B * capn * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&c->coef_dev, sizeof(c->coef)) == hipSuccess;
+  ok = ok && hipMemcpy(c->coef_dev, c->coef, sizeof(c->coef), hipMemcpyHostToDevice) == hipSuccess;
   if (!ok) {
     free_ctx(c);
     return Z2Z_ENOMEM;
@@ -162,6 +170,12 @@ Z2Z_API int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t*
   if (d_entries) *d_entries = ctx->st.ent_tokens;
   if (d_entry_len) *d_entry_len = ctx->st.ent_len;
   if (d_size) *d_size = ctx->st.size;
+  return Z2Z_OK;
+}
+
+Z2Z_API int z2z_lzw_rounds(z2z_ctx* ctx, const int32_t** d_rounds) {
+  if (!ctx || !d_rounds) return Z2Z_EINVAL;
+  *d_rounds = ctx->st.rounds;
   return Z2Z_OK;
 }
 
@@ -388,6 +402,7 @@ Z2Z_API const char* z2z_strerror(int code) {
     case Z2Z_EHIP: return "HIP runtime error";
     case Z2Z_EUNSUPPORTED: return "unsupported dtype or pooling kind";
     case Z2Z_ELIMIT: return "beyond the fixed scratch size of the allocation-free entry point";
+    case Z2Z_ECAPTURE: return "a work buffer would have to grow while the stream is being captured";
     default: return "unknown error";
   }
 }

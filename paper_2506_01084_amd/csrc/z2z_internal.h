@@ -21,6 +21,7 @@ struct LzwState {
   int32_t* size;
   int32_t* prev_code;
   int32_t* prev_len;
+  int32_t* rounds;           // [B] rounds the latest parse kernel took for the sequence (instrumentation)
   int32_t* ent_tokens;
   int32_t* ent_len;
   unsigned long long* slots;
@@ -124,6 +125,20 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
                                   const void* dW_hyper, const z2z_encoder* grad, float* dE, hipStream_t s);
 int z2z_launch_extended_nll(z2z_ctx* c, const void* H, int32_t rows, int32_t rows_per_seq, const void* W_base,
                             const void* W_hyper, const int32_t* targets, float* nll, float* lse, hipStream_t s);
+
+// A work buffer that has to grow is freed and allocated again (hipFree / hipMalloc: the device synchronises that
+// once).  A stream capture does not survive that, so under capture the call is refused instead, before anything
+// is freed: the caller makes one eager call at the shape first.
+inline int z2z_can_allocate(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) return Z2Z_EHIP;
+  return st == hipStreamCaptureStatusNone ? Z2Z_OK : Z2Z_ECAPTURE;
+}
+#define Z2Z_TRY_GROW(s)                        \
+  do {                                         \
+    int _g = z2z_can_allocate(s);              \
+    if (_g != Z2Z_OK) return _g;               \
+  } while (0)
 
 #define Z2Z_HIP_TRY(expr)                      \
   do {                                         \

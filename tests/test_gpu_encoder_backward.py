@@ -217,6 +217,13 @@ def test_backward_on_the_rows_a_keeping_forward_left():
     d_one, g_one = encoder_to_device(one, "bf16"), _grad_buffers(one)
     assert lib.z2z_hyper_encode_backward(h, d_E.data_ptr(), ctypes.byref(d_one.desc), d_dW.data_ptr(),
                                          ctypes.byref(g_one.desc), dE_kept.data_ptr(), api.ENC_KEPT, None) == -1
+    # a codebook change between the keeping call and the backward call makes the kept rows stale: refused
+    ctx.hyper_encode_keep(d_E, d_enc, d_W)
+    d_one_code = torch.zeros((cfg["B"], 1), dtype=torch.int32, device="cuda")
+    scratch_n = torch.empty(cfg["B"], dtype=torch.int32, device="cuda")
+    scratch_st = torch.empty(cfg["B"], dtype=torch.int32, device="cuda")
+    ctx.lzw_decode(d_one_code, None, None, scratch_n, scratch_st, api.APPEND)
+    assert lib.z2z_hyper_encode_backward(*args) == -1
     ctx.close()
     # more slot rows than one pass holds: keeping is refused (the plain backward takes passes)
     ctx = api.Context(B=40, V=V, M=3, cap=600, d=64, dtype="bf16")

@@ -131,13 +131,22 @@ def test_static_entry_point_under_graph_capture_on_a_fresh_context():
     """A fresh context has no buffer of its own for the partials; the allocating entry point would have to call
     hipMalloc inside the capture.  The static one captures and every replay reproduces the eager result."""
     import torch
+    from paper_2506_01084_amd import api
 
     cfg, ctx, ref, E, H, d_E, d_W, d_H = _setup(B=4, rows_per_seq=1, V=2000, d=256, cap=300, seed=8103)
     outs = _outputs(4)
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
+    refused = None
     with torch.cuda.graph(graph, stream=side):
+        # the allocating entry point would have to size the context's buffer now: it says so and enqueues
+        # nothing, and the capture goes on
+        try:
+            ctx.extended_logits(d_H, 1, d_E, d_W, *_outputs(4))
+        except api.Z2ZError as e:
+            refused = e.code
         ctx.extended_logits_static(d_H, 1, d_E, d_W, *outs)
+    assert refused == api.E_CAPTURE
     eager = _outputs(4)
     ctx.extended_logits_static(d_H, 1, d_E, d_W, *eager)
     torch.cuda.synchronize()
