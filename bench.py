@@ -160,8 +160,7 @@ def run_prefill_workload(args, torch, api, wl, name="c2", steps=None, warmup=Non
             ctx.set_option(api.OPT_TIMING, 0)
         with stages["generation_step"]:
             # code of sequence b = argmax of its last position = element b*N of the view starting at N-1
-            ctx.lzw_decode(d_am[N - 1:], d_one, None, d_ntok1, d_st1, api.APPEND, stride=N)
-            ctx.hyper_embed(d_E, d_W, None, max_new=1)
+            ctx.step_update(d_am[N - 1:], d_E, d_W, d_ntok1, d_st1, stride=N)
             ctx.extended_logits(d_Hdec, 1, d_E, d_W, d_am1, d_mx1, d_lse1, None)
         with stages["lzw_decode"]:
             ctx.lzw_decode(d_codes, d_ncodes, d_back, d_nback, d_st2, api.RESET)
@@ -302,8 +301,7 @@ def run_decode_workload(args, torch, api, wl):
     d_lse = torch.empty(B, dtype=torch.float32, device="cuda")
 
     def step(s):
-        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
-        ctx.hyper_embed(d_E, d_W, None, max_new=1)      # the step adds at most one entry per sequence
+        ctx.step_update(new_codes[s], d_E, d_W, d_ntok, d_st)      # codebook update + the new entry's cache row
         ctx.set_option(api.OPT_TIMING, 1)      # HIP events around the decode kernel, on this stream
         ctx.extended_logits(d_H, 1, d_E, d_W, d_am, d_mx, d_lse, None)
         ctx.set_option(api.OPT_TIMING, 0)
@@ -324,8 +322,7 @@ def run_decode_workload(args, torch, api, wl):
     # the same steps captured once in a HIP graph (no event bracketing inside) and replayed: what a
     # serving loop that cannot afford a host round trip per kernel would run
     def step_plain(s):
-        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
-        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+        ctx.step_update(new_codes[s], d_E, d_W, d_ntok, d_st)
         ctx.extended_logits(d_H, 1, d_E, d_W, d_am, d_mx, d_lse, None)
 
     am_eager = d_am.clone()
@@ -346,8 +343,7 @@ def run_decode_workload(args, torch, api, wl):
     d_lp = torch.empty(B, dtype=torch.float32, device="cuda")
 
     def step_sampled(s):
-        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
-        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+        ctx.step_update(new_codes[s], d_E, d_W, d_ntok, d_st)
         ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 2506, s, d_am, d_lp)
 
     for s in range(args.warmup):
@@ -362,8 +358,7 @@ def run_decode_workload(args, torch, api, wl):
 
     # ... and with the top-k / nucleus filters in front of the draw (the logits go through library scratch)
     def step_filtered(s):
-        ctx.lzw_decode(new_codes[s], None, None, d_ntok, d_st, api.APPEND)
-        ctx.hyper_embed(d_E, d_W, None, max_new=1)
+        ctx.step_update(new_codes[s], d_E, d_W, d_ntok, d_st)
         ctx.extended_sample(d_H, 1, d_E, d_W, 0.8, 2506, s, d_am, d_lp, top_k=50, top_p=0.9)
 
     for s in range(args.warmup):

@@ -122,6 +122,18 @@ int z2z_lzw_decode(z2z_ctx* ctx, const int32_t* d_codes, const int32_t* d_n_code
 int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t** d_entry_len,
                  const int32_t** d_size);
 
+/* The codebook side of one generation step in one launch (section 2.3, steps 9-10: the sampled code extends
+ * the codebook; "Hyper-Embedding Cache": only the new hypertoken's vector is computed).  Exactly
+ *   z2z_lzw_decode(ctx, d_codes, d_ones, stride, Z2Z_APPEND, NULL, d_n_tokens, 0, d_status, stream) with d_ones = 1
+ *   for every sequence (ONE code each: the code of sequence b is d_codes[b * stride]), followed by
+ *   z2z_hyper_embed(ctx, d_E, d_W_hyper, NULL, 1, stream)
+ * with the same results bit for bit: the codebook update of the step, then the newest entry's row of the
+ * hyper-embedding cache (recomputed also when the step added no entry; nothing is written when the codebook is
+ * empty).  A decode loop saves a launch per step with it.
+ *   d_codes [B, stride] int32 (column 0 is read); d_n_tokens [B], d_status [B] out as for z2z_lzw_decode */
+int z2z_step_update(z2z_ctx* ctx, const int32_t* d_codes, int32_t stride, const void* d_E, void* d_W_hyper,
+                    int32_t* d_n_tokens, int32_t* d_status, void* stream);
+
 /* Instrumentation: a borrowed device view [B] int32 of how many rounds the latest z2z_lzw_encode or
  * z2z_lzw_decode call took for each sequence.  The parse kernels (section 2.1's sequential loop, restructured)
  * take the elements of a sequence in rounds of up to 64 (one wave) or 256 (four waves) and cut a round at the

@@ -27,7 +27,7 @@ E_INVAL, E_NOMEM, E_HIP, E_UNSUPPORTED, E_LIMIT, E_CAPTURE = -1, -2, -3, -4, -5,
 STATIC_PARTS = 1 << 22
 
 ENC_KEPT = 1
-EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_lzw_rounds", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
+EXPORTS = ["z2z_create", "z2z_destroy", "z2z_reset", "z2z_lzw_encode", "z2z_lzw_decode", "z2z_step_update", "z2z_lzw_rounds", "z2z_codebook", "z2z_codebook_prefill", "z2z_codebook_usage", "z2z_codebook_prune",
            "z2z_hyper_embed", "z2z_hyper_encode", "z2z_hyper_encode_backward", "z2z_hyper_encode_keep", "z2z_extended_logits", "z2z_extended_logits_static", "z2z_extended_sample", "z2z_extended_nll", "z2z_extended_nll_backward", "z2z_hyper_embed_backward", "z2z_set_option",
            "z2z_read_timing", "z2z_read_launches", "z2z_strerror"]
 
@@ -94,6 +94,7 @@ def load_library() -> ctypes.CDLL:
                                    c_void_p, c_void_p]
     lib.z2z_lzw_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32,
                                    c_void_p, c_void_p]
+    lib.z2z_step_update.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.z2z_lzw_rounds.argtypes = [c_void_p, POINTER(c_void_p)]
     lib.z2z_codebook.argtypes = [c_void_p, POINTER(c_void_p), POINTER(c_void_p), POINTER(c_void_p)]
     lib.z2z_codebook_prefill.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
@@ -238,6 +239,16 @@ class Context:
         assert tuple(keep.shape) == (self.B, self.cap) and tuple(new_id.shape) == (self.B, self.cap)
         _check(self._lib.z2z_codebook_prune(self._h, _ptr(keep, torch.int32), _ptr(new_id, torch.int32),
                                             _ptr(n_kept, torch.int32), _stream()), "z2z_codebook_prune")
+
+    def step_update(self, codes: torch.Tensor, E: torch.Tensor, W_hyper: torch.Tensor, n_tokens: torch.Tensor,
+                    status: torch.Tensor, stride: Optional[int] = None) -> None:
+        """One code per sequence (codes[b * stride]) -> codebook update + the newest entry's cache row."""
+        if stride is None:
+            stride = codes.shape[1] if codes.dim() == 2 else 1
+        assert tuple(E.shape) == (self.V, self.d) and tuple(W_hyper.shape) == (self.B, self.cap, self.d)
+        _check(self._lib.z2z_step_update(self._h, _ptr(codes, torch.int32), stride, _ptr(E, self.torch_dtype),
+                                         _ptr(W_hyper, self.torch_dtype), _ptr(n_tokens, torch.int32),
+                                         _ptr(status, torch.int32), _stream()), "z2z_step_update")
 
     def lzw_rounds(self):
         """Zero-copy int32 [B] device tensor: rounds of the latest parse call per sequence (instrumentation)."""

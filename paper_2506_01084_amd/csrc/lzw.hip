@@ -13,7 +13,7 @@
 // when the 160 KiB of a CU allow, at least 1.25); the decoder also keeps (length, first token) of every
 // entry there when it fits.  Tokens and codes are staged in LDS 2048 at a time.  Control flow is
 // wave-uniform (ballots, scalar registers).
-#include "z2z_internal.h"
+#include "hyper_embed_common.h"
 
 #include <string.h>
 
@@ -34,6 +34,7 @@ struct LzwArgs {
   int32_t out_stride;
   int32_t* status;         // [B]
   int32_t lds_ef;          // decode, LDS variant: 1 = (length, first token) of the entries live in LDS too
+  int32_t in_step;         // one-code-at-a-time decoder only: > 0 = row distance of `in` (else `stride`)
 };
 
 __device__ __forceinline__ uint32_t edge_hash(int32_t parent, int32_t tok) {
@@ -796,11 +797,14 @@ __device__ __forceinline__ uint32_t pack_ef(int len, int32_t first) { return ((u
 
 // One code at a time (the textbook loop, wave-uniform): used for short appended calls, where a
 // round of the kernel below would be mostly empty.
+// (a read past the vector L1 of data another wave of the workgroup wrote earlier in the launch)
+__device__ __forceinline__ int32_t load_fresh_i32(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <bool LDS>
-__global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
+__device__ __forceinline__ void lzw_decode_serial_body(const LzwArgs& a, int b, int lane) {
   const LzwState& st = a.st;
-  const int b = blockIdx.x;
-  const int lane = threadIdx.x;
   const int V = st.V, M = st.M, cap = st.cap;
   const bool reset = (a.flags & Z2Z_RESET) != 0;
   const bool ef_lds = LDS && a.lds_ef;
@@ -820,7 +824,7 @@ __global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
   table_open<LDS>(a, b, lane, reset, &t);
 
   const int n = a.in_len ? min(max(__builtin_amdgcn_readfirstlane(a.in_len[b]), 0), a.stride) : a.stride;
-  const int32_t* in = a.in + (size_t)b * a.stride;
+  const int32_t* in = a.in + (size_t)b * (a.in_step > 0 ? a.in_step : a.stride);
   int32_t* out = a.out ? a.out + (size_t)b * a.out_stride : nullptr;
 
   int status = 0;
@@ -925,7 +929,7 @@ __global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
         for (int i = L + 1; i < M; ++i) row[i] = -1;
         ent_len[new_idx] = L + 1;
       }
-      __syncthreads();                // one wave: orders this level's stores before the next level's loads
+      wave_sync();                    // one wave: orders this level's stores before the next level's loads
     }
     // ---- parallel part 2: lane j writes the tokens of code j
     if (out != nullptr && lane < done) {
@@ -948,6 +952,34 @@ __global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
     a.out_n[b] = n_out;
     a.status[b] = status;
   }
+}
+
+template <bool LDS>
+__global__ void __launch_bounds__(kWave) lzw_decode_serial_kernel(LzwArgs a) {
+  lzw_decode_serial_body<LDS>(a, blockIdx.x, threadIdx.x);
+}
+
+// One generation step's codebook side in one launch (section 2.3, steps 9-10; "Hyper-Embedding Cache"): wave 0
+// of the workgroup applies the sequence's new code to its codebook (the one-code-at-a-time update above, table
+// in global memory), then all waves pool the newest entry's constituent embeddings into its row of the cache --
+// what an appended z2z_lzw_decode of one code followed by z2z_hyper_embed of the last entry do in two launches.
+// The newest entry is pooled whether or not this step made it (the row comes out bit-identical).
+constexpr int kStepWaves = 8;
+template <bool BF16>
+__global__ void __launch_bounds__(kStepWaves * kWave) lzw_step_update_kernel(LzwArgs a, z2z_embed::EmbedArgs ea) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (w == 0) lzw_decode_serial_body<false>(a, b, lane);
+  sync_after_global_stores();          // the entry's row and the size are in memory before the other waves read them
+  const int C = min(__builtin_amdgcn_readfirstlane(load_fresh_i32(a.st.size + b)), a.st.cap);
+  if (C <= 0) return;
+  const size_t row = (size_t)b * a.st.cap + (C - 1);
+  const int L = min(max(__builtin_amdgcn_readfirstlane(load_fresh_i32(a.st.ent_len + row)), 1), a.st.M);
+  int32_t toks[Z2Z_MAX_M];
+#pragma unroll
+  for (int j = 0; j < Z2Z_MAX_M; ++j) toks[j] = j < L ? load_fresh_i32(a.st.ent_tokens + row * a.st.M + j) : 0;
+  if (w < ea.split) z2z_embed::embed_row<BF16>(ea, toks, L, row, lane, w);
 }
 
 // Entry data written earlier in the same launch is read past the vector L1.
@@ -1718,6 +1750,7 @@ int z2z_launch_codebook_prefill(z2z_ctx* c, const int32_t* phrases, const int32_
                                 int32_t n_max, int32_t flags, int32_t* n_added, int32_t* status, hipStream_t s) {
   c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
+  memset(&a, 0, sizeof(a));
   a.st = c->st;
   a.in = phrases;
   a.in_len = counts;
@@ -1745,6 +1778,7 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
                           int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s) {
   c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
+  memset(&a, 0, sizeof(a));
   a.st = c->st;
   a.in = tokens;
   a.in_len = lens;
@@ -1777,6 +1811,7 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
                           int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s) {
   c->enc_kept = false;   // the rows a keeping encoder pass left behind belong to the codebook as it was
   LzwArgs a;
+  memset(&a, 0, sizeof(a));
   a.st = c->st;
   a.in = codes;
   a.in_len = n_codes;
@@ -1805,6 +1840,36 @@ int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_cod
     hipLaunchKernelGGL(lzw_decode_kernel<true>, dim3(c->cfg.B), dim3(kWave), smem, s, a);
   else
     hipLaunchKernelGGL(lzw_decode_kernel<false>, dim3(c->cfg.B), dim3(kWave), 0, s, a);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
+int z2z_launch_step_update(z2z_ctx* c, const int32_t* codes, int32_t stride, const void* E, void* W_hyper,
+                           int32_t* n_tokens, int32_t* status, hipStream_t s) {
+  c->enc_kept = false;
+  LzwArgs a;
+  memset(&a, 0, sizeof(a));
+  a.st = c->st;
+  a.in = codes;
+  a.in_len = nullptr;
+  a.stride = 1;                         // one code per sequence; `stride` is the distance between them
+  a.flags = Z2Z_APPEND;
+  a.out = nullptr;
+  a.out_n = n_tokens;
+  a.out_stride = 0;
+  a.status = status;
+  a.lds_ef = 0;
+  a.in_step = stride;
+  z2z_embed::EmbedArgs ea;
+  z2z_embed::fill_embed_args(c, E, W_hyper, &ea);
+  const int chunks = c->cfg.d / (c->cfg.dtype == Z2Z_BF16 ? 8 : 4);
+  int split = 1;
+  while (split < kStepWaves && chunks >= 128 * split) split *= 2;    // a wave takes at least 64 chunks of the row
+  ea.split = split;
+  if (c->cfg.dtype == Z2Z_BF16)
+    hipLaunchKernelGGL(lzw_step_update_kernel<true>, dim3(c->cfg.B), dim3(kStepWaves * kWave), 0, s, a, ea);
+  else
+    hipLaunchKernelGGL(lzw_step_update_kernel<false>, dim3(c->cfg.B), dim3(kStepWaves * kWave), 0, s, a, ea);
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }

@@ -173,6 +173,15 @@ Z2Z_API int z2z_codebook(z2z_ctx* ctx, const int32_t** d_entries, const int32_t*
   return Z2Z_OK;
 }
 
+Z2Z_API int z2z_step_update(z2z_ctx* ctx, const int32_t* d_codes, int32_t stride, const void* d_E, void* d_W_hyper,
+                            int32_t* d_n_tokens, int32_t* d_status, void* stream) {
+  if (!ctx || !d_codes || !d_n_tokens || !d_status || stride < 1) return Z2Z_EINVAL;
+  if (ctx->cfg.cap > 0 && (!d_E || !d_W_hyper)) return Z2Z_EINVAL;
+  if (!aligned16(d_E) || !aligned16(d_W_hyper)) return Z2Z_EINVAL;
+  return z2z_launch_step_update(ctx, d_codes, stride, d_E, d_W_hyper, d_n_tokens, d_status,
+                                static_cast<hipStream_t>(stream));
+}
+
 Z2Z_API int z2z_lzw_rounds(z2z_ctx* ctx, const int32_t** d_rounds) {
   if (!ctx || !d_rounds) return Z2Z_EINVAL;
   *d_rounds = ctx->st.rounds;

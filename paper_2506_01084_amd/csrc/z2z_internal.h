@@ -97,6 +97,8 @@ int z2z_launch_lzw_encode(z2z_ctx* c, const int32_t* tokens, const int32_t* lens
                           int32_t* codes, int32_t* n_codes, int32_t out_stride, int32_t* status, hipStream_t s);
 int z2z_launch_lzw_decode(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t flags,
                           int32_t* tokens, int32_t* n_tokens, int32_t out_stride, int32_t* status, hipStream_t s);
+int z2z_launch_step_update(z2z_ctx* c, const int32_t* codes, int32_t stride, const void* E, void* W_hyper,
+                           int32_t* n_tokens, int32_t* status, hipStream_t s);
 int z2z_launch_codebook_usage(z2z_ctx* c, const int32_t* codes, const int32_t* n_codes, int32_t stride, int32_t* usage,
                               hipStream_t s);
 int z2z_launch_codebook_prune(z2z_ctx* c, const int32_t* keep, int32_t* new_id, int32_t* n_kept, hipStream_t s);
