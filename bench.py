@@ -418,7 +418,9 @@ def run_decode_workload(args, torch, api, wl):
     return dict(workload=cfg["name"], steps=timed, us_per_step=us, graph_us_per_step=graph_us,
                 graph_frac=bytes_step / (graph_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
                 sample_topk50_topp09_us_per_step=filtered_us, learned_encoder_us_per_step=learned_us, learned_encoder_graph_us_per_step=learned_graph_us,
-                sample_us_per_step=sample_us, sample_frac=bytes_step / (sample_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
+                sample_us_per_step=sample_us, sample_frac=bytes_step / (sample_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                sample_topk50_topp09_frac=bytes_step / (filtered_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                learned_encoder_frac=bytes_step / (learned_us * 1e-6) / 1e9 / PEAK_HBM_GBS, algorithmic_bytes=bytes_step, achieved_GBs=gbs,
                 peak_GBs=PEAK_HBM_GBS, frac=gbs / PEAK_HBM_GBS, mean_codebook_size=float(sizes.mean()),
                 roofline={"bound": "hbm", "kernel": "logits_decode_kernel (64 rows, config 3)", "achieved": k_gbs,
                           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": k_gbs / PEAK_HBM_GBS,

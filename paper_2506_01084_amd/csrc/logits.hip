@@ -361,6 +361,11 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   // pass on the tile kernel takes the base vocabulary (all rows at once) and only the hyper units run here
   const bool decode_step = rows_per_seq == 1 && c->decode_ready && c->opt_decode_kernel != 1;
   const bool decode_split = decode_step && fast_ok && rows > 64 && c->opt_logits_kernel != 1;
+  // a few rows per sequence (2..64: a verification step over drafted codes, a short chunk): every sequence's
+  // W_hyper meets only its own rows, so the hyper part is bandwidth-bound like the decode step's; it goes to
+  // that kernel's matrix-core units (one pass over each W_hyper), the base vocabulary to the tile kernel
+  const bool seq_split = !decode_step && fast_ok && rows_per_seq >= 2 && rows_per_seq <= 64 && cap > 0 &&
+                         c->decode_ready && c->opt_decode_kernel != 1 && c->opt_logits_kernel != 1;
   if (decode_step && !decode_split) {
     int n_parts = z2z_logits_decode_parts(c);
     int rc = reserve((size_t)n_parts * rows);
@@ -394,6 +399,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     z2z_logits_decode_units(&base_columns, &hyper_columns);
     hyp_strips = (cap + hyper_columns - 1) / hyper_columns;
   }
+  if (seq_split) hyp_strips = z2z_logits_decode_seq_units(c);
   const int n_parts = base_strips + hyp_strips;
   int rc = reserve((size_t)n_parts * rows);
   if (rc != Z2Z_OK) return rc;
@@ -415,9 +421,10 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   int ns = 0;
   rc = z2z_launch_logits_part(c, false, fast_base, a, W_base, V, 0, 0, strip_b, rows, rows_per_seq, &ns, timed, s);
   if (rc != Z2Z_OK) return rc;
-  if (cap > 0 && decode_split) {
+  if (cap > 0 && (decode_split || seq_split)) {
     int np = 0;
-    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, nullptr, nullptr, s, base_strips, &parts);
+    rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &np, false, nullptr, nullptr, s, base_strips, &parts,
+                                  seq_split ? rows_per_seq : 1);
     if (rc != Z2Z_OK) return rc;
   } else if (cap > 0) {
     rc = z2z_launch_logits_part(c, true, fast_hyper, a, W_hyper, cap, V, base_strips, strip_h, rows, rows_per_seq, &ns, false, s);

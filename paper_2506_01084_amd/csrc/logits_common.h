@@ -511,7 +511,10 @@ struct z2z_sample_params {
 // parts: where the partial triples go (nullptr: the context's buffers)
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s,
-                             int hyper_only_base_parts = -1, const z2z_parts* parts = nullptr);
+                             int hyper_only_base_parts = -1, const z2z_parts* parts = nullptr, int rows_per_seq = 1);
+// rows_per_seq in 2..64 (with hyper_only_base_parts >= 0): the hyper part on the matrix-core units, one workgroup
+// per sequence and 256 rows of its W_hyper; parts per row then: base parts + z2z_logits_decode_seq_units
+int z2z_logits_decode_seq_units(const z2z_ctx* c);
 // `logits` hold logit / temperature as the decode kernel stored them, `row_stat` the rows' maxima, then their
 // log-sum-exps, of those values; `work` is scratch of z2z_sample_truncated_work_floats(rows) floats.
 int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,

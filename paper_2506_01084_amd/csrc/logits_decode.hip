@@ -77,6 +77,10 @@ struct DecodeArgs {
   // leaves its partial tile in `partial`; linear_reduce_kernel adds them up and runs the epilogue
   int32_t ksplit;
   float* partial;           // [n_groups * n_base_units][ksplit][unit rows * 64]
+  // MODE 4, the hyper part of a call with 2..64 hidden rows per sequence: workgroup (b, u) takes rows
+  // [256 u, 256 u + 256) of W_hyper[b] against the sequence's rows_per_seq hidden rows
+  int32_t rows_per_seq;
+  int32_t seq_units;        // ceil(cap / 256)
 };
 
 __device__ __forceinline__ void fold_value(Triple& t, float x, int col) {
@@ -171,14 +175,34 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   // weight rows per unit: 256 for the vocabulary; a dense layer has few output rows and needs many
   // workgroups to fill the machine, so its units are 64 rows
   constexpr int UNIT = MODE == 3 ? D_LINEAR_UNIT : D_BASE_UNIT;
+  // MODE 4 (a sequence's own weights against its few hidden rows): `group` is the sequence, `unit` the block of
+  // 256 rows of its W_hyper, of which only the first C_b exist
+  constexpr bool SEQ = MODE == 4;
   float* tile = reinterpret_cast<float*>(lds);                      // [UNIT][64]
   float* slots = reinterpret_cast<float*>(lds + D_TILE_BYTES);       // [2][8][64][D_SLOT_STRIDE]
+  const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
   const int v0 = unit * UNIT;
-  const int h0 = group * 64;
-  const int n_rows = (MODE == 3 && a.rows_dev) ? min(a.B, *a.rows_dev) : a.B;
+  const int h0 = SEQ ? group * a.rows_per_seq : group * 64;
+  const int n_rows = SEQ ? h0 + a.rows_per_seq : ((MODE == 3 && a.rows_dev) ? min(a.B, *a.rows_dev) : a.B);
   if (h0 >= n_rows) return;                        // (the whole workgroup: nothing is shared yet)
   const int n_h = min(64, n_rows - h0);            // hidden rows of this group
-  const int chunks_per_row = a.d >> 3;             // 16-byte chunks per row
+  const uint4* Wsrc = SEQ ? a.W_hyper + (size_t)group * a.cap * chunks_per_row : a.W_base;
+  const int w_valid = SEQ ? min(max(a.size[group], 0), a.cap) : a.V;      // weight rows that exist
+  const int col0 = SEQ ? a.V : 0;                  // column of weight row 0 in a logits row
+  const int part = SEQ ? a.n_base_units + unit : unit;
+  if (SEQ && v0 >= w_valid) {
+    // none of this block's rows exist: the part is empty for every hidden row of the sequence
+    if (threadIdx.x < n_h) {
+      const size_t p = (size_t)(h0 + threadIdx.x) * a.n_parts + part;
+      a.part_m[p] = kNegInf;
+      a.part_s[p] = 0.f;
+      a.part_i[p] = kNoColumn;
+    }
+    return;
+  }
+  // 16-row blocks to stream: all of the unit, or (MODE 4) those that hold existing rows, in fours
+  const int n_blk = SEQ ? min(UNIT / 16, (((min(UNIT, w_valid - v0) + 15) >> 4) + 3) & ~3) : UNIT / 16;
+  const int g_eff = SEQ ? (n_h + 15) >> 4 : 4;     // groups of 16 hidden rows that hold a valid row
   const int n_slices = a.d / D_KSLICE;
   const int n_phases_all = (n_slices + 7) >> 3;
   // this workgroup's share of K: phases [phase0, phase0 + n_phases) (all of them unless MODE 3 splits K)
@@ -194,16 +218,20 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   // One step = one 16-row block of one phase.  Weight blocks are requested three steps ahead into four
   // register buffers (the loop is unrolled by four so that each buffer has a fixed name); requests past
   // the end of the unit re-read its last block.
-  const int n_steps = n_phases * N_BLK;
+  const int n_steps = n_phases * n_blk;
+  // step -> (phase, block): n_blk is 4, 8, 12 or 16 and there are at most a few hundred steps, for which the
+  // multiplication below divides exactly
+  const uint32_t inv_blk = (65536u + (uint32_t)n_blk - 1) / (uint32_t)n_blk;
+  auto phase_of = [&](int step) { return SEQ ? (int)(((uint32_t)step * inv_blk) >> 16) : step / N_BLK; };
   auto chunk0 = [&](int phase) {
     const int slice = min((phase0 + phase) * 8 + wave, n_slices - 1);
     return slice * (D_KSLICE / 8) + kg;            // first 16-byte chunk of this lane in the slice
   };
   auto load_block = [&](uint4 (&w)[D_QB], int step) {
     step = min(step, n_steps - 1);
-    const int phase = step / N_BLK, blk = step - phase * N_BLK;
-    const int wrow = min(v0 + blk * 16 + m16, a.V - 1);
-    const uint4* p = a.W_base + (size_t)wrow * chunks_per_row + chunk0(phase);
+    const int phase = phase_of(step), blk = step - phase * n_blk;
+    const int wrow = min(v0 + blk * 16 + m16, w_valid - 1);
+    const uint4* p = Wsrc + (size_t)wrow * chunks_per_row + chunk0(phase);
 #pragma unroll
     for (int q = 0; q < D_QB; ++q) w[q] = p[q * 4];
   };
@@ -213,12 +241,14 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int hrow = min(h0 + g * 16 + m16, n_rows - 1);
+      if (!SEQ || g < g_eff) {
 #pragma unroll
-      for (int q = 0; q < D_QB; ++q) hreg[g][q] = a.H[(size_t)hrow * chunks_per_row + c0 + q * 4];
+        for (int q = 0; q < D_QB; ++q) hreg[g][q] = a.H[(size_t)hrow * chunks_per_row + c0 + q * 4];
+      }
     }
   };
   auto compute = [&](const uint4 (&w)[D_QB], int step) {
-    const int phase = step / N_BLK, blk = step - phase * N_BLK;
+    const int phase = phase_of(step), blk = step - phase * n_blk;
     const bool valid = (phase0 + phase) * 8 + wave < n_slices;   // wave-uniform
     f32x4 acc[4];
 #pragma unroll
@@ -228,8 +258,9 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
       for (int q = 0; q < D_QB; ++q)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[q]),
-                                                           __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
+          if (!SEQ || g < g_eff)                               // (wave-uniform)
+            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[q]),
+                                                             __builtin_bit_cast(bf16x8, hreg[g][q]), acc[g], 0, 0, 0);
     }
     // slot layout: hidden-row column c at c * D_SLOT_STRIDE, its 16 weight rows contiguous; this lane
     // holds rows 4 * kg .. + 3 of column g * 16 + m16: one 16-byte store per group
@@ -251,14 +282,14 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     float* trow = tile + (blk * 16 + 2 * wave) * 64 + lane;
     trow[0] += s0;
     trow[64] += s1;
-    if (blk == N_BLK - 1 && phase + 1 < n_phases) load_h(phase + 1);   // next phase: next slice of H
+    if (blk == n_blk - 1 && phase + 1 < n_phases) load_h(phase + 1);   // next phase: next slice of H
   };
   uint4 w0[D_QB], w1[D_QB], w2[D_QB], w3[D_QB];
   load_h(0);
   load_block(w0, 0);
   load_block(w1, 1);
   load_block(w2, 2);
-  for (int step = 0; step < n_steps; step += 4) {   // N_BLK is a multiple of 4, so is n_steps
+  for (int step = 0; step < n_steps; step += 4) {   // n_blk is a multiple of 4, so is n_steps
     load_block(w3, step + 3);
     compute(w0, step);
     load_block(w0, step + 4);
@@ -306,9 +337,9 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
   Draw dr = empty_draw();
   Noise noise;
   noise.group = -1;
-  const int r_hi = min(D_BASE_UNIT, a.V - v0);
+  const int r_hi = min(D_BASE_UNIT, w_valid - v0);
   for (int r = seg * 32; r < min(seg * 32 + 32, r_hi); ++r)
-    fold_logit<MODE>(a, t, dr, noise, tile[r * 64 + j], h0 + j, v0 + r);
+    fold_logit<MODE>(a, t, dr, noise, tile[r * 64 + j], h0 + j, col0 + v0 + r);
   xch[tid] = t;
   if (MODE == 1) xdr[tid] = dr;
   __syncthreads();
@@ -316,7 +347,7 @@ __device__ __forceinline__ void base_unit(const DecodeArgs& a, int unit, int gro
     Triple r = xch[j];
 #pragma unroll
     for (int s = 1; s < 8; ++s) merge_triple(r, xch[s * 64 + j]);
-    const size_t p = (size_t)(h0 + j) * a.n_parts + unit;
+    const size_t p = (size_t)(h0 + j) * a.n_parts + part;
     a.part_m[p] = r.m;
     a.part_s[p] = r.s;
     if (MODE == 1) {
@@ -439,7 +470,9 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
   // that finish last should be the short ones
   const int n_hyper = a.B * a.units_per_seq;
   const int bid = blockIdx.x;
-  if (bid < n_hyper) {
+  if (MODE == 4) {
+    base_unit<MODE>(a, bid % a.seq_units, bid / a.seq_units, 0, lds);
+  } else if (bid < n_hyper) {
     hyper_unit<MODE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
   } else {
     const int bu = bid - n_hyper;
@@ -489,9 +522,10 @@ __global__ void __launch_bounds__(D_THREADS) linear_reduce_kernel(DecodeArgs a) 
 // is given as well: the partials are then those of the scaled logits, and nothing is drawn).
 int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, const void* W_hyper, int* n_parts,
                              bool timed, const z2z_sample_params* sample, float* logits, hipStream_t s,
-                             int hyper_only_base_parts, const z2z_parts* parts) {
+                             int hyper_only_base_parts, const z2z_parts* parts, int rows_per_seq) {
   c->n_launch[Z2Z_KERNEL_DECODE]++;
   DecodeArgs a;
+  memset(&a, 0, sizeof(a));
   a.H = reinterpret_cast<const uint4*>(H);
   a.W_base = reinterpret_cast<const uint4*>(W_base);
   a.W_hyper = reinterpret_cast<const uint4*>(W_hyper);
@@ -525,6 +559,25 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
     a.n_parts = *n_parts;
     grid = (unsigned)(a.B * a.units_per_seq);
     if (grid == 0) return Z2Z_OK;
+  }
+  if (rows_per_seq > 1) {
+    // the hyper part of a call with 2..64 hidden rows per sequence (the base vocabulary is another launch's):
+    // one workgroup per (sequence, 256 rows of its W_hyper), the matrix-core units
+    if (hyper_only_base_parts < 0 || rows_per_seq > 64 || sample || logits) return Z2Z_EUNSUPPORTED;
+    a.rows_per_seq = rows_per_seq;
+    a.seq_units = (a.cap + D_BASE_UNIT - 1) / D_BASE_UNIT;
+    *n_parts = a.n_base_units + a.seq_units;
+    a.n_parts = *n_parts;
+    grid = (unsigned)(a.B * a.seq_units);
+    if (grid == 0) return Z2Z_OK;
+    if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
+    hipLaunchKernelGGL(logits_decode_kernel<4>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+    if (timed) {
+      Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
+      c->n_timed++;
+    }
+    Z2Z_HIP_TRY(hipGetLastError());
+    return Z2Z_OK;
   }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
   if (logits)                                         // with `sample`: stored and folded as logit / temperature
@@ -596,6 +649,8 @@ int z2z_logits_decode_parts(const z2z_ctx* c) {
   return (c->cfg.V + D_BASE_UNIT - 1) / D_BASE_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
 }
 
+int z2z_logits_decode_seq_units(const z2z_ctx* c) { return (c->cfg.cap + D_BASE_UNIT - 1) / D_BASE_UNIT; }
+
 void z2z_logits_decode_units(int* base_columns, int* hyper_columns) {
   *base_columns = D_BASE_UNIT;
   *hyper_columns = D_UNIT;
@@ -614,6 +669,8 @@ int z2z_logits_decode_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_decode_kernel<4>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS));
   return Z2Z_OK;
 }

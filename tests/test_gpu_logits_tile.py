@@ -209,3 +209,128 @@ def test_full_size_every_row_position_of_a_tile(name):
         errs = check_logits_rows(r, am[pick], mx[pick], lse[pick], None)
         print(f"  seq {b}: {pick.size} rows, errors {errs}  {time.time() - t0:.1f}s", flush=True)
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# 2..64 hidden rows per sequence: the hyper part runs on the decode kernel's matrix-core units (one workgroup
+# per sequence and 256 rows of its W_hyper), the base vocabulary on the tile kernel; every row
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,rows_per_seq,V,d,M,cap,pool", [
+    (5, 2, 1000, 128, 3, 300, "mean"),          # two rows per sequence, cap spans two blocks of 256
+    (4, 17, 700, 256, 4, 1030, "weighted"),     # one row past a 16-row group; five blocks, the last with 6 rows
+    (70, 5, 520, 384, 3, 257, "mean"),          # 350 rows: two row tiles of the base part; cap one past a block
+    (3, 64, 300, 1024, 5, 100, "mean"),         # the most rows per sequence this path takes; one full K phase
+    (6, 33, 2000, 4096, 3, 64, "mean"),         # widest rows: four K phases
+])
+def test_few_rows_per_sequence_every_row(B, rows_per_seq, V, d, M, cap, pool):
+    import torch
+    from paper_2506_01084_amd import api
+
+    N = 2400
+    cfg = dict(name="few", B=B, N=N, V=V, d=d, dtype="bf16", M=M, cap=cap, zipf_s=1.2, copy_frac=0.4, span=(2, 7),
+               mode="motif", pool=pool, seed=9900 + V + d)
+    print(f"[case] few rows per sequence B={B} rows/seq={rows_per_seq} V={V} d={d} M={M} cap={cap} {pool}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    lens[1] = 0                          # an empty codebook
+    lens[2] = 9                          # a handful of entries
+    if B > 3:
+        lens[3] = 300                    # a codebook that ends inside a block
+    E = wl.make_embeddings(cfg)
+    rows = B * rows_per_seq
+    H = wl.make_hidden(cfg, rows)
+    w = wl.make_pool_weights(cfg)
+    ctx = _ctx(cfg)
+    gpu_encode(ctx, tokens, lens)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    sizes = [len(r[1]) for r in ref]
+    print(f"  codebook sizes {sizes[:8]}", flush=True)
+    assert sizes[1] == 0 and max(sizes) == cap
+    d_E = torch_storage(E, "bf16")
+    d_W = torch.full((B, cap, d), 1.0, dtype=torch.bfloat16, device="cuda")      # unused slots hold ones
+    ctx.hyper_embed(d_E, d_W)
+    d_Wp = d_W.clone()
+    for b in range(B):
+        d_Wp[b, sizes[b]:] = 900.0       # rows that do not exist must never be read into a result
+    d_H = torch_storage(H, "bf16")
+    am = torch.full((rows,), -5, dtype=torch.int32, device="cuda")
+    mx = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
+    lse = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
+    before = ctx.read_launches()
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am, mx, lse, None)
+    torch.cuda.synchronize()
+    after = ctx.read_launches()
+    assert after["decode"] == before["decode"] + 1 and after["tile_base"] == before["tile_base"] + 1
+    assert after["tile_hyper"] == before["tile_hyper"] and after["general"] == before["general"]
+    am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+    worst = dict(max=0.0, lse=0.0)
+    for b in range(B):
+        Wr = oracle.hyper_embed(E, "bf16", ref[b][1], cap, pool, w)
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        r = oracle.extended_logits(H[sl], E, Wr, sizes[b], "bf16")
+        errs = check_logits_rows(r, am_h[sl], mx_h[sl], lse_h[sl], None)
+        worst = {k: max(worst[k], errs[k]) for k in worst}
+    print(f"  every row ok, worst {worst}", flush=True)
+    # the tile kernels on the same call give the same picks
+    ctx.set_option(api.OPT_DECODE_KERNEL, 1)
+    am2, mx2, lse2 = torch.empty_like(am), torch.empty_like(mx), torch.empty_like(lse)
+    ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am2, mx2, lse2, None)
+    torch.cuda.synchronize()
+    assert ctx.read_launches()["tile_hyper"] == after["tile_hyper"] + 1
+    am2_h, mx2_h, lse2_h = am2.cpu().numpy(), mx2.cpu().numpy(), lse2.cpu().numpy()
+    for b in range(B):
+        Wr = oracle.hyper_embed(E, "bf16", ref[b][1], cap, pool, w)
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        check_logits_rows(oracle.extended_logits(H[sl], E, Wr, sizes[b], "bf16"), am2_h[sl], mx2_h[sl], lse2_h[sl], None)
+    # (picks may differ between the two kernels only where two logits tie within rounding -- a pooled row of a
+    # repeated token equals that token's base row; both were held to the oracle's margin rule above)
+    check_rows = (am != am2).cpu().numpy()
+    assert check_rows.mean() < 0.05
+    assert torch.allclose(mx, mx2, rtol=1e-4, atol=1e-4) and torch.allclose(lse, lse2, rtol=1e-4, atol=1e-4)
+    ctx.close()
+
+
+def test_few_rows_per_sequence_planted_hyper_columns():
+    """Planted rows for the matrix-core hyper units: every existing hyper column of every sequence is the pick of
+    one hidden row of that sequence (64 rows per sequence, 64 columns planted per call, several calls)."""
+    import torch
+
+    B, V, d, cap, M, rps = 3, 400, 256, 600, 3, 64
+    cfg = dict(name="plant2", B=B, N=2000, V=V, d=d, dtype="bf16", M=M, cap=cap, zipf_s=1.1, copy_frac=0.4, span=(2, 6),
+               mode="motif", pool="mean", seed=7300)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    lens[1] = 500
+    ctx = _ctx(cfg)
+    gpu_encode(ctx, tokens, lens)
+    sizes = [len(r[1]) for r in oracle_encode_batch(tokens, lens, V, M, cap)]
+    assert sizes[0] == cap and 0 < sizes[1] < cap
+    Wb = wl.make_embeddings(cfg)
+    Wh = wl.normal_matrix(cfg["seed"] + 50, B * cap, d, 0.02, "bf16").reshape(B, cap, d)
+    d_Wb, d_Wh = torch_storage(Wb, "bf16"), torch_storage(Wh, "bf16")
+    rng = np.random.Generator(np.random.PCG64(cfg["seed"] + 60))
+    n_calls = (cap + rps - 1) // rps
+    for call in range(n_calls):
+        H = wl.make_hidden(wl.scaled(cfg, seed=cfg["seed"] + call), B * rps)
+        planted = np.full(B * rps, -1, dtype=np.int64)
+        for b in range(B):
+            cols = np.arange(call * rps, min((call + 1) * rps, sizes[b]))
+            where = b * rps + rng.permutation(rps)[:cols.size]
+            H[where] = oracle.round_to_storage(64.0 * oracle.to_f64(Wh[b, cols], "bf16"), "bf16")
+            planted[where] = V + cols
+        am = torch.empty(B * rps, dtype=torch.int32, device="cuda")
+        mx = torch.empty(B * rps, dtype=torch.float32, device="cuda")
+        lse = torch.empty(B * rps, dtype=torch.float32, device="cuda")
+        before = ctx.read_launches()["decode"]
+        ctx.extended_logits(torch_storage(H, "bf16"), rps, d_Wb, d_Wh, am, mx, lse, None)
+        torch.cuda.synchronize()
+        assert ctx.read_launches()["decode"] == before + 1
+        am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+        for b in range(B):
+            sl = slice(b * rps, (b + 1) * rps)
+            r = oracle.extended_logits(H[sl], Wb, Wh[b], sizes[b], "bf16")
+            has = planted[sl] >= 0
+            assert (r["argmax"][has] == planted[sl][has]).all() and (r["margin"][has] > 0.5).all()
+            assert (am_h[sl][has] == planted[sl][has]).all(), f"call {call} seq {b}"
+            check_logits_rows(r, am_h[sl], mx_h[sl], lse_h[sl], None)
+    ctx.close()
