@@ -53,6 +53,33 @@ constexpr int F_PAIRS = 32 / F_WAVES;                  // request pairs (8 rows 
 #ifndef F_SPREAD
 #define F_SPREAD (F_WAVES == 4 ? 5 : 4)
 #endif
+// Pacing of the two operand paths inside the MFMA stream.  With one wave per SIMD, and the four waves of a
+// workgroup in step (they meet at a barrier every slab), whatever a wave issues as a burst arrives at the LDS or
+// at the memory pipeline together with the other waves' bursts, and the MFMAs wait behind it.  Measured on the
+// 32768 x 4096 x 128256 problem, same box, each step on top of the previous one: fragment reads of the next
+// k-step one per MFMA instead of eight ahead of the k-step: -2.1 %; the same for the first k-step of the next slab
+// after the hand-over barrier: -1.4 %; the two requests of a pair two MFMAs apart (a request every 2-3 MFMAs)
+// instead of back to back every five: -0.7 %.  Closer spacing of the requests (every 1.5 MFMAs) or wider (every 3,
+// 3.5) is slower, and so are reads that start right at the first MFMA of a k-step.
+//   F_LDS_SPREAD       1 = read n of the next k-step goes out after MFMA F_RD_FIRST + n * F_RD_EVERY of the
+//                      current one (in the order of first use), 0 = all eight ahead of the k-step
+//   F_HANDOVER_SPREAD  1 = the same for the reads that follow the hand-over barrier
+//   F_SPLIT_PAIR       n > 0 = the hidden-row request of a pair goes out n MFMAs after the vocabulary-row one
+#ifndef F_LDS_SPREAD
+#define F_LDS_SPREAD 1
+#endif
+#ifndef F_SPLIT_PAIR
+#define F_SPLIT_PAIR 2
+#endif
+#ifndef F_HANDOVER_SPREAD
+#define F_HANDOVER_SPREAD 1
+#endif
+#ifndef F_RD_FIRST
+#define F_RD_FIRST 3
+#endif
+#ifndef F_RD_EVERY
+#define F_RD_EVERY 1
+#endif
 // Request pair i goes out after the MFMA with window index 1 + i * F_SPREAD, counted from the slab
 // hand-over: first the rest of the hand-over k-step (F_KSTEP - F_NJ MFMAs), then the first three k-steps
 // of the next slab.
@@ -244,6 +271,8 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     load16_to_lds<(i) * 1024>(is_ga, voffA[i], isA);                  \
     load16_to_lds<F_OPER + (i) * 1024>(is_gb, voffB[i], isA);         \
   } while (0)
+#define Z2Z_ISSUE_A(i) load16_to_lds<(i) * 1024>(is_ga, voffA[i], isA)
+#define Z2Z_ISSUE_B(i) load16_to_lds<F_OPER + (i) * 1024>(is_gb, voffB[i], isA)
   auto issue_end = [&]() {
     if (lvt < vt_end && ++lslab == n_slabs) {
       lslab = 0;
@@ -263,6 +292,19 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     for (int i = 0; i < F_NI; ++i) f.a[i] = *reinterpret_cast<const uint4*>(A + i * 32 * F_SLAB);
 #pragma unroll
     for (int j = 0; j < F_NJ; ++j) f.b[j] = *reinterpret_cast<const uint4*>(Bt + j * 32 * F_SLAB);
+  };
+
+  // one fragment of a k-step, so that the reads of the next k-step can be handed out between the MFMAs of the
+  // current one; n counts them in the order the MFMAs (vocabulary block i outer, hidden-row block j inner) first
+  // need them: b0, a0, b1 .. b(NJ-1), a1 .. a(NI-1)
+  auto read_one = [&](Frags& f, int stage, int q, int n) {
+    const int base = stage * F_STAGE + (((2 * q + half) ^ sw) << 4);
+    const bool is_a = n == 1 || n > F_NJ;
+    const int idx = n == 0 ? 0 : (n == 1 ? 0 : (n <= F_NJ ? n - 1 : n - F_NJ));
+    if (is_a)
+      f.a[idx] = *reinterpret_cast<const uint4*>(lds + base + offA0 + idx * 32 * F_SLAB);
+    else
+      f.b[idx] = *reinterpret_cast<const uint4*>(lds + base + F_OPER + offB0 + idx * 32 * F_SLAB);
   };
 
   f32x16 acc[F_NI][F_NJ];
@@ -295,17 +337,78 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   // whose window index is 1 + i * F_SPREAD, request pair i is issued (fenced, so that it stays there: a
   // burst of requests backs up the memory pipeline, and a wave that cannot issue its request cannot issue
   // MFMAs either).
-  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi, int w0) {
+  // the two requests of pair i on their own (F_SPLIT_PAIR: the hidden-row half goes out a few MFMAs after the other)
+  auto issue_a = [&](int i) {
+    switch (i) {
+      case 0: Z2Z_ISSUE_A(0); break;
+      case 1: Z2Z_ISSUE_A(1); break;
+      case 2: Z2Z_ISSUE_A(2); break;
+#if F_WAVES == 4
+      case 3: Z2Z_ISSUE_A(3); break;
+      case 4: Z2Z_ISSUE_A(4); break;
+      case 5: Z2Z_ISSUE_A(5); break;
+      case 6: Z2Z_ISSUE_A(6); break;
+      default: Z2Z_ISSUE_A(7); break;
+#else
+      default: Z2Z_ISSUE_A(3); break;
+#endif
+    }
+  };
+  // The MFMAs of blocks [i_lo, i_hi) x [0, F_NJ); w0 = window index of the first one.  After an MFMA
+  // whose window index is 1 + i * F_SPREAD, request pair i is issued (fenced, so that it stays there: a
+  // burst of requests backs up the memory pipeline, and a wave that cannot issue its request cannot issue
+  // MFMAs either).
+  auto issue_b = [&](int i) {
+    switch (i) {
+      case 0: Z2Z_ISSUE_B(0); break;
+      case 1: Z2Z_ISSUE_B(1); break;
+      case 2: Z2Z_ISSUE_B(2); break;
+#if F_WAVES == 4
+      case 3: Z2Z_ISSUE_B(3); break;
+      case 4: Z2Z_ISSUE_B(4); break;
+      case 5: Z2Z_ISSUE_B(5); break;
+      case 6: Z2Z_ISSUE_B(6); break;
+      default: Z2Z_ISSUE_B(7); break;
+#else
+      default: Z2Z_ISSUE_B(3); break;
+#endif
+    }
+  };
+  // The MFMAs of blocks [i_lo, i_hi) x [0, F_NJ); w0 = window index of the first one.  After an MFMA
+  // whose window index is 1 + i * F_SPREAD, request pair i is issued (fenced, so that it stays there: a
+  // burst of requests backs up the memory pipeline, and a wave that cannot issue its request cannot issue
+  // MFMAs either).
+  // `nf` (may be null): the fragments of the k-step (nstage, nq) are read into it, one read after every
+  // F_RD_EVERY-th MFMA starting at MFMA F_RD_FIRST of this call
+  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi, int w0, Frags* nf = nullptr, int nstage = 0, int nq = 0) {
 #pragma unroll
     for (int i = i_lo; i < i_hi; ++i)
 #pragma unroll
       for (int j = 0; j < F_NJ; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
                                                             __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
+        const int local = (i - i_lo) * F_NJ + j;
+        if (F_LDS_SPREAD && nf != nullptr && local >= F_RD_FIRST && (local - F_RD_FIRST) % F_RD_EVERY == 0 &&
+            (local - F_RD_FIRST) / F_RD_EVERY < F_NI + F_NJ) {
+          __builtin_amdgcn_sched_barrier(0);
+          read_one(*nf, nstage, nq, (local - F_RD_FIRST) / F_RD_EVERY);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         const int w = w0 + (i - i_lo) * F_NJ + j;
-        if (!PROBE_NOREQ && w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
+        if (!PROBE_NOREQ && F_SPLIT_PAIR == 0 && w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
           __builtin_amdgcn_sched_barrier(0);
           issue_pair((w - 1) / F_SPREAD);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!PROBE_NOREQ && F_SPLIT_PAIR > 0 && w >= 1 && (w - 1) % F_SPREAD == 0 && (w - 1) / F_SPREAD < F_PAIRS) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_a((w - 1) / F_SPREAD);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!PROBE_NOREQ && F_SPLIT_PAIR > 0 && w >= 1 + F_SPLIT_PAIR && (w - 1 - F_SPLIT_PAIR) % F_SPREAD == 0 &&
+            (w - 1 - F_SPLIT_PAIR) / F_SPREAD < F_PAIRS) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_b((w - 1 - F_SPLIT_PAIR) / F_SPREAD);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -336,12 +439,20 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
     for (int vt = vt0; vt < vt_end; ++vt) {
       for (int slab = 0; slab < n_slabs; ++slab, ++g) {
         const int stage = g & 1;
-        if (!PROBE_MFMA) read_frags(f1, stage, 1);
-        mfma_rows(f0, 0, F_NI, F_REST);
-        if (!PROBE_MFMA) read_frags(f0, stage, 2);
-        mfma_rows(f1, 0, F_NI, F_REST + F_KSTEP);
-        if (!PROBE_MFMA) read_frags(f1, stage, 3);
-        mfma_rows(f0, 0, F_NI, F_REST + 2 * F_KSTEP);
+        if (F_LDS_SPREAD && !PROBE_MFMA) {
+          // the fragments of k-step q + 1 are read between the MFMAs of k-step q (as one burst per wave the four
+          // waves' reads arrive at the LDS together, right after a barrier, and the MFMAs wait behind them)
+          mfma_rows(f0, 0, F_NI, F_REST, &f1, stage, 1);
+          mfma_rows(f1, 0, F_NI, F_REST + F_KSTEP, &f0, stage, 2);
+          mfma_rows(f0, 0, F_NI, F_REST + 2 * F_KSTEP, &f1, stage, 3);
+        } else {
+          if (!PROBE_MFMA) read_frags(f1, stage, 1);
+          mfma_rows(f0, 0, F_NI, F_REST);
+          if (!PROBE_MFMA) read_frags(f0, stage, 2);
+          mfma_rows(f1, 0, F_NI, F_REST + F_KSTEP);
+          if (!PROBE_MFMA) read_frags(f1, stage, 3);
+          mfma_rows(f0, 0, F_NI, F_REST + 2 * F_KSTEP);
+        }
         if (!PROBE_NOREQ) issue_end();          // the request for slab g+1 is out in full
         // last k-step: a quarter of its MFMAs, then the slab hand-over.  It is the same for every slab,
         // the last ones included (no test inside the loop): past the end of the stream the requests
@@ -349,9 +460,13 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         mfma_rows(f1, 0, 1, 1000);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // slab g+1 (the only one in flight) has landed
         __syncthreads();                            // slab g+1 visible to all; everyone has read slab g
-        if (!PROBE_MFMA) read_frags(f0, stage ^ 1, 0);
         if (!PROBE_NOREQ) issue_begin(stage);       // refill this stage with slab g+2
-        mfma_rows(f1, 1, F_NI, 0);
+        if (F_LDS_SPREAD && F_HANDOVER_SPREAD && !PROBE_MFMA) {
+          mfma_rows(f1, 1, F_NI, 0, &f0, stage ^ 1, 0);
+        } else {
+          if (!PROBE_MFMA) read_frags(f0, stage ^ 1, 0);
+          mfma_rows(f1, 1, F_NI, 0);
+        }
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
       const int v0 = vt * FT;
