@@ -475,3 +475,44 @@ def test_prune_equals_prefill_of_the_survivors_and_round_trips():
     s = LZWStream(3, 3, 20)
     s.prefill([(0, 1), (0, 1, 0), (1, 1)])
     assert s.prune([False, True, True]) == [-1, -1, 0] and s.entries == [(1, 1)]
+
+
+# ---------------------------------------------------------------------------
+# entry usage (discussion section: how many of the created hypertokens are ever used again)
+# ---------------------------------------------------------------------------
+def test_usage_counts_each_entry_by_the_phrases_of_the_parse():
+    """usage is pinned per entry, not through its sum: (1) a hand-worked stream; (2) an independent count -- the
+    stream is decoded code by code and every decoded phrase of two or more tokens is looked up, as a tuple, in
+    the codebook, which names its entry without going through the code's arithmetic; (3) codes that name no
+    entry (base tokens, IDs past the codebook) count nothing."""
+    # (1) V = 6: "to be or not" three times at M = 3 (Fig. 1's example continued): codes 0 1 2 3 6 8 10 3,
+    # entries to-be, be-or, or-not, not-to, to-be-or, or-not-to -> entries 0, 2 and 4 are named once each
+    s = LZWStream(6, 3, 100)
+    codes, st = s.encode_chunk([0, 1, 2, 3] * 3)
+    assert st == ST_OK and codes == [0, 1, 2, 3, 6, 8, 10, 3]
+    assert s.entries[:6] == [(0, 1), (1, 2), (2, 3), (3, 0), (0, 1, 2), (2, 3, 0)]
+    assert s.usage(codes) == [1, 0, 1, 0, 1, 0][:len(s.entries)] + [0] * (len(s.entries) - 6)
+    # (2) random streams over tiny alphabets
+    rnd = random.Random(77)
+    for trial in range(300):
+        V = rnd.choice([2, 3, 5])
+        M, cap = rnd.choice([2, 3, 5]), rnd.choice([3, 10, 60])
+        toks = [rnd.randrange(V) for _ in range(rnd.randint(0, 80))]
+        s = LZWStream(V, M, cap)
+        codes, st = s.encode_chunk(toks)
+        assert st == ST_OK
+        back, entries, dst = lzw_decode(codes, V, M, cap)
+        assert dst == ST_OK and back == toks and [tuple(e) for e in entries] == [tuple(e) for e in s.entries]
+        # phrases of the parse, recovered from the token stream and the code count alone: walk the tokens with a
+        # decoder and record each phrase as a tuple
+        d = LZWStream(V, M, cap)
+        want = [0] * len(s.entries)
+        index = {tuple(e): i for i, e in enumerate(s.entries)}
+        for c in codes:
+            phrase, dst = d.decode_chunk([c])
+            assert dst == ST_OK
+            if len(phrase) >= 2:
+                want[index[tuple(phrase)]] += 1
+        assert s.usage(codes) == want
+        # (3) foreign codes count nothing
+        assert s.usage(list(range(V)) + [V + len(s.entries), V + len(s.entries) + 5, -1]) == [0] * len(s.entries)
