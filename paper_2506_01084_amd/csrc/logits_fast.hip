@@ -178,8 +178,11 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   const size_t row_bytes = (size_t)a.d * 2;
   if (MODE == 1 || MODE == 4) {
     if ((int)blockIdx.x >= a.n_work) return;
-    st = blockIdx.x % a.n_strips;
     rt = blockIdx.x / a.n_strips;
+    // workgroup ids go round-robin over the 8 XCDs, and the strips beyond a sequence's C_b are empty: with the
+    // strip taken straight from the id, the XCDs that own the low strips would do all the work (config 5: 9 of 16
+    // strips exist, XCD 0 owned two of them, the others one).  Rotating by the row tile deals them out evenly.
+    st = (int)((blockIdx.x + (unsigned)rt) % (unsigned)a.n_strips);
     const int b = rt / a.row_tiles;
     r0 = b * a.rows_per_seq + (rt % a.row_tiles) * FT;
     r_end = (b + 1) * a.rows_per_seq;
