@@ -83,7 +83,16 @@ constexpr int F_PAIRS = 32 / F_WAVES;                  // request pairs (8 rows 
 // Request pair i goes out after the MFMA with window index 1 + i * F_SPREAD, counted from the slab
 // hand-over: first the rest of the hand-over k-step (F_KSTEP - F_NJ MFMAs), then the first three k-steps
 // of the next slab.
-constexpr int F_REST = F_KSTEP - F_NJ;
+#ifndef F_HO_ROWS
+#define F_HO_ROWS 1
+#endif
+#ifndef F_HO_RD_FIRST
+#define F_HO_RD_FIRST F_RD_FIRST
+#endif
+constexpr int F_REST = F_KSTEP - F_HO_ROWS * F_NJ;   // MFMAs of the hand-over k-step that follow the barrier
+static_assert(!F_LDS_SPREAD || !F_HANDOVER_SPREAD || F_HO_RD_FIRST + (F_NI + F_NJ - 1) * F_RD_EVERY < F_REST,
+              "the reads after the hand-over must all go out before the k-step ends");
+static_assert(!F_LDS_SPREAD || F_RD_FIRST + (F_NI + F_NJ - 1) * F_RD_EVERY < F_KSTEP, "reads of a k-step must fit it");
 constexpr int F_LAST_IN_HANDOVER = (F_REST - 2) / F_SPREAD;          // last pair issued before the slab ends
 static_assert(F_LAST_IN_HANDOVER < F_PAIRS, "spread too small for this layout");
 static_assert(1 + (F_PAIRS - 1) * F_SPREAD < F_REST + 3 * F_KSTEP, "all pairs must be out before the next hand-over");
@@ -383,7 +392,8 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   // MFMAs either).
   // `nf` (may be null): the fragments of the k-step (nstage, nq) are read into it, one read after every
   // F_RD_EVERY-th MFMA starting at MFMA F_RD_FIRST of this call
-  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi, int w0, Frags* nf = nullptr, int nstage = 0, int nq = 0) {
+  auto mfma_rows = [&](const Frags& f, int i_lo, int i_hi, int w0, Frags* nf = nullptr, int nstage = 0, int nq = 0,
+                       int rd_first = F_RD_FIRST) {
 #pragma unroll
     for (int i = i_lo; i < i_hi; ++i)
 #pragma unroll
@@ -391,10 +401,10 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
                                                             __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
         const int local = (i - i_lo) * F_NJ + j;
-        if (F_LDS_SPREAD && nf != nullptr && local >= F_RD_FIRST && (local - F_RD_FIRST) % F_RD_EVERY == 0 &&
-            (local - F_RD_FIRST) / F_RD_EVERY < F_NI + F_NJ) {
+        if (F_LDS_SPREAD && nf != nullptr && local >= rd_first && (local - rd_first) % F_RD_EVERY == 0 &&
+            (local - rd_first) / F_RD_EVERY < F_NI + F_NJ) {
           __builtin_amdgcn_sched_barrier(0);
-          read_one(*nf, nstage, nq, (local - F_RD_FIRST) / F_RD_EVERY);
+          read_one(*nf, nstage, nq, (local - rd_first) / F_RD_EVERY);
           __builtin_amdgcn_sched_barrier(0);
         }
         const int w = w0 + (i - i_lo) * F_NJ + j;
@@ -460,15 +470,15 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
         // last k-step: a quarter of its MFMAs, then the slab hand-over.  It is the same for every slab,
         // the last ones included (no test inside the loop): past the end of the stream the requests
         // re-read the last slab into a stage nobody reads again.
-        mfma_rows(f1, 0, 1, 1000);
+        mfma_rows(f1, 0, F_HO_ROWS, 1000);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // slab g+1 (the only one in flight) has landed
         __syncthreads();                            // slab g+1 visible to all; everyone has read slab g
         if (!PROBE_NOREQ) issue_begin(stage);       // refill this stage with slab g+2
         if (F_LDS_SPREAD && F_HANDOVER_SPREAD && !PROBE_MFMA) {
-          mfma_rows(f1, 1, F_NI, 0, &f0, stage ^ 1, 0);
+          mfma_rows(f1, F_HO_ROWS, F_NI, 0, &f0, stage ^ 1, 0, F_HO_RD_FIRST);
         } else {
           if (!PROBE_MFMA) read_frags(f0, stage ^ 1, 0);
-          mfma_rows(f1, 1, F_NI, 0);
+          mfma_rows(f1, F_HO_ROWS, F_NI, 0);
         }
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
