@@ -176,7 +176,7 @@ def test_tile_kernels_planted_rows_pin_every_column(B, V, d, cap):
 # full benchmark size, the launch configuration the benchmark times: 256 sampled rows of two sequences that
 # hit every row position of a 256-row tile once, all columns against the oracle
 # ---------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name", ["c2", "c4"])
+@pytest.mark.parametrize("name", ["c2", "c4", "c5"])
 def test_full_size_every_row_position_of_a_tile(name):
     import torch
 
