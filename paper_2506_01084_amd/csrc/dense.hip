@@ -14,8 +14,8 @@ namespace {
 // Dense layer with K split over workgroups of the tile kernel: out = act(sum_ks partial[ks] + bias) + residual,
 // the parts added in a fixed order; one thread per run of 4 columns.
 __global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, int ksplit, int rows, const int32_t* rows_dev,
-                                                         int N, const float* bias, int act, const uint16_t* residual,
-                                                         uint16_t* out) {
+                                                         int N, const float* bias, int act, const void* residual,
+                                                         void* out, int stream_f32) {
   const int n4 = N >> 2;
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   const int r_end = rows_dev ? min(rows, *rows_dev) : rows;
@@ -43,8 +43,19 @@ __global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, i
     x.z = gelu_erf(x.z);
     x.w = gelu_erf(x.w);
   }
+  if (stream_f32) {                                  // fp32 residual and output: no rounding
+    if (residual) {
+      const float4 rv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(residual) + at);
+      x.x += rv.x;
+      x.y += rv.y;
+      x.z += rv.z;
+      x.w += rv.w;
+    }
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + at) = x;
+    return;
+  }
   if (residual) {
-    const uint2 rv = *reinterpret_cast<const uint2*>(residual + at);
+    const uint2 rv = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(residual) + at);
     x.x += __uint_as_float(rv.x << 16);
     x.y += __uint_as_float(rv.x & 0xFFFF0000u);
     x.z += __uint_as_float(rv.y << 16);
@@ -53,7 +64,7 @@ __global__ void __launch_bounds__(256) linear_sum_kernel(const float* partial, i
   uint2 o;
   o.x = bf16_bits_rne(x.x) | (bf16_bits_rne(x.y) << 16);
   o.y = bf16_bits_rne(x.z) | (bf16_bits_rne(x.w) << 16);
-  *reinterpret_cast<uint2*>(out + at) = o;
+  *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + at) = o;
 }
 
 // out[b][c][r] = in[b][r][c] (bf16) for r < R (and r < *rows_dev when given), c < C; columns up to ld_out of out
@@ -105,7 +116,8 @@ int z2z_launch_transpose(const void* in, void* out, int R, const int32_t* rows_d
 }
 
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev) {
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev,
+                      bool stream_f32) {
   // more rows than the 64 the decode-step kernel serves per pass over the weights, but fewer 256 x 256 output
   // tiles than would give every CU one (a few hundred rows, or up to a few thousand with a narrow layer): the
   // tile kernel with K split over workgroups, so that the weights stream once for all rows and every CU has a
@@ -149,8 +161,8 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
       if (rc != Z2Z_OK) return rc;
       const long long n_threads = (long long)R * (N / 4);
       hipLaunchKernelGGL(linear_sum_kernel, dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, s,
-                         reinterpret_cast<const float*>(c->skinny_partial), ksplit, R, rows_dev, N, bias, act,
-                         reinterpret_cast<const uint16_t*>(residual), reinterpret_cast<uint16_t*>(out));
+                         reinterpret_cast<const float*>(c->skinny_partial), ksplit, R, rows_dev, N, bias, act, residual,
+                         out, stream_f32 ? 1 : 0);
       Z2Z_HIP_TRY(hipGetLastError());
       return Z2Z_OK;
     }
@@ -158,7 +170,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   // few rows: bound by the weight bytes, which the decode-step kernel streams at HBM rate (it re-reads them
   // once per 64 rows, so it loses to the tile kernel beyond a few hundred rows)
   if (R <= 512 && c->skinny_ready && K % 128 == 0 && N % 2 == 0 && c->opt_logits_kernel != 2)
-    return z2z_launch_linear_skinny(c, A, W, bias, residual, act, out, R, rows_dev, N, K, s);
+    return z2z_launch_linear_skinny(c, A, W, bias, residual, act, out, R, rows_dev, N, K, s, stream_f32);
   if (!c->fast_ready || K % 64 != 0 || N % 8 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
   LogitsArgs a;
   memset(&a, 0, sizeof(a));
@@ -180,6 +192,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
   a.residual = residual;
   a.act = act;
   a.ldo = N;
+  a.stream_f32 = stream_f32 ? 1 : 0;
   a.rows_dev = nullptr;
   a.k_dev = k_dev;
   if (rows_dev && a.row_tiles >= 16) {

@@ -14,7 +14,9 @@
 // bias / GELU / residual in its epilogue.  The kernels in this file are the bandwidth-bound rest: gather +
 // LayerNorm (one wave per row, the row held in registers: read once), the L x L attention per entry and head
 // (a wave per entry and 512 features: 64 lanes x 16 bytes, a head's dot products reduced across its lanes),
-// and the final mean.  Activations between kernels are bf16, accumulation and statistics fp32.
+// and the final mean.  The residual stream (X, Y, Z) is fp32 from the gather to the final mean; the operands of
+// the matrix products (LayerNorm outputs, q | k | v, attention outputs, the hidden layer) are bf16;
+// accumulation and statistics are fp32.
 #include "logits_common.h"
 
 namespace {
@@ -54,6 +56,18 @@ __device__ __forceinline__ void unpack8(const uint4& x, float (&f)[8]) {
   f[5] = __uint_as_float(x.z & 0xFFFF0000u);
   f[6] = __uint_as_float(x.w << 16);
   f[7] = __uint_as_float(x.w & 0xFFFF0000u);
+}
+
+// 8 consecutive fp32 values of a residual-stream row (two 16-byte accesses)
+__device__ __forceinline__ void load8(const float* p, float (&f)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+  f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+
+__device__ __forceinline__ void store8(float* p, const float (&f)[8]) {
+  *reinterpret_cast<float4*>(p) = float4{f[0], f[1], f[2], f[3]};
+  *reinterpret_cast<float4*>(p + 4) = float4{f[4], f[5], f[6], f[7]};
 }
 
 __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
@@ -109,16 +123,17 @@ __global__ void __launch_bounds__(1024) enc_rows_kernel(RowMap m, int n_units) {
   }
 }
 
-// One wave per row.  GATHER: X[r] = bf16(E[token] + P[slot]) is formed and stored first.  Then A[r] = LN(X[r]) * gamma + beta, statistics
-// over the stored (rounded) values in two steps: mean, then the mean of the squared deviations.
+// One wave per row.  The residual stream X is fp32 (the layers add to it without rounding; only what feeds a
+// matrix product is bf16).  GATHER: X[r] = E[token] + P[slot] is formed and stored first.  Then
+// A[r] = bf16(LN(X[r]) * gamma + beta), statistics in two steps: mean, then the mean of the squared deviations.
 template <bool GATHER>
-__global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E, const uint4* P, uint4* X, uint4* A,
+__global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E, const uint4* P, float* X, uint4* A,
                                                        const float* gamma, const float* beta, int n_units) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= m.row0[n_units]) return;
   const int n_chunks = m.d / 8;
-  uint4* xr = X + (size_t)r * n_chunks;
+  float* xr = X + (size_t)r * m.d;
   uint4* ar = A + (size_t)r * n_chunks;
   float x[E_KCH][8];
   if (GATHER) {
@@ -142,16 +157,16 @@ __global__ void __launch_bounds__(256) enc_norm_kernel(RowMap m, const uint4* E,
 #pragma unroll
           for (int t = 0; t < 8; ++t) ev[t] += pv[t];
         }
-        const uint4 st = pack8(ev);
-        xr[c] = st;
-        unpack8(st, x[k]);
+        store8(xr + c * 8, ev);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[k][t] = ev[t];
       }
     }
   } else {
 #pragma unroll
     for (int k = 0; k < E_KCH; ++k) {
       const int c = lane + 64 * k;
-      if (c < n_chunks) unpack8(xr[c], x[k]);
+      if (c < n_chunks) load8(xr + c * 8, x[k]);
     }
   }
   float sum = 0.f;
@@ -249,7 +264,7 @@ __global__ void __launch_bounds__(256) enc_attention_kernel(RowMap m, const uint
 
 // h = mean of the entry's real slots of Z -> W_hyper[b, e]; one wave per entry.  Passes that start at entry 0
 // (full mode) also zero the rows of missing entries.
-__global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const uint4* Z, uint4* W, int n_units, int zero_missing) {
+__global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const float* Z, uint4* W, int n_units, int zero_missing) {
   const int lane = threadIdx.x & 63;
   const long long bu = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (bu >= n_units) return;
@@ -273,7 +288,7 @@ __global__ void __launch_bounds__(256) enc_pool_kernel(RowMap m, const uint4* Z,
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < L; ++i) {
       float z[8];
-      unpack8(Z[(r0 + i) * n_chunks + c], z);
+      load8(Z + (r0 + i) * m.d + c * 8, z);
 #pragma unroll
       for (int t = 0; t < 8; ++t) acc[t] += z[t];
     }
@@ -390,7 +405,7 @@ __global__ void __launch_bounds__(256) enc_gelu_backward_kernel(uint4* dF, const
 // One wave per row as in the forward kernel: the row of X stays in registers, dN is streamed twice (the second
 // time from cache).  The row's mean and rstd are left in stats[r] for the parameter gradients.
 __global__ void __launch_bounds__(256) enc_norm_backward_kernel(const int32_t* rows_dev, int d, const uint4* dN,
-                                                                const uint4* X, const float* gamma, const uint4* dres,
+                                                                const float* X, const float* gamma, const uint4* dres,
                                                                 uint4* out, float2* stats) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -403,7 +418,7 @@ __global__ void __launch_bounds__(256) enc_norm_backward_kernel(const int32_t* r
   for (int k = 0; k < E_KCH; ++k) {
     const int c = lane + 64 * k;
     if (c < n_chunks) {
-      unpack8(X[(size_t)r * n_chunks + c], x[k]);
+      load8(X + (size_t)r * d + c * 8, x[k]);
 #pragma unroll
       for (int t = 0; t < 8; ++t) sum += x[k][t];
     }
@@ -458,7 +473,7 @@ __global__ void __launch_bounds__(256) enc_norm_backward_kernel(const int32_t* r
 
 // dgamma[n] += sum_r dN[r, n] * xh[r, n],  dbeta[n] += sum_r dN[r, n],  xh = (X - mean[r]) * rstd[r]: column sums
 // in the shape of enc_colsum_kernel (a thread owns 8 columns and a strided set of rows).
-__global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* dN, const uint4* X, const float2* stats,
+__global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* dN, const float* X, const float2* stats,
                                                                   int n_chunks, const int32_t* rows_dev, float* dgamma,
                                                                   float* dbeta) {
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
@@ -469,12 +484,12 @@ __global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* d
   for (int r = blockIdx.y + E_CS_STRIPES * (threadIdx.x >> 6); r < rows; r += 2 * step) {   // two rows in flight
     const bool two = r + step < rows;
     const int r2 = two ? r + step : r;
-    const uint4 qg0 = dN[(size_t)r * n_chunks + c], qx0 = X[(size_t)r * n_chunks + c];
-    const uint4 qg1 = dN[(size_t)r2 * n_chunks + c], qx1 = X[(size_t)r2 * n_chunks + c];
+    const uint4 qg0 = dN[(size_t)r * n_chunks + c], qg1 = dN[(size_t)r2 * n_chunks + c];
+    float g[8], x[8], x1[8];
+    load8(X + ((size_t)r * n_chunks + c) * 8, x);
+    load8(X + ((size_t)r2 * n_chunks + c) * 8, x1);
     const float2 st0 = stats[r], st1 = stats[r2];
-    float g[8], x[8];
     unpack8(qg0, g);
-    unpack8(qx0, x);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       ag[t] += g[t] * ((x[t] - st0.x) * st0.y);
@@ -482,10 +497,9 @@ __global__ void __launch_bounds__(256) enc_norm_param_grad_kernel(const uint4* d
     }
     if (two) {
       unpack8(qg1, g);
-      unpack8(qx1, x);
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        ag[t] += g[t] * ((x[t] - st1.x) * st1.y);
+        ag[t] += g[t] * ((x1[t] - st1.x) * st1.y);
         ab[t] += g[t];
       }
     }
@@ -672,7 +686,8 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
   const size_t R_max = (size_t)B * (size_t)u_step * M;
   const size_t n_units_max = (size_t)B * (size_t)u_step;
   const size_t index_bytes = ((n_units_max + 1 + R_max) * sizeof(int32_t) + 255) & ~(size_t)255;
-  const size_t need = R_max * ((size_t)4 * d + (size_t)3 * d + (size_t)dff) * 2 + index_bytes;
+  // per row: the stream X and Y in fp32 (2 x 4 bytes x d), A, O (d), QKV (3d) and F (d_ff) in bf16
+  const size_t need = R_max * ((size_t)8 * d + ((size_t)2 * d + (size_t)3 * d + (size_t)dff) * 2) + index_bytes;
   if (need > c->enc_ws_bytes) {
     Z2Z_TRY_GROW(s);
     if (c->enc_ws) (void)hipFree(c->enc_ws);
@@ -682,12 +697,11 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
     c->enc_ws_bytes = need;
   }
   int32_t* index = reinterpret_cast<int32_t*>(c->enc_ws);
-  uint16_t* ws = reinterpret_cast<uint16_t*>(reinterpret_cast<unsigned char*>(c->enc_ws) + index_bytes);
-  uint16_t* X = ws;
-  uint16_t* A = X + R_max * d;
+  float* X = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(c->enc_ws) + index_bytes);
+  float* Y = X + R_max * d;
+  uint16_t* A = reinterpret_cast<uint16_t*>(Y + R_max * d);
   uint16_t* O = A + R_max * d;
-  uint16_t* Y = O + R_max * d;
-  uint16_t* QKV = Y + R_max * d;
+  uint16_t* QKV = O + R_max * d;
   uint16_t* F = QKV + R_max * 3 * d;
 
   RowMap m;
@@ -714,41 +728,40 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
     const int32_t* rows_dev = m.row0 + n_units;
     const unsigned row_blocks = (unsigned)((R + 3) / 4);
     hipLaunchKernelGGL(enc_rows_kernel, dim3(1), dim3(1024), 0, s, m, n_units);
-    uint16_t* x = X;
-    uint16_t* y = Y;
+    float* x = X;
+    float* y = Y;
     for (int l = 0; l < enc->n_layers; ++l) {
       const z2z_encoder_layer& lay = enc->layers[l];
       if (l == 0)
         hipLaunchKernelGGL(enc_norm_kernel<true>, dim3(row_blocks), dim3(256), 0, s, m,
-                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos),
-                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
+                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos), x,
+                           reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
       else
-        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(x), reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr, x,
+                           reinterpret_cast<uint4*>(A), lay.ln1_g, lay.ln1_b, n_units);
       int rc = z2z_launch_linear(c, A, lay.w_qkv, lay.b_qkv, nullptr, 0, QKV, R, rows_dev, 3 * d, d, s);
       if (rc != Z2Z_OK) return rc;
       const long long att_waves = (long long)n_units * groups;
       hipLaunchKernelGGL(enc_attention_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
                          reinterpret_cast<const uint4*>(QKV), reinterpret_cast<uint4*>(O), dh / 8, scale, groups,
                          n_units);
-      rc = z2z_launch_linear(c, O, lay.w_o, lay.b_o, x, 0, y, R, rows_dev, d, d, s);
+      rc = z2z_launch_linear(c, O, lay.w_o, lay.b_o, x, 0, y, R, rows_dev, d, d, s, nullptr, true);
       if (rc != Z2Z_OK) return rc;
       if (enc->attention_only) {
-        uint16_t* t = x;
+        float* t = x;
         x = y;
         y = t;
       } else {
-        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(y), reinterpret_cast<uint4*>(A), lay.ln2_g, lay.ln2_b, n_units);
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr, y,
+                           reinterpret_cast<uint4*>(A), lay.ln2_g, lay.ln2_b, n_units);
         rc = z2z_launch_linear(c, A, lay.w_1, lay.b_1, nullptr, 1, F, R, rows_dev, dff, d, s);
         if (rc != Z2Z_OK) return rc;
-        rc = z2z_launch_linear(c, F, lay.w_2, lay.b_2, y, 0, x, R, rows_dev, d, dff, s);
+        rc = z2z_launch_linear(c, F, lay.w_2, lay.b_2, y, 0, x, R, rows_dev, d, dff, s, nullptr, true);
         if (rc != Z2Z_OK) return rc;
       }
     }
-    hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
-                       reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(W_hyper), n_units,
-                       incremental ? 0 : 1);
+    hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m, x,
+                       reinterpret_cast<uint4*>(W_hyper), n_units, incremental ? 0 : 1);
   }
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
@@ -756,8 +769,9 @@ int z2z_launch_hyper_encode(z2z_ctx* c, const void* E, const z2z_encoder* enc, v
 
 namespace {
 
-struct LayerSave {                   // what the training pass keeps of one layer, [rows, .] bf16 each
-  uint16_t *Xin, *A, *QKV, *O, *Y, *N2, *U, *F;
+struct LayerSave {                   // what the training pass keeps of one layer: the stream (Xin, Y) [rows, d] fp32,
+  float *Xin, *Y;                    // the operands of the matrix products [rows, .] bf16
+  uint16_t *A, *QKV, *O, *N2, *U, *F;
 };
 
 int transpose_to(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out, hipStream_t s) {
@@ -797,10 +811,11 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
   const size_t n_units_max = (size_t)B * (size_t)u_step;
   const size_t index_bytes = ((n_units_max + 1 + R_max) * sizeof(int32_t) + 255) & ~(size_t)255;
   const size_t pos_bytes = ((size_t)Z2Z_MAX_M * d * sizeof(float) + 255) & ~(size_t)255;
-  // bf16 elements: per layer what LayerSave names; the running gradients dX dY dN dO (d each), dQKV (3d), dF
-  // (d_ff); two transposed operands [wide, Rp]; one transposed weight
-  const size_t per_layer = R_max * ((size_t)8 * d + (size_t)2 * dff);
-  const size_t elems = (size_t)nl * per_layer + R_max * ((size_t)7 * d + dff) + R_max * d + 2 * (size_t)wide * Rp +
+  // in units of bf16 elements (an fp32 element counts as two): per layer what LayerSave names (Xin and Y fp32);
+  // the last layer's output (fp32); the running gradients dX dY dN dO (d each), dQKV (3d), dF (d_ff); two
+  // transposed operands [wide, Rp]; one transposed weight
+  const size_t per_layer = R_max * ((size_t)10 * d + (size_t)2 * dff);
+  const size_t elems = (size_t)nl * per_layer + R_max * ((size_t)7 * d + dff) + R_max * 2 * d + 2 * (size_t)wide * Rp +
                        (size_t)wide * d;
   const size_t nb_bytes = (R_max * sizeof(float2) + 255) & ~(size_t)255;   // mean and rstd of every row of a LayerNorm
   const size_t need = index_bytes + pos_bytes + nb_bytes + elems * 2;
@@ -826,18 +841,19 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
     p += n;
     return r;
   };
+  auto take_f32 = [&](size_t n) { return reinterpret_cast<float*>(take(2 * n)); };   // (every size is a multiple of 64 elements)
   LayerSave sv[Z2Z_MAX_ENCODER_LAYERS];
   for (int l = 0; l < nl; ++l) {
-    sv[l].Xin = take(R_max * d);
+    sv[l].Xin = take_f32(R_max * d);
+    sv[l].Y = take_f32(R_max * d);
     sv[l].A = take(R_max * d);
     sv[l].QKV = take(R_max * 3 * d);
     sv[l].O = take(R_max * d);
-    sv[l].Y = take(R_max * d);
     sv[l].N2 = take(R_max * d);
     sv[l].U = take(R_max * (size_t)dff);
     sv[l].F = take(R_max * (size_t)dff);
   }
-  uint16_t* Xout = take(R_max * d);
+  float* Xout = take_f32(R_max * d);
   uint16_t* dX = take(R_max * d);
   uint16_t* dY = take(R_max * d);
   uint16_t* dN = take(R_max * d);
@@ -906,47 +922,47 @@ int z2z_launch_hyper_encode_train(z2z_ctx* c, int mode, const void* E, const z2z
     for (int l = 0; l < nl && mode != 2; ++l) {
       const z2z_encoder_layer& lay = enc->layers[l];
       const LayerSave& v = sv[l];
-      uint16_t* next = l + 1 < nl ? sv[l + 1].Xin : Xout;
+      float* next = l + 1 < nl ? sv[l + 1].Xin : Xout;
       if (l == 0)
         hipLaunchKernelGGL(enc_norm_kernel<true>, dim3(row_blocks), dim3(256), 0, s, m,
-                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos),
-                           reinterpret_cast<uint4*>(v.Xin), reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
+                           reinterpret_cast<const uint4*>(E), reinterpret_cast<const uint4*>(enc->pos), v.Xin,
+                           reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
       else
-        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(v.Xin), reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr, v.Xin,
+                           reinterpret_cast<uint4*>(v.A), lay.ln1_g, lay.ln1_b, n_units);
       Z2Z_TRY_RC(z2z_launch_linear(c, v.A, lay.w_qkv, lay.b_qkv, nullptr, 0, v.QKV, R, rows_dev, 3 * d, d, s));
       const long long att_waves = (long long)n_units * groups;
       hipLaunchKernelGGL(enc_attention_kernel, dim3((unsigned)((att_waves + 3) / 4)), dim3(256), 0, s, m,
                          reinterpret_cast<const uint4*>(v.QKV), reinterpret_cast<uint4*>(v.O), dh / 8, scale, groups,
                          n_units);
-      uint16_t* y = ffn ? v.Y : next;
-      Z2Z_TRY_RC(z2z_launch_linear(c, v.O, lay.w_o, lay.b_o, v.Xin, 0, y, R, rows_dev, d, d, s));
+      float* y = ffn ? v.Y : next;
+      Z2Z_TRY_RC(z2z_launch_linear(c, v.O, lay.w_o, lay.b_o, v.Xin, 0, y, R, rows_dev, d, d, s, nullptr, true));
       if (ffn) {
-        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr,
-                           reinterpret_cast<uint4*>(v.Y), reinterpret_cast<uint4*>(v.N2), lay.ln2_g, lay.ln2_b, n_units);
+        hipLaunchKernelGGL(enc_norm_kernel<false>, dim3(row_blocks), dim3(256), 0, s, m, nullptr, nullptr, v.Y,
+                           reinterpret_cast<uint4*>(v.N2), lay.ln2_g, lay.ln2_b, n_units);
         Z2Z_TRY_RC(z2z_launch_linear(c, v.N2, lay.w_1, lay.b_1, nullptr, 0, v.U, R, rows_dev, dff, d, s));
         hipLaunchKernelGGL(enc_gelu_kernel, dim3(flat_grid((size_t)R * dff / 8)), dim3(256), 0, s,
                            reinterpret_cast<const uint4*>(v.U), reinterpret_cast<uint4*>(v.F), dff / 8, rows_dev);
-        Z2Z_TRY_RC(z2z_launch_linear(c, v.F, lay.w_2, lay.b_2, v.Y, 0, next, R, rows_dev, d, dff, s));
+        Z2Z_TRY_RC(z2z_launch_linear(c, v.F, lay.w_2, lay.b_2, v.Y, 0, next, R, rows_dev, d, dff, s, nullptr, true));
       }
     }
 
     if (mode == 1) {
-      hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
-                         reinterpret_cast<const uint4*>(Xout), reinterpret_cast<uint4*>(W_hyper), n_units, 1);
+      hipLaunchKernelGGL(enc_pool_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m, Xout,
+                         reinterpret_cast<uint4*>(W_hyper), n_units, 1);
       continue;
     }
 
     // ---- backward ----
     hipLaunchKernelGGL(enc_pool_backward_kernel, dim3((unsigned)((n_units + 3) / 4)), dim3(256), 0, s, m,
                        reinterpret_cast<const uint4*>(dW_hyper), reinterpret_cast<uint4*>(dX), n_units);
-    auto norm_backward = [&](const uint16_t* dn, const uint16_t* x, const float* gamma, const uint16_t* dres,
+    auto norm_backward = [&](const uint16_t* dn, const float* x, const float* gamma, const uint16_t* dres,
                              uint16_t* out, const float* dgamma, const float* dbeta) {
       hipLaunchKernelGGL(enc_norm_backward_kernel, dim3(row_blocks), dim3(256), 0, s, rows_dev, d,
-                         reinterpret_cast<const uint4*>(dn), reinterpret_cast<const uint4*>(x), gamma,
+                         reinterpret_cast<const uint4*>(dn), x, gamma,
                          reinterpret_cast<const uint4*>(dres), reinterpret_cast<uint4*>(out), ln_stats);
       hipLaunchKernelGGL(enc_norm_param_grad_kernel, dim3((d / 8 + 63) / 64, E_CS_STRIPES), dim3(256), 0, s,
-                         reinterpret_cast<const uint4*>(dn), reinterpret_cast<const uint4*>(x), ln_stats, d / 8, rows_dev,
+                         reinterpret_cast<const uint4*>(dn), x, ln_stats, d / 8, rows_dev,
                          const_cast<float*>(dgamma), const_cast<float*>(dbeta));
     };
     for (int l = nl - 1; l >= 0; --l) {

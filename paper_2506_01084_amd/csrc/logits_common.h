@@ -218,6 +218,7 @@ struct LogitsArgs {
   const void* residual;   // [rows, ldo] bf16 or nullptr
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
+  int32_t stream_f32;     // 1: residual and out are fp32 (a residual stream kept unrounded between layers)
   // probability mode (the backward pass of the loss): out[r, c] = g[r] * (exp(logit - lse[r]) - [col0 + c == target[r]])
   // for the existing columns c < n_valid, 0 for the other columns below ldo; bf16, row stride ldo
   const float* lse;       // [rows]
@@ -413,6 +414,49 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], const Lo
   }
 }
 
+// The same with the residual and the output in fp32 (no rounding): 16-byte loads and stores.
+template <int NI, int NJ>
+__device__ __forceinline__ void store_tile_f32(const f32x16 (&acc)[NI][NJ], const LogitsArgs& a, int row_base, int r_end,
+                                               int col_base, int n_valid) {
+  const int lane31 = threadIdx.x & 31;
+  const float* res = reinterpret_cast<const float*>(a.residual);
+  float* out = reinterpret_cast<float*>(a.out);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = row_base + j * 32 + lane31;
+    if (row >= r_end) continue;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float4 rv[4], bv[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = col_base + i * 32 + g * 8;
+        const bool ok = col < n_valid;
+        rv[g] = (res && ok) ? *reinterpret_cast<const float4*>(res + (size_t)row * a.ldo + col) : float4{0.f, 0.f, 0.f, 0.f};
+        bv[g] = (a.bias && ok) ? *reinterpret_cast<const float4*>(a.bias + col) : float4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = col_base + i * 32 + g * 8;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = read_acc(acc[i][j][g * 4 + e]);
+        x[0] += bv[g].x;
+        x[1] += bv[g].y;
+        x[2] += bv[g].z;
+        x[3] += bv[g].w;
+        if (a.act == 1) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = gelu_erf(x[e]);
+        }
+        if (col < n_valid)
+          *reinterpret_cast<float4*>(out + (size_t)row * a.ldo + col) =
+              float4{x[0] + rv[g].x, x[1] + rv[g].y, x[2] + rv[g].z, x[3] + rv[g].w};
+      }
+    }
+  }
+}
+
 // Store one finished accumulator tile as it is (fp32), for a dense layer whose K range is split over several
 // workgroups: 16-byte stores.
 template <int NI, int NJ>
@@ -490,12 +534,13 @@ int z2z_launch_logits_general(bool bf16, bool hyper, const z2z_logits::LogitsArg
 int z2z_launch_logits_fast(int mode, const z2z_logits::LogitsArgs& a, unsigned grid, hipStream_t s);
 // out[R, N] = act(A[R, K] . W[N, K]^T + bias) + residual, all matrices bf16 (bias float), on the bf16 MFMA kernel
 // (R rows are laid out; with rows_dev only the first *rows_dev of them exist: the others are neither read nor
-// written)
+// written).  stream_f32: residual and out are fp32 instead (a residual stream that is not rounded between layers).
 // bf16 transpose with zero padding of the output rows (see dense.hip)
 int z2z_launch_transpose(const void* in, void* out, int R, const int32_t* rows_dev, int C, int ld_in, int ld_out,
                          int batch, size_t in_batch, size_t out_batch, hipStream_t s);
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
-                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev = nullptr);
+                      void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev = nullptr,
+                      bool stream_f32 = false);
 int z2z_logits_fast_prepare(z2z_ctx* c);
 int z2z_launch_logits_part(z2z_ctx* c, bool hyper, bool fast, z2z_logits::LogitsArgs a, const void* W, int w_rows, int col0,
                            int part0, int strip, int rows, int rows_per_seq, int* n_strips_out, bool timed,
@@ -524,7 +569,8 @@ size_t z2z_sample_truncated_work_floats(int32_t rows);
 // the same layer on the bandwidth-bound kernel of the decode step (few rows: every weight byte is read once per
 // 64 rows); K a multiple of 128, N even
 int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
-                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s);
+                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s,
+                             bool stream_f32 = false);
 int z2z_logits_decode_parts(const z2z_ctx* c);
 void z2z_logits_decode_units(int* base_columns, int* hyper_columns);
 bool z2z_logits_decode_ok(const z2z_ctx* c);

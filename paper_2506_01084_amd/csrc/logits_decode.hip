@@ -67,11 +67,12 @@ struct DecodeArgs {
   uint32_t ctr2, ctr3;    // generator counter words 2, 3: the step
   // MODE 3, a dense layer on a few rows: out[h, v] = act(H[h, :] . W_base[v, :] + bias[v]) + residual[h, v],
   // bf16, row stride ldo; no triples are kept
-  uint16_t* out;
+  void* out;
   const float* bias;
-  const uint16_t* residual;
+  const void* residual;
   int32_t act;            // 0 none, 1 GELU (erf)
   int32_t ldo;
+  int32_t stream_f32;     // 1: residual and out are fp32 (a residual stream kept unrounded between layers)
   const int32_t* rows_dev;  // MODE 3: nullptr, or the number of hidden rows that exist (<= B), on the device
   // MODE 3, K split over ksplit workgroups per unit (layers with few units would leave most CUs idle): each
   // leaves its partial tile in `partial`; linear_reduce_kernel adds them up and runs the epilogue
@@ -157,12 +158,21 @@ __device__ __forceinline__ void linear_epilogue(const DecodeArgs& a, const float
         x1 = gelu_erf(x1);
       }
       const size_t at = (size_t)(h0 + jj) * a.ldo + v0 + r;
+      if (a.stream_f32) {
+        if (a.residual) {
+          const float2 rv = *reinterpret_cast<const float2*>(reinterpret_cast<const float*>(a.residual) + at);
+          x0 += rv.x;
+          x1 += rv.y;
+        }
+        *reinterpret_cast<float2*>(reinterpret_cast<float*>(a.out) + at) = float2{x0, x1};
+        continue;
+      }
       if (a.residual) {
-        const uint32_t rv = *reinterpret_cast<const uint32_t*>(a.residual + at);
+        const uint32_t rv = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(a.residual) + at);
         x0 += __uint_as_float(rv << 16);
         x1 += __uint_as_float(rv & 0xFFFF0000u);
       }
-      *reinterpret_cast<uint32_t*>(a.out + at) = bf16_bits_rne(x0) | (bf16_bits_rne(x1) << 16);
+      *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.out) + at) = bf16_bits_rne(x0) | (bf16_bits_rne(x1) << 16);
     }
   }
 }
@@ -597,7 +607,8 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 // A dense layer on few rows (R up to a few hundred) is bound by the weight bytes like the decode step: the
 // base-unit workgroups of the kernel above, with the layer's epilogue instead of the softmax fold.
 int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual,
-                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s) {
+                             int act, void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s,
+                             bool stream_f32) {
   if (c->lds_limit < D_LDS || K % D_KSLICE != 0 || N % 2 != 0 || R < 1) return Z2Z_EUNSUPPORTED;
   DecodeArgs a;
   memset(&a, 0, sizeof(a));
@@ -610,11 +621,12 @@ int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const flo
   a.n_base_units = (N + D_LINEAR_UNIT - 1) / D_LINEAR_UNIT;
   a.n_groups = (R + 63) / 64;
   a.units_per_seq = 0;
-  a.out = reinterpret_cast<uint16_t*>(out);
+  a.out = out;
   a.bias = bias;
-  a.residual = reinterpret_cast<const uint16_t*>(residual);
+  a.residual = residual;
   a.act = act;
   a.ldo = N;
+  a.stream_f32 = stream_f32 ? 1 : 0;
   a.rows_dev = rows_dev;
   // enough workgroups for every CU: split K (in phases of 1024) where the units alone are too few
   const int n_phases_all = (K / D_KSLICE + 7) / 8;

@@ -483,8 +483,12 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
       }
       // ---- this vocabulary tile is complete: fold its 128 x 128 logits into the running triples ------
       const int v0 = vt * FT;
-      if (MODE == 2)
-        store_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      if (MODE == 2) {
+        if (a.stream_f32)
+          store_tile_f32<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+        else
+          store_tile<F_NI, F_NJ>(acc, a, r0 + wr * (F_NJ * 32), r_end, v0 + wv * 128 + half * 4, n_valid);
+      }
       else if (MODE == 5)
         store_partial_tile<F_NI, F_NJ>(acc, a.partial + (size_t)ks * a.rows * a.ldo, a.ldo, r0 + wr * (F_NJ * 32), r_end,
                                        v0 + wv * 128 + half * 4, n_valid);

@@ -1,15 +1,17 @@
 """GPU parity: hyper_encode (the learned hyper-encoder of section 2.2: attention / transformer layers over an
 entry's padded slots, mean of the real slots) through the C ABI against the float64 oracle.
 
-Bar.  The HIP path keeps activations in bf16 between the steps of a layer (the slot inputs, LayerNorm outputs,
-q|k|v, attention output, the residual stream after each block, the GELU output) and accumulates in fp32; the
-oracle computes in float64 from the same stored parameters and rounds once.  Each rounding is a relative 2^-9 of
-the rounded value; with random-init parameters of the scale used here every product maps order-1 activations to
-order-1 activations, so each of the 6 L + 1 roundings of an L-layer encoder reaches the output with weight of
-order 1.  If they all pushed the same way that would be 13 * 2^-9 = 2.5e-2 for two layers; the tolerance is
-3e-2 * max(1, largest |h| of the row) per element, and a row's mean error has to stay below a quarter of that
-(errors of independent roundings add in quadrature: typical worst elements are near 1e-2; the largest seen over
-5500 random shapes and modes was 2.24e-2, at d = 64 with two layers).
+Bar.  The HIP path keeps the residual stream (slot inputs, the sums after the attention and the feed-forward
+block) in fp32 from the gather to the final mean; what feeds a matrix product is bf16 (LayerNorm outputs, q|k|v,
+attention output, the GELU output) and accumulation is fp32.  The oracle computes in float64 from the same
+stored parameters and rounds once.  Each rounding is a relative 2^-9 of the rounded value and reaches the
+output only through a weight matrix (none sits on the stream itself, where it would arrive with weight 1); with
+random-init parameters of the scale used here every product maps order-1 activations to order-1 activations,
+so the 5 L roundings of an L-layer encoder and the one of the result add in quadrature: sqrt(11) * 2^-9 =
+6.5e-3 for two layers as the typical error of an element, about twice that for the worst element of a tensor.
+The tolerance is 2e-2 * max(1, largest |h| of the row) per element, and a row's mean error has to stay below a
+quarter of that (the largest seen over 2277 random shapes and modes was 1.29e-2; with the stream rounded to
+bf16 after every block it had been 2.24e-2).
 """
 import numpy as np
 import pytest
@@ -21,7 +23,7 @@ from helpers import encoder_to_device, gpu_encode, oracle_encode_batch, storage_
 
 pytestmark = pytest.mark.gpu
 
-TOL = 3e-2
+TOL = 2e-2
 
 
 def _compare(got_bits, ref64, label):

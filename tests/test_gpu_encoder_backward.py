@@ -195,7 +195,7 @@ def test_backward_on_the_rows_a_keeping_forward_left():
         want = oracle.hyper_encode(E, "bf16", entries, cap, enc, rounded=False)
         got = oracle.bf16_bits_to_f64(W[b])
         scale = np.maximum(1.0, np.abs(want).max(axis=-1, keepdims=True))
-        assert (np.abs(got - want) / scale).max() <= 3e-2                  # the forward test's bar
+        assert (np.abs(got - want) / scale).max() <= 2e-2                  # the forward test's bar
         assert (W[b, len(entries):] == 0).all()
     assert torch.allclose(dE_kept, dE_plain, rtol=1e-3, atol=1e-5)
     assert torch.equal(g_kept.params["pos"], g_plain.params["pos"]) or torch.allclose(
