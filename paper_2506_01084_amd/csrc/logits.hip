@@ -565,8 +565,10 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     rc = z2z_launch_logits_decode(c, H, W_base, W_hyper, &n_parts, timed, &sp, c->sample_logits, s);
     if (rc != Z2Z_OK) return rc;
   }
-  rc = launch_combine(ctx_parts(c), n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
-  if (rc != Z2Z_OK) return rc;
+  if (!z2z_sample_truncated_merges_parts(c, n_parts, top_k, base_columns)) {
+    rc = launch_combine(ctx_parts(c), n_parts, rows, nullptr, c->row_max, c->row_max + rows, s);
+    if (rc != Z2Z_OK) return rc;
+  }
   return z2z_launch_sample_truncated(c, c->sample_logits, c->row_max, rows, n_parts, c->row_max + 2 * (size_t)rows, &sp,
                                      top_k, top_p, token, logprob, s, base_columns);
 }

@@ -562,7 +562,10 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
 int z2z_logits_decode_seq_units(const z2z_ctx* c);
 // `logits` hold logit / temperature as the decode kernel stored them, `row_stat` the rows' maxima, then their
 // log-sum-exps, of those values; `work` is scratch of z2z_sample_truncated_work_floats(rows) floats.
-int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
+// z2z_sample_truncated_merges_parts: true when the selection's first kernel merges the parts into `row_stat` itself
+// (the caller then launches no merge); otherwise `row_stat` must hold them when the call is made.
+bool z2z_sample_truncated_merges_parts(const z2z_ctx* c, int n_parts, int32_t top_k, int base_columns);
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, float* row_stat, int32_t rows, int n_parts,
                                 float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
                                 int32_t* token, float* logprob, hipStream_t s, int base_columns = 0);
 size_t z2z_sample_truncated_work_floats(int32_t rows);

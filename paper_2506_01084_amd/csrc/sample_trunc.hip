@@ -28,6 +28,8 @@
 //   4. the draw: one more pass, Gumbel-max over the elements at or before the cut.
 #include "logits_common.h"
 
+#include <string.h>
+
 namespace {
 
 using namespace z2z_logits;
@@ -50,6 +52,10 @@ struct TruncArgs {
   const float* row_max;    // [rows] largest stored value of the row
   const float* row_lse;    // [rows] log-sum-exp of the row's stored values
   const float* part_m;     // [rows, n_parts] largest stored value per part of the row (the decode kernel's units)
+  const float* part_s;     // list kernel, stats_out given: [rows, n_parts] the parts' sums of exp(value - part_m)
+  const int32_t* part_i;   //                               [rows, n_parts] the columns of the parts' maxima
+  float* stats_out;        // list kernel: nullptr (row_max / row_lse are given), or [2 rows]: it merges the row's parts
+                           // itself and leaves the row maxima, then the log-sum-exps, here (= row_max, row_lse)
   int32_t n_parts, n_base_parts, base_columns, hyper_columns;
   int32_t list_depth;      // list kernel: how many of the row's largest parts bound the list
   int32_t* redo;           // [rows] list kernel out: 1 = this row is left to the passes over the whole row;
@@ -90,6 +96,35 @@ __device__ __forceinline__ void sort_and_scan(float* cand_x, int* cand_c, float*
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int n2 = 2;
   while (n2 < cnt) n2 <<= 1;
+  if (cnt <= T_THREADS) {
+    // a short list: every element's position is the number of elements that precede it (the order is strict:
+    // columns differ).  The cnt^2 comparisons are dealt to all threads: thread (g, i) compares element i with
+    // elements g, g + G, ...; a wave's lanes share g, so every LDS read of element j is a broadcast.
+    int P = 64;
+    while (P < cnt) P <<= 1;
+    const int G = T_THREADS / P;
+    uint32_t* rank = reinterpret_cast<uint32_t*>(cand_w);
+    for (int i = tid; i < P; i += T_THREADS) rank[i] = 0u;
+    __syncthreads();
+    const int i = tid & (P - 1), g = tid / P;
+    float xi = 0.f;
+    int ci = 0;
+    if (i < cnt) {
+      xi = cand_x[i];
+      ci = cand_c[i];
+      uint32_t ahead = 0;
+      for (int j = g; j < cnt; j += G) ahead += before(cand_x[j], cand_c[j], xi, ci) ? 1u : 0u;
+      atomicAdd(&rank[i], ahead);
+    }
+    __syncthreads();
+    const uint32_t rk = i < cnt ? rank[i] : 0u;
+    __syncthreads();
+    if (g == 0 && i < cnt) {
+      cand_x[rk] = xi;
+      cand_c[rk] = ci;
+    }
+    __syncthreads();
+  } else {
   for (int i = cnt + tid; i < n2; i += T_THREADS) {
     cand_x[i] = -INFINITY;
     cand_c[i] = 0x7FFFFFFF;
@@ -113,6 +148,7 @@ __device__ __forceinline__ void sort_and_scan(float* cand_x, int* cand_c, float*
       }
       __syncthreads();
     }
+  }
   }
   // masses in sorted order and their inclusive prefix sums: each thread owns a contiguous run
   const int per = (n2 + T_THREADS - 1) / T_THREADS;
@@ -305,8 +341,9 @@ __global__ void __launch_bounds__(T_THREADS) sample_first_pass_kernel(TruncArgs 
   }
 }
 
-__global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a, const float* partial) {
-  extern __shared__ __align__(16) unsigned char lds[];
+// The passes over the whole row (steps 1-4 of the header) for row r, by all threads of a workgroup.  partial: the
+// bin totals sample_first_pass_kernel left, or nullptr (the first pass is made here).  lds: T_LDS bytes.
+__device__ __forceinline__ void truncated_row(const TruncArgs& a, const float* partial, int r, unsigned char* lds) {
   uint32_t* hc = reinterpret_cast<uint32_t*>(lds);                         // [wave][bin][lane]
   float* hm = reinterpret_cast<float*>(lds + T_HIST_BYTES);                // [wave][bin][lane]
   float* edges = reinterpret_cast<float*>(lds + 2 * T_HIST_BYTES);         // [T_BINS + 1]
@@ -322,8 +359,6 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int r = blockIdx.x;
-  if (a.redo && a.redo[r] == 0) return;             // drawn by the list kernel
   const int C = min(max(a.size[r], 0), a.cap);
   const int n = a.V + C;
   const float* x = a.logits + (size_t)r * a.ld;
@@ -395,7 +430,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
     }
     if (st->next != 0) break;                       // uniform: read after a barrier
     const float lo = st->lo, hi = st->hi;
-    if (pass == 0) {
+    if (pass == 0 && partial) {
       // the first pass was done by sample_first_pass_kernel: add up its slices (fixed order)
       if (tid < T_BINS) {
         uint32_t sc = 0;
@@ -634,57 +669,127 @@ __global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a
 // is then a prefix of the row's order that is at least j long: a top-k cut with k <= j, or a nucleus that
 // closes inside the list, is decided on it exactly as on the whole row (total mass: from the row's
 // log-sum-exp).  A row whose list overflows, or whose nucleus does not close inside it, sets redo[row].
-__global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
-  __shared__ __align__(16) float pm[L_PARTS];
-  __shared__ float cand_x[T_CAND];
-  __shared__ int cand_c[T_CAND];
-  __shared__ float cand_w[T_CAND];
-  __shared__ uint32_t misc[48];
-  __shared__ float level;
+// Returns whether the row was settled (uniform over the workgroup); a row that was not has redo[r] = 1.
+// lds: L_LDS bytes.
+constexpr int L_LDS = L_PARTS * 4 + 3 * T_CAND * 4 + 48 * 4 + 4 * (int)sizeof(Triple) + 16;
+__device__ __forceinline__ bool list_row(const TruncArgs& a, int r, int rows, unsigned char* lds) {
+  float* pm = reinterpret_cast<float*>(lds);                                     // [L_PARTS]
+  float* cand_x = pm + L_PARTS;                                                  // [T_CAND]
+  int* cand_c = reinterpret_cast<int*>(cand_x + T_CAND);                         // [T_CAND]
+  float* cand_w = reinterpret_cast<float*>(cand_c + T_CAND);                     // [T_CAND]
+  uint32_t* misc = reinterpret_cast<uint32_t*>(cand_w + T_CAND);                 // [48]
+  Triple* xch = reinterpret_cast<Triple*>(misc + 48);                            // [4]
+  float* row_stat = reinterpret_cast<float*>(xch + 4);                           // [2]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r = blockIdx.x;
   const int C = min(max(a.size[r], 0), a.cap);
   const int n = a.V + C;
   const float* x = a.logits + (size_t)r * a.ld;
   const int n_parts = a.n_parts;
   const int depth = min(a.list_depth, n);
-  const int n4 = (n_parts + 3) & ~3;
+  uint32_t* hist = reinterpret_cast<uint32_t*>(cand_w);          // [4][256]: free until the work items are listed
 
-  for (int i = tid; i < n4; i += T_THREADS) pm[i] = i < n_parts ? a.part_m[(size_t)r * n_parts + i] : -INFINITY;
+  if (!a.stats_out)
+    for (int i = tid; i < n_parts; i += T_THREADS) pm[i] = a.part_m[(size_t)r * n_parts + i];
+  for (int i = tid; i < 4 * 256; i += T_THREADS) hist[i] = 0u;
   if (tid == 0) {
     misc[0] = 0u;            // list length
-    misc[2] = 0u;            // level found
     misc[3] = 0u;            // work items
     misc[4] = 0u;            // mass of the list (float)
   }
-  __syncthreads();
-  // the depth-th largest part maximum: the value v with (number of maxima > v) < depth <= (number >= v)
-  if (depth <= n_parts) {
-    const float4* pm4 = reinterpret_cast<const float4*>(pm);
-    for (int i = tid; i < n_parts; i += T_THREADS) {
-      const float v = pm[i];
-      int gt = 0, ge = 0;
-      for (int j = 0; j < n4 / 4; ++j) {
-        const float4 q = pm4[j];
-        gt += (q.x > v) + (q.y > v) + (q.z > v) + (q.w > v);
-        ge += (q.x >= v) + (q.y >= v) + (q.z >= v) + (q.w >= v);
+  // the row's maximum and log-sum-exp: given, or merged here from the parts' (m, s, column) in the order of
+  // logits_combine_kernel<256> (256 threads striding over the parts, a butterfly per wave, the four waves in turn)
+  if (a.stats_out) {
+    Triple tr = empty_triple();
+    if (tid < 256) {
+      const size_t base = (size_t)r * n_parts;
+      for (int p = tid; p < n_parts; p += 256) {
+        Triple o;
+        o.m = a.part_m[base + p];
+        o.s = a.part_s[base + p];
+        o.i = a.part_i[base + p];
+        pm[p] = o.m;                                  // (the one trip to memory serves both uses)
+        merge_triple(tr, o);
       }
-      if (gt < depth && depth <= ge) {               // equal maxima all write the same value
-        level = v;
-        misc[2] = 1u;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        Triple o;
+        o.m = __shfl_xor(tr.m, off);
+        o.s = __shfl_xor(tr.s, off);
+        o.i = __shfl_xor(tr.i, off);
+        merge_triple(tr, o);
       }
+      if (lane == 0) xch[wave] = tr;
     }
+    __syncthreads();
+    if (tid == 0) {
+      Triple tr0 = xch[0];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) merge_triple(tr0, xch[w]);
+      row_stat[0] = tr0.m;
+      row_stat[1] = tr0.m + logf(tr0.s);
+      a.stats_out[r] = row_stat[0];
+      a.stats_out[rows + r] = row_stat[1];
+    }
+  } else if (tid == 0) {
+    row_stat[0] = a.row_max[r];
+    row_stat[1] = a.row_lse[r];
   }
   __syncthreads();
-  bool ok = misc[2] != 0u && level > -INFINITY;      // uniform
+  const float row_m = row_stat[0], row_l = row_stat[1];
+  // the depth-th largest part maximum, by the digits of the maxima's order-preserving integer images (larger
+  // float <=> larger key; -0 counts as +0): four passes of 8 bits, a 256-bin count each, every wave walks the
+  // bins from the top for itself (the count of larger keys stays below depth until the digit's bin)
+  bool ok = depth >= 1 && depth <= n_parts;          // uniform
+  float level = -INFINITY;
+  if (ok) {
+    uint32_t key[L_PARTS / T_THREADS];
+#pragma unroll
+    for (int q = 0; q < L_PARTS / T_THREADS; ++q) {
+      const int i = tid + q * T_THREADS;
+      const uint32_t u = __float_as_uint((i < n_parts ? pm[i] : 0.f) + 0.0f);
+      key[q] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    }
+    uint32_t prefix = 0u, rem = (uint32_t)depth;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      uint32_t* h = hist + pass * 256;
+#pragma unroll
+      for (int q = 0; q < L_PARTS / T_THREADS; ++q)
+        if (tid + q * T_THREADS < n_parts && (pass == 0 || (key[q] >> (shift + 8)) == prefix))
+          atomicAdd(&h[(key[q] >> shift) & 255u], 1u);
+      __syncthreads();
+      const uint4 cn = reinterpret_cast<const uint4*>(h)[lane];            // bins 4 lane .. 4 lane + 3
+      const uint32_t own = cn.x + cn.y + cn.z + cn.w;
+      uint32_t incl = own;                                                 // this lane's bins and all above
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(incl, off);
+        if (lane + off < 64) incl += o;
+      }
+      const uint32_t a3 = incl - own, a2 = a3 + cn.w, a1 = a2 + cn.z, a0 = a1 + cn.y;   // keys above bin 3, 2, 1, 0
+      int digit = -1;
+      uint32_t left = 0u;
+      if (a3 < rem && rem <= a3 + cn.w) { digit = 4 * lane + 3; left = rem - a3; }
+      else if (a2 < rem && rem <= a2 + cn.z) { digit = 4 * lane + 2; left = rem - a2; }
+      else if (a1 < rem && rem <= a1 + cn.y) { digit = 4 * lane + 1; left = rem - a1; }
+      else if (a0 < rem && rem <= a0 + cn.x) { digit = 4 * lane; left = rem - a0; }
+      const uint64_t who = __ballot(digit >= 0);                           // exactly one lane: rem <= the pass's keys
+      const int src = who != 0ull ? __ffsll((long long)who) - 1 : 0;
+      prefix = (prefix << 8) | (uint32_t)__shfl(digit >= 0 ? digit : 0, src);
+      rem = __shfl(left, src);
+    }
+    level = __uint_as_float((prefix & 0x80000000u) ? (prefix & 0x7FFFFFFFu) : ~prefix);
+    ok = level > -INFINITY;
+  }
+  __syncthreads();                                    // the counts are read: their words become the work items
   // no element weighs more than the largest one, exp(0) = 1 in the units of the masses, and the list comes out
   // about list_depth long: a nucleus alone that needs more mass than twice that many elements could carry
   // is not tried (a flat distribution; the passes over the whole row take it)
-  if (a.top_k <= 0 && a.top_p * __expf((a.row_lse[r] - a.row_max[r]) * a.inv_temperature) > (float)(2 * a.list_depth))
-    ok = false;
+  if (a.top_k <= 0 && a.top_p * __expf((row_l - row_m) * a.inv_temperature) > (float)(2 * a.list_depth)) ok = false;
   const float L = ok ? level : INFINITY;
   // work items: runs of at most 256 columns of the parts that reach L (cand_c is free until the appends start,
   // and they start after the barrier; items are kept in cand_w, which the scan fills later)
@@ -710,15 +815,17 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
   __syncthreads();
   if (ok) {
     const int n_items = (int)misc[3];
-    const float m0 = a.row_max[r];
+    const float m0 = row_m;
     float mass = 0.f;                                // of what this lane appends
-    for (int it = wave * 4; it < n_items; it += T_WAVES * 4) {     // 16 independent loads in flight per wave
-      float v[16];
-      int cc[16];
+    constexpr int IPW = 8;                           // items per wave and round: 4 IPW independent loads in flight
+    for (int it = 0; it < n_items; it += T_WAVES * IPW) {          // items dealt round-robin to the waves
+      float v[4 * IPW];
+      int cc[4 * IPW];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const bool have = it + q < n_items;          // wave-uniform
-        const int c0 = have ? item_c0[it + q] : 0;
+      for (int q = 0; q < IPW; ++q) {
+        const int item = it + q * T_WAVES + wave;
+        const bool have = item < n_items;            // wave-uniform
+        const int c0 = have ? item_c0[item] : 0;
         int c1 = 0;                                  // the run ends with its part, after 256 columns at most
         if (have) {
           const int part_end = c0 < a.V ? min((c0 / a.base_columns + 1) * a.base_columns, a.V)
@@ -733,7 +840,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
         }
       }
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
+      for (int j = 0; j < 4 * IPW; ++j) {
         const bool take = cc[j] >= 0 && v[j] >= L;
         const uint64_t mask = __ballot(take);
         if (mask != 0ull) {
@@ -758,16 +865,16 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
   ok = ok && found <= (uint32_t)T_CAND && found >= 1u;
   if (!ok) {
     if (tid == 0) a.redo[r] = 1;
-    return;
+    return false;
   }
   const int cnt = (int)found;
-  const float m = a.row_max[r];
+  const float m = row_m;
   const float inv_t = a.inv_temperature;
   const uint32_t k_eff = a.top_k > 0 ? (uint32_t)min(a.top_k, n) : (uint32_t)n;
-  const float target = a.top_p < 1.0f ? a.top_p * __expf((a.row_lse[r] - m) * inv_t) : INFINITY;
+  const float target = a.top_p < 1.0f ? a.top_p * __expf((row_l - m) * inv_t) : INFINITY;
   if (a.top_k <= 0 && cnt < n && __uint_as_float(misc[4]) < 0.999f * target) {
     if (tid == 0) a.redo[r] = 1;                     // a nucleus alone, and the whole list weighs too little
-    return;
+    return false;
   }
   sort_and_scan(cand_x, cand_c, cand_w, cnt, m, inv_t, 0u, 0.f, k_eff, target, misc);
   int idx;
@@ -777,7 +884,7 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
     idx = cnt - 1;                                   // the whole row is in the list and rounding kept the mass below p
   else {
     if (tid == 0) a.redo[r] = 1;                     // the cut lies beyond the list
-    return;
+    return false;
   }
   Best best = draw_from_list(cand_x, cand_c, idx, inv_t, r, a.key0, a.key1, a.ctr2, a.ctr3);
   best = block_best(best, misc + 8);
@@ -786,20 +893,56 @@ __global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
     a.token[r] = best.i;
     if (a.logprob) a.logprob[r] = (best.z - m * inv_t) - logf(cand_w[idx]);
   }
+  return true;
+}
+
+__global__ void __launch_bounds__(T_THREADS) sample_truncated_kernel(TruncArgs a, const float* partial) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  if (a.redo && a.redo[blockIdx.x] == 0) return;    // drawn by the list kernel
+  truncated_row(a, partial, blockIdx.x, lds);
+}
+
+__global__ void __launch_bounds__(T_THREADS) sample_list_kernel(TruncArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  (void)list_row(a, blockIdx.x, gridDim.x, lds);
+}
+
+// Both in one launch: the workgroup of a row the list does not settle goes on to the passes over the whole row.
+__global__ void __launch_bounds__(T_THREADS) sample_list_then_row_kernel(TruncArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  if (list_row(a, blockIdx.x, gridDim.x, lds)) return;
+  __syncthreads();
+  truncated_row(a, nullptr, blockIdx.x, lds);
 }
 
 }  // namespace
 
-int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* row_stat, int32_t rows, int n_parts,
+// Whether the selection starts with the short-list kernel (which then also merges the row's parts into the row
+// maxima and log-sum-exps: the caller launches no merge of its own).
+static bool list_first_for(const z2z_ctx* c, int n_parts, int32_t top_k, int base_columns) {
+  int unit_base, unit_hyper;
+  z2z_logits_decode_units(&unit_base, &unit_hyper);
+  if (base_columns > 0) unit_base = base_columns;
+  return c->opt_sample_kernel != 1 && n_parts <= L_PARTS && top_k <= L_DEPTH && unit_base <= 512 && unit_hyper <= 512;
+}
+
+bool z2z_sample_truncated_merges_parts(const z2z_ctx* c, int n_parts, int32_t top_k, int base_columns) {
+  return list_first_for(c, n_parts, top_k, base_columns);
+}
+
+int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, float* row_stat, int32_t rows, int n_parts,
                                 float* work, const z2z_sample_params* sp, int32_t top_k, float top_p,
                                 int32_t* token, float* logprob, hipStream_t s, int base_columns) {
   (void)sp->temperature;                             // the stored values are scaled already
   TruncArgs a;
+  memset(&a, 0, sizeof(a));
   a.logits = logits;
   a.size = c->st.size;
   a.row_max = row_stat;
   a.row_lse = row_stat + rows;
   a.part_m = c->part_m;
+  a.part_s = c->part_s;
+  a.part_i = c->part_i;
   a.n_parts = n_parts;
   z2z_logits_decode_units(&a.base_columns, &a.hyper_columns);
   if (base_columns > 0) a.base_columns = base_columns;   // the base parts came from another kernel's strips
@@ -820,12 +963,22 @@ int z2z_launch_sample_truncated(z2z_ctx* c, const float* logits, const float* ro
   a.list_depth = 0;
   float* partial = work + rows;                      // work: [rows] redo flags, then the first pass's bin totals
   // a short prefix first: rows it cannot settle are flagged, and only those take the passes over the whole row
-  const bool list_first = c->opt_sample_kernel != 1 && n_parts <= L_PARTS && top_k <= L_DEPTH &&
-                          a.base_columns <= 512 && a.hyper_columns <= 512;
+  const bool list_first = list_first_for(c, n_parts, top_k, base_columns);
   if (list_first) {
     a.redo = reinterpret_cast<int32_t*>(work);
     a.list_depth = top_k > 0 ? top_k : L_DEPTH;
-    hipLaunchKernelGGL(sample_list_kernel, dim3(rows), dim3(T_THREADS), 0, s, a);
+    a.stats_out = row_stat;
+    if (top_k > 0) {
+      // With a top-k the list settles every row but those with many equal logits at the cut: the rare row
+      // that is left is finished by the same workgroup (it classifies its elements itself), one launch in all.
+      hipLaunchKernelGGL(sample_list_then_row_kernel, dim3(rows), dim3(T_THREADS), T_LDS, s, a);
+      Z2Z_HIP_TRY(hipGetLastError());
+      return Z2Z_OK;
+    }
+    // A nucleus alone leaves whole batches of flat rows to the passes over the whole row: their first pass is
+    // spread over T_SPLIT workgroups per row, in launches of their own.
+    hipLaunchKernelGGL(sample_list_kernel, dim3(rows), dim3(T_THREADS), L_LDS, s, a);
+    a.stats_out = nullptr;
   }
   hipLaunchKernelGGL(sample_first_pass_kernel, dim3(rows * T_SPLIT), dim3(T_THREADS), T_LDS, s, a, partial);
   hipLaunchKernelGGL(sample_truncated_kernel, dim3(rows), dim3(T_THREADS), T_LDS, s, a, partial);
@@ -841,5 +994,9 @@ int z2z_sample_truncated_prepare(z2z_ctx* c) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sample_first_pass_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sample_list_then_row_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sample_list_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, L_LDS));
   return Z2Z_OK;
 }
