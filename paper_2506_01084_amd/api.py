@@ -194,9 +194,9 @@ class Context:
 
     def read_launches(self) -> dict:
         """Launches enqueued so far per logits kernel family (host-side counters)."""
-        arr = (ctypes.c_int64 * 4)()
+        arr = (ctypes.c_int64 * 5)()
         _check(self._lib.z2z_read_launches(self._h, arr), "z2z_read_launches")
-        return dict(tile_base=arr[0], tile_hyper=arr[1], general=arr[2], decode=arr[3])
+        return dict(tile_base=arr[0], tile_hyper=arr[1], general=arr[2], decode=arr[3], mid=arr[4])
 
     # -- the four operations ------------------------------------------------------------------------
     def lzw_encode(self, tokens: torch.Tensor, lens: Optional[torch.Tensor], codes: torch.Tensor,

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libz2z.so")
 
-SOURCES = ["z2z_api.hip", "lzw.hip", "hyper_embed.hip", "logits.hip", "logits_general.hip", "logits_fast.hip", "logits_decode.hip",
+SOURCES = ["z2z_api.hip", "lzw.hip", "hyper_embed.hip", "logits.hip", "logits_general.hip", "logits_fast.hip", "logits_mid.hip", "logits_decode.hip",
            "sample_trunc.hip", "hyper_encoder.hip", "dense.hip", "loss_backward.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include "logits_common.h"
+#include "logits_mid.h"
 
 namespace {
 
@@ -116,6 +117,7 @@ Z2Z_API int z2z_create(z2z_ctx** out, const z2z_config* cfg) {
     return Z2Z_EHIP;
   }
   c->fast_ready = z2z_logits_fast_prepare(c) == Z2Z_OK;
+  c->mid_ready = z2z_logits_mid_prepare(c) == Z2Z_OK;
   c->skinny_ready = z2z_logits_decode_prepare(c) == Z2Z_OK;      // the kernel itself; decode_ready: for this shape
   c->decode_ready = z2z_logits_decode_ok(c) && c->skinny_ready;
   c->trunc_ready = c->decode_ready && z2z_sample_truncated_prepare(c) == Z2Z_OK;

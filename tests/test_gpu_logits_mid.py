@@ -1,0 +1,142 @@
+"""GPU parity of the base-vocabulary part of extended_logits for calls with few hidden rows in all (a decode step
+of 65..128 sequences, a few rows per sequence at a small batch, a short chunk): every row and, through planted
+rows, every base column.  Joint logits, one softmax over base and hyper vocabulary, the pick: section 2.3,
+steps 7-9.
+
+Two kernels share these calls (bf16 context, d a multiple of 64, no full-logits output, not a decode step of at
+most 64 sequences): up to 64 rows the base units of the decode kernel in a launch of their own (d a multiple of
+128), up to 128 rows the weight-streaming kernel; each test checks the library's launch counters.  Shapes span
+both builds of the streaming kernel (up to 64 and up to 128 rows), a last weight tile with a single row, fewer
+K slabs than weight buffers, a slab count that is no multiple of the buffer count, and both ways of the hyper
+part (the decode kernel's units, the MFMA tile kernel).
+
+Bars as for the other logits tests: max and lse within 2e-2 * max(1, |ref|), argmax identical wherever the
+oracle's two largest logits differ by more than 1e-2 (elsewhere it must name a logit within that gap).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_01084_amd import workloads as wl
+
+from helpers import check_logits_rows, gpu_encode, oracle_encode_batch, torch_storage
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(cfg):
+    from paper_2506_01084_amd import api
+
+    return api.Context(B=cfg["B"], V=cfg["V"], M=cfg["M"], cap=cfg["cap"], d=cfg["d"], dtype="bf16", pool=cfg["pool"],
+                       w=wl.make_pool_weights(cfg).tolist())
+
+
+def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh, base="mid"):
+    """One extended_logits call whose base part must run on the streaming kernel (base = "mid") or on the decode
+    kernel's base units (base = "decode"); host (argmax, max, lse)."""
+    import torch
+
+    rows = d_H.shape[0]
+    am = torch.full((rows,), -5, dtype=torch.int32, device="cuda")
+    mx = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
+    lse = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
+    before = ctx.read_launches()
+    ctx.extended_logits(d_H, rows_per_seq, d_Wb, d_Wh, am, mx, lse, None)
+    torch.cuda.synchronize()
+    after = ctx.read_launches()
+    if base == "mid":
+        assert after["mid"] == before["mid"] + 1, "the base part did not run on the streaming kernel"
+    else:
+        assert after["mid"] == before["mid"] and after["decode"] >= before["decode"] + 1, "base part not on the decode units"
+    assert after["tile_base"] == before["tile_base"] and after["general"] == before["general"]
+    return am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,rows_per_seq,V,d,M,cap,pool", [
+    (65, 1, 1000, 128, 3, 300, "mean"),          # a decode step of 65 sequences: 128-row build, hyper on the decode units
+    (128, 1, 777, 192, 3, 0, "mean"),            # 128 rows, no hyper vocabulary: three K slabs
+    (3, 2, 300, 64, 4, 40, "mean"),              # 6 rows, one K slab (d no multiple of 128): 64-row build, fewer slabs than buffers
+    (1, 100, 2500, 320, 4, 100, "weighted"),     # 100 rows of one sequence: five slabs, hyper on the tile kernel
+    (4, 24, 513, 576, 3, 70, "mean"),            # 96 rows; nine slabs; V one row past two weight tiles
+    (9, 7, 1300, 4096, 3, 257, "mean"),          # 63 rows, d = 4096: the decode kernel's base units, four K phases
+    (5, 3, 700, 448, 3, 100, "mean"),            # 15 rows, d = 448 (no multiple of 128): the streaming kernel, 7 slabs
+    (2, 5, 520, 1024, 3, 30, "mean"),            # 10 rows: the decode kernel's base units, one K phase
+])
+def test_few_rows_base_part_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
+    import torch
+
+    N = 900
+    cfg = dict(name="mid", B=B, N=N, V=V, d=d, dtype="bf16", M=M, cap=cap, zipf_s=1.2, copy_frac=0.4, span=(2, 7),
+               mode="motif", pool=pool, seed=8800 + V + d)
+    print(f"[case] streaming kernel B={B} rows/seq={rows_per_seq} V={V} d={d} M={M} cap={cap} {pool}", flush=True)
+    tokens = wl.make_tokens(cfg)
+    lens = wl.make_lens(cfg)
+    if B > 2:
+        lens[1] = 0                      # an empty codebook beside full ones
+        lens[2] = 9                      # and one with a handful of entries
+    E = wl.make_embeddings(cfg)
+    rows = B * rows_per_seq
+    H = wl.make_hidden(cfg, rows)
+    w = wl.make_pool_weights(cfg)
+    ctx = _ctx(cfg)
+    gpu_encode(ctx, tokens, lens)
+    ref = oracle_encode_batch(tokens, lens, V, M, cap)
+    sizes = [len(r[1]) for r in ref]
+    d_E = torch_storage(E, "bf16")
+    d_W = torch.full((B, cap, d), 1.0, dtype=torch.bfloat16, device="cuda")       # unused slots hold ones
+    if cap:
+        ctx.hyper_embed(d_E, d_W)
+        for b in range(B):
+            d_W[b, sizes[b]:] = 900.0    # rows that do not exist must never be read into a result
+        torch.cuda.synchronize()
+    base = "decode" if rows <= 64 and d % 128 == 0 else "mid"
+    am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_seq, d_E, d_W, base)
+    worst = dict(max=0.0, lse=0.0)
+    for b in range(B):
+        Wr = oracle.hyper_embed(E, "bf16", ref[b][1], cap, pool, w) if cap else np.zeros((0, d), np.uint16)
+        sl = slice(b * rows_per_seq, (b + 1) * rows_per_seq)
+        errs = check_logits_rows(oracle.extended_logits(H[sl], E, Wr, sizes[b], "bf16"), am[sl], mx[sl], lse[sl], None)
+        worst = {k: max(worst[k], errs[k]) for k in worst}
+    print(f"  {rows} rows ok, worst {worst}", flush=True)
+    ctx.close()
+
+
+@pytest.mark.parametrize("rows_per_call,d", [(128, 192), (90, 320), (40, 256), (64, 448)])
+def test_few_rows_base_part_planted_rows_pin_every_base_column(rows_per_call, d):
+    """For every base column v one hidden row is 64 x that column's weight row (exact in bf16), so the oracle's pick
+    for the row is v with a wide gap: a column that lands in the wrong place anywhere between the operand loads,
+    the MFMA lane map, the fold and the merge of the waves moves a pick.  The planted rows sit at scattered
+    positions of the calls' row tiles."""
+    B, V, cap, M = 1, 700, 0, 3
+    cfg = dict(name="midplant", B=B, N=400, V=V, d=d, dtype="bf16", M=M, cap=cap, zipf_s=1.1, copy_frac=0.4, span=(2, 6),
+               mode="motif", pool="mean", seed=7500 + d)
+    print(f"[case] streaming kernel, planted rows: V={V} d={d}, {rows_per_call} rows per call", flush=True)
+    ctx = _ctx(cfg)
+    ctx.reset()
+    Wb = wl.make_embeddings(cfg)
+    d_Wb = torch_storage(Wb, "bf16")
+    import torch
+    d_Wh = torch.zeros((B, cap, d), dtype=torch.bfloat16, device="cuda")
+    rng = np.random.Generator(np.random.PCG64(cfg["seed"] + 1))
+    col = 0
+    call = 0
+    while col < V:
+        n_plant = min(V - col, max(1, (2 * rows_per_call) // 3))                  # a third of the rows stay random
+        H = wl.make_hidden(wl.scaled(cfg, seed=cfg["seed"] + 10 + call), rows_per_call)
+        where = rng.permutation(rows_per_call)[:n_plant]
+        cols = np.arange(col, col + n_plant)
+        H[where] = oracle.round_to_storage(64.0 * oracle.to_f64(Wb[cols], "bf16"), "bf16")
+        planted = np.full(rows_per_call, -1, dtype=np.int64)
+        planted[where] = cols
+        want = oracle.extended_logits(H, Wb, np.zeros((0, d), np.uint16), 0, "bf16")
+        has = planted >= 0
+        assert (want["argmax"][has] == planted[has]).all() and (want["margin"][has] > 0.5).all()
+        am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_call, d_Wb, d_Wh,
+                            "decode" if rows_per_call <= 64 and d % 128 == 0 else "mid")
+        wrong = np.nonzero(has & (am != planted))[0]
+        assert wrong.size == 0, f"call {call}: rows {wrong[:8]} pick {am[wrong[:8]]}, planted {planted[wrong[:8]]}"
+        check_logits_rows(want, am, mx, lse, None)
+        col += n_plant
+        call += 1
+    print(f"  {V} planted columns picked over {call} calls, every row ok", flush=True)
+    ctx.close()

@@ -47,6 +47,7 @@ def _run(ctx, d_H, rows_per_seq, d_Wb, d_Wh, strip, mapping):
     am = torch.full((rows,), -5, dtype=torch.int32, device="cuda")
     mx = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
     lse = torch.full((rows,), 777.0, dtype=torch.float32, device="cuda")
+    ctx.set_option(api.OPT_LOGITS_KERNEL, 4)     # the tile kernel also where few rows would go to the streaming kernel
     ctx.set_option(api.OPT_LOGITS_STRIP, strip)
     ctx.set_option(api.OPT_LOGITS_MAP, mapping)
     before = ctx.read_launches()
@@ -260,8 +261,14 @@ def test_few_rows_per_sequence_every_row(B, rows_per_seq, V, d, M, cap, pool):
     ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am, mx, lse, None)
     torch.cuda.synchronize()
     after = ctx.read_launches()
-    assert after["decode"] == before["decode"] + 1 and after["tile_base"] == before["tile_base"] + 1
-    assert after["tile_hyper"] == before["tile_hyper"] and after["general"] == before["general"]
+    # hyper part: the matrix-core units of the decode kernel.  Base part: up to 64 rows in all the decode kernel's
+    # base units (a launch of their own), up to 128 the weight-streaming kernel, beyond that the tile kernel
+    want_decode = 2 if rows <= 64 else 1
+    want_mid = 1 if 64 < rows <= 128 else 0
+    want_tile = 1 if rows > 128 else 0
+    assert after["decode"] == before["decode"] + want_decode and after["mid"] == before["mid"] + want_mid
+    assert after["tile_base"] == before["tile_base"] + want_tile and after["tile_hyper"] == before["tile_hyper"]
+    assert after["general"] == before["general"]
     am_h, mx_h, lse_h = am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
     worst = dict(max=0.0, lse=0.0)
     for b in range(B):
@@ -273,10 +280,12 @@ def test_few_rows_per_sequence_every_row(B, rows_per_seq, V, d, M, cap, pool):
     print(f"  every row ok, worst {worst}", flush=True)
     # the tile kernels on the same call give the same picks
     ctx.set_option(api.OPT_DECODE_KERNEL, 1)
+    ctx.set_option(api.OPT_LOGITS_KERNEL, 4)
     am2, mx2, lse2 = torch.empty_like(am), torch.empty_like(mx), torch.empty_like(lse)
     ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am2, mx2, lse2, None)
     torch.cuda.synchronize()
     assert ctx.read_launches()["tile_hyper"] == after["tile_hyper"] + 1
+    assert ctx.read_launches()["tile_base"] == after["tile_base"] + 1
     am2_h, mx2_h, lse2_h = am2.cpu().numpy(), mx2.cpu().numpy(), lse2.cpu().numpy()
     for b in range(B):
         Wr = oracle.hyper_embed(E, "bf16", ref[b][1], cap, pool, w)
