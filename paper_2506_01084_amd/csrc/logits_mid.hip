@@ -160,9 +160,15 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
       load_w(w[(u + NBUF - 1) % NBUF], s + NBUF - 1);
     }
   };
-  auto finish = [&](int u) {
+  // (in_loop: the count above holds inside the loop, where every weight request feeds a later iteration.  In the
+  // steps after the loop the compiler drops the requests whose buffers no step reads any more, so there
+  // everything in flight is awaited: a handful of steps per tile.)
+  auto finish = [&](int u, bool in_loop) {
     compute(w[u], stage);
-    wait_loads<HL + 8>();
+    if (in_loop)
+      wait_loads<HL + 8>();
+    else
+      wait_loads<0>();
     __syncthreads();
     stage = stage == 2 ? 0 : stage + 1;
   };
@@ -181,14 +187,14 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
       requests(u, s0 + u);
-      finish(u);
+      finish(u, true);
     }
   }
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
     if (s0 + u < n_slabs) {                                // (uniform)
       requests(u, s0 + u);
-      finish(u);
+      finish(u, false);
     }
   // the requests past the end of the stream (slabs clamped onto the last one) must land before the stages are reused
   wait_loads<0>();

@@ -61,6 +61,10 @@ def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh, base="mid"):
     (9, 7, 1300, 4096, 3, 257, "mean"),          # 63 rows, d = 4096: the decode kernel's base units, four K phases
     (5, 3, 700, 448, 3, 100, "mean"),            # 15 rows, d = 448 (no multiple of 128): the streaming kernel, 7 slabs
     (2, 5, 520, 1024, 3, 30, "mean"),            # 10 rows: the decode kernel's base units, one K phase
+    (1, 64, 255, 192, 3, 0, "mean"),             # 64 rows, 3 slabs: every step is one of those after the buffer loop
+    (1, 64, 700, 320, 3, 0, "mean"),             # 64 rows, 5 slabs (one fewer than buffers); three weight tiles
+    (2, 60, 300, 704, 3, 20, "mean"),            # 120 rows, 11 slabs: one round of the buffers and five steps after
+    (64, 2, 20000, 4096, 3, 64, "mean"),         # 128 rows at the benchmark's width: 79 workgroups of 64 slabs
 ])
 def test_few_rows_base_part_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
     import torch
