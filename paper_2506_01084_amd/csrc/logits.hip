@@ -391,14 +391,12 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;
   const int base_vt = (V + base_tile - 1) / base_tile, hyp_vt = (cap + hyp_tile - 1) / hyp_tile;
   auto pick_strip = [&](long long row_tiles, int n_vt) { return pick_strip_for(c, row_tiles, n_vt); };
-  // few hidden rows in all (several per sequence, or more than 64 sequences): the base part is bound by the bytes
-  // of W_base.  Up to 64 rows: the base units of the decode kernel, which read long runs of every weight row (one
-  // pass over W_base at that kernel's rate); up to 128: the kernel that streams the weights past all rows at once
-  // (two passes of the base units cost more).  One part per 256 weight rows either way.
-  const bool few_ok = fast_base && c->opt_logits_kernel == 0;
-  const bool dec_base = few_ok && !decode_step && rows <= 64 && c->decode_ready && c->opt_decode_kernel != 1;
-  const bool mid_base = few_ok && !dec_base && rows <= 128 && z2z_logits_mid_ok(c, rows);
-  const int strip_b = (dec_base || mid_base) ? 1 : pick_strip((rows + base_tile - 1) / base_tile, base_vt);
+  // few hidden rows in all (several per sequence, or 65..128 sequences): the base part is bound by the bytes of
+  // W_base and goes to the kernel that streams the weights past all rows at once, one part per 256 weight rows
+  // (measured against the decode kernel's base units in a launch of their own at up to 64 rows: 260 against 305 us
+  // for the call at config 2's shape; two passes of those units for 65..128 rows cost more still)
+  const bool mid_base = fast_base && c->opt_logits_kernel == 0 && rows <= 128 && z2z_logits_mid_ok(c, rows);
+  const int strip_b = mid_base ? 1 : pick_strip((rows + base_tile - 1) / base_tile, base_vt);
   const int strip_h = pick_strip((long long)c->cfg.B * ((rows_per_seq + hyp_tile - 1) / hyp_tile), hyp_vt);
   const int base_strips = (base_vt + strip_b - 1) / strip_b;
   int hyp_strips = cap > 0 ? (hyp_vt + strip_h - 1) / strip_h : 0;
@@ -427,9 +425,7 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   a.map_lr = a.map_ls = a.map_xr = a.map_xs = a.map_sb_r = 1;
 
   int ns = 0;
-  if (dec_base) {
-    rc = z2z_launch_logits_decode_base(c, H, rows, W_base, &parts, n_parts, timed, s);
-  } else if (mid_base) {
+  if (mid_base) {
     if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
     rc = z2z_launch_logits_mid(c, a, W_base, V, 0, s);
     if (timed) {

@@ -657,41 +657,6 @@ int z2z_launch_linear_skinny(z2z_ctx* c, const void* A, const void* W, const flo
   return Z2Z_OK;
 }
 
-// The base units alone, for any `rows` hidden rows (64 per pass over W_base): parts 0 .. ceil(V / 256) - 1 of every
-// row, `n_parts` parts per row in all.  The base part of a call with a few rows in all (several per sequence).
-int z2z_launch_logits_decode_base(z2z_ctx* c, const void* H, int rows, const void* W_base, const z2z_parts* parts,
-                                  int n_parts, bool timed, hipStream_t s) {
-  if (rows < 1) return Z2Z_OK;
-  c->n_launch[Z2Z_KERNEL_DECODE]++;
-  DecodeArgs a;
-  memset(&a, 0, sizeof(a));
-  a.H = reinterpret_cast<const uint4*>(H);
-  a.W_base = reinterpret_cast<const uint4*>(W_base);
-  a.size = c->st.size;
-  a.B = rows;
-  a.V = c->cfg.V;
-  a.cap = 0;
-  a.d = c->cfg.d;
-  a.n_base_units = (a.V + D_BASE_UNIT - 1) / D_BASE_UNIT;
-  a.n_groups = (rows + 63) / 64;
-  a.units_per_seq = 0;
-  a.part_m = parts->m;
-  a.part_s = parts->s;
-  a.part_i = parts->i;
-  a.n_parts = n_parts;
-  a.ld = a.V;
-  a.inv_temperature = 1.0f;
-  const unsigned grid = (unsigned)(8 * ((a.n_base_units + 7) / 8) * a.n_groups);
-  if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  hipLaunchKernelGGL(logits_decode_kernel<0>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
-  if (timed) {
-    Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
-    c->n_timed++;
-  }
-  Z2Z_HIP_TRY(hipGetLastError());
-  return Z2Z_OK;
-}
-
 int z2z_logits_decode_parts(const z2z_ctx* c) {
   return (c->cfg.V + D_BASE_UNIT - 1) / D_BASE_UNIT + (c->cfg.cap + D_UNIT - 1) / D_UNIT;
 }

@@ -9,6 +9,4 @@ int z2z_logits_mid_prepare(z2z_ctx* c);
 bool z2z_logits_mid_ok(const z2z_ctx* c, int rows);
 int z2z_logits_mid_tiles(int w_rows);
 int z2z_launch_logits_mid(z2z_ctx* c, z2z_logits::LogitsArgs a, const void* W, int w_rows, int col0, hipStream_t s);
-// (logits_decode.hip) the decode kernel's base units alone on `rows` hidden rows, 64 per pass over W_base
-int z2z_launch_logits_decode_base(z2z_ctx* c, const void* H, int rows, const void* W_base, const z2z_parts* parts,
-                                  int n_parts, bool timed, hipStream_t s);
+

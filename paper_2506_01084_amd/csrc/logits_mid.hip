@@ -1,24 +1,25 @@
-// extended_logits, base-vocabulary part for 65..128 hidden rows in all (gfx950, bf16, d a multiple of 64): a decode
-// step of 65..128 sequences, a few rows per sequence, a short chunk; also up to 64 rows where d is no multiple of
-// 128.  (zip2zip paper, section 2.3, steps 7-9.)
+// extended_logits, base-vocabulary part for up to 128 hidden rows in all (gfx950, bf16, d a multiple of 64): a
+// decode step of 65..128 sequences, a few rows per sequence at a small batch, a short chunk.  (zip2zip paper,
+// section 2.3, steps 7-9.)
 //
 // With so few rows the part is bound by the bytes of W_base, like the one-row-per-sequence step.  That kernel's
-// base units hold 64 hidden rows in registers and would pass over W_base twice; the 256 x 256 tile kernel stages
+// base units hold 64 hidden rows in registers (one pass over W_base per 64 rows); the 256 x 256 tile kernel stages
 // both operands through two LDS stages and waits for memory once per slab (3.4-3.5 TB/s of weights at these row
 // counts).  Here the weights never touch LDS:
 //
 //   workgroup = 8 waves = one tile of 256 weight rows x all hidden rows; wave w owns weight rows 32 w .. 32 w + 31:
-//   2 or 4 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64 and up to 128 rows).
+//   2 or 4 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64 and up to 128 rows; two workgroups
+//   of the 64-row build fit a CU).
 //   K advances in slabs of 64.  A wave loads its own weight fragments straight from global memory in MFMA operand
 //   layout (lane = row, 16 bytes of each 32-byte k-step; the four k-steps of a slab use up whole 128-byte lines),
 //   two slabs at a time (256 contiguous bytes per row: +5 % over single slabs), four to five slabs ahead of their
 //   use in six register buffers.  The hidden rows of a slab (128 x 128 bytes, shared by the 8 waves, served by
 //   L2) go straight from global memory into one of three LDS stages, two slabs ahead, in the tile kernel's
 //   swizzled layout (conflict-free operand reads); one barrier per slab.
+//   The tiles start their walk over K at different slabs (+5-7 %: see below).
 //
-// Measured 3.6-3.8 TB/s of weights (the tile kernel: 3.4-3.5; the decode kernel's base units, which read 2 KiB
-// runs of a weight row per step: 4.5): what bounds all three is how much of a weight row a workgroup asks for
-// at a time, 128-256 bytes here at a stride of a whole row.  The fold of the finished tile into (max, sum-exp,
+// Measured at V = 128256, d = 4096: 4.1-4.9 TB/s of W_base (the tile kernel: 3.4-3.5; the decode kernel's base
+// units in a launch of their own: 4.5 at up to 64 rows).  The fold of the finished tile into (max, sum-exp,
 // argmax) triples is the tile kernel's; the 8 waves' triples of a hidden row are merged through LDS and leave one
 // part per (row, weight tile).
 #include "logits_mid.h"
@@ -87,11 +88,22 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   const size_t row_bytes = (size_t)a.d * 2;
   const int n_slabs = (int)(row_bytes / M_SLAB);
 
+  // The tiles walk K in the same order but start at different slabs (tile t at slab t mod n_slabs, wrapping round):
+  // at any moment the workgroups in flight ask for different 128-byte columns of their weight rows, not all for
+  // the same one, which would keep landing on the same few memory channels (rows are a power of two apart).
+#ifndef M_ROTATE
+#define M_ROTATE 1
+#endif
+  const int rot = M_ROTATE ? vt % n_slabs : 0;
+  auto slab_at = [&](int s) {                              // step -> slab (steps past the end repeat the last one)
+    const int x = min(s, n_slabs - 1) + rot;
+    return x >= n_slabs ? x - n_slabs : x;
+  };
   // weights: this lane's row, clamped onto the last one that exists; 16 bytes at (2 q + half) * 16 of a slab
   const int wrow = min(v0 + wave * 32 + (lane & 31), n_valid - 1);
   const unsigned char* wp = reinterpret_cast<const unsigned char*>(a.W) + (size_t)wrow * row_bytes + half * 16;
   auto load_w = [&](uint4 (&w)[4], int slab) {
-    const unsigned char* p = wp + (size_t)min(slab, n_slabs - 1) * M_SLAB;
+    const unsigned char* p = wp + (size_t)slab_at(slab) * M_SLAB;
 #pragma unroll
     for (int q = 0; q < 4; ++q) w[q] = *reinterpret_cast<const uint4*>(p + q * 32);
   };
@@ -109,7 +121,7 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
     hsrc[i] = (uint32_t)(min(row, nr - 1) * (int)row_bytes + (((lane & 7) ^ ((row >> 1) & 7)) << 4));
   }
   auto issue_h = [&](int slab, int stage) {
-    const unsigned char* p = Ht + (size_t)min(slab, n_slabs - 1) * M_SLAB;
+    const unsigned char* p = Ht + (size_t)slab_at(slab) * M_SLAB;
 #pragma unroll
     for (int i = 0; i < HL; ++i)
       load16_to_lds(p, hsrc[i], lds_base + (uint32_t)(stage * M_STAGE + (i * M_WAVES + wave) * 1024));
@@ -245,7 +257,9 @@ int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, i
   a.col0 = col0;
   a.n_vtiles = (w_rows + M_WT - 1) / M_WT;
   c->n_launch[Z2Z_KERNEL_MID]++;
-  const dim3 grid((unsigned)a.n_vtiles, 1u), block(M_THREADS);
+  // (two workgroups of the 64-row build per weight tile for 65..128 rows, sharing the tile's weights through an
+  // XCD's L2, measured slower than one of the 128-row build: 383 against 293 us at config 2's shape)
+  const dim3 grid((unsigned)a.n_vtiles), block(M_THREADS);
   if (a.rows <= 64)
     hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF>), grid, block, M_LDS, s, a);
   else

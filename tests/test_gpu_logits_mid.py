@@ -1,14 +1,14 @@
-"""GPU parity of the base-vocabulary part of extended_logits for calls with few hidden rows in all (a decode step
-of 65..128 sequences, a few rows per sequence at a small batch, a short chunk): every row and, through planted
-rows, every base column.  Joint logits, one softmax over base and hyper vocabulary, the pick: section 2.3,
-steps 7-9.
+"""GPU parity of the weight-streaming kernel that takes the base-vocabulary part of extended_logits for calls
+with at most 128 hidden rows in all (a decode step of 65..128 sequences, a few rows per sequence at a small
+batch, a short chunk): every row and, through planted rows, every base column.  Joint logits, one softmax over
+base and hyper vocabulary, the pick: section 2.3, steps 7-9.
 
-Two kernels share these calls (bf16 context, d a multiple of 64, no full-logits output, not a decode step of at
-most 64 sequences): up to 64 rows the base units of the decode kernel in a launch of their own (d a multiple of
-128), up to 128 rows the weight-streaming kernel; each test checks the library's launch counters.  Shapes span
-both builds of the streaming kernel (up to 64 and up to 128 rows), a last weight tile with a single row, fewer
-K slabs than weight buffers, a slab count that is no multiple of the buffer count, and both ways of the hyper
-part (the decode kernel's units, the MFMA tile kernel).
+A call lands there when the context is bf16, d is a multiple of 64, no full-logits output is asked for and the
+call is not a decode step of at most 64 sequences; each test checks the library's launch counters.  Shapes span
+both builds of the kernel (up to 64 and up to 128 rows), a last weight tile with a single row, fewer K slabs than
+weight buffers, slab counts that are no multiple of the buffer count, more weight tiles than K slabs (the tiles
+start their walk over K at different slabs), and both ways of the hyper part (the decode kernel's units, the
+MFMA tile kernel).
 
 Bars as for the other logits tests: max and lse within 2e-2 * max(1, |ref|), argmax identical wherever the
 oracle's two largest logits differ by more than 1e-2 (elsewhere it must name a logit within that gap).
@@ -31,9 +31,8 @@ def _ctx(cfg):
                        w=wl.make_pool_weights(cfg).tolist())
 
 
-def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh, base="mid"):
-    """One extended_logits call whose base part must run on the streaming kernel (base = "mid") or on the decode
-    kernel's base units (base = "decode"); host (argmax, max, lse)."""
+def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh):
+    """One extended_logits call whose base part must run on the streaming kernel; host (argmax, max, lse)."""
     import torch
 
     rows = d_H.shape[0]
@@ -44,10 +43,7 @@ def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh, base="mid"):
     ctx.extended_logits(d_H, rows_per_seq, d_Wb, d_Wh, am, mx, lse, None)
     torch.cuda.synchronize()
     after = ctx.read_launches()
-    if base == "mid":
-        assert after["mid"] == before["mid"] + 1, "the base part did not run on the streaming kernel"
-    else:
-        assert after["mid"] == before["mid"] and after["decode"] >= before["decode"] + 1, "base part not on the decode units"
+    assert after["mid"] == before["mid"] + 1, "the base part did not run on the streaming kernel"
     assert after["tile_base"] == before["tile_base"] and after["general"] == before["general"]
     return am.cpu().numpy(), mx.cpu().numpy(), lse.cpu().numpy()
 
@@ -55,18 +51,18 @@ def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh, base="mid"):
 @pytest.mark.parametrize("B,rows_per_seq,V,d,M,cap,pool", [
     (65, 1, 1000, 128, 3, 300, "mean"),          # a decode step of 65 sequences: 128-row build, hyper on the decode units
     (128, 1, 777, 192, 3, 0, "mean"),            # 128 rows, no hyper vocabulary: three K slabs
-    (3, 2, 300, 64, 4, 40, "mean"),              # 6 rows, one K slab (d no multiple of 128): 64-row build, fewer slabs than buffers
+    (3, 2, 300, 64, 4, 40, "mean"),              # 6 rows, one K slab: 64-row build, fewer slabs than buffers
     (1, 100, 2500, 320, 4, 100, "weighted"),     # 100 rows of one sequence: five slabs, hyper on the tile kernel
     (4, 24, 513, 576, 3, 70, "mean"),            # 96 rows; nine slabs; V one row past two weight tiles
-    (9, 7, 1300, 4096, 3, 257, "mean"),          # 63 rows, d = 4096: the decode kernel's base units, four K phases
-    (5, 3, 700, 448, 3, 100, "mean"),            # 15 rows, d = 448 (no multiple of 128): the streaming kernel, 7 slabs
-    (2, 5, 520, 1024, 3, 30, "mean"),            # 10 rows: the decode kernel's base units, one K phase
+    (9, 7, 1300, 4096, 3, 257, "mean"),          # 63 rows, d = 4096: 64 slabs, 6 weight tiles
+    (5, 3, 700, 448, 3, 100, "mean"),            # 15 rows, 7 slabs
+    (2, 5, 5200, 256, 3, 30, "mean"),            # 10 rows, 4 slabs, 21 weight tiles: every starting slab several times
     (1, 64, 255, 192, 3, 0, "mean"),             # 64 rows, 3 slabs: every step is one of those after the buffer loop
     (1, 64, 700, 320, 3, 0, "mean"),             # 64 rows, 5 slabs (one fewer than buffers); three weight tiles
     (2, 60, 300, 704, 3, 20, "mean"),            # 120 rows, 11 slabs: one round of the buffers and five steps after
     (64, 2, 20000, 4096, 3, 64, "mean"),         # 128 rows at the benchmark's width: 79 workgroups of 64 slabs
 ])
-def test_few_rows_base_part_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
+def test_streaming_kernel_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
     import torch
 
     N = 900
@@ -93,8 +89,7 @@ def test_few_rows_base_part_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool
         for b in range(B):
             d_W[b, sizes[b]:] = 900.0    # rows that do not exist must never be read into a result
         torch.cuda.synchronize()
-    base = "decode" if rows <= 64 and d % 128 == 0 else "mid"
-    am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_seq, d_E, d_W, base)
+    am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_seq, d_E, d_W)
     worst = dict(max=0.0, lse=0.0)
     for b in range(B):
         Wr = oracle.hyper_embed(E, "bf16", ref[b][1], cap, pool, w) if cap else np.zeros((0, d), np.uint16)
@@ -106,7 +101,7 @@ def test_few_rows_base_part_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool
 
 
 @pytest.mark.parametrize("rows_per_call,d", [(128, 192), (90, 320), (40, 256), (64, 448)])
-def test_few_rows_base_part_planted_rows_pin_every_base_column(rows_per_call, d):
+def test_streaming_kernel_planted_rows_pin_every_base_column(rows_per_call, d):
     """For every base column v one hidden row is 64 x that column's weight row (exact in bf16), so the oracle's pick
     for the row is v with a wide gap: a column that lands in the wrong place anywhere between the operand loads,
     the MFMA lane map, the fold and the merge of the waves moves a pick.  The planted rows sit at scattered
@@ -135,8 +130,7 @@ def test_few_rows_base_part_planted_rows_pin_every_base_column(rows_per_call, d)
         want = oracle.extended_logits(H, Wb, np.zeros((0, d), np.uint16), 0, "bf16")
         has = planted >= 0
         assert (want["argmax"][has] == planted[has]).all() and (want["margin"][has] > 0.5).all()
-        am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_call, d_Wb, d_Wh,
-                            "decode" if rows_per_call <= 64 and d % 128 == 0 else "mid")
+        am, mx, lse = _call(ctx, torch_storage(H, "bf16"), rows_per_call, d_Wb, d_Wh)
         wrong = np.nonzero(has & (am != planted))[0]
         assert wrong.size == 0, f"call {call}: rows {wrong[:8]} pick {am[wrong[:8]]}, planted {planted[wrong[:8]]}"
         check_logits_rows(want, am, mx, lse, None)
