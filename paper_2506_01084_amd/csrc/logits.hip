@@ -466,12 +466,15 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   sp.seed = seed;
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
-  if (top_k <= 0 && top_p >= 1.0f && rows > 128 && c->cfg.d % 64 == 0 && c->fast_ready && c->opt_logits_kernel != 1) {
+  // 65..128 rows: the base vocabulary goes to the weight-streaming kernel (with the tile kernel's sampling epilogues)
+  const bool mid_base = rows > 64 && c->opt_logits_kernel == 0 && z2z_logits_mid_ok(c, rows);
+  if (top_k <= 0 && top_p >= 1.0f && (rows > 128 || mid_base) && c->cfg.d % 64 == 0 && c->fast_ready &&
+      c->opt_logits_kernel != 1) {
     // no filter, more than two passes of the decode kernel's base units (the generator in the tile kernel's
     // epilogue costs more than the second pass): as for the argmax, the tile kernel takes the base vocabulary
     // (with the draw folded into its epilogue) and the hyper units run alone
     const int base_vt = (c->cfg.V + 255) / 256;
-    const int strip_b = pick_strip_for(c, (rows + 255) / 256, base_vt);
+    const int strip_b = mid_base ? 1 : pick_strip_for(c, (rows + 255) / 256, base_vt);
     const int base_strips = (base_vt + strip_b - 1) / strip_b;
     int base_columns, hyper_columns;
     z2z_logits_decode_units(&base_columns, &hyper_columns);
@@ -500,7 +503,10 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     a.ctr2 = (uint32_t)step;
     a.ctr3 = (uint32_t)(step >> 32);
     int ns = 0;
-    rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
+    if (mid_base)
+      rc = z2z_launch_logits_mid(c, a, W_base, c->cfg.V, 0, s);
+    else
+      rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
     if (rc != Z2Z_OK) return rc;
     if (c->cfg.cap > 0) {
       int np = 0;
@@ -546,7 +552,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     // vocabulary's scaled logits, the hyper units run alone (strips of at most 2 tiles: the selection kernels'
     // short-list pass takes parts of up to 512 columns)
     const int base_vt = (c->cfg.V + 255) / 256;
-    int strip_b = pick_strip_for(c, (rows + 255) / 256, base_vt);
+    int strip_b = mid_base ? 1 : pick_strip_for(c, (rows + 255) / 256, base_vt);
     if (strip_b > 2) strip_b = 2;
     const int base_strips = (base_vt + strip_b - 1) / strip_b;
     int unit_base, unit_hyper;
@@ -569,7 +575,10 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
     a.logits = c->sample_logits;
     a.ld = c->cfg.V + c->cfg.cap;
     int ns = 0;
-    rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
+    if (mid_base)
+      rc = z2z_launch_logits_mid(c, a, W_base, c->cfg.V, 0, s);
+    else
+      rc = z2z_launch_logits_part(c, false, true, a, W_base, c->cfg.V, 0, 0, strip_b, rows, 1, &ns, timed, s);
     if (rc != Z2Z_OK) return rc;
     if (c->cfg.cap > 0) {
       int np = 0;

@@ -8,8 +8,7 @@
 // counts).  Here the weights never touch LDS:
 //
 //   workgroup = 8 waves = one tile of 256 weight rows x all hidden rows; wave w owns weight rows 32 w .. 32 w + 31:
-//   2 or 4 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64 and up to 128 rows; two workgroups
-//   of the 64-row build fit a CU).
+//   2 or 4 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64 and up to 128 rows).
 //   K advances in slabs of 64.  A wave loads its own weight fragments straight from global memory in MFMA operand
 //   layout (lane = row, 16 bytes of each 32-byte k-step; the four k-steps of a slab use up whole 128-byte lines),
 //   two slabs at a time (256 contiguous bytes per row: +5 % over single slabs), four to five slabs ahead of their
@@ -47,7 +46,7 @@ constexpr int M_LDS = M_NSTAGE * M_STAGE;
 #ifndef M_PAIR
 #define M_PAIR 1
 #endif
-static_assert(M_WAVES * M_HT * (int)sizeof(Triple) <= M_LDS, "the waves' triples are merged in the idle stages");
+static_assert(M_WAVES * M_HT * (int)(sizeof(Triple) + sizeof(Draw)) <= M_LDS, "the waves' triples are merged in the idle stages");
 
 // 16 bytes per lane, global -> LDS without passing through registers (as in the tile kernel): address = 64-bit
 // scalar base + 32-bit per-lane offset; the LDS address is the wave-uniform byte offset in M0 plus 16 * lane.
@@ -71,8 +70,10 @@ __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
 }
 
 // NJV: blocks of 32 hidden rows the instance is built for (rows of the tile <= 32 NJV); NBUF: weight register
-// buffers (slabs in flight + the one in use).
-template <int NJV, int NBUF>
+// buffers (slabs in flight + the one in use); SMODE: 0 = fold the logits, 1 = fold logit / T and the Gumbel-max
+// draw (a.sample = 1: part_v, part_l, and the drawn column in part_i), 2 = store logit / T and fold it
+// (a.sample = 2) -- the tile kernel's epilogues for its modes 0, 6 and 7.
+template <int NJV, int NBUF, int SMODE>
 __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
   const int tid = threadIdx.x;
@@ -212,11 +213,21 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   wait_loads<0>();
   __syncthreads();
 
-  // ---- fold the tile, then one triple per hidden row -------------------------------------------------------
+  // ---- fold the tile, then one triple (and draw) per hidden row --------------------------------------------
   Triple run[NJV];
+  Draw draw[NJV];
 #pragma unroll
-  for (int j = 0; j < NJV; ++j) run[j] = empty_triple();
-  fold_tile<1, NJV>(acc, run, v0 + wave * 32 + half * 4, a.col0, n_valid, v0 + M_WT > n_valid);
+  for (int j = 0; j < NJV; ++j) {
+    run[j] = empty_triple();
+    draw[j] = empty_draw();
+  }
+  const int col_base = v0 + wave * 32 + half * 4;
+  if (SMODE == 1)
+    fold_tile_sample<1, NJV>(acc, run, draw, a, r0, col_base, n_valid);
+  else if (SMODE == 2)
+    fold_tile_store<1, NJV>(acc, run, a, r0, r_end, col_base, n_valid);
+  else
+    fold_tile<1, NJV>(acc, run, col_base, a.col0, n_valid, v0 + M_WT > n_valid);
 #pragma unroll
   for (int j = 0; j < NJV; ++j) {                          // lanes l and l + 32 hold the same hidden row
     Triple o;
@@ -224,11 +235,22 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
     o.s = __shfl_xor(run[j].s, 32);
     o.i = __shfl_xor(run[j].i, 32);
     merge_triple(run[j], o);
+    if (SMODE == 1) {
+      Draw od;
+      od.v = __shfl_xor(draw[j].v, 32);
+      od.l = __shfl_xor(draw[j].l, 32);
+      od.i = __shfl_xor(draw[j].i, 32);
+      merge_draw(draw[j], od);
+    }
   }
   Triple* xch = reinterpret_cast<Triple*>(lds);            // [wave][hidden row of the tile]
+  Draw* xdr = reinterpret_cast<Draw*>(xch + M_WAVES * M_HT);
   if (lane < 32) {
 #pragma unroll
-    for (int j = 0; j < NJV; ++j) xch[wave * M_HT + j * 32 + lane] = run[j];
+    for (int j = 0; j < NJV; ++j) {
+      xch[wave * M_HT + j * 32 + lane] = run[j];
+      if (SMODE == 1) xdr[wave * M_HT + j * 32 + lane] = draw[j];
+    }
   }
   __syncthreads();
   if (tid < nr) {
@@ -238,7 +260,16 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
     const size_t p = (size_t)(r0 + tid) * a.n_parts + a.part0 + vt;
     a.part_m[p] = t.m;
     a.part_s[p] = t.s;
-    a.part_i[p] = t.i;
+    if (SMODE == 1) {
+      Draw dw = xdr[tid];
+#pragma unroll
+      for (int w = 1; w < M_WAVES; ++w) merge_draw(dw, xdr[w * M_HT + tid]);
+      a.part_v[p] = dw.v;
+      a.part_l[p] = dw.l;
+      a.part_i[p] = dw.i;
+    } else {
+      a.part_i[p] = t.i;
+    }
   }
 }
 
@@ -249,7 +280,8 @@ bool z2z_logits_mid_ok(const z2z_ctx* c, int rows) {
 }
 
 // The base part of a call: one part per tile of 256 weight rows.  a: H, rows, d, the part arrays, n_parts, part0
-// filled by the caller.
+// filled by the caller; with a.sample = 1 or 2 also the generator words, inv_temperature and part_v / part_l or
+// logits / ld, as for the tile kernel's sampling modes.
 int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, int col0, hipStream_t s) {
   if (!z2z_logits_mid_ok(c, a.rows) || w_rows < 1) return Z2Z_EUNSUPPORTED;
   a.W = W;
@@ -260,10 +292,18 @@ int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, i
   // (two workgroups of the 64-row build per weight tile for 65..128 rows, sharing the tile's weights through an
   // XCD's L2, measured slower than one of the 128-row build: 383 against 293 us at config 2's shape)
   const dim3 grid((unsigned)a.n_vtiles), block(M_THREADS);
-  if (a.rows <= 64)
-    hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF>), grid, block, M_LDS, s, a);
-  else
-    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF>), grid, block, M_LDS, s, a);
+  const bool few = a.rows <= 64;
+  // (the sampling calls come with one row per sequence and more than 64 of them: the 128-row build only)
+  if (a.sample == 1) {
+    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 1>), grid, block, M_LDS, s, a);
+  } else if (a.sample == 2) {
+    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 2>), grid, block, M_LDS, s, a);
+  } else {
+    if (few)
+      hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF, 0>), grid, block, M_LDS, s, a);
+    else
+      hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 0>), grid, block, M_LDS, s, a);
+  }
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
 }
@@ -272,9 +312,11 @@ int z2z_logits_mid_tiles(int w_rows) { return (w_rows + M_WT - 1) / M_WT; }
 
 int z2z_logits_mid_prepare(z2z_ctx* c) {
   if (c->lds_limit < M_LDS) return Z2Z_EUNSUPPORTED;
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, M_LDS));
-  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, M_LDS));
+  const void* kernels[4] = {reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 0>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 0>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 1>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 2>)};
+  for (int k = 0; k < 4; ++k)
+    Z2Z_HIP_TRY(hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, M_LDS));
   return Z2Z_OK;
 }
