@@ -371,7 +371,7 @@ enum {
                                   logits' reduction: 2 = no operand requests after the first two K slabs,
                                   3 = the MFMA stream alone (no requests, no LDS reads, one fold per strip);
                                   4 = the bf16 MFMA tile kernel also for the base part of calls with at most
-                                  128 hidden rows, which otherwise goes to the weight-streaming kernel */
+                                  192 hidden rows, which otherwise goes to the weight-streaming kernel */
   Z2Z_OPT_LOGITS_STRIP = 2,    /* vocabulary tiles swept per workgroup, 0 = automatic               */
   Z2Z_OPT_LZW_KERNEL = 3,      /* 0 = automatic, >0 = force a variant (2: table in global memory, 3: one
                                   code per step in the decoder, 4: one wave per sequence in the encoder) */
@@ -402,7 +402,7 @@ int z2z_read_timing(z2z_ctx* ctx, float* total_ms, int32_t* launches);
  *   counts[Z2Z_KERNEL_TILE_HYPER]  bf16 MFMA tile kernel, per-sequence hyper-vocabulary launches
  *   counts[Z2Z_KERNEL_GENERAL]     the general tile kernel (fp32, d not a multiple of 64, full logits)
  *   counts[Z2Z_KERNEL_DECODE]      the one-row-per-sequence (bandwidth-bound) kernel
- *   counts[Z2Z_KERNEL_MID]         the weight-streaming kernel for the base part of calls with up to 128 hidden rows
+ *   counts[Z2Z_KERNEL_MID]         the weight-streaming kernel for the base part of calls with up to 192 hidden rows
  * `counts` is a host array of Z2Z_N_KERNEL_FAMILIES elements. */
 enum { Z2Z_KERNEL_TILE_BASE = 0, Z2Z_KERNEL_TILE_HYPER = 1, Z2Z_KERNEL_GENERAL = 2, Z2Z_KERNEL_DECODE = 3,
        Z2Z_KERNEL_MID = 4, Z2Z_N_KERNEL_FAMILIES = 5 };

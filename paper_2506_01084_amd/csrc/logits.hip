@@ -391,11 +391,11 @@ int z2z_launch_extended_logits(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   const int base_tile = fast_base ? 256 : 128, hyp_tile = fast_hyper ? 256 : 128;
   const int base_vt = (V + base_tile - 1) / base_tile, hyp_vt = (cap + hyp_tile - 1) / hyp_tile;
   auto pick_strip = [&](long long row_tiles, int n_vt) { return pick_strip_for(c, row_tiles, n_vt); };
-  // few hidden rows in all (several per sequence, or 65..128 sequences): the base part is bound by the bytes of
+  // few hidden rows in all (several per sequence, or 65..192 sequences): the base part is bound by the bytes of
   // W_base and goes to the kernel that streams the weights past all rows at once, one part per 256 weight rows
   // (measured against the decode kernel's base units in a launch of their own at up to 64 rows: 260 against 305 us
-  // for the call at config 2's shape; two passes of those units for 65..128 rows cost more still)
-  const bool mid_base = fast_base && c->opt_logits_kernel == 0 && rows <= 128 && z2z_logits_mid_ok(c, rows);
+  // for the call at config 2's shape; two or three passes of those units for more rows cost more still)
+  const bool mid_base = fast_base && c->opt_logits_kernel == 0 && z2z_logits_mid_ok(c, rows);
   const int strip_b = mid_base ? 1 : pick_strip((rows + base_tile - 1) / base_tile, base_vt);
   const int strip_h = pick_strip((long long)c->cfg.B * ((rows_per_seq + hyp_tile - 1) / hyp_tile), hyp_vt);
   const int base_strips = (base_vt + strip_b - 1) / strip_b;
@@ -466,7 +466,7 @@ int z2z_launch_extended_sample(z2z_ctx* c, const void* H, int32_t rows, int32_t 
   sp.seed = seed;
   sp.step = step;
   const bool timed = c->opt_timing && c->n_timed < Z2Z_MAX_TIMED && c->ev_created;
-  // 65..128 rows: the base vocabulary goes to the weight-streaming kernel (with the tile kernel's sampling epilogues)
+  // 65..192 rows: the base vocabulary goes to the weight-streaming kernel (with the tile kernel's sampling epilogues)
   const bool mid_base = rows > 64 && c->opt_logits_kernel == 0 && z2z_logits_mid_ok(c, rows);
   if (top_k <= 0 && top_p >= 1.0f && (rows > 128 || mid_base) && c->cfg.d % 64 == 0 && c->fast_ready &&
       c->opt_logits_kernel != 1) {

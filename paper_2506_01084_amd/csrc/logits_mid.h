@@ -1,4 +1,4 @@
-// The base part of extended_logits on the weight-streaming kernel (up to 128 hidden rows; logits_mid.hip): one
+// The base part of extended_logits on the weight-streaming kernel (up to 192 hidden rows; logits_mid.hip): one
 // part per tile of 256 weight rows, z2z_logits_mid_tiles(w_rows) of them; `a` carries H, rows, d, the part arrays,
 // n_parts and part0.
 #pragma once

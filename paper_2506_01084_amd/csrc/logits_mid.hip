@@ -1,5 +1,5 @@
-// extended_logits, base-vocabulary part for up to 128 hidden rows in all (gfx950, bf16, d a multiple of 64): a
-// decode step of 65..128 sequences, a few rows per sequence at a small batch, a short chunk.  (zip2zip paper,
+// extended_logits, base-vocabulary part for up to 192 hidden rows in all (gfx950, bf16, d a multiple of 64): a
+// decode step of 65..192 sequences, a few rows per sequence at a small batch, a short chunk.  (zip2zip paper,
 // section 2.3, steps 7-9.)
 //
 // With so few rows the part is bound by the bytes of W_base, like the one-row-per-sequence step.  That kernel's
@@ -8,11 +8,12 @@
 // counts).  Here the weights never touch LDS:
 //
 //   workgroup = 8 waves = one tile of 256 weight rows x all hidden rows; wave w owns weight rows 32 w .. 32 w + 31:
-//   2 or 4 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64 and up to 128 rows).
+//   2, 4 or 6 blocks of v_mfma_f32_32x32x16_bf16 (the kernel is built for up to 64, 128 and 192 rows).
 //   K advances in slabs of 64.  A wave loads its own weight fragments straight from global memory in MFMA operand
 //   layout (lane = row, 16 bytes of each 32-byte k-step; the four k-steps of a slab use up whole 128-byte lines),
 //   two slabs at a time (256 contiguous bytes per row: +5 % over single slabs), four to five slabs ahead of their
-//   use in six register buffers.  The hidden rows of a slab (128 x 128 bytes, shared by the 8 waves, served by
+//   use in six register buffers (two to three ahead in four with 6 blocks of accumulators).  The hidden rows of a
+//   slab (up to 192 x 128 bytes, shared by the 8 waves, served by
 //   L2) go straight from global memory into one of three LDS stages, two slabs ahead, in the tile kernel's
 //   swizzled layout (conflict-free operand reads); one barrier per slab.
 //   The tiles start their walk over K at different slabs (+5-7 %: see below).
@@ -32,15 +33,18 @@ using namespace z2z_logits;
 constexpr int M_WAVES = 8;
 constexpr int M_THREADS = 64 * M_WAVES;
 constexpr int M_WT = 32 * M_WAVES;        // weight rows of a workgroup's tile
-constexpr int M_HT = 128;                 // hidden rows of a call at most (the builds below: 2 or 4 blocks of 32)
+constexpr int M_HT = 192;                 // hidden rows of a call at most (the builds below: 2, 4 or 6 blocks of 32)
 constexpr int M_MAX_ROWS = M_HT;
 constexpr int M_SLAB = 128;               // bytes per row per K slab (64 bf16)
-constexpr int M_STAGE = M_HT * M_SLAB;    // the hidden rows of one slab: 16 KiB
+constexpr int M_STAGE = M_HT * M_SLAB;    // the hidden rows of one slab: 24 KiB
 constexpr int M_NSTAGE = 3;
 constexpr int M_LDS = M_NSTAGE * M_STAGE;
 // weight register buffers per instance (what fits beside 16 NJV accumulators without spilling inside the K loop)
 #ifndef M_NBUF
 #define M_NBUF 6                          // up to 128 hidden rows
+#endif
+#ifndef M_NBUF_6
+#define M_NBUF_6 4                        // up to 192 (96 accumulator registers)
 #endif
 // 1: the weights of two consecutive slabs are requested together, every other step: 256 contiguous bytes per row
 #ifndef M_PAIR
@@ -292,17 +296,27 @@ int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, i
   // (two workgroups of the 64-row build per weight tile for 65..128 rows, sharing the tile's weights through an
   // XCD's L2, measured slower than one of the 128-row build: 383 against 293 us at config 2's shape)
   const dim3 grid((unsigned)a.n_vtiles), block(M_THREADS);
-  const bool few = a.rows <= 64;
-  // (the sampling calls come with one row per sequence and more than 64 of them: the 128-row build only)
+  // builds: 2, 4 or 6 blocks of 32 hidden rows; the sampling calls come with one row per sequence and more than 64
+  // of them.  (8 blocks, up to 256 rows, leave the registers for four buffers at most and measured level with the
+  // tile kernel: 650 against 645 us for a decode step of 256 sequences.)
+  const int blocks = a.rows <= 64 ? 2 : (a.rows <= 128 ? 4 : 6);
   if (a.sample == 1) {
-    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 1>), grid, block, M_LDS, s, a);
-  } else if (a.sample == 2) {
-    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 2>), grid, block, M_LDS, s, a);
-  } else {
-    if (few)
-      hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF, 0>), grid, block, M_LDS, s, a);
+    if (blocks <= 4)
+      hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 1>), grid, block, M_LDS, s, a);
     else
+      hipLaunchKernelGGL((logits_mid_kernel<6, M_NBUF_6, 1>), grid, block, M_LDS, s, a);
+  } else if (a.sample == 2) {
+    if (blocks <= 4)
+      hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 2>), grid, block, M_LDS, s, a);
+    else
+      hipLaunchKernelGGL((logits_mid_kernel<6, M_NBUF_6, 2>), grid, block, M_LDS, s, a);
+  } else {
+    if (blocks == 2)
+      hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF, 0>), grid, block, M_LDS, s, a);
+    else if (blocks == 4)
       hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 0>), grid, block, M_LDS, s, a);
+    else
+      hipLaunchKernelGGL((logits_mid_kernel<6, M_NBUF_6, 0>), grid, block, M_LDS, s, a);
   }
   Z2Z_HIP_TRY(hipGetLastError());
   return Z2Z_OK;
@@ -312,11 +326,14 @@ int z2z_logits_mid_tiles(int w_rows) { return (w_rows + M_WT - 1) / M_WT; }
 
 int z2z_logits_mid_prepare(z2z_ctx* c) {
   if (c->lds_limit < M_LDS) return Z2Z_EUNSUPPORTED;
-  const void* kernels[4] = {reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 0>),
+  const void* kernels[7] = {reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 0>),
                             reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 0>),
                             reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 1>),
-                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 2>)};
-  for (int k = 0; k < 4; ++k)
+                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 2>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 0>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 1>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 2>)};
+  for (int k = 0; k < 7; ++k)
     Z2Z_HIP_TRY(hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, M_LDS));
   return Z2Z_OK;
 }

@@ -82,7 +82,7 @@ struct z2z_ctx {
   int decode_ready;        // the decode-step logits kernel can be launched for this configuration
   int skinny_ready;        // the decode-step kernel's LDS fits this device (dense layers on few rows use it)
   int fast_ready;          // the 128 KiB-LDS bf16 logits kernel can be launched on this device
-  int mid_ready;           // the weight-streaming kernel for up to 128 hidden rows can be launched on this device
+  int mid_ready;           // the weight-streaming kernel for up to 192 hidden rows can be launched on this device
   // timing record
   hipEvent_t ev_start[Z2Z_MAX_TIMED];
   hipEvent_t ev_stop[Z2Z_MAX_TIMED];

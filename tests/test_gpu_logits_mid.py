@@ -1,11 +1,11 @@
 """GPU parity of the weight-streaming kernel that takes the base-vocabulary part of extended_logits for calls
-with at most 128 hidden rows in all (a decode step of 65..128 sequences, a few rows per sequence at a small
+with at most 192 hidden rows in all (a decode step of 65..192 sequences, a few rows per sequence at a small
 batch, a short chunk): every row and, through planted rows, every base column.  Joint logits, one softmax over
 base and hyper vocabulary, the pick: section 2.3, steps 7-9.
 
 A call lands there when the context is bf16, d is a multiple of 64, no full-logits output is asked for and the
 call is not a decode step of at most 64 sequences; each test checks the library's launch counters.  Shapes span
-both builds of the kernel (up to 64 and up to 128 rows), a last weight tile with a single row, fewer K slabs than
+the three builds of the kernel (up to 64, 128 and 192 rows), a last weight tile with a single row, fewer K slabs than
 weight buffers, slab counts that are no multiple of the buffer count, more weight tiles than K slabs (the tiles
 start their walk over K at different slabs), and both ways of the hyper part (the decode kernel's units, the
 MFMA tile kernel).
@@ -61,6 +61,10 @@ def _call(ctx, d_H, rows_per_seq, d_Wb, d_Wh):
     (1, 64, 700, 320, 3, 0, "mean"),             # 64 rows, 5 slabs (one fewer than buffers); three weight tiles
     (2, 60, 300, 704, 3, 20, "mean"),            # 120 rows, 11 slabs: one round of the buffers and five steps after
     (64, 2, 20000, 4096, 3, 64, "mean"),         # 128 rows at the benchmark's width: 79 workgroups of 64 slabs
+    (130, 1, 777, 256, 3, 300, "mean"),          # a decode step of 130 sequences: 192-row build, four slabs (one round of its buffers)
+    (3, 60, 1500, 448, 4, 100, "weighted"),      # 180 rows, seven slabs: a round and three steps after
+    (192, 1, 513, 192, 3, 0, "mean"),            # 192 rows, three slabs: every row of the 192-row build valid
+    (6, 30, 9000, 4096, 3, 40, "mean"),          # 180 rows at the benchmark's width
 ])
 def test_streaming_kernel_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
     import torch
@@ -100,7 +104,7 @@ def test_streaming_kernel_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
     ctx.close()
 
 
-@pytest.mark.parametrize("rows_per_call,d", [(128, 192), (90, 320), (40, 256), (64, 448)])
+@pytest.mark.parametrize("rows_per_call,d", [(128, 192), (90, 320), (40, 256), (64, 448), (192, 320), (150, 128)])
 def test_streaming_kernel_planted_rows_pin_every_base_column(rows_per_call, d):
     """For every base column v one hidden row is 64 x that column's weight row (exact in bf16), so the oracle's pick
     for the row is v with a wide gap: a column that lands in the wrong place anywhere between the operand loads,

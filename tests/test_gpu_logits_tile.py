@@ -261,10 +261,10 @@ def test_few_rows_per_sequence_every_row(B, rows_per_seq, V, d, M, cap, pool):
     ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am, mx, lse, None)
     torch.cuda.synchronize()
     after = ctx.read_launches()
-    # hyper part: the matrix-core units of the decode kernel.  Base part: up to 128 rows in all the weight-streaming
+    # hyper part: the matrix-core units of the decode kernel.  Base part: up to 192 rows in all the weight-streaming
     # kernel, beyond that the tile kernel
-    want_mid = 1 if rows <= 128 else 0
-    want_tile = 1 if rows > 128 else 0
+    want_mid = 1 if rows <= 192 else 0
+    want_tile = 1 if rows > 192 else 0
     assert after["decode"] == before["decode"] + 1 and after["mid"] == before["mid"] + want_mid
     assert after["tile_base"] == before["tile_base"] + want_tile and after["tile_hyper"] == before["tile_hyper"]
     assert after["general"] == before["general"]
