@@ -2,6 +2,7 @@
 // count, the workgroup -> tile mapping of the tile kernel, and the sum of K-split partial tiles.  Used by the
 // learned hyper-encoder (zip2zip paper, section 2.2) and by the backward pass of the loss (section 2.4).
 #include "logits_common.h"
+#include "logits_mid.h"
 
 #include <string.h>
 
@@ -118,6 +119,34 @@ int z2z_launch_transpose(const void* in, void* out, int R, const int32_t* rows_d
 int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bias, const void* residual, int act,
                       void* out, int R, const int32_t* rows_dev, int N, int K, hipStream_t s, const int32_t* k_dev,
                       bool stream_f32) {
+  // up to 128 rows (a decode step's new entries through the learned encoder at a small batch): bound by the weight
+  // bytes; the weight-streaming kernel with K split over workgroups, its fp32 partial tiles summed with the layer's
+  // epilogue.  (The encoder's newest-entry pass at d = 4096, d_ff = 4 d: 347 -> 316 us for 8 sequences, 401 -> 392
+  // for 40; with the 192-row build for 129..192 rows laid out the tile kernel's K split below is faster, 432
+  // against 459 us for 64 sequences.)
+  if (R <= 128 && !k_dev && K % 64 == 0 && N % 4 == 0 && c->opt_logits_kernel == 0 && z2z_logits_mid_ok(c, R)) {
+    const int ksplit = z2z_linear_mid_ksplit(N, K);
+    const size_t need = (size_t)ksplit * R * N * sizeof(float);
+    if (need > c->skinny_partial_bytes) {
+      Z2Z_TRY_GROW(s);
+      if (c->skinny_partial) (void)hipFree(c->skinny_partial);
+      c->skinny_partial = nullptr;
+      c->skinny_partial_bytes = 0;
+      const size_t want = need > ((size_t)64 << 20) ? need : ((size_t)64 << 20);
+      if (hipMalloc(&c->skinny_partial, want) != hipSuccess) return Z2Z_ENOMEM;
+      c->skinny_partial_bytes = want;
+    }
+    int ks = 0;
+    int rc = z2z_launch_linear_mid(c, A, W, R, rows_dev, N, K, reinterpret_cast<float*>(c->skinny_partial),
+                                   c->skinny_partial_bytes / sizeof(float), &ks, s);
+    if (rc != Z2Z_OK) return rc;
+    const long long n_threads = (long long)R * (N / 4);
+    hipLaunchKernelGGL(linear_sum_kernel, dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float*>(c->skinny_partial), ks, R, rows_dev, N, bias, act, residual, out,
+                       stream_f32 ? 1 : 0);
+    Z2Z_HIP_TRY(hipGetLastError());
+    return Z2Z_OK;
+  }
   // more rows than the 64 the decode-step kernel serves per pass over the weights, but fewer 256 x 256 output
   // tiles than would give every CU one (a few hundred rows, or up to a few thousand with a narrow layer): the
   // tile kernel with K split over workgroups, so that the weights stream once for all rows and every CU has a

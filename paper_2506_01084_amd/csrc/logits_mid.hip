@@ -76,7 +76,8 @@ __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
 // NJV: blocks of 32 hidden rows the instance is built for (rows of the tile <= 32 NJV); NBUF: weight register
 // buffers (slabs in flight + the one in use); SMODE: 0 = fold the logits, 1 = fold logit / T and the Gumbel-max
 // draw (a.sample = 1: part_v, part_l, and the drawn column in part_i), 2 = store logit / T and fold it
-// (a.sample = 2) -- the tile kernel's epilogues for its modes 0, 6 and 7.
+// (a.sample = 2) -- the tile kernel's epilogues for its modes 0, 6 and 7; 3 = a dense layer with K split over
+// gridDim.y workgroups per tile: the fp32 partial tile goes to a.partial[ks][row][col] (the tile kernel's mode 5).
 template <int NJV, int NBUF, int SMODE>
 __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
@@ -86,12 +87,17 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   const int half = lane >> 5;
   const int vt = blockIdx.x;                               // weight tile
   const int r0 = 0;                                        // (one row tile: the call has at most M_HT rows)
-  const int r_end = a.rows;
-  const int nr = min(32 * NJV, r_end - r0);                // valid hidden rows (>= 1: the grid covers no empty tile)
+  // SMODE 3 (a dense layer's partial sums): the rows that exist may be known on the device only, and blockIdx.y is
+  // the part of K this workgroup takes (slabs [ks * slabs_per_part, ...))
+  const int r_end = (SMODE == 3 && a.rows_dev) ? min(a.rows, *a.rows_dev) : a.rows;
+  if (r_end <= r0) return;                                 // (the whole workgroup)
+  const int nr = min(32 * NJV, r_end - r0);                // valid hidden rows
   const int n_valid = a.w_rows;
   const int v0 = vt * M_WT;
   const size_t row_bytes = (size_t)a.d * 2;
-  const int n_slabs = (int)(row_bytes / M_SLAB);
+  const int ks = SMODE == 3 ? (int)blockIdx.y : 0;
+  const int slab0 = SMODE == 3 ? ks * a.slabs_per_part : 0;
+  const int n_slabs = SMODE == 3 ? min(a.slabs_per_part, (int)(row_bytes / M_SLAB) - slab0) : (int)(row_bytes / M_SLAB);
 
   // The tiles walk K in the same order but start at different slabs (tile t at slab t mod n_slabs, wrapping round):
   // at any moment the workgroups in flight ask for different 128-byte columns of their weight rows, not all for
@@ -102,7 +108,7 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
   const int rot = M_ROTATE ? vt % n_slabs : 0;
   auto slab_at = [&](int s) {                              // step -> slab (steps past the end repeat the last one)
     const int x = min(s, n_slabs - 1) + rot;
-    return x >= n_slabs ? x - n_slabs : x;
+    return slab0 + (x >= n_slabs ? x - n_slabs : x);
   };
   // weights: this lane's row, clamped onto the last one that exists; 16 bytes at (2 q + half) * 16 of a slab
   const int wrow = min(v0 + wave * 32 + (lane & 31), n_valid - 1);
@@ -226,6 +232,11 @@ __global__ void __launch_bounds__(M_THREADS) logits_mid_kernel(LogitsArgs a) {
     draw[j] = empty_draw();
   }
   const int col_base = v0 + wave * 32 + half * 4;
+  if (SMODE == 3) {
+    // a dense layer's K part: the fp32 tile as it is; linear_sum_kernel adds the parts and runs the layer's epilogue
+    store_partial_tile<1, NJV>(acc, a.partial + (size_t)ks * a.rows * a.ldo, a.ldo, r0, r_end, col_base, n_valid);
+    return;
+  }
   if (SMODE == 1)
     fold_tile_sample<1, NJV>(acc, run, draw, a, r0, col_base, n_valid);
   else if (SMODE == 2)
@@ -322,18 +333,63 @@ int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, i
   return Z2Z_OK;
 }
 
+// Parts of K per weight tile: enough workgroups for every CU where K allows parts of at least four slabs.
+int z2z_linear_mid_ksplit(int N, int K) {
+  const int n_vt = (N + M_WT - 1) / M_WT, n_slabs = K / 64;
+  int ksplit = 1;
+  while (n_vt * ksplit < 256 && n_slabs / (ksplit + 1) >= 4) ++ksplit;
+  const int per = (n_slabs + ksplit - 1) / ksplit;
+  return (n_slabs + per - 1) / per;                        // no empty parts
+}
+
+// Dense layer out = act(A W^T + bias) + residual on R <= 128 rows (or fewer, *rows_dev): the weight-streaming kernel
+// leaves ksplit fp32 partial tiles per weight tile in `partial` ([ksplit][R][N]); the caller sums them
+// (linear_sum_kernel in dense.hip).  Returns the ksplit chosen through *ksplit_out.
+int z2z_launch_linear_mid(z2z_ctx* c, const void* A, const void* W, int R, const int32_t* rows_dev, int N, int K,
+                          float* partial, size_t partial_floats, int* ksplit_out, hipStream_t s) {
+  if (!z2z_logits_mid_ok(c, R) || R > 128 || K % 64 != 0 || N < 1) return Z2Z_EUNSUPPORTED;
+  const int n_vt = (N + M_WT - 1) / M_WT, n_slabs = K / 64;
+  const int ksplit = z2z_linear_mid_ksplit(N, K);
+  const int per = (n_slabs + ksplit - 1) / ksplit;
+  if ((size_t)ksplit * R * N > partial_floats) return Z2Z_ELIMIT;
+  LogitsArgs a;
+  memset(&a, 0, sizeof(a));
+  a.H = A;
+  a.W = W;
+  a.rows = R;
+  a.d = K;
+  a.w_rows = N;
+  a.n_vtiles = n_vt;
+  a.ldo = N;
+  a.rows_dev = rows_dev;
+  a.ksplit = ksplit;
+  a.slabs_per_part = per;
+  a.partial = partial;
+  *ksplit_out = ksplit;
+  c->n_launch[Z2Z_KERNEL_MID]++;
+  const dim3 grid((unsigned)n_vt, (unsigned)ksplit), block(M_THREADS);
+  if (R <= 64)
+    hipLaunchKernelGGL((logits_mid_kernel<2, M_NBUF, 3>), grid, block, M_LDS, s, a);
+  else
+    hipLaunchKernelGGL((logits_mid_kernel<4, M_NBUF, 3>), grid, block, M_LDS, s, a);
+  Z2Z_HIP_TRY(hipGetLastError());
+  return Z2Z_OK;
+}
+
 int z2z_logits_mid_tiles(int w_rows) { return (w_rows + M_WT - 1) / M_WT; }
 
 int z2z_logits_mid_prepare(z2z_ctx* c) {
   if (c->lds_limit < M_LDS) return Z2Z_EUNSUPPORTED;
-  const void* kernels[7] = {reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 0>),
+  const void* kernels[9] = {reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 3>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 3>),
+                            reinterpret_cast<const void*>(logits_mid_kernel<2, M_NBUF, 0>),
                             reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 0>),
                             reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 1>),
                             reinterpret_cast<const void*>(logits_mid_kernel<4, M_NBUF, 2>),
                             reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 0>),
                             reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 1>),
                             reinterpret_cast<const void*>(logits_mid_kernel<6, M_NBUF_6, 2>)};
-  for (int k = 0; k < 7; ++k)
+  for (int k = 0; k < 9; ++k)
     Z2Z_HIP_TRY(hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, M_LDS));
   return Z2Z_OK;
 }
