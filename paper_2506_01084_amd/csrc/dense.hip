@@ -121,7 +121,7 @@ int z2z_launch_linear(z2z_ctx* c, const void* A, const void* W, const float* bia
                       bool stream_f32) {
   // up to 128 rows (a decode step's new entries through the learned encoder at a small batch): bound by the weight
   // bytes; the weight-streaming kernel with K split over workgroups, its fp32 partial tiles summed with the layer's
-  // epilogue.  (The encoder's newest-entry pass at d = 4096, d_ff = 4 d: 347 -> 316 us for 8 sequences, 401 -> 392
+  // epilogue.  (The encoder's newest-entry pass at d = 4096, d_ff = 4 d: 347 -> 302 us for 8 sequences, 401 -> 374
   // for 40; with the 192-row build for 129..192 rows laid out the tile kernel's K split below is faster, 432
   // against 459 us for 64 sequences.)
   if (R <= 128 && !k_dev && K % 64 == 0 && N % 4 == 0 && c->opt_logits_kernel == 0 && z2z_logits_mid_ok(c, R)) {

@@ -333,13 +333,23 @@ int z2z_launch_logits_mid(z2z_ctx* c, LogitsArgs a, const void* W, int w_rows, i
   return Z2Z_OK;
 }
 
-// Parts of K per weight tile: enough workgroups for every CU where K allows parts of at least four slabs.
+// Parts of K per weight tile: the split (parts of at least four slabs, at most 16 parts) with the fewest slab steps
+// on the busiest CU -- rounds of 256 workgroups x (slabs per part + 3 for filling and draining the pipeline); a
+// split that puts a few workgroups into a second round costs a whole round.
 int z2z_linear_mid_ksplit(int N, int K) {
   const int n_vt = (N + M_WT - 1) / M_WT, n_slabs = K / 64;
-  int ksplit = 1;
-  while (n_vt * ksplit < 256 && n_slabs / (ksplit + 1) >= 4) ++ksplit;
-  const int per = (n_slabs + ksplit - 1) / ksplit;
-  return (n_slabs + per - 1) / per;                        // no empty parts
+  int best = 1;
+  long long best_cost = -1;
+  for (int ks = 1; ks <= 16 && (ks == 1 || n_slabs / ks >= 4); ++ks) {
+    const int per = (n_slabs + ks - 1) / ks;
+    const int parts = (n_slabs + per - 1) / per;           // no empty parts
+    const long long cost = (long long)((n_vt * parts + 255) / 256) * (per + 3);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = parts;
+    }
+  }
+  return best;
 }
 
 // Dense layer out = act(A W^T + bias) + residual on R <= 128 rows (or fewer, *rows_dev): the weight-streaming kernel
