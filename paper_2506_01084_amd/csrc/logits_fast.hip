@@ -83,6 +83,9 @@ constexpr int F_PAIRS = 32 / F_WAVES;                  // request pairs (8 rows 
 // Request pair i goes out after the MFMA with window index 1 + i * F_SPREAD, counted from the slab
 // hand-over: first the rest of the hand-over k-step (F_KSTEP - F_NJ MFMAs), then the first three k-steps
 // of the next slab.
+#ifndef F_ROTATE_FEW
+#define F_ROTATE_FEW 1                   // 0: the rotated-K instances (see the kernel) are never launched
+#endif
 #ifndef F_HO_ROWS
 #define F_HO_ROWS 1
 #endif
@@ -170,7 +173,13 @@ struct Frags {
 // requesting operands after the first two slabs (the matrix cores, the LDS reads and the fold run as usual on
 // those two slabs' values), 9 also stops reading LDS and folds once per strip -- the MFMA stream alone.  They
 // bracket what the operand stream costs and give the clock the matrix cores alone are left with.
-template <int MODE>
+// ROT (base part with a single row tile: up to 256 hidden rows): nobody shares a workgroup's weight tiles, so the
+// strips walk K from different slabs, wrapping round.  With all of them at the same
+// slab every request in flight goes to the same 128-byte column of rows a power of two apart, and with it to the
+// same few memory channels.  (With many row tiles the workgroups that share operands through L2 and the
+// memory-side cache must stay in step: there the rotation costs 1-2 %, and so does its arithmetic alone; with two
+// row tiles it is level or 1 % slower.  A decode step of 256 sequences: 646 -> 634 us, with a filtered draw 704 -> 675.)
+template <int MODE, bool ROT = false>
 __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   constexpr bool PROBE_NOREQ = MODE == 8 || MODE == 9;
   constexpr bool PROBE_MFMA = MODE == 9;
@@ -271,11 +280,17 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
   uint32_t isA = 0;                          // LDS destination (operand A) of the slab being requested
   const unsigned char* is_ga = Wp;
   const unsigned char* is_gb = Hp;
+  const int rot = ROT ? st % n_slabs : 0;
   auto issue_begin = [&](int stage) {
     isA = lds_base + stage * F_STAGE + wave * (F_PAIRS * 1024);
     if (lvt < vt_end) {                      // else: keep the last valid source
-      is_ga = Wtile + (size_t)lslab * F_SLAB;
-      is_gb = Hp + (size_t)lslab * F_SLAB;
+      int sl = lslab;
+      if (ROT) {
+        sl += rot;
+        if (sl >= n_slabs) sl -= n_slabs;
+      }
+      is_ga = Wtile + (size_t)sl * F_SLAB;
+      is_gb = Hp + (size_t)sl * F_SLAB;
     }
   };
 #define Z2Z_ISSUE_PAIR(i)                                             \
@@ -563,7 +578,14 @@ __global__ void __launch_bounds__(F_THREADS) logits_fast_kernel(LogitsArgs a) {
 }  // namespace
 
 int z2z_launch_logits_fast(int mode, const LogitsArgs& a, unsigned grid, hipStream_t s) {
-  if (mode == 9)
+  const bool rot = F_ROTATE_FEW && a.row_tiles == 1;
+  if (rot && mode == 0)
+    hipLaunchKernelGGL((logits_fast_kernel<0, true>), dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (rot && mode == 6)
+    hipLaunchKernelGGL((logits_fast_kernel<6, true>), dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (rot && mode == 7)
+    hipLaunchKernelGGL((logits_fast_kernel<7, true>), dim3(grid), dim3(F_THREADS), F_LDS, s, a);
+  else if (mode == 9)
     hipLaunchKernelGGL(logits_fast_kernel<9>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
   else if (mode == 8)
     hipLaunchKernelGGL(logits_fast_kernel<8>, dim3(grid), dim3(F_THREADS), F_LDS, s, a);
@@ -608,6 +630,12 @@ int z2z_logits_fast_prepare(z2z_ctx* c) {
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<8>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<9>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<0, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<6, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
+  Z2Z_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(logits_fast_kernel<7, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS));
   return Z2Z_OK;
 }

@@ -71,6 +71,8 @@ def _run(ctx, d_H, rows_per_seq, d_Wb, d_Wh, strip, mapping):
     (4, 260, 1300, 320, 3, 513, "mean"),        # five slabs (odd: the two LDS stages swap roles per tile)
     (1, 1000, 777, 192, 2, 0, "mean"),          # no hyper vocabulary
     (9, 33, 300, 576, 3, 257, "mean"),          # nine slabs, 297 rows, cap one column past a tile
+    (2, 100, 1300, 320, 3, 300, "mean"),        # 200 rows, a single row tile: the weight tiles walk K from different slabs
+    (1, 250, 2100, 192, 3, 0, "mean"),          # the same with three slabs and nine weight tiles (every start, wrapping round)
 ])
 def test_tile_kernels_every_row_ragged(B, rows_per_seq, V, d, M, cap, pool):
     import torch

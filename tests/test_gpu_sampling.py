@@ -59,9 +59,10 @@ def _setup(cfg, lens=None):
     (65, 300, 1000, 256, 3, 300),
     (128, 120, 1301, 384, 3, 70),           # 128 rows: the base vocabulary on the weight-streaming kernel, 6 K slabs
     (5, 200, 777, 128, 4, 0),
-    (130, 400, 513, 384, 5, 1030),      # beyond 128 rows: the draw folded into the tile kernel (base), hyper units
+    (130, 400, 513, 384, 5, 1030),      # 129..192 rows: the streaming kernel's widest build (base), hyper units
+    (230, 100, 1500, 384, 3, 50),       # 193..256 rows: the draw folded into the tile kernel, one row tile (rotated K walk)
     (300, 150, 2300, 256, 3, 90),       # two row tiles, ragged column tail, every sequence one hyper unit
-    (140, 100, 700, 128, 3, 0),         # the same with no codebook
+    (140, 100, 700, 128, 3, 0),         # 140 rows with no codebook
     (2, 3000, 40000, 4096, 3, 700),
 ])
 def test_draws_match_oracle_every_row(B, N, V, d, M, cap):
@@ -248,7 +249,8 @@ def _check_truncated(logits_row, T, k, p, seed, step, row, tok, lp):
     (6, 3000, 40000, 512, 3, 700),          # rows long enough for several histogram passes; 159 parts
     (9, 2000, 9000, 256, 3, 1500),          # 36 base parts and 3 hyper parts
     (100, 150, 2100, 384, 3, 90),           # 65..128 rows: the weight-streaming kernel stores the base vocabulary's logits
-    (150, 200, 3001, 256, 3, 200),          # beyond 128 rows: the tile kernel stores the base vocabulary's logits
+    (150, 200, 3001, 256, 3, 200),          # 129..192 rows: the streaming kernel's widest build stores them
+    (200, 120, 1800, 384, 3, 60),           # 193..256 rows: the tile kernel stores them, one row tile (rotated K walk)
     (700, 60, 2100, 128, 3, 40),            # three row tiles: base parts of two tiles (512 columns) each
 ])
 def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_only):
