@@ -20,6 +20,11 @@
 //    dot products (v_dot2c_f32_bf16), one weight row per wave at a time, 1 KiB per load instruction,
 //    the hidden row held in registers; rows at and beyond C_b are never touched.
 // Each unit leaves one triple per hidden row in the same [row][part] scratch the prefill kernels use.
+//
+// Where at most four hidden rows meet a weight row -- a decode step of up to four sequences, or the per-sequence
+// part of a call with two to four hidden rows per sequence (a verification step over drafted codes) -- those rows
+// fit in registers, and the dot-product units take that work too (dot_unit below): whole weight rows streamed
+// once, nothing handed over through LDS.
 #include "logits_common.h"
 
 #include <string.h>
@@ -42,6 +47,12 @@ constexpr int D_SLOT_FLOATS = 64 * D_SLOT_STRIDE;         // one wave's 16 x 64 
 constexpr int D_SLOTS_BYTES = 2 * 8 * D_SLOT_FLOATS * 4;  // two buffers x eight waves
 constexpr int D_LDS = D_TILE_BYTES + D_SLOTS_BYTES;       // 144 KiB (the triple exchange reuses the slots)
 constexpr int D_MAXQ = 8;              // hyper units: d <= 512 * D_MAXQ
+#ifndef D_DOT_ROWS
+#define D_DOT_ROWS 4                   // hidden rows per sequence up to which the per-sequence part runs on dot-product units
+#endif
+#ifndef D_DOT_BATCH
+#define D_DOT_BATCH 4                  // sequences per decode step up to which the base vocabulary does too
+#endif
 
 struct DecodeArgs {
   const uint4* H;         // [B, d] bf16
@@ -473,6 +484,128 @@ __device__ __forceinline__ void hyper_unit(const DecodeArgs& a, int b, int u, un
   }
 }
 
+// Dot-product units for R = 1..4 hidden rows: as hyper_rows, with all R rows in registers (R x NQ x 4 of them), so
+// that every weight row streams past once, whole and contiguous -- the access pattern HBM serves best (6.3 TB/s
+// for the per-sequence part of a call with 2 rows per sequence, against 5.2 on the matrix-core units).  Rows
+// [r0, r1) of the matrix W against the hidden rows hrow0 .. hrow0 + R - 1; weight row r is column col0 + r.
+template <int NQ, int R, int MODE>
+__device__ __forceinline__ void dot_rows(const DecodeArgs& a, const uint4* W, int hrow0, int col0, int r0, int r1,
+                                         int lane, int wave, Triple (&t)[R], Draw (&dr)[R]) {
+  const int chunks_per_row = a.d >> 3;
+  Noise noise[R];
+  uint4 h[R][NQ];
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    noise[i].group = -1;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c = q * 64 + lane;
+      h[i][q] = c < chunks_per_row ? a.H[(size_t)(hrow0 + i) * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+    }
+  }
+  for (int r = r0 + wave; r < r1; r += 16) {
+    // two rows per trip (r and r + 8) keep 2 * NQ KiB of loads in flight per wave
+    const int rb = r + 8;
+    const bool has_b = rb < r1;
+    uint4 wa[NQ], wb[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c = q * 64 + lane;
+      const bool in = c < chunks_per_row;
+      wa[q] = in ? W[(size_t)r * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+      wb[q] = (in && has_b) ? W[(size_t)rb * chunks_per_row + c] : uint4{0u, 0u, 0u, 0u};
+    }
+    float sa[R], sb[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) sa[i] = sb[i] = 0.f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const uint32_t xa[4] = {wa[q].x, wa[q].y, wa[q].z, wa[q].w};
+      const uint32_t xb[4] = {wb[q].x, wb[q].y, wb[q].z, wb[q].w};
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        const uint32_t hw[4] = {h[i][q].x, h[i][q].y, h[i][q].z, h[i][q].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          sa[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xa[e]), __builtin_bit_cast(bf16x2, hw[e]),
+                                                  sa[i], false);
+          sb[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xb[e]), __builtin_bit_cast(bf16x2, hw[e]),
+                                                  sb[i], false);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) {
+        sa[i] += __shfl_xor(sa[i], o);
+        sb[i] += __shfl_xor(sb[i], o);
+      }
+      fold_logit<MODE>(a, t[i], dr[i], noise[i], sa[i], hrow0 + i, col0 + r);
+      if (has_b) fold_logit<MODE>(a, t[i], dr[i], noise[i], sb[i], hrow0 + i, col0 + rb);
+      if (MODE == 2 && lane == 0) {
+        a.logits[(size_t)(hrow0 + i) * a.ld + col0 + r] = sa[i] * a.inv_temperature;
+        if (has_b) a.logits[(size_t)(hrow0 + i) * a.ld + col0 + rb] = sb[i] * a.inv_temperature;
+      }
+    }
+  }
+}
+
+// One unit: rows [r0, r1) (r1 <= r0 may be: an empty part) -> part `part` of the hidden rows hrow0 .. hrow0 + R - 1.
+template <int R, int MODE>
+__device__ __forceinline__ void dot_unit(const DecodeArgs& a, const uint4* W, int hrow0, int col0, int r0, int r1,
+                                         int part, unsigned char* lds) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  Triple* xch = reinterpret_cast<Triple*>(lds);                 // [8 waves][R]
+  Draw* xdr = reinterpret_cast<Draw*>(xch + 8 * R);
+  Triple t[R];
+  Draw dr[R];
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    t[i] = empty_triple();
+    dr[i] = empty_draw();
+  }
+  if (r0 < r1) {
+    const int nq = (a.d + 511) >> 9;
+    if (nq <= 4)
+      dot_rows<4, R, MODE>(a, W, hrow0, col0, r0, r1, lane, wave, t, dr);
+    else
+      dot_rows<D_MAXQ, R, MODE>(a, W, hrow0, col0, r0, r1, lane, wave, t, dr);
+  }
+  // every lane of a wave holds the same triples; the waves took rows w, w + 8, ...: merging by value and column
+  // restores the lowest-column rule
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      xch[wave * R + i] = t[i];
+      if (MODE == 1) xdr[wave * R + i] = dr[i];
+    }
+  }
+  __syncthreads();
+  if (tid < R) {
+    Triple r = xch[tid];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) merge_triple(r, xch[s * R + tid]);
+    const size_t p = (size_t)(hrow0 + tid) * a.n_parts + part;
+    a.part_m[p] = r.m;
+    a.part_s[p] = r.s;
+    if (MODE == 1) {
+      Draw d0 = xdr[tid];
+#pragma unroll
+      for (int s = 1; s < 8; ++s) merge_draw(d0, xdr[s * R + tid]);
+      a.part_v[p] = d0.v;
+      a.part_l[p] = d0.l;
+      a.part_i[p] = d0.i;
+    } else {
+      a.part_i[p] = r.i;
+    }
+  }
+}
+
+constexpr size_t D_DOT_LDS = 8 * 4 * (sizeof(Triple) + sizeof(Draw));
+
 template <int MODE>
 __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -497,6 +630,45 @@ __global__ void __launch_bounds__(D_THREADS) logits_decode_kernel(DecodeArgs a) 
     if (unit >= a.n_base_units) return;
     base_unit<MODE>(a, unit, group, MODE == 3 ? rest / units8 : 0, lds);
   }
+}
+
+// The per-sequence part of a call with R = 2..4 hidden rows per sequence (R = a.rows_per_seq) on dot-product units:
+// workgroup (b, u) takes rows [256 u, 256 u + 256) of W_hyper[b], one part each (the layout of the matrix-core
+// units that take more rows per sequence); plain logits only.
+template <int R>
+__global__ void __launch_bounds__(D_THREADS) logits_decode_rows_kernel(DecodeArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int b = blockIdx.x / a.seq_units, u = blockIdx.x % a.seq_units;
+  const int C = min(max(a.size[b], 0), a.cap);
+  dot_unit<R, 0>(a, a.W_hyper + (size_t)b * a.cap * (a.d >> 3), b * R, a.V, u * D_BASE_UNIT, min(C, (u + 1) * D_BASE_UNIT),
+                 a.n_base_units + u, lds);
+}
+
+// A decode step of R = B <= 4 sequences: the base vocabulary on dot-product units as well (256 rows of W_base
+// against all R hidden rows, part = unit as for the matrix-core units), behind the hyper units of
+// logits_decode_kernel.
+template <int R, int MODE>
+__global__ void __launch_bounds__(D_THREADS) logits_decode_small_kernel(DecodeArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int n_hyper = a.B * a.units_per_seq;
+  const int bid = blockIdx.x;
+  if (bid < n_hyper) {
+    hyper_unit<MODE>(a, bid / a.units_per_seq, bid % a.units_per_seq, lds);
+  } else {
+    const int unit = bid - n_hyper;
+    if (unit >= a.n_base_units) return;
+    dot_unit<R, MODE>(a, a.W_base, 0, 0, unit * D_BASE_UNIT, min(a.V, (unit + 1) * D_BASE_UNIT), unit, lds);
+  }
+}
+
+template <int R>
+void launch_small(int mode, unsigned grid, hipStream_t s, const DecodeArgs& a) {
+  if (mode == 2)
+    hipLaunchKernelGGL((logits_decode_small_kernel<R, 2>), dim3(grid), dim3(D_THREADS), D_DOT_LDS, s, a);
+  else if (mode == 1)
+    hipLaunchKernelGGL((logits_decode_small_kernel<R, 1>), dim3(grid), dim3(D_THREADS), D_DOT_LDS, s, a);
+  else
+    hipLaunchKernelGGL((logits_decode_small_kernel<R, 0>), dim3(grid), dim3(D_THREADS), D_DOT_LDS, s, a);
 }
 
 // Dense layer with K split: one workgroup per (unit, group) adds the ksplit partial tiles in a fixed order and
@@ -581,7 +753,15 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
     grid = (unsigned)(a.B * a.seq_units);
     if (grid == 0) return Z2Z_OK;
     if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-    hipLaunchKernelGGL(logits_decode_kernel<4>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
+    constexpr size_t rows_lds = D_DOT_LDS;
+    if (rows_per_seq == 2 && D_DOT_ROWS >= 2)       // few enough to keep in registers: whole weight rows streamed
+      hipLaunchKernelGGL(logits_decode_rows_kernel<2>, dim3(grid), dim3(D_THREADS), rows_lds, s, a);
+    else if (rows_per_seq == 3 && D_DOT_ROWS >= 3)
+      hipLaunchKernelGGL(logits_decode_rows_kernel<3>, dim3(grid), dim3(D_THREADS), rows_lds, s, a);
+    else if (rows_per_seq == 4 && D_DOT_ROWS >= 4)
+      hipLaunchKernelGGL(logits_decode_rows_kernel<4>, dim3(grid), dim3(D_THREADS), rows_lds, s, a);
+    else
+      hipLaunchKernelGGL(logits_decode_kernel<4>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
     if (timed) {
       Z2Z_HIP_TRY(hipEventRecord(c->ev_stop[c->n_timed], s));
       c->n_timed++;
@@ -590,7 +770,20 @@ int z2z_launch_logits_decode(z2z_ctx* c, const void* H, const void* W_base, cons
     return Z2Z_OK;
   }
   if (timed) Z2Z_HIP_TRY(hipEventRecord(c->ev_start[c->n_timed], s));
-  if (logits)                                         // with `sample`: stored and folded as logit / temperature
+  if (hyper_only_base_parts < 0 && a.B <= D_DOT_BATCH) {
+    // up to 4 sequences: their hidden rows fit in registers, so the base vocabulary streams through dot-product
+    // units too (whole rows, no hand-over through LDS)
+    const int mode = logits ? 2 : (sample ? 1 : 0);
+    grid = (unsigned)(a.B * a.units_per_seq + a.n_base_units);
+    if (a.B == 1)
+      launch_small<1>(mode, grid, s, a);
+    else if (a.B == 2)
+      launch_small<2>(mode, grid, s, a);
+    else if (a.B == 3)
+      launch_small<3>(mode, grid, s, a);
+    else
+      launch_small<4>(mode, grid, s, a);
+  } else if (logits)                                  // with `sample`: stored and folded as logit / temperature
     hipLaunchKernelGGL(logits_decode_kernel<2>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);
   else if (sample)
     hipLaunchKernelGGL(logits_decode_kernel<1>, dim3(grid), dim3(D_THREADS), D_LDS, s, a);

@@ -382,7 +382,10 @@ def test_full_size_decode_step_c3():
                                         # rows the base vocabulary goes to the tile kernel, the hyper units stay)
     (140, 100, 400, 256, 3, 0),         # the same split with no codebook at all
     (300, 120, 2000, 512, 3, 100),      # two row tiles of the tile kernel, 300 hyper units
-    (1, 5000, 50000, 256, 2, 600),      # one row
+    (1, 5000, 50000, 256, 2, 600),      # one row: up to 4 sequences the base vocabulary runs on dot-product units too
+    (2, 900, 3000, 4096, 3, 700),       # two rows, widest d
+    (4, 600, 1300, 2560, 4, 300),       # four rows (one codebook empty, one nearly); d no multiple of 512
+    (3, 500, 513, 1024, 3, 1030),       # three rows; V one row past two units, cap spans three hyper units
     (64, 64, 300, 4096, 3, 512),        # widest d the kernel takes
 ])
 def test_decode_kernel_small_shapes_every_row(B, N, V, d, M, cap):

@@ -215,11 +215,15 @@ def test_full_size_every_row_position_of_a_tile(name):
 
 
 # ---------------------------------------------------------------------------------------------------
-# 2..64 hidden rows per sequence: the hyper part runs on the decode kernel's matrix-core units (one workgroup
-# per sequence and 256 rows of its W_hyper), the base vocabulary on the tile kernel; every row
+# 2..64 hidden rows per sequence: the hyper part runs on the decode kernel's per-sequence units (one workgroup
+# per sequence and 256 rows of its W_hyper: dot-product units with the hidden rows in registers up to 4 rows per
+# sequence, matrix-core units beyond), the base vocabulary on the streaming or the tile kernel; every row
 # ---------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("B,rows_per_seq,V,d,M,cap,pool", [
     (5, 2, 1000, 128, 3, 300, "mean"),          # two rows per sequence, cap spans two blocks of 256
+    (7, 3, 900, 512, 3, 520, "mean"),           # three rows per sequence; cap ends 8 rows into a third block
+    (6, 4, 1500, 4096, 4, 300, "weighted"),     # four rows per sequence (the most the dot-product units take), widest rows
+    (4, 2, 800, 2560, 3, 257, "mean"),          # d no multiple of 512: lanes whose last chunk lies past the row end
     (4, 17, 700, 256, 4, 1030, "weighted"),     # one row past a 16-row group; five blocks, the last with 6 rows
     (70, 5, 520, 384, 3, 257, "mean"),          # 350 rows: two row tiles of the base part; cap one past a block
     (3, 64, 300, 1024, 5, 100, "mean"),         # the most rows per sequence this path takes; one full K phase
@@ -263,7 +267,7 @@ def test_few_rows_per_sequence_every_row(B, rows_per_seq, V, d, M, cap, pool):
     ctx.extended_logits(d_H, rows_per_seq, d_E, d_Wp, am, mx, lse, None)
     torch.cuda.synchronize()
     after = ctx.read_launches()
-    # hyper part: the matrix-core units of the decode kernel.  Base part: up to 192 rows in all the weight-streaming
+    # hyper part: the per-sequence units of the decode kernel.  Base part: up to 192 rows in all the weight-streaming
     # kernel, beyond that the tile kernel
     want_mid = 1 if rows <= 192 else 0
     want_tile = 1 if rows > 192 else 0

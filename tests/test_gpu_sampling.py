@@ -64,6 +64,9 @@ def _setup(cfg, lens=None):
     (300, 150, 2300, 256, 3, 90),       # two row tiles, ragged column tail, every sequence one hyper unit
     (140, 100, 700, 128, 3, 0),         # 140 rows with no codebook
     (2, 3000, 40000, 4096, 3, 700),
+    (1, 500, 3000, 512, 3, 600),        # up to 4 sequences: the base vocabulary on dot-product units, draw folded in
+    (4, 300, 2000, 2560, 3, 513),       # four sequences; d no multiple of 512
+    (3, 400, 1300, 1024, 4, 100),
 ])
 def test_draws_match_oracle_every_row(B, N, V, d, M, cap):
     import torch
@@ -71,7 +74,8 @@ def test_draws_match_oracle_every_row(B, N, V, d, M, cap):
     cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=7 * B + V)
     print(f"[case] sampling B={B} V={V} d={d} cap={cap}", flush=True)
     lens = wl.make_lens(cfg)
-    lens[1] = 0
+    if B > 1:
+        lens[1] = 0
     ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, lens)
     tok = torch.empty(B, dtype=torch.int32, device="cuda")
     lp = torch.empty(B, dtype=torch.float32, device="cuda")
@@ -88,7 +92,7 @@ def test_draws_match_oracle_every_row(B, N, V, d, M, cap):
             assert 0 <= tok_h[b] < V + C
             _check_draws(r, tok_h[b:b + 1], lp_h[b:b + 1], T)
             decided += int(r["gap"][0] > GAP)
-        assert decided >= 0.9 * B           # the comparison is not vacuous
+        assert decided >= 0.9 * B - (1 if B < 8 else 0)           # the comparison is not vacuous
     ctx.close()
 
 
@@ -252,6 +256,8 @@ def _check_truncated(logits_row, T, k, p, seed, step, row, tok, lp):
     (150, 200, 3001, 256, 3, 200),          # 129..192 rows: the streaming kernel's widest build stores them
     (200, 120, 1800, 384, 3, 60),           # 193..256 rows: the tile kernel stores them, one row tile (rotated K walk)
     (700, 60, 2100, 128, 3, 40),            # three row tiles: base parts of two tiles (512 columns) each
+    (1, 2000, 9000, 512, 3, 1500),          # one sequence: the dot-product units store the base vocabulary's logits
+    (4, 600, 5000, 2560, 3, 300),           # four sequences
 ])
 def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_only):
     """Both ways of finding the kept prefix: the short list built from the parts with the largest maxima
@@ -263,7 +269,8 @@ def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_on
     cfg = wl.scaled(wl.CONFIGS["c3"], B=B, N=N, V=V, d=d, M=M, cap=cap, zipf_s=1.3, seed=3 * B + V)
     print(f"[case] truncated sampling B={B} V={V} d={d} cap={cap}", flush=True)
     lens = wl.make_lens(cfg)
-    lens[1] = 0
+    if B > 1:
+        lens[1] = 0
     ctx, ref, E, H, w, d_E, d_W, d_H = _setup(cfg, lens)
     ctx.set_option(api.OPT_SAMPLE_KERNEL, whole_row_only)
     tok = torch.empty(B, dtype=torch.int32, device="cuda")
@@ -275,6 +282,7 @@ def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_on
     settings = [(1.0, 1, 1.0), (0.7, 5, 1.0), (1.0, 50, 1.0), (1.0, 0, 0.3), (0.5, 0, 0.9), (1.3, 40, 0.8),
                 (1.0, 10 ** 9, 0.9999), (2.0, 7000, 1.0), (0.05, 0, 0.5), (1.0, 2, 0.99), (0.9, 36, 1.0),
                 (1.1, 39, 0.97), (1.0, 256, 1.0), (0.3, 257, 0.9)]
+    n_decided = 0
     for si, (T, k, p) in enumerate(settings):
         seed, step = 900 + si, (si << 33) | 17
         ctx.extended_sample(d_H, 1, d_E, d_W, T, seed, step, tok, lp, top_k=k, top_p=p)
@@ -282,7 +290,9 @@ def test_truncated_draws_match_oracle_every_row(B, N, V, d, M, cap, whole_row_on
         tok_h, lp_h = tok.cpu().numpy(), lp.cpu().numpy()
         decided = sum(_check_truncated(rows_logits[b], T, k, p, seed, step, b, int(tok_h[b]), float(lp_h[b]))
                       for b in range(B))
-        assert decided >= 0.8 * B, (T, k, p, decided)
+        assert decided >= 0.8 * B - (1 if B < 8 else 0), (T, k, p, decided)
+        n_decided += decided
+    assert n_decided >= 0.8 * B * len(settings)
     ctx.close()
 
 
